@@ -1,0 +1,62 @@
+"""Write tests/golden/cfg<N>.json: full-space search results of the benchmark
+configurations, computed by the CPU checker only (oracle/'s tabulated walk,
+which tests/test_oracle_pins.py checks against the plain per-index search).
+
+Usage: python tests/golden/make_golden.py [--threads T] cfg [cfg ...]
+Runtime on 8 cores: cfg 1-2 seconds, cfg 3 about 3 minutes, cfg 4 about
+25 minutes, cfg 5 about 1.5 hours.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
+
+import oracle  # noqa: E402
+from paper_2407_03583_amd import workloads as wl  # noqa: E402
+
+# demand points also searched under the index-only tie rule
+INDEX_ONLY_POINTS = {1: 1, 2: 1, 3: 64, 4: 8, 5: 0}
+
+
+def record(b, demand):
+    return dict(demand_mqps=int(demand), found=int(b.found), index=int(b.index),
+                accuracy_hex=float(b.accuracy).hex(), accuracy=float(b.accuracy),
+                workers=int(b.workers), n_feasible=int(b.n_feasible))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--threads", type=int, default=None)
+    ap.add_argument("cfgs", type=int, nargs="+")
+    args = ap.parse_args()
+    for cfg in args.cfgs:
+        w = wl.config(cfg)
+        prob = oracle.Problem(w.pipeline)
+        doc = dict(config=cfg, name=w.name, seed=w.seed, workload_digest=w.digest(),
+                   n_candidates=prob.num_candidates(), workers=w.workers, slo_us=w.slo_us, comm_us=w.comm_us,
+                   written_by="tests/golden/make_golden.py (oracle.Problem.search_tabulated)",
+                   results=[], results_index_only=[])
+        t0 = time.time()
+        for m, d in enumerate(w.demand_mqps):
+            b = prob.search_tabulated(d, w.workers, w.slo_us, w.comm_us, threads=args.threads)
+            doc["results"].append(record(b, d))
+            if m < INDEX_ONLY_POINTS[cfg]:
+                b = prob.search_tabulated(d, w.workers, w.slo_us, w.comm_us, tie_index_only=True,
+                                          threads=args.threads)
+                doc["results_index_only"].append(record(b, d))
+            print(f"cfg {cfg} point {m + 1}/{len(w.demand_mqps)} {time.time() - t0:.0f}s", flush=True)
+        doc["seconds"] = round(time.time() - t0, 1)
+        doc["threads"] = args.threads or oracle.max_threads()
+        with open(os.path.join(HERE, f"cfg{cfg}.json"), "w") as f:
+            json.dump(doc, f, indent=1)
+            f.write("\n")
+
+
+if __name__ == "__main__":
+    main()

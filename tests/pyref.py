@@ -1,0 +1,149 @@
+"""A second, independent reading of the candidate evaluation, used only to pin
+the C checker in oracle/ on small problems.
+
+Written in exact rational arithmetic in *real units* (queries/second, not the
+checker's scaled integers): demand at a task is D * prod(fan-out) as a
+Fraction, capacity is x * q as a Fraction, the task accuracy is a Fraction that
+is rounded to a double exactly once.  The fp64 steps (path products root
+first, path sum in leaf order, division by the number of paths) then follow in
+Python floats, which are IEEE doubles with no contraction.
+
+Citations: eq. (1)-(3), (6), (7), (12) and Algorithm 1 of the Loki paper
+(HPDC'24), Sections 4.1, 4.2 and 5.1.
+"""
+from __future__ import annotations
+
+from fractions import Fraction
+from typing import Dict, List, Tuple
+
+BAD_WORKERS, BAD_DEMAND, BAD_EMPTY, BAD_LATENCY = 1, 2, 4, 8
+
+
+def _tables(p):
+    """Nested dicts: task -> variant -> {replica_limit, acc, lat{b}, thr{b}} plus batch lists."""
+    tasks = []
+    v = b = t = 0
+    for i in range(p.n_tasks):
+        batches = list(p.batch_size[b:b + p.n_batches[i]])
+        variants = []
+        for k in range(p.n_variants[i]):
+            lat = {bi: p.latency_us[t + k * len(batches) + bi] for bi in range(len(batches))}
+            thr = {bi: p.thr_mqps[t + k * len(batches) + bi] for bi in range(len(batches))}
+            variants.append(dict(limit=p.max_replicas[v + k], acc=p.acc_ppm[v + k], lat=lat, thr=thr))
+        tasks.append(dict(batches=batches, variants=variants, parent=p.parent[i],
+                          fan=Fraction(p.fanout_q4[i], 4)))
+        v += p.n_variants[i]
+        b += p.n_batches[i]
+        t += p.n_variants[i] * len(batches)
+    return tasks
+
+
+def decode(p, index: int) -> List[Tuple[List[int], int]]:
+    """index -> per task (replica counts, batch digit); task 0 and variant 0 least significant,
+    the batch digit is the most significant digit of a task's group."""
+    plan = []
+    for task in _tables(p):
+        xs = []
+        for var in task["variants"]:
+            xs.append(index % (var["limit"] + 1))
+            index //= var["limit"] + 1
+        beta = index % len(task["batches"])
+        index //= len(task["batches"])
+        plan.append((xs, beta))
+    return plan
+
+
+def num_candidates(p) -> int:
+    n = 1
+    for task in _tables(p):
+        n *= len(task["batches"])
+        for var in task["variants"]:
+            n *= var["limit"] + 1
+    return n
+
+
+def evaluate(p, index: int, demand_mqps: int, workers: int, slo_us: int, comm_us: int = 0) -> Dict:
+    tasks = _tables(p)
+    plan = decode(p, index)
+    # demand per task in QPS (eq. (1), one factor per edge)
+    demand = []
+    for i, task in enumerate(tasks):
+        demand.append(Fraction(demand_mqps, 1000) if i == 0 else demand[task["parent"]] * task["fan"])
+    mask = 0
+    used_workers = sum(sum(xs) for xs, _ in plan)
+    if used_workers > workers:
+        mask |= BAD_WORKERS
+    acc_task, lat_task = [], []
+    for i, task in enumerate(tasks):
+        xs, beta = plan[i]
+        hosted = [k for k in range(len(xs)) if xs[k] > 0]
+        hosted.sort(key=lambda k: (-task["variants"][k]["acc"], k))
+        if not hosted:
+            mask |= BAD_EMPTY
+        left = demand[i]
+        gained = Fraction(0)
+        in_use = []
+        for pos, k in enumerate(hosted):
+            var = task["variants"][k]
+            capacity = xs[k] * Fraction(var["thr"][beta], 1000)
+            take = min(left, capacity)
+            if take > 0 or pos == 0:
+                in_use.append(var["lat"][beta])
+            gained += take * Fraction(var["acc"], 1_000_000)
+            left -= take
+        if left > 0:
+            mask |= BAD_DEMAND
+        lat_task.append(max(in_use) if in_use else 0)
+        if demand[i] > 0:
+            acc_task.append(gained / demand[i])
+        elif hosted:
+            acc_task.append(Fraction(task["variants"][hosted[0]]["acc"], 1_000_000))
+        else:
+            acc_task.append(Fraction(0))
+    leaves = [i for i in range(len(tasks)) if all(t["parent"] != i for t in tasks)]
+    paths = []
+    for leaf in leaves:
+        path, i = [], leaf
+        while i >= 0:
+            path.append(i)
+            i = tasks[i]["parent"]
+        paths.append(path[::-1])
+    for path in paths:
+        room = slo_us - comm_us * len(path)
+        if room < 0 or sum(lat_task[i] for i in path) > room // 2:
+            mask |= BAD_LATENCY
+    out = dict(infeasible=mask, workers=used_workers, accuracy=0.0, task_lat=lat_task)
+    if mask == 0:
+        a = [float(f) for f in acc_task]  # one correct rounding each
+        total = None
+        for path in paths:
+            prod = a[path[0]]
+            for i in path[1:]:
+                prod = prod * a[i]
+            total = prod if total is None else total + prod
+        out["accuracy"] = total / float(len(paths))
+        # exact value of the objective, for error-bound checks
+        exact = Fraction(0)
+        for path in paths:
+            pr = Fraction(1)
+            for i in path:
+                pr *= acc_task[i]
+            exact += pr
+        out["exact"] = exact / len(paths)
+    return out
+
+
+def search(p, demand_mqps: int, workers: int, slo_us: int, comm_us: int = 0, tie_index_only: bool = False):
+    best = None
+    n_feasible = 0
+    for index in range(num_candidates(p)):
+        e = evaluate(p, index, demand_mqps, workers, slo_us, comm_us)
+        if e["infeasible"]:
+            continue
+        n_feasible += 1
+        key = (-e["accuracy"], 0 if tie_index_only else e["workers"], index)
+        if best is None or key < best[0]:
+            best = (key, index, e["accuracy"], e["workers"])
+    if best is None:
+        return dict(found=0, index=(1 << 64) - 1, accuracy=0.0, workers=-1, n_feasible=0)
+    return dict(found=1, index=best[1], accuracy=best[2], workers=best[3], n_feasible=n_feasible)

@@ -1,0 +1,434 @@
+"""Pins for the CPU checker (oracle/): everything here compares it with
+something that is not itself -- a hand-derived example, closed forms, an
+exact-rational second implementation, and invariants the paper's constraints
+imply.  No GPU."""
+import json
+import math
+import os
+import random
+from fractions import Fraction
+from types import SimpleNamespace
+
+import pytest
+
+import oracle
+import pyref
+from paper_2407_03583_amd import workloads as wl
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+NONE = (1 << 64) - 1
+
+
+def pipeline(**kw):
+    return SimpleNamespace(**kw)
+
+
+def one_task(acc, lat, thr, limits, batches):
+    k = len(acc)
+    return pipeline(n_tasks=1, parent=[-1], fanout_q4=[4], n_variants=[k], n_batches=[len(batches)],
+                    batch_size=list(batches), max_replicas=list(limits), acc_ppm=list(acc),
+                    latency_us=[v for row in lat for v in row], thr_mqps=[v for row in thr for v in row])
+
+
+# ---- P1: the hand-derived two-task example ---------------------------------------------------
+
+@pytest.fixture(scope="module")
+def worked():
+    with open(os.path.join(HERE, "golden", "worked_example_2task.json")) as f:
+        doc = json.load(f)
+    return doc, pipeline(**doc["pipeline"])
+
+
+def test_worked_example_winners(worked):
+    doc, p = worked
+    prob = oracle.Problem(p)
+    assert prob.num_candidates() == doc["n_candidates"]
+    for case in doc["cases"]:
+        b = prob.search(case["demand_mqps"], doc["workers"], doc["slo_us"], doc["comm_us"], threads=3)
+        assert b.found == 1
+        assert b.index == case["winner_index"]
+        assert b.workers == case["winner_workers"]
+        a = [float(Fraction(s)) for s in case["winner_task_acc"]]
+        assert b.accuracy == (a[0] * a[1]) / 1.0
+        e = prob.eval(b.index, case["demand_mqps"], doc["workers"], doc["slo_us"], doc["comm_us"])
+        assert [e.task_acc[0], e.task_acc[1]] == a
+
+
+def test_worked_example_details(worked):
+    doc, p = worked
+    prob = oracle.Problem(p)
+    case = doc["cases"][0]
+    d, w, slo = case["demand_mqps"], doc["workers"], doc["slo_us"]
+    top = prob.eval(case["winner_index"], d, w, slo).accuracy
+    for idx in case["tied_indices_same_workers"]:
+        e = prob.eval(idx, d, w, slo)
+        assert e.infeasible == 0 and e.workers == case["winner_workers"] and e.accuracy == top
+    assert prob.eval(case["infeasible_by_latency_index"], d, w, slo).infeasible == oracle.BAD_LATENCY
+    c = case["candidate_237"]
+    e = prob.eval(237, d, w, slo)
+    assert e.infeasible == 0 and e.workers == c["workers"]
+    assert [e.task_acc[0], e.task_acc[1]] == [float(Fraction(s)) for s in c["task_acc"]]
+    assert e.task_maxlat[0] + e.task_maxlat[1] == c["path_latency_us"]
+    # the decoded plan of the winner is the one the derivation names
+    x, beta = prob.decode(111)
+    assert x == [0, 1, 0, 2] and beta == [0, 0]
+    assert prob.encode(x, beta) == 111
+    # with two workers only one replica per task fits: (0,1) at 100 QPS and (1,0) at 250 QPS
+    two = prob.search(d, 2, slo)
+    assert (two.found, two.workers, two.accuracy) == (1, 2, float(Fraction(9, 10)) * float(Fraction(4, 5)))
+    assert prob.search(d, 1, slo).found == 0
+
+
+def test_worked_example_against_rational_enumeration(worked):
+    doc, p = worked
+    prob = oracle.Problem(p)
+    for case in doc["cases"]:
+        for tie in (False, True):
+            ref = pyref.search(p, case["demand_mqps"], doc["workers"], doc["slo_us"], 0, tie)
+            b = prob.search(case["demand_mqps"], doc["workers"], doc["slo_us"], 0, tie_index_only=tie, threads=2)
+            assert (b.found, b.index, b.accuracy, b.workers, b.n_feasible) == \
+                (ref["found"], ref["index"], ref["accuracy"], ref["workers"], ref["n_feasible"])
+
+
+# ---- P2 / P3: closed forms ---------------------------------------------------------------------
+
+def test_one_task_one_variant_closed_form():
+    # feasible iff x*thr(b) >= D, lat(b) <= budget, 1 <= x <= min(R, W); accuracy = A;
+    # winner = fewest workers, then lowest index  (Step 1, eq. (11))
+    rng = random.Random(7)
+    for _ in range(200):
+        batches = [1, 2, 4, 8][: rng.randint(1, 4)]
+        lat = [rng.randint(2000, 9000) + rng.randint(1000, 9000) * b for b in batches]
+        thr = [b * 10**9 // l for b, l in zip(batches, lat)]
+        R, W = rng.randint(1, 7), rng.randint(1, 7)
+        A = rng.randint(1, 10**6)
+        D = rng.randint(0, 900_000)
+        slo = rng.randint(4000, 120_000)
+        p = one_task([A], [lat], [thr], [R], batches)
+        best = None
+        count = 0
+        for beta, b in enumerate(batches):
+            for x in range(1, min(R, W) + 1):
+                if x * thr[beta] >= D and lat[beta] <= slo // 2:
+                    count += 1
+                    key = (x, x + (R + 1) * beta)
+                    if best is None or key < best:
+                        best = key
+        got = oracle.Problem(p).search(D, W, slo, threads=1)
+        if best is None:
+            assert got.found == 0 and got.index == NONE and got.workers == -1 and got.n_feasible == 0
+        else:
+            assert (got.found, got.workers, got.index, got.n_feasible) == (1, best[0], best[1], count)
+            assert got.accuracy == A / 1000000.0
+            if D > 0:  # fewest workers at the chosen batch size = ceil(D / thr)
+                beta = best[1] // (R + 1)
+                assert best[0] == max(1, -(-D // thr[beta]))
+
+
+def test_one_task_two_variants_closed_form():
+    # a = (min(D, c_hi) A_hi + (D - min(D, c_hi)) A_lo) / (D 1e6)
+    rng = random.Random(11)
+    for _ in range(300):
+        a_lo, a_hi = sorted(rng.sample(range(1, 10**6), 2))
+        hi_first = rng.random() < 0.5
+        thr_lo, thr_hi = rng.randint(50_000, 900_000), rng.randint(20_000, 400_000)
+        acc = [a_hi, a_lo] if hi_first else [a_lo, a_hi]
+        thr = [[thr_hi], [thr_lo]] if hi_first else [[thr_lo], [thr_hi]]
+        p = one_task(acc, [[5000], [5000]], thr, [3, 3], [1])
+        x_hi, x_lo = rng.randint(1, 3), rng.randint(1, 3)
+        D = rng.randint(1, 2_000_000)
+        x = [x_hi, x_lo] if hi_first else [x_lo, x_hi]
+        idx = x[0] + 4 * x[1]
+        e = oracle.Problem(p).eval(idx, D, 6, 100_000)
+        c_hi, c_lo = x_hi * thr_hi, x_lo * thr_lo
+        if c_hi + c_lo < D:
+            assert e.infeasible == oracle.BAD_DEMAND
+            continue
+        assert e.infeasible == 0
+        served_hi = min(D, c_hi)
+        exact = Fraction(served_hi * a_hi + (D - served_hi) * a_lo, D * 10**6)
+        assert e.accuracy == float(exact)
+        # the slower variant's latency only counts when it carries traffic
+        assert e.task_maxlat[0] == 5000
+
+
+# ---- P9: every candidate of random small problems against the rational reading ------------------
+
+@pytest.mark.parametrize("seed", range(40))
+def test_every_candidate_matches_rational_reading(seed):
+    w = wl.random_small(seed, max_candidates=3000)
+    p = w.pipeline
+    prob = oracle.Problem(p)
+    n = prob.num_candidates()
+    assert n == pyref.num_candidates(p) == p.num_candidates()
+    d = w.demand_mqps[0]
+    for index in range(n):
+        e = prob.eval(index, d, w.workers, w.slo_us, w.comm_us)
+        r = pyref.evaluate(p, index, d, w.workers, w.slo_us, w.comm_us)
+        assert e.infeasible == r["infeasible"], index
+        assert e.workers == r["workers"], index
+        assert e.accuracy == r["accuracy"], index
+        assert [e.task_maxlat[i] for i in range(p.n_tasks)] == r["task_lat"], index
+        if not r["infeasible"]:
+            # fp64 objective within the a-priori bound of the exact rational value
+            n_ops = 2 * p.n_tasks + 2
+            assert abs(Fraction(e.accuracy) - r["exact"]) <= r["exact"] * n_ops * Fraction(1, 2**52)
+        x, beta = prob.decode(index)
+        plan = pyref.decode(p, index)
+        assert x == [v for xs, _ in plan for v in xs] and beta == [b for _, b in plan]
+        assert prob.encode(x, beta) == index
+    for tie in (False, True):
+        ref = pyref.search(p, d, w.workers, w.slo_us, w.comm_us, tie)
+        for b in (prob.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=tie, threads=3),
+                  prob.search_tabulated(d, w.workers, w.slo_us, w.comm_us, tie_index_only=tie, threads=3)):
+            assert (b.found, b.index, b.accuracy, b.workers, b.n_feasible) == \
+                (ref["found"], ref["index"], ref["accuracy"], ref["workers"], ref["n_feasible"])
+
+
+# ---- P4-P7: special cases and invariants ------------------------------------------------------------
+
+def top_accuracy(p):
+    """Mean over root-to-leaf paths of the product of each task's best accuracy (root first)."""
+    tops, v = [], 0
+    for i in range(p.n_tasks):
+        tops.append(max(p.acc_ppm[v:v + p.n_variants[i]]) / 1000000.0)
+        v += p.n_variants[i]
+    leaves = [i for i in range(p.n_tasks) if i not in p.parent]
+    total = None
+    for leaf in leaves:
+        path, i = [], leaf
+        while i >= 0:
+            path.append(i)
+            i = p.parent[i]
+        prod = None
+        for i in reversed(path):
+            prod = tops[i] if prod is None else prod * tops[i]
+        total = prod if total is None else total + prod
+    return total / float(len(leaves))
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 4])
+def test_zero_demand_best_is_the_most_accurate_variants(cfg):
+    w = wl.config(cfg)
+    p = w.pipeline
+    prob = oracle.Problem(p)
+    if cfg == 1:
+        b = prob.search(0, w.workers, w.slo_us)
+    else:  # 2^30 candidates: the tabulated walk, itself checked against the plain one elsewhere
+        b = prob.search_tabulated(0, w.workers, w.slo_us)
+    assert b.found == 1
+    assert b.accuracy == top_accuracy(p)
+    assert b.workers == p.n_tasks  # one replica of each task's best variant
+    x, beta = prob.decode(b.index)
+    v = 0
+    for i in range(p.n_tasks):
+        xs = x[v:v + p.n_variants[i]]
+        k_top = max(range(p.n_variants[i]), key=lambda k: (p.acc_ppm[v + k], -k))
+        assert xs == [1 if k == k_top else 0 for k in range(p.n_variants[i])]
+        assert beta[i] == 0  # lowest index among equal plans: smallest batch digit
+        v += p.n_variants[i]
+
+
+def test_monotone_in_workers_demand_and_slo():
+    w = wl.config(1)
+    prob = oracle.Problem(w.pipeline)
+
+    def key(b):
+        return (b.accuracy if b.found else -1.0, b.n_feasible)
+
+    prev = None
+    for workers in range(0, 19):
+        cur = key(prob.search(w.demand_mqps[0], workers, w.slo_us))
+        if prev is not None:
+            assert cur[0] >= prev[0] and cur[1] >= prev[1]
+        prev = cur
+    prev = None
+    for demand in range(0, 400_000, 10_000):
+        cur = key(prob.search(demand, w.workers, w.slo_us))
+        if prev is not None:
+            assert cur[0] <= prev[0] and cur[1] <= prev[1]
+        prev = cur
+    assert prev[0] == -1.0  # 390 QPS cannot be served by 8 workers here
+    prev = None
+    for slo in range(10_000, 400_000, 15_000):
+        cur = key(prob.search(w.demand_mqps[0], w.workers, slo))
+        if prev is not None:
+            assert cur[0] >= prev[0] and cur[1] >= prev[1]
+        prev = cur
+
+
+def test_slo_floor():
+    # below twice the sum of the fastest latencies along a path nothing is feasible (Section 6.4)
+    w = wl.config(1)
+    p = w.pipeline
+    prob = oracle.Problem(p)
+    t, floor = 0, 0
+    for i in range(p.n_tasks):
+        floor += min(p.latency_us[t: t + p.n_variants[i] * p.n_batches[i]])
+        t += p.n_variants[i] * p.n_batches[i]
+    assert prob.search(0, 18, 2 * floor - 1).found == 0
+    assert prob.search(0, 18, 2 * floor).found == 1
+    assert prob.search(0, 18, 2 * floor + 1).found == 1
+    # communication latency is charged once per task on the path, before halving
+    assert prob.search(0, 18, 2 * floor + 2 * 700, comm_us=700).found == 1
+    assert prob.search(0, 18, 2 * floor + 2 * 700 - 1, comm_us=700).found == 0
+
+
+def test_capacity_ceiling_flips_at_one_milli_qps():
+    w = wl.config(1)
+    p = w.pipeline
+    prob = oracle.Problem(p)
+    nb = p.n_batches[0]
+    ceiling = sum(p.max_replicas[k] * max(p.thr_mqps[k * nb:(k + 1) * nb]) for k in range(p.n_variants[0]))
+    one = one_task(p.acc_ppm[:3], [p.latency_us[k * nb:(k + 1) * nb] for k in range(3)],
+                   [p.thr_mqps[k * nb:(k + 1) * nb] for k in range(3)], p.max_replicas[:3], p.batch_size[:nb])
+    prob1 = oracle.Problem(one)
+    # thr is increasing in b here, so the ceiling is reached at the largest batch
+    assert prob1.search(ceiling, 9, 10**7).found == 1
+    assert prob1.search(ceiling, 9, 10**7).n_feasible == 1
+    assert prob1.search(ceiling + 1, 9, 10**7).found == 0
+    assert prob.search(ceiling + 1, 18, 10**7).found == 0
+
+
+def test_tie_break_modes_differ_only_in_workers():
+    w = wl.config(1)
+    prob = oracle.Problem(w.pipeline)
+    a = prob.search(20_000, 18, w.slo_us)
+    b = prob.search(20_000, 18, w.slo_us, tie_index_only=True)
+    assert a.accuracy == b.accuracy and a.n_feasible == b.n_feasible
+    assert a.workers <= b.workers and b.index <= a.index
+
+
+# ---- P8: the fill rule is the best split for a fixed plan (Section 5.1, last paragraph) ---------------
+
+def test_most_accurate_first_is_the_best_split():
+    rng = random.Random(3)
+    for seed in range(30):
+        w = wl.random_small(1000 + seed, max_tasks=1, max_variants=3, max_replicas=3)
+        p = w.pipeline
+        prob = oracle.Problem(p)
+        d = max(1, w.demand_mqps[0])
+        for index in range(prob.num_candidates()):
+            e = prob.eval(index, d, 99, 10**7)
+            if e.infeasible:
+                continue
+            x, beta = prob.decode(index)
+            caps = [x[k] * p.thr_mqps[k * p.n_batches[0] + beta[0]] for k in range(p.n_variants[0])]
+            for _ in range(5):  # random alternative splits within capacity
+                left, alt = d, 0
+                order = list(range(len(caps)))
+                rng.shuffle(order)
+                for k in order:
+                    take = min(left, rng.randint(0, caps[k]))
+                    alt += take * p.acc_ppm[k]
+                    left -= take
+                if left == 0:
+                    assert Fraction(alt, d * 10**6) <= Fraction(e.task_acc[0]) * (1 + Fraction(1, 2**52))
+
+
+# ---- P10: swapping two sibling leaves leaves the optimum unchanged -----------------------------------
+
+def test_leaf_swap_symmetry():
+    w = wl.config(4)
+    p = w.pipeline
+    # shrink to keep the plain search affordable: 2 variants, replicas 0..2
+    def cut(task_slices, per):
+        out = []
+        for s in task_slices:
+            out.extend(s[:per])
+        return out
+    nb = 4
+    small = pipeline(n_tasks=3, parent=[-1, 0, 0], fanout_q4=p.fanout_q4, n_variants=[2, 2, 2], n_batches=[nb] * 3,
+                     batch_size=p.batch_size, max_replicas=[2] * 6,
+                     acc_ppm=cut([p.acc_ppm[0:4], p.acc_ppm[4:8], p.acc_ppm[8:12]], 2),
+                     latency_us=cut([p.latency_us[0:16], p.latency_us[16:32], p.latency_us[32:48]], 2 * nb),
+                     thr_mqps=cut([p.thr_mqps[0:16], p.thr_mqps[16:32], p.thr_mqps[32:48]], 2 * nb))
+    swapped = pipeline(n_tasks=3, parent=[-1, 0, 0],
+                       fanout_q4=[small.fanout_q4[0], small.fanout_q4[2], small.fanout_q4[1]],
+                       n_variants=[2, 2, 2], n_batches=[nb] * 3, batch_size=small.batch_size, max_replicas=[2] * 6,
+                       acc_ppm=small.acc_ppm[0:2] + small.acc_ppm[4:6] + small.acc_ppm[2:4],
+                       latency_us=small.latency_us[0:8] + small.latency_us[16:24] + small.latency_us[8:16],
+                       thr_mqps=small.thr_mqps[0:8] + small.thr_mqps[16:24] + small.thr_mqps[8:16])
+    for demand in (0, 30_000, 60_000):
+        a = oracle.Problem(small).search(demand, 8, 200_000)
+        b = oracle.Problem(swapped).search(demand, 8, 200_000)
+        assert a.found == b.found == 1
+        assert (a.accuracy, a.workers, a.n_feasible) == (b.accuracy, b.workers, b.n_feasible)
+
+
+# ---- tabulated walk == plain search, on slices of the real configurations ------------------------------
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_tabulated_walk_equals_plain_search_on_slices(cfg):
+    w = wl.config(cfg)
+    prob = oracle.Problem(w.pipeline)
+    n = prob.num_candidates()
+    assert n == w.pipeline.num_candidates()
+    rng = random.Random(cfg)
+    d = w.demand_mqps[len(w.demand_mqps) // 3]
+    spans = [(0, min(n, 1 << 16))]
+    for _ in range(3):
+        lo = rng.randrange(0, n - (1 << 17)) if n > (1 << 17) else 0
+        spans.append((lo, min(n, lo + (1 << 17) - rng.randrange(0, 999))))
+    for tie in (False, True):
+        for lo, hi in spans:
+            a = prob.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=tie, begin=lo, end=hi, threads=3)
+            b = prob.search_tabulated(d, w.workers, w.slo_us, w.comm_us, tie_index_only=tie, begin=lo, end=hi, threads=5)
+            assert a.as_tuple() == b.as_tuple()
+
+
+def test_search_range_split_is_consistent():
+    w = wl.config(1)
+    prob = oracle.Problem(w.pipeline)
+    n = prob.num_candidates()
+    whole = prob.search(w.demand_mqps[0], w.workers, w.slo_us, threads=1)
+    cuts = [0, 777, 30_000, 30_001, n]
+    parts = [prob.search(w.demand_mqps[0], w.workers, w.slo_us, begin=a, end=b, threads=2)
+             for a, b in zip(cuts, cuts[1:])]
+    assert sum(p.n_feasible for p in parts) == whole.n_feasible
+    best = min((p for p in parts if p.found), key=lambda p: (-p.accuracy, p.workers, p.index))
+    assert (best.index, best.accuracy, best.workers) == (whole.index, whole.accuracy, whole.workers)
+    empty = prob.search(w.demand_mqps[0], w.workers, w.slo_us, begin=5, end=5)
+    assert empty.found == 0 and empty.n_feasible == 0
+
+
+# ---- P11: Algorithm 1 for one plan ------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(25))
+def test_route_table_conservation(seed):
+    w = wl.random_small(500 + seed, max_candidates=4000)
+    p = w.pipeline
+    prob = oracle.Problem(p)
+    d = w.demand_mqps[0]
+    b = prob.search(d, 99, 10**8)
+    if not b.found:
+        return
+    r = prob.route_table(b.index, d)
+    e = prob.eval(b.index, d, 99, 10**8)
+    x, beta = prob.decode(b.index)
+    v = 0
+    for i in range(p.n_tasks):
+        K = p.n_variants[i]
+        assert r.demand[i] == e.task_demand[i]
+        assert r.unserved[i] == 0
+        assert sum(r.routed[i][k] for k in range(K)) == r.demand[i]
+        weighted = 0
+        for k in range(K):
+            assert 0 <= r.routed[i][k] <= r.capacity[i][k]
+            assert r.leftover[i][k] == r.capacity[i][k] - r.routed[i][k]
+            assert (r.budget_us[i][k] > 0) == (x[v + k] > 0)
+            weighted += r.routed[i][k] * p.acc_ppm[v + k]
+            # a less accurate variant carries traffic only if every more accurate hosted one is full
+            if r.routed[i][k] > 0:
+                for k2 in range(K):
+                    if (p.acc_ppm[v + k2], -k2) > (p.acc_ppm[v + k], -k) and x[v + k2] > 0:
+                        assert r.leftover[i][k2] == 0
+        if r.demand[i] > 0:
+            assert e.task_acc[i] == weighted / float(r.demand[i] * 10**6)
+        # probabilities leaving each parent variant (or the frontend) sum to one
+        parents = [0] if i == 0 else [k for k in range(p.n_variants[p.parent[i]]) if r.routed[p.parent[i]][k] > 0]
+        if r.demand[i] > 0:
+            for pk in parents:
+                s = sum(r.prob[i][pk][k] for k in range(K))
+                assert abs(s - 1.0) <= K * 2.0**-52
+        v += K
