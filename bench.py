@@ -1,0 +1,137 @@
+"""Benchmark: candidates evaluated per second of the exhaustive allocation search on one MI355X.
+
+A step is one pass of the whole hot path (per-task tables, the kernel that visits
+every plan, the final merge) over one benchmark configuration; inputs are resident
+in device memory except the O(KB) constant block each call stages itself.
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = one 32- or 64-bit vector ALU
+# operation per lane per clock (fp64 FMA counted as two gives the published 78.6 TFLOP/s).
+VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
+def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -> float:
+    """Vector-ALU operations one plan needs in the kernel that visits every plan.
+    Tabulated kernel: [product with the last task's accuracy] + [add to the other
+    paths' sum] + 2 feasibility compares + 1 compare against the lane's best."""
+    if not per_lane:
+        return (1 if n_tasks >= 2 else 0) + (1 if n_paths > 1 else 0) + 2 + 1
+    # per-lane kernel: 20 per (task, variant) + 30 per task + 50 per plan (decode, fill, divide, paths, key)
+    return sum(20 * k + 30 for k in pipeline.n_variants) + 50
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
+    ap.add_argument("--per-lane", action="store_true", help="time the kernel that scores whole plans per lane")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the search shards by index range; see DESIGN.md); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2407_03583_amd import binding, workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+    w = wl.config(args.config)
+    P = binding.Problem(w.pipeline)
+    n = P.num_candidates()
+    m = len(w.demand_mqps)
+    flags = binding.LOKI_SEARCH_PER_LANE if args.per_lane else 0
+    end = n
+    if args.per_lane and n * m > (1 << 36):  # keep a step to seconds: a prefix of the index space
+        end = (1 << 36) // m
+    evaluations = end * m
+
+    results = torch.empty(32 * m, dtype=torch.uint8, device="cuda")
+    for _ in range(args.warmup):
+        P.alloc_search_enqueue(w.demand_mqps, w.workers, w.slo_us, w.comm_us, flags=flags, end=end, results=results)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        P.alloc_search_enqueue(w.demand_mqps, w.workers, w.slo_us, w.comm_us, flags=flags, end=end, results=results)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = max(gpu_ms, wall_ms) / args.steps
+    first = binding.results_from_bytes(results.cpu().numpy().tobytes())
+
+    # duration of the dominant kernel alone (HIP events inside the library, on the same stream)
+    kernel_ms = []
+    for _ in range(max(1, min(args.steps, 5))):
+        chk = P.alloc_search(w.demand_mqps, w.workers, w.slo_us, w.comm_us, flags=flags, end=end)
+        kernel_ms.append(P.last_search_ms())
+    assert [r.as_tuple() for r in chk] == [r.as_tuple() for r in first]
+    main_ms = sum(k[1] for k in kernel_ms) / len(kernel_ms)
+    n_paths = sum(1 for i in range(w.pipeline.n_tasks) if i not in w.pipeline.parent)
+    ops = algorithmic_lane_ops(w.pipeline.n_tasks, n_paths, args.per_lane, w.pipeline)
+    achieved = ops * evaluations / (main_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "allocation candidates evaluated/sec (1 GPU)",
+        "value": evaluations / (ms_per_step * 1e-3),
+        "unit": "candidates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int64+f64",
+        "data": "synthetic",
+        "config": {"workload": w.name, "seed": w.seed, "candidates": n, "demand_points": m,
+                   "index_end": end, "evaluations_per_step": evaluations,
+                   "kernel": "per_lane" if args.per_lane else "tabulated",
+                   "feasible_fraction_point0": first[0].n_feasible / end},
+        "kernel_ms": {"task_tables": sum(k[0] for k in kernel_ms) / len(kernel_ms), "search": main_ms,
+                      "final_merge": sum(k[2] for k in kernel_ms) / len(kernel_ms)},
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
+                     "frac": achieved / VALU_PEAK_TLANEOPS, "traffic": None,
+                     "lane_ops_per_candidate": ops},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        O = oracle.Problem(w.pipeline)
+        sample = min(n, 1 << 30)
+        stride = max(1, n // sample)
+        if stride > 1 and stride % 2 == 0:
+            stride -= 1  # odd stride: every digit of the index varies over the sample
+        threads = oracle.max_threads()
+        t0 = time.perf_counter()
+        b = O.search(w.demand_mqps[0], w.workers, w.slo_us, w.comm_us, begin=0, end=min(n, sample * stride),
+                     stride=stride, threads=threads)
+        dt = time.perf_counter() - t0
+        done = (min(n, sample * stride) + stride - 1) // stride
+        out["cpu_baseline"] = {"value": done / dt, "unit": "candidates/s", "cores": threads, "kind": "oracle",
+                               "sample": f"{done} candidates of demand point 0, every {stride}th index from 0, "
+                                         f"plain per-index search, {dt:.1f} s",
+                               "feasible_in_sample": int(b.n_feasible)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,561 @@
+// Host side of the C-ABI declared in include/loki_alloc.h: validation, the
+// fixed-point range proof, workspace layout, launch configuration, and the
+// per-plan routing table (Algorithm 1 of the Loki paper, Section 5.1).
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/loki_alloc.h"
+#include "loki_device.h"
+#include "loki_launch.h"
+
+using namespace loki;
+
+static_assert(LOKI_MAX_TASKS == kMaxTasks && LOKI_MAX_VARIANTS == kMaxVariants && LOKI_MAX_BATCHES == kMaxBatches,
+              "header and kernels disagree on limits");
+static_assert(sizeof(loki_result_t) == 32 && sizeof(loki_eval_t) == 16 && sizeof(BestRec) == 32 &&
+                  sizeof(TaskRec) == 16 && sizeof(MidRec) == 32,
+              "record layouts");
+
+namespace {
+
+constexpr uint32_t kTargetBlocks = 2048;  // about 8 blocks per compute unit
+constexpr int64_t kTwo53 = int64_t(1) << 53;
+constexpr size_t kAlign = 256;
+
+thread_local int g_last_hip = 0;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t off_P, off_Dn, off_table, off_recs, off_results, total;
+};
+
+Layout search_layout(uint32_t table_total, int64_t M) {
+    Layout l;
+    l.off_P = 0;
+    l.off_Dn = align_up(sizeof(DevProblem));
+    l.off_table = align_up(l.off_Dn + size_t(M) * kMaxTasks * sizeof(int64_t));
+    l.off_recs = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
+    l.off_results = align_up(l.off_recs + (size_t(kTargetBlocks) + size_t(M)) * sizeof(BestRec));
+    l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
+    return l;
+}
+
+struct EvalLayout {
+    size_t off_P, off_idx, off_out, total;
+};
+
+EvalLayout eval_layout(int64_t n) {
+    EvalLayout l;
+    l.off_P = 0;
+    l.off_idx = align_up(sizeof(DevProblem));
+    l.off_out = align_up(l.off_idx + size_t(n) * sizeof(uint64_t));
+    l.total = align_up(l.off_out + size_t(n) * sizeof(loki_eval_t));
+    return l;
+}
+
+}  // namespace
+
+struct loki_problem {
+    DevProblem dev;
+    int32_t n;
+    int32_t fanout_q4[kMaxTasks];
+    int32_t depth[kMaxTasks];
+    int32_t batch_size[kMaxTasks][kMaxBatches];
+    int64_t thr[kMaxTasks][kMaxVariants][kMaxBatches];  // unscaled
+    int32_t voff[kMaxTasks];
+    uint64_t n_candidates;
+    // pinned staging: [DevProblem | Dn (cap_points * 8 int64) | results (cap_points)]
+    unsigned char *staging = nullptr;
+    int64_t cap_points = 0;
+    hipEvent_t staged = nullptr, ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool staged_pending = false;
+    float last_ms[3] = {0.f, 0.f, 0.f};  // per-task tables, main search kernel, final merge
+    bool have_ms = false;
+};
+
+namespace {
+
+int hip_fail(hipError_t e) {
+    g_last_hip = static_cast<int>(e);
+    return LOKI_E_HIP;
+}
+
+#define LOKI_HIP(expr)                                \
+    do {                                              \
+        hipError_t e_ = (expr);                       \
+        if (e_ != hipSuccess) return hip_fail(e_);    \
+    } while (0)
+
+size_t staging_bytes(int64_t points) {
+    return align_up(sizeof(DevProblem)) + align_up(size_t(points) * kMaxTasks * sizeof(int64_t)) +
+           align_up(size_t(points) * sizeof(loki_result_t));
+}
+
+int ensure_staging(loki_problem *p, int64_t points) {
+    if (!p->staged) {  // first GPU use of this handle: events for staging reuse and timing
+        LOKI_HIP(hipEventCreateWithFlags(&p->staged, hipEventDisableTiming));
+        for (auto &e : p->ev) LOKI_HIP(hipEventCreate(&e));
+    }
+    if (points <= p->cap_points) return LOKI_OK;
+    if (p->staged_pending) {
+        LOKI_HIP(hipEventSynchronize(p->staged));
+        p->staged_pending = false;
+    }
+    if (p->staging) {
+        LOKI_HIP(hipHostFree(p->staging));
+        p->staging = nullptr;
+        p->cap_points = 0;
+    }
+    int64_t cap = std::max<int64_t>(points, 1024);
+    void *ptr = nullptr;
+    LOKI_HIP(hipHostMalloc(&ptr, staging_bytes(cap), hipHostMallocDefault));
+    p->staging = static_cast<unsigned char *>(ptr);
+    p->cap_points = cap;
+    return LOKI_OK;
+}
+
+// Demand at each task (eq. (1), one factor per edge) with the overflow proof for
+// everything downstream: Dn_i * 10^6 must stay below 2^53.
+int task_demand(const loki_problem *p, int64_t demand_mqps, int64_t *Dn) {
+    if (demand_mqps < 0) return LOKI_E_RANGE;
+    Dn[0] = demand_mqps;
+    for (int i = 0; i < kMaxTasks; i++) {
+        if (i >= p->n) {
+            Dn[i] = 0;
+            continue;
+        }
+        if (i > 0) {
+            const int64_t up = Dn[p->dev.parent[i]];
+            if (up > kTwo53 / 1000000 / p->fanout_q4[i]) return LOKI_E_RANGE;
+            Dn[i] = up * p->fanout_q4[i];
+        }
+        if (Dn[i] >= kTwo53 / 1000000) return LOKI_E_RANGE;
+    }
+    return LOKI_OK;
+}
+
+void path_budgets(const loki_problem *p, int64_t slo_us, int64_t comm_us, int64_t *budget) {
+    for (int i = 0; i < kMaxTasks; i++) {
+        budget[i] = -1;
+        if (i < p->n) {
+            const int64_t room = slo_us - comm_us * p->dev.path_len[i];
+            budget[i] = room < 0 ? -1 : room / 2;  // SLO halved for queueing (Section 4.1)
+        }
+    }
+}
+
+int check_scalars(int32_t workers, int64_t slo_us, int64_t comm_us) {
+    if (workers < 0 || workers > (1 << 30)) return LOKI_E_RANGE;
+    if (slo_us < 0 || slo_us > (int64_t(1) << 40)) return LOKI_E_RANGE;
+    if (comm_us < 0 || comm_us > (int64_t(1) << 30)) return LOKI_E_RANGE;
+    return LOKI_OK;
+}
+
+int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers, int64_t slo_us,
+                   int64_t comm_us, uint32_t flags, uint64_t index_begin, uint64_t index_end, void *d_workspace,
+                   size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed) {
+    if (!p || !demand_mqps || !d_workspace) return LOKI_E_NULL;
+    if (n_demand < 1 || n_demand > LOKI_MAX_DEMAND_POINTS) return LOKI_E_ARG;
+    if (flags & ~(LOKI_TIE_INDEX_ONLY | LOKI_SEARCH_PER_LANE)) return LOKI_E_ARG;
+    if (index_begin > index_end || index_end > p->n_candidates) return LOKI_E_ARG;
+    int rc = check_scalars(workers, slo_us, comm_us);
+    if (rc) return rc;
+    const Layout lay = search_layout(p->dev.table_total, n_demand);
+    if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
+        return LOKI_E_WORKSPACE;
+    if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
+
+    rc = ensure_staging(p, n_demand);
+    if (rc) return rc;
+    if (p->staged_pending) {  // the previous call's copy may still be reading the staging buffer
+        LOKI_HIP(hipEventSynchronize(p->staged));
+        p->staged_pending = false;
+    }
+    int64_t *hDn = reinterpret_cast<int64_t *>(p->staging + align_up(sizeof(DevProblem)));
+    for (int32_t m = 0; m < n_demand; m++) {
+        rc = task_demand(p, demand_mqps[m], hDn + size_t(m) * kMaxTasks);
+        if (rc) return rc;
+    }
+    std::memcpy(p->staging, &p->dev, sizeof(DevProblem));
+
+    unsigned char *ws = static_cast<unsigned char *>(d_workspace);
+    const size_t head = align_up(sizeof(DevProblem)) + size_t(n_demand) * kMaxTasks * sizeof(int64_t);
+    static_assert(sizeof(DevProblem) % 8 == 0, "alignment of the demand block");
+    LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, head, hipMemcpyHostToDevice, stream));
+    LOKI_HIP(hipEventRecord(p->staged, stream));
+    p->staged_pending = true;
+
+    SearchArgs A;
+    std::memset(&A, 0, sizeof(A));
+    A.P = reinterpret_cast<const DevProblem *>(ws + lay.off_P);
+    A.Dn = reinterpret_cast<const int64_t *>(ws + lay.off_Dn);
+    A.table = reinterpret_cast<TaskRec *>(ws + lay.off_table);
+    A.recs = reinterpret_cast<BestRec *>(ws + lay.off_recs);
+    A.results = d_results ? d_results : static_cast<void *>(ws + lay.off_results);
+    path_budgets(p, slo_us, comm_us, A.budget);
+    A.begin = index_begin;
+    A.end = index_end;
+    A.W = workers;
+    A.M = n_demand;
+    A.tie_index_only = (flags & LOKI_TIE_INDEX_ONLY) ? 1u : 0u;
+    const uint32_t max_bpm = std::max<uint32_t>(1u, (kTargetBlocks + n_demand - 1) / n_demand);
+    const uint64_t span = index_end - index_begin;
+    const int n = p->n, L = n - 1;
+
+    if (timed) LOKI_HIP(hipEventRecord(p->ev[0], stream));
+    if (flags & LOKI_SEARCH_PER_LANE) {
+        const uint64_t want = (span + kBlockThreads - 1) / kBlockThreads;
+        A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
+        uint64_t lanes = uint64_t(A.blocks_per_m) * kBlockThreads;
+        for (int i = 0; i < n; i++) {  // digits of the lane count; the last digit keeps the rest
+            if (i < n - 1) {
+                A.lane_step_digits[i] = lanes % p->dev.C[i];
+                lanes /= p->dev.C[i];
+            } else {
+                A.lane_step_digits[i] = lanes;
+            }
+        }
+        if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
+        LOKI_HIP(launch_per_lane_search(A, stream));
+    } else {
+        const int slots = 4;
+        const uint32_t chunk = 64u * slots;
+        const uint64_t strideL = p->dev.stride[L];
+        const uint32_t CL = p->dev.C[L];
+        uint64_t F = 1;
+        for (int j = 1; j < L; j++) F *= p->dev.C[j];
+        const uint32_t mid_count = n >= 2 ? p->dev.C[0] : 1u;
+        A.far_count = F;
+        A.mid_tiles = (mid_count + kMidTile - 1) / kMidTile;
+        if (span == 0) {
+            A.cl_first = 0;
+            A.chunk_groups = 0;
+            A.cpb = 1;
+            A.items = 0;
+        } else {
+            const uint32_t cl_first = static_cast<uint32_t>(index_begin / strideL);
+            const uint32_t cl_last = static_cast<uint32_t>((index_end - 1) / strideL);
+            const uint32_t n_chunks = (cl_last - cl_first + 1 + chunk - 1) / chunk;
+            A.cl_first = cl_first;
+            A.cpb = n_chunks >= 4 ? 4u : (n_chunks >= 2 ? 2u : 1u);
+            A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
+            A.items = uint64_t(A.chunk_groups) * F * A.mid_tiles;
+            (void)CL;
+        }
+        A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(A.items, 1), max_bpm));
+        if (A.items > (uint64_t(1) << 62) / A.blocks_per_m) A.blocks_per_m = 1;  // keep items*block in 64 bits
+        const bool range = !(index_begin == 0 && index_end == p->n_candidates);
+        const int np = p->dev.n_paths;
+        const bool divide = (np & (np - 1)) != 0;
+        LOKI_HIP(launch_task_table(A, p->dev.table_total, stream));
+        if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
+        LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, stream));
+    }
+    if (timed) LOKI_HIP(hipEventRecord(p->ev[2], stream));
+    LOKI_HIP(launch_final_reduce(A, stream));
+    if (timed) LOKI_HIP(hipEventRecord(p->ev[3], stream));
+    return LOKI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
+    if (!in || !out) return LOKI_E_NULL;
+    if (!in->parent || !in->fanout_q4 || !in->n_variants || !in->n_batches || !in->batch_size ||
+        !in->max_replicas || !in->acc_ppm || !in->latency_us || !in->thr_mqps)
+        return LOKI_E_NULL;
+    const int n = in->n_tasks;
+    if (n < 1 || n > kMaxTasks) return LOKI_E_RANGE;
+    if (in->parent[0] != -1) return LOKI_E_INVALID_GRAPH;
+    for (int i = 1; i < n; i++)
+        if (in->parent[i] < 0 || in->parent[i] >= i) return LOKI_E_INVALID_GRAPH;
+
+    loki_problem *p = new (std::nothrow) loki_problem();
+    if (!p) return LOKI_E_RANGE;
+    std::memset(&p->dev, 0, sizeof(p->dev));
+    DevProblem &d = p->dev;
+    p->n = n;
+    d.n_tasks = n;
+    int v = 0, b = 0, t = 0;
+    uint64_t N = 1;
+    uint32_t table_total = 0;
+    int rc = LOKI_OK;
+    for (int i = 0; i < n && rc == LOKI_OK; i++) {
+        const int K = in->n_variants[i], nb = in->n_batches[i];
+        if (K < 1 || K > kMaxVariants || nb < 1 || nb > kMaxBatches) {
+            rc = LOKI_E_RANGE;
+            break;
+        }
+        d.parent[i] = in->parent[i];
+        d.is_leaf[i] = 1;
+        p->depth[i] = i == 0 ? 0 : p->depth[in->parent[i]] + 1;
+        d.path_len[i] = p->depth[i] + 1;
+        if (i > 0) {
+            d.is_leaf[in->parent[i]] = 0;
+            if (in->fanout_q4[i] < 1 || in->fanout_q4[i] > 4096) rc = LOKI_E_RANGE;
+        }
+        p->fanout_q4[i] = i > 0 ? in->fanout_q4[i] : 4;
+        d.K[i] = K;
+        d.nb[i] = nb;
+        p->voff[i] = v;
+        const int64_t scale = int64_t(1) << (2 * p->depth[i]);
+        uint64_t choices = uint64_t(nb);
+        for (int bi = 0; bi < nb; bi++) {
+            const int32_t bs = in->batch_size[b + bi];
+            if (bs < 1 || (bi > 0 && bs <= in->batch_size[b + bi - 1])) rc = LOKI_E_RANGE;
+            p->batch_size[i][bi] = bs;
+        }
+        for (int k = 0; k < K; k++) {
+            const int32_t R = in->max_replicas[v + k], acc = in->acc_ppm[v + k];
+            if (R < 0 || R > LOKI_MAX_REPLICAS || acc < 0 || acc > 1000000) {
+                rc = LOKI_E_RANGE;
+                break;
+            }
+            d.radix[i][k] = uint32_t(R) + 1;
+            d.magic[i][k] = R == 0 ? 0u : uint32_t(((uint64_t(1) << 32) + uint64_t(R)) / (uint64_t(R) + 1));
+            d.acc[i][k] = acc;
+            choices *= uint64_t(R) + 1;
+            if (choices > LOKI_MAX_CHOICES) {
+                rc = LOKI_E_RANGE;
+                break;
+            }
+            for (int bi = 0; bi < nb; bi++) {
+                const int64_t lat = in->latency_us[t + k * nb + bi], thr = in->thr_mqps[t + k * nb + bi];
+                if (lat < 1 || lat > (int64_t(1) << 30) || thr < 0 || thr > (int64_t(1) << 40)) rc = LOKI_E_RANGE;
+                d.lat[i][k][bi] = lat;
+                p->thr[i][k][bi] = thr;
+                d.thr_s[i][k][bi] = thr * scale;  // <= 2^40 * 4^7 = 2^54; times 255 replicas stays below 2^63
+            }
+        }
+        if (rc) break;
+        // route order: accuracy descending, variant index ascending (Algorithm 1 sorts by single-model accuracy)
+        int ord[kMaxVariants];
+        for (int k = 0; k < K; k++) ord[k] = k;
+        std::stable_sort(ord, ord + K, [&](int x, int y) { return d.acc[i][x] > d.acc[i][y]; });
+        for (int k = 0; k < K; k++) d.order[i][k] = ord[k];
+        d.C[i] = uint32_t(choices);
+        d.stride[i] = N;
+        d.table_off[i] = table_total;
+        table_total += uint32_t(choices);
+        if (N > (uint64_t(1) << 63) / choices) {
+            rc = LOKI_E_RANGE;
+            break;
+        }
+        N *= choices;
+        v += K;
+        b += nb;
+        t += K * nb;
+    }
+    if (rc == LOKI_OK && N >= (uint64_t(1) << 63)) rc = LOKI_E_RANGE;
+    if (rc != LOKI_OK) {
+        delete p;
+        return rc;
+    }
+    d.table_total = table_total;
+    d.n_paths = 0;
+    for (int i = 0; i < n; i++) d.n_paths += d.is_leaf[i];
+    p->n_candidates = N;
+
+    *out = p;
+    return LOKI_OK;
+}
+
+void loki_problem_destroy(loki_problem_t *p) {
+    if (!p) return;
+    if (p->staged_pending && p->staged) (void)hipEventSynchronize(p->staged);
+    if (p->staging) (void)hipHostFree(p->staging);
+    if (p->staged) (void)hipEventDestroy(p->staged);
+    for (auto e : p->ev)
+        if (e) (void)hipEventDestroy(e);
+    delete p;
+}
+
+int loki_num_candidates(const loki_problem_t *p, uint64_t *n) {
+    if (!p || !n) return LOKI_E_NULL;
+    *n = p->n_candidates;
+    return LOKI_OK;
+}
+
+int loki_workspace_bytes(const loki_problem_t *p, int64_t n_demand, size_t *bytes) {
+    if (!p || !bytes) return LOKI_E_NULL;
+    if (n_demand < 1) return LOKI_E_ARG;
+    *bytes = std::max(search_layout(p->dev.table_total, n_demand).total, eval_layout(n_demand).total);
+    return LOKI_OK;
+}
+
+int loki_decode(const loki_problem_t *p, uint64_t index, int32_t *x, int32_t *batch) {
+    if (!p || !x || !batch) return LOKI_E_NULL;
+    if (index >= p->n_candidates) return LOKI_E_RANGE;
+    for (int i = 0; i < p->n; i++) {
+        uint64_t c = index % p->dev.C[i];
+        index /= p->dev.C[i];
+        for (int k = 0; k < p->dev.K[i]; k++) {
+            x[p->voff[i] + k] = int32_t(c % p->dev.radix[i][k]);
+            c /= p->dev.radix[i][k];
+        }
+        batch[i] = p->batch_size[i][c];
+    }
+    return LOKI_OK;
+}
+
+int loki_alloc_search_enqueue(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers,
+                              int64_t slo_us, int64_t comm_us, uint32_t flags, uint64_t index_begin,
+                              uint64_t index_end, void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                              void *d_results) {
+    if (!d_results) return LOKI_E_NULL;
+    return enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
+                          d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream), d_results, false);
+}
+
+int loki_alloc_search(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers,
+                      int64_t slo_us, int64_t comm_us, uint32_t flags, uint64_t index_begin, uint64_t index_end,
+                      void *d_workspace, size_t workspace_bytes, void *hip_stream, loki_result_t *out) {
+    if (!out) return LOKI_E_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int rc = enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
+                            d_workspace, workspace_bytes, stream, nullptr, true);
+    if (rc) return rc;
+    const Layout lay = search_layout(p->dev.table_total, n_demand);
+    unsigned char *hres = p->staging + align_up(sizeof(DevProblem)) +
+                          align_up(size_t(p->cap_points) * kMaxTasks * sizeof(int64_t));
+    LOKI_HIP(hipMemcpyAsync(hres, static_cast<unsigned char *>(d_workspace) + lay.off_results,
+                            size_t(n_demand) * sizeof(loki_result_t), hipMemcpyDeviceToHost, stream));
+    LOKI_HIP(hipStreamSynchronize(stream));
+    p->staged_pending = false;
+    std::memcpy(out, hres, size_t(n_demand) * sizeof(loki_result_t));
+    p->have_ms = true;
+    for (int k = 0; k < 3; k++)
+        p->have_ms = p->have_ms && hipEventElapsedTime(&p->last_ms[k], p->ev[k], p->ev[k + 1]) == hipSuccess;
+    return LOKI_OK;
+}
+
+int loki_alloc_eval(loki_problem_t *p, const uint64_t *indices, int64_t n_indices, int64_t demand_mqps,
+                    int32_t workers, int64_t slo_us, int64_t comm_us, void *d_workspace, size_t workspace_bytes,
+                    void *hip_stream, loki_eval_t *out) {
+    if (!p || !indices || !d_workspace || !out) return LOKI_E_NULL;
+    if (n_indices < 1 || n_indices > (int64_t(1) << 31) - 1024) return LOKI_E_ARG;
+    int rc = check_scalars(workers, slo_us, comm_us);
+    if (rc) return rc;
+    for (int64_t j = 0; j < n_indices; j++)
+        if (indices[j] >= p->n_candidates) return LOKI_E_RANGE;
+    const EvalLayout lay = eval_layout(n_indices);
+    if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
+        return LOKI_E_WORKSPACE;
+    EvalArgs A;
+    std::memset(&A, 0, sizeof(A));
+    rc = task_demand(p, demand_mqps, A.Dn);
+    if (rc) return rc;
+    path_budgets(p, slo_us, comm_us, A.budget);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(d_workspace);
+    rc = ensure_staging(p, 1);
+    if (rc) return rc;
+    if (p->staged_pending) {
+        LOKI_HIP(hipEventSynchronize(p->staged));
+        p->staged_pending = false;
+    }
+    std::memcpy(p->staging, &p->dev, sizeof(DevProblem));
+    LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, sizeof(DevProblem), hipMemcpyHostToDevice, stream));
+    LOKI_HIP(hipMemcpyAsync(ws + lay.off_idx, indices, size_t(n_indices) * sizeof(uint64_t), hipMemcpyHostToDevice,
+                            stream));
+    A.P = reinterpret_cast<const DevProblem *>(ws + lay.off_P);
+    A.indices = reinterpret_cast<const uint64_t *>(ws + lay.off_idx);
+    A.out = ws + lay.off_out;
+    A.n = n_indices;
+    A.W = workers;
+    LOKI_HIP(launch_eval(A, stream));
+    LOKI_HIP(hipMemcpyAsync(out, ws + lay.off_out, size_t(n_indices) * sizeof(loki_eval_t), hipMemcpyDeviceToHost,
+                            stream));
+    LOKI_HIP(hipStreamSynchronize(stream));
+    return LOKI_OK;
+}
+
+// Algorithm 1 (MostAccurateFirst) for one plan, with all replicas of a variant
+// treated as one worker of capacity x*q: tasks in topological order, workers of a
+// task by accuracy, each worker's outgoing requests placed on the child's workers
+// by accuracy while capacity lasts; the entries are the routing probabilities.
+// What is left of each capacity afterwards is the backup table of Section 5.1,
+// and the latency at the configured batch is the task's latency budget (Section 4.2).
+int loki_route_table(const loki_problem_t *p, uint64_t index, int64_t demand_mqps, loki_route_t *out) {
+    if (!p || !out) return LOKI_E_NULL;
+    if (index >= p->n_candidates) return LOKI_E_RANGE;
+    int64_t Dn[kMaxTasks];
+    int rc = task_demand(p, demand_mqps, Dn);
+    if (rc) return rc;
+    loki_route_t r;
+    std::memset(&r, 0, sizeof(r));
+    const int n = p->n;
+    uint64_t rest = index;
+    for (int i = 0; i < n; i++) {
+        uint64_t c = rest % p->dev.C[i];
+        rest /= p->dev.C[i];
+        for (int k = 0; k < p->dev.K[i]; k++) {
+            r.replicas[i][k] = int32_t(c % p->dev.radix[i][k]);
+            c /= p->dev.radix[i][k];
+        }
+        const int beta = int(c);
+        r.batch[i] = p->batch_size[i][beta];
+        r.demand[i] = Dn[i];
+        r.scale[i] = int64_t(1) << (2 * p->depth[i]);
+        for (int k = 0; k < p->dev.K[i]; k++) {
+            r.capacity[i][k] = int64_t(r.replicas[i][k]) * p->dev.thr_s[i][k][beta];
+            r.leftover[i][k] = r.capacity[i][k];
+            r.budget_us[i][k] = r.replicas[i][k] > 0 ? p->dev.lat[i][k][beta] : 0;
+        }
+    }
+    // place `amount` requests from one source on the workers of task j
+    auto place = [&](int j, int64_t amount, double *prob_row) -> int64_t {
+        const int64_t total = amount;
+        for (int o = 0; o < p->dev.K[j] && amount > 0; o++) {
+            const int k = p->dev.order[j][o];
+            const int64_t take = std::min(amount, r.leftover[j][k]);
+            if (take <= 0) continue;
+            prob_row[k] = double(take) / double(total);
+            r.leftover[j][k] -= take;
+            r.routed[j][k] += take;
+            amount -= take;
+        }
+        return amount;
+    };
+    r.unserved[0] = place(0, Dn[0], r.prob[0][0]);
+    for (int i = 0; i < n; i++)
+        for (int o = 0; o < p->dev.K[i]; o++) {
+            const int k = p->dev.order[i][o];
+            for (int j = i + 1; j < n; j++)
+                if (p->dev.parent[j] == i)
+                    r.unserved[j] += place(j, r.routed[i][k] * int64_t(p->fanout_q4[j]), r.prob[j][k]);
+        }
+    *out = r;
+    return LOKI_OK;
+}
+
+int loki_last_search_ms(const loki_problem_t *p, float *ms) {
+    if (!p || !ms) return LOKI_E_NULL;
+    if (!p->have_ms) return LOKI_E_ARG;
+    for (int k = 0; k < 3; k++) ms[k] = p->last_ms[k];
+    return LOKI_OK;
+}
+
+const char *loki_strerror(int code) {
+    switch (code) {
+        case LOKI_OK: return "ok";
+        case LOKI_E_NULL: return "null pointer";
+        case LOKI_E_INVALID_GRAPH: return "pipeline is not a rooted tree in topological order";
+        case LOKI_E_RANGE: return "value out of range or fixed-point overflow risk";
+        case LOKI_E_WORKSPACE: return "workspace too small or misaligned";
+        case LOKI_E_HIP: return "HIP runtime error";
+        case LOKI_E_ARG: return "inconsistent arguments";
+        default: return "unknown error";
+    }
+}
+
+int loki_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"

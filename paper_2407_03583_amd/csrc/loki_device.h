@@ -1,0 +1,100 @@
+// Plain-data structures shared by the host side of the library and its
+// gfx950 kernels.  Everything here is laid out for direct copies into device
+// memory and LDS.
+#pragma once
+
+#include <stdint.h>
+
+namespace loki {
+
+constexpr int kMaxTasks = 8;
+constexpr int kMaxVariants = 8;
+constexpr int kMaxBatches = 8;
+constexpr int kBlockThreads = 256;          // 4 wavefronts of 64
+constexpr int kWavesPerBlock = kBlockThreads / 64;
+constexpr int kMidTile = 1024;              // root-task choices staged in LDS per work item
+constexpr int32_t kNever = 0x7fffffff;      // latency marker: this choice can never be part of a feasible plan
+
+// Per-handle constants (Table 1 inputs after validation, plus derived radices).
+struct DevProblem {
+    int32_t n_tasks;
+    int32_t n_paths;
+    int32_t parent[kMaxTasks];
+    int32_t is_leaf[kMaxTasks];
+    int32_t path_len[kMaxTasks];            // number of tasks on the root..i chain
+    int32_t K[kMaxTasks];
+    int32_t nb[kMaxTasks];
+    uint32_t C[kMaxTasks];                  // choices per task
+    uint32_t radix[kMaxTasks][kMaxVariants];  // R(i,k)+1
+    uint32_t magic[kMaxTasks][kMaxVariants];  // ceil(2^32 / radix); unused for radix 1
+    int32_t order[kMaxTasks][kMaxVariants];   // route order (accuracy descending, index ascending) -> variant
+    int32_t acc[kMaxTasks][kMaxVariants];     // ppm, by variant
+    uint32_t table_off[kMaxTasks];          // first record of task i in a per-demand task table
+    uint32_t table_total;                   // sum of C_i
+    uint32_t pad0;
+    uint64_t stride[kMaxTasks];             // prod_{j<i} C_j
+    int64_t lat[kMaxTasks][kMaxVariants][kMaxBatches];    // microseconds
+    int64_t thr_s[kMaxTasks][kMaxVariants][kMaxBatches];  // throughput * 4^depth
+};
+
+// What a task contributes to any plan that uses one of its choices
+// (depends on the task's own digits and its demand only).
+struct TaskRec {
+    double a;      // traffic-weighted accuracy of the task
+    int32_t w;     // replicas used
+    int32_t lat;   // largest latency among the variants in use; kNever if the
+                   // choice leaves demand unserved or hosts nothing
+};
+
+// Everything the plans sharing one choice of every task but the last have in
+// common.  Staged in LDS per work item, read as a broadcast.
+struct MidRec {
+    double pre;       // product of the accuracies of the last task's ancestors, root first
+    double presum;    // sum of the path values of all earlier leaves, in leaf order
+    int32_t w_rem;    // workers left for the last task; -1 if the shared part is already infeasible
+    int32_t tl;       // latency left for the last task on its path
+    uint32_t cl_lo;   // first choice of the last task inside the index range
+    uint32_t cl_cnt;  // number of its choices inside the index range
+};
+
+struct BestRec {
+    double acc;
+    uint64_t idx;
+    uint64_t nfeas;
+    int32_t w;
+    int32_t found;
+};
+
+struct SearchArgs {
+    const DevProblem *P;
+    const int64_t *Dn;      // [M][kMaxTasks]
+    TaskRec *table;         // [M][table_total]
+    BestRec *recs;          // [M][blocks_per_m]
+    void *results;          // [M] loki_result_t
+    int64_t budget[kMaxTasks];  // per task i: floor((slo - comm*path_len[i]) / 2), -1 if negative
+    uint64_t begin, end;    // index range
+    uint64_t far_count;     // F = prod of C_j over the tasks strictly between the first and the last
+    uint64_t items;         // work items per demand point
+    uint32_t cl_first;      // first choice of the last task touched by the range
+    uint32_t chunk_groups;  // groups of chunks of the last task
+    uint32_t mid_tiles;
+    uint32_t cpb;           // chunks handled side by side in a block (1, 2 or 4)
+    int32_t W;
+    int32_t M;
+    uint32_t blocks_per_m;
+    uint32_t tie_index_only;
+    // per-lane search only
+    uint64_t lane_step_digits[kMaxTasks];   // digits (radix C_i) of the total number of lanes
+};
+
+struct EvalArgs {
+    const DevProblem *P;
+    const uint64_t *indices;
+    void *out;              // loki_eval_t
+    int64_t n;
+    int64_t Dn[kMaxTasks];
+    int64_t budget[kMaxTasks];
+    int32_t W;
+};
+
+}  // namespace loki

@@ -1,0 +1,674 @@
+// gfx950 kernels of the exhaustive allocation search.
+//
+// Scoring rules: Loki (HPDC'24) Section 4.1 eq. (1)-(3), (6), (7), (12) and the
+// fill rule of Algorithm 1 (Section 5.1); the exact fixed-point and fp64
+// conventions are stated in include/loki_alloc.h.
+//
+// Two ways to cover the plan space, with identical results:
+//  * per-lane: every lane decodes one index and scores the whole plan;
+//  * tabulated (default): a plan's score separates into a part per task that
+//    depends on that task's digits only (replicas, largest latency in use,
+//    traffic-weighted accuracy) and a cheap combination (worker sum, path
+//    latency sums, path products, leaf sum).  task_table_kernel scores every
+//    choice of every task once; combine_kernel then visits every plan, with the
+//    last task's records held in registers (one per lane and slot), the other
+//    tasks' combination staged in LDS and read as a broadcast.  Each plan still
+//    gets its own verdict and objective with the same operations in the same
+//    order, so the bits match the per-lane path.
+//
+// All fp64 arithmetic is individually rounded: the file is compiled with
+// -ffp-contract=off and additionally pins the pragma below.
+#include <hip/hip_runtime.h>
+
+#include <stddef.h>
+
+#include "loki_device.h"
+#include "loki_launch.h"
+
+#pragma clang fp contract(off)
+
+namespace loki {
+
+namespace {
+
+constexpr uint32_t kBadWorkers = 1u, kBadDemand = 2u, kBadEmpty = 4u, kBadLatency = 8u;
+
+struct ResultOut {  // mirrors loki_result_t
+    uint64_t index;
+    double accuracy;
+    uint64_t n_feasible;
+    int32_t workers_used;
+    int32_t status;
+};
+
+struct EvalOut {  // mirrors loki_eval_t
+    double accuracy;
+    int32_t workers;
+    uint32_t infeasible;
+};
+
+template <typename T>
+__device__ __forceinline__ T pick(const T (&v)[kMaxTasks], int idx) {
+    T r = v[0];
+#pragma unroll
+    for (int q = 1; q < kMaxTasks; q++) r = (idx == q) ? v[q] : r;
+    return r;
+}
+
+// Copy the first `bytes` of the problem constants into LDS (bytes is a multiple of 4).
+__device__ __forceinline__ void stage_problem(DevProblem *dst, const DevProblem *src, uint32_t bytes) {
+    const uint32_t *s = reinterpret_cast<const uint32_t *>(src);
+    uint32_t *d = reinterpret_cast<uint32_t *>(dst);
+    for (uint32_t i = threadIdx.x; i < bytes / 4; i += blockDim.x) d[i] = s[i];
+}
+
+// ---- the per-task part -----------------------------------------------------------------------
+struct TaskOut {
+    int32_t w;          // sum of replicas
+    int32_t any;        // hosts something
+    int64_t rem;        // unserved demand
+    int64_t maxlat;     // largest latency among variants in use
+    int64_t weighted;   // sum routed * acc_ppm
+    int32_t first_acc;  // accuracy of the first hosted variant in route order
+};
+
+// Decode choice c of task i (variant 0 least significant, batch digit on top) and
+// fill the hosted variants most accurate first (eq. (2), Algorithm 1's fill rule).
+__device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o) {
+    const int K = P->K[i];
+    uint64_t digits = 0;  // 8 bits per variant
+    int32_t w = 0;
+    for (int k = 0; k < K; k++) {
+        const uint32_t radix = P->radix[i][k];
+        // c * radix < 2^32 (checked at problem creation), so the multiply-high quotient is exact
+        const uint32_t q = radix == 1 ? c : __umulhi(c, P->magic[i][k]);
+        const uint32_t x = c - q * radix;
+        c = q;
+        digits |= static_cast<uint64_t>(x) << (8 * k);
+        w += static_cast<int32_t>(x);
+    }
+    const uint32_t beta = c;
+    int64_t rem = Dn, maxlat = 0, weighted = 0;
+    int32_t any = 0, first_acc = 0;
+    for (int r = 0; r < K; r++) {
+        const int k = P->order[i][r];
+        const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
+        const int64_t cap = x * P->thr_s[i][k][beta];
+        const int64_t lat = P->lat[i][k][beta];
+        const int32_t acc = P->acc[i][k];
+        const int64_t routed = rem < cap ? rem : cap;
+        const bool hosted = x > 0;
+        const bool used = hosted && (routed > 0 || !any);
+        if (used && lat > maxlat) maxlat = lat;
+        if (hosted && !any) first_acc = acc;
+        weighted += routed * static_cast<int64_t>(acc);
+        rem -= routed;
+        any |= hosted ? 1 : 0;
+    }
+    o.w = w;
+    o.any = any;
+    o.rem = rem;
+    o.maxlat = maxlat;
+    o.weighted = weighted;
+    o.first_acc = first_acc;
+}
+
+// One correctly rounded fp64 division of two exactly converted integers (< 2^53).
+__device__ __forceinline__ double task_accuracy(const TaskOut &o, int64_t Dn) {
+    if (Dn > 0) return static_cast<double>(o.weighted) / static_cast<double>(Dn * 1000000);
+    return static_cast<double>(o.first_acc) / 1000000.0;
+}
+
+// ---- a whole plan in one lane ---------------------------------------------------------------------
+__device__ __forceinline__ void eval_plan(const DevProblem *P, const uint32_t (&c)[kMaxTasks], const int64_t *Dn,
+                                          const int64_t *budget, int32_t W, uint32_t &mask, int32_t &workers,
+                                          double &accuracy) {
+    const int n = P->n_tasks;
+    double pp[kMaxTasks];   // product of accuracies root..i, root first
+    int64_t pl[kMaxTasks];  // latency sum root..i
+    mask = 0;
+    workers = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        pp[i] = 0.0;
+        pl[i] = 0;
+    }
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        if (i < n) {
+            TaskOut o;
+            eval_task(P, i, c[i], Dn[i], o);
+            workers += o.w;
+            if (!o.any) mask |= kBadEmpty;
+            if (o.rem > 0) mask |= kBadDemand;
+            const double a = task_accuracy(o, Dn[i]);
+            if (i == 0) {
+                pp[0] = a;
+                pl[0] = o.maxlat;
+            } else {
+                const int par = P->parent[i];
+                pp[i] = pick(pp, par) * a;
+                pl[i] = pick(pl, par) + o.maxlat;
+            }
+        }
+    }
+    if (workers > W) mask |= kBadWorkers;  // eq. (3)
+    double sum = 0.0;
+    bool first = true;
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        if (i < n && P->is_leaf[i]) {
+            if (budget[i] < 0 || pl[i] > budget[i]) mask |= kBadLatency;  // eq. (7) with the halved SLO
+            sum = first ? pp[i] : sum + pp[i];
+            first = false;
+        }
+    }
+    accuracy = mask ? 0.0 : sum / static_cast<double>(P->n_paths);
+}
+
+// ---- ordering and reductions -----------------------------------------------------------------------
+// Strict total order on found plans: accuracy desc, workers asc (unless tie_index_only), index asc.
+// A record with acc < 0 means "nothing found" and loses to everything.
+__device__ __forceinline__ bool better(double acc, int32_t w, uint64_t idx, double bacc, int32_t bw, uint64_t bidx,
+                                       bool tie_index_only) {
+    if (acc > bacc) return true;
+    if (acc < bacc) return false;
+    if (!tie_index_only) {
+        if (w < bw) return true;
+        if (w > bw) return false;
+    }
+    return idx < bidx;
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp32(uint32_t v) {
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, false));
+}
+
+// Exchange step s of the wavefront butterfly: steps 0-3 stay inside a row of 16
+// lanes and use DPP controls (quad_perm [1,0,3,2], quad_perm [2,3,0,1],
+// row_half_mirror, row_mirror); steps 4-5 cross rows through ds_bpermute.
+template <int STEP>
+__device__ __forceinline__ uint32_t wave_xchg(uint32_t v) {
+    if constexpr (STEP == 0) return dpp32<0xB1>(v);
+    if constexpr (STEP == 1) return dpp32<0x4E>(v);
+    if constexpr (STEP == 2) return dpp32<0x141>(v);
+    if constexpr (STEP == 3) return dpp32<0x140>(v);
+    if constexpr (STEP == 4) return static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), 16, 64));
+    return static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), 32, 64));
+}
+
+template <int STEP>
+__device__ __forceinline__ void wave_best_step(double &acc, int32_t &w, uint64_t &idx, bool tie_index_only) {
+    const uint64_t ab = static_cast<uint64_t>(__double_as_longlong(acc));
+    const uint64_t oab = (static_cast<uint64_t>(wave_xchg<STEP>(static_cast<uint32_t>(ab >> 32))) << 32) |
+                         wave_xchg<STEP>(static_cast<uint32_t>(ab));
+    const uint64_t oidx = (static_cast<uint64_t>(wave_xchg<STEP>(static_cast<uint32_t>(idx >> 32))) << 32) |
+                          wave_xchg<STEP>(static_cast<uint32_t>(idx));
+    const int32_t ow = static_cast<int32_t>(wave_xchg<STEP>(static_cast<uint32_t>(w)));
+    const double oacc = __longlong_as_double(static_cast<long long>(oab));
+    if (better(oacc, ow, oidx, acc, w, idx, tie_index_only)) {
+        acc = oacc;
+        w = ow;
+        idx = oidx;
+    }
+}
+
+// After this every lane of the wavefront holds the wavefront's best record.
+// Must be called by all 64 lanes.
+__device__ __forceinline__ void wave_best(double &acc, int32_t &w, uint64_t &idx, bool tie_index_only) {
+    wave_best_step<0>(acc, w, idx, tie_index_only);
+    wave_best_step<1>(acc, w, idx, tie_index_only);
+    wave_best_step<2>(acc, w, idx, tie_index_only);
+    wave_best_step<3>(acc, w, idx, tie_index_only);
+    wave_best_step<4>(acc, w, idx, tie_index_only);
+    wave_best_step<5>(acc, w, idx, tie_index_only);
+}
+
+__device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t lo = static_cast<uint32_t>(__shfl_xor(static_cast<int>(static_cast<uint32_t>(v)), off, 64));
+        const uint32_t hi = static_cast<uint32_t>(__shfl_xor(static_cast<int>(static_cast<uint32_t>(v >> 32)), off, 64));
+        v += (static_cast<uint64_t>(hi) << 32) | lo;
+    }
+    return v;
+}
+
+// Block-level merge of per-wavefront records and store of one BestRec.
+// nfeas is the wavefront's total (uniform across its lanes).
+__device__ __forceinline__ void block_store_best(double acc, int32_t w, uint64_t idx, uint64_t nfeas, bool tie_index_only,
+                                                 BestRec *sBest, BestRec *dst) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    wave_best(acc, w, idx, tie_index_only);
+    if (lane == 0) {
+        sBest[wave].acc = acc;
+        sBest[wave].idx = idx;
+        sBest[wave].w = w;
+        sBest[wave].nfeas = nfeas;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        BestRec b = sBest[0];
+        for (int v = 1; v < static_cast<int>(blockDim.x >> 6); v++) {
+            b.nfeas += sBest[v].nfeas;
+            if (better(sBest[v].acc, sBest[v].w, sBest[v].idx, b.acc, b.w, b.idx, tie_index_only)) {
+                b.acc = sBest[v].acc;
+                b.w = sBest[v].w;
+                b.idx = sBest[v].idx;
+            }
+        }
+        b.found = b.acc >= 0.0 ? 1 : 0;
+        *dst = b;
+    }
+}
+
+// ---- kernel: score every choice of every task, per demand point ----------------------------------------
+__global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A) {
+    __shared__ DevProblem sP;
+    stage_problem(&sP, A.P, sizeof(DevProblem));
+    __syncthreads();
+    const uint32_t t = blockIdx.x * kBlockThreads + threadIdx.x;
+    const int m = blockIdx.y;
+    if (t >= sP.table_total) return;
+    int i = sP.n_tasks - 1;
+    while (i > 0 && t < sP.table_off[i]) i--;
+    const uint32_t c = t - sP.table_off[i];
+    const int64_t Dn = A.Dn[static_cast<size_t>(m) * kMaxTasks + i];
+    TaskOut o;
+    eval_task(&sP, i, c, Dn, o);
+    TaskRec rec;
+    rec.a = task_accuracy(o, Dn);
+    rec.w = o.w;
+    rec.lat = (o.any && o.rem == 0) ? static_cast<int32_t>(o.maxlat) : kNever;
+    A.table[static_cast<size_t>(m) * sP.table_total + t] = rec;
+}
+
+// ---- kernel: visit every plan, combining the per-task records -------------------------------------------
+// Work item = (group of chunks of the last task's choices, combination f of the
+// tasks strictly between the first and the last, tile of the first task's choices).
+// A wavefront keeps S*64 records of the last task in registers; the block builds
+// the MidRec of every first-task choice in the tile once, then each wavefront
+// walks the tile and scores S*64 plans per LDS broadcast read.
+template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE>
+__global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
+    constexpr uint32_t kHeadBytes = offsetof(DevProblem, lat);
+    __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
+    __shared__ MidRec sMid[kMidTile];
+    __shared__ BestRec sBest[kWavesPerBlock];
+    DevProblem *sP = reinterpret_cast<DevProblem *>(sPraw);  // only the head is valid
+    stage_problem(sP, A.P, kHeadBytes);
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = blockIdx.y;
+    const int n = sP->n_tasks, L = n - 1;
+    const uint32_t CL = sP->C[L];
+    const uint32_t mid_count = n >= 2 ? sP->C[0] : 1u;
+    const uint64_t strideL = sP->stride[L];
+    const uint32_t C0 = n >= 2 ? sP->C[0] : 1u;
+    const TaskRec *tab = A.table + static_cast<size_t>(m) * sP->table_total;
+    const TaskRec *tabL = tab + sP->table_off[L];
+    const bool tie_index_only = A.tie_index_only != 0;
+    const double npd = static_cast<double>(sP->n_paths);
+    const int32_t W = A.W;
+
+    const uint32_t cpb = A.cpb;
+    const uint32_t chunk_in_group = wave % cpb, midpart = wave / cpb, mid_split = kWavesPerBlock / cpb;
+
+    const uint64_t item_lo = A.items * blockIdx.x / A.blocks_per_m;
+    const uint64_t item_hi = A.items * (blockIdx.x + 1) / A.blocks_per_m;
+
+    double a[S];
+    int32_t w[S], lat[S];
+    double bsum = -1.0;  // best key so far in this lane (path sum, or accuracy when DIVIDE)
+    int32_t bw = kNever;
+    uint64_t bidx = ~0ull;
+    uint64_t nfeas = 0;  // wavefront total
+    uint64_t cur_group = ~0ull;
+    uint32_t cbase = 0;
+
+    for (uint64_t item = item_lo; item < item_hi; ++item) {
+        const uint32_t r = static_cast<uint32_t>(item % A.mid_tiles);
+        const uint64_t t = item / A.mid_tiles;
+        const uint64_t f = t % A.far_count;
+        const uint64_t g = t / A.far_count;
+        if (g != cur_group) {
+            cur_group = g;
+            cbase = A.cl_first + (static_cast<uint32_t>(g) * cpb + chunk_in_group) * (64u * S);
+#pragma unroll
+            for (int s = 0; s < S; s++) {
+                const uint32_t cL = cbase + s * 64 + lane;
+                if (cL < CL) {
+                    const TaskRec rec = tabL[cL];
+                    a[s] = rec.a;
+                    w[s] = rec.w;
+                    lat[s] = rec.lat;
+                } else {
+                    a[s] = 0.0;
+                    w[s] = 0;
+                    lat[s] = kNever;
+                }
+            }
+        }
+        // records of the tasks strictly between the first and the last (uniform)
+        double fa[kMaxTasks];
+        int32_t fw[kMaxTasks], flat[kMaxTasks];
+        {
+            uint64_t rest = f;
+#pragma unroll
+            for (int j = 1; j < kMaxTasks; j++) {
+                fa[j] = 0.0;
+                fw[j] = 0;
+                flat[j] = 0;
+                if (j < L) {
+                    const uint32_t cj = static_cast<uint32_t>(rest % sP->C[j]);
+                    rest /= sP->C[j];
+                    const TaskRec rec = tab[sP->table_off[j] + cj];
+                    fa[j] = rec.a;
+                    fw[j] = rec.w;
+                    flat[j] = rec.lat;
+                }
+            }
+        }
+        const uint32_t tile_base = r * kMidTile;
+        const uint32_t cnt = mid_count - tile_base < static_cast<uint32_t>(kMidTile) ? mid_count - tile_base
+                                                                                      : static_cast<uint32_t>(kMidTile);
+        const uint64_t base_f = static_cast<uint64_t>(C0) * f;  // index contribution of the tasks in between
+
+        __syncthreads();  // the previous item's tile is no longer being read
+        for (uint32_t e = threadIdx.x; e < cnt; e += kBlockThreads) {
+            const uint32_t cM = tile_base + e;
+            double pp[kMaxTasks];
+            int64_t pl[kMaxTasks];
+            int64_t wsum = 0;
+            bool ok = true;
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++) {
+                pp[j] = 1.0;
+                pl[j] = 0;
+            }
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++) {
+                if (j < L) {
+                    double aj;
+                    int32_t wj, lj;
+                    if (j == 0) {
+                        const TaskRec rec = tab[cM];
+                        aj = rec.a;
+                        wj = rec.w;
+                        lj = rec.lat;
+                    } else {
+                        aj = fa[j];
+                        wj = fw[j];
+                        lj = flat[j];
+                    }
+                    ok = ok && lj != kNever;
+                    wsum += wj;
+                    if (j == 0) {
+                        pp[0] = aj;
+                        pl[0] = lj;
+                    } else {
+                        const int par = sP->parent[j];
+                        pp[j] = pick(pp, par) * aj;
+                        pl[j] = pick(pl, par) + lj;
+                    }
+                }
+            }
+            MidRec u;
+            u.presum = 0.0;
+            bool first = true;
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++) {
+                if (j < L && sP->is_leaf[j]) {
+                    ok = ok && A.budget[j] >= 0 && pl[j] <= A.budget[j];
+                    u.presum = first ? pp[j] : u.presum + pp[j];
+                    first = false;
+                }
+            }
+            int64_t tl = A.budget[L];
+            if (n >= 2) {
+                const int par = sP->parent[L];
+                u.pre = pick(pp, par);
+                tl = tl < 0 ? -1 : tl - pick(pl, par);
+            } else {
+                u.pre = 1.0;
+            }
+            if (tl < 0) tl = -1;
+            if (tl > kNever - 1) tl = kNever - 1;
+            u.tl = static_cast<int32_t>(tl);
+            const int64_t wr = static_cast<int64_t>(W) - wsum;
+            u.w_rem = (ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
+            u.cl_lo = 0;
+            u.cl_cnt = CL;
+            if (RANGE) {
+                const uint64_t base = base_f + cM;  // index of the plan with the last task's choice 0
+                const uint64_t lo = A.begin > base ? (A.begin - base + strideL - 1) / strideL : 0;
+                uint64_t hi = A.end > base ? (A.end - base + strideL - 1) / strideL : 0;
+                if (hi > CL) hi = CL;
+                u.cl_lo = static_cast<uint32_t>(lo < hi ? lo : hi);
+                u.cl_cnt = static_cast<uint32_t>(hi > lo ? hi - lo : 0);
+            }
+            sMid[e] = u;
+        }
+        __syncthreads();
+
+        for (uint32_t e = midpart; e < cnt; e += mid_split) {
+            const MidRec u = sMid[e];
+#pragma unroll
+            for (int s = 0; s < S; s++) {
+                const double tprod = u.pre * a[s];
+                double key = HAS_PRESUM ? u.presum + tprod : tprod;
+                if (DIVIDE) key = key / npd;
+                bool feas = (w[s] <= u.w_rem) & (lat[s] <= u.tl);
+                if (RANGE) feas = feas & ((cbase + s * 64 + lane - u.cl_lo) < u.cl_cnt);
+                nfeas += __popcll(__builtin_amdgcn_ballot_w64(feas));
+                const bool trig = feas & (key >= bsum);
+                if (__builtin_amdgcn_ballot_w64(trig) != 0) {
+                    if (trig) {
+                        const uint32_t cL = cbase + s * 64 + lane;
+                        const uint64_t idx = base_f + (tile_base + e) + strideL * cL;
+                        const int32_t wt = (W - u.w_rem) + w[s];
+                        if (better(key, wt, idx, bsum, bw, bidx, tie_index_only)) {
+                            bsum = key;
+                            bw = wt;
+                            bidx = idx;
+                        }
+                    }
+                }
+            }
+        }
+    }
+    // the key is the path sum unless DIVIDE; dividing by the (power-of-two) path count is exact and monotone
+    double bacc = bsum;
+    if (!DIVIDE && bsum >= 0.0) bacc = bsum / npd;
+    __syncthreads();
+    block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
+                     A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
+}
+
+// ---- kernel: every lane scores whole plans (no tables) ---------------------------------------------------
+__global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchArgs A) {
+    __shared__ DevProblem sP;
+    __shared__ BestRec sBest[kWavesPerBlock];
+    stage_problem(&sP, A.P, sizeof(DevProblem));
+    __syncthreads();
+    const int m = blockIdx.y;
+    const int n = sP.n_tasks;
+    const bool tie_index_only = A.tie_index_only != 0;
+    const uint64_t lanes = static_cast<uint64_t>(gridDim.x) * kBlockThreads;
+    uint64_t idx = A.begin + static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x;
+    int64_t Dn[kMaxTasks];
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) Dn[i] = A.Dn[static_cast<size_t>(m) * kMaxTasks + i];
+
+    uint32_t c[kMaxTasks];
+    {
+        uint64_t rest = idx;
+#pragma unroll
+        for (int i = 0; i < kMaxTasks; i++) {
+            c[i] = 0;
+            if (i < n) {
+                c[i] = static_cast<uint32_t>(rest % sP.C[i]);
+                rest /= sP.C[i];
+            }
+        }
+    }
+    double bacc = -1.0;
+    int32_t bw = kNever;
+    uint64_t bidx = ~0ull;
+    uint64_t nfeas = 0;
+    while (idx < A.end) {
+        uint32_t mask;
+        int32_t workers;
+        double acc;
+        eval_plan(&sP, c, Dn, A.budget, A.W, mask, workers, acc);
+        if (mask == 0) {
+            nfeas++;
+            // indices grow within a lane, so on a full tie the earlier plan stays
+            if (acc > bacc || (acc == bacc && !tie_index_only && workers < bw)) {
+                bacc = acc;
+                bw = workers;
+                bidx = idx;
+            }
+        }
+        idx += lanes;
+        uint32_t carry = 0;  // add the lane count in mixed radix
+#pragma unroll
+        for (int i = 0; i < kMaxTasks; i++) {
+            if (i < n) {
+                uint64_t v = static_cast<uint64_t>(c[i]) + A.lane_step_digits[i] + carry;
+                carry = 0;
+                if (v >= sP.C[i] && i < n - 1) {
+                    v -= sP.C[i];
+                    carry = 1;
+                }
+                c[i] = static_cast<uint32_t>(v);
+            }
+        }
+    }
+    nfeas = wave_sum(nfeas);
+    block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
+                     A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
+}
+
+// ---- kernel: merge the block records of each demand point -------------------------------------------------
+__global__ void __launch_bounds__(kBlockThreads) final_reduce_kernel(SearchArgs A) {
+    __shared__ BestRec sBest[kWavesPerBlock];
+    __shared__ BestRec sOut;
+    const int m = blockIdx.x;
+    const bool tie_index_only = A.tie_index_only != 0;
+    const BestRec *recs = A.recs + static_cast<size_t>(m) * A.blocks_per_m;
+    double bacc = -1.0;
+    int32_t bw = kNever;
+    uint64_t bidx = ~0ull;
+    uint64_t nfeas = 0;
+    for (uint32_t b = threadIdx.x; b < A.blocks_per_m; b += kBlockThreads) {
+        const BestRec r = recs[b];
+        nfeas += r.nfeas;
+        if (r.found && better(r.acc, r.w, r.idx, bacc, bw, bidx, tie_index_only)) {
+            bacc = r.acc;
+            bw = r.w;
+            bidx = r.idx;
+        }
+    }
+    nfeas = wave_sum(nfeas);
+    block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest, &sOut);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        ResultOut o;
+        if (sOut.found) {
+            o.index = sOut.idx;
+            o.accuracy = sOut.acc;
+            o.workers_used = sOut.w;
+            o.status = 0;
+        } else {
+            o.index = ~0ull;
+            o.accuracy = 0.0;
+            o.workers_used = -1;
+            o.status = 1;
+        }
+        o.n_feasible = sOut.nfeas;
+        static_cast<ResultOut *>(A.results)[m] = o;
+    }
+}
+
+// ---- kernel: score listed plans ------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlockThreads) eval_kernel(EvalArgs A) {
+    __shared__ DevProblem sP;
+    stage_problem(&sP, A.P, sizeof(DevProblem));
+    __syncthreads();
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * kBlockThreads + threadIdx.x;
+    if (t >= A.n) return;
+    uint64_t rest = A.indices[t];
+    uint32_t c[kMaxTasks];
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        c[i] = 0;
+        if (i < sP.n_tasks) {
+            c[i] = static_cast<uint32_t>(rest % sP.C[i]);
+            rest /= sP.C[i];
+        }
+    }
+    uint32_t mask;
+    int32_t workers;
+    double acc;
+    eval_plan(&sP, c, A.Dn, A.budget, A.W, mask, workers, acc);
+    EvalOut o;
+    o.accuracy = acc;
+    o.workers = workers;
+    o.infeasible = mask;
+    static_cast<EvalOut *>(A.out)[t] = o;
+}
+
+template <int S>
+hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, hipStream_t stream) {
+    const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
+#define LOKI_LAUNCH(P, D, R)                                                     \
+    hipLaunchKernelGGL((combine_kernel<S, P, D, R>), grid, block, 0, stream, A); \
+    return hipGetLastError();
+    if (has_presum) {
+        if (divide) {
+            if (range) { LOKI_LAUNCH(true, true, true) } else { LOKI_LAUNCH(true, true, false) }
+        } else {
+            if (range) { LOKI_LAUNCH(true, false, true) } else { LOKI_LAUNCH(true, false, false) }
+        }
+    } else {
+        if (range) { LOKI_LAUNCH(false, false, true) } else { LOKI_LAUNCH(false, false, false) }
+    }
+#undef LOKI_LAUNCH
+}
+
+}  // namespace
+
+hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStream_t stream) {
+    const dim3 grid((table_total + kBlockThreads - 1) / kBlockThreads, A.M), block(kBlockThreads);
+    hipLaunchKernelGGL(task_table_kernel, grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool divide, bool range,
+                          hipStream_t stream) {
+    if (slots == 8) return launch_combine_s<8>(A, has_presum, divide, range, stream);
+    return launch_combine_s<4>(A, has_presum, divide, range, stream);
+}
+
+hipError_t launch_per_lane_search(const SearchArgs &A, hipStream_t stream) {
+    const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
+    hipLaunchKernelGGL(per_lane_search_kernel, grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream) {
+    const dim3 grid(A.M), block(kBlockThreads);
+    hipLaunchKernelGGL(final_reduce_kernel, grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval(const EvalArgs &A, hipStream_t stream) {
+    const dim3 grid(static_cast<uint32_t>((A.n + kBlockThreads - 1) / kBlockThreads)), block(kBlockThreads);
+    hipLaunchKernelGGL(eval_kernel, grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+}  // namespace loki

@@ -1,0 +1,111 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol,
+and its host-side logic (validation, decode, routing table) agrees with the CPU
+checker.  No kernels are launched."""
+import os
+import re
+from types import SimpleNamespace
+
+import pytest
+
+import oracle
+from paper_2407_03583_amd import binding, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "loki_alloc.h")).read()
+    declared = set(re.findall(r"\b(loki_[a-z_]+)\s*\(", header))
+    declared -= {"loki_problem"}  # type name
+    L = binding.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(binding.EXPORTS)
+
+
+def test_num_candidates_and_decode_match_the_checker():
+    for cfg in (1, 2, 3, 4, 5):
+        w = wl.config(cfg)
+        P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+        n = P.num_candidates()
+        assert n == O.num_candidates() == w.pipeline.num_candidates()
+        batches = w.pipeline.batch_size
+        for idx in (0, 1, n - 1, n // 2, n // 3 + 7, 12345 % n):
+            x, b = P.decode(idx)
+            xo, beta = O.decode(idx)
+            assert x == xo
+            off = 0
+            for i in range(w.pipeline.n_tasks):
+                assert b[i] == batches[off + beta[i]]
+                off += w.pipeline.n_batches[i]
+        with pytest.raises(binding.LokiError) as e:
+            P.decode(n)
+        assert e.value.code == binding.LOKI_E_RANGE
+        assert P.workspace_bytes(len(w.demand_mqps)) > 0
+
+
+def test_validation_rejects_bad_inputs():
+    good = dict(n_tasks=2, parent=[-1, 0], fanout_q4=[4, 8], n_variants=[1, 1], n_batches=[1, 1], batch_size=[1, 1],
+                max_replicas=[2, 2], acc_ppm=[900000, 800000], latency_us=[5000, 6000], thr_mqps=[200000, 150000])
+    binding.Problem(SimpleNamespace(**good))
+    cases = [
+        (dict(parent=[0, 0]), binding.LOKI_E_INVALID_GRAPH),
+        (dict(parent=[-1, 1]), binding.LOKI_E_INVALID_GRAPH),
+        (dict(parent=[-1, -1]), binding.LOKI_E_INVALID_GRAPH),
+        (dict(n_tasks=9, parent=[-1] + list(range(8))), binding.LOKI_E_RANGE),
+        (dict(fanout_q4=[4, 0]), binding.LOKI_E_RANGE),
+        (dict(n_variants=[0, 1]), binding.LOKI_E_RANGE),
+        (dict(n_batches=[1, 9]), binding.LOKI_E_RANGE),
+        (dict(max_replicas=[2, 256]), binding.LOKI_E_RANGE),
+        (dict(acc_ppm=[900000, 1000001]), binding.LOKI_E_RANGE),
+        (dict(latency_us=[0, 6000]), binding.LOKI_E_RANGE),
+        (dict(thr_mqps=[-1, 150000]), binding.LOKI_E_RANGE),
+        (dict(n_batches=[2, 1], batch_size=[2, 2, 1], latency_us=[5000, 5000, 6000],
+              thr_mqps=[200000, 200000, 150000]), binding.LOKI_E_RANGE),
+    ]
+    for change, code in cases:
+        bad = dict(good)
+        bad.update(change)
+        with pytest.raises(binding.LokiError) as e:
+            binding.Problem(SimpleNamespace(**bad))
+        assert e.value.code == code, change
+    # too many choices in one task: 8 variants with 255 replicas
+    big = dict(n_tasks=1, parent=[-1], fanout_q4=[4], n_variants=[8], n_batches=[1], batch_size=[1],
+               max_replicas=[255] * 8, acc_ppm=[1] * 8, latency_us=[1] * 8, thr_mqps=[1] * 8)
+    with pytest.raises(binding.LokiError):
+        binding.Problem(SimpleNamespace(**big))
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_route_table_matches_the_checker(seed):
+    w = wl.random_small(700 + seed, max_tasks=4, max_candidates=5000)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    n = P.num_candidates()
+    d = w.demand_mqps[0]
+    for idx in {0, n - 1, n // 2, (seed * 7919) % n}:
+        r, ro = P.route_table(idx, d), O.route_table(idx, d)
+        x, batch = P.decode(idx)
+        v = 0
+        for i in range(w.pipeline.n_tasks):
+            assert (r.demand[i], r.scale[i], r.unserved[i], r.batch[i]) == \
+                (ro.demand[i], ro.scale[i], ro.unserved[i], batch[i])
+            for k in range(w.pipeline.n_variants[i]):
+                assert r.replicas[i][k] == x[v + k]
+                assert (r.capacity[i][k], r.routed[i][k], r.leftover[i][k], r.budget_us[i][k]) == \
+                    (ro.capacity[i][k], ro.routed[i][k], ro.leftover[i][k], ro.budget_us[i][k])
+                for k2 in range(oracle.MAX_VARIANTS):
+                    assert r.prob[i][k][k2] == ro.prob[i][k][k2]
+            v += w.pipeline.n_variants[i]
+    with pytest.raises(binding.LokiError):
+        P.route_table(n, d)
+    with pytest.raises(binding.LokiError):
+        P.route_table(0, -1)
+
+
+def test_workload_generator_is_stable():
+    """Digest of every benchmark configuration's arrays (guards against drift of the generator)."""
+    import json
+    path = os.path.join(ROOT, "tests", "golden", "workload_digests.json")
+    want = json.load(open(path))
+    for cfg in (1, 2, 3, 4, 5):
+        assert wl.config(cfg).digest() == want[str(cfg)], cfg

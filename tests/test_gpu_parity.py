@@ -1,0 +1,286 @@
+"""GPU parity: the HIP library (through its C-ABI) against the CPU checker on
+the same seeded inputs.  Integer outputs and the fp64 objective must match bit
+for bit (both sides take every decision in int64 / individually rounded fp64)."""
+import json
+import os
+import random
+import struct
+
+import pytest
+
+import oracle
+from paper_2407_03583_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+TIE, LANE = binding.LOKI_TIE_INDEX_ONLY, binding.LOKI_SEARCH_PER_LANE
+ALL_FLAGS = [0, TIE, LANE, LANE | TIE]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: these tests must run on an MI355X")
+    binding.lib()
+
+
+def bits(x: float) -> int:
+    return struct.unpack("<Q", struct.pack("<d", x))[0]
+
+
+def same(res: binding.Result, ref) -> bool:
+    """ref: oracle.Best or a golden record dict."""
+    if isinstance(ref, dict):
+        t = (ref["index"], float.fromhex(ref["accuracy_hex"]), ref["n_feasible"], ref["workers"], ref["found"])
+    else:
+        t = ref.as_tuple()
+    got = res.as_tuple()
+    return got[0] == t[0] and bits(got[1]) == bits(t[1]) and got[2:] == t[2:]
+
+
+def check(res, ref, what):
+    assert same(res, ref), f"{what}: gpu {res.as_tuple()} vs ref {ref if isinstance(ref, dict) else ref.as_tuple()}"
+
+
+# ---- sizes the checker finishes in seconds: exhaustive comparison -----------------------------------------
+
+def test_config1_full_space_all_modes():
+    w = wl.config(1)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    d = w.demand_mqps[0]
+    for flags in ALL_FLAGS:
+        res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, flags=flags)[0]
+        ref = O.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags & TIE))
+        check(res, ref, f"cfg1 flags={flags}")
+    # a sweep of demand points in one call, from zero demand to beyond capacity
+    demands = [0, 1, 50_000, 120_000, 200_000, 300_000, 10**7]
+    for flags in ALL_FLAGS:
+        out = P.alloc_search(demands, w.workers, w.slo_us, w.comm_us, flags=flags)
+        for dd, res in zip(demands, out):
+            check(res, O.search(dd, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags & TIE)),
+                  f"cfg1 sweep d={dd} flags={flags}")
+    assert out[-1].status == binding.LOKI_NO_FEASIBLE and out[-1].index == binding.UINT64_MAX
+
+
+def test_config1_every_candidate_eval():
+    w = wl.config(1)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    n = P.num_candidates()
+    for d in (0, w.demand_mqps[0]):
+        got = P.alloc_eval(list(range(n)), d, w.workers, w.slo_us, w.comm_us)
+        for idx in range(n):
+            e = O.eval(idx, d, w.workers, w.slo_us, w.comm_us)
+            g = got[idx]
+            assert (g.infeasible, g.workers, bits(g.accuracy)) == (e.infeasible, e.workers, bits(e.accuracy)), idx
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_small_problems(seed):
+    """Ragged K_i / R_ik / |B_i|, random trees with up to 4 tasks, duplicate accuracies,
+    communication latency, zero demand now and then."""
+    w = wl.random_small(seed, max_tasks=4, max_variants=3, max_replicas=3, max_candidates=60000)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    n = P.num_candidates()
+    assert n == O.num_candidates()
+    d = w.demand_mqps[0]
+    for flags in ALL_FLAGS:
+        res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, flags=flags)[0]
+        ref = O.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags & TIE))
+        check(res, ref, f"{w.name} flags={flags}")
+    rng = random.Random(seed)
+    idxs = list(range(n)) if n <= 4096 else [rng.randrange(n) for _ in range(4096)]
+    got = P.alloc_eval(idxs, d, w.workers, w.slo_us, w.comm_us)
+    for g, idx in zip(got, idxs):
+        e = O.eval(idx, d, w.workers, w.slo_us, w.comm_us)
+        assert (g.infeasible, g.workers, bits(g.accuracy)) == (e.infeasible, e.workers, bits(e.accuracy)), idx
+        assert P.decode(idx)[0] == O.decode(idx)[0]
+    # a ragged sub-range
+    if n > 10:
+        lo = rng.randrange(0, n // 2)
+        hi = rng.randrange(lo, n + 1)
+        for flags in ALL_FLAGS:
+            res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, flags=flags, begin=lo, end=hi)[0]
+            ref = O.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags & TIE), begin=lo, end=hi)
+            check(res, ref, f"{w.name} range [{lo},{hi}) flags={flags}")
+
+
+def test_degenerate_cases():
+    w = wl.config(1)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    d = w.demand_mqps[0]
+    n = P.num_candidates()
+    for flags in ALL_FLAGS:
+        # empty range
+        r = P.alloc_search([d], w.workers, w.slo_us, flags=flags, begin=777, end=777)[0]
+        assert r.as_tuple() == (binding.UINT64_MAX, 0.0, 0, -1, 0)
+        # single candidate ranges (first, last, the winner)
+        for idx in (0, n - 1, 29744):
+            r = P.alloc_search([d], w.workers, w.slo_us, flags=flags, begin=idx, end=idx + 1)[0]
+            check(r, O.search(d, w.workers, w.slo_us, begin=idx, end=idx + 1), f"single {idx}")
+        # no workers, no time, negative room after communication latency
+        for (W, slo, comm) in ((0, w.slo_us, 0), (w.workers, 0, 0), (w.workers, 5000, 4000)):
+            r = P.alloc_search([d], W, slo, comm, flags=flags)[0]
+            check(r, O.search(d, W, slo, comm), f"W={W} slo={slo} comm={comm}")
+            assert r.status == binding.LOKI_NO_FEASIBLE
+    # one task, one variant, one batch size: 2 candidates
+    from types import SimpleNamespace
+    tiny = SimpleNamespace(n_tasks=1, parent=[-1], fanout_q4=[4], n_variants=[1], n_batches=[1], batch_size=[4],
+                           max_replicas=[1], acc_ppm=[1000000], latency_us=[9000], thr_mqps=[444444])
+    Pt, Ot = binding.Problem(tiny), oracle.Problem(tiny)
+    for flags in ALL_FLAGS:
+        for dd in (0, 444444, 444445):
+            check(Pt.alloc_search([dd], 1, 18000, flags=flags)[0], Ot.search(dd, 1, 18000), f"tiny d={dd}")
+
+
+def test_error_paths_do_not_launch():
+    import torch
+    w = wl.config(1)
+    P = binding.Problem(w.pipeline)
+    ws = torch.empty(P.workspace_bytes(1) + 512, dtype=torch.uint8, device="cuda")
+    L = binding.lib()
+    import ctypes as C
+    out = (binding.Result * 1)()
+    dem = (C.c_int64 * 1)(120000)
+    n = P.num_candidates()
+    base = ws.data_ptr()
+    assert base % 256 == 0
+
+    def call(demand=dem, m=1, W=8, slo=200000, comm=0, flags=0, b=0, e=n, ptr=base, size=ws.numel(), o=out):
+        return L.loki_alloc_search(P._h, demand, m, W, slo, comm, flags, b, e, ptr, size, 0, o)
+    assert call(size=1024) == binding.LOKI_E_WORKSPACE
+    assert call(ptr=base + 8) == binding.LOKI_E_WORKSPACE
+    assert call(flags=64) == binding.LOKI_E_ARG
+    assert call(b=5, e=4) == binding.LOKI_E_ARG
+    assert call(e=n + 1) == binding.LOKI_E_ARG
+    assert call(m=0) == binding.LOKI_E_ARG
+    assert call(W=-1) == binding.LOKI_E_RANGE
+    assert call(demand=(C.c_int64 * 1)(-5)) == binding.LOKI_E_RANGE
+    assert call(demand=(C.c_int64 * 1)(1 << 40)) == binding.LOKI_E_RANGE
+    assert call(demand=None) == binding.LOKI_E_NULL
+    assert call() == binding.LOKI_OK
+
+
+# ---- full benchmark sizes --------------------------------------------------------------------------------------
+
+def golden(cfg):
+    path = os.path.join(HERE, "golden", f"cfg{cfg}.json")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} not generated yet (tests/golden/make_golden.py)")
+    with open(path) as f:
+        doc = json.load(f)
+    w = wl.config(cfg)
+    assert doc["workload_digest"] == w.digest(), "golden file is for different inputs"
+    return doc, w
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_full_size_search_against_stored_checker_results(cfg):
+    """The launch configuration the benchmark times: all demand points in one call, whole index space."""
+    doc, w = golden(cfg)
+    P = binding.Problem(w.pipeline)
+    assert P.num_candidates() == doc["n_candidates"]
+    out = P.alloc_search(w.demand_mqps, w.workers, w.slo_us, w.comm_us)
+    assert len(out) == len(doc["results"])
+    for m, (res, ref) in enumerate(zip(out, doc["results"])):
+        check(res, ref, f"cfg{cfg} point {m}")
+    k = len(doc["results_index_only"])
+    if k:
+        out = P.alloc_search(w.demand_mqps[:k], w.workers, w.slo_us, w.comm_us, flags=TIE)
+        for m, (res, ref) in enumerate(zip(out, doc["results_index_only"])):
+            check(res, ref, f"cfg{cfg} point {m} index-only")
+
+
+def test_config2_full_space_per_lane_kernel():
+    doc, w = golden(2)
+    P = binding.Problem(w.pipeline)
+    for flags in (LANE, LANE | TIE):
+        res = P.alloc_search(w.demand_mqps, w.workers, w.slo_us, w.comm_us, flags=flags)[0]
+        check(res, doc["results"][0] if not flags & TIE else doc["results_index_only"][0], f"cfg2 flags={flags}")
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_sampled_candidates_and_subranges(cfg):
+    w = wl.config(cfg)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    n = P.num_candidates()
+    rng = random.Random(100 + cfg)
+    demands = [w.demand_mqps[0], w.demand_mqps[len(w.demand_mqps) // 2], min(w.demand_mqps)]
+    # (i) sampled candidates one by one; half of them near the winner so that feasible ones are hit
+    for d in demands[:2]:
+        win = P.alloc_search([d], w.workers, w.slo_us, w.comm_us)[0]
+        idxs = [rng.randrange(n) for _ in range(6000)]
+        if win.status == binding.LOKI_FOUND:
+            e = O.eval(win.index, d, w.workers, w.slo_us, w.comm_us)
+            assert e.infeasible == 0 and bits(e.accuracy) == bits(win.accuracy) and e.workers == win.workers_used
+            digits_span = min(n, 1 << 20)
+            idxs += [(win.index // digits_span) * digits_span + rng.randrange(digits_span) for _ in range(6000)]
+            idxs.append(win.index)
+        got = P.alloc_eval(idxs, d, w.workers, w.slo_us, w.comm_us)
+        n_feas = 0
+        for g, idx in zip(got, idxs):
+            e = O.eval(idx, d, w.workers, w.slo_us, w.comm_us)
+            assert (g.infeasible, g.workers, bits(g.accuracy)) == (e.infeasible, e.workers, bits(e.accuracy)), idx
+            if g.infeasible == 0:
+                n_feas += 1
+                # no sampled feasible plan beats the reported winner
+                assert (g.accuracy, -g.workers, -idx) <= (win.accuracy, -win.workers_used, -win.index)
+        print(f"cfg{cfg} d={d}: {n_feas} feasible among {len(idxs)} sampled")
+    # (ii) sub-ranges the plain per-index checker can enumerate, in both kernels
+    d = demands[2]
+    for span in (1 << 18, (1 << 20) - 12345):
+        lo = rng.randrange(0, n - span)
+        win = P.alloc_search([d], w.workers, w.slo_us, w.comm_us)[0]
+        spots = [lo]
+        if win.status == binding.LOKI_FOUND:
+            spots.append(max(0, min(n - span, win.index - span // 3)))
+        for b in spots:
+            ref = O.search(d, w.workers, w.slo_us, w.comm_us, begin=b, end=b + span)
+            for flags in (0, LANE):
+                res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, flags=flags, begin=b, end=b + span)[0]
+                check(res, ref, f"cfg{cfg} range [{b},{b + span}) flags={flags}")
+
+
+def test_range_partition_merges_to_full_result():
+    doc, w = golden(2)
+    P = binding.Problem(w.pipeline)
+    n = P.num_candidates()
+    cuts = [0, 123_456_789, 535_286_220, 535_286_221, 900_000_001, n]
+    parts = [P.alloc_search(w.demand_mqps, w.workers, w.slo_us, begin=a, end=b)[0] for a, b in zip(cuts, cuts[1:])]
+    ref = doc["results"][0]
+    assert sum(p.n_feasible for p in parts) == ref["n_feasible"]
+    best = min((p for p in parts if p.status == 0), key=lambda p: (-p.accuracy, p.workers_used, p.index))
+    assert (best.index, best.accuracy.hex(), best.workers_used) == (ref["index"], ref["accuracy_hex"], ref["workers"])
+
+
+def test_enqueue_variant_matches_blocking_call():
+    import torch
+    w = wl.config(1)
+    P = binding.Problem(w.pipeline)
+    blocking = P.alloc_search(w.demand_mqps, w.workers, w.slo_us)
+    for flags in (0, LANE):
+        buf = P.alloc_search_enqueue(w.demand_mqps, w.workers, w.slo_us, flags=flags)
+        buf2 = P.alloc_search_enqueue(w.demand_mqps, w.workers, w.slo_us, flags=flags)  # back to back, same handle
+        torch.cuda.synchronize()
+        for b in (buf, buf2):
+            got = binding.results_from_bytes(bytes(b.cpu().numpy().tobytes()))
+            assert got[0].as_tuple() == blocking[0].as_tuple()
+    assert P.last_search_ms()[1] > 0.0
+
+
+def test_route_table_of_the_winner():
+    for cfg in (1, 2):
+        w = wl.config(cfg)
+        P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+        d = w.demand_mqps[0]
+        win = P.alloc_search([d], w.workers, w.slo_us)[0]
+        assert win.status == binding.LOKI_FOUND
+        r, ro = P.route_table(win.index, d), O.route_table(win.index, d)
+        for i in range(w.pipeline.n_tasks):
+            assert r.demand[i] == ro.demand[i] and r.scale[i] == ro.scale[i] and r.unserved[i] == ro.unserved[i] == 0
+            for k in range(w.pipeline.n_variants[i]):
+                assert (r.capacity[i][k], r.routed[i][k], r.leftover[i][k], r.budget_us[i][k]) == \
+                    (ro.capacity[i][k], ro.routed[i][k], ro.leftover[i][k], ro.budget_us[i][k])
+                for k2 in range(oracle.MAX_VARIANTS):
+                    assert bits(r.prob[i][k][k2]) == bits(ro.prob[i][k][k2])
