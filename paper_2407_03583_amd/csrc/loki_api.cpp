@@ -17,7 +17,7 @@ using namespace loki;
 static_assert(LOKI_MAX_TASKS == kMaxTasks && LOKI_MAX_VARIANTS == kMaxVariants && LOKI_MAX_BATCHES == kMaxBatches,
               "header and kernels disagree on limits");
 static_assert(sizeof(loki_result_t) == 32 && sizeof(loki_eval_t) == 16 && sizeof(BestRec) == 32 &&
-                  sizeof(TaskRec) == 16 && sizeof(MidRec) == 32,
+                  sizeof(TaskRec) == 16 && sizeof(MidRec) == 40,
               "record layouts");
 
 namespace {
@@ -223,10 +223,10 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
         LOKI_HIP(launch_per_lane_search(A, stream));
     } else {
-        const int slots = 4;
+        const uint32_t CL = p->dev.C[L];
+        const int slots = CL >= 512 ? 8 : 4;
         const uint32_t chunk = 64u * slots;
         const uint64_t strideL = p->dev.stride[L];
-        const uint32_t CL = p->dev.C[L];
         uint64_t F = 1;
         for (int j = 1; j < L; j++) F *= p->dev.C[j];
         const uint32_t mid_count = n >= 2 ? p->dev.C[0] : 1u;
@@ -245,7 +245,6 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
             A.cpb = n_chunks >= 4 ? 4u : (n_chunks >= 2 ? 2u : 1u);
             A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
             A.items = uint64_t(A.chunk_groups) * F * A.mid_tiles;
-            (void)CL;
         }
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(A.items, 1), max_bpm));
         if (A.items > (uint64_t(1) << 62) / A.blocks_per_m) A.blocks_per_m = 1;  // keep items*block in 64 bits

@@ -53,6 +53,8 @@ struct MidRec {
     double presum;    // sum of the path values of all earlier leaves, in leaf order
     int32_t w_rem;    // workers left for the last task; -1 if the shared part is already infeasible
     int32_t tl;       // latency left for the last task on its path
+    int32_t w_out;    // workers used by all other tasks
+    int32_t pad;
     uint32_t cl_lo;   // first choice of the last task inside the index range
     uint32_t cl_cnt;  // number of its choices inside the index range
 };

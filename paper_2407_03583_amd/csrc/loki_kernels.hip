@@ -55,6 +55,14 @@ __device__ __forceinline__ T pick(const T (&v)[kMaxTasks], int idx) {
     return r;
 }
 
+__device__ __forceinline__ uint32_t uni(uint32_t v) {
+    return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
+}
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t uni64(uint64_t v) {
+    return (static_cast<uint64_t>(uni(static_cast<uint32_t>(v >> 32))) << 32) | uni(static_cast<uint32_t>(v));
+}
+
 // Copy the first `bytes` of the problem constants into LDS (bytes is a multiple of 4).
 __device__ __forceinline__ void stage_problem(DevProblem *dst, const DevProblem *src, uint32_t bytes) {
     const uint32_t *s = reinterpret_cast<const uint32_t *>(src);
@@ -300,17 +308,20 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
     stage_problem(sP, A.P, kHeadBytes);
     __syncthreads();
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // Values that are the same in every lane are passed through readfirstlane so that the
+    // compiler keeps them (and the loops they control) on the scalar unit.
+    const int lane = threadIdx.x & 63;
+    const int wave = uni(threadIdx.x >> 6);
     const int m = blockIdx.y;
-    const int n = sP->n_tasks, L = n - 1;
-    const uint32_t CL = sP->C[L];
-    const uint32_t mid_count = n >= 2 ? sP->C[0] : 1u;
-    const uint64_t strideL = sP->stride[L];
-    const uint32_t C0 = n >= 2 ? sP->C[0] : 1u;
-    const TaskRec *tab = A.table + static_cast<size_t>(m) * sP->table_total;
-    const TaskRec *tabL = tab + sP->table_off[L];
+    const int n = uni(sP->n_tasks), L = n - 1;
+    const uint32_t CL = uni(sP->C[L]);
+    const uint32_t mid_count = n >= 2 ? uni(sP->C[0]) : 1u;
+    const uint64_t strideL = uni64(sP->stride[L]);
+    const uint32_t C0 = mid_count;
+    const TaskRec *tab = A.table + static_cast<size_t>(m) * uni(sP->table_total);
+    const TaskRec *tabL = tab + uni(sP->table_off[L]);
     const bool tie_index_only = A.tie_index_only != 0;
-    const double npd = static_cast<double>(sP->n_paths);
+    const double npd = static_cast<double>(uni(sP->n_paths));
     const int32_t W = A.W;
 
     const uint32_t cpb = A.cpb;
@@ -326,7 +337,8 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
     uint64_t bidx = ~0ull;
     uint64_t nfeas = 0;  // wavefront total
     uint64_t cur_group = ~0ull;
-    uint32_t cbase = 0;
+    uint32_t cbase = 0;  // first choice of the last task in this wavefront's chunk
+    uint32_t cl0 = 0;    // this lane's choice in slot 0
 
     for (uint64_t item = item_lo; item < item_hi; ++item) {
         const uint32_t r = static_cast<uint32_t>(item % A.mid_tiles);
@@ -336,9 +348,10 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
         if (g != cur_group) {
             cur_group = g;
             cbase = A.cl_first + (static_cast<uint32_t>(g) * cpb + chunk_in_group) * (64u * S);
+            cl0 = cbase + lane;
 #pragma unroll
             for (int s = 0; s < S; s++) {
-                const uint32_t cL = cbase + s * 64 + lane;
+                const uint32_t cL = cl0 + s * 64;
                 if (cL < CL) {
                     const TaskRec rec = tabL[cL];
                     a[s] = rec.a;
@@ -439,6 +452,8 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
             u.tl = static_cast<int32_t>(tl);
             const int64_t wr = static_cast<int64_t>(W) - wsum;
             u.w_rem = (ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
+            u.w_out = static_cast<int32_t>(wsum);
+            u.pad = 0;
             u.cl_lo = 0;
             u.cl_cnt = CL;
             if (RANGE) {
@@ -453,31 +468,62 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
         }
         __syncthreads();
 
-        for (uint32_t e = midpart; e < cnt; e += mid_split) {
-            const MidRec u = sMid[e];
+        // Score the S*64 plans this wavefront holds against one LDS record.
+        uint32_t fcount = 0;  // feasible plans of this item seen by this wavefront (< 2^20)
+        auto score = [&](const MidRec &u, uint32_t e) {
+            double key[S];
+            uint64_t trig[S];
+            uint64_t any = 0;
 #pragma unroll
             for (int s = 0; s < S; s++) {
                 const double tprod = u.pre * a[s];
-                double key = HAS_PRESUM ? u.presum + tprod : tprod;
-                if (DIVIDE) key = key / npd;
-                bool feas = (w[s] <= u.w_rem) & (lat[s] <= u.tl);
-                if (RANGE) feas = feas & ((cbase + s * 64 + lane - u.cl_lo) < u.cl_cnt);
-                nfeas += __popcll(__builtin_amdgcn_ballot_w64(feas));
-                const bool trig = feas & (key >= bsum);
-                if (__builtin_amdgcn_ballot_w64(trig) != 0) {
-                    if (trig) {
-                        const uint32_t cL = cbase + s * 64 + lane;
-                        const uint64_t idx = base_f + (tile_base + e) + strideL * cL;
-                        const int32_t wt = (W - u.w_rem) + w[s];
-                        if (better(key, wt, idx, bsum, bw, bidx, tie_index_only)) {
-                            bsum = key;
+                key[s] = HAS_PRESUM ? u.presum + tprod : tprod;
+                if (DIVIDE) key[s] = key[s] / npd;
+                // eq. (3) and eq. (7) for the last task, one wavefront-wide mask each
+                uint64_t feas = __builtin_amdgcn_ballot_w64(w[s] <= u.w_rem) &
+                                __builtin_amdgcn_ballot_w64(lat[s] <= u.tl);
+                if (RANGE) feas &= __builtin_amdgcn_ballot_w64((cl0 + s * 64 - u.cl_lo) < u.cl_cnt);
+                fcount += static_cast<uint32_t>(__builtin_popcountll(feas));
+                trig[s] = feas & __builtin_amdgcn_ballot_w64(key[s] >= bsum);
+                any |= trig[s];
+            }
+            if (__builtin_expect(any != 0, 0)) {
+                // rare: some lane may have a new best; nothing of this is worth computing early
+                uint32_t ee = e;
+                asm volatile("" : "+s"(ee));
+#pragma unroll
+                for (int s = 0; s < S; s++) {
+                    if ((trig[s] >> lane) & 1) {
+                        const uint64_t idx = base_f + (tile_base + ee) + strideL * (cl0 + s * 64);
+                        const int32_t wt = u.w_out + w[s];
+                        if (better(key[s], wt, idx, bsum, bw, bidx, tie_index_only)) {
+                            bsum = key[s];
                             bw = wt;
                             bidx = idx;
                         }
                     }
                 }
             }
+        };
+        // Two records in flight: the next one is fetched while the current one is used.
+        if (midpart < cnt) {
+            uint32_t e = midpart;
+            MidRec uA = sMid[e];
+            while (true) {
+                const uint32_t e1 = e + mid_split;
+                const bool has1 = e1 < cnt;
+                const MidRec uB = sMid[has1 ? e1 : e];
+                score(uA, e);
+                if (!has1) break;
+                const uint32_t e2 = e1 + mid_split;
+                const bool has2 = e2 < cnt;
+                uA = sMid[has2 ? e2 : e1];
+                score(uB, e1);
+                if (!has2) break;
+                e = e2;
+            }
         }
+        nfeas += fcount;
     }
     // the key is the path sum unless DIVIDE; dividing by the (power-of-two) path count is exact and monotone
     double bacc = bsum;
