@@ -17,7 +17,7 @@ using namespace loki;
 static_assert(LOKI_MAX_TASKS == kMaxTasks && LOKI_MAX_VARIANTS == kMaxVariants && LOKI_MAX_BATCHES == kMaxBatches,
               "header and kernels disagree on limits");
 static_assert(sizeof(loki_result_t) == 32 && sizeof(loki_eval_t) == 16 && sizeof(BestRec) == 32 &&
-                  sizeof(TaskRec) == 16 && sizeof(MidRec) == 40,
+                  sizeof(TaskRec) == 16 && sizeof(MidVal) == 16 && sizeof(MidLim) == 16,
               "record layouts");
 
 namespace {
@@ -31,15 +31,17 @@ thread_local int g_last_hip = 0;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t off_P, off_Dn, off_table, off_recs, off_results, total;
+    size_t off_P, off_Dn, off_table, off_perm, off_run, off_recs, off_results, total;
 };
 
-Layout search_layout(uint32_t table_total, int64_t M) {
+Layout search_layout(uint32_t table_total, uint32_t c0, int64_t M) {
     Layout l;
     l.off_P = 0;
     l.off_Dn = align_up(sizeof(DevProblem));
     l.off_table = align_up(l.off_Dn + size_t(M) * kMaxTasks * sizeof(int64_t));
-    l.off_recs = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
+    l.off_perm = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
+    l.off_run = align_up(l.off_perm + size_t(M) * c0 * sizeof(uint32_t));
+    l.off_recs = align_up(l.off_run + size_t(M) * c0 * sizeof(uint32_t));
     l.off_results = align_up(l.off_recs + (size_t(kTargetBlocks) + size_t(M)) * sizeof(BestRec));
     l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
     return l;
@@ -165,7 +167,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     if (index_begin > index_end || index_end > p->n_candidates) return LOKI_E_ARG;
     int rc = check_scalars(workers, slo_us, comm_us);
     if (rc) return rc;
-    const Layout lay = search_layout(p->dev.table_total, n_demand);
+    const Layout lay = search_layout(p->dev.table_total, p->dev.C[0], n_demand);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
         return LOKI_E_WORKSPACE;
     if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
@@ -196,6 +198,8 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     A.Dn = reinterpret_cast<const int64_t *>(ws + lay.off_Dn);
     A.table = reinterpret_cast<TaskRec *>(ws + lay.off_table);
     A.recs = reinterpret_cast<BestRec *>(ws + lay.off_recs);
+    A.perm = reinterpret_cast<uint32_t *>(ws + lay.off_perm);
+    A.run_end = reinterpret_cast<uint32_t *>(ws + lay.off_run);
     A.results = d_results ? d_results : static_cast<void *>(ws + lay.off_results);
     path_budgets(p, slo_us, comm_us, A.budget);
     A.begin = index_begin;
@@ -252,6 +256,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         const int np = p->dev.n_paths;
         const bool divide = (np & (np - 1)) != 0;
         LOKI_HIP(launch_task_table(A, p->dev.table_total, stream));
+        if (n >= 2) LOKI_HIP(launch_root_order(A, stream));
         if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
         LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, stream));
     }
@@ -358,6 +363,17 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         return rc;
     }
     d.table_total = table_total;
+    {  // distinct latencies and replica total of the first task (run ordering of its choices)
+        std::vector<int32_t> lats;
+        for (int k = 0; k < d.K[0]; k++)
+            for (int bi = 0; bi < d.nb[0]; bi++) lats.push_back(int32_t(d.lat[0][k][bi]));
+        std::sort(lats.begin(), lats.end());
+        lats.erase(std::unique(lats.begin(), lats.end()), lats.end());
+        d.n_lat0 = int32_t(lats.size());
+        for (size_t q = 0; q < lats.size(); q++) d.lat0_sorted[q] = lats[q];
+        d.sum_r0 = 0;
+        for (int k = 0; k < d.K[0]; k++) d.sum_r0 += int32_t(d.radix[0][k]) - 1;
+    }
     d.n_paths = 0;
     for (int i = 0; i < n; i++) d.n_paths += d.is_leaf[i];
     p->n_candidates = N;
@@ -385,7 +401,7 @@ int loki_num_candidates(const loki_problem_t *p, uint64_t *n) {
 int loki_workspace_bytes(const loki_problem_t *p, int64_t n_demand, size_t *bytes) {
     if (!p || !bytes) return LOKI_E_NULL;
     if (n_demand < 1) return LOKI_E_ARG;
-    *bytes = std::max(search_layout(p->dev.table_total, n_demand).total, eval_layout(n_demand).total);
+    *bytes = std::max(search_layout(p->dev.table_total, p->dev.C[0], n_demand).total, eval_layout(n_demand).total);
     return LOKI_OK;
 }
 
@@ -421,7 +437,7 @@ int loki_alloc_search(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_d
     int rc = enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
                             d_workspace, workspace_bytes, stream, nullptr, true);
     if (rc) return rc;
-    const Layout lay = search_layout(p->dev.table_total, n_demand);
+    const Layout lay = search_layout(p->dev.table_total, p->dev.C[0], n_demand);
     unsigned char *hres = p->staging + align_up(sizeof(DevProblem)) +
                           align_up(size_t(p->cap_points) * kMaxTasks * sizeof(int64_t));
     LOKI_HIP(hipMemcpyAsync(hres, static_cast<unsigned char *>(d_workspace) + lay.off_results,

@@ -31,7 +31,10 @@ struct DevProblem {
     int32_t acc[kMaxTasks][kMaxVariants];     // ppm, by variant
     uint32_t table_off[kMaxTasks];          // first record of task i in a per-demand task table
     uint32_t table_total;                   // sum of C_i
-    uint32_t pad0;
+    int32_t n_lat0;                         // number of distinct profiled latencies of task 0
+    int32_t sum_r0;                         // sum of the replica limits of task 0
+    int32_t pad0;
+    int32_t lat0_sorted[kMaxVariants * kMaxBatches];  // those latencies, ascending
     uint64_t stride[kMaxTasks];             // prod_{j<i} C_j
     int64_t lat[kMaxTasks][kMaxVariants][kMaxBatches];    // microseconds
     int64_t thr_s[kMaxTasks][kMaxVariants][kMaxBatches];  // throughput * 4^depth
@@ -46,15 +49,18 @@ struct TaskRec {
                    // choice leaves demand unserved or hosts nothing
 };
 
-// Everything the plans sharing one choice of every task but the last have in
-// common.  Staged in LDS per work item, read as a broadcast.
-struct MidRec {
+// What the plans sharing one choice of every task but the last have in common,
+// staged in LDS per work item and read as a broadcast.  MidVal feeds the
+// objective; MidLim holds the limits left for the last task and is the same
+// for every record of a run.
+struct MidVal {
     double pre;       // product of the accuracies of the last task's ancestors, root first
     double presum;    // sum of the path values of all earlier leaves, in leaf order
+};
+
+struct MidLim {
     int32_t w_rem;    // workers left for the last task; -1 if the shared part is already infeasible
     int32_t tl;       // latency left for the last task on its path
-    int32_t w_out;    // workers used by all other tasks
-    int32_t pad;
     uint32_t cl_lo;   // first choice of the last task inside the index range
     uint32_t cl_cnt;  // number of its choices inside the index range
 };
@@ -72,6 +78,8 @@ struct SearchArgs {
     const int64_t *Dn;      // [M][kMaxTasks]
     TaskRec *table;         // [M][table_total]
     BestRec *recs;          // [M][blocks_per_m]
+    uint32_t *perm;         // [M][C_0] first-task choices in run order
+    uint32_t *run_end;      // [M][C_0] end (exclusive) of the run each position belongs to
     void *results;          // [M] loki_result_t
     int64_t budget[kMaxTasks];  // per task i: floor((slo - comm*path_len[i]) / 2), -1 if negative
     uint64_t begin, end;    // index range

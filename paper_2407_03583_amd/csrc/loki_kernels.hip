@@ -292,17 +292,93 @@ __global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A)
     A.table[static_cast<size_t>(m) * sP.table_total + t] = rec;
 }
 
+// ---- kernel: order the first task's choices into runs of equal (feasible, replicas, latency) ------------
+// Everything the combine kernel derives from a first-task choice besides its
+// accuracy depends only on that triple, so plans visited in this order share
+// their feasibility masks over a whole run.  One block per demand point: a
+// counting sort with the histogram in LDS.  The latency of a choice is one of
+// the task's profiled latencies, so (replicas, rank of the latency) numbers the
+// buckets; unusable choices share the last bucket.  With more buckets than fit,
+// the identity order with runs of length one is used instead.
+constexpr uint32_t kMaxBuckets = 4096;
+constexpr int kSortThreads = 1024;
+
+__device__ __forceinline__ uint32_t root_bucket(const DevProblem *P, const TaskRec &rec, uint32_t n_buckets) {
+    if (rec.lat == kNever) return n_buckets - 1;
+    uint32_t rank = 0;
+    while (rank + 1 < static_cast<uint32_t>(P->n_lat0) && P->lat0_sorted[rank] < rec.lat) rank++;
+    return static_cast<uint32_t>(rec.w) * P->n_lat0 + rank;
+}
+
+__global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) {
+    __shared__ uint32_t sHist[kMaxBuckets];   // counts, then next free position per bucket
+    __shared__ uint32_t sEnd[kMaxBuckets];    // end position per bucket
+    __shared__ uint32_t sWaveTot[kSortThreads / 64];
+    const int m = blockIdx.x;
+    const DevProblem *P = A.P;
+    const uint32_t C0 = P->C[0];
+    const TaskRec *tab = A.table + static_cast<size_t>(m) * P->table_total;
+    uint32_t *perm = A.perm + static_cast<size_t>(m) * C0;
+    uint32_t *run_end = A.run_end + static_cast<size_t>(m) * C0;
+    const uint32_t n_buckets = static_cast<uint32_t>(P->sum_r0 + 1) * P->n_lat0 + 1;
+    if (n_buckets > kMaxBuckets) {
+        for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) {
+            perm[r] = r;
+            run_end[r] = r + 1;
+        }
+        return;
+    }
+    for (uint32_t b = threadIdx.x; b < kMaxBuckets; b += kSortThreads) sHist[b] = 0;
+    __syncthreads();
+    for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) atomicAdd(&sHist[root_bucket(P, tab[r], n_buckets)], 1u);
+    __syncthreads();
+    // exclusive prefix sum over the buckets: each thread owns kMaxBuckets / kSortThreads consecutive ones
+    constexpr uint32_t kPer = kMaxBuckets / kSortThreads;
+    uint32_t cnt[kPer], local = 0;
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; q++) {
+        cnt[q] = sHist[threadIdx.x * kPer + q];
+        local += cnt[q];
+    }
+    uint32_t incl = local;
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = static_cast<uint32_t>(__shfl_up(static_cast<int>(incl), off, 64));
+        if (static_cast<int>(threadIdx.x & 63) >= off) incl += up;
+    }
+    if ((threadIdx.x & 63) == 63) sWaveTot[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    uint32_t pos = incl - local;
+    for (uint32_t v = 0; v < (threadIdx.x >> 6); v++) pos += sWaveTot[v];
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; q++) {
+        sHist[threadIdx.x * kPer + q] = pos;
+        pos += cnt[q];
+        sEnd[threadIdx.x * kPer + q] = pos;
+    }
+    __syncthreads();
+    for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) {
+        const uint32_t b = root_bucket(P, tab[r], n_buckets);
+        const uint32_t at = atomicAdd(&sHist[b], 1u);  // order inside a bucket is immaterial
+        perm[at] = r;
+        run_end[at] = sEnd[b];
+    }
+}
+
 // ---- kernel: visit every plan, combining the per-task records -------------------------------------------
 // Work item = (group of chunks of the last task's choices, combination f of the
-// tasks strictly between the first and the last, tile of the first task's choices).
-// A wavefront keeps S*64 records of the last task in registers; the block builds
-// the MidRec of every first-task choice in the tile once, then each wavefront
-// walks the tile and scores S*64 plans per LDS broadcast read.
+// tasks strictly between the first and the last, tile of the first task's choices
+// in run order).  A wavefront keeps S*64 records of the last task in registers;
+// the block builds the MidRec of every first-task choice in the tile once, then
+// each wavefront walks its part of the tile.  Per run of equal (w_rem, tl) it
+// takes the feasibility masks of its S*64 plans once (eq. (3), eq. (7)); per
+// record it then only forms the S*64 objectives (one fp64 multiply, one add)
+// and compares them with the lanes' best under those masks.
 template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE>
 __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
     constexpr uint32_t kHeadBytes = offsetof(DevProblem, lat);
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
-    __shared__ MidRec sMid[kMidTile];
+    __shared__ MidVal sVal[kMidTile];
+    __shared__ MidLim sLim[kMidTile];
     __shared__ BestRec sBest[kWavesPerBlock];
     DevProblem *sP = reinterpret_cast<DevProblem *>(sPraw);  // only the head is valid
     stage_problem(sP, A.P, kHeadBytes);
@@ -320,6 +396,8 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
     const uint32_t C0 = mid_count;
     const TaskRec *tab = A.table + static_cast<size_t>(m) * uni(sP->table_total);
     const TaskRec *tabL = tab + uni(sP->table_off[L]);
+    const uint32_t *perm = A.perm + static_cast<size_t>(m) * C0;
+    const uint32_t *run_end = A.run_end + static_cast<size_t>(m) * C0;
     const bool tie_index_only = A.tie_index_only != 0;
     const double npd = static_cast<double>(uni(sP->n_paths));
     const int32_t W = A.W;
@@ -391,7 +469,7 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
 
         __syncthreads();  // the previous item's tile is no longer being read
         for (uint32_t e = threadIdx.x; e < cnt; e += kBlockThreads) {
-            const uint32_t cM = tile_base + e;
+            const uint32_t cM = n >= 2 ? perm[tile_base + e] : 0u;
             double pp[kMaxTasks];
             int64_t pl[kMaxTasks];
             int64_t wsum = 0;
@@ -428,100 +506,116 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
                     }
                 }
             }
-            MidRec u;
-            u.presum = 0.0;
+            MidVal uv;
+            MidLim ul;
+            uv.presum = 0.0;
             bool first = true;
 #pragma unroll
             for (int j = 0; j < kMaxTasks; j++) {
                 if (j < L && sP->is_leaf[j]) {
                     ok = ok && A.budget[j] >= 0 && pl[j] <= A.budget[j];
-                    u.presum = first ? pp[j] : u.presum + pp[j];
+                    uv.presum = first ? pp[j] : uv.presum + pp[j];
                     first = false;
                 }
             }
             int64_t tl = A.budget[L];
             if (n >= 2) {
                 const int par = sP->parent[L];
-                u.pre = pick(pp, par);
+                uv.pre = pick(pp, par);
                 tl = tl < 0 ? -1 : tl - pick(pl, par);
             } else {
-                u.pre = 1.0;
+                uv.pre = 1.0;
             }
             if (tl < 0) tl = -1;
             if (tl > kNever - 1) tl = kNever - 1;
-            u.tl = static_cast<int32_t>(tl);
+            ul.tl = static_cast<int32_t>(tl);
             const int64_t wr = static_cast<int64_t>(W) - wsum;
-            u.w_rem = (ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
-            u.w_out = static_cast<int32_t>(wsum);
-            u.pad = 0;
-            u.cl_lo = 0;
-            u.cl_cnt = CL;
+            ul.w_rem = (ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
+            ul.cl_lo = 0;
+            ul.cl_cnt = CL;
             if (RANGE) {
                 const uint64_t base = base_f + cM;  // index of the plan with the last task's choice 0
                 const uint64_t lo = A.begin > base ? (A.begin - base + strideL - 1) / strideL : 0;
                 uint64_t hi = A.end > base ? (A.end - base + strideL - 1) / strideL : 0;
                 if (hi > CL) hi = CL;
-                u.cl_lo = static_cast<uint32_t>(lo < hi ? lo : hi);
-                u.cl_cnt = static_cast<uint32_t>(hi > lo ? hi - lo : 0);
+                ul.cl_lo = static_cast<uint32_t>(lo < hi ? lo : hi);
+                ul.cl_cnt = static_cast<uint32_t>(hi > lo ? hi - lo : 0);
             }
-            sMid[e] = u;
+            sVal[e] = uv;
+            sLim[e] = ul;
         }
         __syncthreads();
 
-        // Score the S*64 plans this wavefront holds against one LDS record.
+        // this wavefront's contiguous part of the tile
+        const uint32_t e_lo = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * midpart / mid_split);
+        const uint32_t e_hi = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * (midpart + 1) / mid_split);
         uint32_t fcount = 0;  // feasible plans of this item seen by this wavefront (< 2^20)
-        auto score = [&](const MidRec &u, uint32_t e) {
-            double key[S];
-            uint64_t trig[S];
-            uint64_t any = 0;
+        uint32_t e = e_lo;
+        while (e < e_hi) {
+            // ---- start of a run: masks of the S*64 plans, valid for every record of the run
+            uint32_t run_hi = e + 1;
+            if (!RANGE && n >= 2) {
+                run_hi = uni(run_end[tile_base + e]) - tile_base;  // a run may end beyond this wavefront's part
+                if (run_hi > e_hi) run_hi = e_hi;
+            }
+            const MidLim ul = sLim[e];
+            uint64_t fm[S];
+            uint32_t run_feas = 0;
 #pragma unroll
             for (int s = 0; s < S; s++) {
-                const double tprod = u.pre * a[s];
-                key[s] = HAS_PRESUM ? u.presum + tprod : tprod;
-                if (DIVIDE) key[s] = key[s] / npd;
-                // eq. (3) and eq. (7) for the last task, one wavefront-wide mask each
-                uint64_t feas = __builtin_amdgcn_ballot_w64(w[s] <= u.w_rem) &
-                                __builtin_amdgcn_ballot_w64(lat[s] <= u.tl);
-                if (RANGE) feas &= __builtin_amdgcn_ballot_w64((cl0 + s * 64 - u.cl_lo) < u.cl_cnt);
-                fcount += static_cast<uint32_t>(__builtin_popcountll(feas));
-                trig[s] = feas & __builtin_amdgcn_ballot_w64(key[s] >= bsum);
-                any |= trig[s];
+                fm[s] = __builtin_amdgcn_ballot_w64(w[s] <= ul.w_rem) & __builtin_amdgcn_ballot_w64(lat[s] <= ul.tl);
+                if (RANGE) fm[s] &= __builtin_amdgcn_ballot_w64((cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt);
+                run_feas += static_cast<uint32_t>(__builtin_popcountll(fm[s]));
             }
-            if (__builtin_expect(any != 0, 0)) {
-                // rare: some lane may have a new best; nothing of this is worth computing early
-                uint32_t ee = e;
-                asm volatile("" : "+s"(ee));
+            // ---- every record of the run: S*64 objectives against the lanes' best
+            auto score = [&](const MidVal &u, uint32_t ee) {
+                uint64_t any = 0;
 #pragma unroll
                 for (int s = 0; s < S; s++) {
-                    if ((trig[s] >> lane) & 1) {
-                        const uint64_t idx = base_f + (tile_base + ee) + strideL * (cl0 + s * 64);
-                        const int32_t wt = u.w_out + w[s];
-                        if (better(key[s], wt, idx, bsum, bw, bidx, tie_index_only)) {
-                            bsum = key[s];
-                            bw = wt;
-                            bidx = idx;
+                    const double tprod = u.pre * a[s];
+                    double key = HAS_PRESUM ? u.presum + tprod : tprod;
+                    if (DIVIDE) key = key / npd;
+                    any |= fm[s] & __builtin_amdgcn_ballot_w64(key >= bsum);
+                }
+                fcount += run_feas;
+                if (__builtin_expect(any != 0, 0)) {
+                    // rare: some lane may have a new best; redo the slots with the full order
+                    asm volatile("" : "+s"(ee));
+                    const uint32_t cM = n >= 2 ? perm[tile_base + ee] : 0u;
+                    const int32_t w_out = W - ul.w_rem;
+#pragma unroll
+                    for (int s = 0; s < S; s++) {
+                        const double tprod = u.pre * a[s];
+                        double key = HAS_PRESUM ? u.presum + tprod : tprod;
+                        if (DIVIDE) key = key / npd;
+                        if (((fm[s] >> lane) & 1) && key >= bsum) {
+                            const uint64_t idx = base_f + cM + strideL * (cl0 + s * 64);
+                            const int32_t wt = w_out + w[s];
+                            if (better(key, wt, idx, bsum, bw, bidx, tie_index_only)) {
+                                bsum = key;
+                                bw = wt;
+                                bidx = idx;
+                            }
                         }
                     }
                 }
-            }
-        };
-        // Two records in flight: the next one is fetched while the current one is used.
-        if (midpart < cnt) {
-            uint32_t e = midpart;
-            MidRec uA = sMid[e];
+            };
+            // two records in flight: the next one is fetched while the current one is used
+            MidVal uA = sVal[e];
             while (true) {
-                const uint32_t e1 = e + mid_split;
-                const bool has1 = e1 < cnt;
-                const MidRec uB = sMid[has1 ? e1 : e];
+                const uint32_t e1 = e + 1;
+                const bool has1 = e1 < run_hi;
+                const MidVal uB = sVal[has1 ? e1 : e];
                 score(uA, e);
                 if (!has1) break;
-                const uint32_t e2 = e1 + mid_split;
-                const bool has2 = e2 < cnt;
-                uA = sMid[has2 ? e2 : e1];
+                const uint32_t e2 = e1 + 1;
+                const bool has2 = e2 < run_hi;
+                uA = sVal[has2 ? e2 : e1];
                 score(uB, e1);
                 if (!has2) break;
                 e = e2;
             }
+            e = run_hi;
         }
         nfeas += fcount;
     }
@@ -690,6 +784,11 @@ hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, b
 hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStream_t stream) {
     const dim3 grid((table_total + kBlockThreads - 1) / kBlockThreads, A.M), block(kBlockThreads);
     hipLaunchKernelGGL(task_table_kernel, grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream) {
+    hipLaunchKernelGGL(root_order_kernel, dim3(A.M), dim3(kSortThreads), 0, stream, A);
     return hipGetLastError();
 }
 

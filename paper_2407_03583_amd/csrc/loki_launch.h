@@ -9,6 +9,7 @@
 namespace loki {
 
 hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStream_t stream);
+hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool divide, bool range,
                           hipStream_t stream);
 hipError_t launch_per_lane_search(const SearchArgs &A, hipStream_t stream);
