@@ -370,9 +370,9 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // in run order).  A wavefront keeps S*64 records of the last task in registers;
 // the block builds the MidRec of every first-task choice in the tile once, then
 // each wavefront walks its part of the tile.  Per run of equal (w_rem, tl) it
-// takes the feasibility masks of its S*64 plans once (eq. (3), eq. (7)); per
-// record it then only forms the S*64 objectives (one fp64 multiply, one add)
-// and compares them with the lanes' best under those masks.
+// takes the feasibility of its S*64 plans once (eq. (3), eq. (7)); per record it
+// then only forms the S*64 objectives (one fp64 multiply, one add each), keeps
+// their running maximum, and compares that with the lanes' best.
 template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE>
 __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
     constexpr uint32_t kHeadBytes = offsetof(DevProblem, lat);
@@ -560,27 +560,34 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
             }
             const MidLim ul = sLim[e];
             uint64_t fm[S];
+            int32_t amh[S];  // high word of the accuracy, or of a huge negative number where the plan is infeasible
             uint32_t run_feas = 0;
 #pragma unroll
             for (int s = 0; s < S; s++) {
-                fm[s] = __builtin_amdgcn_ballot_w64(w[s] <= ul.w_rem) & __builtin_amdgcn_ballot_w64(lat[s] <= ul.tl);
-                if (RANGE) fm[s] &= __builtin_amdgcn_ballot_w64((cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt);
+                bool ok = (w[s] <= ul.w_rem) & (lat[s] <= ul.tl);
+                if (RANGE) ok = ok & ((cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt);
+                fm[s] = __builtin_amdgcn_ballot_w64(ok);
                 run_feas += static_cast<uint32_t>(__builtin_popcountll(fm[s]));
+                amh[s] = ok ? __double2hiint(a[s]) : static_cast<int32_t>(0xFFE00000u);
             }
-            // ---- every record of the run: S*64 objectives against the lanes' best
+            // ---- every record of the run: S*64 objectives; an infeasible plan's stand-in is far below
+            // any best, so one running maximum and one compare per record tell whether any lane improved
             auto score = [&](const MidVal &u, uint32_t ee) {
-                uint64_t any = 0;
+                double kmax = 0.0;
 #pragma unroll
                 for (int s = 0; s < S; s++) {
-                    const double tprod = u.pre * a[s];
+                    const double am = __hiloint2double(amh[s], __double2loint(a[s]));
+                    const double tprod = u.pre * am;
                     double key = HAS_PRESUM ? u.presum + tprod : tprod;
                     if (DIVIDE) key = key / npd;
-                    any |= fm[s] & __builtin_amdgcn_ballot_w64(key >= bsum);
+                    kmax = s == 0 ? key : __builtin_fmax(kmax, key);
                 }
                 fcount += run_feas;
-                if (__builtin_expect(any != 0, 0)) {
-                    // rare: some lane may have a new best; redo the slots with the full order
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(kmax >= bsum) != 0, 0)) {
+                    // rare: some lane may have a new best; redo the slots with the real masks and the full order
                     asm volatile("" : "+s"(ee));
+                    uint32_t cl = cl0;
+                    asm volatile("" : "+v"(cl));
                     const uint32_t cM = n >= 2 ? perm[tile_base + ee] : 0u;
                     const int32_t w_out = W - ul.w_rem;
 #pragma unroll
@@ -589,7 +596,7 @@ __global__ void __launch_bounds__(kBlockThreads) combine_kernel(SearchArgs A) {
                         double key = HAS_PRESUM ? u.presum + tprod : tprod;
                         if (DIVIDE) key = key / npd;
                         if (((fm[s] >> lane) & 1) && key >= bsum) {
-                            const uint64_t idx = base_f + cM + strideL * (cl0 + s * 64);
+                            const uint64_t idx = base_f + cM + strideL * (cl + s * 64);
                             const int32_t wt = w_out + w[s];
                             if (better(key, wt, idx, bsum, bw, bidx, tie_index_only)) {
                                 bsum = key;
