@@ -22,12 +22,17 @@ VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
 def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -> float:
-    """Vector-ALU operations one plan needs in the kernel that visits every plan.
-    Tabulated kernel: [product with the last task's accuracy] + [add to the other
-    paths' sum] + 2 feasibility compares + 1 compare against the lane's best."""
+    """Vector-ALU operations (one lane, one 32- or 64-bit operation) a plan needs in the
+    kernel that visits every plan.
+
+    Tabulated kernel: one fp64 multiply (prefix product times the last task's accuracy), one
+    fp64 add (the other paths' sum) when the tree has several leaves, and one fp64 max/compare
+    against the lane's best.  The two feasibility compares of eq. (3) and eq. (7) are taken
+    once per run of first-task choices with equal replicas and latency and are not counted.
+    Per-lane kernel: the estimate of 20 per (task, variant) + 30 per task + 50 per plan
+    (decode, fill, one fp64 division per task, paths, key)."""
     if not per_lane:
-        return (1 if n_tasks >= 2 else 0) + (1 if n_paths > 1 else 0) + 2 + 1
-    # per-lane kernel: 20 per (task, variant) + 30 per task + 50 per plan (decode, fill, divide, paths, key)
+        return (1 if n_tasks >= 2 else 0) + (1 if n_paths > 1 else 0) + 1
     return sum(20 * k + 30 for k in pipeline.n_variants) + 50
 
 

@@ -1,0 +1,125 @@
+"""GPU parity on shapes that take the less travelled paths of the tabulated kernel."""
+import random
+import struct
+from types import SimpleNamespace
+
+import pytest
+
+import oracle
+from paper_2407_03583_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TIE, LANE = binding.LOKI_TIE_INDEX_ONLY, binding.LOKI_SEARCH_PER_LANE
+
+
+def bits(x):
+    return struct.unpack("<Q", struct.pack("<d", x))[0]
+
+
+def agree(res, ref):
+    got, want = res.as_tuple(), ref.as_tuple()
+    return got[0] == want[0] and bits(got[1]) == bits(want[1]) and got[2:] == want[2:]
+
+
+def profile(rng, k, batches):
+    acc = [rng.randint(600000, 950000) for _ in range(k)]
+    lat, thr = [], []
+    for _ in range(k):
+        l0, l1 = rng.randint(2000, 10000), rng.randint(1000, 20000)
+        for b in batches:
+            lat.append(l0 + l1 * b)
+            thr.append(b * 10**9 // (l0 + l1 * b))
+    return acc, lat, thr
+
+
+def test_root_task_with_more_buckets_than_the_ordering_kernel_holds():
+    """Root: 2 variants x 256 replica counts x 5 batch sizes = 327,680 choices and 511 x 10 + 1
+    (replicas, latency) classes, which exceeds the ordering kernel's histogram: identity order."""
+    rng = random.Random(5)
+    a0, l0, t0 = profile(rng, 2, [1, 2, 4, 8, 16])
+    a1, l1, t1 = profile(rng, 1, [4])
+    p = SimpleNamespace(n_tasks=2, parent=[-1, 0], fanout_q4=[4, 6], n_variants=[2, 1], n_batches=[5, 1],
+                        batch_size=[1, 2, 4, 8, 16, 4], max_replicas=[255, 255, 1], acc_ppm=a0 + a1,
+                        latency_us=l0 + l1, thr_mqps=t0 + t1)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    assert P.num_candidates() == 327680 * 2
+    for demand, W in ((30_000, 20), (150_000, 300), (0, 511)):
+        for flags in (0, TIE):
+            res = P.alloc_search([demand], W, 400_000, flags=flags)[0]
+            ref = O.search(demand, W, 400_000, tie_index_only=bool(flags & TIE))
+            assert agree(res, ref), (demand, W, flags, res.as_tuple(), ref.as_tuple())
+
+
+def test_seven_leaf_star_uses_the_true_division():
+    """Root with 7 children: 7 paths (not a power of two), so the mean over paths is a real division."""
+    rng = random.Random(9)
+    n = 8
+    acc, lat, thr, nv, nb, bs, rep = [], [], [], [], [], [], []
+    for i in range(n):
+        a, l, t = profile(rng, 2, [1, 4])
+        acc += a
+        lat += l
+        thr += t
+        nv.append(2)
+        nb.append(2)
+        bs += [1, 4]
+        rep += [1, 1]
+    p = SimpleNamespace(n_tasks=n, parent=[-1] + [0] * 7, fanout_q4=[4] + [rng.randint(2, 6) for _ in range(7)],
+                        n_variants=nv, n_batches=nb, batch_size=bs, max_replicas=rep, acc_ppm=acc,
+                        latency_us=lat, thr_mqps=thr)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    assert P.num_candidates() == 8 ** 8  # 16.7M
+    for demand in (0, 20_000, 45_000):
+        ref = O.search(demand, 12, 300_000)
+        for flags in (0, LANE):
+            res = P.alloc_search([demand], 12, 300_000, flags=flags)[0]
+            assert agree(res, ref), (demand, flags, res.as_tuple(), ref.as_tuple())
+    # three leaves below a two-level tree, with ranges cutting through the last task's choices
+    p3 = SimpleNamespace(n_tasks=5, parent=[-1, 0, 1, 1, 0], fanout_q4=[4, 5, 6, 4, 9],
+                         n_variants=nv[:5], n_batches=nb[:5], batch_size=bs[:10], max_replicas=[2] * 10,
+                         acc_ppm=acc[:10], latency_us=lat[:20], thr_mqps=thr[:20])
+    P, O = binding.Problem(p3), oracle.Problem(p3)
+    nn = P.num_candidates()
+    assert nn == 18 ** 5
+    for lo, hi in ((0, nn), (12345, 1_000_000), (nn - 700_001, nn - 1)):
+        ref = O.search(25_000, 9, 250_000, begin=lo, end=hi)
+        for flags in (0, LANE, TIE):
+            if flags & TIE:
+                ref = O.search(25_000, 9, 250_000, begin=lo, end=hi, tie_index_only=True)
+            res = P.alloc_search([25_000], 9, 250_000, flags=flags, begin=lo, end=hi)[0]
+            assert agree(res, ref), (lo, hi, flags, res.as_tuple(), ref.as_tuple())
+
+
+def test_deep_chain_of_eight_tasks():
+    rng = random.Random(21)
+    acc, lat, thr = [], [], []
+    for i in range(8):
+        a, l, t = profile(rng, 2, [2])
+        acc += a
+        lat += [v // 4 for v in l]
+        thr += [v * 40 for v in t]
+    p = SimpleNamespace(n_tasks=8, parent=[-1, 0, 1, 2, 3, 4, 5, 6], fanout_q4=[4, 5, 4, 6, 4, 5, 4, 4],
+                        n_variants=[2] * 8, n_batches=[1] * 8, batch_size=[2] * 8, max_replicas=[1, 2] * 8,
+                        acc_ppm=acc, latency_us=lat, thr_mqps=thr)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    assert P.num_candidates() == 6 ** 8
+    for demand, W, comm in ((10_000, 12, 0), (200_000, 20, 500), (0, 8, 0)):
+        ref = O.search(demand, W, 200_000, comm)
+        for flags in (0, LANE):
+            res = P.alloc_search([demand], W, 200_000, comm, flags=flags)[0]
+            assert agree(res, ref), (demand, W, flags, res.as_tuple(), ref.as_tuple())
+
+
+def test_many_demand_points_in_one_call():
+    w = wl.config(1)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    rng = random.Random(2)
+    demands = [rng.randint(0, 260_000) for _ in range(3000)]
+    out = P.alloc_search(demands, w.workers, w.slo_us)
+    for d, res in list(zip(demands, out))[::37]:
+        assert agree(res, O.search(d, w.workers, w.slo_us)), d
+    # monotone in demand across the whole sweep (a property that needs no checker)
+    order = sorted(range(len(demands)), key=lambda i: demands[i])
+    accs = [out[i].accuracy if out[i].status == 0 else -1.0 for i in order]
+    assert all(a >= b for a, b in zip(accs, accs[1:]))
