@@ -55,6 +55,16 @@ __device__ __forceinline__ T pick(const T (&v)[kMaxTasks], int idx) {
     return r;
 }
 
+// v[idx] for a uniform idx known to be below `bound` (a compile-time constant after unrolling).
+template <typename T>
+__device__ __forceinline__ T pick_below(const T (&v)[kMaxTasks], int idx, int bound) {
+    T r = v[0];
+#pragma unroll
+    for (int q = 1; q < kMaxTasks; q++)
+        if (q < bound) r = (idx == q) ? v[q] : r;
+    return r;
+}
+
 __device__ __forceinline__ uint32_t uni(uint32_t v) {
     return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
 }
@@ -414,18 +424,35 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     int32_t bw = kNever;
     uint64_t bidx = ~0ull;
     uint64_t nfeas = 0;  // wavefront total
-    uint64_t cur_group = ~0ull;
+    uint32_t cur_group = ~0u;
     uint32_t cbase = 0;  // first choice of the last task in this wavefront's chunk
     uint32_t cl0 = 0;    // this lane's choice in slot 0
 
+    // Position of the first item in (tile r, digits of the tasks in between, chunk group g);
+    // later items advance it like an odometer, so no division sits in the item loop.
+    uint32_t r = 0, g = 0;
+    uint32_t cj[kMaxTasks];  // choice of every task strictly between the first and the last
+    uint64_t f = 0;          // those digits as one number: sum cj[j] * prod_{1<=i<j} C_i
+    {
+        r = static_cast<uint32_t>(item_lo % A.mid_tiles);
+        const uint64_t t = item_lo / A.mid_tiles;
+        f = t % A.far_count;
+        g = static_cast<uint32_t>(t / A.far_count);
+        uint64_t rest = f;
+#pragma unroll
+        for (int j = 1; j < kMaxTasks; j++) {
+            cj[j] = 0;
+            if (j < L) {
+                cj[j] = static_cast<uint32_t>(rest % sP->C[j]);
+                rest /= sP->C[j];
+            }
+        }
+        cj[0] = 0;
+    }
     for (uint64_t item = item_lo; item < item_hi; ++item) {
-        const uint32_t r = static_cast<uint32_t>(item % A.mid_tiles);
-        const uint64_t t = item / A.mid_tiles;
-        const uint64_t f = t % A.far_count;
-        const uint64_t g = t / A.far_count;
         if (g != cur_group) {
             cur_group = g;
-            cbase = A.cl_first + (static_cast<uint32_t>(g) * cpb + chunk_in_group) * (64u * S);
+            cbase = A.cl_first + (g * cpb + chunk_in_group) * (64u * S);
             cl0 = cbase + lane;
 #pragma unroll
             for (int s = 0; s < S; s++) {
@@ -442,26 +469,44 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                 }
             }
         }
-        // records of the tasks strictly between the first and the last (uniform)
+        // What the tasks strictly between the first and the last contribute (the same for the
+        // whole tile): replicas, feasibility, latency along each chain without the first task.
         double fa[kMaxTasks];
-        int32_t fw[kMaxTasks], flat[kMaxTasks];
-        {
-            uint64_t rest = f;
+        int64_t flp[kMaxTasks];  // latency sum over root..j without the root
+        int64_t w_far = 0;
+        bool ok_far = true;
+        int64_t lat0_cap = kNever - 1;  // largest first-task latency every other leaf's path tolerates
 #pragma unroll
-            for (int j = 1; j < kMaxTasks; j++) {
-                fa[j] = 0.0;
-                fw[j] = 0;
-                flat[j] = 0;
-                if (j < L) {
-                    const uint32_t cj = static_cast<uint32_t>(rest % sP->C[j]);
-                    rest /= sP->C[j];
-                    const TaskRec rec = tab[sP->table_off[j] + cj];
-                    fa[j] = rec.a;
-                    fw[j] = rec.w;
-                    flat[j] = rec.lat;
-                }
+        for (int j = 0; j < kMaxTasks; j++) {
+            fa[j] = 1.0;
+            flp[j] = 0;
+        }
+#pragma unroll
+        for (int j = 1; j < kMaxTasks; j++) {
+            if (j < L) {
+                const TaskRec rec = tab[sP->table_off[j] + cj[j]];
+                fa[j] = rec.a;
+                w_far += rec.w;
+                ok_far = ok_far && rec.lat != kNever;
+                flp[j] = pick_below(flp, sP->parent[j], j) + rec.lat;
             }
         }
+#pragma unroll
+        for (int j = 0; j < kMaxTasks; j++) {
+            if (j < L && sP->is_leaf[j]) {
+                const int64_t room = A.budget[j] < 0 ? -1 : A.budget[j] - flp[j];
+                if (room < lat0_cap) lat0_cap = room;
+            }
+        }
+        if (lat0_cap < 0) ok_far = false;
+        int64_t tl_base = A.budget[L];  // latency left for the first and the last task together
+        int parL = 0;
+        if (n >= 2) {
+            parL = sP->parent[L];
+            tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parL, kMaxTasks);
+        }
+        const int64_t w_room = static_cast<int64_t>(W) - w_far;
+
         const uint32_t tile_base = r * kMidTile;
         const uint32_t cnt = mid_count - tile_base < static_cast<uint32_t>(kMidTile) ? mid_count - tile_base
                                                                                       : static_cast<uint32_t>(kMidTile);
@@ -469,43 +514,26 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 
         __syncthreads();  // the previous item's tile is no longer being read
         for (uint32_t e = threadIdx.x; e < cnt; e += kBlockThreads) {
-            const uint32_t cM = n >= 2 ? perm[tile_base + e] : 0u;
+            uint32_t cM = 0;
+            double a0 = 1.0;
+            int64_t w0 = 0, lat0 = 0;
+            bool ok = ok_far;
+            if (n >= 2) {
+                cM = perm[tile_base + e];
+                const TaskRec rec = tab[cM];
+                a0 = rec.a;
+                w0 = rec.w;
+                lat0 = rec.lat;
+                ok = ok && rec.lat != kNever && lat0 <= lat0_cap;
+            }
+            // path values root first: pp[j] = pp[parent[j]] * a_j  (eq. (12) objective, product stand-in)
             double pp[kMaxTasks];
-            int64_t pl[kMaxTasks];
-            int64_t wsum = 0;
-            bool ok = true;
 #pragma unroll
-            for (int j = 0; j < kMaxTasks; j++) {
-                pp[j] = 1.0;
-                pl[j] = 0;
-            }
+            for (int j = 0; j < kMaxTasks; j++) pp[j] = 1.0;
+            pp[0] = a0;
 #pragma unroll
-            for (int j = 0; j < kMaxTasks; j++) {
-                if (j < L) {
-                    double aj;
-                    int32_t wj, lj;
-                    if (j == 0) {
-                        const TaskRec rec = tab[cM];
-                        aj = rec.a;
-                        wj = rec.w;
-                        lj = rec.lat;
-                    } else {
-                        aj = fa[j];
-                        wj = fw[j];
-                        lj = flat[j];
-                    }
-                    ok = ok && lj != kNever;
-                    wsum += wj;
-                    if (j == 0) {
-                        pp[0] = aj;
-                        pl[0] = lj;
-                    } else {
-                        const int par = sP->parent[j];
-                        pp[j] = pick(pp, par) * aj;
-                        pl[j] = pick(pl, par) + lj;
-                    }
-                }
-            }
+            for (int j = 1; j < kMaxTasks; j++)
+                if (j < L) pp[j] = pick_below(pp, sP->parent[j], j) * fa[j];
             MidVal uv;
             MidLim ul;
             uv.presum = 0.0;
@@ -513,23 +541,16 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 #pragma unroll
             for (int j = 0; j < kMaxTasks; j++) {
                 if (j < L && sP->is_leaf[j]) {
-                    ok = ok && A.budget[j] >= 0 && pl[j] <= A.budget[j];
                     uv.presum = first ? pp[j] : uv.presum + pp[j];
                     first = false;
                 }
             }
-            int64_t tl = A.budget[L];
-            if (n >= 2) {
-                const int par = sP->parent[L];
-                uv.pre = pick(pp, par);
-                tl = tl < 0 ? -1 : tl - pick(pl, par);
-            } else {
-                uv.pre = 1.0;
-            }
+            uv.pre = n >= 2 ? pick_below(pp, parL, kMaxTasks) : 1.0;
+            int64_t tl = tl_base < 0 ? -1 : tl_base - lat0;
             if (tl < 0) tl = -1;
             if (tl > kNever - 1) tl = kNever - 1;
             ul.tl = static_cast<int32_t>(tl);
-            const int64_t wr = static_cast<int64_t>(W) - wsum;
+            const int64_t wr = w_room - w0;
             ul.w_rem = (ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
             ul.cl_lo = 0;
             ul.cl_cnt = CL;
@@ -625,6 +646,26 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             e = run_hi;
         }
         nfeas += fcount;
+        // next item
+        if (++r == A.mid_tiles) {
+            r = 0;
+            ++f;
+            bool carry = true;
+#pragma unroll
+            for (int j = 1; j < kMaxTasks; j++) {
+                if (j < L && carry) {
+                    if (++cj[j] == sP->C[j]) {
+                        cj[j] = 0;
+                    } else {
+                        carry = false;
+                    }
+                }
+            }
+            if (carry) {  // every digit wrapped (or there is none): next chunk group
+                f = 0;
+                ++g;
+            }
+        }
     }
     // the key is the path sum unless DIVIDE; dividing by the (power-of-two) path count is exact and monotone
     double bacc = bsum;
