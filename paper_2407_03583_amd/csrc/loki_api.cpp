@@ -246,7 +246,8 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
             const uint32_t cl_last = static_cast<uint32_t>((index_end - 1) / strideL);
             const uint32_t n_chunks = (cl_last - cl_first + 1 + chunk - 1) / chunk;
             A.cl_first = cl_first;
-            A.cpb = n_chunks >= 4 ? 4u : (n_chunks >= 2 ? 2u : 1u);
+            A.cpb = 1;
+            while (A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
             A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
             A.items = uint64_t(A.chunk_groups) * F * A.mid_tiles;
         }

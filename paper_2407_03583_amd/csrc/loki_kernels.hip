@@ -47,22 +47,28 @@ struct EvalOut {  // mirrors loki_eval_t
     uint32_t infeasible;
 };
 
-template <typename T>
-__device__ __forceinline__ T pick(const T (&v)[kMaxTasks], int idx) {
-    T r = v[0];
+// v[idx] for a uniform idx known to be below `bound` (a compile-time constant after unrolling).
+// Blended with integer masks rather than selected: a chain of selects over array elements is
+// folded by the optimizer into one dynamically indexed load, which would push the array into
+// scratch memory.
+__device__ __forceinline__ uint64_t pick_bits(const uint64_t (&v)[kMaxTasks], int idx, int bound) {
+    uint64_t r = 0;
 #pragma unroll
-    for (int q = 1; q < kMaxTasks; q++) r = (idx == q) ? v[q] : r;
+    for (int q = 0; q < kMaxTasks; q++)
+        if (q < bound) r |= v[q] & (idx == q ? ~0ull : 0ull);
     return r;
 }
-
-// v[idx] for a uniform idx known to be below `bound` (a compile-time constant after unrolling).
-template <typename T>
-__device__ __forceinline__ T pick_below(const T (&v)[kMaxTasks], int idx, int bound) {
-    T r = v[0];
+__device__ __forceinline__ double pick_below(const double (&v)[kMaxTasks], int idx, int bound) {
+    uint64_t b[kMaxTasks];
 #pragma unroll
-    for (int q = 1; q < kMaxTasks; q++)
-        if (q < bound) r = (idx == q) ? v[q] : r;
-    return r;
+    for (int q = 0; q < kMaxTasks; q++) b[q] = static_cast<uint64_t>(__double_as_longlong(v[q]));
+    return __longlong_as_double(static_cast<long long>(pick_bits(b, idx, bound)));
+}
+__device__ __forceinline__ int64_t pick_below(const int64_t (&v)[kMaxTasks], int idx, int bound) {
+    uint64_t b[kMaxTasks];
+#pragma unroll
+    for (int q = 0; q < kMaxTasks; q++) b[q] = static_cast<uint64_t>(v[q]);
+    return static_cast<int64_t>(pick_bits(b, idx, bound));
 }
 
 __device__ __forceinline__ uint32_t uni(uint32_t v) {
@@ -165,8 +171,8 @@ __device__ __forceinline__ void eval_plan(const DevProblem *P, const uint32_t (&
                 pl[0] = o.maxlat;
             } else {
                 const int par = P->parent[i];
-                pp[i] = pick(pp, par) * a;
-                pl[i] = pick(pl, par) + o.maxlat;
+                pp[i] = pick_below(pp, par, i) * a;
+                pl[i] = pick_below(pl, par, i) + o.maxlat;
             }
         }
     }
