@@ -395,6 +395,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
     __shared__ MidVal sVal[kMidTile];
     __shared__ MidLim sLim[kMidTile];
+    __shared__ uint32_t sChoice[kMidTile];  // first-task choice of each tile entry (cold path only)
     __shared__ BestRec sBest[kWavesPerBlock];
     DevProblem *sP = reinterpret_cast<DevProblem *>(sPraw);  // only the head is valid
     stage_problem(sP, A.P, kHeadBytes);
@@ -426,9 +427,16 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 
     double a[S];
     int32_t w[S], lat[S];
-    double bsum = -1.0;  // best key so far in this lane (path sum, or accuracy when DIVIDE)
+    // best plan so far in this lane: key (path sum, or accuracy when DIVIDE), workers, and the index
+    // split into the last task's choice and the rest (index = rest + strideL * choice, rest < strideL)
+    double bsum = -1.0;
     int32_t bw = kNever;
-    uint64_t bidx = ~0ull;
+    uint32_t bcl = ~0u;
+    uint64_t blow = ~0ull;
+    // of this lane's slots that can ever be feasible: fewest replicas and the lowest choice having them,
+    // and the lowest choice at all (what a tie needs to beat the lane's best is bounded by these)
+    int32_t minw = kNever;
+    uint32_t cmin = ~0u, cfirst = ~0u;
     uint64_t nfeas = 0;  // wavefront total
     uint32_t cur_group = ~0u;
     uint32_t cbase = 0;  // first choice of the last task in this wavefront's chunk
@@ -472,6 +480,19 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     a[s] = 0.0;
                     w[s] = 0;
                     lat[s] = kNever;
+                }
+            }
+            minw = kNever;
+            cmin = ~0u;
+            cfirst = ~0u;
+#pragma unroll
+            for (int s = S - 1; s >= 0; s--) {
+                if (lat[s] != kNever) {
+                    cfirst = cl0 + s * 64;
+                    if (w[s] <= minw) {
+                        minw = w[s];
+                        cmin = cl0 + s * 64;
+                    }
                 }
             }
         }
@@ -570,6 +591,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             }
             sVal[e] = uv;
             sLim[e] = ul;
+            sChoice[e] = cM;
         }
         __syncthreads();
 
@@ -611,24 +633,42 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                 }
                 fcount += run_feas;
                 if (__builtin_expect(__builtin_amdgcn_ballot_w64(kmax >= bsum) != 0, 0)) {
-                    // rare: some lane may have a new best; redo the slots with the real masks and the full order
+                    // Some lane's maximum reached its best.  Usually that is a tie that cannot win:
+                    // first bound what a tie of this lane could achieve, and only if some lane can
+                    // really improve redo the slots with the real masks and the full order.
                     asm volatile("" : "+s"(ee));
                     uint32_t cl = cl0;
                     asm volatile("" : "+v"(cl));
-                    const uint32_t cM = n >= 2 ? perm[tile_base + ee] : 0u;
+                    const uint64_t low = base_f + sChoice[ee];  // index of the plan without the last task's part
                     const int32_t w_out = W - ul.w_rem;
+                    bool maybe = kmax > bsum;
+                    const bool low_wins = low < blow;
+                    if (tie_index_only) {
+                        maybe = maybe | (cfirst < bcl) | ((cfirst == bcl) & low_wins);
+                    } else {
+                        const int32_t t = w_out + minw;
+                        maybe = maybe | (t < bw) | ((t == bw) & ((cmin < bcl) | ((cmin == bcl) & low_wins)));
+                    }
+                    if (__builtin_amdgcn_ballot_w64(maybe & (kmax >= bsum)) != 0) {
 #pragma unroll
-                    for (int s = 0; s < S; s++) {
-                        const double tprod = u.pre * a[s];
-                        double key = HAS_PRESUM ? u.presum + tprod : tprod;
-                        if (DIVIDE) key = key / npd;
-                        if (((fm[s] >> lane) & 1) && key >= bsum) {
-                            const uint64_t idx = base_f + cM + strideL * (cl + s * 64);
-                            const int32_t wt = w_out + w[s];
-                            if (better(key, wt, idx, bsum, bw, bidx, tie_index_only)) {
-                                bsum = key;
-                                bw = wt;
-                                bidx = idx;
+                        for (int s = 0; s < S; s++) {
+                            const double tprod = u.pre * a[s];
+                            double key = HAS_PRESUM ? u.presum + tprod : tprod;
+                            if (DIVIDE) key = key / npd;
+                            if (((fm[s] >> lane) & 1) && key >= bsum) {
+                                const uint32_t cL = cl + s * 64;
+                                const int32_t wt = w_out + w[s];
+                                bool win = key > bsum;
+                                if (key == bsum) {
+                                    const bool idx_wins = (cL < bcl) | ((cL == bcl) & low_wins);
+                                    win = tie_index_only ? idx_wins : ((wt < bw) | ((wt == bw) & idx_wins));
+                                }
+                                if (win) {
+                                    bsum = key;
+                                    bw = wt;
+                                    bcl = cL;
+                                    blow = low;
+                                }
                             }
                         }
                     }
@@ -676,6 +716,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     // the key is the path sum unless DIVIDE; dividing by the (power-of-two) path count is exact and monotone
     double bacc = bsum;
     if (!DIVIDE && bsum >= 0.0) bacc = bsum / npd;
+    const uint64_t bidx = bsum >= 0.0 ? blow + strideL * bcl : ~0ull;
     __syncthreads();
     block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
                      A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
