@@ -109,6 +109,12 @@ typedef struct {
     const int32_t *acc_ppm;      /* concatenated over (task, variant): A(v_ik) in 0..1000000 */
     const int64_t *latency_us;   /* concatenated over (task, variant, batch): 1..2^30 */
     const int64_t *thr_mqps;     /* concatenated over (task, variant, batch): per-replica throughput, 0..2^40 */
+    const int32_t *variant_factor_q4; /* NULL, or concatenated over (task, variant): the multiplicative factor
+                                    r(i,k) of eq. (1) in quarters, 1..64.  With it the requests task i creates
+                                    for a child j are sum_k routed(i,k) * r(i,k) * fanout_q4[j] (Section 5.1:
+                                    outgoing = incoming * multFactor * branchRatio), a child's demand depends
+                                    on its parent's part of the plan, tasks work in units of milli-QPS /
+                                    16^depth, and every search runs with LOKI_SEARCH_PER_LANE. */
 } loki_pipeline_t;
 
 typedef struct loki_problem loki_problem_t; /* opaque handle */

@@ -44,7 +44,8 @@ class _Pipeline(C.Structure):
                 ("max_replicas", C.POINTER(C.c_int32)),
                 ("acc_ppm", C.POINTER(C.c_int32)),
                 ("latency_us", C.POINTER(C.c_int64)),
-                ("thr_mqps", C.POINTER(C.c_int64))]
+                ("thr_mqps", C.POINTER(C.c_int64)),
+                ("variant_factor_q4", C.POINTER(C.c_int32))]
 
 
 class EvalOut(C.Structure):
@@ -133,6 +134,9 @@ class Problem:
             "latency_us": _arr(C.c_int64, pipeline.latency_us),
             "thr_mqps": _arr(C.c_int64, pipeline.thr_mqps),
         }
+        vf = getattr(pipeline, "variant_factor_q4", None)
+        if vf is not None:
+            self._keep["variant_factor_q4"] = _arr(C.c_int32, vf)
         k = self._keep
         self.c = _Pipeline(self.n_tasks,
                            C.cast(k["parent"], C.POINTER(C.c_int32)),
@@ -143,7 +147,9 @@ class Problem:
                            C.cast(k["max_replicas"], C.POINTER(C.c_int32)),
                            C.cast(k["acc_ppm"], C.POINTER(C.c_int32)),
                            C.cast(k["latency_us"], C.POINTER(C.c_int64)),
-                           C.cast(k["thr_mqps"], C.POINTER(C.c_int64)))
+                           C.cast(k["thr_mqps"], C.POINTER(C.c_int64)),
+                           C.cast(k["variant_factor_q4"], C.POINTER(C.c_int32)) if vf is not None
+                           else C.POINTER(C.c_int32)())
 
     def num_candidates(self) -> int:
         return int(lib().lo_num_candidates(C.byref(self.c)))

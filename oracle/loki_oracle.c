@@ -94,17 +94,25 @@ uint64_t lo_encode(const lo_pipeline *p, const int32_t *x, const int32_t *batch_
     return index;
 }
 
-/* ---- demand at each task (eq. (1) with one factor per edge) -----------------
- * Dn_i = D * prod of fan-out quarters on the edges root -> i; the task works in
- * units of milli-QPS / 4^depth_i, so Dn_i / scale_i is its demand in milli-QPS. */
+/* ---- demand at each task (eq. (1)) ---------------------------------------------
+ * Per-edge model: Dn_i = D * prod of fan-out quarters on the edges root -> i; the task
+ * works in units of milli-QPS / 4^depth_i, so Dn_i / scale_i is its demand in milli-QPS.
+ * With per-variant factors a level multiplies by two quarter-valued numbers, the units
+ * are milli-QPS / 16^depth_i, and Dn_i follows from the parent's routing (see lo_eval). */
+static void task_scale(const lo_pipeline *p, int64_t *scale)
+{
+    int64_t per_level = p->variant_factor_q4 ? 16 : 4;
+    scale[0] = 1;
+    for (int i = 1; i < p->n_tasks; i++)
+        scale[i] = scale[p->parent[i]] * per_level;
+}
+
 static void task_demand(const lo_pipeline *p, int64_t demand_mqps, int64_t *Dn, int64_t *scale)
 {
+    task_scale(p, scale);
     Dn[0] = demand_mqps;
-    scale[0] = 1;
-    for (int i = 1; i < p->n_tasks; i++) {
+    for (int i = 1; i < p->n_tasks; i++)
         Dn[i] = Dn[p->parent[i]] * (int64_t)p->fanout_q4[i];
-        scale[i] = scale[p->parent[i]] * 4;
-    }
 }
 
 /* ---- route order: accuracy descending, variant index ascending ------------- */
@@ -131,6 +139,7 @@ typedef struct {
     int64_t maxlat;    /* max latency over variants in use */
     int64_t weighted;  /* N_i = sum routed_k * acc_ppm_k */
     int32_t first_acc; /* acc_ppm of the first hosted variant in route order */
+    int64_t outflow;   /* sum routed_k * r(i,k): requests created per unit of child fan-out */
 } lo_task_t;
 
 static void task_eval(const lo_pipeline *p, const lo_layout *L, int i, const int32_t *x, int32_t beta,
@@ -147,6 +156,7 @@ static void task_eval(const lo_pipeline *p, const lo_layout *L, int i, const int
     t->maxlat = 0;
     t->weighted = 0;
     t->first_acc = 0;
+    t->outflow = 0;
     if (routed_out)
         for (int k = 0; k < K; k++)
             routed_out[k] = 0;
@@ -164,6 +174,8 @@ static void task_eval(const lo_pipeline *p, const lo_layout *L, int i, const int
         if (!t->any)
             t->first_acc = p->acc_ppm[L->voff[i] + k];
         t->weighted += routed * (int64_t)p->acc_ppm[L->voff[i] + k];
+        if (p->variant_factor_q4)
+            t->outflow += routed * (int64_t)p->variant_factor_q4[L->voff[i] + k];
         rem -= routed;
         t->any = 1;
         if (routed_out)
@@ -259,8 +271,11 @@ void lo_eval(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, int32_t 
     layout_of(p, &L);
     lo_decode(p, index, x, beta);
     task_demand(p, demand_mqps, Dn, scale);
-    for (int i = 0; i < L.n; i++)
+    for (int i = 0; i < L.n; i++) {
+        if (p->variant_factor_q4 && i > 0) /* what the parent's variants create for this child */
+            Dn[i] = t[p->parent[i]].outflow * (int64_t)p->fanout_q4[i];
         task_eval(p, &L, i, x + L.voff[i], beta[i], Dn[i], scale[i], &t[i], NULL);
+    }
     pipeline_eval(p, t, Dn, workers, slo_us, comm_us, out);
 }
 
@@ -356,6 +371,10 @@ void lo_search_tabulated(const lo_pipeline *p, int64_t demand_mqps, int32_t work
     lo_layout L;
     int64_t Dn[LO_MAX_TASKS], scale[LO_MAX_TASKS];
     lo_task_t *table[LO_MAX_TASKS];
+    if (p->variant_factor_q4) { /* a task's demand is not fixed: no table */
+        lo_search(p, demand_mqps, workers, slo_us, comm_us, tie_index_only, index_begin, index_end, 1, n_threads, out);
+        return;
+    }
     layout_of(p, &L);
     task_demand(p, demand_mqps, Dn, scale);
     for (int i = 0; i < L.n; i++) {
@@ -461,6 +480,12 @@ void lo_route_table(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, l
                 int corder[LO_MAX_VARIANTS];
                 route_order(p, &L, j, corder);
                 int64_t outgoing = r->routed[i][k] * (int64_t)p->fanout_q4[j];
+                if (p->variant_factor_q4) { /* the child's demand is what its parent's variants create */
+                    outgoing *= (int64_t)p->variant_factor_q4[L.voff[i] + k];
+                    if (o == 0)
+                        r->demand[j] = 0;
+                    r->demand[j] += outgoing;
+                }
                 int64_t total = outgoing;
                 for (int co = 0; co < p->n_variants[j]; co++) {
                     int ck = corder[co];

@@ -9,7 +9,11 @@
  *   a candidate allocation plan gives, per task i, a replica count x(i,k) for
  *   every model variant k and one batch size for the task.  It is scored by
  *   - per-task demand: root demand D times the fan-out of every edge on the
- *     way to the task (eq. (1), per-edge factors),
+ *     way to the task (eq. (1), per-edge factors); with per-variant factors
+ *     r(i,k) the requests a task creates are the sum over its variants of the
+ *     traffic placed on the variant times its factor (eq. (1) as printed,
+ *     Algorithm 1's outgoing = incoming * multFactor * branchRatio), so a
+ *     child's demand depends on the parent's part of the plan,
  *   - the worker budget  sum x(i,k) <= S  (eq. (3)),
  *   - serving all of each task's demand within the hosted capacity
  *     x(i,k) * q(i,k,b) (eq. (2)), traffic placed most-accurate-variant-first
@@ -62,6 +66,9 @@ typedef struct {
     const int32_t *acc_ppm;      /* concat over (task, variant) */
     const int64_t *latency_us;   /* concat over (task, variant, batch) */
     const int64_t *thr_mqps;     /* concat over (task, variant, batch) */
+    const int32_t *variant_factor_q4; /* NULL, or concat over (task, variant): multiplicative factor r(i,k)
+                                         of eq. (1) in quarters; requests created for a child =
+                                         sum_k routed_k * r(i,k) * fanout(child) (Section 5.1) */
 } lo_pipeline;
 
 typedef struct {
@@ -110,7 +117,9 @@ void lo_search(const lo_pipeline *p, int64_t demand_mqps, int32_t workers, int64
 
 /* Same search with each task's per-choice result tabulated once and looked up
  * while walking the indices in order: the same two functions lo_eval calls
- * (task part, then pipeline part), composed through a table. */
+ * (task part, then pipeline part), composed through a table.  Only without
+ * per-variant factors (with them a task's demand is not fixed); falls back to
+ * lo_search otherwise. */
 void lo_search_tabulated(const lo_pipeline *p, int64_t demand_mqps, int32_t workers, int64_t slo_us,
                          int64_t comm_us, int tie_index_only, uint64_t index_begin,
                          uint64_t index_end, int n_threads, lo_best_t *out);

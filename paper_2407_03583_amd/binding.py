@@ -47,7 +47,8 @@ class PipelineC(C.Structure):
                 ("max_replicas", C.POINTER(C.c_int32)),
                 ("acc_ppm", C.POINTER(C.c_int32)),
                 ("latency_us", C.POINTER(C.c_int64)),
-                ("thr_mqps", C.POINTER(C.c_int64))]
+                ("thr_mqps", C.POINTER(C.c_int64)),
+                ("variant_factor_q4", C.POINTER(C.c_int32))]
 
 
 class Result(C.Structure):
@@ -138,7 +139,11 @@ def _pipeline_struct(p):
     keep = [_arr(C.c_int32, p.parent), _arr(C.c_int32, p.fanout_q4), _arr(C.c_int32, p.n_variants),
             _arr(C.c_int32, p.n_batches), _arr(C.c_int32, p.batch_size), _arr(C.c_int32, p.max_replicas),
             _arr(C.c_int32, p.acc_ppm), _arr(C.c_int64, p.latency_us), _arr(C.c_int64, p.thr_mqps)]
-    s = PipelineC(int(p.n_tasks), *[C.cast(a, C.POINTER(a._type_)) for a in keep])
+    vf = getattr(p, "variant_factor_q4", None)
+    vf_arr = _arr(C.c_int32, vf) if vf is not None else None
+    s = PipelineC(int(p.n_tasks), *[C.cast(a, C.POINTER(a._type_)) for a in keep],
+                  C.cast(vf_arr, C.POINTER(C.c_int32)) if vf_arr is not None else C.POINTER(C.c_int32)())
+    keep.append(vf_arr)
     return s, keep
 
 

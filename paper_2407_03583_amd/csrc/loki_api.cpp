@@ -70,6 +70,7 @@ struct loki_problem {
     int32_t batch_size[kMaxTasks][kMaxBatches];
     int64_t thr[kMaxTasks][kMaxVariants][kMaxBatches];  // unscaled
     int32_t voff[kMaxTasks];
+    int32_t max_vf[kMaxTasks];  // largest variant factor of the task (4 without per-variant factors)
     uint64_t n_candidates;
     // pinned staging: [DevProblem | Dn (cap_points * 8 int64) | results (cap_points)]
     unsigned char *staging = nullptr;
@@ -121,8 +122,10 @@ int ensure_staging(loki_problem *p, int64_t points) {
     return LOKI_OK;
 }
 
-// Demand at each task (eq. (1), one factor per edge) with the overflow proof for
-// everything downstream: Dn_i * 10^6 must stay below 2^53.
+// Demand at each task (eq. (1)) with the overflow proof for everything downstream:
+// Dn_i * 10^6 must stay below 2^53.  With one factor per edge Dn_i is exact; with per-variant
+// factors it is the largest value any plan can reach (every request served by the variant
+// with the largest factor) and only Dn_0 is used by the kernels.
 int task_demand(const loki_problem *p, int64_t demand_mqps, int64_t *Dn) {
     if (demand_mqps < 0) return LOKI_E_RANGE;
     Dn[0] = demand_mqps;
@@ -132,9 +135,10 @@ int task_demand(const loki_problem *p, int64_t demand_mqps, int64_t *Dn) {
             continue;
         }
         if (i > 0) {
-            const int64_t up = Dn[p->dev.parent[i]];
-            if (up > kTwo53 / 1000000 / p->fanout_q4[i]) return LOKI_E_RANGE;
-            Dn[i] = up * p->fanout_q4[i];
+            const int par = p->dev.parent[i];
+            const int64_t factor = int64_t(p->fanout_q4[i]) * (p->dev.has_vf ? p->max_vf[par] : 1);
+            if (Dn[par] > kTwo53 / 1000000 / factor) return LOKI_E_RANGE;
+            Dn[i] = Dn[par] * factor;
         }
         if (Dn[i] >= kTwo53 / 1000000) return LOKI_E_RANGE;
     }
@@ -165,6 +169,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     if (n_demand < 1 || n_demand > LOKI_MAX_DEMAND_POINTS) return LOKI_E_ARG;
     if (flags & ~(LOKI_TIE_INDEX_ONLY | LOKI_SEARCH_PER_LANE)) return LOKI_E_ARG;
     if (index_begin > index_end || index_end > p->n_candidates) return LOKI_E_ARG;
+    if (p->dev.has_vf) flags |= LOKI_SEARCH_PER_LANE;  // a task's demand depends on its parent's part of the plan
     int rc = check_scalars(workers, slo_us, comm_us);
     if (rc) return rc;
     const Layout lay = search_layout(p->dev.table_total, p->dev.C[0], n_demand);
@@ -288,6 +293,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
     DevProblem &d = p->dev;
     p->n = n;
     d.n_tasks = n;
+    d.has_vf = in->variant_factor_q4 ? 1 : 0;
     int v = 0, b = 0, t = 0;
     uint64_t N = 1;
     uint32_t table_total = 0;
@@ -310,8 +316,11 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         d.K[i] = K;
         d.nb[i] = nb;
         p->voff[i] = v;
-        const int64_t scale = int64_t(1) << (2 * p->depth[i]);
+        const int per_level_bits = in->variant_factor_q4 ? 4 : 2;  // units of milli-QPS / 16^depth or / 4^depth
+        const int64_t scale = int64_t(1) << (per_level_bits * p->depth[i]);
         uint64_t choices = uint64_t(nb);
+        d.fanout[i] = i > 0 ? in->fanout_q4[i] : 4;
+        p->max_vf[i] = 4;
         for (int bi = 0; bi < nb; bi++) {
             const int32_t bs = in->batch_size[b + bi];
             if (bs < 1 || (bi > 0 && bs <= in->batch_size[b + bi - 1])) rc = LOKI_E_RANGE;
@@ -326,6 +335,16 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
             d.radix[i][k] = uint32_t(R) + 1;
             d.magic[i][k] = R == 0 ? 0u : uint32_t(((uint64_t(1) << 32) + uint64_t(R)) / (uint64_t(R) + 1));
             d.acc[i][k] = acc;
+            d.vf[i][k] = 4;
+            if (in->variant_factor_q4) {
+                const int32_t f = in->variant_factor_q4[v + k];
+                if (f < 1 || f > 64) {
+                    rc = LOKI_E_RANGE;
+                    break;
+                }
+                d.vf[i][k] = f;
+                p->max_vf[i] = k == 0 ? f : std::max(p->max_vf[i], f);
+            }
             choices *= uint64_t(R) + 1;
             if (choices > LOKI_MAX_CHOICES) {
                 rc = LOKI_E_RANGE;
@@ -336,7 +355,8 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
                 if (lat < 1 || lat > (int64_t(1) << 30) || thr < 0 || thr > (int64_t(1) << 40)) rc = LOKI_E_RANGE;
                 d.lat[i][k][bi] = lat;
                 p->thr[i][k][bi] = thr;
-                d.thr_s[i][k][bi] = thr * scale;  // <= 2^40 * 4^7 = 2^54; times 255 replicas stays below 2^63
+                if (thr > (int64_t(1) << 54) / scale) rc = LOKI_E_RANGE;  // keeps 255 replicas * thr * scale below 2^63
+                d.thr_s[i][k][bi] = thr * scale;
             }
         }
         if (rc) break;
@@ -519,7 +539,7 @@ int loki_route_table(const loki_problem_t *p, uint64_t index, int64_t demand_mqp
         const int beta = int(c);
         r.batch[i] = p->batch_size[i][beta];
         r.demand[i] = Dn[i];
-        r.scale[i] = int64_t(1) << (2 * p->depth[i]);
+        r.scale[i] = int64_t(1) << ((p->dev.has_vf ? 4 : 2) * p->depth[i]);
         for (int k = 0; k < p->dev.K[i]; k++) {
             r.capacity[i][k] = int64_t(r.replicas[i][k]) * p->dev.thr_s[i][k][beta];
             r.leftover[i][k] = r.capacity[i][k];
@@ -544,9 +564,16 @@ int loki_route_table(const loki_problem_t *p, uint64_t index, int64_t demand_mqp
     for (int i = 0; i < n; i++)
         for (int o = 0; o < p->dev.K[i]; o++) {
             const int k = p->dev.order[i][o];
-            for (int j = i + 1; j < n; j++)
-                if (p->dev.parent[j] == i)
-                    r.unserved[j] += place(j, r.routed[i][k] * int64_t(p->fanout_q4[j]), r.prob[j][k]);
+            for (int j = i + 1; j < n; j++) {
+                if (p->dev.parent[j] != i) continue;
+                int64_t created = r.routed[i][k] * int64_t(p->fanout_q4[j]);
+                if (p->dev.has_vf) {  // the child's demand is what the parent's variants create
+                    created *= p->dev.vf[i][k];
+                    if (o == 0) r.demand[j] = 0;
+                    r.demand[j] += created;
+                }
+                r.unserved[j] += place(j, created, r.prob[j][k]);
+            }
         }
     *out = r;
     return LOKI_OK;

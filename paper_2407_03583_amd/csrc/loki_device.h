@@ -33,8 +33,10 @@ struct DevProblem {
     uint32_t table_total;                   // sum of C_i
     int32_t n_lat0;                         // number of distinct profiled latencies of task 0
     int32_t sum_r0;                         // sum of the replica limits of task 0
-    int32_t pad0;
+    int32_t has_vf;                         // per-variant multiplicative factors are present
     int32_t lat0_sorted[kMaxVariants * kMaxBatches];  // those latencies, ascending
+    int32_t fanout[kMaxTasks];              // quarters, edge parent[i] -> i
+    int32_t vf[kMaxTasks][kMaxVariants];    // quarters, by variant (4 everywhere when absent)
     uint64_t stride[kMaxTasks];             // prod_{j<i} C_j
     int64_t lat[kMaxTasks][kMaxVariants][kMaxBatches];    // microseconds
     int64_t thr_s[kMaxTasks][kMaxVariants][kMaxBatches];  // throughput * 4^depth

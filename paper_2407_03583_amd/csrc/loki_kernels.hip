@@ -94,6 +94,7 @@ struct TaskOut {
     int64_t maxlat;     // largest latency among variants in use
     int64_t weighted;   // sum routed * acc_ppm
     int32_t first_acc;  // accuracy of the first hosted variant in route order
+    int64_t outflow;    // sum routed * variant factor: what the task creates per unit of child fan-out
 };
 
 // Decode choice c of task i (variant 0 least significant, batch digit on top) and
@@ -112,8 +113,9 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         w += static_cast<int32_t>(x);
     }
     const uint32_t beta = c;
-    int64_t rem = Dn, maxlat = 0, weighted = 0;
+    int64_t rem = Dn, maxlat = 0, weighted = 0, outflow = 0;
     int32_t any = 0, first_acc = 0;
+    const bool has_vf = P->has_vf != 0;
     for (int r = 0; r < K; r++) {
         const int k = P->order[i][r];
         const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
@@ -126,6 +128,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         if (used && lat > maxlat) maxlat = lat;
         if (hosted && !any) first_acc = acc;
         weighted += routed * static_cast<int64_t>(acc);
+        if (has_vf) outflow += routed * static_cast<int64_t>(P->vf[i][k]);
         rem -= routed;
         any |= hosted ? 1 : 0;
     }
@@ -135,6 +138,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     o.maxlat = maxlat;
     o.weighted = weighted;
     o.first_acc = first_acc;
+    o.outflow = outflow;
 }
 
 // One correctly rounded fp64 division of two exactly converted integers (< 2^53).
@@ -148,29 +152,36 @@ __device__ __forceinline__ void eval_plan(const DevProblem *P, const uint32_t (&
                                           const int64_t *budget, int32_t W, uint32_t &mask, int32_t &workers,
                                           double &accuracy) {
     const int n = P->n_tasks;
-    double pp[kMaxTasks];   // product of accuracies root..i, root first
-    int64_t pl[kMaxTasks];  // latency sum root..i
+    const bool has_vf = P->has_vf != 0;
+    double pp[kMaxTasks];    // product of accuracies root..i, root first
+    int64_t pl[kMaxTasks];   // latency sum root..i
+    int64_t out[kMaxTasks];  // requests task i creates per unit of child fan-out (per-variant factors)
     mask = 0;
     workers = 0;
 #pragma unroll
     for (int i = 0; i < kMaxTasks; i++) {
         pp[i] = 0.0;
         pl[i] = 0;
+        out[i] = 0;
     }
 #pragma unroll
     for (int i = 0; i < kMaxTasks; i++) {
         if (i < n) {
+            const int par = i > 0 ? P->parent[i] : 0;
+            // eq. (1): fixed per task with per-edge factors, else what the parent's variants create
+            int64_t dn = Dn[i];
+            if (has_vf && i > 0) dn = pick_below(out, par, i) * static_cast<int64_t>(P->fanout[i]);
             TaskOut o;
-            eval_task(P, i, c[i], Dn[i], o);
+            eval_task(P, i, c[i], dn, o);
+            out[i] = o.outflow;
             workers += o.w;
             if (!o.any) mask |= kBadEmpty;
             if (o.rem > 0) mask |= kBadDemand;
-            const double a = task_accuracy(o, Dn[i]);
+            const double a = task_accuracy(o, dn);
             if (i == 0) {
                 pp[0] = a;
                 pl[0] = o.maxlat;
             } else {
-                const int par = P->parent[i];
                 pp[i] = pick_below(pp, par, i) * a;
                 pl[i] = pick_below(pl, par, i) + o.maxlat;
             }

@@ -26,7 +26,7 @@ from __future__ import annotations
 import hashlib
 import math
 from dataclasses import dataclass, field
-from typing import List, Sequence
+from typing import List, Optional, Sequence
 
 MASK64 = (1 << 64) - 1
 
@@ -76,6 +76,9 @@ class Pipeline:
     acc_ppm: List[int]           # concat over (task, variant)
     latency_us: List[int]        # concat over (task, variant, batch)
     thr_mqps: List[int]          # concat over (task, variant, batch)
+    # optional: multiplicative factor of each variant in quarters (4 = 1.00), concat over (task, variant);
+    # None = the factor of a task does not depend on the variant that served the request
+    variant_factor_q4: Optional[List[int]] = None
 
     def choices_per_task(self) -> List[int]:
         out, v = [], 0
@@ -99,6 +102,9 @@ class Pipeline:
                      "max_replicas", "acc_ppm", "latency_us", "thr_mqps"):
             h.update(name.encode())
             h.update(",".join(str(int(v)) for v in getattr(self, name)).encode())
+        if self.variant_factor_q4 is not None:
+            h.update(b"variant_factor_q4")
+            h.update(",".join(str(int(v)) for v in self.variant_factor_q4).encode())
         return h.hexdigest()
 
 
@@ -195,7 +201,7 @@ def config(cfg: int, seed: int | None = None) -> Workload:
 
 
 def random_small(seed: int, max_tasks: int = 3, max_variants: int = 3, max_replicas: int = 2,
-                 max_batches: int = 3, max_candidates: int = 20000) -> Workload:
+                 max_batches: int = 3, max_candidates: int = 20000, variant_factors: bool = False) -> Workload:
     """A small random problem (ragged K_i, R_ik and |B_i|, random tree) for
     exhaustive cross-checks.  Demand, worker count and SLO are drawn so that a
     healthy share of candidates is feasible."""
@@ -226,6 +232,9 @@ def random_small(seed: int, max_tasks: int = 3, max_variants: int = 3, max_repli
                     p.thr_mqps.append((b * 1_000_000_000) // lat)
         if 1 <= p.num_candidates() <= max_candidates:
             break
+    if variant_factors:
+        # a more accurate variant tends to create more downstream work (Section 4.2): factor grows with accuracy
+        p.variant_factor_q4 = [max(1, min(12, (a - 500000) // 60000 + rng.randint(0, 2))) for a in p.acc_ppm]
     demand = [0 if rng.randint(0, 9) == 0 else rng.randint(1_000, 400_000)]
     workers = rng.randint(1, 2 * n * max_replicas + 1)
     slo = rng.randint(40_000, 400_000)

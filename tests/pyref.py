@@ -29,7 +29,9 @@ def _tables(p):
         for k in range(p.n_variants[i]):
             lat = {bi: p.latency_us[t + k * len(batches) + bi] for bi in range(len(batches))}
             thr = {bi: p.thr_mqps[t + k * len(batches) + bi] for bi in range(len(batches))}
-            variants.append(dict(limit=p.max_replicas[v + k], acc=p.acc_ppm[v + k], lat=lat, thr=thr))
+            vf = getattr(p, "variant_factor_q4", None)
+            variants.append(dict(limit=p.max_replicas[v + k], acc=p.acc_ppm[v + k], lat=lat, thr=thr,
+                                 factor=None if vf is None else Fraction(vf[v + k], 4)))
         tasks.append(dict(batches=batches, variants=variants, parent=p.parent[i],
                           fan=Fraction(p.fanout_q4[i], 4)))
         v += p.n_variants[i]
@@ -65,10 +67,14 @@ def num_candidates(p) -> int:
 def evaluate(p, index: int, demand_mqps: int, workers: int, slo_us: int, comm_us: int = 0) -> Dict:
     tasks = _tables(p)
     plan = decode(p, index)
-    # demand per task in QPS (eq. (1), one factor per edge)
+    # demand per task in QPS (eq. (1)): with one factor per edge it is fixed up front; with
+    # per-variant factors a child's demand is what the parent's variants create (filled in below)
+    per_variant = tasks[0]["variants"][0]["factor"] is not None
     demand = []
     for i, task in enumerate(tasks):
-        demand.append(Fraction(demand_mqps, 1000) if i == 0 else demand[task["parent"]] * task["fan"])
+        demand.append(Fraction(demand_mqps, 1000) if i == 0 else
+                      (None if per_variant else demand[task["parent"]] * task["fan"]))
+    created = [Fraction(0)] * len(tasks)  # requests per second a task creates per unit of child fan-out
     mask = 0
     used_workers = sum(sum(xs) for xs, _ in plan)
     if used_workers > workers:
@@ -76,6 +82,8 @@ def evaluate(p, index: int, demand_mqps: int, workers: int, slo_us: int, comm_us
     acc_task, lat_task = [], []
     for i, task in enumerate(tasks):
         xs, beta = plan[i]
+        if per_variant and i > 0:
+            demand[i] = created[task["parent"]] * task["fan"]
         hosted = [k for k in range(len(xs)) if xs[k] > 0]
         hosted.sort(key=lambda k: (-task["variants"][k]["acc"], k))
         if not hosted:
@@ -90,6 +98,8 @@ def evaluate(p, index: int, demand_mqps: int, workers: int, slo_us: int, comm_us
             if take > 0 or pos == 0:
                 in_use.append(var["lat"][beta])
             gained += take * Fraction(var["acc"], 1_000_000)
+            if per_variant:
+                created[i] += take * var["factor"]
             left -= take
         if left > 0:
             mask |= BAD_DEMAND

@@ -60,6 +60,8 @@ def test_validation_rejects_bad_inputs():
         (dict(acc_ppm=[900000, 1000001]), binding.LOKI_E_RANGE),
         (dict(latency_us=[0, 6000]), binding.LOKI_E_RANGE),
         (dict(thr_mqps=[-1, 150000]), binding.LOKI_E_RANGE),
+        (dict(variant_factor_q4=[4, 0]), binding.LOKI_E_RANGE),
+        (dict(variant_factor_q4=[65, 4]), binding.LOKI_E_RANGE),
         (dict(n_batches=[2, 1], batch_size=[2, 2, 1], latency_us=[5000, 5000, 6000],
               thr_mqps=[200000, 200000, 150000]), binding.LOKI_E_RANGE),
     ]
@@ -78,7 +80,7 @@ def test_validation_rejects_bad_inputs():
 
 @pytest.mark.parametrize("seed", range(30))
 def test_route_table_matches_the_checker(seed):
-    w = wl.random_small(700 + seed, max_tasks=4, max_candidates=5000)
+    w = wl.random_small(700 + seed, max_tasks=4, max_candidates=5000, variant_factors=seed % 2 == 1)
     P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
     n = P.num_candidates()
     d = w.demand_mqps[0]

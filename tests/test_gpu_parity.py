@@ -284,3 +284,32 @@ def test_route_table_of_the_winner():
                     (ro.capacity[i][k], ro.routed[i][k], ro.leftover[i][k], ro.budget_us[i][k])
                 for k2 in range(oracle.MAX_VARIANTS):
                     assert bits(r.prob[i][k][k2]) == bits(ro.prob[i][k][k2])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_per_variant_multiplicative_factors(seed):
+    """Child demand follows the parent's routing (eq. (1) with r(i,k)); the library takes the per-lane path."""
+    w = wl.random_small(5000 + seed, max_tasks=4, max_variants=3, max_replicas=3, max_candidates=60000,
+                        variant_factors=True)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    n = P.num_candidates()
+    d = w.demand_mqps[0]
+    for flags in ALL_FLAGS:
+        res = P.alloc_search([d, d // 2], w.workers, w.slo_us, w.comm_us, flags=flags)
+        for dd, r in zip((d, d // 2), res):
+            check(r, O.search(dd, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags & TIE)),
+                  f"{w.name} d={dd} flags={flags}")
+    rng = random.Random(seed)
+    idxs = list(range(n)) if n <= 4096 else [rng.randrange(n) for _ in range(4096)]
+    got = P.alloc_eval(idxs, d, w.workers, w.slo_us, w.comm_us)
+    for g, idx in zip(got, idxs):
+        e = O.eval(idx, d, w.workers, w.slo_us, w.comm_us)
+        assert (g.infeasible, g.workers, bits(g.accuracy)) == (e.infeasible, e.workers, bits(e.accuracy)), idx
+    win = P.alloc_search([d], w.workers, w.slo_us, w.comm_us)[0]
+    if win.status == binding.LOKI_FOUND:
+        r, ro = P.route_table(win.index, d), O.route_table(win.index, d)
+        for i in range(w.pipeline.n_tasks):
+            assert (r.demand[i], r.scale[i], r.unserved[i]) == (ro.demand[i], ro.scale[i], ro.unserved[i])
+            for k in range(w.pipeline.n_variants[i]):
+                assert (r.capacity[i][k], r.routed[i][k], r.leftover[i][k]) == \
+                    (ro.capacity[i][k], ro.routed[i][k], ro.leftover[i][k])

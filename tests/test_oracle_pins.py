@@ -432,3 +432,60 @@ def test_route_table_conservation(seed):
                 s = sum(r.prob[i][pk][k] for k in range(K))
                 assert abs(s - 1.0) <= K * 2.0**-52
         v += K
+
+
+# ---- per-variant multiplicative factors r(i,k) (eq. (1) as printed; Section 4.2 "Estimating multiplicative factors")
+
+@pytest.mark.parametrize("seed", range(25))
+def test_per_variant_factors_match_rational_reading(seed):
+    w = wl.random_small(3000 + seed, max_candidates=2500, variant_factors=True)
+    p = w.pipeline
+    prob = oracle.Problem(p)
+    d = w.demand_mqps[0]
+    for index in range(prob.num_candidates()):
+        e = prob.eval(index, d, w.workers, w.slo_us, w.comm_us)
+        r = pyref.evaluate(p, index, d, w.workers, w.slo_us, w.comm_us)
+        assert (e.infeasible, e.workers, e.accuracy) == (r["infeasible"], r["workers"], r["accuracy"]), index
+    for tie in (False, True):
+        ref = pyref.search(p, d, w.workers, w.slo_us, w.comm_us, tie)
+        for b in (prob.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=tie, threads=3),
+                  prob.search_tabulated(d, w.workers, w.slo_us, w.comm_us, tie_index_only=tie, threads=2)):
+            assert (b.found, b.index, b.accuracy, b.workers, b.n_feasible) == \
+                (ref["found"], ref["index"], ref["accuracy"], ref["workers"], ref["n_feasible"])
+
+
+def test_unit_variant_factors_reduce_to_the_per_edge_model():
+    # r(i,k) = 1.00 everywhere: feasible plans, objective bits and winner are those of the per-edge model
+    for seed in range(12):
+        w = wl.random_small(4000 + seed, max_candidates=4000)
+        p = w.pipeline
+        ones = SimpleNamespace(**{k: getattr(p, k) for k in ("n_tasks", "parent", "fanout_q4", "n_variants",
+                                                              "n_batches", "batch_size", "max_replicas", "acc_ppm",
+                                                              "latency_us", "thr_mqps")},
+                               variant_factor_q4=[4] * len(p.acc_ppm))
+        d = w.demand_mqps[0]
+        a = oracle.Problem(p).search(d, w.workers, w.slo_us, w.comm_us)
+        b = oracle.Problem(ones).search(d, w.workers, w.slo_us, w.comm_us)
+        assert a.as_tuple() == b.as_tuple()
+
+
+def test_child_demand_follows_the_parents_split():
+    # detector with a 0.70 variant creating 1.00 requests per request and a 0.90 variant creating 2.50;
+    # classifier behind a 1.50 branch ratio.  120 QPS: 100 on the accurate variant, 20 on the other.
+    p = pipeline(n_tasks=2, parent=[-1, 0], fanout_q4=[4, 6], n_variants=[2, 1], n_batches=[1, 1], batch_size=[1, 1],
+                 max_replicas=[1, 1, 3], acc_ppm=[700000, 900000, 800000], latency_us=[4000, 9000, 5000],
+                 thr_mqps=[250000, 100000, 200000], variant_factor_q4=[4, 10])
+    prob = oracle.Problem(p)
+    idx = prob.encode([1, 1, 3], [0, 0])
+    e = prob.eval(idx, 120_000, 9, 100_000)
+    # created = 100 * 2.5 + 20 * 1.0 = 270 per second; times 1.5 = 405 QPS at the classifier
+    assert e.task_demand[1] == 405_000 * 16            # units of milli-QPS / 16
+    assert e.infeasible == 0                           # 3 replicas x 200 QPS >= 405 QPS
+    assert e.task_acc[0] == float(Fraction(100 * 900000 + 20 * 700000, 120 * 10**6))
+    assert prob.eval(prob.encode([1, 1, 2], [0, 0]), 120_000, 9, 100_000).infeasible == oracle.BAD_DEMAND
+    # only the cheap variant: 120 * 1.0 * 1.5 = 180 QPS downstream, one classifier replica is enough
+    e = prob.eval(prob.encode([1, 0, 1], [0, 0]), 120_000, 9, 100_000)
+    assert e.task_demand[1] == 180_000 * 16 and e.infeasible == 0
+    r = prob.route_table(idx, 120_000)
+    assert r.demand[1] == 405_000 * 16 and r.unserved[1] == 0
+    assert r.prob[1][1][0] == 1.0 and r.prob[1][0][0] == 1.0
