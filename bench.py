@@ -29,11 +29,13 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
     fp64 add (the other paths' sum) when the tree has several leaves, and one fp64 max/compare
     against the lane's best.  The two feasibility compares of eq. (3) and eq. (7) are taken
     once per run of first-task choices with equal replicas and latency and are not counted.
-    Per-lane kernel: the estimate of 20 per (task, variant) + 30 per task + 50 per plan
-    (decode, fill, one fp64 division per task, paths, key)."""
+    Per-lane kernel (estimate): the last task is scored per plan -- 20 per variant (digit, capacity,
+    fill, weighted sum) + 30 (one fp64 division, conversions) -- plus 50 to finish the plan (masks,
+    path value, sum, division, key); the other tasks are scored once per strip of 64 plans."""
     if not per_lane:
         return (1 if n_tasks >= 2 else 0) + (1 if n_paths > 1 else 0) + 1
-    return sum(20 * k + 30 for k in pipeline.n_variants) + 50
+    per_task = [20 * k + 30 for k in pipeline.n_variants]
+    return per_task[-1] + 50 + sum(per_task[:-1]) / 64.0
 
 
 def main() -> int:

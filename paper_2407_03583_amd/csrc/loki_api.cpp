@@ -218,17 +218,19 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
 
     if (timed) LOKI_HIP(hipEventRecord(p->ev[0], stream));
     if (flags & LOKI_SEARCH_PER_LANE) {
-        const uint64_t want = (span + kBlockThreads - 1) / kBlockThreads;
-        A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
-        uint64_t lanes = uint64_t(A.blocks_per_m) * kBlockThreads;
-        for (int i = 0; i < n; i++) {  // digits of the lane count; the last digit keeps the rest
-            if (i < n - 1) {
-                A.lane_step_digits[i] = lanes % p->dev.C[i];
-                lanes /= p->dev.C[i];
-            } else {
-                A.lane_step_digits[i] = lanes;
-            }
+        // one work item = one choice of all tasks but the last x a strip of 64 choices of the last;
+        // only the strips the index range touches are visited (cl_first/chunk_groups carry them)
+        uint64_t items = 0;
+        if (span > 0) {
+            const uint64_t strideL = p->dev.stride[L];
+            const uint32_t strip_first = static_cast<uint32_t>(index_begin / strideL) / 64;
+            const uint32_t strip_last = static_cast<uint32_t>((index_end - 1) / strideL) / 64;
+            A.cl_first = strip_first;
+            A.chunk_groups = strip_last - strip_first + 1;
+            items = strideL * A.chunk_groups;
         }
+        const uint64_t want = (items + kBlockThreads - 1) / kBlockThreads;
+        A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
         if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
         LOKI_HIP(launch_per_lane_search(A, stream));
     } else {

@@ -95,8 +95,6 @@ struct SearchArgs {
     int32_t M;
     uint32_t blocks_per_m;
     uint32_t tie_index_only;
-    // per-lane search only
-    uint64_t lane_step_digits[kMaxTasks];   // digits (radix C_i) of the total number of lanes
 };
 
 struct EvalArgs {

@@ -734,62 +734,121 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 }
 
 // ---- kernel: every lane scores whole plans (no tables) ---------------------------------------------------
+// A work item is one choice of every task but the last plus a strip of kStrip choices of the
+// last task.  The lane scores the shared part once (each task in topological order, so that
+// with per-variant factors a child's demand can follow from its parent's routing, eq. (1))
+// and then walks the strip, scoring the last task and finishing the plan per step.
+constexpr uint32_t kStrip = 64;
+
 __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchArgs A) {
     __shared__ DevProblem sP;
     __shared__ BestRec sBest[kWavesPerBlock];
     stage_problem(&sP, A.P, sizeof(DevProblem));
     __syncthreads();
+    const DevProblem *P = &sP;
     const int m = blockIdx.y;
-    const int n = sP.n_tasks;
+    const int n = P->n_tasks, L = n - 1;
+    const bool has_vf = P->has_vf != 0;
     const bool tie_index_only = A.tie_index_only != 0;
     const uint64_t lanes = static_cast<uint64_t>(gridDim.x) * kBlockThreads;
-    uint64_t idx = A.begin + static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x;
+    const uint64_t strideL = P->stride[L];  // number of choice combinations of all other tasks
+    const uint32_t CL = P->C[L];
+    const uint32_t n_strips = A.chunk_groups;  // strips of the last task's choices touched by the index range
+    const uint32_t strip_first = A.cl_first;
+    const uint64_t items = strideL * n_strips;
+    const double npd = static_cast<double>(P->n_paths);
+    const int parL = n >= 2 ? P->parent[L] : 0;
     int64_t Dn[kMaxTasks];
 #pragma unroll
     for (int i = 0; i < kMaxTasks; i++) Dn[i] = A.Dn[static_cast<size_t>(m) * kMaxTasks + i];
 
-    uint32_t c[kMaxTasks];
-    {
-        uint64_t rest = idx;
-#pragma unroll
-        for (int i = 0; i < kMaxTasks; i++) {
-            c[i] = 0;
-            if (i < n) {
-                c[i] = static_cast<uint32_t>(rest % sP.C[i]);
-                rest /= sP.C[i];
-            }
-        }
-    }
     double bacc = -1.0;
     int32_t bw = kNever;
     uint64_t bidx = ~0ull;
     uint64_t nfeas = 0;
-    while (idx < A.end) {
-        uint32_t mask;
-        int32_t workers;
-        double acc;
-        eval_plan(&sP, c, Dn, A.budget, A.W, mask, workers, acc);
-        if (mask == 0) {
-            nfeas++;
-            // indices grow within a lane, so on a full tie the earlier plan stays
-            if (acc > bacc || (acc == bacc && !tie_index_only && workers < bw)) {
-                bacc = acc;
-                bw = workers;
-                bidx = idx;
-            }
-        }
-        idx += lanes;
-        uint32_t carry = 0;  // add the lane count in mixed radix
+    for (uint64_t item = static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x; item < items; item += lanes) {
+        const uint64_t o = item / n_strips;  // index of the plan with the last task's choice 0
+        const uint32_t strip = strip_first + static_cast<uint32_t>(item - o * n_strips);
+        // skip strips wholly outside [begin, end)
+        const uint32_t c_lo = strip * kStrip;
+        const uint32_t c_hi = c_lo + kStrip < CL ? c_lo + kStrip : CL;
+        if (o + strideL * c_lo >= A.end || o + strideL * (c_hi - 1) < A.begin) continue;
+
+        // ---- the shared part: tasks 0 .. L-1
+        double pp[kMaxTasks];    // product of accuracies root..i, root first
+        int64_t pl[kMaxTasks];   // latency sum root..i
+        int64_t out[kMaxTasks];  // requests task i creates per unit of child fan-out
+        uint32_t mask0 = 0;
+        int32_t workers0 = 0;
 #pragma unroll
         for (int i = 0; i < kMaxTasks; i++) {
-            if (i < n) {
-                uint64_t v = static_cast<uint64_t>(c[i]) + A.lane_step_digits[i] + carry;
-                carry = 0;
-                if (v >= sP.C[i] && i < n - 1) {
-                    v -= sP.C[i];
-                    carry = 1;
+            pp[i] = 0.0;
+            pl[i] = 0;
+            out[i] = 0;
+        }
+        uint64_t rest = o;
+#pragma unroll
+        for (int i = 0; i < kMaxTasks; i++) {
+            if (i < L) {
+                const uint32_t ci = static_cast<uint32_t>(rest % P->C[i]);
+                rest /= P->C[i];
+                const int par = i > 0 ? P->parent[i] : 0;
+                int64_t dn = Dn[i];
+                if (has_vf && i > 0) dn = pick_below(out, par, i) * static_cast<int64_t>(P->fanout[i]);
+                TaskOut t;
+                eval_task(P, i, ci, dn, t);
+                out[i] = t.outflow;
+                workers0 += t.w;
+                if (!t.any) mask0 |= kBadEmpty;
+                if (t.rem > 0) mask0 |= kBadDemand;
+                const double a = task_accuracy(t, dn);
+                if (i == 0) {
+                    pp[0] = a;
+                    pl[0] = t.maxlat;
+                } else {
+                    pp[i] = pick_below(pp, par, i) * a;
+                    pl[i] = pick_below(pl, par, i) + t.maxlat;
                 }
-                c[i] = static_cast<uint32_t>(v);
+            }
+        }
+        double presum = 0.0;
+        bool first = true;
+#pragma unroll
+        for (int i = 0; i < kMaxTasks; i++) {
+            if (i < L && P->is_leaf[i]) {
+                if (A.budget[i] < 0 || pl[i] > A.budget[i]) mask0 |= kBadLatency;
+                presum = first ? pp[i] : presum + pp[i];
+                first = false;
+            }
+        }
+        const double pre = pick_below(pp, parL, kMaxTasks);
+        const int64_t lat_pre = n >= 2 ? pick_below(pl, parL, kMaxTasks) : 0;
+        int64_t dnL = Dn[L];
+        if (has_vf && n >= 2) dnL = pick_below(out, parL, kMaxTasks) * static_cast<int64_t>(P->fanout[L]);
+
+        // ---- the strip: the last task's choices
+        for (uint32_t cL = c_lo; cL < c_hi; cL++) {
+            const uint64_t idx = o + strideL * cL;
+            if (idx < A.begin || idx >= A.end) continue;
+            TaskOut t;
+            eval_task(P, L, cL, dnL, t);
+            uint32_t mask = mask0;
+            const int32_t workers = workers0 + t.w;
+            if (!t.any) mask |= kBadEmpty;
+            if (t.rem > 0) mask |= kBadDemand;
+            if (workers > A.W) mask |= kBadWorkers;                                            // eq. (3)
+            if (A.budget[L] < 0 || lat_pre + t.maxlat > A.budget[L]) mask |= kBadLatency;  // eq. (7)
+            if (mask == 0) {
+                const double a = task_accuracy(t, dnL);
+                const double path = n >= 2 ? pre * a : a;
+                const double sum = first ? path : presum + path;
+                const double acc = sum / npd;
+                nfeas++;
+                if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                    bacc = acc;
+                    bw = workers;
+                    bidx = idx;
+                }
             }
         }
     }
