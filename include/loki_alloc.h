@@ -41,6 +41,10 @@
  *   index    = sum_i choice_i * prod_{j<i} C_j            task 0 least significant
  *   choice_i = sum_k x(i,k) * prod_{k'<k} (R(i,k')+1) + beta_i * prod_k (R(i,k)+1)
  *   C_i      = n_batches_i * prod_k (R(i,k)+1),  beta_i = position in the task's batch list.
+ * With per_variant_batch every variant carries its own batch position:
+ *   choice_i = sum_k g(i,k) * prod_{k'<k} (1 + R(i,k')*n_batches_i),
+ *   g(i,k)   = 0 if the variant is not hosted, else 1 + (x(i,k)-1)*n_batches_i + beta(i,k),
+ *   C_i      = prod_k (1 + R(i,k)*n_batches_i).
  *
  * Memory: the caller owns every buffer.  "host" pointers are ordinary host
  * memory, "device" pointers are HIP device memory on the current device.  The
@@ -115,6 +119,8 @@ typedef struct {
                                     outgoing = incoming * multFactor * branchRatio), a child's demand depends
                                     on its parent's part of the plan, tasks work in units of milli-QPS /
                                     16^depth, and every search runs with LOKI_SEARCH_PER_LANE. */
+    int32_t per_variant_batch;   /* 0: one batch size per task.  1: a batch size per hosted variant, the y(i,k)
+                                    of Section 4.1 "Output" and eq. (4); see the index layout above */
 } loki_pipeline_t;
 
 typedef struct loki_problem loki_problem_t; /* opaque handle */
@@ -142,7 +148,7 @@ typedef struct {
     int64_t scale[LOKI_MAX_TASKS];                      /* 4^depth_i */
     int64_t unserved[LOKI_MAX_TASKS];                   /* demand that found no capacity (0 when feasible) */
     int32_t replicas[LOKI_MAX_TASKS][LOKI_MAX_VARIANTS];  /* x(i,k) */
-    int32_t batch[LOKI_MAX_TASKS];                      /* configured batch size of the task */
+    int32_t batch[LOKI_MAX_TASKS][LOKI_MAX_VARIANTS];     /* configured batch size; 0 if not hosted */
     int64_t capacity[LOKI_MAX_TASKS][LOKI_MAX_VARIANTS];  /* x * q * scale */
     int64_t routed[LOKI_MAX_TASKS][LOKI_MAX_VARIANTS];    /* traffic placed on the variant */
     int64_t leftover[LOKI_MAX_TASKS][LOKI_MAX_VARIANTS];  /* capacity - routed */
@@ -170,7 +176,8 @@ int loki_num_candidates(const loki_problem_t *problem, uint64_t *n);
 int loki_workspace_bytes(const loki_problem_t *problem, int64_t n_demand, size_t *bytes);
 
 /* index -> plan.  x: [sum_i K_i] replica counts in input order; batch: [n] batch
- * sizes (values, not positions).  Host arrays.  LOKI_E_RANGE if index >= N. */
+ * sizes (values, not positions), or with per_variant_batch [sum_i K_i] batch sizes
+ * (0 where the variant is not hosted).  Host arrays.  LOKI_E_RANGE if index >= N. */
 int loki_decode(const loki_problem_t *problem, uint64_t index, int32_t *x, int32_t *batch);
 
 /* The search (accuracy-scaling step, eq. (12), with the hardware-scaling

@@ -45,7 +45,8 @@ class _Pipeline(C.Structure):
                 ("acc_ppm", C.POINTER(C.c_int32)),
                 ("latency_us", C.POINTER(C.c_int64)),
                 ("thr_mqps", C.POINTER(C.c_int64)),
-                ("variant_factor_q4", C.POINTER(C.c_int32))]
+                ("variant_factor_q4", C.POINTER(C.c_int32)),
+                ("per_variant_batch", C.c_int32)]
 
 
 class EvalOut(C.Structure):
@@ -149,14 +150,16 @@ class Problem:
                            C.cast(k["latency_us"], C.POINTER(C.c_int64)),
                            C.cast(k["thr_mqps"], C.POINTER(C.c_int64)),
                            C.cast(k["variant_factor_q4"], C.POINTER(C.c_int32)) if vf is not None
-                           else C.POINTER(C.c_int32)())
+                           else C.POINTER(C.c_int32)(),
+                           1 if getattr(pipeline, "per_variant_batch", False) else 0)
+        self.per_variant_batch = bool(getattr(pipeline, "per_variant_batch", False))
 
     def num_candidates(self) -> int:
         return int(lib().lo_num_candidates(C.byref(self.c)))
 
     def decode(self, index: int):
         x = (C.c_int32 * sum(self.n_variants))()
-        b = (C.c_int32 * self.n_tasks)()
+        b = (C.c_int32 * (sum(self.n_variants) if self.per_variant_batch else self.n_tasks))()
         lib().lo_decode(C.byref(self.c), index, x, b)
         return list(x), list(b)
 

@@ -30,9 +30,10 @@ static void layout_of(const lo_pipeline *p, lo_layout *L)
         L->voff[i] = v;
         L->boff[i] = b;
         L->toff[i] = t;
-        uint64_t c = (uint64_t)p->n_batches[i];
+        uint64_t c = p->per_variant_batch ? 1 : (uint64_t)p->n_batches[i];
         for (int k = 0; k < p->n_variants[i]; k++)
-            c *= (uint64_t)(p->max_replicas[v + k] + 1);
+            c *= p->per_variant_batch ? (uint64_t)(1 + p->max_replicas[v + k] * p->n_batches[i])
+                                      : (uint64_t)(p->max_replicas[v + k] + 1);
         L->choices[i] = c;
         v += p->n_variants[i];
         b += p->n_batches[i];
@@ -55,14 +56,26 @@ uint64_t lo_num_candidates(const lo_pipeline *p)
  * choice_i = sum_k x_ik * prod_{k'<k} (R_ik'+1) + beta_i * prod_k (R_ik+1)
  */
 static void decode_choice(const lo_pipeline *p, const lo_layout *L, int i, uint64_t choice,
-                          int32_t *x /* K_i */, int32_t *beta)
+                          int32_t *x /* K_i */, int32_t *beta /* K_i: batch position per variant */)
 {
-    for (int k = 0; k < p->n_variants[i]; k++) {
+    int K = p->n_variants[i], nb = p->n_batches[i];
+    if (p->per_variant_batch) {
+        for (int k = 0; k < K; k++) {
+            uint64_t radix = (uint64_t)(1 + p->max_replicas[L->voff[i] + k] * nb);
+            uint64_t g = choice % radix;
+            choice /= radix;
+            x[k] = g == 0 ? 0 : (int32_t)((g - 1) / (uint64_t)nb) + 1;
+            beta[k] = g == 0 ? 0 : (int32_t)((g - 1) % (uint64_t)nb);
+        }
+        return;
+    }
+    for (int k = 0; k < K; k++) {
         uint64_t radix = (uint64_t)(p->max_replicas[L->voff[i] + k] + 1);
         x[k] = (int32_t)(choice % radix);
         choice /= radix;
     }
-    *beta = (int32_t)choice;
+    for (int k = 0; k < K; k++)
+        beta[k] = (int32_t)choice;
 }
 
 void lo_decode(const lo_pipeline *p, uint64_t index, int32_t *x, int32_t *batch_digit)
@@ -70,9 +83,15 @@ void lo_decode(const lo_pipeline *p, uint64_t index, int32_t *x, int32_t *batch_
     lo_layout L;
     layout_of(p, &L);
     for (int i = 0; i < L.n; i++) {
+        int32_t beta[LO_MAX_VARIANTS];
         uint64_t choice = index % L.choices[i];
         index /= L.choices[i];
-        decode_choice(p, &L, i, choice, x + L.voff[i], &batch_digit[i]);
+        decode_choice(p, &L, i, choice, x + L.voff[i], beta);
+        if (p->per_variant_batch)
+            for (int k = 0; k < p->n_variants[i]; k++)
+                batch_digit[L.voff[i] + k] = beta[k];
+        else
+            batch_digit[i] = beta[0];
     }
 }
 
@@ -83,11 +102,20 @@ uint64_t lo_encode(const lo_pipeline *p, const int32_t *x, const int32_t *batch_
     uint64_t index = 0, stride = 1;
     for (int i = 0; i < L.n; i++) {
         uint64_t choice = 0, r = 1;
+        int nb = p->n_batches[i];
         for (int k = 0; k < p->n_variants[i]; k++) {
-            choice += (uint64_t)x[L.voff[i] + k] * r;
-            r *= (uint64_t)(p->max_replicas[L.voff[i] + k] + 1);
+            int xk = x[L.voff[i] + k];
+            if (p->per_variant_batch) {
+                uint64_t g = xk == 0 ? 0 : (uint64_t)(1 + (xk - 1) * nb + batch_digit[L.voff[i] + k]);
+                choice += g * r;
+                r *= (uint64_t)(1 + p->max_replicas[L.voff[i] + k] * nb);
+            } else {
+                choice += (uint64_t)xk * r;
+                r *= (uint64_t)(p->max_replicas[L.voff[i] + k] + 1);
+            }
         }
-        choice += (uint64_t)batch_digit[i] * r;
+        if (!p->per_variant_batch)
+            choice += (uint64_t)batch_digit[i] * r;
         index += choice * stride;
         stride *= L.choices[i];
     }
@@ -142,8 +170,9 @@ typedef struct {
     int64_t outflow;   /* sum routed_k * r(i,k): requests created per unit of child fan-out */
 } lo_task_t;
 
-static void task_eval(const lo_pipeline *p, const lo_layout *L, int i, const int32_t *x, int32_t beta,
-                      int64_t Dn, int64_t scale, lo_task_t *t, int64_t *routed_out /* K_i or NULL */)
+static void task_eval(const lo_pipeline *p, const lo_layout *L, int i, const int32_t *x,
+                      const int32_t *beta /* K_i */, int64_t Dn, int64_t scale, lo_task_t *t,
+                      int64_t *routed_out /* K_i or NULL */)
 {
     int order[LO_MAX_VARIANTS];
     int K = p->n_variants[i], nb = p->n_batches[i];
@@ -164,8 +193,8 @@ static void task_eval(const lo_pipeline *p, const lo_layout *L, int i, const int
         int k = order[o];
         if (x[k] <= 0)
             continue;
-        int64_t thr = p->thr_mqps[L->toff[i] + k * nb + beta];
-        int64_t lat = p->latency_us[L->toff[i] + k * nb + beta];
+        int64_t thr = p->thr_mqps[L->toff[i] + k * nb + beta[k]];
+        int64_t lat = p->latency_us[L->toff[i] + k * nb + beta[k]];
         int64_t cap = (int64_t)x[k] * thr * scale;          /* eq. (2) right-hand side */
         int64_t routed = rem < cap ? rem : cap;             /* Algorithm 1 fill rule */
         int used = (routed > 0) || !t->any;
@@ -265,16 +294,19 @@ void lo_eval(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, int32_t 
              int64_t comm_us, lo_eval_t *out)
 {
     lo_layout L;
-    int32_t x[LO_MAX_TASKS * LO_MAX_VARIANTS], beta[LO_MAX_TASKS];
     int64_t Dn[LO_MAX_TASKS], scale[LO_MAX_TASKS];
     lo_task_t t[LO_MAX_TASKS];
     layout_of(p, &L);
-    lo_decode(p, index, x, beta);
     task_demand(p, demand_mqps, Dn, scale);
+    uint64_t rest = index;
     for (int i = 0; i < L.n; i++) {
+        int32_t x[LO_MAX_VARIANTS], beta[LO_MAX_VARIANTS];
+        uint64_t choice = rest % L.choices[i];
+        rest /= L.choices[i];
+        decode_choice(p, &L, i, choice, x, beta);
         if (p->variant_factor_q4 && i > 0) /* what the parent's variants create for this child */
             Dn[i] = t[p->parent[i]].outflow * (int64_t)p->fanout_q4[i];
-        task_eval(p, &L, i, x + L.voff[i], beta[i], Dn[i], scale[i], &t[i], NULL);
+        task_eval(p, &L, i, x, beta, Dn[i], scale[i], &t[i], NULL);
     }
     pipeline_eval(p, t, Dn, workers, slo_us, comm_us, out);
 }
@@ -380,8 +412,8 @@ void lo_search_tabulated(const lo_pipeline *p, int64_t demand_mqps, int32_t work
     for (int i = 0; i < L.n; i++) {
         table[i] = (lo_task_t *)malloc(sizeof(lo_task_t) * (size_t)L.choices[i]);
         for (uint64_t c = 0; c < L.choices[i]; c++) {
-            int32_t x[LO_MAX_VARIANTS], beta;
-            decode_choice(p, &L, i, c, x, &beta);
+            int32_t x[LO_MAX_VARIANTS], beta[LO_MAX_VARIANTS];
+            decode_choice(p, &L, i, c, x, beta);
             task_eval(p, &L, i, x, beta, Dn[i], scale[i], &table[i][c], NULL);
         }
     }
@@ -436,19 +468,22 @@ void lo_search_tabulated(const lo_pipeline *p, int64_t demand_mqps, int32_t work
 void lo_route_table(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, lo_route_t *r)
 {
     lo_layout L;
-    int32_t x[LO_MAX_TASKS * LO_MAX_VARIANTS], beta[LO_MAX_TASKS];
+    int32_t x[LO_MAX_TASKS * LO_MAX_VARIANTS], beta[LO_MAX_TASKS][LO_MAX_VARIANTS];
     layout_of(p, &L);
-    lo_decode(p, index, x, beta);
     memset(r, 0, sizeof(*r));
     task_demand(p, demand_mqps, r->demand, r->scale);
     int n = p->n_tasks;
+    uint64_t rest = index;
     for (int i = 0; i < n; i++) {
         int nb = p->n_batches[i];
+        uint64_t choice = rest % L.choices[i];
+        rest /= L.choices[i];
+        decode_choice(p, &L, i, choice, x + L.voff[i], beta[i]);
         for (int k = 0; k < p->n_variants[i]; k++) {
             int xk = x[L.voff[i] + k];
-            r->capacity[i][k] = (int64_t)xk * p->thr_mqps[L.toff[i] + k * nb + beta[i]] * r->scale[i];
+            r->capacity[i][k] = (int64_t)xk * p->thr_mqps[L.toff[i] + k * nb + beta[i][k]] * r->scale[i];
             r->leftover[i][k] = r->capacity[i][k];
-            r->budget_us[i][k] = xk > 0 ? p->latency_us[L.toff[i] + k * nb + beta[i]] : 0;
+            r->budget_us[i][k] = xk > 0 ? p->latency_us[L.toff[i] + k * nb + beta[i][k]] : 0;
         }
     }
     /* frontend -> first task */

@@ -69,6 +69,9 @@ typedef struct {
     const int32_t *variant_factor_q4; /* NULL, or concat over (task, variant): multiplicative factor r(i,k)
                                          of eq. (1) in quarters; requests created for a child =
                                          sum_k routed_k * r(i,k) * fanout(child) (Section 5.1) */
+    int32_t per_variant_batch;   /* 0: one batch size per task.  1: y(i,k) of Section 4.1, a batch size per
+                                    hosted variant; a variant's digit is 0 (not hosted) or
+                                    1 + (replicas - 1) * |B_i| + batch position */
 } lo_pipeline;
 
 typedef struct {
@@ -104,7 +107,8 @@ typedef struct {
 } lo_route_t;
 
 uint64_t lo_num_candidates(const lo_pipeline *p);
-void lo_decode(const lo_pipeline *p, uint64_t index, int32_t *x /* sum K_i */, int32_t *batch_digit /* n */);
+/* batch_digit: [n] batch positions (one per task), or with per_variant_batch [sum K_i] (0 where not hosted). */
+void lo_decode(const lo_pipeline *p, uint64_t index, int32_t *x /* sum K_i */, int32_t *batch_digit);
 uint64_t lo_encode(const lo_pipeline *p, const int32_t *x, const int32_t *batch_digit);
 
 void lo_eval(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, int32_t workers,

@@ -48,7 +48,8 @@ class PipelineC(C.Structure):
                 ("acc_ppm", C.POINTER(C.c_int32)),
                 ("latency_us", C.POINTER(C.c_int64)),
                 ("thr_mqps", C.POINTER(C.c_int64)),
-                ("variant_factor_q4", C.POINTER(C.c_int32))]
+                ("variant_factor_q4", C.POINTER(C.c_int32)),
+                ("per_variant_batch", C.c_int32)]
 
 
 class Result(C.Structure):
@@ -75,7 +76,7 @@ class Route(C.Structure):
                 ("scale", C.c_int64 * MAX_TASKS),
                 ("unserved", C.c_int64 * MAX_TASKS),
                 ("replicas", (C.c_int32 * MAX_VARIANTS) * MAX_TASKS),
-                ("batch", C.c_int32 * MAX_TASKS),
+                ("batch", (C.c_int32 * MAX_VARIANTS) * MAX_TASKS),
                 ("capacity", (C.c_int64 * MAX_VARIANTS) * MAX_TASKS),
                 ("routed", (C.c_int64 * MAX_VARIANTS) * MAX_TASKS),
                 ("leftover", (C.c_int64 * MAX_VARIANTS) * MAX_TASKS),
@@ -142,7 +143,8 @@ def _pipeline_struct(p):
     vf = getattr(p, "variant_factor_q4", None)
     vf_arr = _arr(C.c_int32, vf) if vf is not None else None
     s = PipelineC(int(p.n_tasks), *[C.cast(a, C.POINTER(a._type_)) for a in keep],
-                  C.cast(vf_arr, C.POINTER(C.c_int32)) if vf_arr is not None else C.POINTER(C.c_int32)())
+                  C.cast(vf_arr, C.POINTER(C.c_int32)) if vf_arr is not None else C.POINTER(C.c_int32)(),
+                  1 if getattr(p, "per_variant_batch", False) else 0)
     keep.append(vf_arr)
     return s, keep
 
@@ -156,6 +158,7 @@ class Problem:
         _check(lib().loki_problem_create(C.byref(s), C.byref(self._h)), "loki_problem_create")
         self.n_tasks = int(pipeline.n_tasks)
         self.n_variants = [int(v) for v in pipeline.n_variants]
+        self.per_variant_batch = bool(getattr(pipeline, "per_variant_batch", False))
         self._ws = None
 
     def close(self):
@@ -181,7 +184,7 @@ class Problem:
 
     def decode(self, index: int):
         x = (C.c_int32 * sum(self.n_variants))()
-        b = (C.c_int32 * self.n_tasks)()
+        b = (C.c_int32 * (sum(self.n_variants) if self.per_variant_batch else self.n_tasks))()
         _check(lib().loki_decode(self._h, index, x, b), "loki_decode")
         return list(x), list(b)
 

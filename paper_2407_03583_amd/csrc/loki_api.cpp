@@ -296,6 +296,11 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
     p->n = n;
     d.n_tasks = n;
     d.has_vf = in->variant_factor_q4 ? 1 : 0;
+    d.pv_batch = in->per_variant_batch ? 1 : 0;
+    if (in->per_variant_batch != 0 && in->per_variant_batch != 1) {
+        delete p;
+        return LOKI_E_RANGE;
+    }
     int v = 0, b = 0, t = 0;
     uint64_t N = 1;
     uint32_t table_total = 0;
@@ -320,7 +325,8 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         p->voff[i] = v;
         const int per_level_bits = in->variant_factor_q4 ? 4 : 2;  // units of milli-QPS / 16^depth or / 4^depth
         const int64_t scale = int64_t(1) << (per_level_bits * p->depth[i]);
-        uint64_t choices = uint64_t(nb);
+        uint64_t choices = d.pv_batch ? 1u : uint64_t(nb);
+        d.magic_nb[i] = ((uint64_t(1) << 36) + uint64_t(nb) - 1) / uint64_t(nb);
         d.fanout[i] = i > 0 ? in->fanout_q4[i] : 4;
         p->max_vf[i] = 4;
         for (int bi = 0; bi < nb; bi++) {
@@ -334,8 +340,8 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
                 rc = LOKI_E_RANGE;
                 break;
             }
-            d.radix[i][k] = uint32_t(R) + 1;
-            d.magic[i][k] = R == 0 ? 0u : uint32_t(((uint64_t(1) << 32) + uint64_t(R)) / (uint64_t(R) + 1));
+            d.radix[i][k] = d.pv_batch ? 1u + uint32_t(R) * uint32_t(nb) : uint32_t(R) + 1;
+            d.magic[i][k] = ((uint64_t(1) << 36) + d.radix[i][k] - 1) / d.radix[i][k];
             d.acc[i][k] = acc;
             d.vf[i][k] = 4;
             if (in->variant_factor_q4) {
@@ -347,7 +353,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
                 d.vf[i][k] = f;
                 p->max_vf[i] = k == 0 ? f : std::max(p->max_vf[i], f);
             }
-            choices *= uint64_t(R) + 1;
+            choices *= d.radix[i][k];
             if (choices > LOKI_MAX_CHOICES) {
                 rc = LOKI_E_RANGE;
                 break;
@@ -428,17 +434,40 @@ int loki_workspace_bytes(const loki_problem_t *p, int64_t n_demand, size_t *byte
     return LOKI_OK;
 }
 
+namespace {
+
+// choice of task i -> replica counts and batch positions per variant
+void decode_choice(const loki_problem *p, int i, uint64_t c, int32_t *x, int32_t *beta) {
+    const int K = p->dev.K[i], nb = p->dev.nb[i];
+    for (int k = 0; k < K; k++) {
+        const uint64_t g = c % p->dev.radix[i][k];
+        c /= p->dev.radix[i][k];
+        if (p->dev.pv_batch) {
+            x[k] = g == 0 ? 0 : int32_t((g - 1) / nb) + 1;
+            beta[k] = g == 0 ? 0 : int32_t((g - 1) % nb);
+        } else {
+            x[k] = int32_t(g);
+        }
+    }
+    if (!p->dev.pv_batch)
+        for (int k = 0; k < K; k++) beta[k] = int32_t(c);
+}
+
+}  // namespace
+
 int loki_decode(const loki_problem_t *p, uint64_t index, int32_t *x, int32_t *batch) {
     if (!p || !x || !batch) return LOKI_E_NULL;
     if (index >= p->n_candidates) return LOKI_E_RANGE;
     for (int i = 0; i < p->n; i++) {
-        uint64_t c = index % p->dev.C[i];
+        int32_t beta[kMaxVariants];
+        decode_choice(p, i, index % p->dev.C[i], x + p->voff[i], beta);
         index /= p->dev.C[i];
-        for (int k = 0; k < p->dev.K[i]; k++) {
-            x[p->voff[i] + k] = int32_t(c % p->dev.radix[i][k]);
-            c /= p->dev.radix[i][k];
+        if (p->dev.pv_batch) {
+            for (int k = 0; k < p->dev.K[i]; k++)
+                batch[p->voff[i] + k] = x[p->voff[i] + k] > 0 ? p->batch_size[i][beta[k]] : 0;
+        } else {
+            batch[i] = p->batch_size[i][beta[0]];
         }
-        batch[i] = p->batch_size[i][c];
     }
     return LOKI_OK;
 }
@@ -532,20 +561,17 @@ int loki_route_table(const loki_problem_t *p, uint64_t index, int64_t demand_mqp
     const int n = p->n;
     uint64_t rest = index;
     for (int i = 0; i < n; i++) {
-        uint64_t c = rest % p->dev.C[i];
+        int32_t beta[kMaxVariants];
+        decode_choice(p, i, rest % p->dev.C[i], r.replicas[i], beta);
         rest /= p->dev.C[i];
-        for (int k = 0; k < p->dev.K[i]; k++) {
-            r.replicas[i][k] = int32_t(c % p->dev.radix[i][k]);
-            c /= p->dev.radix[i][k];
-        }
-        const int beta = int(c);
-        r.batch[i] = p->batch_size[i][beta];
         r.demand[i] = Dn[i];
         r.scale[i] = int64_t(1) << ((p->dev.has_vf ? 4 : 2) * p->depth[i]);
         for (int k = 0; k < p->dev.K[i]; k++) {
-            r.capacity[i][k] = int64_t(r.replicas[i][k]) * p->dev.thr_s[i][k][beta];
+            const bool hosted = r.replicas[i][k] > 0;
+            r.batch[i][k] = hosted ? p->batch_size[i][beta[k]] : 0;
+            r.capacity[i][k] = int64_t(r.replicas[i][k]) * p->dev.thr_s[i][k][beta[k]];
             r.leftover[i][k] = r.capacity[i][k];
-            r.budget_us[i][k] = r.replicas[i][k] > 0 ? p->dev.lat[i][k][beta] : 0;
+            r.budget_us[i][k] = hosted ? p->dev.lat[i][k][beta[k]] : 0;
         }
     }
     // place `amount` requests from one source on the workers of task j

@@ -25,8 +25,7 @@ struct DevProblem {
     int32_t K[kMaxTasks];
     int32_t nb[kMaxTasks];
     uint32_t C[kMaxTasks];                  // choices per task
-    uint32_t radix[kMaxTasks][kMaxVariants];  // R(i,k)+1
-    uint32_t magic[kMaxTasks][kMaxVariants];  // ceil(2^32 / radix); unused for radix 1
+    uint32_t radix[kMaxTasks][kMaxVariants];  // R(i,k)+1, or 1+R(i,k)*|B_i| with per-variant batch sizes
     int32_t order[kMaxTasks][kMaxVariants];   // route order (accuracy descending, index ascending) -> variant
     int32_t acc[kMaxTasks][kMaxVariants];     // ppm, by variant
     uint32_t table_off[kMaxTasks];          // first record of task i in a per-demand task table
@@ -34,10 +33,14 @@ struct DevProblem {
     int32_t n_lat0;                         // number of distinct profiled latencies of task 0
     int32_t sum_r0;                         // sum of the replica limits of task 0
     int32_t has_vf;                         // per-variant multiplicative factors are present
+    int32_t pv_batch;                       // a batch size per hosted variant instead of one per task
+    int32_t pad1;
     int32_t lat0_sorted[kMaxVariants * kMaxBatches];  // those latencies, ascending
     int32_t fanout[kMaxTasks];              // quarters, edge parent[i] -> i
     int32_t vf[kMaxTasks][kMaxVariants];    // quarters, by variant (4 everywhere when absent)
     uint64_t stride[kMaxTasks];             // prod_{j<i} C_j
+    uint64_t magic[kMaxTasks][kMaxVariants];  // ceil(2^36 / radix): (c * magic) >> 36 = c / radix for c * radix <= 2^36
+    uint64_t magic_nb[kMaxTasks];           // ceil(2^36 / |B_i|)
     int64_t lat[kMaxTasks][kMaxVariants][kMaxBatches];    // microseconds
     int64_t thr_s[kMaxTasks][kMaxVariants][kMaxBatches];  // throughput * 4^depth
 };

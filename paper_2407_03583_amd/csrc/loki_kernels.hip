@@ -97,28 +97,40 @@ struct TaskOut {
     int64_t outflow;    // sum routed * variant factor: what the task creates per unit of child fan-out
 };
 
-// Decode choice c of task i (variant 0 least significant, batch digit on top) and
-// fill the hosted variants most accurate first (eq. (2), Algorithm 1's fill rule).
+// Decode choice c of task i (variant 0 least significant; the batch digit on top, or a batch
+// position inside every variant's digit) and fill the hosted variants most accurate first
+// (eq. (2), Algorithm 1's fill rule).
 __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o) {
     const int K = P->K[i];
-    uint64_t digits = 0;  // 8 bits per variant
+    const bool pv = P->pv_batch != 0;
+    const uint32_t nb = static_cast<uint32_t>(P->nb[i]);
+    uint64_t digits = 0;  // replicas, 8 bits per variant
+    uint32_t betas = 0;   // batch position, 4 bits per variant (per-variant batch sizes only)
     int32_t w = 0;
     for (int k = 0; k < K; k++) {
         const uint32_t radix = P->radix[i][k];
-        // c * radix < 2^32 (checked at problem creation), so the multiply-high quotient is exact
-        const uint32_t q = radix == 1 ? c : __umulhi(c, P->magic[i][k]);
-        const uint32_t x = c - q * radix;
+        // c * radix <= 2^36 (checked at problem creation), so the multiply-shift quotient is exact
+        const uint32_t q = static_cast<uint32_t>((static_cast<uint64_t>(c) * P->magic[i][k]) >> 36);
+        const uint32_t g = c - q * radix;
         c = q;
+        uint32_t x = g;
+        if (pv) {  // g = 0: not hosted; else 1 + (x-1)*nb + batch position
+            const uint32_t t = g - 1;
+            const uint32_t xq = static_cast<uint32_t>((static_cast<uint64_t>(t) * P->magic_nb[i]) >> 36);
+            x = g == 0 ? 0u : xq + 1;
+            betas |= (g == 0 ? 0u : t - xq * nb) << (4 * k);
+        }
         digits |= static_cast<uint64_t>(x) << (8 * k);
         w += static_cast<int32_t>(x);
     }
-    const uint32_t beta = c;
+    const uint32_t beta_task = c;
     int64_t rem = Dn, maxlat = 0, weighted = 0, outflow = 0;
     int32_t any = 0, first_acc = 0;
     const bool has_vf = P->has_vf != 0;
     for (int r = 0; r < K; r++) {
         const int k = P->order[i][r];
         const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
+        const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
         const int64_t cap = x * P->thr_s[i][k][beta];
         const int64_t lat = P->lat[i][k][beta];
         const int32_t acc = P->acc[i][k];

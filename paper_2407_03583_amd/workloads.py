@@ -79,13 +79,18 @@ class Pipeline:
     # optional: multiplicative factor of each variant in quarters (4 = 1.00), concat over (task, variant);
     # None = the factor of a task does not depend on the variant that served the request
     variant_factor_q4: Optional[List[int]] = None
+    # False: one batch size per task (a task's choice = replica counts x batch position).
+    # True: every hosted variant has its own batch size, y(i,k) of Section 4.1; per variant the
+    # digit is 0 (not hosted) or 1 + (replicas - 1) * |B_i| + batch position.
+    per_variant_batch: bool = False
 
     def choices_per_task(self) -> List[int]:
         out, v = [], 0
         for i in range(self.n_tasks):
-            c = self.n_batches[i]
+            c = 1 if self.per_variant_batch else self.n_batches[i]
             for k in range(self.n_variants[i]):
-                c *= self.max_replicas[v + k] + 1
+                r = self.max_replicas[v + k]
+                c *= 1 + r * self.n_batches[i] if self.per_variant_batch else r + 1
             v += self.n_variants[i]
             out.append(c)
         return out
@@ -105,6 +110,8 @@ class Pipeline:
         if self.variant_factor_q4 is not None:
             h.update(b"variant_factor_q4")
             h.update(",".join(str(int(v)) for v in self.variant_factor_q4).encode())
+        if self.per_variant_batch:
+            h.update(b"per_variant_batch")
         return h.hexdigest()
 
 
@@ -201,7 +208,8 @@ def config(cfg: int, seed: int | None = None) -> Workload:
 
 
 def random_small(seed: int, max_tasks: int = 3, max_variants: int = 3, max_replicas: int = 2,
-                 max_batches: int = 3, max_candidates: int = 20000, variant_factors: bool = False) -> Workload:
+                 max_batches: int = 3, max_candidates: int = 20000, variant_factors: bool = False,
+                 per_variant_batch: bool = False) -> Workload:
     """A small random problem (ragged K_i, R_ik and |B_i|, random tree) for
     exhaustive cross-checks.  Demand, worker count and SLO are drawn so that a
     healthy share of candidates is feasible."""
@@ -210,7 +218,8 @@ def random_small(seed: int, max_tasks: int = 3, max_variants: int = 3, max_repli
         n = rng.randint(1, max_tasks)
         parent = [-1] + [rng.randint(0, i - 1) for i in range(1, n)]
         p = Pipeline(n_tasks=n, parent=parent, fanout_q4=[], n_variants=[], n_batches=[],
-                     batch_size=[], max_replicas=[], acc_ppm=[], latency_us=[], thr_mqps=[])
+                     batch_size=[], max_replicas=[], acc_ppm=[], latency_us=[], thr_mqps=[],
+                     per_variant_batch=per_variant_batch)
         for i in range(n):
             k_i = rng.randint(1, max_variants)
             nb = rng.randint(1, max_batches)

@@ -40,27 +40,43 @@ def _tables(p):
     return tasks
 
 
-def decode(p, index: int) -> List[Tuple[List[int], int]]:
-    """index -> per task (replica counts, batch digit); task 0 and variant 0 least significant,
-    the batch digit is the most significant digit of a task's group."""
+def decode(p, index: int) -> List[Tuple[List[int], List[int]]]:
+    """index -> per task (replica counts, batch position per variant); task 0 and variant 0 least
+    significant.  One batch size per task: the batch digit is the most significant digit of the
+    task's group.  Per-variant batch sizes: a variant's digit is 0 (not hosted) or
+    1 + (replicas - 1) * |B| + batch position."""
+    pv = bool(getattr(p, "per_variant_batch", False))
     plan = []
     for task in _tables(p):
-        xs = []
+        nb = len(task["batches"])
+        xs, betas = [], []
         for var in task["variants"]:
-            xs.append(index % (var["limit"] + 1))
-            index //= var["limit"] + 1
-        beta = index % len(task["batches"])
-        index //= len(task["batches"])
-        plan.append((xs, beta))
+            if pv:
+                radix = 1 + var["limit"] * nb
+                g = index % radix
+                index //= radix
+                xs.append(0 if g == 0 else (g - 1) // nb + 1)
+                betas.append(0 if g == 0 else (g - 1) % nb)
+            else:
+                xs.append(index % (var["limit"] + 1))
+                index //= var["limit"] + 1
+        if not pv:
+            beta = index % nb
+            index //= nb
+            betas = [beta] * len(xs)
+        plan.append((xs, betas))
     return plan
 
 
 def num_candidates(p) -> int:
+    pv = bool(getattr(p, "per_variant_batch", False))
     n = 1
     for task in _tables(p):
-        n *= len(task["batches"])
+        nb = len(task["batches"])
+        if not pv:
+            n *= nb
         for var in task["variants"]:
-            n *= var["limit"] + 1
+            n *= 1 + var["limit"] * nb if pv else var["limit"] + 1
     return n
 
 
@@ -81,7 +97,7 @@ def evaluate(p, index: int, demand_mqps: int, workers: int, slo_us: int, comm_us
         mask |= BAD_WORKERS
     acc_task, lat_task = [], []
     for i, task in enumerate(tasks):
-        xs, beta = plan[i]
+        xs, betas = plan[i]
         if per_variant and i > 0:
             demand[i] = created[task["parent"]] * task["fan"]
         hosted = [k for k in range(len(xs)) if xs[k] > 0]
@@ -93,10 +109,10 @@ def evaluate(p, index: int, demand_mqps: int, workers: int, slo_us: int, comm_us
         in_use = []
         for pos, k in enumerate(hosted):
             var = task["variants"][k]
-            capacity = xs[k] * Fraction(var["thr"][beta], 1000)
+            capacity = xs[k] * Fraction(var["thr"][betas[k]], 1000)
             take = min(left, capacity)
             if take > 0 or pos == 0:
-                in_use.append(var["lat"][beta])
+                in_use.append(var["lat"][betas[k]])
             gained += take * Fraction(var["acc"], 1_000_000)
             if per_variant:
                 created[i] += take * var["factor"]

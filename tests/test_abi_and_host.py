@@ -80,7 +80,8 @@ def test_validation_rejects_bad_inputs():
 
 @pytest.mark.parametrize("seed", range(30))
 def test_route_table_matches_the_checker(seed):
-    w = wl.random_small(700 + seed, max_tasks=4, max_candidates=5000, variant_factors=seed % 2 == 1)
+    w = wl.random_small(700 + seed, max_tasks=4, max_candidates=5000, variant_factors=seed % 2 == 1,
+                        per_variant_batch=seed % 3 == 2)
     P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
     n = P.num_candidates()
     d = w.demand_mqps[0]
@@ -89,10 +90,11 @@ def test_route_table_matches_the_checker(seed):
         x, batch = P.decode(idx)
         v = 0
         for i in range(w.pipeline.n_tasks):
-            assert (r.demand[i], r.scale[i], r.unserved[i], r.batch[i]) == \
-                (ro.demand[i], ro.scale[i], ro.unserved[i], batch[i])
+            assert (r.demand[i], r.scale[i], r.unserved[i]) == (ro.demand[i], ro.scale[i], ro.unserved[i])
             for k in range(w.pipeline.n_variants[i]):
                 assert r.replicas[i][k] == x[v + k]
+                want_batch = batch[v + k] if w.pipeline.per_variant_batch else (batch[i] if x[v + k] > 0 else 0)
+                assert r.batch[i][k] == want_batch
                 assert (r.capacity[i][k], r.routed[i][k], r.leftover[i][k], r.budget_us[i][k]) == \
                     (ro.capacity[i][k], ro.routed[i][k], ro.leftover[i][k], ro.budget_us[i][k])
                 for k2 in range(oracle.MAX_VARIANTS):
@@ -111,3 +113,22 @@ def test_workload_generator_is_stable():
     want = json.load(open(path))
     for cfg in (1, 2, 3, 4, 5):
         assert wl.config(cfg).digest() == want[str(cfg)], cfg
+
+
+def test_decode_with_per_variant_batch_sizes():
+    for seed in range(10):
+        w = wl.random_small(900 + seed, max_variants=2, max_replicas=2, max_candidates=5000, per_variant_batch=True)
+        p = w.pipeline
+        P, O = binding.Problem(p), oracle.Problem(p)
+        n = P.num_candidates()
+        assert n == O.num_candidates() == p.num_candidates()
+        for idx in {0, n - 1, n // 2, (seed * 104729) % n}:
+            x, batch = P.decode(idx)
+            xo, beta = O.decode(idx)
+            assert x == xo
+            v = b = 0
+            for i in range(p.n_tasks):
+                for k in range(p.n_variants[i]):
+                    assert batch[v + k] == (p.batch_size[b + beta[v + k]] if x[v + k] > 0 else 0)
+                v += p.n_variants[i]
+                b += p.n_batches[i]

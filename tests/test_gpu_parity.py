@@ -313,3 +313,35 @@ def test_per_variant_multiplicative_factors(seed):
             for k in range(w.pipeline.n_variants[i]):
                 assert (r.capacity[i][k], r.routed[i][k], r.leftover[i][k]) == \
                     (ro.capacity[i][k], ro.routed[i][k], ro.leftover[i][k])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_per_variant_batch_sizes(seed):
+    """y(i,k): every hosted variant with its own batch size; still separable per task, so both kernels apply."""
+    w = wl.random_small(8000 + seed, max_tasks=3, max_variants=2, max_replicas=2, max_batches=3, max_candidates=200000,
+                        per_variant_batch=True, variant_factors=seed % 4 == 3)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    n = P.num_candidates()
+    d = w.demand_mqps[0]
+    for flags in ALL_FLAGS:
+        res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, flags=flags)[0]
+        check(res, O.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags & TIE)),
+              f"{w.name} flags={flags}")
+    rng = random.Random(seed)
+    idxs = list(range(n)) if n <= 4096 else [rng.randrange(n) for _ in range(4096)]
+    got = P.alloc_eval(idxs, d, w.workers, w.slo_us, w.comm_us)
+    for g, idx in zip(got, idxs):
+        e = O.eval(idx, d, w.workers, w.slo_us, w.comm_us)
+        assert (g.infeasible, g.workers, bits(g.accuracy)) == (e.infeasible, e.workers, bits(e.accuracy)), idx
+
+
+def test_per_variant_batch_sizes_at_scale():
+    """Config-1 profiles with a batch size per variant: 13^3 choices per task, 4.8M plans, 2197 root choices."""
+    w = wl.config(1)
+    w.pipeline.per_variant_batch = True
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    assert P.num_candidates() == 13 ** 6
+    for d in (0, w.demand_mqps[0], 2 * w.demand_mqps[0]):
+        ref = O.search(d, w.workers, w.slo_us)
+        for flags in (0, LANE):
+            check(P.alloc_search([d], w.workers, w.slo_us, flags=flags)[0], ref, f"pv cfg1 d={d} flags={flags}")

@@ -175,7 +175,7 @@ def test_every_candidate_matches_rational_reading(seed):
             assert abs(Fraction(e.accuracy) - r["exact"]) <= r["exact"] * n_ops * Fraction(1, 2**52)
         x, beta = prob.decode(index)
         plan = pyref.decode(p, index)
-        assert x == [v for xs, _ in plan for v in xs] and beta == [b for _, b in plan]
+        assert x == [v for xs, _ in plan for v in xs] and beta == [bs[0] for _, bs in plan]
         assert prob.encode(x, beta) == index
     for tie in (False, True):
         ref = pyref.search(p, d, w.workers, w.slo_us, w.comm_us, tie)
@@ -489,3 +489,69 @@ def test_child_demand_follows_the_parents_split():
     r = prob.route_table(idx, 120_000)
     assert r.demand[1] == 405_000 * 16 and r.unserved[1] == 0
     assert r.prob[1][1][0] == 1.0 and r.prob[1][0][0] == 1.0
+
+
+# ---- per-variant batch sizes y(i,k) (Section 4.1 "Output", eq. (4)) -----------------------------------------
+
+@pytest.mark.parametrize("seed", range(20))
+def test_per_variant_batch_matches_rational_reading(seed):
+    w = wl.random_small(6000 + seed, max_variants=2, max_replicas=2, max_batches=3, max_candidates=4000,
+                        per_variant_batch=True, variant_factors=seed % 3 == 0)
+    p = w.pipeline
+    prob = oracle.Problem(p)
+    n = prob.num_candidates()
+    assert n == pyref.num_candidates(p) == p.num_candidates()
+    d = w.demand_mqps[0]
+    for index in range(n):
+        e = prob.eval(index, d, w.workers, w.slo_us, w.comm_us)
+        r = pyref.evaluate(p, index, d, w.workers, w.slo_us, w.comm_us)
+        assert (e.infeasible, e.workers, e.accuracy) == (r["infeasible"], r["workers"], r["accuracy"]), index
+        x, beta = prob.decode(index)
+        plan = pyref.decode(p, index)
+        assert x == [v for xs, _ in plan for v in xs] and beta == [b for _, bs in plan for b in bs]
+        assert prob.encode(x, beta) == index
+    for tie in (False, True):
+        ref = pyref.search(p, d, w.workers, w.slo_us, w.comm_us, tie)
+        for b in (prob.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=tie, threads=3),
+                  prob.search_tabulated(d, w.workers, w.slo_us, w.comm_us, tie_index_only=tie, threads=2)):
+            assert (b.found, b.index, b.accuracy, b.workers, b.n_feasible) == \
+                (ref["found"], ref["index"], ref["accuracy"], ref["workers"], ref["n_feasible"])
+
+
+def test_per_variant_batch_contains_the_per_task_plans():
+    fields = ("n_tasks", "parent", "fanout_q4", "n_variants", "n_batches", "batch_size", "max_replicas",
+              "acc_ppm", "latency_us", "thr_mqps")
+    for seed in range(10):
+        w = wl.random_small(7000 + seed, max_variants=2, max_replicas=2, max_batches=3, max_candidates=3000)
+        p = w.pipeline
+        pv = SimpleNamespace(**{k: getattr(p, k) for k in fields}, per_variant_batch=True)
+        A, B = oracle.Problem(p), oracle.Problem(pv)
+        d = w.demand_mqps[0]
+        # every per-task plan has a twin with the same batch position on all hosted variants
+        for index in range(A.num_candidates()):
+            x, beta = A.decode(index)
+            per_variant, v = [], 0
+            for i in range(p.n_tasks):
+                per_variant += [beta[i] if x[v + k] > 0 else 0 for k in range(p.n_variants[i])]
+                v += p.n_variants[i]
+            twin = B.encode(x, per_variant)
+            ea, eb = A.eval(index, d, w.workers, w.slo_us, w.comm_us), B.eval(twin, d, w.workers, w.slo_us, w.comm_us)
+            assert (ea.infeasible, ea.workers, ea.accuracy) == (eb.infeasible, eb.workers, eb.accuracy)
+        a, b = A.search(d, w.workers, w.slo_us, w.comm_us), B.search(d, w.workers, w.slo_us, w.comm_us)
+        assert b.found >= a.found
+        if a.found:
+            assert (b.accuracy, -b.workers) >= (a.accuracy, -a.workers)
+        # with a single batch size the two plan spaces and their indices coincide
+        one = SimpleNamespace(**{k: getattr(p, k) for k in fields})
+        nb, lat, thr, bs, t = [], [], [], [], 0
+        for i in range(p.n_tasks):
+            for k in range(p.n_variants[i]):
+                lat.append(p.latency_us[t + k * p.n_batches[i]])
+                thr.append(p.thr_mqps[t + k * p.n_batches[i]])
+            t += p.n_variants[i] * p.n_batches[i]
+            bs.append(p.batch_size[sum(p.n_batches[:i])])
+            nb.append(1)
+        one.n_batches, one.batch_size, one.latency_us, one.thr_mqps = nb, bs, lat, thr
+        one_pv = SimpleNamespace(**vars(one), per_variant_batch=True)
+        assert oracle.Problem(one).search(d, w.workers, w.slo_us).as_tuple() == \
+            oracle.Problem(one_pv).search(d, w.workers, w.slo_us).as_tuple()
