@@ -220,6 +220,16 @@ int loki_alloc_eval(loki_problem_t *problem, const uint64_t *indices, int64_t n_
 int loki_route_table(const loki_problem_t *problem, uint64_t index, int64_t demand_mqps,
                      loki_route_t *out);
 
+/* The same for many plans at once, on the GPU: plan indices[j] under root demand
+ * demand_mqps[j], one lane per plan -- typically the winners of a demand sweep, so
+ * that the routing tables of every demand point come back with one call.
+ *   indices, demand_mqps  host, [n];  out  host, [n]
+ *   d_workspace  device, 256-byte aligned, >= loki_route_workspace_bytes(n) */
+int loki_route_workspace_bytes(const loki_problem_t *problem, int64_t n, size_t *bytes);
+int loki_route_table_batch(loki_problem_t *problem, const uint64_t *indices, const int64_t *demand_mqps,
+                           int64_t n, void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                           loki_route_t *out);
+
 /* GPU time of the most recent loki_alloc_search on this handle, from HIP events
  * on the caller's stream: ms[0] per-task tables (0 for LOKI_SEARCH_PER_LANE),
  * ms[1] the kernel that visits every plan, ms[2] the final merge.  ms: host, [3].

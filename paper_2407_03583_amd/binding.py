@@ -25,7 +25,7 @@ UINT64_MAX = (1 << 64) - 1
 
 EXPORTS = ["loki_problem_create", "loki_problem_destroy", "loki_num_candidates", "loki_workspace_bytes",
            "loki_decode", "loki_alloc_search", "loki_alloc_search_enqueue", "loki_alloc_eval",
-           "loki_route_table", "loki_last_search_ms", "loki_strerror", "loki_last_hip_error"]
+           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_last_search_ms", "loki_strerror", "loki_last_hip_error"]
 
 
 class LokiError(RuntimeError):
@@ -117,6 +117,11 @@ def lib():
                                       C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(Eval)]
         L.loki_route_table.restype = C.c_int
         L.loki_route_table.argtypes = [P, C.c_uint64, C.c_int64, C.POINTER(Route)]
+        L.loki_route_workspace_bytes.restype = C.c_int
+        L.loki_route_workspace_bytes.argtypes = [P, C.c_int64, C.POINTER(C.c_size_t)]
+        L.loki_route_table_batch.restype = C.c_int
+        L.loki_route_table_batch.argtypes = [P, C.POINTER(C.c_uint64), C.POINTER(C.c_int64), C.c_int64, C.c_void_p,
+                                             C.c_size_t, C.c_void_p, C.POINTER(Route)]
         L.loki_last_search_ms.restype = C.c_int
         L.loki_last_search_ms.argtypes = [P, C.POINTER(C.c_float)]
         L.loki_strerror.restype = C.c_char_p
@@ -240,6 +245,17 @@ class Problem:
         out = Route()
         _check(lib().loki_route_table(self._h, index, demand_mqps, C.byref(out)), "loki_route_table")
         return out
+
+    def route_table_batch(self, indices: Sequence[int], demand_mqps: Sequence[int]) -> List[Route]:
+        import torch
+        n = len(indices)
+        need = C.c_size_t()
+        _check(lib().loki_route_workspace_bytes(self._h, n, C.byref(need)), "loki_route_workspace_bytes")
+        ws = torch.empty(int(need.value), dtype=torch.uint8, device="cuda")
+        out = (Route * n)()
+        _check(lib().loki_route_table_batch(self._h, _arr(C.c_uint64, indices), _arr(C.c_int64, demand_mqps), n,
+                                            ws.data_ptr(), ws.numel(), self._stream(), out), "loki_route_table_batch")
+        return list(out)
 
     def last_search_ms(self) -> List[float]:
         """[per-task tables, main search kernel, final merge] of the last blocking search, in ms."""

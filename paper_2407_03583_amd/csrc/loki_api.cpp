@@ -16,6 +16,7 @@ using namespace loki;
 
 static_assert(LOKI_MAX_TASKS == kMaxTasks && LOKI_MAX_VARIANTS == kMaxVariants && LOKI_MAX_BATCHES == kMaxBatches,
               "header and kernels disagree on limits");
+static_assert(sizeof(loki_route_t) == sizeof(RouteOut), "route record layout");
 static_assert(sizeof(loki_result_t) == 32 && sizeof(loki_eval_t) == 16 && sizeof(BestRec) == 32 &&
                   sizeof(TaskRec) == 16 && sizeof(MidVal) == 16 && sizeof(MidLim) == 16,
               "record layouts");
@@ -328,11 +329,13 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         uint64_t choices = d.pv_batch ? 1u : uint64_t(nb);
         d.magic_nb[i] = ((uint64_t(1) << 36) + uint64_t(nb) - 1) / uint64_t(nb);
         d.fanout[i] = i > 0 ? in->fanout_q4[i] : 4;
+        d.scale[i] = scale;
         p->max_vf[i] = 4;
         for (int bi = 0; bi < nb; bi++) {
             const int32_t bs = in->batch_size[b + bi];
             if (bs < 1 || (bi > 0 && bs <= in->batch_size[b + bi - 1])) rc = LOKI_E_RANGE;
             p->batch_size[i][bi] = bs;
+            d.batch_size[i][bi] = bs;
         }
         for (int k = 0; k < K; k++) {
             const int32_t R = in->max_replicas[v + k], acc = in->acc_ppm[v + k];
@@ -604,6 +607,53 @@ int loki_route_table(const loki_problem_t *p, uint64_t index, int64_t demand_mqp
             }
         }
     *out = r;
+    return LOKI_OK;
+}
+
+int loki_route_workspace_bytes(const loki_problem_t *p, int64_t n, size_t *bytes) {
+    if (!p || !bytes) return LOKI_E_NULL;
+    if (n < 1) return LOKI_E_ARG;
+    *bytes = align_up(sizeof(DevProblem)) + align_up(size_t(n) * 8) + align_up(size_t(n) * 8) +
+             align_up(size_t(n) * sizeof(RouteOut));
+    return LOKI_OK;
+}
+
+int loki_route_table_batch(loki_problem_t *p, const uint64_t *indices, const int64_t *demand_mqps, int64_t n,
+                           void *d_workspace, size_t workspace_bytes, void *hip_stream, loki_route_t *out) {
+    if (!p || !indices || !demand_mqps || !d_workspace || !out) return LOKI_E_NULL;
+    if (n < 1 || n > (int64_t(1) << 24)) return LOKI_E_ARG;
+    size_t need = 0;
+    (void)loki_route_workspace_bytes(p, n, &need);
+    if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0) return LOKI_E_WORKSPACE;
+    for (int64_t j = 0; j < n; j++) {
+        if (indices[j] >= p->n_candidates) return LOKI_E_RANGE;
+        int64_t Dn[kMaxTasks];
+        const int rc = task_demand(p, demand_mqps[j], Dn);
+        if (rc) return rc;
+    }
+    int rc = ensure_staging(p, 1);
+    if (rc) return rc;
+    if (p->staged_pending) {
+        LOKI_HIP(hipEventSynchronize(p->staged));
+        p->staged_pending = false;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(d_workspace);
+    const size_t off_idx = align_up(sizeof(DevProblem)), off_dem = off_idx + align_up(size_t(n) * 8),
+                 off_out = off_dem + align_up(size_t(n) * 8);
+    std::memcpy(p->staging, &p->dev, sizeof(DevProblem));
+    LOKI_HIP(hipMemcpyAsync(ws, p->staging, sizeof(DevProblem), hipMemcpyHostToDevice, stream));
+    LOKI_HIP(hipMemcpyAsync(ws + off_idx, indices, size_t(n) * 8, hipMemcpyHostToDevice, stream));
+    LOKI_HIP(hipMemcpyAsync(ws + off_dem, demand_mqps, size_t(n) * 8, hipMemcpyHostToDevice, stream));
+    RouteArgs A;
+    A.P = reinterpret_cast<const DevProblem *>(ws);
+    A.indices = reinterpret_cast<const uint64_t *>(ws + off_idx);
+    A.demand = reinterpret_cast<const int64_t *>(ws + off_dem);
+    A.out = reinterpret_cast<RouteOut *>(ws + off_out);
+    A.n = n;
+    LOKI_HIP(launch_route(A, stream));
+    LOKI_HIP(hipMemcpyAsync(out, ws + off_out, size_t(n) * sizeof(RouteOut), hipMemcpyDeviceToHost, stream));
+    LOKI_HIP(hipStreamSynchronize(stream));
     return LOKI_OK;
 }
 

@@ -38,6 +38,8 @@ struct DevProblem {
     int32_t lat0_sorted[kMaxVariants * kMaxBatches];  // those latencies, ascending
     int32_t fanout[kMaxTasks];              // quarters, edge parent[i] -> i
     int32_t vf[kMaxTasks][kMaxVariants];    // quarters, by variant (4 everywhere when absent)
+    int32_t batch_size[kMaxTasks][kMaxBatches];
+    int64_t scale[kMaxTasks];               // 4^depth, or 16^depth with per-variant factors
     uint64_t stride[kMaxTasks];             // prod_{j<i} C_j
     uint64_t magic[kMaxTasks][kMaxVariants];  // ceil(2^36 / radix): (c * magic) >> 36 = c / radix for c * radix <= 2^36
     uint64_t magic_nb[kMaxTasks];           // ceil(2^36 / |B_i|)
@@ -98,6 +100,28 @@ struct SearchArgs {
     int32_t M;
     uint32_t blocks_per_m;
     uint32_t tie_index_only;
+};
+
+// Mirrors loki_route_t (include/loki_alloc.h).
+struct RouteOut {
+    int64_t demand[kMaxTasks];
+    int64_t scale[kMaxTasks];
+    int64_t unserved[kMaxTasks];
+    int32_t replicas[kMaxTasks][kMaxVariants];
+    int32_t batch[kMaxTasks][kMaxVariants];
+    int64_t capacity[kMaxTasks][kMaxVariants];
+    int64_t routed[kMaxTasks][kMaxVariants];
+    int64_t leftover[kMaxTasks][kMaxVariants];
+    int64_t budget_us[kMaxTasks][kMaxVariants];
+    double prob[kMaxTasks][kMaxVariants][kMaxVariants];
+};
+
+struct RouteArgs {
+    const DevProblem *P;
+    const uint64_t *indices;
+    const int64_t *demand;
+    RouteOut *out;
+    int64_t n;
 };
 
 struct EvalArgs {

@@ -938,6 +938,78 @@ __global__ void __launch_bounds__(kBlockThreads) eval_kernel(EvalArgs A) {
     static_cast<EvalOut *>(A.out)[t] = o;
 }
 
+// ---- kernel: routing tables of listed plans, one lane per plan ---------------------------------------------
+// Algorithm 1 (MostAccurateFirst) with all replicas of a variant treated as one worker of
+// capacity x*q: tasks in topological order, a task's workers by accuracy, each worker's outgoing
+// requests placed on the child's workers by accuracy while capacity lasts.  Not a hot path: the
+// lane works directly on its output record in global memory.
+__device__ int64_t route_place(const DevProblem *P, RouteOut &r, int j, int64_t amount, double *prob_row) {
+    const int64_t total = amount;
+    for (int o = 0; o < P->K[j] && amount > 0; o++) {
+        const int k = P->order[j][o];
+        const int64_t room = r.leftover[j][k];
+        const int64_t take = amount < room ? amount : room;
+        if (take <= 0) continue;
+        prob_row[k] = static_cast<double>(take) / static_cast<double>(total);
+        r.leftover[j][k] = room - take;
+        r.routed[j][k] += take;
+        amount -= take;
+    }
+    return amount;
+}
+
+__global__ void __launch_bounds__(kBlockThreads) route_kernel(RouteArgs A) {
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * kBlockThreads + threadIdx.x;
+    if (t >= A.n) return;
+    const DevProblem *P = A.P;
+    RouteOut &r = A.out[t];
+    uint64_t *words = reinterpret_cast<uint64_t *>(&r);
+    for (uint32_t q = 0; q < sizeof(RouteOut) / 8; q++) words[q] = 0;
+    const int n = P->n_tasks;
+    uint64_t rest = A.indices[t];
+    for (int i = 0; i < n; i++) {
+        uint64_t c = rest % P->C[i];
+        rest /= P->C[i];
+        const uint32_t nb = static_cast<uint32_t>(P->nb[i]);
+        uint32_t beta[kMaxVariants];
+        for (int k = 0; k < P->K[i]; k++) {
+            const uint64_t g = c % P->radix[i][k];
+            c /= P->radix[i][k];
+            if (P->pv_batch) {
+                r.replicas[i][k] = g == 0 ? 0 : static_cast<int32_t>((g - 1) / nb) + 1;
+                beta[k] = g == 0 ? 0u : static_cast<uint32_t>((g - 1) % nb);
+            } else {
+                r.replicas[i][k] = static_cast<int32_t>(g);
+            }
+        }
+        r.scale[i] = P->scale[i];
+        r.demand[i] = i == 0 ? A.demand[t] : r.demand[P->parent[i]] * P->fanout[i];  // replaced below with r(i,k)
+        for (int k = 0; k < P->K[i]; k++) {
+            const uint32_t b = P->pv_batch ? beta[k] : static_cast<uint32_t>(c);
+            const bool hosted = r.replicas[i][k] > 0;
+            r.batch[i][k] = hosted ? P->batch_size[i][b] : 0;
+            r.capacity[i][k] = static_cast<int64_t>(r.replicas[i][k]) * P->thr_s[i][k][b];
+            r.leftover[i][k] = r.capacity[i][k];
+            r.budget_us[i][k] = hosted ? P->lat[i][k][b] : 0;
+        }
+    }
+    r.unserved[0] = route_place(P, r, 0, r.demand[0], r.prob[0][0]);
+    for (int i = 0; i < n; i++)
+        for (int o = 0; o < P->K[i]; o++) {
+            const int k = P->order[i][o];
+            for (int j = i + 1; j < n; j++) {
+                if (P->parent[j] != i) continue;
+                int64_t created = r.routed[i][k] * static_cast<int64_t>(P->fanout[j]);
+                if (P->has_vf) {  // the child's demand is what the parent's variants create
+                    created *= P->vf[i][k];
+                    if (o == 0) r.demand[j] = 0;
+                    r.demand[j] += created;
+                }
+                r.unserved[j] += route_place(P, r, j, created, r.prob[j][k]);
+            }
+        }
+}
+
 template <int S>
 hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
@@ -984,6 +1056,12 @@ hipError_t launch_per_lane_search(const SearchArgs &A, hipStream_t stream) {
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream) {
     const dim3 grid(A.M), block(kBlockThreads);
     hipLaunchKernelGGL(final_reduce_kernel, grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_route(const RouteArgs &A, hipStream_t stream) {
+    const dim3 grid(static_cast<uint32_t>((A.n + kBlockThreads - 1) / kBlockThreads)), block(kBlockThreads);
+    hipLaunchKernelGGL(route_kernel, grid, block, 0, stream, A);
     return hipGetLastError();
 }
 

@@ -15,5 +15,6 @@ hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool 
 hipError_t launch_per_lane_search(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_eval(const EvalArgs &A, hipStream_t stream);
+hipError_t launch_route(const RouteArgs &A, hipStream_t stream);
 
 }  // namespace loki

@@ -345,3 +345,27 @@ def test_per_variant_batch_sizes_at_scale():
         ref = O.search(d, w.workers, w.slo_us)
         for flags in (0, LANE):
             check(P.alloc_search([d], w.workers, w.slo_us, flags=flags)[0], ref, f"pv cfg1 d={d} flags={flags}")
+
+
+def test_batched_route_tables_match_the_host_path_and_the_checker():
+    import ctypes as C
+    cases = [wl.config(1), wl.config(4)]
+    cases += [wl.random_small(9000 + s, max_tasks=4, max_candidates=30000, variant_factors=s % 2 == 0,
+                              per_variant_batch=s % 3 == 0) for s in range(8)]
+    for w in cases:
+        P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+        demands = w.demand_mqps if len(w.demand_mqps) > 1 else [w.demand_mqps[0] * f // 4 for f in range(0, 9)]
+        demands = demands[:48]
+        wins = P.alloc_search(demands, w.workers, w.slo_us, w.comm_us)
+        idxs = [r.index if r.status == binding.LOKI_FOUND else (7 * m) % P.num_candidates() for m, r in enumerate(wins)]
+        batch = P.route_table_batch(idxs, demands)
+        for idx, d, got in zip(idxs, demands, batch):
+            host = P.route_table(idx, d)
+            assert bytes(got) == bytes(host), (w.name, idx, d)
+            ro = O.route_table(idx, d)
+            for i in range(w.pipeline.n_tasks):
+                assert (got.demand[i], got.unserved[i]) == (ro.demand[i], ro.unserved[i])
+                for k in range(w.pipeline.n_variants[i]):
+                    assert (got.routed[i][k], got.leftover[i][k]) == (ro.routed[i][k], ro.leftover[i][k])
+                    for k2 in range(oracle.MAX_VARIANTS):
+                        assert bits(got.prob[i][k][k2]) == bits(ro.prob[i][k][k2])
