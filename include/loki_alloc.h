@@ -230,6 +230,29 @@ int loki_route_table_batch(loki_problem_t *problem, const uint64_t *indices, con
                            int64_t n, void *d_workspace, size_t workspace_bytes, void *hip_stream,
                            loki_route_t *out);
 
+/* The Resource Manager's periodic loop over a demand history (Section 4.2, "Solving the MILP"):
+ * the demand to serve is an exponentially weighted moving average of the recent demand,
+ *   est_0 = trace_0,  est_t = floor((alpha_ppm * trace_t + (10^6 - alpha_ppm) * est_{t-1}) / 10^6),
+ * and every estimate gets its allocation from one batched search.  phase tells which of the two
+ * steps of Section 4 produced the plan: LOKI_PHASE_HARDWARE if the best accuracy is the one of
+ * the most accurate variants (the plan is then the minimum-worker plan, eq. (11)),
+ * LOKI_PHASE_ACCURACY if accuracy had to be given up (eq. (12)), LOKI_PHASE_OVERLOAD if no plan
+ * serves the estimate.
+ *   trace_mqps  host, [n], >= 0;  alpha_ppm in 1..10^6;  out  host, [n]
+ *   d_workspace as for loki_alloc_search with n demand points. */
+#define LOKI_PHASE_HARDWARE 0
+#define LOKI_PHASE_ACCURACY 1
+#define LOKI_PHASE_OVERLOAD 2
+typedef struct { /* 48 bytes */
+    int64_t estimate_mqps;
+    loki_result_t plan;
+    int32_t phase;
+    int32_t pad;
+} loki_plan_step_t;
+int loki_plan_trace(loki_problem_t *problem, const int64_t *trace_mqps, int32_t n, int32_t alpha_ppm,
+                    int32_t workers, int64_t slo_us, int64_t comm_us, uint32_t flags,
+                    void *d_workspace, size_t workspace_bytes, void *hip_stream, loki_plan_step_t *out);
+
 /* GPU time of the most recent loki_alloc_search on this handle, from HIP events
  * on the caller's stream: ms[0] per-task tables (0 for LOKI_SEARCH_PER_LANE),
  * ms[1] the kernel that visits every plan, ms[2] the final merge.  ms: host, [3].

@@ -21,11 +21,12 @@ LOKI_E_NULL, LOKI_E_INVALID_GRAPH, LOKI_E_RANGE, LOKI_E_WORKSPACE, LOKI_E_HIP, L
 LOKI_TIE_WORKERS_THEN_INDEX, LOKI_TIE_INDEX_ONLY, LOKI_SEARCH_PER_LANE = 0, 1, 2
 LOKI_FOUND, LOKI_NO_FEASIBLE = 0, 1
 LOKI_BAD_WORKERS, LOKI_BAD_DEMAND, LOKI_BAD_EMPTY, LOKI_BAD_LATENCY = 1, 2, 4, 8
+LOKI_PHASE_HARDWARE, LOKI_PHASE_ACCURACY, LOKI_PHASE_OVERLOAD = 0, 1, 2
 UINT64_MAX = (1 << 64) - 1
 
 EXPORTS = ["loki_problem_create", "loki_problem_destroy", "loki_num_candidates", "loki_workspace_bytes",
            "loki_decode", "loki_alloc_search", "loki_alloc_search_enqueue", "loki_alloc_eval",
-           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_last_search_ms", "loki_strerror", "loki_last_hip_error"]
+           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_last_search_ms", "loki_strerror", "loki_last_hip_error"]
 
 
 class LokiError(RuntimeError):
@@ -63,6 +64,13 @@ class Result(C.Structure):
         """(index, accuracy, n_feasible, workers, found) -- found = 1 when a plan was returned."""
         return (int(self.index), float(self.accuracy), int(self.n_feasible), int(self.workers_used),
                 1 if self.status == LOKI_FOUND else 0)
+
+
+class PlanStep(C.Structure):
+    _fields_ = [("estimate_mqps", C.c_int64),
+                ("plan", Result),
+                ("phase", C.c_int32),
+                ("pad", C.c_int32)]
 
 
 class Eval(C.Structure):
@@ -122,6 +130,9 @@ def lib():
         L.loki_route_table_batch.restype = C.c_int
         L.loki_route_table_batch.argtypes = [P, C.POINTER(C.c_uint64), C.POINTER(C.c_int64), C.c_int64, C.c_void_p,
                                              C.c_size_t, C.c_void_p, C.POINTER(Route)]
+        L.loki_plan_trace.restype = C.c_int
+        L.loki_plan_trace.argtypes = [P, C.POINTER(C.c_int64), C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
+                                      C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(PlanStep)]
         L.loki_last_search_ms.restype = C.c_int
         L.loki_last_search_ms.argtypes = [P, C.POINTER(C.c_float)]
         L.loki_strerror.restype = C.c_char_p
@@ -255,6 +266,15 @@ class Problem:
         out = (Route * n)()
         _check(lib().loki_route_table_batch(self._h, _arr(C.c_uint64, indices), _arr(C.c_int64, demand_mqps), n,
                                             ws.data_ptr(), ws.numel(), self._stream(), out), "loki_route_table_batch")
+        return list(out)
+
+    def plan_trace(self, trace_mqps: Sequence[int], alpha_ppm: int, workers: int, slo_us: int, comm_us: int = 0,
+                   *, flags: int = 0) -> List[PlanStep]:
+        n = len(trace_mqps)
+        ws = self._workspace(n)
+        out = (PlanStep * n)()
+        _check(lib().loki_plan_trace(self._h, _arr(C.c_int64, trace_mqps), n, alpha_ppm, workers, slo_us, comm_us,
+                                     flags, ws.data_ptr(), ws.numel(), self._stream(), out), "loki_plan_trace")
         return list(out)
 
     def last_search_ms(self) -> List[float]:

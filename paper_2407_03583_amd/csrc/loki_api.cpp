@@ -657,6 +657,43 @@ int loki_route_table_batch(loki_problem_t *p, const uint64_t *indices, const int
     return LOKI_OK;
 }
 
+int loki_plan_trace(loki_problem_t *p, const int64_t *trace_mqps, int32_t n, int32_t alpha_ppm, int32_t workers,
+                    int64_t slo_us, int64_t comm_us, uint32_t flags, void *d_workspace, size_t workspace_bytes,
+                    void *hip_stream, loki_plan_step_t *out) {
+    if (!p || !trace_mqps || !out) return LOKI_E_NULL;
+    if (n < 1 || n > LOKI_MAX_DEMAND_POINTS || alpha_ppm < 1 || alpha_ppm > 1000000) return LOKI_E_ARG;
+    std::vector<int64_t> est(static_cast<size_t>(n));
+    std::vector<loki_result_t> res(static_cast<size_t>(n));
+    for (int32_t t = 0; t < n; t++) {
+        if (trace_mqps[t] < 0 || trace_mqps[t] > (int64_t(1) << 40)) return LOKI_E_RANGE;
+        est[t] = t == 0 ? trace_mqps[0]
+                        : (int64_t(alpha_ppm) * trace_mqps[t] + int64_t(1000000 - alpha_ppm) * est[t - 1]) / 1000000;
+    }
+    const int rc = loki_alloc_search(p, est.data(), n, workers, slo_us, comm_us, flags, 0, p->n_candidates,
+                                     d_workspace, workspace_bytes, hip_stream, res.data());
+    if (rc) return rc;
+    // accuracy of the most accurate variants: the same operations in the same order as for any plan
+    double pp[kMaxTasks], sum = 0.0;
+    bool first = true;
+    for (int i = 0; i < p->n; i++) {
+        const double a = double(p->dev.acc[i][p->dev.order[i][0]]) / 1000000.0;
+        pp[i] = i == 0 ? a : pp[p->dev.parent[i]] * a;
+        if (p->dev.is_leaf[i]) {
+            sum = first ? pp[i] : sum + pp[i];
+            first = false;
+        }
+    }
+    const double top = sum / double(p->dev.n_paths);
+    for (int32_t t = 0; t < n; t++) {
+        out[t].estimate_mqps = est[t];
+        out[t].plan = res[t];
+        out[t].phase = res[t].status != LOKI_FOUND ? LOKI_PHASE_OVERLOAD
+                                                   : (res[t].accuracy == top ? LOKI_PHASE_HARDWARE : LOKI_PHASE_ACCURACY);
+        out[t].pad = 0;
+    }
+    return LOKI_OK;
+}
+
 int loki_last_search_ms(const loki_problem_t *p, float *ms) {
     if (!p || !ms) return LOKI_E_NULL;
     if (!p->have_ms) return LOKI_E_ARG;

@@ -369,3 +369,37 @@ def test_batched_route_tables_match_the_host_path_and_the_checker():
                     assert (got.routed[i][k], got.leftover[i][k]) == (ro.routed[i][k], ro.leftover[i][k])
                     for k2 in range(oracle.MAX_VARIANTS):
                         assert bits(got.prob[i][k][k2]) == bits(ro.prob[i][k][k2])
+
+
+def test_plan_trace_follows_the_two_step_resource_manager():
+    """EWMA demand estimate, one allocation per estimate, and the phase (hardware scaling while the most
+    accurate variants suffice, then accuracy scaling, then overload): Section 4 and Section 4.2, and the
+    shape of the paper's Figure 1 walk-through on a rising demand ramp."""
+    from fractions import Fraction
+    w = wl.config(1)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    rng = random.Random(4)
+    ramp = [int(3_000 * t + rng.randint(0, 2_000)) for t in range(120)]
+    alpha = 300_000
+    steps = P.plan_trace(ramp, alpha, w.workers, w.slo_us)
+    top = O.search(0, w.workers, w.slo_us).accuracy          # zero demand: the most accurate variants
+    est = None
+    phases = []
+    for t, (d, s) in enumerate(zip(ramp, steps)):
+        est = d if t == 0 else (Fraction(alpha * d + (10**6 - alpha) * est, 10**6)).__floor__()
+        assert s.estimate_mqps == est
+        check(s.plan, O.search(est, w.workers, w.slo_us), f"trace step {t}")
+        want = binding.LOKI_PHASE_OVERLOAD if s.plan.status != binding.LOKI_FOUND else (
+            binding.LOKI_PHASE_HARDWARE if s.plan.accuracy == top else binding.LOKI_PHASE_ACCURACY)
+        assert s.phase == want
+        phases.append(s.phase)
+    # estimates of a rising ramp rise, so the phases come in order and all three occur
+    assert phases == sorted(phases) and set(phases) == {0, 1, 2}
+    hw = [s for s in steps if s.phase == binding.LOKI_PHASE_HARDWARE]
+    assert all(a.plan.workers_used <= b.plan.workers_used for a, b in zip(hw, hw[1:]))   # servers added first
+    assert hw[-1].plan.workers_used <= w.workers
+    acc = [s.plan.accuracy for s in steps if s.phase != binding.LOKI_PHASE_OVERLOAD]
+    assert all(a >= b for a, b in zip(acc, acc[1:]))                                      # then accuracy is traded
+    # a constant trace is its own estimate
+    flat = P.plan_trace([77_777] * 5, 1, w.workers, w.slo_us)
+    assert [s.estimate_mqps for s in flat] == [77_777] * 5
