@@ -48,7 +48,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the search shards by index range; see DESIGN.md); "
+        print("bench.py: this build runs on one GPU only (more GPUs would each take an index range); "
               "use --gpus 1", file=sys.stderr)
         return 2
 
@@ -119,6 +119,10 @@ def main() -> int:
                      "frac": achieved / VALU_PEAK_TLANEOPS, "traffic": None,
                      "lane_ops_per_candidate": ops},
     }
+    # what a dependency-free stream of the search's own instructions sustains on this GPU
+    mix = binding.measure_valu_rate("search_mix")
+    out["roofline"]["sustained_mix_Tlane_op_s"] = mix * 64 / 1e12
+    out["roofline"]["sustained_u32_Tlane_op_s"] = binding.measure_valu_rate("v_add_u32") * 64 / 1e12
     if not args.no_cpu_baseline:
         import oracle
         O = oracle.Problem(w.pipeline)

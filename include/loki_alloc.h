@@ -259,6 +259,15 @@ int loki_plan_trace(loki_problem_t *problem, const int64_t *trace_mqps, int32_t 
  * LOKI_E_ARG if no blocking search has completed yet. */
 int loki_last_search_ms(const loki_problem_t *problem, float *ms);
 
+/* Measurement aid for the roofline (for callers that report a fraction of peak, not for the
+ * search itself): sustained issue rate, in wavefront instructions per second over the whole
+ * GPU, of a dependency-free stream of one vector-ALU instruction class, 8 wavefronts per SIMD.
+ *   kind  0 v_mul_f64, 1 v_add_f64, 2 v_max_f64, 3 the search's multiply/add/max mix, 4 v_add_u32
+ *   d_workspace  device, >= 4 MiB.  Blocks until the measurement (tens of ms) is done.
+ * The nominal figure is compute_units * 4 SIMDs * clock / 4 cycles. */
+int loki_measure_valu_rate(int kind, void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                           double *wave_instructions_per_second);
+
 const char *loki_strerror(int code);
 int loki_last_hip_error(void);
 

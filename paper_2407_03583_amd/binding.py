@@ -26,7 +26,7 @@ UINT64_MAX = (1 << 64) - 1
 
 EXPORTS = ["loki_problem_create", "loki_problem_destroy", "loki_num_candidates", "loki_workspace_bytes",
            "loki_decode", "loki_alloc_search", "loki_alloc_search_enqueue", "loki_alloc_eval",
-           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_last_search_ms", "loki_strerror", "loki_last_hip_error"]
+           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_measure_valu_rate", "loki_last_search_ms", "loki_strerror", "loki_last_hip_error"]
 
 
 class LokiError(RuntimeError):
@@ -133,6 +133,8 @@ def lib():
         L.loki_plan_trace.restype = C.c_int
         L.loki_plan_trace.argtypes = [P, C.POINTER(C.c_int64), C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                       C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(PlanStep)]
+        L.loki_measure_valu_rate.restype = C.c_int
+        L.loki_measure_valu_rate.argtypes = [C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
         L.loki_last_search_ms.restype = C.c_int
         L.loki_last_search_ms.argtypes = [P, C.POINTER(C.c_float)]
         L.loki_strerror.restype = C.c_char_p
@@ -282,6 +284,20 @@ class Problem:
         ms = (C.c_float * 3)()
         _check(lib().loki_last_search_ms(self._h, ms), "loki_last_search_ms")
         return [float(v) for v in ms]
+
+
+RATE_KINDS = {"v_mul_f64": 0, "v_add_f64": 1, "v_max_f64": 2, "search_mix": 3, "v_add_u32": 4}
+
+
+def measure_valu_rate(kind: str) -> float:
+    """Sustained wavefront instructions per second of one vector-ALU instruction class."""
+    import torch
+    ws = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")
+    rate = C.c_double()
+    _check(lib().loki_measure_valu_rate(RATE_KINDS[kind], ws.data_ptr(), ws.numel(),
+                                        int(torch.cuda.current_stream().cuda_stream), C.byref(rate)),
+           "loki_measure_valu_rate")
+    return float(rate.value)
 
 
 def results_from_bytes(buf: bytes) -> List[Result]:

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libloki_alloc.so")
-SOURCES = ["loki_kernels.hip", "loki_api.cpp"]
+SOURCES = ["loki_kernels.hip", "loki_valu_rate.hip", "loki_api.cpp"]
 HEADERS = ["loki_device.h", "loki_launch.h"]
 
 HIPCC_FLAGS = [

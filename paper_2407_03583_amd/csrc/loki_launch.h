@@ -17,4 +17,13 @@ hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_eval(const EvalArgs &A, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &A, hipStream_t stream);
 
+// instruction classes of launch_valu_rate (mirrors LOKI_RATE_* of the public header)
+#define LOKI_RATE_MUL_F64 0
+#define LOKI_RATE_ADD_F64 1
+#define LOKI_RATE_MAX_F64 2
+#define LOKI_RATE_SEARCH_MIX 3
+#define LOKI_RATE_ADD_U32 4
+// `out` needs blocks * 256 doubles; every thread runs iters trips of 16 instructions
+hipError_t launch_valu_rate(int kind, double *out, int blocks, int iters, hipStream_t stream);
+
 }  // namespace loki

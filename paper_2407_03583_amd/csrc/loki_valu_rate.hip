@@ -1,0 +1,79 @@
+// Sustained issue rate of the vector-ALU instruction classes the search is made of, measured
+// with dependency-free streams (16 independent instructions per loop trip, 8 wavefronts per
+// SIMD).  A measurement aid for the roofline: the nominal peak assumes one vector instruction
+// per SIMD every 4 cycles at 2.4 GHz; this tells what the GPU at hand actually sustains.
+#include <hip/hip_runtime.h>
+
+#include "loki_launch.h"
+
+#pragma clang fp contract(off)
+
+namespace loki {
+
+namespace {
+
+#define LOKI_REP16(OP)                                                                              \
+    OP " %0, %0, %8\n" OP " %1, %1, %8\n" OP " %2, %2, %8\n" OP " %3, %3, %8\n" OP " %4, %4, %8\n"  \
+    OP " %5, %5, %8\n" OP " %6, %6, %8\n" OP " %7, %7, %8\n" OP " %0, %0, %8\n" OP " %1, %1, %8\n"  \
+    OP " %2, %2, %8\n" OP " %3, %3, %8\n" OP " %4, %4, %8\n" OP " %5, %5, %8\n" OP " %6, %6, %8\n"  \
+    OP " %7, %7, %8\n"
+
+template <int KIND>
+__global__ void __launch_bounds__(256) valu_rate_kernel(double *out, int iters, double seed) {
+    double a0 = seed, a1 = seed * 2, a2 = seed * 3, a3 = seed * 4, a4 = seed * 5, a5 = seed * 6, a6 = seed * 7,
+           a7 = seed * 8;
+    const double c = 1.0 - 1e-9;
+    for (int it = 0; it < iters; it++) {
+        if (KIND == LOKI_RATE_MUL_F64)
+            asm volatile(LOKI_REP16("v_mul_f64")
+                         : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)
+                         : "v"(c));
+        if (KIND == LOKI_RATE_ADD_F64)
+            asm volatile(LOKI_REP16("v_add_f64")
+                         : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)
+                         : "v"(c));
+        if (KIND == LOKI_RATE_MAX_F64)
+            asm volatile(LOKI_REP16("v_max_f64")
+                         : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)
+                         : "v"(c));
+        if (KIND == LOKI_RATE_SEARCH_MIX)  // the inner loop of the search: multiply, add, running maximum
+            asm volatile(
+                "v_mul_f64 %0, %4, %8\n v_add_f64 %0, %0, %5\n v_max_f64 %7, %7, %0\n"
+                "v_mul_f64 %1, %4, %8\n v_add_f64 %1, %1, %5\n v_max_f64 %7, %7, %1\n"
+                "v_mul_f64 %2, %4, %8\n v_add_f64 %2, %2, %5\n v_max_f64 %7, %7, %2\n"
+                "v_mul_f64 %3, %4, %8\n v_add_f64 %3, %3, %5\n v_max_f64 %7, %7, %3\n"
+                "v_mul_f64 %0, %6, %8\n v_add_f64 %0, %0, %5\n v_max_f64 %7, %7, %0\n"
+                "v_mul_f64 %1, %6, %8\n"
+                : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)
+                : "v"(c));
+        if (KIND == LOKI_RATE_ADD_U32) {
+            int x0 = it, x1 = it + 1, x2 = it + 2, x3 = it + 3;
+            asm volatile(
+                "v_add_u32 %0, %0, %4\n v_add_u32 %1, %1, %4\n v_add_u32 %2, %2, %4\n v_add_u32 %3, %3, %4\n"
+                "v_add_u32 %0, %0, %4\n v_add_u32 %1, %1, %4\n v_add_u32 %2, %2, %4\n v_add_u32 %3, %3, %4\n"
+                "v_add_u32 %0, %0, %4\n v_add_u32 %1, %1, %4\n v_add_u32 %2, %2, %4\n v_add_u32 %3, %3, %4\n"
+                "v_add_u32 %0, %0, %4\n v_add_u32 %1, %1, %4\n v_add_u32 %2, %2, %4\n v_add_u32 %3, %3, %4\n"
+                : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+                : "v"(it));
+            a0 += x0 + x1 + x2 + x3;
+        }
+    }
+    out[blockIdx.x * 256 + threadIdx.x] = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7;
+}
+
+}  // namespace
+
+hipError_t launch_valu_rate(int kind, double *out, int blocks, int iters, hipStream_t stream) {
+    const dim3 grid(blocks), block(256);
+    switch (kind) {
+        case LOKI_RATE_MUL_F64: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_MUL_F64>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_ADD_F64: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_ADD_F64>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_MAX_F64: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_MAX_F64>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_SEARCH_MIX: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_SEARCH_MIX>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_ADD_U32: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_ADD_U32>, grid, block, 0, stream, out, iters, 0.5); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace loki

@@ -123,3 +123,10 @@ def test_many_demand_points_in_one_call():
     order = sorted(range(len(demands)), key=lambda i: demands[i])
     accs = [out[i].accuracy if out[i].status == 0 else -1.0 for i in order]
     assert all(a >= b for a, b in zip(accs, accs[1:]))
+
+
+def test_valu_rate_measurement_is_plausible():
+    nominal = 256 * 4 * 2.4e9 / 4          # wavefront instructions per second at one per SIMD per 4 cycles
+    for kind in binding.RATE_KINDS:
+        rate = binding.measure_valu_rate(kind)
+        assert 0.3 * nominal < rate < 1.05 * nominal, (kind, rate)
