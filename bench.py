@@ -136,7 +136,12 @@ def main() -> int:
                      stride=stride, threads=threads)
         dt = time.perf_counter() - t0
         done = (min(n, sample * stride) + stride - 1) // stride
+        t1 = time.perf_counter()
+        one = min(done, 1 << 23)
+        O.search(w.demand_mqps[0], w.workers, w.slo_us, w.comm_us, begin=0, end=one * stride, stride=stride, threads=1)
+        single = one / (time.perf_counter() - t1)
         out["cpu_baseline"] = {"value": done / dt, "unit": "candidates/s", "cores": threads, "kind": "oracle",
+                               "single_thread_value": single,
                                "sample": f"{done} candidates of demand point 0, every {stride}th index from 0, "
                                          f"plain per-index search, {dt:.1f} s",
                                "feasible_in_sample": int(b.n_feasible)}

@@ -210,12 +210,12 @@ def test_full_size_sampled_candidates_and_subranges(cfg):
     # (i) sampled candidates one by one; half of them near the winner so that feasible ones are hit
     for d in demands[:2]:
         win = P.alloc_search([d], w.workers, w.slo_us, w.comm_us)[0]
-        idxs = [rng.randrange(n) for _ in range(6000)]
+        idxs = [rng.randrange(n) for _ in range(25000)]
         if win.status == binding.LOKI_FOUND:
             e = O.eval(win.index, d, w.workers, w.slo_us, w.comm_us)
             assert e.infeasible == 0 and bits(e.accuracy) == bits(win.accuracy) and e.workers == win.workers_used
             digits_span = min(n, 1 << 20)
-            idxs += [(win.index // digits_span) * digits_span + rng.randrange(digits_span) for _ in range(6000)]
+            idxs += [(win.index // digits_span) * digits_span + rng.randrange(digits_span) for _ in range(25000)]
             idxs.append(win.index)
         got = P.alloc_eval(idxs, d, w.workers, w.slo_us, w.comm_us)
         n_feas = 0
