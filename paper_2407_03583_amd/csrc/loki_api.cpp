@@ -69,7 +69,6 @@ struct loki_problem {
     int32_t fanout_q4[kMaxTasks];
     int32_t depth[kMaxTasks];
     int32_t batch_size[kMaxTasks][kMaxBatches];
-    int64_t thr[kMaxTasks][kMaxVariants][kMaxBatches];  // unscaled
     int32_t voff[kMaxTasks];
     int32_t max_vf[kMaxTasks];  // largest variant factor of the task (4 without per-variant factors)
     uint64_t n_candidates;
@@ -365,7 +364,6 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
                 const int64_t lat = in->latency_us[t + k * nb + bi], thr = in->thr_mqps[t + k * nb + bi];
                 if (lat < 1 || lat > (int64_t(1) << 30) || thr < 0 || thr > (int64_t(1) << 40)) rc = LOKI_E_RANGE;
                 d.lat[i][k][bi] = lat;
-                p->thr[i][k][bi] = thr;
                 if (thr > (int64_t(1) << 54) / scale) rc = LOKI_E_RANGE;  // keeps 255 replicas * thr * scale below 2^63
                 d.thr_s[i][k][bi] = thr * scale;
             }
@@ -404,7 +402,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         d.n_lat0 = int32_t(lats.size());
         for (size_t q = 0; q < lats.size(); q++) d.lat0_sorted[q] = lats[q];
         d.sum_r0 = 0;
-        for (int k = 0; k < d.K[0]; k++) d.sum_r0 += int32_t(d.radix[0][k]) - 1;
+        for (int k = 0; k < d.K[0]; k++) d.sum_r0 += in->max_replicas[k];  // task 0's variants come first
     }
     d.n_paths = 0;
     for (int i = 0; i < n; i++) d.n_paths += d.is_leaf[i];
