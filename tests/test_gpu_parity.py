@@ -403,3 +403,20 @@ def test_plan_trace_follows_the_two_step_resource_manager():
     # a constant trace is its own estimate
     flat = P.plan_trace([77_777] * 5, 1, w.workers, w.slo_us)
     assert [s.estimate_mqps for s in flat] == [77_777] * 5
+
+
+def test_per_variant_factors_on_benchmark_profiles():
+    """Config 1 in full and a 2^26-plan slice of config 2, with r(i,k) growing with accuracy."""
+    for cfg, span in ((1, None), (2, 1 << 26)):
+        w = wl.config(cfg)
+        p = w.pipeline
+        p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]   # 0.75 .. 1.5
+        P, O = binding.Problem(p), oracle.Problem(p)
+        n = P.num_candidates()
+        d = w.demand_mqps[0] // 2
+        spans = [(0, n)] if span is None else [(0, span), (n // 2 - 12345, n // 2 - 12345 + span)]
+        for lo, hi in spans:
+            for flags in (0, TIE):
+                res = P.alloc_search([d], w.workers, w.slo_us, flags=flags, begin=lo, end=hi)[0]
+                ref = O.search(d, w.workers, w.slo_us, tie_index_only=bool(flags & TIE), begin=lo, end=hi)
+                check(res, ref, f"cfg{cfg} vf [{lo},{hi}) flags={flags}")
