@@ -87,8 +87,12 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        # LOKI_ORACLE_LIB: a test may point at a deliberately broken build of the checker to show
+        # that the pins notice (tests/test_oracle_mutants.py); otherwise the in-tree build is used
+        override = os.environ.get("LOKI_ORACLE_LIB")
+        if not override:
+            build()
+        L = C.CDLL(override or _LIB)
         P = C.POINTER(_Pipeline)
         L.lo_num_candidates.restype = C.c_uint64
         L.lo_num_candidates.argtypes = [P]

@@ -130,3 +130,20 @@ def test_valu_rate_measurement_is_plausible():
     for kind in binding.RATE_KINDS:
         rate = binding.measure_valu_rate(kind)
         assert 0.3 * nominal < rate < 1.05 * nominal, (kind, rate)
+
+
+def test_objective_operation_order_on_the_gpu():
+    """Cases where root-first and leaf-first products (and forward and reverse leaf sums) differ in the last bit."""
+    def simple(parent, accs):
+        n = len(accs)
+        return SimpleNamespace(n_tasks=n, parent=parent, fanout_q4=[4] * n, n_variants=[1] * n, n_batches=[1] * n,
+                               batch_size=[1] * n, max_replicas=[1] * n, acc_ppm=accs, latency_us=[1000] * n,
+                               thr_mqps=[10**9] * n)
+    for p in (simple([-1, 0, 1], [600000, 661725, 772830]), simple([-1, 0, 0, 0], [800000, 600000, 661725, 735795]),
+              simple([-1, 0, 1, 1, 0], [800000, 600000, 661725, 735795, 772830])):
+        P, O = binding.Problem(p), oracle.Problem(p)
+        ref = O.search(1000, 8, 100_000)
+        assert ref.found == 1
+        for flags in (0, LANE):
+            res = P.alloc_search([1000], 8, 100_000, flags=flags)[0]
+            assert agree(res, ref), (flags, res.as_tuple(), ref.as_tuple())

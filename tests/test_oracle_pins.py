@@ -555,3 +555,24 @@ def test_per_variant_batch_contains_the_per_task_plans():
         one_pv = SimpleNamespace(**vars(one), per_variant_batch=True)
         assert oracle.Problem(one).search(d, w.workers, w.slo_us).as_tuple() == \
             oracle.Problem(one_pv).search(d, w.workers, w.slo_us).as_tuple()
+
+
+# ---- the order of the fp64 operations of the objective (products root first, leaf sum in leaf order) -------------
+
+def test_objective_operation_order():
+    def chain_or_star(parent, accs):
+        n = len(accs)
+        return pipeline(n_tasks=n, parent=parent, fanout_q4=[4] * n, n_variants=[1] * n, n_batches=[1] * n,
+                        batch_size=[1] * n, max_replicas=[1] * n, acc_ppm=accs, latency_us=[1000] * n,
+                        thr_mqps=[10**9] * n)
+    # three-task chain: ((a0 * a1) * a2), which differs in the last bit from the leaf-first product
+    a = [600000, 661725, 772830]
+    f = [v / 1000000.0 for v in a]
+    assert (f[0] * f[1]) * f[2] != (f[2] * f[1]) * f[0]
+    b = oracle.Problem(chain_or_star([-1, 0, 1], a)).search(1000, 3, 100_000)
+    assert b.found == 1 and b.accuracy == ((f[0] * f[1]) * f[2]) / 1.0
+    # root with three leaves: ((r*l1 + r*l2) + r*l3) / 3, which differs from the reverse sum
+    r, l = 0.8, [0.6, 0.661725, 0.735795]
+    assert (r * l[0] + r * l[1]) + r * l[2] != (r * l[2] + r * l[1]) + r * l[0]
+    b = oracle.Problem(chain_or_star([-1, 0, 0, 0], [800000, 600000, 661725, 735795])).search(1000, 4, 100_000)
+    assert b.found == 1 and b.accuracy == ((r * l[0] + r * l[1]) + r * l[2]) / 3.0
