@@ -119,6 +119,24 @@ def main() -> int:
                      "frac": achieved / VALU_PEAK_TLANEOPS, "traffic": None,
                      "lane_ops_per_candidate": ops},
     }
+    # the other benchmark configurations, one timed blocking call each (context for `value`)
+    if not args.per_lane:
+        others = {}
+        for c in (1, 2, 3, 4, 5):
+            if c == args.config:
+                continue
+            wc = wl.config(c)
+            Pc = binding.Problem(wc.pipeline)
+            Pc.alloc_search(wc.demand_mqps, wc.workers, wc.slo_us, wc.comm_us)
+            t0 = time.perf_counter()
+            rc = Pc.alloc_search(wc.demand_mqps, wc.workers, wc.slo_us, wc.comm_us)
+            dt = time.perf_counter() - t0
+            ev = Pc.num_candidates() * len(wc.demand_mqps)
+            others[wc.name] = {"evaluations": ev, "ms_call": dt * 1e3, "ms_search_kernel": Pc.last_search_ms()[1],
+                               "candidates_per_s": ev / dt,
+                               "feasible_points": sum(1 for r in rc if r.status == binding.LOKI_FOUND),
+                               "feasible_fraction": sum(r.n_feasible for r in rc) / ev}
+        out["other_configs"] = others
     # what a dependency-free stream of the search's own instructions sustains on this GPU
     mix = binding.measure_valu_rate("search_mix")
     out["roofline"]["sustained_mix_Tlane_op_s"] = mix * 64 / 1e12
