@@ -102,6 +102,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2407_03583_amd.build` "
                                "(or __graft_entry__.build()) first; there is no fallback path")
+        # PyTorch owns the device memory and the stream this library works on, so its HIP runtime
+        # must be the one in the process: load it before the library pulls in another copy.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         P = C.c_void_p
         L.loki_problem_create.restype = C.c_int

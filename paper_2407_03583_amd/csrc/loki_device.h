@@ -68,7 +68,8 @@ struct MidVal {
 struct MidLim {
     int32_t w_rem;    // workers left for the last task; -1 if the shared part is already infeasible
     int32_t tl;       // latency left for the last task on its path
-    uint32_t cl_lo;   // first choice of the last task inside the index range
+    uint32_t cl_lo;   // first choice of the last task inside the index range; when the whole space is
+                      // searched: end (exclusive, tile relative) of the run this entry belongs to
     uint32_t cl_cnt;  // number of its choices inside the index range
 };
 

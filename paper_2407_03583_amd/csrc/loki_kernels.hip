@@ -602,7 +602,9 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             ul.tl = static_cast<int32_t>(tl);
             const int64_t wr = w_room - w0;
             ul.w_rem = (ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
-            ul.cl_lo = 0;
+            // without a range every choice of the last task is admissible and the slot carries the end of
+            // the entry's run instead (tile relative; a run may go on beyond the tile)
+            ul.cl_lo = n >= 2 ? run_end[tile_base + e] - tile_base : e + 1;
             ul.cl_cnt = CL;
             if (RANGE) {
                 const uint64_t base = base_f + cM;  // index of the plan with the last task's choice 0
@@ -623,14 +625,23 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         const uint32_t e_hi = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * (midpart + 1) / mid_split);
         uint32_t fcount = 0;  // feasible plans of this item seen by this wavefront (< 2^20)
         uint32_t e = e_lo;
+        // the limits and the first record of a run are fetched during the run before it
+        MidLim ul_ahead = sLim[e_lo < e_hi ? e_lo : 0];
+        MidVal u_ahead = sVal[e_lo < e_hi ? e_lo : 0];
         while (e < e_hi) {
             // ---- start of a run: masks of the S*64 plans, valid for every record of the run
+            const MidLim ul = ul_ahead;
             uint32_t run_hi = e + 1;
-            if (!RANGE && n >= 2) {
-                run_hi = uni(run_end[tile_base + e]) - tile_base;  // a run may end beyond this wavefront's part
+            if (!RANGE) {
+                run_hi = uni(ul.cl_lo);  // end of the run; it may lie beyond this wavefront's part
                 if (run_hi > e_hi) run_hi = e_hi;
             }
-            const MidLim ul = sLim[e];
+            MidVal uA = u_ahead;
+            {
+                const uint32_t e_next = run_hi < e_hi ? run_hi : e;
+                ul_ahead = sLim[e_next];
+                u_ahead = sVal[e_next];
+            }
             uint64_t fm[S];
             int32_t amh[S];  // high word of the accuracy, or of a huge negative number where the plan is infeasible
             uint32_t run_feas = 0;
@@ -678,7 +689,10 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                             const double tprod = u.pre * a[s];
                             double key = HAS_PRESUM ? u.presum + tprod : tprod;
                             if (DIVIDE) key = key / npd;
-                            if (((fm[s] >> lane) & 1) && key >= bsum) {
+                            // which lanes have a feasible plan here that reaches their best; usually none
+                            const uint64_t hit = fm[s] & __builtin_amdgcn_ballot_w64(key >= bsum);
+                            if (hit == 0) continue;
+                            if ((hit >> lane) & 1) {
                                 const uint32_t cL = cl + s * 64;
                                 const int32_t wt = w_out + w[s];
                                 bool win = key > bsum;
@@ -698,7 +712,6 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                 }
             };
             // two records in flight: the next one is fetched while the current one is used
-            MidVal uA = sVal[e];
             while (true) {
                 const uint32_t e1 = e + 1;
                 const bool has1 = e1 < run_hi;
