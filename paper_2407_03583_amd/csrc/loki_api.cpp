@@ -232,7 +232,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         const uint64_t want = (items + kBlockThreads - 1) / kBlockThreads;
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
         if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
-        LOKI_HIP(launch_per_lane_search(A, stream));
+        LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, stream));
     } else {
         const uint32_t CL = p->dev.C[L];
         const int slots = CL >= 512 ? 8 : 4;
@@ -344,6 +344,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
             }
             d.radix[i][k] = d.pv_batch ? 1u + uint32_t(R) * uint32_t(nb) : uint32_t(R) + 1;
             d.magic[i][k] = ((uint64_t(1) << 36) + d.radix[i][k] - 1) / d.radix[i][k];
+            d.magic32[i][k] = d.radix[i][k] == 1 ? 0u : uint32_t(((uint64_t(1) << 32) + d.radix[i][k] - 1) / d.radix[i][k]);
             d.acc[i][k] = acc;
             d.vf[i][k] = 4;
             if (in->variant_factor_q4) {

@@ -26,6 +26,7 @@ struct DevProblem {
     int32_t nb[kMaxTasks];
     uint32_t C[kMaxTasks];                  // choices per task
     uint32_t radix[kMaxTasks][kMaxVariants];  // R(i,k)+1, or 1+R(i,k)*|B_i| with per-variant batch sizes
+    uint32_t magic32[kMaxTasks][kMaxVariants];  // ceil(2^32 / radix): umulhi(c, magic32) = c / radix for c * radix < 2^32
     int32_t order[kMaxTasks][kMaxVariants];   // route order (accuracy descending, index ascending) -> variant
     int32_t acc[kMaxTasks][kMaxVariants];     // ppm, by variant
     uint32_t table_off[kMaxTasks];          // first record of task i in a per-demand task table

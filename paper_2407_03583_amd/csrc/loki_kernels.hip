@@ -5,7 +5,8 @@
 // conventions are stated in include/loki_alloc.h.
 //
 // Two ways to cover the plan space, with identical results:
-//  * per-lane: every lane decodes one index and scores the whole plan;
+//  * per-lane: a lane scores whole plans from their digits (all tasks but the last once per
+//    strip of the last task's choices, then the last task and the plan per step);
 //  * tabulated (default): a plan's score separates into a part per task that
 //    depends on that task's digits only (replicas, largest latency in use,
 //    traffic-weighted accuracy) and a cheap combination (worker sum, path
@@ -100,17 +101,21 @@ struct TaskOut {
 // Decode choice c of task i (variant 0 least significant; the batch digit on top, or a batch
 // position inside every variant's digit) and fill the hosted variants most accurate first
 // (eq. (2), Algorithm 1's fill rule).
+// PV: a batch size per hosted variant; VF: per-variant multiplicative factors.
+template <bool PV, bool VF>
 __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o) {
     const int K = P->K[i];
-    const bool pv = P->pv_batch != 0;
+    constexpr bool pv = PV;
     const uint32_t nb = static_cast<uint32_t>(P->nb[i]);
     uint64_t digits = 0;  // replicas, 8 bits per variant
     uint32_t betas = 0;   // batch position, 4 bits per variant (per-variant batch sizes only)
     int32_t w = 0;
     for (int k = 0; k < K; k++) {
         const uint32_t radix = P->radix[i][k];
-        // c * radix <= 2^36 (checked at problem creation), so the multiply-shift quotient is exact
-        const uint32_t q = static_cast<uint32_t>((static_cast<uint64_t>(c) * P->magic[i][k]) >> 36);
+        // exact quotients by multiply-shift: c * radix < 2^32 with one batch size per task (radix <= 256),
+        // c * radix <= 2^36 otherwise (both checked at problem creation)
+        const uint32_t q = pv ? static_cast<uint32_t>((static_cast<uint64_t>(c) * P->magic[i][k]) >> 36)
+                              : (radix == 1 ? c : __umulhi(c, P->magic32[i][k]));
         const uint32_t g = c - q * radix;
         c = q;
         uint32_t x = g;
@@ -126,7 +131,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     const uint32_t beta_task = c;
     int64_t rem = Dn, maxlat = 0, weighted = 0, outflow = 0;
     int32_t any = 0, first_acc = 0;
-    const bool has_vf = P->has_vf != 0;
+    constexpr bool has_vf = VF;
     for (int r = 0; r < K; r++) {
         const int k = P->order[i][r];
         const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
@@ -151,6 +156,17 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     o.weighted = weighted;
     o.first_acc = first_acc;
     o.outflow = outflow;
+}
+
+// The same with the two switches read from the problem (kernels that are not time critical).
+__device__ __forceinline__ void eval_task_any(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o) {
+    if (P->pv_batch) {
+        if (P->has_vf) eval_task<true, true>(P, i, c, Dn, o);
+        else eval_task<true, false>(P, i, c, Dn, o);
+    } else {
+        if (P->has_vf) eval_task<false, true>(P, i, c, Dn, o);
+        else eval_task<false, false>(P, i, c, Dn, o);
+    }
 }
 
 // One correctly rounded fp64 division of two exactly converted integers (< 2^53).
@@ -184,7 +200,7 @@ __device__ __forceinline__ void eval_plan(const DevProblem *P, const uint32_t (&
             int64_t dn = Dn[i];
             if (has_vf && i > 0) dn = pick_below(out, par, i) * static_cast<int64_t>(P->fanout[i]);
             TaskOut o;
-            eval_task(P, i, c[i], dn, o);
+            eval_task_any(P, i, c[i], dn, o);
             out[i] = o.outflow;
             workers += o.w;
             if (!o.any) mask |= kBadEmpty;
@@ -323,7 +339,7 @@ __global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A)
     const uint32_t c = t - sP.table_off[i];
     const int64_t Dn = A.Dn[static_cast<size_t>(m) * kMaxTasks + i];
     TaskOut o;
-    eval_task(&sP, i, c, Dn, o);
+    eval_task_any(&sP, i, c, Dn, o);
     TaskRec rec;
     rec.a = task_accuracy(o, Dn);
     rec.w = o.w;
@@ -407,7 +423,7 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // Work item = (group of chunks of the last task's choices, combination f of the
 // tasks strictly between the first and the last, tile of the first task's choices
 // in run order).  A wavefront keeps S*64 records of the last task in registers;
-// the block builds the MidRec of every first-task choice in the tile once, then
+// the block builds the MidVal/MidLim of every first-task choice in the tile once, then
 // each wavefront walks its part of the tile.  Per run of equal (w_rem, tl) it
 // takes the feasibility of its S*64 plans once (eq. (3), eq. (7)); per record it
 // then only forms the S*64 objectives (one fp64 multiply, one add each), keeps
@@ -765,6 +781,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 // and then walks the strip, scoring the last task and finishing the plan per step.
 constexpr uint32_t kStrip = 64;
 
+template <bool PV, bool VF>
 __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchArgs A) {
     __shared__ DevProblem sP;
     __shared__ BestRec sBest[kWavesPerBlock];
@@ -773,7 +790,7 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
     const DevProblem *P = &sP;
     const int m = blockIdx.y;
     const int n = P->n_tasks, L = n - 1;
-    const bool has_vf = P->has_vf != 0;
+    constexpr bool has_vf = VF;
     const bool tie_index_only = A.tie_index_only != 0;
     const uint64_t lanes = static_cast<uint64_t>(gridDim.x) * kBlockThreads;
     const uint64_t strideL = P->stride[L];  // number of choice combinations of all other tasks
@@ -821,7 +838,7 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
                 int64_t dn = Dn[i];
                 if (has_vf && i > 0) dn = pick_below(out, par, i) * static_cast<int64_t>(P->fanout[i]);
                 TaskOut t;
-                eval_task(P, i, ci, dn, t);
+                eval_task<PV, VF>(P, i, ci, dn, t);
                 out[i] = t.outflow;
                 workers0 += t.w;
                 if (!t.any) mask0 |= kBadEmpty;
@@ -856,7 +873,7 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
             const uint64_t idx = o + strideL * cL;
             if (idx < A.begin || idx >= A.end) continue;
             TaskOut t;
-            eval_task(P, L, cL, dnL, t);
+            eval_task<PV, VF>(P, L, cL, dnL, t);
             uint32_t mask = mask0;
             const int32_t workers = workers0 + t.w;
             if (!t.any) mask |= kBadEmpty;
@@ -1060,9 +1077,15 @@ hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool 
     return launch_combine_s<4>(A, has_presum, divide, range, stream);
 }
 
-hipError_t launch_per_lane_search(const SearchArgs &A, hipStream_t stream) {
+hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
-    hipLaunchKernelGGL(per_lane_search_kernel, grid, block, 0, stream, A);
+    if (pv_batch) {
+        if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<true, true>), grid, block, 0, stream, A);
+        else hipLaunchKernelGGL((per_lane_search_kernel<true, false>), grid, block, 0, stream, A);
+    } else {
+        if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<false, true>), grid, block, 0, stream, A);
+        else hipLaunchKernelGGL((per_lane_search_kernel<false, false>), grid, block, 0, stream, A);
+    }
     return hipGetLastError();
 }
 

@@ -12,7 +12,7 @@ hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStrea
 hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool divide, bool range,
                           hipStream_t stream);
-hipError_t launch_per_lane_search(const SearchArgs &A, hipStream_t stream);
+hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, hipStream_t stream);
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_eval(const EvalArgs &A, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &A, hipStream_t stream);
