@@ -23,7 +23,11 @@ static_assert(sizeof(loki_result_t) == 32 && sizeof(loki_eval_t) == 16 && sizeof
 
 namespace {
 
-constexpr uint32_t kTargetBlocks = 2048;  // about 8 blocks per compute unit
+// Blocks per launch: far more than the 1024 that are resident at once, so that the hardware's own
+// block dispatch evens out compute units and demand points that finish at different times.
+constexpr uint32_t kTargetBlocks = 32768;
+constexpr uint32_t kMinTile = 256;     // shortest tile of root-task choices per work item
+constexpr uint64_t kFewItems = 8192;   // below this many work items per launch the tile is shortened
 constexpr int64_t kTwo53 = int64_t(1) << 53;
 constexpr size_t kAlign = 256;
 
@@ -242,7 +246,8 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         for (int j = 1; j < L; j++) F *= p->dev.C[j];
         const uint32_t mid_count = n >= 2 ? p->dev.C[0] : 1u;
         A.far_count = F;
-        A.mid_tiles = (mid_count + kMidTile - 1) / kMidTile;
+        A.tile_len = kMidTile;
+        A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
         if (span == 0) {
             A.cl_first = 0;
             A.chunk_groups = 0;
@@ -257,6 +262,13 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
             while (A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
             A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
             A.items = uint64_t(A.chunk_groups) * F * A.mid_tiles;
+            // a search with few work items gets shorter ones: blocks that meet many feasible plans
+            // run long, and only spare items let the others take over the rest
+            while (A.tile_len > kMinTile && A.items * n_demand < kFewItems) {
+                A.tile_len /= 2;
+                A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
+                A.items = uint64_t(A.chunk_groups) * F * A.mid_tiles;
+            }
         }
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(A.items, 1), max_bpm));
         if (A.items > (uint64_t(1) << 62) / A.blocks_per_m) A.blocks_per_m = 1;  // keep items*block in 64 bits

@@ -12,7 +12,7 @@ constexpr int kMaxVariants = 8;
 constexpr int kMaxBatches = 8;
 constexpr int kBlockThreads = 256;          // 4 wavefronts of 64
 constexpr int kWavesPerBlock = kBlockThreads / 64;
-constexpr int kMidTile = 1024;              // root-task choices staged in LDS per work item
+constexpr int kMidTile = 1024;              // most root-task choices staged in LDS per work item
 constexpr int32_t kNever = 0x7fffffff;      // latency marker: this choice can never be part of a feasible plan
 
 // Per-handle constants (Table 1 inputs after validation, plus derived radices).
@@ -96,7 +96,8 @@ struct SearchArgs {
     uint64_t items;         // work items per demand point
     uint32_t cl_first;      // first choice of the last task touched by the range
     uint32_t chunk_groups;  // groups of chunks of the last task
-    uint32_t mid_tiles;
+    uint32_t tile_len;      // root-task choices per work item, at most kMidTile
+    uint32_t mid_tiles;     // ceil(C_0 / tile_len)
     uint32_t cpb;           // chunks handled side by side in a block (1, 2 or 4)
     int32_t W;
     int32_t M;

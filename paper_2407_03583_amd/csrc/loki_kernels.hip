@@ -573,9 +573,8 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         }
         const int64_t w_room = static_cast<int64_t>(W) - w_far;
 
-        const uint32_t tile_base = r * kMidTile;
-        const uint32_t cnt = mid_count - tile_base < static_cast<uint32_t>(kMidTile) ? mid_count - tile_base
-                                                                                      : static_cast<uint32_t>(kMidTile);
+        const uint32_t tile_base = r * A.tile_len;
+        const uint32_t cnt = mid_count - tile_base < A.tile_len ? mid_count - tile_base : A.tile_len;
         const uint64_t base_f = static_cast<uint64_t>(C0) * f;  // index contribution of the tasks in between
 
         __syncthreads();  // the previous item's tile is no longer being read

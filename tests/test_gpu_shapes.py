@@ -111,6 +111,29 @@ def test_deep_chain_of_eight_tasks():
             assert agree(res, ref), (demand, W, flags, res.as_tuple(), ref.as_tuple())
 
 
+def test_every_tile_length_with_a_ragged_last_tile():
+    """The launch shortens the tile of root-task choices when a call has few work items.  One chain,
+    root with 7 x 10 x 9 x 3 = 1,890 choices, searched for 1, 10 and 24 demand points: the three calls
+    land on tiles of 256, 512 and 1,024 entries (the library's thresholds), each with several tiles and
+    a last tile that is not full."""
+    rng = random.Random(33)
+    a0, l0, t0 = profile(rng, 3, [1, 2, 4])
+    a1, l1, t1 = profile(rng, 2, [2, 8])
+    a2, l2, t2 = profile(rng, 2, [4])
+    p = SimpleNamespace(n_tasks=3, parent=[-1, 0, 1], fanout_q4=[4, 5, 6], n_variants=[3, 2, 2],
+                        n_batches=[3, 2, 1], batch_size=[1, 2, 4, 2, 8, 4], max_replicas=[6, 9, 8, 11, 11, 5, 6],
+                        acc_ppm=a0 + a1 + a2, latency_us=l0 + l1 + l2, thr_mqps=t0 + t1 + t2)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    assert P.num_candidates() == (7 * 10 * 9 * 3) * (12 * 12 * 2) * (6 * 7)   # root: 1,890 choices
+    for n_points in (1, 10, 24):
+        demands = [rng.randint(5_000, 700_000) for _ in range(n_points)]
+        for flags in (0, TIE):
+            out = P.alloc_search(demands, 40, 300_000, flags=flags)
+            for d, res in list(zip(demands, out))[:: max(1, n_points // 4)]:
+                ref = O.search_tabulated(d, 40, 300_000, tie_index_only=bool(flags & TIE))
+                assert agree(res, ref), (n_points, d, flags, res.as_tuple(), ref.as_tuple())
+
+
 def test_many_demand_points_in_one_call():
     w = wl.config(1)
     P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
