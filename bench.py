@@ -46,6 +46,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
     ap.add_argument("--per-lane", action="store_true", help="time the kernel that scores whole plans per lane")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the other configurations and the instruction-rate probes (profiling runs: "
+                         "only the timed workload's kernels are launched)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (more GPUs would each take an index range); "
@@ -120,7 +123,7 @@ def main() -> int:
                      "lane_ops_per_candidate": ops},
     }
     # the other benchmark configurations, one timed blocking call each (context for `value`)
-    if not args.per_lane:
+    if not args.per_lane and not args.no_context:
         others = {}
         for c in (1, 2, 3, 4, 5):
             if c == args.config:
@@ -138,9 +141,10 @@ def main() -> int:
                                "feasible_fraction": sum(r.n_feasible for r in rc) / ev}
         out["other_configs"] = others
     # what a dependency-free stream of the search's own instructions sustains on this GPU
-    mix = binding.measure_valu_rate("search_mix")
-    out["roofline"]["sustained_mix_Tlane_op_s"] = mix * 64 / 1e12
-    out["roofline"]["sustained_u32_Tlane_op_s"] = binding.measure_valu_rate("v_add_u32") * 64 / 1e12
+    if not args.no_context:
+        mix = binding.measure_valu_rate("search_mix")
+        out["roofline"]["sustained_mix_Tlane_op_s"] = mix * 64 / 1e12
+        out["roofline"]["sustained_u32_Tlane_op_s"] = binding.measure_valu_rate("v_add_u32") * 64 / 1e12
     if not args.no_cpu_baseline:
         import oracle
         O = oracle.Problem(w.pipeline)

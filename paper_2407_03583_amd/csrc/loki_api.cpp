@@ -716,8 +716,9 @@ int loki_measure_valu_rate(int kind, void *d_workspace, size_t workspace_bytes, 
                            double *wave_instructions_per_second) {
     if (!d_workspace || !wave_instructions_per_second) return LOKI_E_NULL;
     if (kind < 0 || kind > LOKI_RATE_ADD_U32) return LOKI_E_ARG;
-    const int blocks = 2048, iters = 100000;  // 8 blocks of 4 wavefronts per compute unit on 256 CUs
-    if (workspace_bytes < size_t(blocks) * 256 * sizeof(double) || (reinterpret_cast<uintptr_t>(d_workspace) % 8) != 0)
+    // many short blocks: the block dispatcher then keeps every SIMD full to the end, as in the search
+    const int blocks = 32768, iters = 6250, sink_blocks = 2048;
+    if (workspace_bytes < size_t(sink_blocks) * 256 * sizeof(double) || (reinterpret_cast<uintptr_t>(d_workspace) % 8) != 0)
         return LOKI_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipEvent_t e0 = nullptr, e1 = nullptr;
