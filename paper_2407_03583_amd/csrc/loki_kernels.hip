@@ -432,7 +432,7 @@ template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE>
 __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4))) combine_kernel(SearchArgs A) {
     constexpr uint32_t kHeadBytes = offsetof(DevProblem, lat);
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
-    __shared__ MidVal sVal[kMidTile];
+    __shared__ MidVal sVal[kMidTile + 2];  // two spare entries: the record fetch runs ahead of the run's end
     __shared__ MidLim sLim[kMidTile];
     __shared__ uint32_t sChoice[kMidTile];  // first-task choice of each tile entry (cold path only)
     __shared__ BestRec sBest[kWavesPerBlock];
@@ -660,11 +660,18 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             uint64_t fm[S];
             int32_t amh[S];  // high word of the accuracy, or of a huge negative number where the plan is infeasible
             uint32_t run_feas = 0;
+            const int32_t w_rem = uni(ul.w_rem), tl = uni(ul.tl);  // the same in every lane: scalar operands
 #pragma unroll
             for (int s = 0; s < S; s++) {
-                bool ok = (w[s] <= ul.w_rem) & (lat[s] <= ul.tl);
-                if (RANGE) ok = ok & ((cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt);
-                fm[s] = __builtin_amdgcn_ballot_w64(ok);
+                // one ballot per compare: the masks then come straight from the compare results
+                const bool ok_w = w[s] <= w_rem, ok_l = lat[s] <= tl;
+                fm[s] = __builtin_amdgcn_ballot_w64(ok_w) & __builtin_amdgcn_ballot_w64(ok_l);
+                bool ok = ok_w & ok_l;
+                if (RANGE) {
+                    const bool ok_r = (cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt;
+                    fm[s] &= __builtin_amdgcn_ballot_w64(ok_r);
+                    ok = ok & ok_r;
+                }
                 run_feas += static_cast<uint32_t>(__builtin_popcountll(fm[s]));
                 amh[s] = ok ? __double2hiint(a[s]) : static_cast<int32_t>(0xFFE00000u);
             }
@@ -689,7 +696,8 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     uint32_t cl = cl0;
                     asm volatile("" : "+v"(cl));
                     const uint64_t low = base_f + sChoice[ee];  // index of the plan without the last task's part
-                    const int32_t w_out = W - ul.w_rem;
+                    int32_t w_out = W - w_rem;
+                    asm volatile("" : "+s"(w_out));  // keeps the sums with w[] below out of the run start
                     bool maybe = kmax > bsum;
                     const bool low_wins = low < blow;
                     if (tie_index_only) {
@@ -726,19 +734,22 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     }
                 }
             };
-            // two records in flight: the next one is fetched while the current one is used
+            // two records in flight: the next one is fetched while the current one is used.  The fetch
+            // may reach up to two entries past the run (the tile arrays are padded for that); what it
+            // brings is then not used.  The entry's byte offset lives in a vector register, so that the
+            // reads take their distance as an immediate and one add per pair moves them on.
+            uint32_t eb = e * static_cast<uint32_t>(sizeof(MidVal));
+            asm volatile("" : "+v"(eb));
+            const char *val_bytes = reinterpret_cast<const char *>(sVal);
             while (true) {
-                const uint32_t e1 = e + 1;
-                const bool has1 = e1 < run_hi;
-                const MidVal uB = sVal[has1 ? e1 : e];
+                const MidVal uB = *reinterpret_cast<const MidVal *>(val_bytes + eb + sizeof(MidVal));
                 score(uA, e);
-                if (!has1) break;
-                const uint32_t e2 = e1 + 1;
-                const bool has2 = e2 < run_hi;
-                uA = sVal[has2 ? e2 : e1];
-                score(uB, e1);
-                if (!has2) break;
-                e = e2;
+                if (e + 1 >= run_hi) break;
+                uA = *reinterpret_cast<const MidVal *>(val_bytes + eb + 2 * sizeof(MidVal));
+                score(uB, e + 1);
+                if (e + 2 >= run_hi) break;
+                e += 2;
+                eb += 2 * static_cast<uint32_t>(sizeof(MidVal));
             }
             e = run_hi;
         }
