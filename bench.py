@@ -8,6 +8,7 @@ Prints one JSON line.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -36,6 +37,29 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
         return (1 if n_tasks >= 2 else 0) + (1 if n_paths > 1 else 0) + 1
     per_task = [20 * k + 30 for k in pipeline.n_variants]
     return per_task[-1] + 50 + sum(per_task[:-1]) / 64.0
+
+
+# HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
+# factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
+# They hold for the kernel sources they were taken with; with other sources `traffic` is null.
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (445 + 1024) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (274 + 1024) * 1024}
+TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
+TRAFFIC_SOURCES_SHA256 = "92dfaa5f39dcdba996a3cc5a3689e00356e5137513ce7655ff73292853d3886e"
+
+
+def measured_traffic(workload: str, kernel: str):
+    h = hashlib.sha256()
+    csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2407_03583_amd", "csrc")
+    try:
+        for f in TRAFFIC_SOURCES:
+            with open(os.path.join(csrc, f), "rb") as fh:
+                h.update(fh.read())
+    except OSError:
+        return None
+    if h.hexdigest() != TRAFFIC_SOURCES_SHA256:
+        return None
+    return MEASURED_TRAFFIC_BYTES.get((workload, kernel))
 
 
 def main() -> int:
@@ -119,7 +143,8 @@ def main() -> int:
         "kernel_ms": {"task_tables": sum(k[0] for k in kernel_ms) / len(kernel_ms), "search": main_ms,
                       "final_merge": sum(k[2] for k in kernel_ms) / len(kernel_ms)},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
-                     "frac": achieved / VALU_PEAK_TLANEOPS, "traffic": None,
+                     "frac": achieved / VALU_PEAK_TLANEOPS,
+                     "traffic": measured_traffic(w.name, "per_lane" if args.per_lane else "tabulated"),
                      "lane_ops_per_candidate": ops},
     }
     # the other benchmark configurations, one timed blocking call each (context for `value`)
