@@ -46,7 +46,8 @@ class _Pipeline(C.Structure):
                 ("latency_us", C.POINTER(C.c_int64)),
                 ("thr_mqps", C.POINTER(C.c_int64)),
                 ("variant_factor_q4", C.POINTER(C.c_int32)),
-                ("per_variant_batch", C.c_int32)]
+                ("per_variant_batch", C.c_int32),
+                ("path_acc_ppm", C.POINTER(C.c_int32))]
 
 
 class EvalOut(C.Structure):
@@ -142,6 +143,9 @@ class Problem:
         vf = getattr(pipeline, "variant_factor_q4", None)
         if vf is not None:
             self._keep["variant_factor_q4"] = _arr(C.c_int32, vf)
+        pt = getattr(pipeline, "path_acc_ppm", None)
+        if pt is not None:
+            self._keep["path_acc_ppm"] = _arr(C.c_int32, pt)
         k = self._keep
         self.c = _Pipeline(self.n_tasks,
                            C.cast(k["parent"], C.POINTER(C.c_int32)),
@@ -155,7 +159,9 @@ class Problem:
                            C.cast(k["thr_mqps"], C.POINTER(C.c_int64)),
                            C.cast(k["variant_factor_q4"], C.POINTER(C.c_int32)) if vf is not None
                            else C.POINTER(C.c_int32)(),
-                           1 if getattr(pipeline, "per_variant_batch", False) else 0)
+                           1 if getattr(pipeline, "per_variant_batch", False) else 0,
+                           C.cast(k["path_acc_ppm"], C.POINTER(C.c_int32)) if pt is not None
+                           else C.POINTER(C.c_int32)())
         self.per_variant_batch = bool(getattr(pipeline, "per_variant_batch", False))
 
     def num_candidates(self) -> int:

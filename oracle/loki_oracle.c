@@ -290,6 +290,94 @@ static void pipeline_eval(const lo_pipeline *p, const lo_task_t *t, const int64_
     out->accuracy = sum / (double)n_paths;
 }
 
+/* ---- objective from profiled path accuracies: sum_p c(p) * A-hat(p) (Section 4.1 "Accuracy") ----
+ * Per root-to-leaf task path, p runs over the combinations of one variant per task.  c(p) is the
+ * product of: the frontend's split over the root's variants, and per edge the probability that the
+ * routing table of the upstream variant (Algorithm 1, lo_route_table) sends a request to the
+ * downstream variant.  An upstream variant without traffic (zero demand) has no table; its requests,
+ * if there were any, would go to the first hosted downstream variant in route order, the same
+ * convention as for a task's accuracy at zero demand.
+ * fp64 order: c(p) is multiplied up root first, then times A-hat(p)/10^6; the terms of a task path
+ * are added up with the root's variants outermost, every level in route order (accuracy descending);
+ * the task paths' sums are added in leaf order and divided by the number of task paths. */
+typedef struct {
+    const lo_pipeline *p;
+    const lo_layout *L;
+    const lo_route_t *r;
+    const int32_t *x;     /* replicas, concat over (task, variant) */
+    const int *path;      /* tasks root..leaf */
+    int len;
+    const int32_t *table; /* A-hat of this task path */
+    double sum;
+} lo_walk;
+
+static void path_walk(lo_walk *c, int depth, int prev_variant, double mass, uint64_t entry, uint64_t stride)
+{
+    const lo_pipeline *p = c->p;
+    int i = c->path[depth], K = p->n_variants[i];
+    int order[LO_MAX_VARIANTS];
+    route_order(p, c->L, i, order);
+    int first_hosted = -1;
+    for (int o = 0; o < K && first_hosted < 0; o++)
+        if (c->x[c->L->voff[i] + order[o]] > 0)
+            first_hosted = order[o];
+    int has_traffic = depth == 0 ? c->r->demand[0] > 0 : c->r->routed[c->path[depth - 1]][prev_variant] > 0;
+    for (int o = 0; o < K; o++) {
+        int k = order[o];
+        double share;
+        if (has_traffic)
+            share = depth == 0 ? c->r->prob[0][0][k] : c->r->prob[i][prev_variant][k];
+        else
+            share = k == first_hosted ? 1.0 : 0.0;
+        if (share == 0.0)
+            continue; /* no request takes this branch */
+        double m = depth == 0 ? share : mass * share;
+        uint64_t e = entry + (uint64_t)k * stride;
+        if (depth == c->len - 1)
+            c->sum = c->sum + m * ((double)c->table[e] / 1000000.0);
+        else
+            path_walk(c, depth + 1, k, m, e, stride * (uint64_t)K);
+    }
+}
+
+static double path_objective(const lo_pipeline *p, const lo_layout *L, uint64_t index, int64_t demand_mqps)
+{
+    lo_route_t r;
+    int32_t x[LO_MAX_TASKS * LO_MAX_VARIANTS], beta[LO_MAX_TASKS * LO_MAX_VARIANTS];
+    int n = p->n_tasks;
+    lo_route_table(p, index, demand_mqps, &r);
+    lo_decode(p, index, x, beta);
+    int is_leaf[LO_MAX_TASKS];
+    for (int i = 0; i < n; i++)
+        is_leaf[i] = 1;
+    for (int i = 1; i < n; i++)
+        is_leaf[p->parent[i]] = 0;
+    const int32_t *table = p->path_acc_ppm;
+    double total = 0.0;
+    int n_paths = 0;
+    for (int leaf = 0; leaf < n; leaf++) {
+        if (!is_leaf[leaf])
+            continue;
+        int rev[LO_MAX_TASKS], path[LO_MAX_TASKS], len = 0;
+        for (int i = leaf; i >= 0; i = p->parent[i])
+            rev[len++] = i;
+        uint64_t size = 1;
+        for (int s = 0; s < len; s++) {
+            path[s] = rev[len - 1 - s];
+            size *= (uint64_t)p->n_variants[path[s]];
+        }
+        lo_walk c = {p, L, &r, x, path, len, table, 0.0};
+        path_walk(&c, 0, 0, 0.0, 0, 1);
+        if (n_paths == 0)
+            total = c.sum;
+        else
+            total = total + c.sum;
+        n_paths++;
+        table += size;
+    }
+    return total / (double)n_paths;
+}
+
 void lo_eval(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, int32_t workers, int64_t slo_us,
              int64_t comm_us, lo_eval_t *out)
 {
@@ -309,6 +397,8 @@ void lo_eval(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, int32_t 
         task_eval(p, &L, i, x, beta, Dn[i], scale[i], &t[i], NULL);
     }
     pipeline_eval(p, t, Dn, workers, slo_us, comm_us, out);
+    if (p->path_acc_ppm && !out->infeasible)
+        out->accuracy = path_objective(p, &L, index, demand_mqps);
 }
 
 /* ---- the search: plain argmax ------------------------------------------------ */
@@ -403,7 +493,7 @@ void lo_search_tabulated(const lo_pipeline *p, int64_t demand_mqps, int32_t work
     lo_layout L;
     int64_t Dn[LO_MAX_TASKS], scale[LO_MAX_TASKS];
     lo_task_t *table[LO_MAX_TASKS];
-    if (p->variant_factor_q4) { /* a task's demand is not fixed: no table */
+    if (p->variant_factor_q4 || p->path_acc_ppm) { /* a task's demand is not fixed / the objective couples tasks: no table */
         lo_search(p, demand_mqps, workers, slo_us, comm_us, tie_index_only, index_begin, index_end, 1, n_threads, out);
         return;
     }

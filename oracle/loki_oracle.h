@@ -23,7 +23,13 @@
  *     the SLO halving and the communication-latency paragraph of Section 4.2),
  *   - pipeline accuracy = mean over root-to-leaf paths of the product of the
  *     tasks' traffic-weighted accuracies (Section 2.1's pipeline accuracy,
- *     eq. (12) objective).
+ *     eq. (12) objective); or, when profiled end-to-end accuracies of the
+ *     variant paths are given (A-hat(p) of Section 4.1 "Accuracy"), the mean
+ *     over root-to-leaf task paths of  sum_p c(p) * A-hat(p), where p runs
+ *     over the combinations of one variant per task of the path and c(p) is
+ *     the share of requests taking it: the frontend's split over the root's
+ *     variants times, per edge, the probability with which Algorithm 1's
+ *     routing table of the upstream variant picks the downstream variant.
  *   The search is the plain definition: evaluate every index, keep the best
  *   under (accuracy descending, workers ascending, index ascending), which is
  *   eq. (12) followed by eq. (11) as a tie-break.
@@ -72,6 +78,9 @@ typedef struct {
     int32_t per_variant_batch;   /* 0: one batch size per task.  1: y(i,k) of Section 4.1, a batch size per
                                     hosted variant; a variant's digit is 0 (not hosted) or
                                     1 + (replicas - 1) * |B_i| + batch position */
+    const int32_t *path_acc_ppm; /* NULL, or A-hat(p) in ppm: concat over the leaves in ascending task index;
+                                    a leaf's table has one entry per combination of variants of the tasks
+                                    root..leaf, entry = sum_j k_j * prod_{j'<j} K_j' (root least significant) */
 } lo_pipeline;
 
 typedef struct {

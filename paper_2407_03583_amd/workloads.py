@@ -83,6 +83,33 @@ class Pipeline:
     # True: every hosted variant has its own batch size, y(i,k) of Section 4.1; per variant the
     # digit is 0 (not hosted) or 1 + (replicas - 1) * |B_i| + batch position.
     per_variant_batch: bool = False
+    # optional: profiled end-to-end accuracy of every variant path (the paper's A-hat(p), Section 4.1
+    # "Accuracy"), in ppm.  Concatenated over the leaves in ascending task index; the table of a leaf has
+    # one entry per combination of variants of the tasks root..leaf, the root's variant least significant.
+    # None = the product of the single-model accuracies stands in for it.
+    path_acc_ppm: Optional[List[int]] = None
+
+    def leaf_paths(self) -> List[List[int]]:
+        """Task indices root..leaf for every leaf, leaves in ascending index."""
+        out = []
+        for leaf in range(self.n_tasks):
+            if leaf in self.parent:
+                continue
+            path, i = [], leaf
+            while i >= 0:
+                path.append(i)
+                i = self.parent[i]
+            out.append(path[::-1])
+        return out
+
+    def path_table_sizes(self) -> List[int]:
+        sizes = []
+        for path in self.leaf_paths():
+            n = 1
+            for i in path:
+                n *= self.n_variants[i]
+            sizes.append(n)
+        return sizes
 
     def choices_per_task(self) -> List[int]:
         out, v = [], 0
@@ -112,6 +139,9 @@ class Pipeline:
             h.update(",".join(str(int(v)) for v in self.variant_factor_q4).encode())
         if self.per_variant_batch:
             h.update(b"per_variant_batch")
+        if self.path_acc_ppm is not None:
+            h.update(b"path_acc_ppm")
+            h.update(",".join(str(int(v)) for v in self.path_acc_ppm).encode())
         return h.hexdigest()
 
 
@@ -207,9 +237,34 @@ def config(cfg: int, seed: int | None = None) -> Workload:
     raise ValueError(f"unknown config {cfg}")
 
 
+def draw_path_tables(p: Pipeline, rng: SplitMix64, spread_pct: int = 8) -> List[int]:
+    """Profiled end-to-end accuracies of all variant paths: what independent errors would give (the
+    product of the single-model accuracies, rounded down to a ppm) moved by a seeded relative deviation
+    of up to +-spread_pct percent, which stands for errors that compound or cancel along a path."""
+    voff, v = [], 0
+    for i in range(p.n_tasks):
+        voff.append(v)
+        v += p.n_variants[i]
+    out = []
+    for path in p.leaf_paths():
+        size = 1
+        for i in path:
+            size *= p.n_variants[i]
+        for e in range(size):
+            rest, num = e, 1
+            for i in path:
+                k = rest % p.n_variants[i]
+                rest //= p.n_variants[i]
+                num *= p.acc_ppm[voff[i] + k]
+            base = num // (10 ** (6 * (len(path) - 1)))
+            dev = rng.randint(-spread_pct * 100, spread_pct * 100)   # hundredths of a percent
+            out.append(max(0, min(1_000_000, base + base * dev // 10000)))
+    return out
+
+
 def random_small(seed: int, max_tasks: int = 3, max_variants: int = 3, max_replicas: int = 2,
                  max_batches: int = 3, max_candidates: int = 20000, variant_factors: bool = False,
-                 per_variant_batch: bool = False) -> Workload:
+                 per_variant_batch: bool = False, path_tables: bool = False) -> Workload:
     """A small random problem (ragged K_i, R_ik and |B_i|, random tree) for
     exhaustive cross-checks.  Demand, worker count and SLO are drawn so that a
     healthy share of candidates is feasible."""
@@ -244,6 +299,8 @@ def random_small(seed: int, max_tasks: int = 3, max_variants: int = 3, max_repli
     if variant_factors:
         # a more accurate variant tends to create more downstream work (Section 4.2): factor grows with accuracy
         p.variant_factor_q4 = [max(1, min(12, (a - 500000) // 60000 + rng.randint(0, 2))) for a in p.acc_ppm]
+    if path_tables:
+        p.path_acc_ppm = draw_path_tables(p, SplitMix64(seed ^ 0x0F1E_2D3C_4B5A_6978))
     demand = [0 if rng.randint(0, 9) == 0 else rng.randint(1_000, 400_000)]
     workers = rng.randint(1, 2 * n * max_replicas + 1)
     slo = rng.randint(40_000, 400_000)

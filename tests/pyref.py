@@ -139,6 +139,10 @@ def evaluate(p, index: int, demand_mqps: int, workers: int, slo_us: int, comm_us
         if room < 0 or sum(lat_task[i] for i in path) > room // 2:
             mask |= BAD_LATENCY
     out = dict(infeasible=mask, workers=used_workers, accuracy=0.0, task_lat=lat_task)
+    if mask == 0 and getattr(p, "path_acc_ppm", None) is not None:
+        out["exact"] = path_objective_exact(p, index, demand_mqps)
+        out["accuracy"] = float(out["exact"])   # within a few ulps of the checker's step-by-step fp64 value
+        return out
     if mask == 0:
         a = [float(f) for f in acc_task]  # one correct rounding each
         total = None
@@ -173,3 +177,96 @@ def search(p, demand_mqps: int, workers: int, slo_us: int, comm_us: int = 0, tie
     if best is None:
         return dict(found=0, index=(1 << 64) - 1, accuracy=0.0, workers=-1, n_feasible=0)
     return dict(found=1, index=best[1], accuracy=best[2], workers=best[3], n_feasible=n_feasible)
+
+
+def placement(p, index: int, demand_mqps: int):
+    """Where every task's requests sit, as intervals of the task's request stream in QPS: the stream is
+    handed to the hosted variants in order of accuracy (ties: lower index first), each taking what its
+    capacity allows (Algorithm 1).  Returns per task: demand, {variant: (start, end)} and, per variant,
+    the requests it creates per unit of child fan-out."""
+    tasks = _tables(p)
+    plan = decode(p, index)
+    per_variant = tasks[0]["variants"][0]["factor"] is not None
+    demand, spans, created = [], [], []
+    for i, task in enumerate(tasks):
+        xs, betas = plan[i]
+        if i == 0:
+            d = Fraction(demand_mqps, 1000)
+        else:
+            d = sum(created[task["parent"]].values(), Fraction(0)) * task["fan"]
+        hosted = sorted((k for k in range(len(xs)) if xs[k] > 0), key=lambda k: (-task["variants"][k]["acc"], k))
+        at, span, made = Fraction(0), {}, {}
+        for k in hosted:
+            var = task["variants"][k]
+            take = min(d - at, xs[k] * Fraction(var["thr"][betas[k]], 1000))
+            span[k] = (at, at + take)
+            made[k] = take * (var["factor"] if per_variant else 1)
+            at += take
+        demand.append(d)
+        spans.append(span)
+        created.append(made)
+    return tasks, plan, demand, spans, created
+
+
+def path_objective_exact(p, index: int, demand_mqps: int) -> Fraction:
+    """sum_p c(p) * A-hat(p), averaged over the root-to-leaf task paths, in exact arithmetic.
+
+    The requests a variant creates for a child occupy one interval of the child's request stream, the
+    upstream variants lined up by accuracy like the child's own variants; the share of an upstream
+    variant's requests that a downstream variant serves is the overlap of the two intervals over the
+    upstream interval's length.  (The checker instead replays Algorithm 1's sequential bookkeeping.)"""
+    tasks, plan, demand, spans, created = placement(p, index, demand_mqps)
+    leaves = [i for i in range(len(tasks)) if all(t["parent"] != i for t in tasks)]
+    table = list(p.path_acc_ppm)
+    offset = 0
+    total = Fraction(0)
+
+    def first_hosted(i):
+        xs = plan[i][0]
+        hosted = sorted((k for k in range(len(xs)) if xs[k] > 0), key=lambda k: (-tasks[i]["variants"][k]["acc"], k))
+        return hosted[0]
+
+    def split(i, upstream):
+        """Shares over task i's variants of the requests coming from `upstream` = (parent task, variant),
+        or from the frontend when upstream is None."""
+        if upstream is None:
+            lo, hi = Fraction(0), demand[0]
+        else:
+            par, kp = upstream
+            order = sorted(created[par], key=lambda k: (-tasks[par]["variants"][k]["acc"], k))
+            lo = sum((created[par][k] for k in order[:order.index(kp)]), Fraction(0)) * tasks[i]["fan"]
+            hi = lo + created[par][kp] * tasks[i]["fan"]
+        if hi == lo:
+            return {first_hosted(i): Fraction(1)}
+        shares = {}
+        for k, (a, b) in spans[i].items():
+            overlap = min(b, hi) - max(a, lo)
+            if overlap > 0:
+                shares[k] = overlap / (hi - lo)
+        return shares
+
+    for leaf in leaves:
+        path, i = [], leaf
+        while i >= 0:
+            path.append(i)
+            i = tasks[i]["parent"]
+        path = path[::-1]
+        sizes = [len(tasks[i]["variants"]) for i in path]
+
+        def walk(depth, upstream, mass, entry, stride):
+            i = path[depth]
+            acc = Fraction(0)
+            for k, share in split(i, upstream).items():
+                e = entry + k * stride
+                if depth == len(path) - 1:
+                    acc += mass * share * Fraction(table[offset + e], 1_000_000)
+                else:
+                    acc += walk(depth + 1, (i, k), mass * share, e, stride * sizes[depth])
+            return acc
+
+        total += walk(0, None, Fraction(1), 0, 1)
+        n = 1
+        for s_ in sizes:
+            n *= s_
+        offset += n
+    return total / len(leaves)

@@ -45,6 +45,16 @@ MUTANTS = [
     ("per-variant factor not applied", "t->outflow += routed * (int64_t)p->variant_factor_q4[L->voff[i] + k];",
      "t->outflow += routed * 4;"),
     ("batch digit of a variant ignored", "beta[k] = g == 0 ? 0 : (int32_t)((g - 1) % (uint64_t)nb);", "beta[k] = 0;"),
+    # objective with profiled path accuracies
+    ("routing probabilities read transposed", "c->r->prob[i][prev_variant][k]", "c->r->prob[i][k][prev_variant]"),
+    ("share of the path so far not carried down", "double m = depth == 0 ? share : mass * share;", "double m = share;"),
+    ("a variant without traffic leads nowhere", "share = k == first_hosted ? 1.0 : 0.0;", "share = 0.0;"),
+    ("every leaf reads the first leaf's table", "table += size;", "table += 0;"),
+    ("mean over the task paths not taken", "return total / (double)n_paths;", "return total;"),
+    ("table stride not advanced with the depth", "path_walk(c, depth + 1, k, m, e, stride * (uint64_t)K);",
+     "path_walk(c, depth + 1, k, m, e, stride);"),
+    ("frontend split ignored at the root", "share = depth == 0 ? c->r->prob[0][0][k] : c->r->prob[i][prev_variant][k];",
+     "share = depth == 0 ? (k == first_hosted ? 1.0 : 0.0) : c->r->prob[i][prev_variant][k];"),
 ]
 
 
@@ -60,7 +70,7 @@ def test_pins_catch_a_planted_mistake(what, old, new):
                         "-I", os.path.join(ROOT, "oracle"), "-o", lib, src], check=True)
         env = dict(os.environ, LOKI_ORACLE_LIB=lib)
         r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
-                            "-x", "-q", "-p", "no:cacheprovider",
+                            os.path.join(ROOT, "tests", "test_oracle_path_tables.py"), "-x", "-q", "-p", "no:cacheprovider",
                             "-k", "not slices and not zero_demand and not symmetry"],
                            env=env, cwd=ROOT, capture_output=True, text=True, timeout=600)
         assert r.returncode != 0, f"no pin noticed: {what}\n{r.stdout[-800:]}"
