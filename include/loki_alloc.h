@@ -71,6 +71,7 @@ extern "C" {
 #define LOKI_MAX_REPLICAS 255
 #define LOKI_MAX_CHOICES (1u << 24) /* per task */
 #define LOKI_MAX_DEMAND_POINTS 65535
+#define LOKI_MAX_PATH_ENTRIES 32768 /* profiled path accuracies, all leaves together */
 
 enum {
     LOKI_OK = 0,
@@ -121,6 +122,21 @@ typedef struct {
                                     16^depth, and every search runs with LOKI_SEARCH_PER_LANE. */
     int32_t per_variant_batch;   /* 0: one batch size per task.  1: a batch size per hosted variant, the y(i,k)
                                     of Section 4.1 "Output" and eq. (4); see the index layout above */
+    const int32_t *path_acc_ppm; /* NULL, or the profiled end-to-end accuracy A-hat(p) of every variant path
+                                    (Section 4.1 "Accuracy"), 0..1000000: concatenated over the leaves in
+                                    ascending task index; a leaf's table has one entry per combination of
+                                    variants of the tasks root..leaf, entry = sum_j k_j * prod_{j'<j} K_j'
+                                    with the root's variant least significant; at most LOKI_MAX_PATH_ENTRIES
+                                    entries in total.  The objective of a feasible plan is then the mean over
+                                    the root-to-leaf task paths of sum_p c(p) * A-hat(p), where c(p) is the
+                                    frontend's split over the root's variants times, per edge, the probability
+                                    with which the upstream variant's routing table (Algorithm 1, what
+                                    loki_route_table returns in prob) picks the downstream variant; a variant
+                                    without traffic hands on to the first hosted downstream variant in route
+                                    order.  fp64 order: c(p) multiplied up root first, times A-hat(p)/10^6,
+                                    terms added with the root's variants outermost and every level in route
+                                    order, task paths added in leaf order, one division by their number.
+                                    Tasks are coupled through c(p): every search scores whole plans per lane. */
 } loki_pipeline_t;
 
 typedef struct loki_problem loki_problem_t; /* opaque handle */

@@ -50,7 +50,8 @@ class PipelineC(C.Structure):
                 ("latency_us", C.POINTER(C.c_int64)),
                 ("thr_mqps", C.POINTER(C.c_int64)),
                 ("variant_factor_q4", C.POINTER(C.c_int32)),
-                ("per_variant_batch", C.c_int32)]
+                ("per_variant_batch", C.c_int32),
+                ("path_acc_ppm", C.POINTER(C.c_int32))]
 
 
 class Result(C.Structure):
@@ -163,10 +164,13 @@ def _pipeline_struct(p):
             _arr(C.c_int32, p.acc_ppm), _arr(C.c_int64, p.latency_us), _arr(C.c_int64, p.thr_mqps)]
     vf = getattr(p, "variant_factor_q4", None)
     vf_arr = _arr(C.c_int32, vf) if vf is not None else None
+    pt = getattr(p, "path_acc_ppm", None)
+    pt_arr = _arr(C.c_int32, pt) if pt is not None else None
     s = PipelineC(int(p.n_tasks), *[C.cast(a, C.POINTER(a._type_)) for a in keep],
                   C.cast(vf_arr, C.POINTER(C.c_int32)) if vf_arr is not None else C.POINTER(C.c_int32)(),
-                  1 if getattr(p, "per_variant_batch", False) else 0)
-    keep.append(vf_arr)
+                  1 if getattr(p, "per_variant_batch", False) else 0,
+                  C.cast(pt_arr, C.POINTER(C.c_int32)) if pt_arr is not None else C.POINTER(C.c_int32)())
+    keep.extend([vf_arr, pt_arr])
     return s, keep
 
 

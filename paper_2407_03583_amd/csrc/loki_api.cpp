@@ -39,10 +39,12 @@ struct Layout {
     size_t off_P, off_Dn, off_table, off_perm, off_run, off_recs, off_results, total;
 };
 
-Layout search_layout(uint32_t table_total, uint32_t c0, int64_t M) {
+// `cb` is the size of the constant block: the problem constants followed by the profiled path
+// accuracies (if any), see const_block().
+Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M) {
     Layout l;
     l.off_P = 0;
-    l.off_Dn = align_up(sizeof(DevProblem));
+    l.off_Dn = cb;
     l.off_table = align_up(l.off_Dn + size_t(M) * kMaxTasks * sizeof(int64_t));
     l.off_perm = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
     l.off_run = align_up(l.off_perm + size_t(M) * c0 * sizeof(uint32_t));
@@ -56,10 +58,10 @@ struct EvalLayout {
     size_t off_P, off_idx, off_out, total;
 };
 
-EvalLayout eval_layout(int64_t n) {
+EvalLayout eval_layout(size_t cb, int64_t n) {
     EvalLayout l;
     l.off_P = 0;
-    l.off_idx = align_up(sizeof(DevProblem));
+    l.off_idx = cb;
     l.off_out = align_up(l.off_idx + size_t(n) * sizeof(uint64_t));
     l.total = align_up(l.off_out + size_t(n) * sizeof(loki_eval_t));
     return l;
@@ -76,7 +78,8 @@ struct loki_problem {
     int32_t voff[kMaxTasks];
     int32_t max_vf[kMaxTasks];  // largest variant factor of the task (4 without per-variant factors)
     uint64_t n_candidates;
-    // pinned staging: [DevProblem | Dn (cap_points * 8 int64) | results (cap_points)]
+    std::vector<double> path_acc;  // profiled path accuracies as fractions (ppm / 10^6), all leaves
+    // pinned staging: [DevProblem, path accuracies | Dn (cap_points * 8 int64) | results (cap_points)]
     unsigned char *staging = nullptr;
     int64_t cap_points = 0;
     hipEvent_t staged = nullptr, ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -98,8 +101,23 @@ int hip_fail(hipError_t e) {
         if (e_ != hipSuccess) return hip_fail(e_);    \
     } while (0)
 
-size_t staging_bytes(int64_t points) {
-    return align_up(sizeof(DevProblem)) + align_up(size_t(points) * kMaxTasks * sizeof(int64_t)) +
+// Constant block of a handle: DevProblem, directly followed by the path accuracies.
+size_t const_block(const loki_problem *p) {
+    return align_up(sizeof(DevProblem) + p->path_acc.size() * sizeof(double));
+}
+
+void fill_const_block(loki_problem *p) {
+    std::memcpy(p->staging, &p->dev, sizeof(DevProblem));
+    if (!p->path_acc.empty())
+        std::memcpy(p->staging + sizeof(DevProblem), p->path_acc.data(), p->path_acc.size() * sizeof(double));
+}
+
+const double *device_path_acc(const loki_problem *p, const unsigned char *ws) {
+    return p->path_acc.empty() ? nullptr : reinterpret_cast<const double *>(ws + sizeof(DevProblem));
+}
+
+size_t staging_bytes(const loki_problem *p, int64_t points) {
+    return const_block(p) + align_up(size_t(points) * kMaxTasks * sizeof(int64_t)) +
            align_up(size_t(points) * sizeof(loki_result_t));
 }
 
@@ -120,7 +138,7 @@ int ensure_staging(loki_problem *p, int64_t points) {
     }
     int64_t cap = std::max<int64_t>(points, 1024);
     void *ptr = nullptr;
-    LOKI_HIP(hipHostMalloc(&ptr, staging_bytes(cap), hipHostMallocDefault));
+    LOKI_HIP(hipHostMalloc(&ptr, staging_bytes(p, cap), hipHostMallocDefault));
     p->staging = static_cast<unsigned char *>(ptr);
     p->cap_points = cap;
     return LOKI_OK;
@@ -173,10 +191,12 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     if (n_demand < 1 || n_demand > LOKI_MAX_DEMAND_POINTS) return LOKI_E_ARG;
     if (flags & ~(LOKI_TIE_INDEX_ONLY | LOKI_SEARCH_PER_LANE)) return LOKI_E_ARG;
     if (index_begin > index_end || index_end > p->n_candidates) return LOKI_E_ARG;
-    if (p->dev.has_vf) flags |= LOKI_SEARCH_PER_LANE;  // a task's demand depends on its parent's part of the plan
+    // a task's demand depends on its parent's part of the plan / the objective couples the tasks
+    if (p->dev.has_vf || p->dev.has_path) flags |= LOKI_SEARCH_PER_LANE;
     int rc = check_scalars(workers, slo_us, comm_us);
     if (rc) return rc;
-    const Layout lay = search_layout(p->dev.table_total, p->dev.C[0], n_demand);
+    const size_t cb = const_block(p);
+    const Layout lay = search_layout(cb, p->dev.table_total, p->dev.C[0], n_demand);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
         return LOKI_E_WORKSPACE;
     if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
@@ -187,15 +207,15 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         LOKI_HIP(hipEventSynchronize(p->staged));
         p->staged_pending = false;
     }
-    int64_t *hDn = reinterpret_cast<int64_t *>(p->staging + align_up(sizeof(DevProblem)));
+    int64_t *hDn = reinterpret_cast<int64_t *>(p->staging + cb);
     for (int32_t m = 0; m < n_demand; m++) {
         rc = task_demand(p, demand_mqps[m], hDn + size_t(m) * kMaxTasks);
         if (rc) return rc;
     }
-    std::memcpy(p->staging, &p->dev, sizeof(DevProblem));
+    fill_const_block(p);
 
     unsigned char *ws = static_cast<unsigned char *>(d_workspace);
-    const size_t head = align_up(sizeof(DevProblem)) + size_t(n_demand) * kMaxTasks * sizeof(int64_t);
+    const size_t head = cb + size_t(n_demand) * kMaxTasks * sizeof(int64_t);
     static_assert(sizeof(DevProblem) % 8 == 0, "alignment of the demand block");
     LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, head, hipMemcpyHostToDevice, stream));
     LOKI_HIP(hipEventRecord(p->staged, stream));
@@ -210,6 +230,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     A.perm = reinterpret_cast<uint32_t *>(ws + lay.off_perm);
     A.run_end = reinterpret_cast<uint32_t *>(ws + lay.off_run);
     A.results = d_results ? d_results : static_cast<void *>(ws + lay.off_results);
+    A.path_acc = device_path_acc(p, ws);
     path_budgets(p, slo_us, comm_us, A.budget);
     A.begin = index_begin;
     A.end = index_end;
@@ -221,7 +242,13 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     const int n = p->n, L = n - 1;
 
     if (timed) LOKI_HIP(hipEventRecord(p->ev[0], stream));
-    if (flags & LOKI_SEARCH_PER_LANE) {
+    if (p->dev.has_path) {
+        // whole plans per lane, a contiguous stretch of the range each
+        const uint64_t want = (span + kBlockThreads - 1) / kBlockThreads;
+        A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
+        if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
+        LOKI_HIP(launch_path_search(A, stream));
+    } else if (flags & LOKI_SEARCH_PER_LANE) {
         // one work item = one choice of all tasks but the last x a strip of 64 choices of the last;
         // only the strips the index range touches are visited (cl_first/chunk_groups carry them)
         uint64_t items = 0;
@@ -420,6 +447,37 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
     d.n_paths = 0;
     for (int i = 0; i < n; i++) d.n_paths += d.is_leaf[i];
     p->n_candidates = N;
+    for (int i = 0; i < n; i++) {  // chain root..i, root first
+        int at = d.path_len[i] - 1;
+        for (int j = i; j >= 0; j = d.parent[j]) d.leaf_path[i][at--] = j;
+    }
+    if (in->path_acc_ppm) {
+        // profiled accuracy of every variant path, per leaf (Section 4.1 "Accuracy"); stored as the
+        // fraction ppm / 10^6, one correctly rounded division each
+        d.has_path = 1;
+        uint64_t total = 0;
+        for (int i = 0; i < n; i++) {
+            if (!d.is_leaf[i]) continue;
+            uint64_t size = 1;
+            for (int j = 0; j < d.path_len[i]; j++) size *= uint64_t(d.K[d.leaf_path[i][j]]);
+            d.path_off[i] = uint32_t(total);
+            total += size;
+            if (total > LOKI_MAX_PATH_ENTRIES) {
+                delete p;
+                return LOKI_E_RANGE;
+            }
+        }
+        d.path_total = uint32_t(total);
+        p->path_acc.resize(total);
+        for (uint64_t e = 0; e < total; e++) {
+            const int32_t a = in->path_acc_ppm[e];
+            if (a < 0 || a > 1000000) {
+                delete p;
+                return LOKI_E_RANGE;
+            }
+            p->path_acc[e] = double(a) / 1000000.0;
+        }
+    }
 
     *out = p;
     return LOKI_OK;
@@ -444,7 +502,8 @@ int loki_num_candidates(const loki_problem_t *p, uint64_t *n) {
 int loki_workspace_bytes(const loki_problem_t *p, int64_t n_demand, size_t *bytes) {
     if (!p || !bytes) return LOKI_E_NULL;
     if (n_demand < 1) return LOKI_E_ARG;
-    *bytes = std::max(search_layout(p->dev.table_total, p->dev.C[0], n_demand).total, eval_layout(n_demand).total);
+    *bytes = std::max(search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total,
+                      eval_layout(const_block(p), n_demand).total);
     return LOKI_OK;
 }
 
@@ -503,8 +562,8 @@ int loki_alloc_search(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_d
     int rc = enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
                             d_workspace, workspace_bytes, stream, nullptr, true);
     if (rc) return rc;
-    const Layout lay = search_layout(p->dev.table_total, p->dev.C[0], n_demand);
-    unsigned char *hres = p->staging + align_up(sizeof(DevProblem)) +
+    const Layout lay = search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand);
+    unsigned char *hres = p->staging + const_block(p) +
                           align_up(size_t(p->cap_points) * kMaxTasks * sizeof(int64_t));
     LOKI_HIP(hipMemcpyAsync(hres, static_cast<unsigned char *>(d_workspace) + lay.off_results,
                             size_t(n_demand) * sizeof(loki_result_t), hipMemcpyDeviceToHost, stream));
@@ -526,7 +585,7 @@ int loki_alloc_eval(loki_problem_t *p, const uint64_t *indices, int64_t n_indice
     if (rc) return rc;
     for (int64_t j = 0; j < n_indices; j++)
         if (indices[j] >= p->n_candidates) return LOKI_E_RANGE;
-    const EvalLayout lay = eval_layout(n_indices);
+    const EvalLayout lay = eval_layout(const_block(p), n_indices);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
         return LOKI_E_WORKSPACE;
     EvalArgs A;
@@ -542,13 +601,15 @@ int loki_alloc_eval(loki_problem_t *p, const uint64_t *indices, int64_t n_indice
         LOKI_HIP(hipEventSynchronize(p->staged));
         p->staged_pending = false;
     }
-    std::memcpy(p->staging, &p->dev, sizeof(DevProblem));
-    LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, sizeof(DevProblem), hipMemcpyHostToDevice, stream));
+    fill_const_block(p);
+    LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, sizeof(DevProblem) + p->path_acc.size() * sizeof(double),
+                            hipMemcpyHostToDevice, stream));
     LOKI_HIP(hipMemcpyAsync(ws + lay.off_idx, indices, size_t(n_indices) * sizeof(uint64_t), hipMemcpyHostToDevice,
                             stream));
     A.P = reinterpret_cast<const DevProblem *>(ws + lay.off_P);
     A.indices = reinterpret_cast<const uint64_t *>(ws + lay.off_idx);
     A.out = ws + lay.off_out;
+    A.path_acc = device_path_acc(p, ws);
     A.n = n_indices;
     A.W = workers;
     LOKI_HIP(launch_eval(A, stream));

@@ -46,6 +46,11 @@ struct DevProblem {
     uint64_t magic_nb[kMaxTasks];           // ceil(2^36 / |B_i|)
     int64_t lat[kMaxTasks][kMaxVariants][kMaxBatches];    // microseconds
     int64_t thr_s[kMaxTasks][kMaxVariants][kMaxBatches];  // throughput * 4^depth
+    // profiled accuracies of the variant paths (only the kernels that stage the whole block use these)
+    int32_t has_path;                       // a table per leaf is present
+    uint32_t path_total;                    // entries over all leaves
+    uint32_t path_off[kMaxTasks];           // first entry of leaf i's table
+    int32_t leaf_path[kMaxTasks][kMaxTasks];  // tasks on the chain root..i, root first (path_len[i] of them)
 };
 
 // What a task contributes to any plan that uses one of its choices
@@ -90,6 +95,7 @@ struct SearchArgs {
     uint32_t *perm;         // [M][C_0] first-task choices in run order
     uint32_t *run_end;      // [M][C_0] end (exclusive) of the run each position belongs to
     void *results;          // [M] loki_result_t
+    const double *path_acc; // [path_total] profiled path accuracies as fractions, or null
     int64_t budget[kMaxTasks];  // per task i: floor((slo - comm*path_len[i]) / 2), -1 if negative
     uint64_t begin, end;    // index range
     uint64_t far_count;     // F = prod of C_j over the tasks strictly between the first and the last
@@ -131,6 +137,7 @@ struct EvalArgs {
     const DevProblem *P;
     const uint64_t *indices;
     void *out;              // loki_eval_t
+    const double *path_acc; // profiled path accuracies as fractions, or null
     int64_t n;
     int64_t Dn[kMaxTasks];
     int64_t budget[kMaxTasks];

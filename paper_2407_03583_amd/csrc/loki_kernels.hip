@@ -229,6 +229,140 @@ __device__ __forceinline__ void eval_plan(const DevProblem *P, const uint32_t (&
     accuracy = mask ? 0.0 : sum / static_cast<double>(P->n_paths);
 }
 
+// ---- objective from profiled path accuracies ------------------------------------------------------
+// System accuracy = sum over variant paths p of c(p) * A-hat(p) (Section 4.1 "Accuracy"), averaged over
+// the root-to-leaf task paths.  c(p): the frontend's split over the root's variants times, per edge,
+// the share of the upstream variant's requests that Algorithm 1 (Section 5.1) places on the
+// downstream variant.  Algorithm 1 hands the upstream variants' requests, most accurate variant first,
+// to the downstream variants, most accurate first: both sides are consecutive intervals of the
+// downstream task's request stream, and a share is the overlap of two intervals over the length of
+// the upstream one.  The walk below visits one task of the path per level; a level goes through the
+// task's hosted variants in route order, which yields their intervals one after the other.
+struct PathWalk {
+    const DevProblem *P;
+    const double *tab;   // A-hat of this task path, as fractions
+    int leaf;
+    uint32_t c[kMaxTasks];    // the plan: choice per task
+    int64_t dn[kMaxTasks];    // demand per task under this plan
+    double sum;
+};
+
+__device__ __forceinline__ uint32_t pick32(const uint32_t (&v)[kMaxTasks], int idx) {
+    uint32_t r = 0;
+#pragma unroll
+    for (int q = 0; q < kMaxTasks; q++) r |= v[q] & (idx == q ? ~0u : 0u);
+    return r;
+}
+
+// lo, len: the interval of this task's request stream that holds the requests coming from the variant
+// chosen one level up (the whole stream at the root); mass: c(p) so far; entry, stride: position in
+// the table.  A variant that sends nothing (len == 0, only at zero demand) hands on to the first
+// hosted variant.
+template <int J>
+__device__ void path_level(PathWalk &X, int64_t lo, int64_t len, double mass, uint32_t entry, uint32_t stride) {
+    const DevProblem *P = X.P;
+    const int i = P->leaf_path[X.leaf][J];
+    const int K = P->K[i];
+    const bool pv = P->pv_batch != 0, has_vf = P->has_vf != 0;
+    const uint32_t nb = static_cast<uint32_t>(P->nb[i]);
+    uint32_t c = pick32(X.c, i);
+    uint64_t digits = 0;
+    uint32_t betas = 0;
+    for (int k = 0; k < K; k++) {
+        const uint32_t radix = P->radix[i][k];
+        const uint32_t q = c / radix;
+        const uint32_t g = c - q * radix;
+        c = q;
+        uint32_t x = g;
+        if (pv) {
+            x = g == 0 ? 0u : (g - 1) / nb + 1;
+            betas |= (g == 0 ? 0u : (g - 1) % nb) << (4 * k);
+        }
+        digits |= static_cast<uint64_t>(x) << (8 * k);
+    }
+    const uint32_t beta_task = c;
+    const int64_t dn = pick_below(X.dn, i, kMaxTasks);
+    const bool last = J == P->path_len[X.leaf] - 1;
+    const int next = last ? 0 : P->leaf_path[X.leaf][J + 1 < kMaxTasks ? J + 1 : J];
+    const int64_t fan = last ? 0 : static_cast<int64_t>(P->fanout[next]);
+    int64_t at = 0;     // requests of this task placed so far = start of the next variant's interval
+    int64_t made = 0;   // requests created so far for a child, per unit of its fan-out
+    bool any = false;
+    for (int r = 0; r < K; r++) {
+        const int k = P->order[i][r];
+        const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
+        if (x == 0) continue;
+        const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
+        const int64_t cap = x * P->thr_s[i][k][beta];
+        const int64_t room = dn - at;
+        const int64_t routed = room < cap ? room : cap;
+        double share;
+        if (len > 0) {
+            const int64_t hi_a = at + routed, hi_b = lo + len;
+            const int64_t ov = (hi_a < hi_b ? hi_a : hi_b) - (at > lo ? at : lo);
+            share = ov > 0 ? static_cast<double>(ov) / static_cast<double>(len) : 0.0;
+        } else {
+            share = any ? 0.0 : 1.0;
+        }
+        any = true;
+        const int64_t out = has_vf ? routed * static_cast<int64_t>(P->vf[i][k]) : routed;
+        if (share != 0.0) {
+            const double m = J == 0 ? share : mass * share;
+            const uint32_t e = entry + static_cast<uint32_t>(k) * stride;
+            if (last) {
+                X.sum = X.sum + m * X.tab[e];
+            } else {
+                if constexpr (J + 1 < kMaxTasks)
+                    path_level<J + 1>(X, made * fan, out * fan, m, e, stride * static_cast<uint32_t>(K));
+            }
+        }
+        at += routed;
+        made += out;
+    }
+}
+
+// Objective of a feasible plan.  Dn: per-task demand with one factor per edge (only Dn[0] is used
+// with per-variant factors, where every task's demand follows from its parent's part of the plan).
+__device__ __noinline__ double path_objective(const DevProblem *P, const double *path_acc, const uint32_t (&c)[kMaxTasks],
+                                              const int64_t *Dn) {
+    PathWalk X;
+    X.P = P;
+    const int n = P->n_tasks;
+    const bool has_vf = P->has_vf != 0;
+    int64_t out[kMaxTasks];
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        X.c[i] = c[i];
+        X.dn[i] = 0;
+        out[i] = 0;
+    }
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        if (i < n) {
+            int64_t dn = Dn[i];
+            if (has_vf) {
+                if (i > 0) dn = pick_below(out, P->parent[i], i) * static_cast<int64_t>(P->fanout[i]);
+                TaskOut o;
+                eval_task_any(P, i, c[i], dn, o);
+                out[i] = o.outflow;
+            }
+            X.dn[i] = dn;
+        }
+    }
+    double total = 0.0;
+    bool first = true;
+    for (int leaf = 0; leaf < n; leaf++) {
+        if (!P->is_leaf[leaf]) continue;
+        X.leaf = leaf;
+        X.tab = path_acc + P->path_off[leaf];
+        X.sum = 0.0;
+        path_level<0>(X, 0, X.dn[0], 0.0, 0u, 1u);
+        total = first ? X.sum : total + X.sum;
+        first = false;
+    }
+    return total / static_cast<double>(P->n_paths);
+}
+
 // ---- ordering and reductions -----------------------------------------------------------------------
 // Strict total order on found plans: accuracy desc, workers asc (unless tie_index_only), index asc.
 // A record with acc < 0 means "nothing found" and loses to everything.
@@ -909,6 +1043,73 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
                      A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
 }
 
+// ---- kernel: whole plans per lane, objective from profiled path accuracies ------------------------------
+// The objective couples the tasks, so nothing is shared between plans: a lane takes a contiguous
+// stretch of the index range, decodes its first index once and then steps the choices like an odometer.
+__global__ void __launch_bounds__(kBlockThreads) path_search_kernel(SearchArgs A) {
+    __shared__ DevProblem sP;
+    __shared__ BestRec sBest[kWavesPerBlock];
+    stage_problem(&sP, A.P, sizeof(DevProblem));
+    __syncthreads();
+    const DevProblem *P = &sP;
+    const int m = blockIdx.y;
+    const int n = P->n_tasks;
+    const bool tie_index_only = A.tie_index_only != 0;
+    const uint64_t lanes = static_cast<uint64_t>(gridDim.x) * kBlockThreads;
+    const uint64_t span = A.end - A.begin;
+    const uint64_t per_lane = (span + lanes - 1) / lanes;
+    const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x;
+    uint64_t idx = A.begin + (t < span ? t * per_lane : span);
+    uint64_t idx_end = idx + per_lane;
+    if (idx_end > A.end || idx_end < idx) idx_end = A.end;
+    if (idx > A.end) idx = A.end;
+    int64_t Dn[kMaxTasks];
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) Dn[i] = A.Dn[static_cast<size_t>(m) * kMaxTasks + i];
+    uint32_t c[kMaxTasks];
+    {
+        uint64_t rest = idx;
+#pragma unroll
+        for (int i = 0; i < kMaxTasks; i++) {
+            c[i] = 0;
+            if (i < n) {
+                c[i] = static_cast<uint32_t>(rest % P->C[i]);
+                rest /= P->C[i];
+            }
+        }
+    }
+    double bacc = -1.0;
+    int32_t bw = kNever;
+    uint64_t bidx = ~0ull;
+    uint64_t nfeas = 0;
+    for (; idx < idx_end; ++idx) {
+        uint32_t mask;
+        int32_t workers;
+        double acc;
+        eval_plan(P, c, Dn, A.budget, A.W, mask, workers, acc);
+        if (mask == 0) {
+            acc = path_objective(P, A.path_acc, c, Dn);
+            nfeas++;
+            if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                bacc = acc;
+                bw = workers;
+                bidx = idx;
+            }
+        }
+        bool carry = true;
+#pragma unroll
+        for (int i = 0; i < kMaxTasks; i++) {
+            if (i < n && carry) {
+                if (++c[i] == P->C[i]) c[i] = 0;
+                else carry = false;
+            }
+        }
+    }
+    nfeas = wave_sum(nfeas);
+    block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
+                     A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
+}
+
 // ---- kernel: merge the block records of each demand point -------------------------------------------------
 __global__ void __launch_bounds__(kBlockThreads) final_reduce_kernel(SearchArgs A) {
     __shared__ BestRec sBest[kWavesPerBlock];
@@ -971,6 +1172,7 @@ __global__ void __launch_bounds__(kBlockThreads) eval_kernel(EvalArgs A) {
     int32_t workers;
     double acc;
     eval_plan(&sP, c, A.Dn, A.budget, A.W, mask, workers, acc);
+    if (A.path_acc && mask == 0) acc = path_objective(&sP, A.path_acc, c, A.Dn);
     EvalOut o;
     o.accuracy = acc;
     o.workers = workers;
@@ -1096,6 +1298,12 @@ hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_v
         if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<false, true>), grid, block, 0, stream, A);
         else hipLaunchKernelGGL((per_lane_search_kernel<false, false>), grid, block, 0, stream, A);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_path_search(const SearchArgs &A, hipStream_t stream) {
+    const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
+    hipLaunchKernelGGL(path_search_kernel, grid, block, 0, stream, A);
     return hipGetLastError();
 }
 

@@ -13,6 +13,7 @@ hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool divide, bool range,
                           hipStream_t stream);
 hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, hipStream_t stream);
+hipError_t launch_path_search(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_eval(const EvalArgs &A, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &A, hipStream_t stream);
@@ -23,7 +24,8 @@ hipError_t launch_route(const RouteArgs &A, hipStream_t stream);
 #define LOKI_RATE_MAX_F64 2
 #define LOKI_RATE_SEARCH_MIX 3
 #define LOKI_RATE_ADD_U32 4
-// `out` needs blocks * 256 doubles; every thread runs iters trips of 16 instructions
+// `out` needs 2048 * 256 doubles (a sink shared by blocks 2048 apart); every thread runs iters trips
+// of 16 instructions
 hipError_t launch_valu_rate(int kind, double *out, int blocks, int iters, hipStream_t stream);
 
 }  // namespace loki

@@ -62,6 +62,8 @@ def test_validation_rejects_bad_inputs():
         (dict(thr_mqps=[-1, 150000]), binding.LOKI_E_RANGE),
         (dict(variant_factor_q4=[4, 0]), binding.LOKI_E_RANGE),
         (dict(variant_factor_q4=[65, 4]), binding.LOKI_E_RANGE),
+        (dict(path_acc_ppm=[1000001]), binding.LOKI_E_RANGE),
+        (dict(path_acc_ppm=[-1]), binding.LOKI_E_RANGE),
         (dict(n_batches=[2, 1], batch_size=[2, 2, 1], latency_us=[5000, 5000, 6000],
               thr_mqps=[200000, 200000, 150000]), binding.LOKI_E_RANGE),
     ]
@@ -71,6 +73,14 @@ def test_validation_rejects_bad_inputs():
         with pytest.raises(binding.LokiError) as e:
             binding.Problem(SimpleNamespace(**bad))
         assert e.value.code == code, change
+    binding.Problem(SimpleNamespace(**dict(good, path_acc_ppm=[123456])))
+    # more profiled path accuracies than the library takes: a chain of 6 tasks with 8 variants each
+    deep = dict(n_tasks=6, parent=[-1, 0, 1, 2, 3, 4], fanout_q4=[4] * 6, n_variants=[8] * 6, n_batches=[1] * 6,
+                batch_size=[1] * 6, max_replicas=[1] * 48, acc_ppm=[500000] * 48, latency_us=[1000] * 48,
+                thr_mqps=[1000] * 48, path_acc_ppm=[0] * 8)   # the count is checked before the table is read
+    with pytest.raises(binding.LokiError) as e:
+        binding.Problem(SimpleNamespace(**deep))
+    assert e.value.code == binding.LOKI_E_RANGE
     # too many choices in one task: 8 variants with 255 replicas
     big = dict(n_tasks=1, parent=[-1], fanout_q4=[4], n_variants=[8], n_batches=[1], batch_size=[1],
                max_replicas=[255] * 8, acc_ppm=[1] * 8, latency_us=[1] * 8, thr_mqps=[1] * 8)

@@ -1,0 +1,144 @@
+"""GPU parity for the objective from profiled path accuracies (sum_p c(p) * A-hat(p), Section 4.1
+"Accuracy"; c(p) from Algorithm 1's routing, Section 5.1): search results and per-plan objectives
+against the CPU checker, bit for bit."""
+import json
+import os
+import random
+import struct
+from types import SimpleNamespace
+
+import pytest
+
+import oracle
+from paper_2407_03583_amd import binding, workloads as wl
+from test_oracle_path_tables import tight_problem
+
+pytestmark = pytest.mark.gpu
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+TIE = binding.LOKI_TIE_INDEX_ONLY
+
+
+def bits(x):
+    return struct.unpack("<Q", struct.pack("<d", x))[0]
+
+
+def agree(res, ref):
+    got, want = res.as_tuple(), ref.as_tuple()
+    return got[0] == want[0] and bits(got[1]) == bits(want[1]) and got[2:] == want[2:]
+
+
+def check_plans(P, O, indices, demand, workers, slo, comm=0):
+    out = P.alloc_eval(indices, demand, workers, slo, comm)
+    feasible = 0
+    for idx, got in zip(indices, out):
+        e = O.eval(idx, demand, workers, slo, comm)
+        assert got.infeasible == e.infeasible and got.workers == e.workers, idx
+        assert bits(got.accuracy) == bits(e.accuracy), (idx, got.accuracy, e.accuracy)
+        feasible += e.infeasible == 0
+    return feasible
+
+
+def test_hand_derived_example():
+    g = json.load(open(os.path.join(GOLDEN, "path_table_example.json")))
+    p = SimpleNamespace(**g["pipeline"])
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert check_plans(P, O, list(range(n)), g["demand_mqps"], g["workers"], g["slo_us"]) > 0
+    idx = O.encode(g["plan_x"], [0, 0])
+    got = P.alloc_eval([idx], g["demand_mqps"], g["workers"], g["slo_us"])[0]
+    assert abs(got.accuracy - 0.779) < 1e-15
+    for demand in (g["demand_mqps"], 0, 30_000, 160_000, 10**7):
+        for flags in (0, TIE):
+            res = P.alloc_search([demand], g["workers"], g["slo_us"], flags=flags)[0]
+            assert agree(res, O.search(demand, g["workers"], g["slo_us"], tie_index_only=bool(flags))), demand
+
+
+@pytest.mark.parametrize("variant_factors", [False, True])
+@pytest.mark.parametrize("per_variant_batch", [False, True])
+def test_small_random_problems(variant_factors, per_variant_batch):
+    found = 0
+    for seed in range(48):
+        w = wl.random_small(seed, path_tables=True, variant_factors=variant_factors,
+                            per_variant_batch=per_variant_batch, max_candidates=6000)
+        P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+        n = P.num_candidates()
+        d = w.demand_mqps[0]
+        for flags in (0, TIE):
+            res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, flags=flags)[0]
+            ref = O.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags))
+            assert agree(res, ref), (seed, flags, res.as_tuple(), ref.as_tuple())
+        found += res.status == 0
+        check_plans(P, O, list(range(0, n, max(1, n // 300))), d, w.workers, w.slo_us, w.comm_us)
+        # a split range merges to the same answer as the checker on the same range
+        a, b = n // 3, n - n // 5
+        res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, begin=a, end=b)[0]
+        assert agree(res, O.search(d, w.workers, w.slo_us, w.comm_us, begin=a, end=b)), seed
+    assert found >= 8
+
+
+@pytest.mark.parametrize("variant_factors", [False, True])
+@pytest.mark.parametrize("per_variant_batch", [False, True])
+def test_plans_that_split_traffic_at_every_task(variant_factors, per_variant_batch):
+    rng = random.Random(500 + 2 * variant_factors + per_variant_batch)
+    feasible = 0
+    for _ in range(10):
+        p, demand = tight_problem(rng, variant_factors, per_variant_batch)
+        P, O = binding.Problem(p), oracle.Problem(p)
+        n = P.num_candidates()
+        feasible += check_plans(P, O, rng.sample(range(n), min(n, 3000)), demand, 99, 1_000_000)
+        if n <= 300_000:
+            for flags in (0, TIE):
+                res = P.alloc_search([demand, demand // 2, 2 * demand], 99, 1_000_000, flags=flags)
+                for d, r in zip([demand, demand // 2, 2 * demand], res):
+                    assert agree(r, O.search(d, 99, 1_000_000, tie_index_only=bool(flags))), (d, flags)
+    assert feasible > 300
+
+
+def test_four_task_tree_with_three_variants():
+    """Tree 0 -> 1 -> 2, 0 -> 3: two task paths of different length, tables of 27 and 9 entries, 8.5
+    million plans, searched in one call for several demand points and in two halves."""
+    rng = wl.SplitMix64(80)
+    p = wl.make_pipeline([-1, 0, 1, 0], 3, 2, (1, 4), rng)
+    p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(78))
+    assert p.path_table_sizes() == [27, 9]
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n == (27 * 2) ** 4
+    demands = [20_000, 60_000, 150_000, 300_000]
+    out = P.alloc_search(demands, 20, 600_000)
+    found = 0
+    for d, res in zip(demands, out):
+        ref = O.search(d, 20, 600_000)
+        assert agree(res, ref), (d, res.as_tuple(), ref.as_tuple())
+        found += ref.found
+    assert found == 3
+    half = n // 2 + 12345
+    lo = P.alloc_search([60_000], 20, 600_000, begin=0, end=half)[0]
+    hi = P.alloc_search([60_000], 20, 600_000, begin=half, end=n)[0]
+    assert agree(lo, O.search(60_000, 20, 600_000, begin=0, end=half))
+    assert agree(hi, O.search(60_000, 20, 600_000, begin=half, end=n))
+    assert lo.n_feasible + hi.n_feasible == out[1].n_feasible
+
+
+def test_deep_chain_reaches_the_last_level():
+    """Eight tasks in a chain with two variants each: one table of 256 entries, eight levels of the walk."""
+    rng = random.Random(3)
+    acc, lat, thr = [], [], []
+    for i in range(8):
+        for k in range(2):
+            acc.append(rng.randint(70, 95) * 10000)
+            l = rng.randint(1500, 3000)
+            lat.append(l)
+            thr.append(rng.randint(60_000, 140_000))
+    p = wl.Pipeline(n_tasks=8, parent=[-1, 0, 1, 2, 3, 4, 5, 6], fanout_q4=[4] * 8, n_variants=[2] * 8,
+                    n_batches=[1] * 8, batch_size=[2] * 8, max_replicas=[1, 2] * 8, acc_ppm=acc, latency_us=lat,
+                    thr_mqps=thr)
+    p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(5))
+    assert p.path_table_sizes() == [256]
+    P, O = binding.Problem(p), oracle.Problem(p)
+    assert P.num_candidates() == 6 ** 8
+    for demand, W in ((150_000, 24), (0, 8), (100_000, 12)):
+        res = P.alloc_search([demand], W, 100_000)[0]
+        ref = O.search(demand, W, 100_000)
+        assert agree(res, ref), (demand, res.as_tuple(), ref.as_tuple())
