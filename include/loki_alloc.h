@@ -250,8 +250,9 @@ int loki_route_table_batch(loki_problem_t *problem, const uint64_t *indices, con
  * the demand to serve is an exponentially weighted moving average of the recent demand,
  *   est_0 = trace_0,  est_t = floor((alpha_ppm * trace_t + (10^6 - alpha_ppm) * est_{t-1}) / 10^6),
  * and every estimate gets its allocation from one batched search.  phase tells which of the two
- * steps of Section 4 produced the plan: LOKI_PHASE_HARDWARE if the best accuracy is the one of
- * the most accurate variants (the plan is then the minimum-worker plan, eq. (11)),
+ * steps of Section 4 produced the plan: LOKI_PHASE_HARDWARE if the best accuracy is not below the
+ * one of the most accurate variants (the plan is then the minimum-worker plan, eq. (11); with
+ * profiled path accuracies another combination of variants may score above it),
  * LOKI_PHASE_ACCURACY if accuracy had to be given up (eq. (12)), LOKI_PHASE_OVERLOAD if no plan
  * serves the estimate.
  *   trace_mqps  host, [n], >= 0;  alpha_ppm in 1..10^6;  out  host, [n]

@@ -745,13 +745,24 @@ int loki_plan_trace(loki_problem_t *p, const int64_t *trace_mqps, int32_t n, int
                                      d_workspace, workspace_bytes, hip_stream, res.data());
     if (rc) return rc;
     // accuracy of the most accurate variants: the same operations in the same order as for any plan
+    // (with profiled path accuracies: the entry of the most accurate variants on every task path)
     double pp[kMaxTasks], sum = 0.0;
     bool first = true;
     for (int i = 0; i < p->n; i++) {
         const double a = double(p->dev.acc[i][p->dev.order[i][0]]) / 1000000.0;
         pp[i] = i == 0 ? a : pp[p->dev.parent[i]] * a;
         if (p->dev.is_leaf[i]) {
-            sum = first ? pp[i] : sum + pp[i];
+            double leaf_value = pp[i];
+            if (p->dev.has_path) {
+                uint32_t entry = 0, stride = 1;
+                for (int j = 0; j < p->dev.path_len[i]; j++) {
+                    const int task = p->dev.leaf_path[i][j];
+                    entry += uint32_t(p->dev.order[task][0]) * stride;
+                    stride *= uint32_t(p->dev.K[task]);
+                }
+                leaf_value = p->path_acc[p->dev.path_off[i] + entry];
+            }
+            sum = first ? leaf_value : sum + leaf_value;
             first = false;
         }
     }
@@ -760,7 +771,7 @@ int loki_plan_trace(loki_problem_t *p, const int64_t *trace_mqps, int32_t n, int
         out[t].estimate_mqps = est[t];
         out[t].plan = res[t];
         out[t].phase = res[t].status != LOKI_FOUND ? LOKI_PHASE_OVERLOAD
-                                                   : (res[t].accuracy == top ? LOKI_PHASE_HARDWARE : LOKI_PHASE_ACCURACY);
+                                                   : (res[t].accuracy >= top ? LOKI_PHASE_HARDWARE : LOKI_PHASE_ACCURACY);
         out[t].pad = 0;
     }
     return LOKI_OK;

@@ -142,3 +142,25 @@ def test_deep_chain_reaches_the_last_level():
         res = P.alloc_search([demand], W, 100_000)[0]
         ref = O.search(demand, W, 100_000)
         assert agree(res, ref), (demand, res.as_tuple(), ref.as_tuple())
+
+
+def test_plan_trace_with_path_tables():
+    """The demand-trace planner on config 1 with profiled path accuracies: every step's plan against the
+    checker, and the phase against the entry of the most accurate variants."""
+    w = wl.config(1)
+    p = w.pipeline
+    p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(9))
+    P, O = binding.Problem(p), oracle.Problem(p)
+    ramp = [7_000 * t for t in range(60)]
+    steps = P.plan_trace(ramp, 500_000, w.workers, w.slo_us)
+    top_entry = (p.n_variants[0] - 1) + p.n_variants[0] * (p.n_variants[1] - 1)   # accuracies are sorted ascending
+    top = p.path_acc_ppm[top_entry] / 1000000.0
+    phases = set()
+    for t, s in enumerate(steps):
+        ref = O.search(s.estimate_mqps, w.workers, w.slo_us)
+        assert agree(s.plan, ref), (t, s.plan.as_tuple(), ref.as_tuple())
+        want = binding.LOKI_PHASE_OVERLOAD if not ref.found else (
+            binding.LOKI_PHASE_HARDWARE if ref.accuracy >= top else binding.LOKI_PHASE_ACCURACY)
+        assert s.phase == want, t
+        phases.add(s.phase)
+    assert phases == {0, 1, 2}
