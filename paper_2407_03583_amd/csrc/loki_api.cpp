@@ -247,7 +247,9 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         const uint64_t want = (span + kBlockThreads - 1) / kBlockThreads;
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
         if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
-        LOKI_HIP(launch_path_search(A, stream));
+        int longest = 1;
+        for (int i = 0; i < n; i++) longest = std::max(longest, p->dev.path_len[i]);
+        LOKI_HIP(launch_path_search(A, longest, stream));
     } else if (flags & LOKI_SEARCH_PER_LANE) {
         // one work item = one choice of all tasks but the last x a strip of 64 choices of the last;
         // only the strips the index range touches are visited (cl_first/chunk_groups carry them)

@@ -258,7 +258,8 @@ __device__ __forceinline__ uint32_t pick32(const uint32_t (&v)[kMaxTasks], int i
 // chosen one level up (the whole stream at the root); mass: c(p) so far; entry, stride: position in
 // the table.  A variant that sends nothing (len == 0, only at zero demand) hands on to the first
 // hosted variant.
-template <int J>
+// MAXD: number of levels compiled (the longest task path the caller will meet).
+template <int J, int MAXD>
 __device__ void path_level(PathWalk &X, int64_t lo, int64_t len, double mass, uint32_t entry, uint32_t stride) {
     const DevProblem *P = X.P;
     const int i = P->leaf_path[X.leaf][J];
@@ -283,7 +284,7 @@ __device__ void path_level(PathWalk &X, int64_t lo, int64_t len, double mass, ui
     const uint32_t beta_task = c;
     const int64_t dn = pick_below(X.dn, i, kMaxTasks);
     const bool last = J == P->path_len[X.leaf] - 1;
-    const int next = last ? 0 : P->leaf_path[X.leaf][J + 1 < kMaxTasks ? J + 1 : J];
+    const int next = last ? 0 : P->leaf_path[X.leaf][J + 1 < MAXD ? J + 1 : J];
     const int64_t fan = last ? 0 : static_cast<int64_t>(P->fanout[next]);
     int64_t at = 0;     // requests of this task placed so far = start of the next variant's interval
     int64_t made = 0;   // requests created so far for a child, per unit of its fan-out
@@ -312,8 +313,8 @@ __device__ void path_level(PathWalk &X, int64_t lo, int64_t len, double mass, ui
             if (last) {
                 X.sum = X.sum + m * X.tab[e];
             } else {
-                if constexpr (J + 1 < kMaxTasks)
-                    path_level<J + 1>(X, made * fan, out * fan, m, e, stride * static_cast<uint32_t>(K));
+                if constexpr (J + 1 < MAXD)
+                    path_level<J + 1, MAXD>(X, made * fan, out * fan, m, e, stride * static_cast<uint32_t>(K));
             }
         }
         at += routed;
@@ -323,6 +324,7 @@ __device__ void path_level(PathWalk &X, int64_t lo, int64_t len, double mass, ui
 
 // Objective of a feasible plan.  Dn: per-task demand with one factor per edge (only Dn[0] is used
 // with per-variant factors, where every task's demand follows from its parent's part of the plan).
+template <int MAXD>
 __device__ __noinline__ double path_objective(const DevProblem *P, const double *path_acc, const uint32_t (&c)[kMaxTasks],
                                               const int64_t *Dn) {
     PathWalk X;
@@ -356,7 +358,7 @@ __device__ __noinline__ double path_objective(const DevProblem *P, const double 
         X.leaf = leaf;
         X.tab = path_acc + P->path_off[leaf];
         X.sum = 0.0;
-        path_level<0>(X, 0, X.dn[0], 0.0, 0u, 1u);
+        path_level<0, MAXD>(X, 0, X.dn[0], 0.0, 0u, 1u);
         total = first ? X.sum : total + X.sum;
         first = false;
     }
@@ -1046,6 +1048,7 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
 // ---- kernel: whole plans per lane, objective from profiled path accuracies ------------------------------
 // The objective couples the tasks, so nothing is shared between plans: a lane takes a contiguous
 // stretch of the index range, decodes its first index once and then steps the choices like an odometer.
+template <int MAXD>
 __global__ void __launch_bounds__(kBlockThreads) path_search_kernel(SearchArgs A) {
     __shared__ DevProblem sP;
     __shared__ BestRec sBest[kWavesPerBlock];
@@ -1088,7 +1091,7 @@ __global__ void __launch_bounds__(kBlockThreads) path_search_kernel(SearchArgs A
         double acc;
         eval_plan(P, c, Dn, A.budget, A.W, mask, workers, acc);
         if (mask == 0) {
-            acc = path_objective(P, A.path_acc, c, Dn);
+            acc = path_objective<MAXD>(P, A.path_acc, c, Dn);
             nfeas++;
             if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
                 bacc = acc;
@@ -1172,7 +1175,7 @@ __global__ void __launch_bounds__(kBlockThreads) eval_kernel(EvalArgs A) {
     int32_t workers;
     double acc;
     eval_plan(&sP, c, A.Dn, A.budget, A.W, mask, workers, acc);
-    if (A.path_acc && mask == 0) acc = path_objective(&sP, A.path_acc, c, A.Dn);
+    if (A.path_acc && mask == 0) acc = path_objective<kMaxTasks>(&sP, A.path_acc, c, A.Dn);
     EvalOut o;
     o.accuracy = acc;
     o.workers = workers;
@@ -1301,9 +1304,10 @@ hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_v
     return hipGetLastError();
 }
 
-hipError_t launch_path_search(const SearchArgs &A, hipStream_t stream) {
+hipError_t launch_path_search(const SearchArgs &A, int longest_path, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
-    hipLaunchKernelGGL(path_search_kernel, grid, block, 0, stream, A);
+    if (longest_path <= 4) hipLaunchKernelGGL(path_search_kernel<4>, grid, block, 0, stream, A);
+    else hipLaunchKernelGGL(path_search_kernel<kMaxTasks>, grid, block, 0, stream, A);
     return hipGetLastError();
 }
 
