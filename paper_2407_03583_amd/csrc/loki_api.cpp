@@ -77,6 +77,7 @@ struct loki_problem {
     int32_t batch_size[kMaxTasks][kMaxBatches];
     int32_t voff[kMaxTasks];
     int32_t max_vf[kMaxTasks];  // largest variant factor of the task (4 without per-variant factors)
+    int32_t sum_r[kMaxTasks];   // sum of the replica limits of the task
     uint64_t n_candidates;
     std::vector<double> path_acc;  // profiled path accuracies as fractions (ppm / 10^6), all leaves
     // pinned staging: [DevProblem, path accuracies | Dn (cap_points * 8 int64) | results (cap_points)]
@@ -235,6 +236,11 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     A.begin = index_begin;
     A.end = index_end;
     A.W = workers;
+    {
+        int64_t others = 0;
+        for (int i = 1; i < p->n; i++) others += p->sum_r[i];
+        A.w_free = static_cast<int32_t>(std::max<int64_t>(int64_t(workers) - others, -1));
+    }
     A.M = n_demand;
     A.tie_index_only = (flags & LOKI_TIE_INDEX_ONLY) ? 1u : 0u;
     const uint32_t max_bpm = std::max<uint32_t>(1u, (kTargetBlocks + n_demand - 1) / n_demand);
@@ -371,6 +377,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         d.fanout[i] = i > 0 ? in->fanout_q4[i] : 4;
         d.scale[i] = scale;
         p->max_vf[i] = 4;
+        p->sum_r[i] = 0;
         for (int bi = 0; bi < nb; bi++) {
             const int32_t bs = in->batch_size[b + bi];
             if (bs < 1 || (bi > 0 && bs <= in->batch_size[b + bi - 1])) rc = LOKI_E_RANGE;
@@ -383,6 +390,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
                 rc = LOKI_E_RANGE;
                 break;
             }
+            p->sum_r[i] += R;
             d.radix[i][k] = d.pv_batch ? 1u + uint32_t(R) * uint32_t(nb) : uint32_t(R) + 1;
             d.magic[i][k] = ((uint64_t(1) << 36) + d.radix[i][k] - 1) / d.radix[i][k];
             d.magic32[i][k] = d.radix[i][k] == 1 ? 0u : uint32_t(((uint64_t(1) << 32) + d.radix[i][k] - 1) / d.radix[i][k]);

@@ -106,6 +106,7 @@ struct SearchArgs {
     uint32_t mid_tiles;     // ceil(C_0 / tile_len)
     uint32_t cpb;           // chunks handled side by side in a block (1, 2 or 4)
     int32_t W;
+    int32_t w_free;         // first-task replica counts up to this never make the worker budget bind (may be < 0)
     int32_t M;
     uint32_t blocks_per_m;
     uint32_t tie_index_only;

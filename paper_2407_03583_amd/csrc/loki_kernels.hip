@@ -494,11 +494,17 @@ __global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A)
 constexpr uint32_t kMaxBuckets = 4096;
 constexpr int kSortThreads = 1024;
 
-__device__ __forceinline__ uint32_t root_bucket(const DevProblem *P, const TaskRec &rec, uint32_t n_buckets) {
+// w_free: the largest replica count of the first task with which the worker budget (eq. (3)) can
+// never bind, whatever the other tasks choose (negative: none).  Choices at or below it leave the
+// last task the same feasibility masks, so they share a bucket per latency; the workers of a
+// winning plan are taken from its own entry, not from the run.
+__device__ __forceinline__ uint32_t root_bucket(const DevProblem *P, const TaskRec &rec, uint32_t n_buckets,
+                                                int32_t w_free) {
     if (rec.lat == kNever) return n_buckets - 1;
     uint32_t rank = 0;
     while (rank + 1 < static_cast<uint32_t>(P->n_lat0) && P->lat0_sorted[rank] < rec.lat) rank++;
-    return static_cast<uint32_t>(rec.w) * P->n_lat0 + rank;
+    const int32_t wk = w_free < 0 ? rec.w : (rec.w > w_free ? rec.w - w_free : 0);
+    return static_cast<uint32_t>(wk) * P->n_lat0 + rank;
 }
 
 __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) {
@@ -521,7 +527,7 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
     }
     for (uint32_t b = threadIdx.x; b < kMaxBuckets; b += kSortThreads) sHist[b] = 0;
     __syncthreads();
-    for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) atomicAdd(&sHist[root_bucket(P, tab[r], n_buckets)], 1u);
+    for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) atomicAdd(&sHist[root_bucket(P, tab[r], n_buckets, A.w_free)], 1u);
     __syncthreads();
     // exclusive prefix sum over the buckets: each thread owns kMaxBuckets / kSortThreads consecutive ones
     constexpr uint32_t kPer = kMaxBuckets / kSortThreads;
@@ -548,7 +554,7 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
     }
     __syncthreads();
     for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) {
-        const uint32_t b = root_bucket(P, tab[r], n_buckets);
+        const uint32_t b = root_bucket(P, tab[r], n_buckets, A.w_free);
         const uint32_t at = atomicAdd(&sHist[b], 1u);  // order inside a bucket is immaterial
         perm[at] = r;
         run_end[at] = sEnd[b];
@@ -832,8 +838,9 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     uint32_t cl = cl0;
                     asm volatile("" : "+v"(cl));
                     const uint64_t low = base_f + sChoice[ee];  // index of the plan without the last task's part
-                    int32_t w_out = W - w_rem;
-                    asm volatile("" : "+s"(w_out));  // keeps the sums with w[] below out of the run start
+                    // replicas of all tasks but the last, from the entry itself: the entries of a run
+                    // share their masks, not necessarily their replica counts
+                    const int32_t w_out = W - sLim[ee].w_rem;
                     bool maybe = kmax > bsum;
                     const bool low_wins = low < blow;
                     if (tie_index_only) {
