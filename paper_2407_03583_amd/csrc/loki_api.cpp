@@ -260,13 +260,19 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         // one work item = one choice of all tasks but the last x a strip of 64 choices of the last;
         // only the strips the index range touches are visited (cl_first/chunk_groups carry them)
         uint64_t items = 0;
+        A.far_first = 0;
+        A.far_span = 1;
         if (span > 0) {
             const uint64_t strideL = p->dev.stride[L];
             const uint32_t strip_first = static_cast<uint32_t>(index_begin / strideL) / 64;
             const uint32_t strip_last = static_cast<uint32_t>((index_end - 1) / strideL) / 64;
             A.cl_first = strip_first;
             A.chunk_groups = strip_last - strip_first + 1;
-            items = strideL * A.chunk_groups;
+            // a range shorter than one step of the last task's choice touches only `span` of the
+            // combinations of the other tasks, in cyclic order from its first index
+            A.far_first = span < strideL ? index_begin % strideL : 0;
+            A.far_span = span < strideL ? span : strideL;
+            items = A.far_span * A.chunk_groups;
         }
         const uint64_t want = (items + kBlockThreads - 1) / kBlockThreads;
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
@@ -283,6 +289,8 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         A.far_count = F;
         A.tile_len = kMidTile;
         A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
+        A.far_first = 0;
+        A.far_span = F;
         if (span == 0) {
             A.cl_first = 0;
             A.chunk_groups = 0;
@@ -296,13 +304,23 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
             A.cpb = 1;
             while (A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
             A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
-            A.items = uint64_t(A.chunk_groups) * F * A.mid_tiles;
+            // a range shorter than one step of the last task's choice touches only some of the
+            // combinations of the tasks in between, in cyclic order from that of its first index
+            if (span < strideL) {
+                const uint64_t o_first = index_begin % strideL;  // position among all tasks but the last
+                const uint64_t touched = (o_first % mid_count + span + mid_count - 1) / mid_count;
+                if (touched < F) {
+                    A.far_first = o_first / mid_count;
+                    A.far_span = touched;
+                }
+            }
+            A.items = uint64_t(A.chunk_groups) * A.far_span * A.mid_tiles;
             // a search with few work items gets shorter ones: blocks that meet many feasible plans
             // run long, and only spare items let the others take over the rest
             while (A.tile_len > kMinTile && A.items * n_demand < kFewItems) {
                 A.tile_len /= 2;
                 A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
-                A.items = uint64_t(A.chunk_groups) * F * A.mid_tiles;
+                A.items = uint64_t(A.chunk_groups) * A.far_span * A.mid_tiles;
             }
         }
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(A.items, 1), max_bpm));

@@ -99,6 +99,10 @@ struct SearchArgs {
     int64_t budget[kMaxTasks];  // per task i: floor((slo - comm*path_len[i]) / 2), -1 if negative
     uint64_t begin, end;    // index range
     uint64_t far_count;     // F = prod of C_j over the tasks strictly between the first and the last
+    // The part of the space an index range touches.  Tabulated kernel: far_span combinations of the tasks
+    // in between, cyclically from far_first (0 and F for the whole space).  Per-lane kernel: far_span
+    // combinations of all tasks but the last, cyclically from far_first.
+    uint64_t far_first, far_span;
     uint64_t items;         // work items per demand point
     uint32_t cl_first;      // first choice of the last task touched by the range
     uint32_t chunk_groups;  // groups of chunks of the last task

@@ -628,11 +628,13 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     uint32_t r = 0, g = 0;
     uint32_t cj[kMaxTasks];  // choice of every task strictly between the first and the last
     uint64_t f = 0;          // those digits as one number: sum cj[j] * prod_{1<=i<j} C_i
-    {
-        r = static_cast<uint32_t>(item_lo % A.mid_tiles);
-        const uint64_t t = item_lo / A.mid_tiles;
-        f = t % A.far_count;
-        g = static_cast<uint32_t>(t / A.far_count);
+    // With an index range only the combinations the range touches are visited: far_span of them,
+    // cyclically from far_first (the whole space: all far_count from 0).
+    auto locate = [&](uint64_t item) {
+        r = static_cast<uint32_t>(item % A.mid_tiles);
+        const uint64_t t = item / A.mid_tiles;
+        f = (A.far_first + t % A.far_span) % A.far_count;
+        g = static_cast<uint32_t>(t / A.far_span);
         uint64_t rest = f;
 #pragma unroll
         for (int j = 1; j < kMaxTasks; j++) {
@@ -643,7 +645,8 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             }
         }
         cj[0] = 0;
-    }
+    };
+    locate(item_lo);
     for (uint64_t item = item_lo; item < item_hi; ++item) {
         if (g != cur_group) {
             cur_group = g;
@@ -898,7 +901,9 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         }
         nfeas += fcount;
         // next item
-        if (++r == A.mid_tiles) {
+        if (RANGE) {
+            if (item + 1 < item_hi) locate(item + 1);
+        } else if (++r == A.mid_tiles) {
             r = 0;
             ++f;
             bool carry = true;
@@ -950,7 +955,8 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
     const uint32_t CL = P->C[L];
     const uint32_t n_strips = A.chunk_groups;  // strips of the last task's choices touched by the index range
     const uint32_t strip_first = A.cl_first;
-    const uint64_t items = strideL * n_strips;
+    // choice combinations of the other tasks touched by the range: far_span of them, cyclically from far_first
+    const uint64_t items = A.far_span * n_strips;
     const double npd = static_cast<double>(P->n_paths);
     const int parL = n >= 2 ? P->parent[L] : 0;
     int64_t Dn[kMaxTasks];
@@ -962,8 +968,10 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
     uint64_t bidx = ~0ull;
     uint64_t nfeas = 0;
     for (uint64_t item = static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x; item < items; item += lanes) {
-        const uint64_t o = item / n_strips;  // index of the plan with the last task's choice 0
-        const uint32_t strip = strip_first + static_cast<uint32_t>(item - o * n_strips);
+        const uint64_t oi = item / n_strips;
+        const uint32_t strip = strip_first + static_cast<uint32_t>(item - oi * n_strips);
+        uint64_t o = A.far_first + oi;  // index of the plan with the last task's choice 0
+        if (o >= strideL) o -= strideL;
         // skip strips wholly outside [begin, end)
         const uint32_t c_lo = strip * kStrip;
         const uint32_t c_hi = c_lo + kStrip < CL ? c_lo + kStrip : CL;

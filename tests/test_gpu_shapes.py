@@ -148,6 +148,56 @@ def test_many_demand_points_in_one_call():
     assert all(a >= b for a, b in zip(accs, accs[1:]))
 
 
+def test_plan_space_of_two_to_the_62_searched_by_ranges():
+    """Three tasks with 2^20, 2^21 and 2^21 choices: 2^62 plans, just below the library's limit.  Ranges
+    at the bottom, across a carry of the last task's choice, and at the very top, through both kernels;
+    the 64-bit index arithmetic is what is being checked."""
+    rng = random.Random(62)
+    acc, lat, thr, bs = [], [], [], []
+    for i, batches in enumerate(([2], [1, 4], [2, 8])):
+        a, l, t = profile(rng, 5, batches)
+        acc += a
+        lat += [v // 8 for v in l]
+        thr += [v * (30 if i else 10) for v in t]
+        bs += batches
+    p = SimpleNamespace(n_tasks=3, parent=[-1, 0, 0], fanout_q4=[4, 6, 9], n_variants=[5, 5, 5], n_batches=[1, 2, 2],
+                        batch_size=bs, max_replicas=[15] * 15, acc_ppm=acc, latency_us=lat, thr_mqps=thr)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n == 1 << 62
+    stride_last = 1 << 41
+    span = 1 << 17
+    found = 0
+    for begin in (0, 5 * stride_last - span // 2, (1 << 61) + 987_654_321, n - span):
+        for flags in (0, LANE):
+            res = P.alloc_search([900_000], 400, 400_000, flags=flags, begin=begin, end=begin + span)[0]
+            ref = O.search(900_000, 400, 400_000, begin=begin, end=begin + span)
+            assert agree(res, ref), (begin, flags, res.as_tuple(), ref.as_tuple())
+        found += ref.found
+    assert found >= 2
+    idxs = [0, 1, n - 1, n - 2, (1 << 61) + 1, 3 * stride_last - 1, 3 * stride_last]
+    for got, idx in zip(P.alloc_eval(idxs, 900_000, 400, 400_000), idxs):
+        e = O.eval(idx, 900_000, 400, 400_000)
+        assert (got.infeasible, got.workers, bits(got.accuracy)) == (e.infeasible, e.workers, bits(e.accuracy)), idx
+
+
+def test_the_largest_number_of_demand_points():
+    """65,535 demand points (the limit of one call) on config 1."""
+    w = wl.config(1)
+    P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
+    rng = random.Random(8)
+    demands = [rng.randint(0, 300_000) for _ in range(65_535)]
+    out = P.alloc_search(demands, w.workers, w.slo_us)
+    assert len(out) == 65_535
+    for j in list(range(0, 65_535, 1111)) + [65_534]:
+        assert agree(out[j], O.search(demands[j], w.workers, w.slo_us)), j
+    order = sorted(range(len(demands)), key=lambda i: demands[i])
+    accs = [out[i].accuracy if out[i].status == 0 else -1.0 for i in order]
+    assert all(a >= b for a, b in zip(accs, accs[1:]))
+    with pytest.raises(binding.LokiError):
+        P.alloc_search(demands + [1], w.workers, w.slo_us)
+
+
 def test_valu_rate_measurement_is_plausible():
     nominal = 256 * 4 * 2.4e9 / 4          # wavefront instructions per second at one per SIMD per 4 cycles
     for kind in binding.RATE_KINDS:
