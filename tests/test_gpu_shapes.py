@@ -181,6 +181,28 @@ def test_plan_space_of_two_to_the_62_searched_by_ranges():
         assert (got.infeasible, got.workers, bits(got.accuracy)) == (e.infeasible, e.workers, bits(e.accuracy)), idx
 
 
+def test_the_most_choices_a_task_may_have():
+    """2^24 choices in one task (six variants, up to 15 replicas each): alone, and as the first task of a
+    chain, where the ordering kernel sorts all of them into runs."""
+    rng = random.Random(24)
+    a0, l0, t0 = profile(rng, 6, [4])
+    a1, l1, t1 = profile(rng, 1, [1, 2])
+    one = SimpleNamespace(n_tasks=1, parent=[-1], fanout_q4=[4], n_variants=[6], n_batches=[1], batch_size=[4],
+                          max_replicas=[15] * 6, acc_ppm=a0, latency_us=l0, thr_mqps=t0)
+    two = SimpleNamespace(n_tasks=2, parent=[-1, 0], fanout_q4=[4, 5], n_variants=[6, 1], n_batches=[1, 2],
+                          batch_size=[4, 1, 2], max_replicas=[15] * 6 + [3], acc_ppm=a0 + a1, latency_us=l0 + l1,
+                          thr_mqps=t0 + [40 * v for v in t1])
+    for p, n in ((one, 1 << 24), (two, 1 << 27)):
+        P, O = binding.Problem(p), oracle.Problem(p)
+        assert P.num_candidates() == n
+        for demand, W in ((2_500_000, 40), (400_000, 93)):
+            for flags in (0, TIE):
+                res = P.alloc_search([demand], W, 300_000, flags=flags)[0]
+                ref = O.search_tabulated(demand, W, 300_000, tie_index_only=bool(flags & TIE))
+                assert agree(res, ref), (n, demand, flags, res.as_tuple(), ref.as_tuple())
+            assert ref.found
+
+
 def test_the_largest_number_of_demand_points():
     """65,535 demand points (the limit of one call) on config 1."""
     w = wl.config(1)
