@@ -42,10 +42,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (445 + 1024) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (274 + 1024) * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (451 + 1024) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (272 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "92dfaa5f39dcdba996a3cc5a3689e00356e5137513ce7655ff73292853d3886e"
+TRAFFIC_SOURCES_SHA256 = "11a7c0a09ff638dc2384a437e6bf97a5c159629ed40d56b99be037a617d013f5"
 
 
 def measured_traffic(workload: str, kernel: str):
