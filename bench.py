@@ -36,6 +36,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
     if not per_lane:
         return (1 if n_tasks >= 2 else 0) + (1 if n_paths > 1 else 0) + 1
     per_task = [20 * k + 30 for k in pipeline.n_variants]
+    if getattr(pipeline, "path_acc_ppm", None) is not None:
+        # profiled path accuracies: every task is scored per plan (nothing is shared between plans); the
+        # walk over the variant paths runs for feasible plans only and is not counted
+        return sum(per_task) + 50
     return per_task[-1] + 50 + sum(per_task[:-1]) / 64.0
 
 
@@ -69,6 +73,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
     ap.add_argument("--per-lane", action="store_true", help="time the kernel that scores whole plans per lane")
+    ap.add_argument("--variant-factors", action="store_true",
+                    help="per-variant multiplicative factors r(i,k), 0.75 .. 1.5 rising with accuracy "
+                         "(the search then scores whole plans per lane)")
+    ap.add_argument("--per-variant-batch", action="store_true", help="a batch size per hosted variant")
+    ap.add_argument("--path-tables", action="store_true",
+                    help="objective from seeded profiled path accuracies (whole plans per lane)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the other configurations and the instruction-rate probes (profiling runs: "
@@ -87,6 +97,19 @@ def main() -> int:
         return 1
     torch.cuda.set_device(0)
     w = wl.config(args.config)
+    variant = []
+    if args.variant_factors:
+        w.pipeline.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in w.pipeline.acc_ppm]
+        variant.append("variant_factors")
+    if args.per_variant_batch:
+        w.pipeline.per_variant_batch = True
+        variant.append("per_variant_batch")
+    if args.path_tables:
+        w.pipeline.path_acc_ppm = wl.draw_path_tables(w.pipeline, wl.SplitMix64(w.seed + 1))
+        variant.append("path_tables")
+    if variant:
+        w.name += "+" + "+".join(variant)
+    args.per_lane = args.per_lane or args.variant_factors or args.path_tables  # what the library does anyway
     P = binding.Problem(w.pipeline)
     n = P.num_candidates()
     m = len(w.demand_mqps)
@@ -94,6 +117,8 @@ def main() -> int:
     end = n
     if args.per_lane and n * m > (1 << 36):  # keep a step to seconds: a prefix of the index space
         end = (1 << 36) // m
+    if not args.per_lane and n * m > (1 << 45):
+        end = (1 << 45) // m
     evaluations = end * m
 
     results = torch.empty(32 * m, dtype=torch.uint8, device="cuda")
@@ -138,7 +163,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "seed": w.seed, "candidates": n, "demand_points": m,
                    "index_end": end, "evaluations_per_step": evaluations,
-                   "kernel": "per_lane" if args.per_lane else "tabulated",
+                   "kernel": ("path" if args.path_tables else "per_lane") if args.per_lane else "tabulated",
                    "feasible_fraction_point0": first[0].n_feasible / end},
         "kernel_ms": {"task_tables": sum(k[0] for k in kernel_ms) / len(kernel_ms), "search": main_ms,
                       "final_merge": sum(k[2] for k in kernel_ms) / len(kernel_ms)},
@@ -148,7 +173,7 @@ def main() -> int:
                      "lane_ops_per_candidate": ops},
     }
     # the other benchmark configurations, one timed blocking call each (context for `value`)
-    if not args.per_lane and not args.no_context:
+    if not args.per_lane and not variant and not args.no_context:
         others = {}
         for c in (1, 2, 3, 4, 5):
             if c == args.config:
