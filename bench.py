@@ -36,10 +36,8 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
     if not per_lane:
         return (1 if n_tasks >= 2 else 0) + (1 if n_paths > 1 else 0) + 1
     per_task = [20 * k + 30 for k in pipeline.n_variants]
-    if getattr(pipeline, "path_acc_ppm", None) is not None:
-        # profiled path accuracies: every task is scored per plan (nothing is shared between plans); the
-        # walk over the variant paths runs for feasible plans only and is not counted
-        return sum(per_task) + 50
+    # (with profiled path accuracies the walk over the variant paths runs for feasible plans only and is
+    # not counted)
     return per_task[-1] + 50 + sum(per_task[:-1]) / 64.0
 
 

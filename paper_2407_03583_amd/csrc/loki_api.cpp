@@ -248,15 +248,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     const int n = p->n, L = n - 1;
 
     if (timed) LOKI_HIP(hipEventRecord(p->ev[0], stream));
-    if (p->dev.has_path) {
-        // whole plans per lane, a contiguous stretch of the range each
-        const uint64_t want = (span + kBlockThreads - 1) / kBlockThreads;
-        A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
-        if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
-        int longest = 1;
-        for (int i = 0; i < n; i++) longest = std::max(longest, p->dev.path_len[i]);
-        LOKI_HIP(launch_path_search(A, longest, stream));
-    } else if (flags & LOKI_SEARCH_PER_LANE) {
+    if (flags & LOKI_SEARCH_PER_LANE) {
         // one work item = one choice of all tasks but the last x a strip of 64 choices of the last;
         // only the strips the index range touches are visited (cl_first/chunk_groups carry them)
         uint64_t items = 0;
@@ -277,7 +269,10 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         const uint64_t want = (items + kBlockThreads - 1) / kBlockThreads;
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(want, 1), max_bpm));
         if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
-        LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, stream));
+        int path_levels = 0;
+        if (p->dev.has_path)
+            for (int i = 0; i < n; i++) path_levels = std::max(path_levels, p->dev.path_len[i]);
+        LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, path_levels, stream));
     } else {
         const uint32_t CL = p->dev.C[L];
         const int slots = CL >= 512 ? 8 : 4;

@@ -939,7 +939,9 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 // and then walks the strip, scoring the last task and finishing the plan per step.
 constexpr uint32_t kStrip = 64;
 
-template <bool PV, bool VF>
+// MAXD > 0: the objective comes from profiled path accuracies (path_objective with MAXD levels compiled
+// in); the feasibility part is the same, and the walk over the variant paths runs for feasible plans only.
+template <bool PV, bool VF, int MAXD>
 __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchArgs A) {
     __shared__ DevProblem sP;
     __shared__ BestRec sBest[kWavesPerBlock];
@@ -990,11 +992,15 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
             out[i] = 0;
         }
         uint64_t rest = o;
+        uint32_t c[kMaxTasks];  // the plan's choice per task (used by the walk over the variant paths)
+#pragma unroll
+        for (int i = 0; i < kMaxTasks; i++) c[i] = 0;
 #pragma unroll
         for (int i = 0; i < kMaxTasks; i++) {
             if (i < L) {
                 const uint32_t ci = static_cast<uint32_t>(rest % P->C[i]);
                 rest /= P->C[i];
+                c[i] = ci;
                 const int par = i > 0 ? P->parent[i] : 0;
                 int64_t dn = Dn[i];
                 if (has_vf && i > 0) dn = pick_below(out, par, i) * static_cast<int64_t>(P->fanout[i]);
@@ -1045,81 +1051,17 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
                 const double a = task_accuracy(t, dnL);
                 const double path = n >= 2 ? pre * a : a;
                 const double sum = first ? path : presum + path;
-                const double acc = sum / npd;
+                double acc = sum / npd;
+                if constexpr (MAXD > 0) {
+                    c[L] = cL;
+                    acc = path_objective<MAXD>(P, A.path_acc, c, Dn);
+                }
                 nfeas++;
                 if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
                     bacc = acc;
                     bw = workers;
                     bidx = idx;
                 }
-            }
-        }
-    }
-    nfeas = wave_sum(nfeas);
-    block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
-                     A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
-}
-
-// ---- kernel: whole plans per lane, objective from profiled path accuracies ------------------------------
-// The objective couples the tasks, so nothing is shared between plans: a lane takes a contiguous
-// stretch of the index range, decodes its first index once and then steps the choices like an odometer.
-template <int MAXD>
-__global__ void __launch_bounds__(kBlockThreads) path_search_kernel(SearchArgs A) {
-    __shared__ DevProblem sP;
-    __shared__ BestRec sBest[kWavesPerBlock];
-    stage_problem(&sP, A.P, sizeof(DevProblem));
-    __syncthreads();
-    const DevProblem *P = &sP;
-    const int m = blockIdx.y;
-    const int n = P->n_tasks;
-    const bool tie_index_only = A.tie_index_only != 0;
-    const uint64_t lanes = static_cast<uint64_t>(gridDim.x) * kBlockThreads;
-    const uint64_t span = A.end - A.begin;
-    const uint64_t per_lane = (span + lanes - 1) / lanes;
-    const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x;
-    uint64_t idx = A.begin + (t < span ? t * per_lane : span);
-    uint64_t idx_end = idx + per_lane;
-    if (idx_end > A.end || idx_end < idx) idx_end = A.end;
-    if (idx > A.end) idx = A.end;
-    int64_t Dn[kMaxTasks];
-#pragma unroll
-    for (int i = 0; i < kMaxTasks; i++) Dn[i] = A.Dn[static_cast<size_t>(m) * kMaxTasks + i];
-    uint32_t c[kMaxTasks];
-    {
-        uint64_t rest = idx;
-#pragma unroll
-        for (int i = 0; i < kMaxTasks; i++) {
-            c[i] = 0;
-            if (i < n) {
-                c[i] = static_cast<uint32_t>(rest % P->C[i]);
-                rest /= P->C[i];
-            }
-        }
-    }
-    double bacc = -1.0;
-    int32_t bw = kNever;
-    uint64_t bidx = ~0ull;
-    uint64_t nfeas = 0;
-    for (; idx < idx_end; ++idx) {
-        uint32_t mask;
-        int32_t workers;
-        double acc;
-        eval_plan(P, c, Dn, A.budget, A.W, mask, workers, acc);
-        if (mask == 0) {
-            acc = path_objective<MAXD>(P, A.path_acc, c, Dn);
-            nfeas++;
-            if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
-                bacc = acc;
-                bw = workers;
-                bidx = idx;
-            }
-        }
-        bool carry = true;
-#pragma unroll
-        for (int i = 0; i < kMaxTasks; i++) {
-            if (i < n && carry) {
-                if (++c[i] == P->C[i]) c[i] = 0;
-                else carry = false;
             }
         }
     }
@@ -1307,22 +1249,22 @@ hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool 
     return launch_combine_s<4>(A, has_presum, divide, range, stream);
 }
 
-hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, hipStream_t stream) {
+template <int MAXD>
+void launch_per_lane_depth(const SearchArgs &A, bool pv_batch, bool has_vf, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
     if (pv_batch) {
-        if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<true, true>), grid, block, 0, stream, A);
-        else hipLaunchKernelGGL((per_lane_search_kernel<true, false>), grid, block, 0, stream, A);
+        if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<true, true, MAXD>), grid, block, 0, stream, A);
+        else hipLaunchKernelGGL((per_lane_search_kernel<true, false, MAXD>), grid, block, 0, stream, A);
     } else {
-        if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<false, true>), grid, block, 0, stream, A);
-        else hipLaunchKernelGGL((per_lane_search_kernel<false, false>), grid, block, 0, stream, A);
+        if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<false, true, MAXD>), grid, block, 0, stream, A);
+        else hipLaunchKernelGGL((per_lane_search_kernel<false, false, MAXD>), grid, block, 0, stream, A);
     }
-    return hipGetLastError();
 }
 
-hipError_t launch_path_search(const SearchArgs &A, int longest_path, hipStream_t stream) {
-    const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
-    if (longest_path <= 4) hipLaunchKernelGGL(path_search_kernel<4>, grid, block, 0, stream, A);
-    else hipLaunchKernelGGL(path_search_kernel<kMaxTasks>, grid, block, 0, stream, A);
+hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels, hipStream_t stream) {
+    if (path_levels <= 0) launch_per_lane_depth<0>(A, pv_batch, has_vf, stream);
+    else if (path_levels <= 4) launch_per_lane_depth<4>(A, pv_batch, has_vf, stream);
+    else launch_per_lane_depth<kMaxTasks>(A, pv_batch, has_vf, stream);
     return hipGetLastError();
 }
 

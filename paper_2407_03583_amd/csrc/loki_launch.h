@@ -12,9 +12,10 @@ hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStrea
 hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool divide, bool range,
                           hipStream_t stream);
-hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, hipStream_t stream);
-// longest_path: tasks on the longest root-to-leaf chain (selects how many levels of the walk are compiled in)
-hipError_t launch_path_search(const SearchArgs &A, int longest_path, hipStream_t stream);
+// path_levels: 0, or with profiled path accuracies the number of tasks on the longest root-to-leaf chain
+// (selects how many levels of the walk over the variant paths are compiled in)
+hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels,
+                                  hipStream_t stream);
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_eval(const EvalArgs &A, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &A, hipStream_t stream);
