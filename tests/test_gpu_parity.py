@@ -420,3 +420,38 @@ def test_per_variant_factors_on_benchmark_profiles():
                 res = P.alloc_search([d], w.workers, w.slo_us, flags=flags, begin=lo, end=hi)[0]
                 ref = O.search(d, w.workers, w.slo_us, tie_index_only=bool(flags & TIE), begin=lo, end=hi)
                 check(res, ref, f"cfg{cfg} vf [{lo},{hi}) flags={flags}")
+
+
+def test_hardware_scaling_step_through_the_same_search():
+    """Step 1 of Section 4 (eq. (8)-(11)): only the most accurate variant of every task may be hosted
+    (replica limit 0 for the others, eq. (10)) and the winner is the plan with the fewest servers.  On
+    config 4's profiles, for demands from 0 to 160 QPS: the masked search against the checker, and
+    against the full search, which must return the same accuracy and server count wherever Step 1 has
+    a solution."""
+    import copy
+    w = wl.config(4)
+    p = w.pipeline
+    masked = copy.deepcopy(p)
+    v = 0
+    for i in range(p.n_tasks):
+        top = max(p.acc_ppm[v:v + p.n_variants[i]])
+        for k in range(p.n_variants[i]):
+            if p.acc_ppm[v + k] != top:
+                masked.max_replicas[v + k] = 0
+        v += p.n_variants[i]
+    P1, O1, P2 = binding.Problem(masked), oracle.Problem(masked), binding.Problem(p)
+    assert P1.num_candidates() == 16 ** 3                        # one variant, 0..3 replicas, 4 batch sizes
+    demands = list(range(0, 160_000, 2_500))
+    step1 = P1.alloc_search(demands, w.workers, w.slo_us)
+    full = P2.alloc_search(demands, w.workers, w.slo_us)
+    solved = 0
+    for d, s1, f in zip(demands, step1, full):
+        check(s1, O1.search(d, w.workers, w.slo_us), f"step 1 at {d}")
+        if s1.status == binding.LOKI_FOUND:
+            solved += 1
+            assert f.status == binding.LOKI_FOUND and bits(f.accuracy) == bits(s1.accuracy), d
+            assert f.workers_used == s1.workers_used, d
+        elif f.status == binding.LOKI_FOUND:
+            assert f.accuracy < step1[0].accuracy, d             # Step 2: accuracy is given up
+    assert 10 < solved < len(step1) and step1[0].status == binding.LOKI_FOUND
+    assert any(f.status == binding.LOKI_FOUND and s.status != binding.LOKI_FOUND for s, f in zip(step1, full))

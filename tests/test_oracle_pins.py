@@ -2,6 +2,7 @@
 something that is not itself -- a hand-derived example, closed forms, an
 exact-rational second implementation, and invariants the paper's constraints
 imply.  No GPU."""
+import copy
 import json
 import math
 import os
@@ -576,3 +577,58 @@ def test_objective_operation_order():
     assert (r * l[0] + r * l[1]) + r * l[2] != (r * l[2] + r * l[1]) + r * l[0]
     b = oracle.Problem(chain_or_star([-1, 0, 0, 0], [800000, 600000, 661725, 735795])).search(1000, 4, 100_000)
     assert b.found == 1 and b.accuracy == ((r * l[0] + r * l[1]) + r * l[2]) / 3.0
+
+
+# ---- the two steps of Section 4 through one search -------------------------------------------------------
+
+def mask_to_most_accurate(p):
+    """Step 1 (hardware scaling, eq. (8)-(11)) allows the most accurate variant of every task only
+    (eq. (10)): a copy of the inputs with the replica limit of every other variant set to zero."""
+    q = copy.deepcopy(p)
+    v = 0
+    for i in range(p.n_tasks):
+        k_i = p.n_variants[i]
+        top = max(p.acc_ppm[v:v + k_i])          # (variants that tie for the top accuracy all stay)
+        for k in range(k_i):
+            if p.acc_ppm[v + k] != top:
+                q.max_replicas[v + k] = 0
+        v += k_i
+    return q
+
+
+def test_hardware_scaling_step_is_the_search_over_the_most_accurate_variants():
+    """Step 1 minimises the servers subject to everything being served by the most accurate variants
+    (eq. (11)); Step 2 maximises accuracy (eq. (12)) and is needed only when Step 1 has no solution.
+    One search with the order (accuracy, workers, index) covers both: whenever Step 1 is feasible, the
+    full search returns the top accuracy with exactly Step 1's number of servers.  Checked by brute force
+    over the masked space with the exact-rational reference."""
+    agree = step1_feasible = step2_only = 0
+    for seed in range(300):
+        w = wl.random_small(seed, max_candidates=3000)
+        p = w.pipeline
+        masked = mask_to_most_accurate(p)
+        d = w.demand_mqps[0]
+        full = oracle.Problem(p).search(d, w.workers, w.slo_us, w.comm_us)
+        step1 = oracle.Problem(masked).search(d, w.workers, w.slo_us, w.comm_us)
+        # Step 1 by its definition: fewest servers among the feasible plans of the masked space
+        fewest = None
+        for idx in range(pyref.num_candidates(masked)):
+            r = pyref.evaluate(masked, idx, d, w.workers, w.slo_us, w.comm_us)
+            if not r["infeasible"] and (fewest is None or r["workers"] < fewest):
+                fewest = r["workers"]
+        assert (fewest is not None) == bool(step1.found), seed
+        if step1.found:
+            step1_feasible += 1
+            assert step1.workers == fewest
+            assert full.found and full.accuracy == step1.accuracy and full.workers == step1.workers, seed
+            agree += 1
+        elif full.found:
+            step2_only += 1
+            top, v = [], 0                                    # accuracy was given up
+            for i in range(p.n_tasks):
+                top.append(Fraction(max(p.acc_ppm[v:v + p.n_variants[i]]), 10**6))
+                v += p.n_variants[i]
+            paths = p.leaf_paths()
+            best_possible = sum((math.prod(top[i] for i in path) for path in paths), Fraction(0)) / len(paths)
+            assert Fraction(full.accuracy) < best_possible
+    assert step1_feasible >= 15 and step2_only >= 3
