@@ -192,6 +192,7 @@ def main() -> int:
     if not args.no_context:
         mix = binding.measure_valu_rate("search_mix")
         out["roofline"]["sustained_mix_Tlane_op_s"] = mix * 64 / 1e12
+        out["roofline"]["frac_of_sustained_mix"] = achieved / (mix * 64 / 1e12)
         out["roofline"]["sustained_u32_Tlane_op_s"] = binding.measure_valu_rate("v_add_u32") * 64 / 1e12
     if not args.no_cpu_baseline:
         import oracle
