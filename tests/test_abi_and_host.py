@@ -142,3 +142,25 @@ def test_decode_with_per_variant_batch_sizes():
                     assert batch[v + k] == (p.batch_size[b + beta[v + k]] if x[v + k] > 0 else 0)
                 v += p.n_variants[i]
                 b += p.n_batches[i]
+
+
+def test_bench_refuses_more_than_one_gpu_and_counts_operations():
+    """bench.py: more than one GPU is refused with a message (one GPU per run); the operation counts
+    behind `roofline.achieved` are the documented ones."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
+    sys.path.insert(0, root)
+    import bench
+    p5 = wl.config(5).pipeline
+    assert bench.algorithmic_lane_ops(4, 2, False, p5) == 3          # multiply, add, max/compare
+    assert bench.algorithmic_lane_ops(3, 1, False, wl.config(2).pipeline) == 2
+    assert bench.algorithmic_lane_ops(1, 1, False, p5) == 1
+    assert bench.algorithmic_lane_ops(4, 2, True, p5) == (20 * 4 + 30) + 50 + 3 * (20 * 4 + 30) / 64.0
+    assert abs(bench.VALU_PEAK_TLANEOPS - 39.3216) < 1e-9
+    # the HBM traffic figure is reported only for the sources it was measured with
+    t = bench.measured_traffic("cfg5_tree4_k4", "tabulated")
+    assert t is None or t == (451 + 1024) * 1024
+    assert bench.measured_traffic("cfg1_chain2_k3", "tabulated") is None
