@@ -244,3 +244,34 @@ def test_objective_operation_order_on_the_gpu():
         for flags in (0, LANE):
             res = P.alloc_search([1000], 8, 100_000, flags=flags)[0]
             assert agree(res, ref), (flags, res.as_tuple(), ref.as_tuple())
+
+
+def test_values_at_the_ends_of_their_ranges():
+    """Eight variants and eight batch sizes in one task, 255 replicas of a single variant in another, a
+    fan-out of 1024.00, the largest latency and throughputs that pass the range proof, accuracies 0 and 1."""
+    rng = random.Random(99)
+    # task 0: 8 variants x up to 3 replicas x 8 batch sizes = 524,288 choices
+    acc0 = [0, 1_000_000] + [rng.randint(1, 999_999) for _ in range(6)]
+    lat0, thr0 = [], []
+    for k in range(8):
+        for b in range(8):
+            lat0.append(rng.randint(1, 40_000))
+            thr0.append(rng.randint(0, 3_000_000))
+    # task 1: one variant, 0..255 replicas, two batch sizes; fan-out 4096 quarters
+    lat1 = [1 << 30, 1000]
+    thr1 = [(1 << 40), 9_000_000]
+    p = SimpleNamespace(n_tasks=2, parent=[-1, 0], fanout_q4=[4, 4096], n_variants=[8, 1], n_batches=[8, 2],
+                        batch_size=[1, 2, 3, 5, 8, 13, 21, 34, 1, 64], max_replicas=[3] * 8 + [255],
+                        acc_ppm=acc0 + [777_777], latency_us=lat0 + lat1, thr_mqps=thr0 + thr1)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n == (4 ** 8 * 8) * (256 * 2)
+    idxs = [0, n - 1] + [rng.randrange(n) for _ in range(4000)]
+    for demand, W, slo in ((2_000_000, 300, 2 * ((1 << 30) + 50_000)), (1_000, 20, 100_000), (0, 9, 90_000)):
+        for got, idx in zip(P.alloc_eval(idxs, demand, W, slo), idxs):
+            e = O.eval(idx, demand, W, slo)
+            assert (got.infeasible, got.workers, bits(got.accuracy)) == (e.infeasible, e.workers, bits(e.accuracy)), idx
+        for flags in (0, TIE, LANE):
+            res = P.alloc_search([demand], W, slo, flags=flags)[0]
+            ref = O.search_tabulated(demand, W, slo, tie_index_only=bool(flags & TIE))
+            assert agree(res, ref), (demand, flags, res.as_tuple(), ref.as_tuple())
