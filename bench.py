@@ -47,7 +47,7 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (451 + 1024) * 1024,
                           ("cfg5_tree4_k4", "per_lane"): (272 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "a79697aae3f149c1b38d4cef6fa0ae354017aff08f67f2b4bd0047cf1bef9a12"
+TRAFFIC_SOURCES_SHA256 = "9765c4a036f41e86a76bd882022fee1a1004e4dcdb15d6e02f6b4cb24bb97c24"
 
 
 def measured_traffic(workload: str, kernel: str):

@@ -566,8 +566,9 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // tasks strictly between the first and the last, tile of the first task's choices
 // in run order).  A wavefront keeps S*64 records of the last task in registers;
 // the block builds the MidVal/MidLim of every first-task choice in the tile once, then
-// each wavefront walks its part of the tile.  Per run of equal (w_rem, tl) it
-// takes the feasibility of its S*64 plans once (eq. (3), eq. (7)); per record it
+// each wavefront walks its part of the tile.  Per run (same latency left, and the same workers
+// left or more than the last task can ever use) it takes the feasibility of its S*64 plans
+// once (eq. (3), eq. (7)); per record it
 // then only forms the S*64 objectives (one fp64 multiply, one add each), keeps
 // their running maximum, and compares that with the lanes' best.
 template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE>
