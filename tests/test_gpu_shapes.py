@@ -275,3 +275,23 @@ def test_values_at_the_ends_of_their_ranges():
             res = P.alloc_search([demand], W, slo, flags=flags)[0]
             ref = O.search_tabulated(demand, W, slo, tie_index_only=bool(flags & TIE))
             assert agree(res, ref), (demand, flags, res.as_tuple(), ref.as_tuple())
+
+
+def test_handles_can_be_created_used_and_destroyed_many_times():
+    """Every handle owns pinned staging memory and events: 200 handles, each used once and closed, and
+    several handles used alternately on one stream, give the same answers throughout."""
+    w1, w2 = wl.config(1), wl.random_small(5)
+    ref1 = oracle.Problem(w1.pipeline).search(w1.demand_mqps[0], w1.workers, w1.slo_us)
+    ref2 = oracle.Problem(w2.pipeline).search(w2.demand_mqps[0], w2.workers, w2.slo_us, w2.comm_us)
+    for _ in range(200):
+        P = binding.Problem(w1.pipeline)
+        assert agree(P.alloc_search(w1.demand_mqps, w1.workers, w1.slo_us)[0], ref1)
+        P.close()
+    a, b, c = binding.Problem(w1.pipeline), binding.Problem(w2.pipeline), binding.Problem(w1.pipeline)
+    for _ in range(20):
+        assert agree(a.alloc_search(w1.demand_mqps, w1.workers, w1.slo_us)[0], ref1)
+        assert agree(b.alloc_search(w2.demand_mqps, w2.workers, w2.slo_us, w2.comm_us)[0], ref2)
+        assert agree(c.alloc_search(w1.demand_mqps, w1.workers, w1.slo_us, flags=LANE)[0], ref1)
+    for h in (a, b, c):
+        h.close()
+        h.close()   # closing twice is harmless
