@@ -474,6 +474,24 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         int at = d.path_len[i] - 1;
         for (int j = i; j >= 0; j = d.parent[j]) d.leaf_path[i][at--] = j;
     }
+    {  // steps that turn the first task's accuracy into the path values without the last task
+        const int L = n - 1;
+        auto push = [&](int op, int task) {
+            d.prog_op[d.n_prog] = int8_t(op);
+            d.prog_task[d.n_prog] = int8_t(task);
+            d.n_prog++;
+        };
+        for (int j = 0; j < L; j++) {
+            if (!d.is_leaf[j]) continue;
+            for (int q = 1; q < d.path_len[j]; q++) push(kStepMul, d.leaf_path[j][q]);
+            push(kStepLeaf, -1);
+        }
+        if (n >= 2) {
+            const int parL = d.parent[L];
+            for (int q = 1; q < d.path_len[parL]; q++) push(kStepMul, d.leaf_path[parL][q]);
+            push(kStepPre, -1);
+        }
+    }
     if (in->path_acc_ppm) {
         // profiled accuracy of every variant path, per leaf (Section 4.1 "Accuracy"); stored as the
         // fraction ppm / 10^6, one correctly rounded division each

@@ -13,6 +13,7 @@ constexpr int kMaxBatches = 8;
 constexpr int kBlockThreads = 256;          // 4 wavefronts of 64
 constexpr int kWavesPerBlock = kBlockThreads / 64;
 constexpr int kMidTile = 1024;              // most root-task choices staged in LDS per work item
+constexpr int kStepMul = 0, kStepLeaf = 1, kStepPre = 2;
 constexpr int32_t kNever = 0x7fffffff;      // latency marker: this choice can never be part of a feasible plan
 
 // Per-handle constants (Table 1 inputs after validation, plus derived radices).
@@ -37,6 +38,15 @@ struct DevProblem {
     int32_t pv_batch;                       // a batch size per hosted variant instead of one per task
     int32_t pad1;
     int32_t lat0_sorted[kMaxVariants * kMaxBatches];  // those latencies, ascending
+    // How the path values that do not involve the last task are formed from the first task's accuracy:
+    // a list of steps, each "multiply by the accuracy of task prog_task[q]" (kStepMul), "the value is a
+    // leaf's path value: add it to the sum of the earlier leaves and start again from the first task's
+    // accuracy" (kStepLeaf) or "the value is the product over the last task's ancestors" (kStepPre).
+    // Leaves in ascending order, every chain root first: the operation order of eq. (12)'s objective.
+    int32_t n_prog;
+    int32_t pad2;
+    int8_t prog_task[64];
+    int8_t prog_op[64];
     int32_t fanout[kMaxTasks];              // quarters, edge parent[i] -> i
     int32_t vf[kMaxTasks][kMaxVariants];    // quarters, by variant (4 everywhere when absent)
     int32_t batch_size[kMaxTasks][kMaxBatches];

@@ -578,6 +578,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     __shared__ MidVal sVal[kMidTile + 2];  // two spare entries: the record fetch runs ahead of the run's end
     __shared__ MidLim sLim[kMidTile];
     __shared__ uint32_t sChoice[kMidTile];  // first-task choice of each tile entry (cold path only)
+    __shared__ double sFac[64];             // the accuracies the path-value steps multiply by (per work item)
     __shared__ BestRec sBest[kWavesPerBlock];
     DevProblem *sP = reinterpret_cast<DevProblem *>(sPraw);  // only the head is valid
     stage_problem(sP, A.P, kHeadBytes);
@@ -683,21 +684,16 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         }
         // What the tasks strictly between the first and the last contribute (the same for the
         // whole tile): replicas, feasibility, latency along each chain without the first task.
-        double fa[kMaxTasks];
         int64_t flp[kMaxTasks];  // latency sum over root..j without the root
         int64_t w_far = 0;
         bool ok_far = true;
         int64_t lat0_cap = kNever - 1;  // largest first-task latency every other leaf's path tolerates
 #pragma unroll
-        for (int j = 0; j < kMaxTasks; j++) {
-            fa[j] = 1.0;
-            flp[j] = 0;
-        }
+        for (int j = 0; j < kMaxTasks; j++) flp[j] = 0;
 #pragma unroll
         for (int j = 1; j < kMaxTasks; j++) {
             if (j < L) {
                 const TaskRec rec = tab[sP->table_off[j] + cj[j]];
-                fa[j] = rec.a;
                 w_far += rec.w;
                 ok_far = ok_far && rec.lat != kNever;
                 flp[j] = pick_below(flp, sP->parent[j], j) + rec.lat;
@@ -723,61 +719,96 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         const uint32_t cnt = mid_count - tile_base < A.tile_len ? mid_count - tile_base : A.tile_len;
         const uint64_t base_f = static_cast<uint64_t>(C0) * f;  // index contribution of the tasks in between
 
-        __syncthreads();  // the previous item's tile is no longer being read
-        for (uint32_t e = threadIdx.x; e < cnt; e += kBlockThreads) {
-            uint32_t cM = 0;
-            double a0 = 1.0;
-            int64_t w0 = 0, lat0 = 0;
-            bool ok = ok_far;
-            if (n >= 2) {
-                cM = perm[tile_base + e];
-                const TaskRec rec = tab[cM];
-                a0 = rec.a;
-                w0 = rec.w;
-                lat0 = rec.lat;
-                ok = ok && rec.lat != kNever && lat0 <= lat0_cap;
+        // The accuracies the steps multiply by, one per step, for this combination of the tasks in
+        // between.  (The factors of the previous item were last read before its tile was published.)
+        if (threadIdx.x < static_cast<uint32_t>(sP->n_prog)) {
+            const int t = sP->prog_task[threadIdx.x];
+            if (t >= 0) sFac[threadIdx.x] = tab[sP->table_off[t] + pick32(cj, t)].a;
+        }
+        __syncthreads();  // the previous item's tile is no longer being read; the factors are visible
+        // Every thread builds its entries of the tile two at a time, side by side: the steps are read once
+        // per pair and applied to both.
+        constexpr int kSide = 2;
+        for (uint32_t e_first = threadIdx.x; e_first < cnt; e_first += kSide * kBlockThreads) {
+            uint32_t cMs[kSide];
+            double a0s[kSide], val[kSide], presum[kSide], pre[kSide];
+            int32_t w0s[kSide], lat0s[kSide];
+            bool oks[kSide];
+#pragma unroll
+            for (int k = 0; k < kSide; k++) {
+                const uint32_t e = e_first + k * kBlockThreads;
+                cMs[k] = 0;
+                a0s[k] = 1.0;
+                w0s[k] = 0;
+                lat0s[k] = 0;
+                oks[k] = ok_far;
+                if (n >= 2 && e < cnt) {
+                    cMs[k] = perm[tile_base + e];
+                    const TaskRec rec = tab[cMs[k]];
+                    a0s[k] = rec.a;
+                    w0s[k] = rec.w;
+                    lat0s[k] = rec.lat;
+                    oks[k] = ok_far && rec.lat != kNever && static_cast<int64_t>(rec.lat) <= lat0_cap;
+                }
+                val[k] = a0s[k];
+                presum[k] = 0.0;
+                pre[k] = 1.0;
             }
-            // path values root first: pp[j] = pp[parent[j]] * a_j  (eq. (12) objective, product stand-in)
-            double pp[kMaxTasks];
-#pragma unroll
-            for (int j = 0; j < kMaxTasks; j++) pp[j] = 1.0;
-            pp[0] = a0;
-#pragma unroll
-            for (int j = 1; j < kMaxTasks; j++)
-                if (j < L) pp[j] = pick_below(pp, sP->parent[j], j) * fa[j];
-            MidVal uv;
-            MidLim ul;
-            uv.presum = 0.0;
+            // path values root first (eq. (12) objective, product stand-in): value = a_0 * a_j1 * a_j2 ...
             bool first = true;
+            const int n_prog = uni(sP->n_prog);
+            for (int q = 0; q < n_prog; q++) {
+                const int op = uni(static_cast<int>(sP->prog_op[q]));
+                if (op == kStepMul) {
+                    const double fac = sFac[q];
 #pragma unroll
-            for (int j = 0; j < kMaxTasks; j++) {
-                if (j < L && sP->is_leaf[j]) {
-                    uv.presum = first ? pp[j] : uv.presum + pp[j];
+                    for (int k = 0; k < kSide; k++) val[k] = val[k] * fac;
+                } else if (op == kStepLeaf) {
+#pragma unroll
+                    for (int k = 0; k < kSide; k++) {
+                        presum[k] = first ? val[k] : presum[k] + val[k];
+                        val[k] = a0s[k];
+                    }
                     first = false;
+                } else {
+#pragma unroll
+                    for (int k = 0; k < kSide; k++) {
+                        pre[k] = val[k];
+                        val[k] = a0s[k];
+                    }
                 }
             }
-            uv.pre = n >= 2 ? pick_below(pp, parL, kMaxTasks) : 1.0;
-            int64_t tl = tl_base < 0 ? -1 : tl_base - lat0;
-            if (tl < 0) tl = -1;
-            if (tl > kNever - 1) tl = kNever - 1;
-            ul.tl = static_cast<int32_t>(tl);
-            const int64_t wr = w_room - w0;
-            ul.w_rem = (ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
-            // without a range every choice of the last task is admissible and the slot carries the end of
-            // the entry's run instead (tile relative; a run may go on beyond the tile)
-            ul.cl_lo = n >= 2 ? run_end[tile_base + e] - tile_base : e + 1;
-            ul.cl_cnt = CL;
-            if (RANGE) {
-                const uint64_t base = base_f + cM;  // index of the plan with the last task's choice 0
-                const uint64_t lo = A.begin > base ? (A.begin - base + strideL - 1) / strideL : 0;
-                uint64_t hi = A.end > base ? (A.end - base + strideL - 1) / strideL : 0;
-                if (hi > CL) hi = CL;
-                ul.cl_lo = static_cast<uint32_t>(lo < hi ? lo : hi);
-                ul.cl_cnt = static_cast<uint32_t>(hi > lo ? hi - lo : 0);
+#pragma unroll
+            for (int k = 0; k < kSide; k++) {
+                const uint32_t e = e_first + k * kBlockThreads;
+                if (e < cnt) {
+                    MidVal uv;
+                    MidLim ul;
+                    uv.pre = pre[k];
+                    uv.presum = presum[k];
+                    int64_t tl = tl_base < 0 ? -1 : tl_base - static_cast<int64_t>(lat0s[k]);
+                    if (tl < 0) tl = -1;
+                    if (tl > kNever - 1) tl = kNever - 1;
+                    ul.tl = static_cast<int32_t>(tl);
+                    const int64_t wr = w_room - static_cast<int64_t>(w0s[k]);
+                    ul.w_rem = (oks[k] && wr >= 0) ? static_cast<int32_t>(wr) : -1;
+                    // without a range every choice of the last task is admissible and the slot carries the
+                    // end of the entry's run instead (tile relative; a run may go on beyond the tile)
+                    ul.cl_lo = n >= 2 ? run_end[tile_base + e] - tile_base : e + 1;
+                    ul.cl_cnt = CL;
+                    if (RANGE) {
+                        const uint64_t base = base_f + cMs[k];  // index of the plan with the last task's choice 0
+                        const uint64_t lo = A.begin > base ? (A.begin - base + strideL - 1) / strideL : 0;
+                        uint64_t hi = A.end > base ? (A.end - base + strideL - 1) / strideL : 0;
+                        if (hi > CL) hi = CL;
+                        ul.cl_lo = static_cast<uint32_t>(lo < hi ? lo : hi);
+                        ul.cl_cnt = static_cast<uint32_t>(hi > lo ? hi - lo : 0);
+                    }
+                    sVal[e] = uv;
+                    sLim[e] = ul;
+                    sChoice[e] = cMs[k];
+                }
             }
-            sVal[e] = uv;
-            sLim[e] = ul;
-            sChoice[e] = cM;
         }
         __syncthreads();
 
