@@ -633,16 +633,16 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     // With an index range only the combinations the range touches are visited: far_span of them,
     // cyclically from far_first (the whole space: all far_count from 0).
     auto locate = [&](uint64_t item) {
-        r = static_cast<uint32_t>(item % A.mid_tiles);
+        r = uni(static_cast<uint32_t>(item % A.mid_tiles));
         const uint64_t t = item / A.mid_tiles;
-        f = (A.far_first + t % A.far_span) % A.far_count;
-        g = static_cast<uint32_t>(t / A.far_span);
+        f = uni64((A.far_first + t % A.far_span) % A.far_count);
+        g = uni(static_cast<uint32_t>(t / A.far_span));
         uint64_t rest = f;
 #pragma unroll
         for (int j = 1; j < kMaxTasks; j++) {
             cj[j] = 0;
             if (j < L) {
-                cj[j] = static_cast<uint32_t>(rest % sP->C[j]);
+                cj[j] = uni(static_cast<uint32_t>(rest % sP->C[j]));
                 rest /= sP->C[j];
             }
         }
@@ -693,15 +693,18 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 #pragma unroll
         for (int j = 1; j < kMaxTasks; j++) {
             if (j < L) {
+                // the same record in every lane: through readfirstlane, so that the sums, limits and
+                // selections that follow stay on the scalar unit
                 const TaskRec rec = tab[sP->table_off[j] + cj[j]];
-                w_far += rec.w;
-                ok_far = ok_far && rec.lat != kNever;
-                flp[j] = pick_below(flp, sP->parent[j], j) + rec.lat;
+                const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
+                w_far += rw;
+                ok_far = ok_far && rlat != kNever;
+                flp[j] = pick_below(flp, uni(sP->parent[j]), j) + rlat;
             }
         }
 #pragma unroll
         for (int j = 0; j < kMaxTasks; j++) {
-            if (j < L && sP->is_leaf[j]) {
+            if (j < L && uni(sP->is_leaf[j])) {
                 const int64_t room = A.budget[j] < 0 ? -1 : A.budget[j] - flp[j];
                 if (room < lat0_cap) lat0_cap = room;
             }
@@ -710,7 +713,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         int64_t tl_base = A.budget[L];  // latency left for the first and the last task together
         int parL = 0;
         if (n >= 2) {
-            parL = sP->parent[L];
+            parL = uni(sP->parent[L]);
             tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parL, kMaxTasks);
         }
         const int64_t w_room = static_cast<int64_t>(W) - w_far;
@@ -942,7 +945,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 #pragma unroll
             for (int j = 1; j < kMaxTasks; j++) {
                 if (j < L && carry) {
-                    if (++cj[j] == sP->C[j]) {
+                    if (++cj[j] == uni(sP->C[j])) {
                         cj[j] = 0;
                     } else {
                         carry = false;
