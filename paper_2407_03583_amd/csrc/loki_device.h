@@ -12,7 +12,7 @@ constexpr int kMaxVariants = 8;
 constexpr int kMaxBatches = 8;
 constexpr int kBlockThreads = 256;          // 4 wavefronts of 64
 constexpr int kWavesPerBlock = kBlockThreads / 64;
-constexpr int kMidTile = 1024;              // most root-task choices staged in LDS per work item
+constexpr int kMidTile = 512;               // most root-task choices staged in LDS per work item
 constexpr int kStepMul = 0, kStepLeaf = 1, kStepPre = 2;
 constexpr int32_t kNever = 0x7fffffff;      // latency marker: this choice can never be part of a feasible plan
 

@@ -572,7 +572,7 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // then only forms the S*64 objectives (one fp64 multiply, one add each), keeps
 // their running maximum, and compares that with the lanes' best.
 template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE>
-__global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(4))) combine_kernel(SearchArgs A) {
+__global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(5))) combine_kernel(SearchArgs A) {
     constexpr uint32_t kHeadBytes = offsetof(DevProblem, lat);
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
     __shared__ MidVal sVal[kMidTile + 2];  // two spare entries: the record fetch runs ahead of the run's end

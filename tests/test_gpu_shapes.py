@@ -113,9 +113,9 @@ def test_deep_chain_of_eight_tasks():
 
 def test_every_tile_length_with_a_ragged_last_tile():
     """The launch shortens the tile of root-task choices when a call has few work items.  One chain,
-    root with 7 x 10 x 9 x 3 = 1,890 choices, searched for 1, 10 and 24 demand points: the three calls
-    land on tiles of 256, 512 and 1,024 entries (the library's thresholds), each with several tiles and
-    a last tile that is not full."""
+    root with 7 x 10 x 9 x 3 = 1,890 choices, searched for 1, 10 and 24 demand points: the calls land on
+    tiles of 256 entries (one point) and of 512 (the library's thresholds), each with several tiles and a
+    last tile that is not full."""
     rng = random.Random(33)
     a0, l0, t0 = profile(rng, 3, [1, 2, 4])
     a1, l1, t1 = profile(rng, 2, [2, 8])
