@@ -44,10 +44,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (426 + 1024) * 1024,
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (431 + 1024) * 1024,
                           ("cfg5_tree4_k4", "per_lane"): (272 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "c3ce4b991377808b96b681be8fec2526b2c8537a0bc8d1bed45560ab37be3969"
+TRAFFIC_SOURCES_SHA256 = "f9a952fc8c14dbd40f306db58f79a3999a3bb0ec92c265b43742ad5d523284a8"
 
 
 def measured_traffic(workload: str, kernel: str):
