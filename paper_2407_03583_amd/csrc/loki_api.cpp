@@ -426,7 +426,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
             for (int bi = 0; bi < nb; bi++) {
                 const int64_t lat = in->latency_us[t + k * nb + bi], thr = in->thr_mqps[t + k * nb + bi];
                 if (lat < 1 || lat > (int64_t(1) << 30) || thr < 0 || thr > (int64_t(1) << 40)) rc = LOKI_E_RANGE;
-                d.lat[i][k][bi] = lat;
+                d.lat[i][k][bi] = int32_t(lat);  // range-checked above
                 if (thr > (int64_t(1) << 54) / scale) rc = LOKI_E_RANGE;  // keeps 255 replicas * thr * scale below 2^63
                 d.thr_s[i][k][bi] = thr * scale;
             }

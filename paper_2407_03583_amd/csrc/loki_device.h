@@ -54,7 +54,7 @@ struct DevProblem {
     uint64_t stride[kMaxTasks];             // prod_{j<i} C_j
     uint64_t magic[kMaxTasks][kMaxVariants];  // ceil(2^36 / radix): (c * magic) >> 36 = c / radix for c * radix <= 2^36
     uint64_t magic_nb[kMaxTasks];           // ceil(2^36 / |B_i|)
-    int64_t lat[kMaxTasks][kMaxVariants][kMaxBatches];    // microseconds
+    int32_t lat[kMaxTasks][kMaxVariants][kMaxBatches];    // microseconds (at most 2^30)
     int64_t thr_s[kMaxTasks][kMaxVariants][kMaxBatches];  // throughput * 4^depth
     // profiled accuracies of the variant paths (only the kernels that stage the whole block use these)
     int32_t has_path;                       // a table per leaf is present

@@ -92,7 +92,7 @@ struct TaskOut {
     int32_t w;          // sum of replicas
     int32_t any;        // hosts something
     int64_t rem;        // unserved demand
-    int64_t maxlat;     // largest latency among variants in use
+    int32_t maxlat;     // largest latency among variants in use
     int64_t weighted;   // sum routed * acc_ppm
     int32_t first_acc;  // accuracy of the first hosted variant in route order
     int64_t outflow;    // sum routed * variant factor: what the task creates per unit of child fan-out
@@ -129,15 +129,15 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         w += static_cast<int32_t>(x);
     }
     const uint32_t beta_task = c;
-    int64_t rem = Dn, maxlat = 0, weighted = 0, outflow = 0;
-    int32_t any = 0, first_acc = 0;
+    int64_t rem = Dn, weighted = 0, outflow = 0;
+    int32_t any = 0, first_acc = 0, maxlat = 0;
     constexpr bool has_vf = VF;
     for (int r = 0; r < K; r++) {
         const int k = P->order[i][r];
         const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
         const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
         const int64_t cap = x * P->thr_s[i][k][beta];
-        const int64_t lat = P->lat[i][k][beta];
+        const int32_t lat = P->lat[i][k][beta];
         const int32_t acc = P->acc[i][k];
         const int64_t routed = rem < cap ? rem : cap;
         const bool hosted = x > 0;
