@@ -45,9 +45,9 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
 MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (431 + 1024) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (272 + 1024) * 1024}
+                          ("cfg5_tree4_k4", "per_lane"): (268 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "f9a952fc8c14dbd40f306db58f79a3999a3bb0ec92c265b43742ad5d523284a8"
+TRAFFIC_SOURCES_SHA256 = "a4f2b98107afdbc2236420fb7b519ced7e0a7b8c64e9b1cefc7466e927e14ba7"
 
 
 def measured_traffic(workload: str, kernel: str):
