@@ -117,7 +117,11 @@ def main() -> int:
         variant.append("path_tables")
     if variant:
         w.name += "+" + "+".join(variant)
-    args.per_lane = args.per_lane or args.variant_factors or args.path_tables  # what the library does anyway
+    # what the library does anyway: whole plans per lane with path tables, and with per-variant factors
+    # unless every other task is a child of the first one (then the tabulated kernels run class by class)
+    star = all(par == 0 for par in w.pipeline.parent[1:]) and w.pipeline.n_tasks >= 2
+    by_class = args.variant_factors and star and not args.per_lane and not args.path_tables
+    args.per_lane = args.per_lane or args.path_tables or (args.variant_factors and not by_class)
     P = binding.Problem(w.pipeline)
     n = P.num_candidates()
     m = len(w.demand_mqps)
@@ -171,7 +175,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "seed": w.seed, "candidates": n, "demand_points": m,
                    "index_end": end, "evaluations_per_step": evaluations,
-                   "kernel": ("path" if args.path_tables else "per_lane") if args.per_lane else "tabulated",
+                   "kernel": ("path" if args.path_tables else "per_lane") if args.per_lane
+                   else ("tabulated_by_class" if by_class else "tabulated"),
                    "feasible_fraction_point0": first[0].n_feasible / end},
         "kernel_ms": {"task_tables": sum(k[0] for k in kernel_ms) / len(kernel_ms), "search": main_ms,
                       "final_merge": sum(k[2] for k in kernel_ms) / len(kernel_ms)},

@@ -118,8 +118,11 @@ typedef struct {
                                     r(i,k) of eq. (1) in quarters, 1..64.  With it the requests task i creates
                                     for a child j are sum_k routed(i,k) * r(i,k) * fanout_q4[j] (Section 5.1:
                                     outgoing = incoming * multFactor * branchRatio), a child's demand depends
-                                    on its parent's part of the plan, tasks work in units of milli-QPS /
-                                    16^depth, and every search runs with LOKI_SEARCH_PER_LANE. */
+                                    on its parent's part of the plan and tasks work in units of milli-QPS /
+                                    16^depth.  Searches score whole plans per lane (LOKI_SEARCH_PER_LANE),
+                                    except where every other task is a child of task 0: a child's demand then
+                                    depends on task 0's choice only through the requests it creates, and the
+                                    tabulated kernels run once per distinct amount (same results). */
     int32_t per_variant_batch;   /* 0: one batch size per task.  1: a batch size per hosted variant, the y(i,k)
                                     of Section 4.1 "Output" and eq. (4); see the index layout above */
     const int32_t *path_acc_ppm; /* NULL, or the profiled end-to-end accuracy A-hat(p) of every variant path

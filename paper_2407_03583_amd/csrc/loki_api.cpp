@@ -54,6 +54,36 @@ Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M) {
     return l;
 }
 
+// Per-variant factors on a tree whose other tasks all hang off the first task: the search runs over
+// (demand point, class) pairs, at most kClassBatch of them per set of launches.
+constexpr int64_t kMaxClassPoints = 65535;
+constexpr int32_t kClassBatch = 1024;
+
+// Whether a handle's searches can run class by class: per-variant factors, product objective, every
+// other task a child of the first one, the first task's choices orderable into runs, and tables small
+// enough to keep kClassBatch copies of them in the workspace.
+bool class_search_applies(const loki_problem *p);
+
+struct ClassLayout {
+    size_t off_P, off_vDn, off_vOut, off_vCount, off_vPoint, off_batch, off_class_results, off_results, total;
+    Layout batch;  // offsets inside the batch region (its off_P / off_Dn are not used)
+};
+
+ClassLayout class_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M) {
+    ClassLayout l;
+    l.off_P = 0;
+    l.off_vDn = cb;
+    l.off_vOut = align_up(l.off_vDn + size_t(kMaxClassPoints) * kMaxTasks * sizeof(int64_t));
+    l.off_vCount = align_up(l.off_vOut + size_t(kMaxClassPoints) * sizeof(int64_t));
+    l.off_vPoint = align_up(l.off_vCount + size_t(kMaxClassPoints) * sizeof(uint32_t));
+    l.off_batch = align_up(l.off_vPoint + size_t(kMaxClassPoints) * sizeof(int32_t));
+    l.batch = search_layout(0, table_total, c0, kClassBatch);
+    l.off_class_results = l.off_batch + l.batch.off_results;
+    l.off_results = align_up(l.off_batch + l.batch.total);
+    l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
+    return l;
+}
+
 struct EvalLayout {
     size_t off_P, off_idx, off_out, total;
 };
@@ -80,6 +110,9 @@ struct loki_problem {
     int32_t sum_r[kMaxTasks];   // sum of the replica limits of the task
     uint64_t n_candidates;
     std::vector<double> path_acc;  // profiled path accuracies as fractions (ppm / 10^6), all leaves
+    // pinned staging of the (demand point, class) descriptors: [Dn 8 int64 | amount int64 | count u32 | point i32] arrays
+    unsigned char *class_staging = nullptr;
+    bool star = false;  // every other task is a child of the first task
     // pinned staging: [DevProblem, path accuracies | Dn (cap_points * 8 int64) | results (cap_points)]
     unsigned char *staging = nullptr;
     int64_t cap_points = 0;
@@ -185,17 +218,268 @@ int check_scalars(int32_t workers, int64_t slo_us, int64_t comm_us) {
     return LOKI_OK;
 }
 
+// What choice c of the first task does with demand D (eq. (2), Algorithm 1's fill rule; the first task's
+// units are milli-QPS): whether it serves all of it, and the requests it creates per unit of a child's
+// fan-out, sum_k routed(k) * r(0,k) (eq. (1) with per-variant factors).  Mirrors the kernels' eval_task.
+bool first_task_outflow(const loki_problem *p, uint64_t c, int64_t D, int64_t *outflow) {
+    const DevProblem &d = p->dev;
+    const int K = d.K[0], nb = d.nb[0];
+    int32_t x[kMaxVariants], beta[kMaxVariants];
+    for (int k = 0; k < K; k++) {
+        const uint64_t g = c % d.radix[0][k];
+        c /= d.radix[0][k];
+        if (d.pv_batch) {
+            x[k] = g == 0 ? 0 : int32_t((g - 1) / nb) + 1;
+            beta[k] = g == 0 ? 0 : int32_t((g - 1) % nb);
+        } else {
+            x[k] = int32_t(g);
+        }
+    }
+    if (!d.pv_batch)
+        for (int k = 0; k < K; k++) beta[k] = int32_t(c);
+    int64_t rem = D, out = 0;
+    bool any = false;
+    for (int o = 0; o < K; o++) {
+        const int k = d.order[0][o];
+        if (x[k] == 0) continue;
+        const int64_t cap = int64_t(x[k]) * d.thr_s[0][k][beta[k]];
+        const int64_t routed = std::min(rem, cap);
+        out += routed * int64_t(d.vf[0][k]);
+        rem -= routed;
+        any = true;
+    }
+    *outflow = out;
+    return any && rem == 0;
+}
+
+// The (demand point, class) pairs of a call: per demand point the distinct amounts of requests the
+// first task's usable choices create, ascending, with the number of choices per amount.
+struct ClassPoints {
+    std::vector<int64_t> Dn;        // [n][kMaxTasks]
+    std::vector<int64_t> amount;    // [n]
+    std::vector<uint32_t> count;    // [n]
+    std::vector<int32_t> point;     // [n]
+};
+
+int build_class_points(const loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, ClassPoints &cp) {
+    std::vector<int64_t> amounts;
+    for (int32_t m = 0; m < n_demand; m++) {
+        int64_t Dn[kMaxTasks];
+        const int rc = task_demand(p, demand_mqps[m], Dn);  // range proof with the largest factors
+        if (rc) return rc;
+        amounts.clear();
+        for (uint64_t c = 0; c < p->dev.C[0]; c++) {
+            int64_t out;
+            if (first_task_outflow(p, c, demand_mqps[m], &out)) amounts.push_back(out);
+        }
+        std::sort(amounts.begin(), amounts.end());
+        for (size_t a = 0; a < amounts.size();) {
+            size_t b = a;
+            while (b < amounts.size() && amounts[b] == amounts[a]) b++;
+            if (int64_t(cp.amount.size()) >= kMaxClassPoints) return LOKI_E_ARG;  // caller falls back
+            cp.amount.push_back(amounts[a]);
+            cp.count.push_back(uint32_t(b - a));
+            cp.point.push_back(m);
+            for (int i = 0; i < kMaxTasks; i++)
+                cp.Dn.push_back(i == 0 ? demand_mqps[m] : (i < p->n ? amounts[a] * int64_t(p->fanout_q4[i]) : 0));
+            a = b;
+        }
+    }
+    return LOKI_OK;
+}
+
+// Launch configuration and launches of the tabulated kernels (per-task tables, run order, the kernel
+// that visits every plan) for the A.M points A describes.  root_choices: the most first-task choices any
+// point visits (all of them, or the largest class).  before_search / after_search: events recorded around
+// the kernel that visits every plan, or null.
+int launch_tabulated(loki_problem *p, SearchArgs A, uint32_t root_choices, uint64_t index_begin, uint64_t index_end,
+                     hipStream_t stream, hipEvent_t before_search, hipEvent_t after_search) {
+    const int n = p->n, L = n - 1;
+    const uint64_t span = index_end - index_begin;
+    const uint32_t n_points = static_cast<uint32_t>(A.M);
+    const uint32_t max_bpm = std::max<uint32_t>(1u, (kTargetBlocks + n_points - 1) / n_points);
+    const uint32_t CL = p->dev.C[L];
+    const int slots = CL >= 512 ? 8 : 4;
+    const uint32_t chunk = 64u * slots;
+    const uint64_t strideL = p->dev.stride[L];
+    uint64_t F = 1;
+    for (int j = 1; j < L; j++) F *= p->dev.C[j];
+    const uint32_t C0 = n >= 2 ? p->dev.C[0] : 1u;
+    const uint32_t mid_count = std::max<uint32_t>(1u, std::min(root_choices, C0));
+    A.far_count = F;
+    A.tile_len = kMidTile;
+    A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
+    A.far_first = 0;
+    A.far_span = F;
+    if (span == 0) {
+        A.cl_first = 0;
+        A.chunk_groups = 0;
+        A.cpb = 1;
+        A.items = 0;
+    } else {
+        const uint32_t cl_first = static_cast<uint32_t>(index_begin / strideL);
+        const uint32_t cl_last = static_cast<uint32_t>((index_end - 1) / strideL);
+        const uint32_t n_chunks = (cl_last - cl_first + 1 + chunk - 1) / chunk;
+        A.cl_first = cl_first;
+        A.cpb = 1;
+        while (A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
+        A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
+        // a range shorter than one step of the last task's choice touches only some of the
+        // combinations of the tasks in between, in cyclic order from that of its first index
+        if (span < strideL) {
+            const uint64_t o_first = index_begin % strideL;  // position among all tasks but the last
+            const uint64_t touched = (o_first % C0 + span + C0 - 1) / C0;
+            if (touched < F) {
+                A.far_first = o_first / C0;
+                A.far_span = touched;
+            }
+        }
+        A.items = uint64_t(A.chunk_groups) * A.far_span * A.mid_tiles;
+        // a search with few work items gets shorter ones: blocks that meet many feasible plans
+        // run long, and only spare items let the others take over the rest
+        while (A.tile_len > kMinTile && A.items * n_points < kFewItems) {
+            A.tile_len /= 2;
+            A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
+            A.items = uint64_t(A.chunk_groups) * A.far_span * A.mid_tiles;
+        }
+    }
+    A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(A.items, 1), max_bpm));
+    if (A.items > (uint64_t(1) << 62) / A.blocks_per_m) A.blocks_per_m = 1;  // keep items*block in 64 bits
+    const bool range = !(index_begin == 0 && index_end == p->n_candidates);
+    const int np = p->dev.n_paths;
+    const bool divide = (np & (np - 1)) != 0;
+    LOKI_HIP(launch_task_table(A, p->dev.table_total, stream));
+    if (n >= 2) LOKI_HIP(launch_root_order(A, stream));
+    if (before_search) LOKI_HIP(hipEventRecord(before_search, stream));
+    LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, stream));
+    if (after_search) LOKI_HIP(hipEventRecord(after_search, stream));
+    LOKI_HIP(launch_final_reduce(A, stream));
+    return LOKI_OK;
+}
+
+bool class_search_applies(const loki_problem *p) {
+    return p->dev.has_vf && !p->dev.has_path && p->star && p->dev.table_total <= (1u << 16) &&
+           uint64_t(p->dev.sum_r0 + 1) * uint64_t(p->dev.n_lat0) + 1 <= 4096;
+}
+
+int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers,
+                         int64_t slo_us, int64_t comm_us, uint32_t flags, uint64_t index_begin, uint64_t index_end,
+                         void *d_workspace, size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed,
+                         void **results_at) {
+    const size_t cb = const_block(p);
+    const ClassLayout lay = class_layout(cb, p->dev.table_total, p->dev.C[0], n_demand);
+    if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
+        return LOKI_E_WORKSPACE;
+    if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
+    ClassPoints cp;
+    int rc = build_class_points(p, demand_mqps, n_demand, cp);
+    if (rc) return rc;
+    const int64_t V = int64_t(cp.amount.size());
+
+    rc = ensure_staging(p, n_demand);
+    if (rc) return rc;
+    if (p->staged_pending) {  // an earlier call's copies may still be reading the staging buffers
+        LOKI_HIP(hipEventSynchronize(p->staged));
+        p->staged_pending = false;
+    }
+    const size_t per_point = kMaxTasks * sizeof(int64_t) + sizeof(int64_t) + sizeof(uint32_t) + sizeof(int32_t);
+    if (!p->class_staging) {
+        void *ptr = nullptr;
+        LOKI_HIP(hipHostMalloc(&ptr, size_t(kMaxClassPoints) * per_point, hipHostMallocDefault));
+        p->class_staging = static_cast<unsigned char *>(ptr);
+    }
+    unsigned char *ws = static_cast<unsigned char *>(d_workspace);
+    fill_const_block(p);
+    LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, cb, hipMemcpyHostToDevice, stream));
+    if (V > 0) {
+        unsigned char *h = p->class_staging;
+        const size_t nDn = size_t(V) * kMaxTasks * sizeof(int64_t), nOut = size_t(V) * sizeof(int64_t),
+                     nCount = size_t(V) * sizeof(uint32_t), nPoint = size_t(V) * sizeof(int32_t);
+        std::memcpy(h, cp.Dn.data(), nDn);
+        std::memcpy(h + nDn, cp.amount.data(), nOut);
+        std::memcpy(h + nDn + nOut, cp.count.data(), nCount);
+        std::memcpy(h + nDn + nOut + nCount, cp.point.data(), nPoint);
+        LOKI_HIP(hipMemcpyAsync(ws + lay.off_vDn, h, nDn, hipMemcpyHostToDevice, stream));
+        LOKI_HIP(hipMemcpyAsync(ws + lay.off_vOut, h + nDn, nOut, hipMemcpyHostToDevice, stream));
+        LOKI_HIP(hipMemcpyAsync(ws + lay.off_vCount, h + nDn + nOut, nCount, hipMemcpyHostToDevice, stream));
+        LOKI_HIP(hipMemcpyAsync(ws + lay.off_vPoint, h + nDn + nOut + nCount, nPoint, hipMemcpyHostToDevice, stream));
+    }
+    LOKI_HIP(hipEventRecord(p->staged, stream));
+    p->staged_pending = true;
+
+    MergeArgs G;
+    std::memset(&G, 0, sizeof(G));
+    G.results = d_results ? d_results : static_cast<void *>(ws + lay.off_results);
+    if (results_at) *results_at = G.results;
+    G.M = n_demand;
+    G.tie_index_only = (flags & LOKI_TIE_INDEX_ONLY) ? 1u : 0u;
+    if (timed) LOKI_HIP(hipEventRecord(p->ev[0], stream));
+    LOKI_HIP(launch_results_init(G, stream));
+    if (timed && V == 0) {
+        LOKI_HIP(hipEventRecord(p->ev[1], stream));
+        LOKI_HIP(hipEventRecord(p->ev[2], stream));
+    }
+
+    SearchArgs A;
+    std::memset(&A, 0, sizeof(A));
+    unsigned char *bw = ws + lay.off_batch;
+    A.P = reinterpret_cast<const DevProblem *>(ws + lay.off_P);
+    A.table = reinterpret_cast<TaskRec *>(bw + lay.batch.off_table);
+    A.recs = reinterpret_cast<BestRec *>(bw + lay.batch.off_recs);
+    A.perm = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm);
+    A.run_end = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run);
+    A.results = ws + lay.off_class_results;
+    path_budgets(p, slo_us, comm_us, A.budget);
+    A.begin = index_begin;
+    A.end = index_end;
+    A.W = workers;
+    {
+        int64_t others = 0;
+        for (int i = 1; i < p->n; i++) others += p->sum_r[i];
+        A.w_free = static_cast<int32_t>(std::max<int64_t>(int64_t(workers) - others, -1));
+    }
+    A.tie_index_only = G.tie_index_only;
+    for (int64_t v0 = 0; v0 < V; v0 += kClassBatch) {
+        const int32_t nb = int32_t(std::min<int64_t>(kClassBatch, V - v0));
+        A.M = nb;
+        A.Dn = reinterpret_cast<const int64_t *>(ws + lay.off_vDn) + size_t(v0) * kMaxTasks;
+        A.class_out = reinterpret_cast<const int64_t *>(ws + lay.off_vOut) + v0;
+        A.root_count = reinterpret_cast<const uint32_t *>(ws + lay.off_vCount) + v0;
+        uint32_t most = 1;
+        for (int32_t j = 0; j < nb; j++) most = std::max(most, cp.count[size_t(v0 + j)]);
+        const bool first = v0 == 0, last = v0 + nb >= V;
+        rc = launch_tabulated(p, A, most, index_begin, index_end, stream, timed && first ? p->ev[1] : nullptr,
+                              timed && last ? p->ev[2] : nullptr);
+        if (rc) return rc;
+        G.class_results = A.results;
+        G.point = reinterpret_cast<const int32_t *>(ws + lay.off_vPoint) + v0;
+        G.n = nb;
+        LOKI_HIP(launch_class_merge(G, stream));
+    }
+    if (timed) LOKI_HIP(hipEventRecord(p->ev[3], stream));
+    return LOKI_OK;
+}
+
+// results_at (optional): where on the device the results of the demand points are written.
 int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers, int64_t slo_us,
                    int64_t comm_us, uint32_t flags, uint64_t index_begin, uint64_t index_end, void *d_workspace,
-                   size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed) {
+                   size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed, void **results_at) {
     if (!p || !demand_mqps || !d_workspace) return LOKI_E_NULL;
     if (n_demand < 1 || n_demand > LOKI_MAX_DEMAND_POINTS) return LOKI_E_ARG;
     if (flags & ~(LOKI_TIE_INDEX_ONLY | LOKI_SEARCH_PER_LANE)) return LOKI_E_ARG;
     if (index_begin > index_end || index_end > p->n_candidates) return LOKI_E_ARG;
-    // a task's demand depends on its parent's part of the plan / the objective couples the tasks
-    if (p->dev.has_vf || p->dev.has_path) flags |= LOKI_SEARCH_PER_LANE;
     int rc = check_scalars(workers, slo_us, comm_us);
     if (rc) return rc;
+    // Per-variant factors: a task's demand depends on its parent's part of the plan.  Where every other
+    // task is a child of the first one, that dependence is one number per first-task choice (the requests
+    // it creates), and the tabulated kernels run once per distinct value; otherwise whole plans per lane.
+    if (class_search_applies(p) && !(flags & LOKI_SEARCH_PER_LANE)) {
+        rc = enqueue_class_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
+                                  d_workspace, workspace_bytes, stream, d_results, timed, results_at);
+        if (rc != LOKI_E_ARG) return rc;  // LOKI_E_ARG: too many classes, take the general path
+    }
+    // the objective couples the tasks
+    if (p->dev.has_vf || p->dev.has_path) flags |= LOKI_SEARCH_PER_LANE;
     const size_t cb = const_block(p);
     const Layout lay = search_layout(cb, p->dev.table_total, p->dev.C[0], n_demand);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
@@ -231,6 +515,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     A.perm = reinterpret_cast<uint32_t *>(ws + lay.off_perm);
     A.run_end = reinterpret_cast<uint32_t *>(ws + lay.off_run);
     A.results = d_results ? d_results : static_cast<void *>(ws + lay.off_results);
+    if (results_at) *results_at = A.results;
     A.path_acc = device_path_acc(p, ws);
     path_budgets(p, slo_us, comm_us, A.budget);
     A.begin = index_begin;
@@ -273,63 +558,13 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         if (p->dev.has_path)
             for (int i = 0; i < n; i++) path_levels = std::max(path_levels, p->dev.path_len[i]);
         LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, path_levels, stream));
+        if (timed) LOKI_HIP(hipEventRecord(p->ev[2], stream));
+        LOKI_HIP(launch_final_reduce(A, stream));
     } else {
-        const uint32_t CL = p->dev.C[L];
-        const int slots = CL >= 512 ? 8 : 4;
-        const uint32_t chunk = 64u * slots;
-        const uint64_t strideL = p->dev.stride[L];
-        uint64_t F = 1;
-        for (int j = 1; j < L; j++) F *= p->dev.C[j];
-        const uint32_t mid_count = n >= 2 ? p->dev.C[0] : 1u;
-        A.far_count = F;
-        A.tile_len = kMidTile;
-        A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
-        A.far_first = 0;
-        A.far_span = F;
-        if (span == 0) {
-            A.cl_first = 0;
-            A.chunk_groups = 0;
-            A.cpb = 1;
-            A.items = 0;
-        } else {
-            const uint32_t cl_first = static_cast<uint32_t>(index_begin / strideL);
-            const uint32_t cl_last = static_cast<uint32_t>((index_end - 1) / strideL);
-            const uint32_t n_chunks = (cl_last - cl_first + 1 + chunk - 1) / chunk;
-            A.cl_first = cl_first;
-            A.cpb = 1;
-            while (A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
-            A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
-            // a range shorter than one step of the last task's choice touches only some of the
-            // combinations of the tasks in between, in cyclic order from that of its first index
-            if (span < strideL) {
-                const uint64_t o_first = index_begin % strideL;  // position among all tasks but the last
-                const uint64_t touched = (o_first % mid_count + span + mid_count - 1) / mid_count;
-                if (touched < F) {
-                    A.far_first = o_first / mid_count;
-                    A.far_span = touched;
-                }
-            }
-            A.items = uint64_t(A.chunk_groups) * A.far_span * A.mid_tiles;
-            // a search with few work items gets shorter ones: blocks that meet many feasible plans
-            // run long, and only spare items let the others take over the rest
-            while (A.tile_len > kMinTile && A.items * n_demand < kFewItems) {
-                A.tile_len /= 2;
-                A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
-                A.items = uint64_t(A.chunk_groups) * A.far_span * A.mid_tiles;
-            }
-        }
-        A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(A.items, 1), max_bpm));
-        if (A.items > (uint64_t(1) << 62) / A.blocks_per_m) A.blocks_per_m = 1;  // keep items*block in 64 bits
-        const bool range = !(index_begin == 0 && index_end == p->n_candidates);
-        const int np = p->dev.n_paths;
-        const bool divide = (np & (np - 1)) != 0;
-        LOKI_HIP(launch_task_table(A, p->dev.table_total, stream));
-        if (n >= 2) LOKI_HIP(launch_root_order(A, stream));
-        if (timed) LOKI_HIP(hipEventRecord(p->ev[1], stream));
-        LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, stream));
+        rc = launch_tabulated(p, A, n >= 2 ? p->dev.C[0] : 1u, index_begin, index_end, stream,
+                              timed ? p->ev[1] : nullptr, timed ? p->ev[2] : nullptr);
+        if (rc) return rc;
     }
-    if (timed) LOKI_HIP(hipEventRecord(p->ev[2], stream));
-    LOKI_HIP(launch_final_reduce(A, stream));
     if (timed) LOKI_HIP(hipEventRecord(p->ev[3], stream));
     return LOKI_OK;
 }
@@ -470,6 +705,8 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
     d.n_paths = 0;
     for (int i = 0; i < n; i++) d.n_paths += d.is_leaf[i];
     p->n_candidates = N;
+    p->star = n >= 2;
+    for (int i = 1; i < n; i++) p->star = p->star && d.parent[i] == 0;
     for (int i = 0; i < n; i++) {  // chain root..i, root first
         int at = d.path_len[i] - 1;
         for (int j = i; j >= 0; j = d.parent[j]) d.leaf_path[i][at--] = j;
@@ -528,6 +765,7 @@ void loki_problem_destroy(loki_problem_t *p) {
     if (!p) return;
     if (p->staged_pending && p->staged) (void)hipEventSynchronize(p->staged);
     if (p->staging) (void)hipHostFree(p->staging);
+    if (p->class_staging) (void)hipHostFree(p->class_staging);
     if (p->staged) (void)hipEventDestroy(p->staged);
     for (auto e : p->ev)
         if (e) (void)hipEventDestroy(e);
@@ -545,6 +783,8 @@ int loki_workspace_bytes(const loki_problem_t *p, int64_t n_demand, size_t *byte
     if (n_demand < 1) return LOKI_E_ARG;
     *bytes = std::max(search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total,
                       eval_layout(const_block(p), n_demand).total);
+    if (class_search_applies(p))
+        *bytes = std::max(*bytes, class_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total);
     return LOKI_OK;
 }
 
@@ -592,7 +832,7 @@ int loki_alloc_search_enqueue(loki_problem_t *p, const int64_t *demand_mqps, int
                               void *d_results) {
     if (!d_results) return LOKI_E_NULL;
     return enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
-                          d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream), d_results, false);
+                          d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream), d_results, false, nullptr);
 }
 
 int loki_alloc_search(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers,
@@ -600,14 +840,13 @@ int loki_alloc_search(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_d
                       void *d_workspace, size_t workspace_bytes, void *hip_stream, loki_result_t *out) {
     if (!out) return LOKI_E_NULL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    void *d_res = nullptr;
     int rc = enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
-                            d_workspace, workspace_bytes, stream, nullptr, true);
+                            d_workspace, workspace_bytes, stream, nullptr, true, &d_res);
     if (rc) return rc;
-    const Layout lay = search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand);
     unsigned char *hres = p->staging + const_block(p) +
                           align_up(size_t(p->cap_points) * kMaxTasks * sizeof(int64_t));
-    LOKI_HIP(hipMemcpyAsync(hres, static_cast<unsigned char *>(d_workspace) + lay.off_results,
-                            size_t(n_demand) * sizeof(loki_result_t), hipMemcpyDeviceToHost, stream));
+    LOKI_HIP(hipMemcpyAsync(hres, d_res, size_t(n_demand) * sizeof(loki_result_t), hipMemcpyDeviceToHost, stream));
     LOKI_HIP(hipStreamSynchronize(stream));
     p->staged_pending = false;
     std::memcpy(out, hres, size_t(n_demand) * sizeof(loki_result_t));

@@ -106,6 +106,12 @@ struct SearchArgs {
     uint32_t *run_end;      // [M][C_0] end (exclusive) of the run each position belongs to
     void *results;          // [M] loki_result_t
     const double *path_acc; // [path_total] profiled path accuracies as fractions, or null
+    // Per-variant factors on a tree whose other tasks all hang off the first task: a "point" of the launch
+    // is then a (demand point, class) pair, the class being one value of the requests the first task
+    // creates per unit of fan-out.  class_out[point] is that value (first-task choices that create another
+    // amount do not belong to the point), root_count[point] the number of first-task choices that do.
+    const int64_t *class_out;   // null: points are plain demand points
+    const uint32_t *root_count;
     int64_t budget[kMaxTasks];  // per task i: floor((slo - comm*path_len[i]) / 2), -1 if negative
     uint64_t begin, end;    // index range
     uint64_t far_count;     // F = prod of C_j over the tasks strictly between the first and the last
@@ -146,6 +152,16 @@ struct RouteArgs {
     const int64_t *demand;
     RouteOut *out;
     int64_t n;
+};
+
+// Merge of the per-class results into the results of the demand points they belong to.
+struct MergeArgs {
+    const void *class_results;  // [n] loki_result_t, one per (demand point, class)
+    const int32_t *point;       // [n] demand point of each
+    void *results;              // [M] loki_result_t, updated in place
+    int32_t n;
+    int32_t M;                  // used by the initialising launch only
+    uint32_t tie_index_only;
 };
 
 struct EvalArgs {

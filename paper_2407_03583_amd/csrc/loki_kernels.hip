@@ -479,7 +479,10 @@ __global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A)
     TaskRec rec;
     rec.a = task_accuracy(o, Dn);
     rec.w = o.w;
-    rec.lat = (o.any && o.rem == 0) ? static_cast<int32_t>(o.maxlat) : kNever;
+    bool usable = o.any && o.rem == 0;
+    // (demand point, class) pairs: only the first-task choices that create the class's amount of requests
+    if (A.class_out && i == 0) usable = usable && o.outflow == A.class_out[m];
+    rec.lat = usable ? static_cast<int32_t>(o.maxlat) : kNever;
     A.table[static_cast<size_t>(m) * sP.table_total + t] = rec;
 }
 
@@ -591,9 +594,11 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     const int m = blockIdx.y;
     const int n = uni(sP->n_tasks), L = n - 1;
     const uint32_t CL = uni(sP->C[L]);
-    const uint32_t mid_count = n >= 2 ? uni(sP->C[0]) : 1u;
+    const uint32_t C0 = n >= 2 ? uni(sP->C[0]) : 1u;
+    // first-task choices to visit, in run order: all of them, or with classes those of this point's class
+    // (the ordering kernel puts them first; the rest belong to other points)
+    const uint32_t mid_count = A.root_count ? uni(A.root_count[m]) : C0;
     const uint64_t strideL = uni64(sP->stride[L]);
-    const uint32_t C0 = mid_count;
     const TaskRec *tab = A.table + static_cast<size_t>(m) * uni(sP->table_total);
     const TaskRec *tabL = tab + uni(sP->table_off[L]);
     const uint32_t *perm = A.perm + static_cast<size_t>(m) * C0;
@@ -719,7 +724,9 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         const int64_t w_room = static_cast<int64_t>(W) - w_far;
 
         const uint32_t tile_base = r * A.tile_len;
-        const uint32_t cnt = mid_count - tile_base < A.tile_len ? mid_count - tile_base : A.tile_len;
+        // (a point with few first-task choices may leave the later tiles of the launch empty)
+        const uint32_t left = tile_base < mid_count ? mid_count - tile_base : 0u;
+        const uint32_t cnt = left < A.tile_len ? left : A.tile_len;
         const uint64_t base_f = static_cast<uint64_t>(C0) * f;  // index contribution of the tasks in between
 
         // The accuracies the steps multiply by, one per step, for this combination of the tasks in
@@ -1247,6 +1254,40 @@ __global__ void __launch_bounds__(kBlockThreads) route_kernel(RouteArgs A) {
         }
 }
 
+// ---- kernels: results of (demand point, class) pairs -> results of the demand points ------------------
+__global__ void results_init_kernel(MergeArgs A) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= A.M) return;
+    ResultOut o;
+    o.index = ~0ull;
+    o.accuracy = 0.0;
+    o.n_feasible = 0;
+    o.workers_used = -1;
+    o.status = 1;
+    static_cast<ResultOut *>(A.results)[m] = o;
+}
+
+// One thread: the classes of a demand point are few and this runs once per batch of points.
+__global__ void class_merge_kernel(MergeArgs A) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const ResultOut *in = static_cast<const ResultOut *>(A.class_results);
+    ResultOut *out = static_cast<ResultOut *>(A.results);
+    const bool tie_index_only = A.tie_index_only != 0;
+    for (int v = 0; v < A.n; v++) {
+        const ResultOut c = in[v];
+        ResultOut o = out[A.point[v]];
+        o.n_feasible += c.n_feasible;
+        if (c.status == 0 && (o.status != 0 || better(c.accuracy, c.workers_used, c.index, o.accuracy, o.workers_used,
+                                                      o.index, tie_index_only))) {
+            o.index = c.index;
+            o.accuracy = c.accuracy;
+            o.workers_used = c.workers_used;
+            o.status = 0;
+        }
+        out[A.point[v]] = o;
+    }
+}
+
 template <int S>
 hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
@@ -1306,6 +1347,16 @@ hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_v
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream) {
     const dim3 grid(A.M), block(kBlockThreads);
     hipLaunchKernelGGL(final_reduce_kernel, grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_results_init(const MergeArgs &A, hipStream_t stream) {
+    hipLaunchKernelGGL(results_init_kernel, dim3((A.M + 255) / 256), dim3(256), 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_class_merge(const MergeArgs &A, hipStream_t stream) {
+    hipLaunchKernelGGL(class_merge_kernel, dim3(1), dim3(64), 0, stream, A);
     return hipGetLastError();
 }
 

@@ -17,6 +17,8 @@ hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool 
 hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels,
                                   hipStream_t stream);
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);
+hipError_t launch_results_init(const MergeArgs &A, hipStream_t stream);
+hipError_t launch_class_merge(const MergeArgs &A, hipStream_t stream);
 hipError_t launch_eval(const EvalArgs &A, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &A, hipStream_t stream);
 

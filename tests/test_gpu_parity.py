@@ -455,3 +455,34 @@ def test_hardware_scaling_step_through_the_same_search():
             assert f.accuracy < step1[0].accuracy, d             # Step 2: accuracy is given up
     assert 10 < solved < len(step1) and step1[0].status == binding.LOKI_FOUND
     assert any(f.status == binding.LOKI_FOUND and s.status != binding.LOKI_FOUND for s, f in zip(step1, full))
+
+
+def test_per_variant_factors_class_by_class_on_a_detector_with_two_classifiers():
+    """Config 4's tree (0 -> 1, 0 -> 2) with factors rising with accuracy: the other tasks' demand depends
+    on the first task's choice only through the requests it creates, and the library runs the tabulated
+    kernels once per distinct amount.  Against the kernel that scores whole plans per lane at every demand
+    point, against the checker on two of them (2^30 plans each), and on split ranges."""
+    w = wl.config(4)
+    p = w.pipeline
+    p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]   # 0.75 .. 1.5
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    demands = sorted(w.demand_mqps)[::40] + [0, 30_000]
+    for flags in (0, TIE):
+        by_class = P.alloc_search(demands, w.workers, w.slo_us, flags=flags)
+        per_lane = P.alloc_search(demands, w.workers, w.slo_us, flags=flags | LANE)
+        for d, a, b in zip(demands, by_class, per_lane):
+            assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
+                a.as_tuple()[2:] == b.as_tuple()[2:], (d, flags, a.as_tuple(), b.as_tuple())
+    assert sum(r.status == binding.LOKI_FOUND for r in by_class) >= 3
+    for d in (demands[1], 30_000):
+        check(P.alloc_search([d], w.workers, w.slo_us)[0], O.search(d, w.workers, w.slo_us), f"demand {d}")
+    cut = n // 3 + 777
+    d = demands[1]
+    lo = P.alloc_search([d], w.workers, w.slo_us, begin=0, end=cut)[0]
+    hi = P.alloc_search([d], w.workers, w.slo_us, begin=cut, end=n)[0]
+    whole = P.alloc_search([d], w.workers, w.slo_us)[0]
+    assert lo.n_feasible + hi.n_feasible == whole.n_feasible
+    best = min((r for r in (lo, hi) if r.status == binding.LOKI_FOUND),
+               key=lambda r: (-r.accuracy, r.workers_used, r.index))
+    assert (best.index, bits(best.accuracy), best.workers_used) == (whole.index, bits(whole.accuracy), whole.workers_used)
