@@ -5,6 +5,7 @@ import json
 import os
 import random
 import struct
+from types import SimpleNamespace
 
 import pytest
 
@@ -486,3 +487,33 @@ def test_per_variant_factors_class_by_class_on_a_detector_with_two_classifiers()
     best = min((r for r in (lo, hi) if r.status == binding.LOKI_FOUND),
                key=lambda r: (-r.accuracy, r.workers_used, r.index))
     assert (best.index, bits(best.accuracy), best.workers_used) == (whole.index, bits(whole.accuracy), whole.workers_used)
+
+
+def test_per_variant_factors_with_more_classes_than_one_call_takes():
+    """65,535 demand points on a small detector-and-classifier pipeline with factors: the (demand point,
+    class) pairs exceed what one call handles class by class, so the library scores whole plans per lane;
+    12,000 points stay below the limit.  Both against the checker on samples."""
+    p = SimpleNamespace(n_tasks=2, parent=[-1, 0], fanout_q4=[4, 6], n_variants=[2, 2], n_batches=[2, 1],
+                        batch_size=[1, 4, 2], max_replicas=[2, 2, 3, 3], acc_ppm=[700000, 900000, 650000, 880000],
+                        latency_us=[3000, 9000, 5000, 14000, 4000, 7000],
+                        thr_mqps=[333333, 444444, 200000, 285714, 500000, 285714],
+                        variant_factor_q4=[3, 6, 4, 4])
+    P, O = binding.Problem(p), oracle.Problem(p)
+    rng = random.Random(17)
+
+    def classes(d):   # distinct amounts of requests the first task's usable choices create (18 choices)
+        amounts = set()
+        for c0 in range(18):
+            r = O.route_table(c0, d)
+            if r.unserved[0] == 0 and any(r.capacity[0][k] > 0 for k in range(2)):
+                amounts.add(sum(r.routed[0][k] * p.variant_factor_q4[k] for k in range(2)))
+        return len(amounts)
+
+    sample = [rng.randint(0, 1_500_000) for _ in range(500)]
+    per_point = sum(classes(d) for d in sample) / len(sample)
+    assert per_point * 65_535 > 80_000 and per_point * 12_000 < 50_000, per_point
+    for n_points in (65_535, 12_000):
+        demands = [rng.randint(0, 1_500_000) for _ in range(n_points)]
+        out = P.alloc_search(demands, 9, 60_000)
+        for j in list(range(0, n_points, 997)) + [n_points - 1]:
+            check(out[j], O.search(demands[j], 9, 60_000), f"{n_points} points, point {j}")
