@@ -982,11 +982,21 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 constexpr uint32_t kStrip = 64;
 
 // MAXD > 0: the objective comes from profiled path accuracies (path_objective with MAXD levels compiled
-// in); the feasibility part is the same, and the walk over the variant paths runs for feasible plans only.
+// in); the feasibility part is the same.  The walk over the variant paths costs far more than the
+// feasibility check and only feasible plans need it, so a wavefront does not walk a plan where it finds
+// it: the lane puts the plan's index in a queue of its wavefront, and whenever the queue holds 64 plans
+// all 64 lanes walk one each (any lane may own any plan: the running best is a maximum under a strict
+// total order).  The loops below therefore have the same trip count in every lane of a wavefront.
+// The four-level walk is held to the registers of 3 wavefronts per SIMD: its spills cost less than the
+// scoring loop gains from the third wavefront.
+constexpr uint32_t kWalkQueue = 128;  // per wavefront: below 64 waiting + at most 64 new per step
+
 template <bool PV, bool VF, int MAXD>
-__global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchArgs A) {
+__global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_search_kernel(SearchArgs A) {
     __shared__ DevProblem sP;
     __shared__ BestRec sBest[kWavesPerBlock];
+    __shared__ uint64_t sWalkIdx[MAXD > 0 ? kWavesPerBlock : 1][MAXD > 0 ? kWalkQueue : 1];
+    __shared__ int32_t sWalkW[MAXD > 0 ? kWavesPerBlock : 1][MAXD > 0 ? kWalkQueue : 1];
     stage_problem(&sP, A.P, sizeof(DevProblem));
     __syncthreads();
     const DevProblem *P = &sP;
@@ -1003,6 +1013,7 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
     const uint64_t items = A.far_span * n_strips;
     const double npd = static_cast<double>(P->n_paths);
     const int parL = n >= 2 ? P->parent[L] : 0;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int64_t Dn[kMaxTasks];
 #pragma unroll
     for (int i = 0; i < kMaxTasks; i++) Dn[i] = A.Dn[static_cast<size_t>(m) * kMaxTasks + i];
@@ -1011,15 +1022,50 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
     int32_t bw = kNever;
     uint64_t bidx = ~0ull;
     uint64_t nfeas = 0;
-    for (uint64_t item = static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x; item < items; item += lanes) {
-        const uint64_t oi = item / n_strips;
+    uint32_t waiting = 0;  // plans in this wavefront's queue (the same in every lane)
+
+    // the first `count` lanes take the queue entries [from, from + count) and walk them
+    auto walk_queued = [&](uint32_t from, uint32_t count) {
+        if constexpr (MAXD > 0) {
+            if (lane < count) {
+                const uint64_t idx = sWalkIdx[wave][from + lane];
+                const int32_t workers = sWalkW[wave][from + lane];
+                uint32_t c[kMaxTasks];
+                uint64_t rest = idx;
+#pragma unroll
+                for (int i = 0; i < kMaxTasks; i++) {
+                    c[i] = 0;
+                    if (i < n) {
+                        c[i] = static_cast<uint32_t>(rest % P->C[i]);
+                        rest /= P->C[i];
+                    }
+                }
+                const double acc = path_objective<MAXD>(P, A.path_acc, c, Dn);
+                if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                    bacc = acc;
+                    bw = workers;
+                    bidx = idx;
+                }
+            }
+        }
+    };
+
+    const uint64_t first_item = static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x;
+    const uint64_t rounds = (items + lanes - 1) / lanes;
+    for (uint64_t round = 0; round < rounds; round++) {
+        const uint64_t item = first_item + round * lanes;
+        bool live = item < items;
+        const uint64_t oi = live ? item / n_strips : 0;
         const uint32_t strip = strip_first + static_cast<uint32_t>(item - oi * n_strips);
         uint64_t o = A.far_first + oi;  // index of the plan with the last task's choice 0
         if (o >= strideL) o -= strideL;
-        // skip strips wholly outside [begin, end)
         const uint32_t c_lo = strip * kStrip;
         const uint32_t c_hi = c_lo + kStrip < CL ? c_lo + kStrip : CL;
-        if (o + strideL * c_lo >= A.end || o + strideL * (c_hi - 1) < A.begin) continue;
+        // strips wholly outside [begin, end) are not scored
+        if (live && (o + strideL * c_lo >= A.end || o + strideL * (c_hi - 1) < A.begin)) live = false;
+        if constexpr (MAXD == 0) {
+            if (!live) continue;
+        }
 
         // ---- the shared part: tasks 0 .. L-1
         double pp[kMaxTasks];    // product of accuracies root..i, root first
@@ -1033,43 +1079,41 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
             pl[i] = 0;
             out[i] = 0;
         }
-        uint64_t rest = o;
-        uint32_t c[kMaxTasks];  // the plan's choice per task (used by the walk over the variant paths)
-#pragma unroll
-        for (int i = 0; i < kMaxTasks; i++) c[i] = 0;
-#pragma unroll
-        for (int i = 0; i < kMaxTasks; i++) {
-            if (i < L) {
-                const uint32_t ci = static_cast<uint32_t>(rest % P->C[i]);
-                rest /= P->C[i];
-                c[i] = ci;
-                const int par = i > 0 ? P->parent[i] : 0;
-                int64_t dn = Dn[i];
-                if (has_vf && i > 0) dn = pick_below(out, par, i) * static_cast<int64_t>(P->fanout[i]);
-                TaskOut t;
-                eval_task<PV, VF>(P, i, ci, dn, t);
-                out[i] = t.outflow;
-                workers0 += t.w;
-                if (!t.any) mask0 |= kBadEmpty;
-                if (t.rem > 0) mask0 |= kBadDemand;
-                const double a = task_accuracy(t, dn);
-                if (i == 0) {
-                    pp[0] = a;
-                    pl[0] = t.maxlat;
-                } else {
-                    pp[i] = pick_below(pp, par, i) * a;
-                    pl[i] = pick_below(pl, par, i) + t.maxlat;
-                }
-            }
-        }
         double presum = 0.0;
         bool first = true;
+        if (live) {
+            uint64_t rest = o;
 #pragma unroll
-        for (int i = 0; i < kMaxTasks; i++) {
-            if (i < L && P->is_leaf[i]) {
-                if (A.budget[i] < 0 || pl[i] > A.budget[i]) mask0 |= kBadLatency;
-                presum = first ? pp[i] : presum + pp[i];
-                first = false;
+            for (int i = 0; i < kMaxTasks; i++) {
+                if (i < L) {
+                    const uint32_t ci = static_cast<uint32_t>(rest % P->C[i]);
+                    rest /= P->C[i];
+                    const int par = i > 0 ? P->parent[i] : 0;
+                    int64_t dn = Dn[i];
+                    if (has_vf && i > 0) dn = pick_below(out, par, i) * static_cast<int64_t>(P->fanout[i]);
+                    TaskOut t;
+                    eval_task<PV, VF>(P, i, ci, dn, t);
+                    out[i] = t.outflow;
+                    workers0 += t.w;
+                    if (!t.any) mask0 |= kBadEmpty;
+                    if (t.rem > 0) mask0 |= kBadDemand;
+                    const double a = task_accuracy(t, dn);
+                    if (i == 0) {
+                        pp[0] = a;
+                        pl[0] = t.maxlat;
+                    } else {
+                        pp[i] = pick_below(pp, par, i) * a;
+                        pl[i] = pick_below(pl, par, i) + t.maxlat;
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kMaxTasks; i++) {
+                if (i < L && P->is_leaf[i]) {
+                    if (A.budget[i] < 0 || pl[i] > A.budget[i]) mask0 |= kBadLatency;
+                    presum = first ? pp[i] : presum + pp[i];
+                    first = false;
+                }
             }
         }
         const double pre = pick_below(pp, parL, kMaxTasks);
@@ -1078,35 +1122,59 @@ __global__ void __launch_bounds__(kBlockThreads) per_lane_search_kernel(SearchAr
         if (has_vf && n >= 2) dnL = pick_below(out, parL, kMaxTasks) * static_cast<int64_t>(P->fanout[L]);
 
         // ---- the strip: the last task's choices
-        for (uint32_t cL = c_lo; cL < c_hi; cL++) {
+        const uint32_t steps = MAXD > 0 ? kStrip : c_hi - c_lo;
+        for (uint32_t step = 0; step < steps; step++) {
+            const uint32_t cL = c_lo + step;
             const uint64_t idx = o + strideL * cL;
-            if (idx < A.begin || idx >= A.end) continue;
-            TaskOut t;
-            eval_task<PV, VF>(P, L, cL, dnL, t);
-            uint32_t mask = mask0;
-            const int32_t workers = workers0 + t.w;
-            if (!t.any) mask |= kBadEmpty;
-            if (t.rem > 0) mask |= kBadDemand;
-            if (workers > A.W) mask |= kBadWorkers;                                            // eq. (3)
-            if (A.budget[L] < 0 || lat_pre + t.maxlat > A.budget[L]) mask |= kBadLatency;  // eq. (7)
-            if (mask == 0) {
-                const double a = task_accuracy(t, dnL);
-                const double path = n >= 2 ? pre * a : a;
-                const double sum = first ? path : presum + path;
-                double acc = sum / npd;
-                if constexpr (MAXD > 0) {
-                    c[L] = cL;
-                    acc = path_objective<MAXD>(P, A.path_acc, c, Dn);
+            bool feasible = false;
+            int32_t workers = 0;
+            if (live && cL < c_hi && idx >= A.begin && idx < A.end) {
+                TaskOut t;
+                eval_task<PV, VF>(P, L, cL, dnL, t);
+                uint32_t mask = mask0;
+                workers = workers0 + t.w;
+                if (!t.any) mask |= kBadEmpty;
+                if (t.rem > 0) mask |= kBadDemand;
+                if (workers > A.W) mask |= kBadWorkers;                                            // eq. (3)
+                if (A.budget[L] < 0 || lat_pre + t.maxlat > A.budget[L]) mask |= kBadLatency;  // eq. (7)
+                feasible = mask == 0;
+                if constexpr (MAXD == 0) {
+                    if (feasible) {
+                        const double a = task_accuracy(t, dnL);
+                        const double path = n >= 2 ? pre * a : a;
+                        const double sum = first ? path : presum + path;
+                        const double acc = sum / npd;
+                        if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                            bacc = acc;
+                            bw = workers;
+                            bidx = idx;
+                        }
+                    }
                 }
-                nfeas++;
-                if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
-                    bacc = acc;
-                    bw = workers;
-                    bidx = idx;
+                if (feasible) nfeas++;
+            }
+            if constexpr (MAXD > 0) {
+                // every lane of the wavefront is here: queue the feasible plans, walk 64 when there are that many
+                const uint64_t vote = __ballot(feasible);
+                if (vote) {
+                    if (feasible) {
+                        const uint32_t at = waiting + __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(vote >> 32),
+                                                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(vote), 0u));
+                        sWalkIdx[wave][at] = idx;
+                        sWalkW[wave][at] = workers;
+                    }
+                    waiting += static_cast<uint32_t>(__popcll(vote));
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    if (waiting >= 64) {
+                        waiting -= 64;
+                        walk_queued(waiting, 64);
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    }
                 }
             }
         }
     }
+    if constexpr (MAXD > 0) walk_queued(0, waiting);
     nfeas = wave_sum(nfeas);
     block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
                      A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
