@@ -293,7 +293,8 @@ class Problem:
         return [float(v) for v in ms]
 
 
-RATE_KINDS = {"v_mul_f64": 0, "v_add_f64": 1, "v_max_f64": 2, "search_mix": 3, "v_add_u32": 4}
+RATE_KINDS = {"v_mul_f64": 0, "v_add_f64": 1, "v_max_f64": 2, "search_mix": 3, "v_add_u32": 4, "v_fma_f64": 5,
+              "v_rcp_f64": 6, "v_mul_lo_u32": 7, "v_mul_hi_u32": 8, "v_min_u32": 9, "ds_read_b64": 10}
 
 
 def measure_valu_rate(kind: str) -> float:

@@ -1067,9 +1067,12 @@ int loki_last_search_ms(const loki_problem_t *p, float *ms) {
 int loki_measure_valu_rate(int kind, void *d_workspace, size_t workspace_bytes, void *hip_stream,
                            double *wave_instructions_per_second) {
     if (!d_workspace || !wave_instructions_per_second) return LOKI_E_NULL;
-    if (kind < 0 || kind > LOKI_RATE_ADD_U32) return LOKI_E_ARG;
+    if (kind < 0 || kind > LOKI_RATE_LAST) return LOKI_E_ARG;
     // many short blocks: the block dispatcher then keeps every SIMD full to the end, as in the search
-    const int blocks = 32768, iters = 6250, sink_blocks = 2048;
+    // (fewer trips for the classes that issue at a quarter of the rate or less)
+    const bool slow = kind == LOKI_RATE_RCP_F64 || kind == LOKI_RATE_MUL_LO_U32 || kind == LOKI_RATE_MUL_HI_U32 ||
+                      kind == LOKI_RATE_LDS_READ_B64;
+    const int blocks = 32768, iters = slow ? 1000 : 6250, sink_blocks = 2048;
     if (workspace_bytes < size_t(sink_blocks) * 256 * sizeof(double) || (reinterpret_cast<uintptr_t>(d_workspace) % 8) != 0)
         return LOKI_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);

@@ -18,12 +18,66 @@ namespace {
     OP " %2, %2, %8\n" OP " %3, %3, %8\n" OP " %4, %4, %8\n" OP " %5, %5, %8\n" OP " %6, %6, %8\n"  \
     OP " %7, %7, %8\n"
 
+#define LOKI_REP16_UNARY(OP)                                                                      \
+    OP " %0, %0\n" OP " %1, %1\n" OP " %2, %2\n" OP " %3, %3\n" OP " %4, %4\n" OP " %5, %5\n"       \
+    OP " %6, %6\n" OP " %7, %7\n" OP " %0, %0\n" OP " %1, %1\n" OP " %2, %2\n" OP " %3, %3\n"       \
+    OP " %4, %4\n" OP " %5, %5\n" OP " %6, %6\n" OP " %7, %7\n"
+
+#define LOKI_REP16_FMA(OP)                                                                                  \
+    OP " %0, %0, %8, %8\n" OP " %1, %1, %8, %8\n" OP " %2, %2, %8, %8\n" OP " %3, %3, %8, %8\n"            \
+    OP " %4, %4, %8, %8\n" OP " %5, %5, %8, %8\n" OP " %6, %6, %8, %8\n" OP " %7, %7, %8, %8\n"            \
+    OP " %0, %0, %8, %8\n" OP " %1, %1, %8, %8\n" OP " %2, %2, %8, %8\n" OP " %3, %3, %8, %8\n"            \
+    OP " %4, %4, %8, %8\n" OP " %5, %5, %8, %8\n" OP " %6, %6, %8, %8\n" OP " %7, %7, %8, %8\n"
+
+// 16 reads of 8 bytes per lane (consecutive lanes 8 bytes apart: no bank conflicts), waited for once
+#define LOKI_REP16_LDS                                                                                      \
+    "ds_read_b64 %0, %8\n ds_read_b64 %1, %8 offset:2048\n ds_read_b64 %2, %8 offset:4096\n"                 \
+    "ds_read_b64 %3, %8 offset:6144\n ds_read_b64 %4, %8\n ds_read_b64 %5, %8 offset:2048\n"                 \
+    "ds_read_b64 %6, %8 offset:4096\n ds_read_b64 %7, %8 offset:6144\n ds_read_b64 %0, %8\n"                 \
+    "ds_read_b64 %1, %8 offset:2048\n ds_read_b64 %2, %8 offset:4096\n ds_read_b64 %3, %8 offset:6144\n"     \
+    "ds_read_b64 %4, %8\n ds_read_b64 %5, %8 offset:2048\n ds_read_b64 %6, %8 offset:4096\n"                 \
+    "ds_read_b64 %7, %8 offset:6144\n s_waitcnt lgkmcnt(0)\n"
+
 template <int KIND>
 __global__ void __launch_bounds__(256) valu_rate_kernel(double *out, int iters, double seed) {
     double a0 = seed, a1 = seed * 2, a2 = seed * 3, a3 = seed * 4, a4 = seed * 5, a5 = seed * 6, a6 = seed * 7,
            a7 = seed * 8;
     const double c = 1.0 - 1e-9;
+    uint32_t u0 = threadIdx.x + 1, u1 = u0 + 1, u2 = u0 + 2, u3 = u0 + 3, u4 = u0 + 4, u5 = u0 + 5, u6 = u0 + 6, u7 = u0 + 7;
+    const uint32_t uc = 2654435761u;
+    __shared__ double sLds[KIND == LOKI_RATE_LDS_READ_B64 ? 1024 : 1];
+    // byte address in LDS: the low half of a generic pointer into LDS is the offset within LDS
+    const uint32_t lds_at = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(&sLds[0])) + threadIdx.x * 8;
+    if (KIND == LOKI_RATE_LDS_READ_B64) {
+        for (int q = threadIdx.x; q < 1024; q += 256) sLds[q] = seed + q;
+        __syncthreads();
+    }
     for (int it = 0; it < iters; it++) {
+        if (KIND == LOKI_RATE_FMA_F64)
+            asm volatile(LOKI_REP16_FMA("v_fma_f64")
+                         : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)
+                         : "v"(c));
+        if (KIND == LOKI_RATE_RCP_F64)
+            asm volatile(LOKI_REP16_UNARY("v_rcp_f64")
+                         : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)
+                         : "v"(c));
+        if (KIND == LOKI_RATE_MUL_LO_U32)
+            asm volatile(LOKI_REP16("v_mul_lo_u32")
+                         : "+v"(u0), "+v"(u1), "+v"(u2), "+v"(u3), "+v"(u4), "+v"(u5), "+v"(u6), "+v"(u7)
+                         : "v"(uc));
+        if (KIND == LOKI_RATE_MUL_HI_U32)
+            asm volatile(LOKI_REP16("v_mul_hi_u32")
+                         : "+v"(u0), "+v"(u1), "+v"(u2), "+v"(u3), "+v"(u4), "+v"(u5), "+v"(u6), "+v"(u7)
+                         : "v"(uc));
+        if (KIND == LOKI_RATE_MIN_U32)
+            asm volatile(LOKI_REP16("v_min_u32")
+                         : "+v"(u0), "+v"(u1), "+v"(u2), "+v"(u3), "+v"(u4), "+v"(u5), "+v"(u6), "+v"(u7)
+                         : "v"(uc));
+        if (KIND == LOKI_RATE_LDS_READ_B64)
+            asm volatile(LOKI_REP16_LDS
+                         : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)
+                         : "v"(lds_at)
+                         : "memory");
         if (KIND == LOKI_RATE_MUL_F64)
             asm volatile(LOKI_REP16("v_mul_f64")
                          : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(a5), "+v"(a6), "+v"(a7)
@@ -59,7 +113,8 @@ __global__ void __launch_bounds__(256) valu_rate_kernel(double *out, int iters, 
         }
     }
     // the sink only keeps the arithmetic alive; blocks 2048 apart share a slot
-    out[(blockIdx.x & 2047) * 256 + threadIdx.x] = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7;
+    out[(blockIdx.x & 2047) * 256 + threadIdx.x] =
+        a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7 + static_cast<double>(u0 ^ u1 ^ u2 ^ u3 ^ u4 ^ u5 ^ u6 ^ u7);
 }
 
 }  // namespace
@@ -72,6 +127,12 @@ hipError_t launch_valu_rate(int kind, double *out, int blocks, int iters, hipStr
         case LOKI_RATE_MAX_F64: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_MAX_F64>, grid, block, 0, stream, out, iters, 0.5); break;
         case LOKI_RATE_SEARCH_MIX: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_SEARCH_MIX>, grid, block, 0, stream, out, iters, 0.5); break;
         case LOKI_RATE_ADD_U32: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_ADD_U32>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_FMA_F64: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_FMA_F64>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_RCP_F64: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_RCP_F64>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_MUL_LO_U32: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_MUL_LO_U32>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_MUL_HI_U32: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_MUL_HI_U32>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_MIN_U32: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_MIN_U32>, grid, block, 0, stream, out, iters, 0.5); break;
+        case LOKI_RATE_LDS_READ_B64: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_LDS_READ_B64>, grid, block, 0, stream, out, iters, 0.5); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

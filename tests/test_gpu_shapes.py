@@ -222,11 +222,16 @@ def test_the_largest_number_of_demand_points():
 
 def test_valu_rate_measurement_is_plausible():
     nominal = 256 * 4 * 2.4e9 / 4          # wavefront instructions per second at one per SIMD per 4 cycles
+    # classes that issue at the full rate; the 32-bit integer streams have been seen above the nominal figure
+    full = {"v_mul_f64": 1.05, "v_add_f64": 1.05, "v_max_f64": 1.05, "search_mix": 1.05, "v_fma_f64": 1.05,
+            "v_add_u32": 1.4, "v_min_u32": 1.4}
     for kind in binding.RATE_KINDS:
         rate = binding.measure_valu_rate(kind)
-        # fp64 streams come close to the nominal rate; the 32-bit integer stream has been seen above it
-        hi = 1.4 if kind == "v_add_u32" else 1.05
-        assert 0.5 * nominal < rate < hi * nominal, (kind, rate)
+        print(kind, rate / nominal)
+        if kind in full:
+            assert 0.5 * nominal < rate < full[kind] * nominal, (kind, rate)
+        else:   # 32-bit multiplies, the fp64 reciprocal, LDS reads: slower classes, never faster than the full rate
+            assert 0.02 * nominal < rate < 1.05 * nominal, (kind, rate)
 
 
 def test_objective_operation_order_on_the_gpu():
