@@ -40,8 +40,12 @@
  * is fp64, one correctly rounded operation at a time, no FMA contraction.
  *
  * Pins: tests/test_oracle_*.py (hand-derived worked example, closed forms,
- * exact-rational brute force, invariants).  Unpinned: whether the paper's own
- * MILP optimum equals this bounded search's optimum (different search space).
+ * exact-rational brute force, invariants, and an LP / MILP solver on the
+ * paper's own formulation where the two must agree: product tables, task paths
+ * of two tasks, latency not binding).  Unpinned: the paper's MILP optimum with
+ * unbounded replica counts, with a binding latency limit (its limit is per
+ * variant path, the search's per task) or on longer paths (solver-chosen path
+ * ratios can beat hop-by-hop routing there).
  */
 #ifndef LOKI_ORACLE_H
 #define LOKI_ORACLE_H
