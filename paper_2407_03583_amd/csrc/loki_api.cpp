@@ -36,32 +36,41 @@ thread_local int g_last_hip = 0;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t off_P, off_Dn, off_table, off_perm, off_run, off_recs, off_results, total;
+    size_t off_P, off_Dn, off_table, off_perm, off_run, off_perm1, off_run1, off_recs, off_results, total;
 };
 
 // `cb` is the size of the constant block: the problem constants followed by the profiled path
 // accuracies (if any), see const_block().
-Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M) {
+// c1: choices of task 1 when its run order is needed too (class-by-class searches), else 0.
+Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, uint32_t c1 = 0) {
     Layout l;
     l.off_P = 0;
     l.off_Dn = cb;
     l.off_table = align_up(l.off_Dn + size_t(M) * kMaxTasks * sizeof(int64_t));
     l.off_perm = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
     l.off_run = align_up(l.off_perm + size_t(M) * c0 * sizeof(uint32_t));
-    l.off_recs = align_up(l.off_run + size_t(M) * c0 * sizeof(uint32_t));
+    l.off_perm1 = align_up(l.off_run + size_t(M) * c0 * sizeof(uint32_t));
+    l.off_run1 = align_up(l.off_perm1 + size_t(M) * c1 * sizeof(uint32_t));
+    l.off_recs = align_up(l.off_run1 + size_t(M) * c1 * sizeof(uint32_t));
     l.off_results = align_up(l.off_recs + (size_t(kTargetBlocks) + size_t(M)) * sizeof(BestRec));
     l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
     return l;
 }
 
 // Per-variant factors on a tree whose other tasks all hang off the first task: the search runs over
-// (demand point, class) pairs, at most kClassBatch of them per set of launches.
+// (demand point, class) pairs, a batch of them per set of launches: as many as keep the per-pair task
+// tables within kClassTableBytes, between 256 and 4096 (more pairs per launch give every block several
+// work items, which spreads its start-up cost).
 constexpr int64_t kMaxClassPoints = 65535;
-constexpr int32_t kClassBatch = 1024;
+constexpr size_t kClassTableBytes = size_t(256) << 20;
+int32_t class_batch(uint32_t table_total) {
+    const size_t fit = kClassTableBytes / (size_t(std::max<uint32_t>(table_total, 1u)) * sizeof(TaskRec));
+    return int32_t(std::min<size_t>(4096, std::max<size_t>(256, fit)));
+}
 
 // Whether a handle's searches can run class by class: per-variant factors, product objective, every
 // other task a child of the first one, the first task's choices orderable into runs, and tables small
-// enough to keep kClassBatch copies of them in the workspace.
+// enough to keep a batch of copies of them in the workspace.
 bool class_search_applies(const loki_problem *p);
 
 struct ClassLayout {
@@ -69,7 +78,7 @@ struct ClassLayout {
     Layout batch;  // offsets inside the batch region (its off_P / off_Dn are not used)
 };
 
-ClassLayout class_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M) {
+ClassLayout class_layout(size_t cb, uint32_t table_total, uint32_t c0, uint32_t c1, int64_t M) {
     ClassLayout l;
     l.off_P = 0;
     l.off_vDn = cb;
@@ -77,7 +86,7 @@ ClassLayout class_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M
     l.off_vCount = align_up(l.off_vOut + size_t(kMaxClassPoints) * sizeof(int64_t));
     l.off_vPoint = align_up(l.off_vCount + size_t(kMaxClassPoints) * sizeof(uint32_t));
     l.off_batch = align_up(l.off_vPoint + size_t(kMaxClassPoints) * sizeof(int32_t));
-    l.batch = search_layout(0, table_total, c0, kClassBatch);
+    l.batch = search_layout(0, table_total, c0, class_batch(table_total), c1);
     l.off_class_results = l.off_batch + l.batch.off_results;
     l.off_results = align_up(l.off_batch + l.batch.total);
     l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
@@ -288,6 +297,46 @@ int build_class_points(const loki_problem *p, const int64_t *demand_mqps, int32_
     return LOKI_OK;
 }
 
+// Order of the (demand point, class) pairs and their split into batches.  The blocks of a launch are
+// shared out evenly among its pairs, so a batch should hold pairs of similar size: pairs go by
+// descending number of first-task choices, a batch takes as many as leave each of its pairs about one
+// block per kClassItemsPerBlock work items, and inside a batch the pairs of a demand point are kept
+// together (the merge folds stretches of equal points).
+constexpr uint64_t kClassItemsPerBlock = 8;
+
+void plan_class_batches(ClassPoints &cp, uint64_t items_per_choice, int32_t batch_limit, std::vector<int64_t> &batch_first) {
+    const size_t V = cp.amount.size();
+    std::vector<uint32_t> order(V);
+    for (size_t v = 0; v < V; v++) order[v] = uint32_t(v);
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return cp.count[a] > cp.count[b]; });
+    batch_first.clear();
+    for (size_t at = 0; at < V;) {
+        const uint64_t items = std::max<uint64_t>(1, uint64_t(cp.count[order[at]]) * items_per_choice);
+        const uint64_t blocks = std::max<uint64_t>(1, (items + kClassItemsPerBlock - 1) / kClassItemsPerBlock);
+        const size_t take = size_t(std::min<uint64_t>(uint64_t(batch_limit), std::max<uint64_t>(1, kTargetBlocks / blocks)));
+        const size_t end = std::min(V, at + take);
+        std::stable_sort(order.begin() + at, order.begin() + end,
+                         [&](uint32_t a, uint32_t b) { return cp.point[a] < cp.point[b]; });
+        batch_first.push_back(int64_t(at));
+        at = end;
+    }
+    batch_first.push_back(int64_t(V));
+    ClassPoints out;
+    out.Dn.resize(cp.Dn.size());
+    out.amount.resize(V);
+    out.count.resize(V);
+    out.point.resize(V);
+    for (size_t v = 0; v < V; v++) {
+        const uint32_t src = order[v];
+        std::copy(cp.Dn.begin() + size_t(src) * kMaxTasks, cp.Dn.begin() + size_t(src + 1) * kMaxTasks,
+                  out.Dn.begin() + v * kMaxTasks);
+        out.amount[v] = cp.amount[src];
+        out.count[v] = cp.count[src];
+        out.point[v] = cp.point[src];
+    }
+    cp = std::move(out);
+}
+
 // Launch configuration and launches of the tabulated kernels (per-task tables, run order, the kernel
 // that visits every plan) for the A.M points A describes.  root_choices: the most first-task choices any
 // point visits (all of them, or the largest class).  before_search / after_search: events recorded around
@@ -305,7 +354,18 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint32_t root_choices, uint6
     uint64_t F = 1;
     for (int j = 1; j < L; j++) F *= p->dev.C[j];
     const uint32_t C0 = n >= 2 ? p->dev.C[0] : 1u;
-    const uint32_t mid_count = std::max<uint32_t>(1u, std::min(root_choices, C0));
+    uint32_t mid_count = std::max<uint32_t>(1u, std::min(root_choices, C0));
+    // Classes on a tree of three or more tasks, whole space: a point's first-task choices are few, so
+    // task 1's choices fill the tiles and the first task's join the work item (see combine_kernel).
+    A.swap = 0;
+    A.far2_count = 1;
+    if (A.class_out && n >= 3 && span > 0 && index_begin == 0 && index_end == p->n_candidates &&
+        uint64_t(p->dev.sum_r1 + 1) * uint64_t(p->dev.n_lat1) + 1 <= 4096) {
+        A.swap = 1;
+        for (int j = 2; j < L; j++) A.far2_count *= p->dev.C[j];
+        F = uint64_t(mid_count) * A.far2_count;  // the most any point has; a point's own count is taken in the kernel
+        mid_count = p->dev.C[1];
+    }
     A.far_count = F;
     A.tile_len = kMidTile;
     A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
@@ -344,6 +404,9 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint32_t root_choices, uint6
         }
     }
     A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(A.items, 1), max_bpm));
+    if (A.swap)  // the pairs of a batch are of similar size (plan_class_batches): several work items per block
+        A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(
+            A.blocks_per_m, std::max<uint64_t>(1, (A.items + kClassItemsPerBlock - 1) / kClassItemsPerBlock)));
     if (A.items > (uint64_t(1) << 62) / A.blocks_per_m) A.blocks_per_m = 1;  // keep items*block in 64 bits
     const bool range = !(index_begin == 0 && index_end == p->n_candidates);
     const int np = p->dev.n_paths;
@@ -367,7 +430,7 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
                          void *d_workspace, size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed,
                          void **results_at) {
     const size_t cb = const_block(p);
-    const ClassLayout lay = class_layout(cb, p->dev.table_total, p->dev.C[0], n_demand);
+    const ClassLayout lay = class_layout(cb, p->dev.table_total, p->dev.C[0], p->n >= 2 ? p->dev.C[1] : 0u, n_demand);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
         return LOKI_E_WORKSPACE;
     if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
@@ -375,6 +438,17 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     int rc = build_class_points(p, demand_mqps, n_demand, cp);
     if (rc) return rc;
     const int64_t V = int64_t(cp.amount.size());
+    std::vector<int64_t> batch_first;
+    {
+        // work items per first-task choice when the tiles hold task 1's choices (else one batch size fits all)
+        const int L = p->n - 1;
+        uint64_t per_choice = 0;
+        if (p->n >= 3 && index_begin == 0 && index_end == p->n_candidates) {
+            per_choice = (p->dev.C[1] + kMidTile - 1) / kMidTile;
+            for (int j = 2; j < L; j++) per_choice *= p->dev.C[j];
+        }
+        plan_class_batches(cp, per_choice, class_batch(p->dev.table_total), batch_first);
+    }
 
     rc = ensure_staging(p, n_demand);
     if (rc) return rc;
@@ -428,6 +502,8 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     A.recs = reinterpret_cast<BestRec *>(bw + lay.batch.off_recs);
     A.perm = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm);
     A.run_end = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run);
+    A.perm1 = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm1);
+    A.run_end1 = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run1);
     A.results = ws + lay.off_class_results;
     path_budgets(p, slo_us, comm_us, A.budget);
     A.begin = index_begin;
@@ -437,10 +513,13 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
         int64_t others = 0;
         for (int i = 1; i < p->n; i++) others += p->sum_r[i];
         A.w_free = static_cast<int32_t>(std::max<int64_t>(int64_t(workers) - others, -1));
+        const int64_t others1 = p->n >= 2 ? others + p->sum_r[0] - p->sum_r[1] : 0;  // all tasks but task 1
+        A.w_free1 = static_cast<int32_t>(std::max<int64_t>(int64_t(workers) - others1, -1));
     }
     A.tie_index_only = G.tie_index_only;
-    for (int64_t v0 = 0; v0 < V; v0 += kClassBatch) {
-        const int32_t nb = int32_t(std::min<int64_t>(kClassBatch, V - v0));
+    for (size_t b = 0; b + 1 < batch_first.size(); b++) {
+        const int64_t v0 = batch_first[b];
+        const int32_t nb = int32_t(batch_first[b + 1] - v0);
         A.M = nb;
         A.Dn = reinterpret_cast<const int64_t *>(ws + lay.off_vDn) + size_t(v0) * kMaxTasks;
         A.class_out = reinterpret_cast<const int64_t *>(ws + lay.off_vOut) + v0;
@@ -702,6 +781,17 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         d.sum_r0 = 0;
         for (int k = 0; k < d.K[0]; k++) d.sum_r0 += in->max_replicas[k];  // task 0's variants come first
     }
+    d.n_lat1 = 1;
+    if (n >= 2) {  // the same for task 1
+        std::vector<int32_t> lats;
+        for (int k = 0; k < d.K[1]; k++)
+            for (int bi = 0; bi < d.nb[1]; bi++) lats.push_back(int32_t(d.lat[1][k][bi]));
+        std::sort(lats.begin(), lats.end());
+        lats.erase(std::unique(lats.begin(), lats.end()), lats.end());
+        d.n_lat1 = int32_t(lats.size());
+        for (size_t q = 0; q < lats.size(); q++) d.lat1_sorted[q] = lats[q];
+        d.sum_r1 = p->sum_r[1];
+    }
     d.n_paths = 0;
     for (int i = 0; i < n; i++) d.n_paths += d.is_leaf[i];
     p->n_candidates = N;
@@ -784,7 +874,7 @@ int loki_workspace_bytes(const loki_problem_t *p, int64_t n_demand, size_t *byte
     *bytes = std::max(search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total,
                       eval_layout(const_block(p), n_demand).total);
     if (class_search_applies(p))
-        *bytes = std::max(*bytes, class_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total);
+        *bytes = std::max(*bytes, class_layout(const_block(p), p->dev.table_total, p->dev.C[0], p->n >= 2 ? p->dev.C[1] : 0u, n_demand).total);
     return LOKI_OK;
 }
 

@@ -61,6 +61,10 @@ struct DevProblem {
     uint32_t path_total;                    // entries over all leaves
     uint32_t path_off[kMaxTasks];           // first entry of leaf i's table
     int32_t leaf_path[kMaxTasks][kMaxTasks];  // tasks on the chain root..i, root first (path_len[i] of them)
+    // the same ordering data as n_lat0 / sum_r0 / lat0_sorted for task 1 (used when its records fill the tiles)
+    int32_t n_lat1;
+    int32_t sum_r1;
+    int32_t lat1_sorted[kMaxVariants * kMaxBatches];
 };
 
 // What a task contributes to any plan that uses one of its choices
@@ -112,6 +116,14 @@ struct SearchArgs {
     // amount do not belong to the point), root_count[point] the number of first-task choices that do.
     const int64_t *class_out;   // null: points are plain demand points
     const uint32_t *root_count;
+    // With classes on a tree of three or more tasks the roles of the first two tasks are swapped: a
+    // point's few first-task choices become part of the work item (with the tasks after task 1), and
+    // the tiles hold task 1's choices in the run order perm1 / run_end1 ([M][C_1]).
+    uint32_t *perm1;
+    uint32_t *run_end1;
+    uint64_t far2_count;    // prod of C_j over the tasks strictly between task 1 and the last
+    uint32_t swap;
+    int32_t w_free1;        // like w_free, for task 1
     int64_t budget[kMaxTasks];  // per task i: floor((slo - comm*path_len[i]) / 2), -1 if negative
     uint64_t begin, end;    // index range
     uint64_t far_count;     // F = prod of C_j over the tasks strictly between the first and the last

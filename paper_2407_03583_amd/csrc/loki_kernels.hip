@@ -501,26 +501,32 @@ constexpr int kSortThreads = 1024;
 // never bind, whatever the other tasks choose (negative: none).  Choices at or below it leave the
 // last task the same feasibility masks, so they share a bucket per latency; the workers of a
 // winning plan are taken from its own entry, not from the run.
-__device__ __forceinline__ uint32_t root_bucket(const DevProblem *P, const TaskRec &rec, uint32_t n_buckets,
-                                                int32_t w_free) {
+__device__ __forceinline__ uint32_t root_bucket(const int32_t *lat_sorted, uint32_t n_lat, const TaskRec &rec,
+                                                uint32_t n_buckets, int32_t w_free) {
     if (rec.lat == kNever) return n_buckets - 1;
     uint32_t rank = 0;
-    while (rank + 1 < static_cast<uint32_t>(P->n_lat0) && P->lat0_sorted[rank] < rec.lat) rank++;
+    while (rank + 1 < n_lat && lat_sorted[rank] < rec.lat) rank++;
     const int32_t wk = w_free < 0 ? rec.w : (rec.w > w_free ? rec.w - w_free : 0);
-    return static_cast<uint32_t>(wk) * P->n_lat0 + rank;
+    return static_cast<uint32_t>(wk) * n_lat + rank;
 }
 
+// blockIdx.y = 0: the first task's choices; 1 (launched only when the roles of the first two tasks are
+// swapped): task 1's.
 __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) {
     __shared__ uint32_t sHist[kMaxBuckets];   // counts, then next free position per bucket
     __shared__ uint32_t sEnd[kMaxBuckets];    // end position per bucket
     __shared__ uint32_t sWaveTot[kSortThreads / 64];
     const int m = blockIdx.x;
     const DevProblem *P = A.P;
-    const uint32_t C0 = P->C[0];
-    const TaskRec *tab = A.table + static_cast<size_t>(m) * P->table_total;
-    uint32_t *perm = A.perm + static_cast<size_t>(m) * C0;
-    uint32_t *run_end = A.run_end + static_cast<size_t>(m) * C0;
-    const uint32_t n_buckets = static_cast<uint32_t>(P->sum_r0 + 1) * P->n_lat0 + 1;
+    const bool second = blockIdx.y != 0;
+    const uint32_t C0 = second ? P->C[1] : P->C[0];
+    const TaskRec *tab = A.table + static_cast<size_t>(m) * P->table_total + (second ? P->table_off[1] : 0u);
+    uint32_t *perm = (second ? A.perm1 : A.perm) + static_cast<size_t>(m) * C0;
+    uint32_t *run_end = (second ? A.run_end1 : A.run_end) + static_cast<size_t>(m) * C0;
+    const uint32_t n_lat = static_cast<uint32_t>(second ? P->n_lat1 : P->n_lat0);
+    const int32_t *lat_sorted = second ? P->lat1_sorted : P->lat0_sorted;
+    const int32_t w_free = second ? A.w_free1 : A.w_free;
+    const uint32_t n_buckets = static_cast<uint32_t>((second ? P->sum_r1 : P->sum_r0) + 1) * n_lat + 1;
     if (n_buckets > kMaxBuckets) {
         for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) {
             perm[r] = r;
@@ -530,7 +536,8 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
     }
     for (uint32_t b = threadIdx.x; b < kMaxBuckets; b += kSortThreads) sHist[b] = 0;
     __syncthreads();
-    for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) atomicAdd(&sHist[root_bucket(P, tab[r], n_buckets, A.w_free)], 1u);
+    for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads)
+        atomicAdd(&sHist[root_bucket(lat_sorted, n_lat, tab[r], n_buckets, w_free)], 1u);
     __syncthreads();
     // exclusive prefix sum over the buckets: each thread owns kMaxBuckets / kSortThreads consecutive ones
     constexpr uint32_t kPer = kMaxBuckets / kSortThreads;
@@ -557,7 +564,7 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
     }
     __syncthreads();
     for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) {
-        const uint32_t b = root_bucket(P, tab[r], n_buckets, A.w_free);
+        const uint32_t b = root_bucket(lat_sorted, n_lat, tab[r], n_buckets, w_free);
         const uint32_t at = atomicAdd(&sHist[b], 1u);  // order inside a bucket is immaterial
         perm[at] = r;
         run_end[at] = sEnd[b];
@@ -574,7 +581,13 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // once (eq. (3), eq. (7)); per record it
 // then only forms the S*64 objectives (one fp64 multiply, one add each), keeps
 // their running maximum, and compares that with the lanes' best.
-template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE>
+//
+// SWAP (per-variant factors class by class, three or more tasks, whole space): a point owns only the few
+// first-task choices of its class, too few to fill a tile.  The tile then holds task 1's choices (in
+// their own run order), and the point's first-task choices join the tasks after task 1 in the work
+// item.  Every task but the first is a leaf below it here, so what an entry needs is the first task's
+// record (the same for the whole tile) and its own.
+template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE, bool SWAP>
 __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(5))) combine_kernel(SearchArgs A) {
     constexpr uint32_t kHeadBytes = offsetof(DevProblem, lat);
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
@@ -597,12 +610,17 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     const uint32_t C0 = n >= 2 ? uni(sP->C[0]) : 1u;
     // first-task choices to visit, in run order: all of them, or with classes those of this point's class
     // (the ordering kernel puts them first; the rest belong to other points)
-    const uint32_t mid_count = A.root_count ? uni(A.root_count[m]) : C0;
+    const uint32_t roots = A.root_count ? uni(A.root_count[m]) : C0;
+    // the task whose choices fill the tiles: the first one, or task 1
+    const uint32_t Cmid = SWAP ? uni(sP->C[1]) : C0;
+    const uint32_t mid_count = SWAP ? Cmid : roots;
     const uint64_t strideL = uni64(sP->stride[L]);
     const TaskRec *tab = A.table + static_cast<size_t>(m) * uni(sP->table_total);
     const TaskRec *tabL = tab + uni(sP->table_off[L]);
-    const uint32_t *perm = A.perm + static_cast<size_t>(m) * C0;
-    const uint32_t *run_end = A.run_end + static_cast<size_t>(m) * C0;
+    const TaskRec *tabM = SWAP ? tab + uni(sP->table_off[1]) : tab;
+    const uint32_t *perm0 = A.perm + static_cast<size_t>(m) * C0;
+    const uint32_t *perm = SWAP ? A.perm1 + static_cast<size_t>(m) * Cmid : perm0;
+    const uint32_t *run_end = SWAP ? A.run_end1 + static_cast<size_t>(m) * Cmid : A.run_end + static_cast<size_t>(m) * C0;
     const bool tie_index_only = A.tie_index_only != 0;
     const double npd = static_cast<double>(uni(sP->n_paths));
     const int32_t W = A.W;
@@ -610,8 +628,11 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     const uint32_t cpb = A.cpb;
     const uint32_t chunk_in_group = wave % cpb, midpart = wave / cpb, mid_split = kWavesPerBlock / cpb;
 
-    const uint64_t item_lo = A.items * blockIdx.x / A.blocks_per_m;
-    const uint64_t item_hi = A.items * (blockIdx.x + 1) / A.blocks_per_m;
+    // SWAP: the number of work items depends on the point (its first-task choices times the rest)
+    const uint64_t far_m = SWAP ? static_cast<uint64_t>(roots) * A.far2_count : A.far_span;
+    const uint64_t items_m = SWAP ? static_cast<uint64_t>(A.chunk_groups) * far_m * A.mid_tiles : A.items;
+    const uint64_t item_lo = items_m * blockIdx.x / A.blocks_per_m;
+    const uint64_t item_hi = items_m * (blockIdx.x + 1) / A.blocks_per_m;
 
     double a[S];
     int32_t w[S], lat[S];
@@ -640,6 +661,25 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     auto locate = [&](uint64_t item) {
         r = uni(static_cast<uint32_t>(item % A.mid_tiles));
         const uint64_t t = item / A.mid_tiles;
+        if (SWAP) {
+            // digits: position among the point's first-task choices, then the tasks after task 1;
+            // f keeps the latter as one number, cj[0] the first task's choice itself
+            const uint64_t ff = t % far_m;
+            g = uni(static_cast<uint32_t>(t / far_m));
+            cj[0] = uni(perm0[static_cast<uint32_t>(ff % roots)]);
+            uint64_t rest = ff / roots;
+            f = uni64(rest);
+            cj[1] = 0;
+#pragma unroll
+            for (int j = 2; j < kMaxTasks; j++) {
+                cj[j] = 0;
+                if (j < L) {
+                    cj[j] = uni(static_cast<uint32_t>(rest % sP->C[j]));
+                    rest /= sP->C[j];
+                }
+            }
+            return;
+        }
         f = uni64((A.far_first + t % A.far_span) % A.far_count);
         g = uni(static_cast<uint32_t>(t / A.far_span));
         uint64_t rest = f;
@@ -653,7 +693,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         }
         cj[0] = 0;
     };
-    locate(item_lo);
+    if (item_lo < item_hi) locate(item_lo);
     for (uint64_t item = item_lo; item < item_hi; ++item) {
         if (g != cur_group) {
             cur_group = g;
@@ -695,31 +735,54 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         int64_t lat0_cap = kNever - 1;  // largest first-task latency every other leaf's path tolerates
 #pragma unroll
         for (int j = 0; j < kMaxTasks; j++) flp[j] = 0;
+        int64_t tl_base = A.budget[L];  // latency left for the tile's task and the last task together
+        double a_first = 1.0;           // SWAP: the first task's accuracy in this work item
+        if (SWAP) {
+            // the first task's record and those of the tasks after task 1 (all leaves below the first
+            // task) are the same for the whole tile; lat0_cap bounds the latency of the entry's own task
+            const TaskRec rec0 = tab[cj[0]];
+            const int32_t w0 = uni(rec0.w), l0 = uni(rec0.lat);
+            a_first = __longlong_as_double(static_cast<long long>(uni64(static_cast<uint64_t>(__double_as_longlong(rec0.a)))));
+            w_far = w0;
+            ok_far = l0 != kNever;
 #pragma unroll
-        for (int j = 1; j < kMaxTasks; j++) {
-            if (j < L) {
-                // the same record in every lane: through readfirstlane, so that the sums, limits and
-                // selections that follow stay on the scalar unit
-                const TaskRec rec = tab[sP->table_off[j] + cj[j]];
-                const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
-                w_far += rw;
-                ok_far = ok_far && rlat != kNever;
-                flp[j] = pick_below(flp, uni(sP->parent[j]), j) + rlat;
+            for (int j = 2; j < kMaxTasks; j++) {
+                if (j < L) {
+                    const TaskRec rec = tab[sP->table_off[j] + cj[j]];
+                    const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
+                    w_far += rw;
+                    ok_far = ok_far && rlat != kNever && A.budget[j] >= 0 &&
+                             static_cast<int64_t>(l0) + rlat <= A.budget[j];
+                }
             }
-        }
+            lat0_cap = A.budget[1] < 0 ? -1 : A.budget[1] - l0;
+            if (lat0_cap < 0) ok_far = false;
+            tl_base = tl_base < 0 ? -1 : tl_base - l0;
+        } else {
 #pragma unroll
-        for (int j = 0; j < kMaxTasks; j++) {
-            if (j < L && uni(sP->is_leaf[j])) {
-                const int64_t room = A.budget[j] < 0 ? -1 : A.budget[j] - flp[j];
-                if (room < lat0_cap) lat0_cap = room;
+            for (int j = 1; j < kMaxTasks; j++) {
+                if (j < L) {
+                    // the same record in every lane: through readfirstlane, so that the sums, limits and
+                    // selections that follow stay on the scalar unit
+                    const TaskRec rec = tab[sP->table_off[j] + cj[j]];
+                    const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
+                    w_far += rw;
+                    ok_far = ok_far && rlat != kNever;
+                    flp[j] = pick_below(flp, uni(sP->parent[j]), j) + rlat;
+                }
             }
-        }
-        if (lat0_cap < 0) ok_far = false;
-        int64_t tl_base = A.budget[L];  // latency left for the first and the last task together
-        int parL = 0;
-        if (n >= 2) {
-            parL = uni(sP->parent[L]);
-            tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parL, kMaxTasks);
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++) {
+                if (j < L && uni(sP->is_leaf[j])) {
+                    const int64_t room = A.budget[j] < 0 ? -1 : A.budget[j] - flp[j];
+                    if (room < lat0_cap) lat0_cap = room;
+                }
+            }
+            if (lat0_cap < 0) ok_far = false;
+            if (n >= 2) {
+                const int parL = uni(sP->parent[L]);
+                tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parL, kMaxTasks);
+            }
         }
         const int64_t w_room = static_cast<int64_t>(W) - w_far;
 
@@ -727,11 +790,15 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         // (a point with few first-task choices may leave the later tiles of the launch empty)
         const uint32_t left = tile_base < mid_count ? mid_count - tile_base : 0u;
         const uint32_t cnt = left < A.tile_len ? left : A.tile_len;
-        const uint64_t base_f = static_cast<uint64_t>(C0) * f;  // index contribution of the tasks in between
+        // index contribution of everything but the tile's task and the last one
+        const uint64_t base_f = SWAP ? cj[0] + static_cast<uint64_t>(C0) * Cmid * f : static_cast<uint64_t>(C0) * f;
 
         // The accuracies the steps multiply by, one per step, for this combination of the tasks in
         // between.  (The factors of the previous item were last read before its tile was published.)
-        if (threadIdx.x < static_cast<uint32_t>(sP->n_prog)) {
+        if (SWAP) {  // the accuracies of the tasks after task 1, by task
+            if (threadIdx.x >= 2 && threadIdx.x < static_cast<uint32_t>(L))
+                sFac[threadIdx.x] = tab[sP->table_off[threadIdx.x] + pick32(cj, threadIdx.x)].a;
+        } else if (threadIdx.x < static_cast<uint32_t>(sP->n_prog)) {
             const int t = sP->prog_task[threadIdx.x];
             if (t >= 0) sFac[threadIdx.x] = tab[sP->table_off[t] + pick32(cj, t)].a;
         }
@@ -754,7 +821,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                 oks[k] = ok_far;
                 if (n >= 2 && e < cnt) {
                     cMs[k] = perm[tile_base + e];
-                    const TaskRec rec = tab[cMs[k]];
+                    const TaskRec rec = tabM[cMs[k]];
                     a0s[k] = rec.a;
                     w0s[k] = rec.w;
                     lat0s[k] = rec.lat;
@@ -765,8 +832,22 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                 pre[k] = 1.0;
             }
             // path values root first (eq. (12) objective, product stand-in): value = a_0 * a_j1 * a_j2 ...
+            if (SWAP) {
+                // leaves in ascending order: task 1 (the entry's), then the tasks after it; the last
+                // task's own path value is added per plan
+#pragma unroll
+                for (int k = 0; k < kSide; k++) {
+                    presum[k] = a_first * a0s[k];
+                    pre[k] = a_first;
+                }
+                for (int j = 2; j < L; j++) {
+                    const double v = a_first * sFac[j];
+#pragma unroll
+                    for (int k = 0; k < kSide; k++) presum[k] = presum[k] + v;
+                }
+            }
             bool first = true;
-            const int n_prog = uni(sP->n_prog);
+            const int n_prog = SWAP ? 0 : uni(sP->n_prog);
             for (int q = 0; q < n_prog; q++) {
                 const int op = uni(static_cast<int>(sP->prog_op[q]));
                 if (op == kStepMul) {
@@ -796,7 +877,8 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     MidLim ul;
                     uv.pre = pre[k];
                     uv.presum = presum[k];
-                    int64_t tl = tl_base < 0 ? -1 : tl_base - static_cast<int64_t>(lat0s[k]);
+                    // (SWAP: the entry's task is not on the last task's path)
+                    int64_t tl = tl_base < 0 ? -1 : tl_base - (SWAP ? 0 : static_cast<int64_t>(lat0s[k]));
                     if (tl < 0) tl = -1;
                     if (tl > kNever - 1) tl = kNever - 1;
                     ul.tl = static_cast<int32_t>(tl);
@@ -816,7 +898,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     }
                     sVal[e] = uv;
                     sLim[e] = ul;
-                    sChoice[e] = cMs[k];
+                    sChoice[e] = SWAP ? C0 * cMs[k] : cMs[k];  // the entry's part of the plan's index
                 }
             }
         }
@@ -943,7 +1025,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         }
         nfeas += fcount;
         // next item
-        if (RANGE) {
+        if (RANGE || SWAP) {
             if (item + 1 < item_hi) locate(item + 1);
         } else if (++r == A.mid_tiles) {
             r = 0;
@@ -1335,15 +1417,20 @@ __global__ void results_init_kernel(MergeArgs A) {
     static_cast<ResultOut *>(A.results)[m] = o;
 }
 
-// One thread: the classes of a demand point are few and this runs once per batch of points.
-__global__ void class_merge_kernel(MergeArgs A) {
-    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+// The classes of a demand point follow one another; the thread of the first class of each such stretch
+// folds the whole stretch into the point's result (a point's classes may continue in the next batch,
+// hence the read of what is there).
+__global__ void __launch_bounds__(kBlockThreads) class_merge_kernel(MergeArgs A) {
+    const int v0 = blockIdx.x * kBlockThreads + threadIdx.x;
+    if (v0 >= A.n) return;
+    const int point = A.point[v0];
+    if (v0 > 0 && A.point[v0 - 1] == point) return;
     const ResultOut *in = static_cast<const ResultOut *>(A.class_results);
     ResultOut *out = static_cast<ResultOut *>(A.results);
     const bool tie_index_only = A.tie_index_only != 0;
-    for (int v = 0; v < A.n; v++) {
+    ResultOut o = out[point];
+    for (int v = v0; v < A.n && A.point[v] == point; v++) {
         const ResultOut c = in[v];
-        ResultOut o = out[A.point[v]];
         o.n_feasible += c.n_feasible;
         if (c.status == 0 && (o.status != 0 || better(c.accuracy, c.workers_used, c.index, o.accuracy, o.workers_used,
                                                       o.index, tie_index_only))) {
@@ -1352,15 +1439,20 @@ __global__ void class_merge_kernel(MergeArgs A) {
             o.workers_used = c.workers_used;
             o.status = 0;
         }
-        out[A.point[v]] = o;
     }
+    out[point] = o;
 }
 
 template <int S>
 hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
-#define LOKI_LAUNCH(P, D, R)                                                     \
-    hipLaunchKernelGGL((combine_kernel<S, P, D, R>), grid, block, 0, stream, A); \
+    if (A.swap) {  // several leaves, whole space (the host sets swap only then)
+        if (divide) hipLaunchKernelGGL((combine_kernel<S, true, true, false, true>), grid, block, 0, stream, A);
+        else hipLaunchKernelGGL((combine_kernel<S, true, false, false, true>), grid, block, 0, stream, A);
+        return hipGetLastError();
+    }
+#define LOKI_LAUNCH(P, D, R)                                                            \
+    hipLaunchKernelGGL((combine_kernel<S, P, D, R, false>), grid, block, 0, stream, A); \
     return hipGetLastError();
     if (has_presum) {
         if (divide) {
@@ -1383,7 +1475,7 @@ hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStrea
 }
 
 hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream) {
-    hipLaunchKernelGGL(root_order_kernel, dim3(A.M), dim3(kSortThreads), 0, stream, A);
+    hipLaunchKernelGGL(root_order_kernel, dim3(A.M, A.swap ? 2 : 1), dim3(kSortThreads), 0, stream, A);
     return hipGetLastError();
 }
 
@@ -1424,7 +1516,7 @@ hipError_t launch_results_init(const MergeArgs &A, hipStream_t stream) {
 }
 
 hipError_t launch_class_merge(const MergeArgs &A, hipStream_t stream) {
-    hipLaunchKernelGGL(class_merge_kernel, dim3(1), dim3(64), 0, stream, A);
+    hipLaunchKernelGGL(class_merge_kernel, dim3((A.n + kBlockThreads - 1) / kBlockThreads), dim3(kBlockThreads), 0, stream, A);
     return hipGetLastError();
 }
 

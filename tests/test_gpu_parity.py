@@ -517,3 +517,38 @@ def test_per_variant_factors_with_more_classes_than_one_call_takes():
         out = P.alloc_search(demands, 9, 60_000)
         for j in list(range(0, n_points, 997)) + [n_points - 1]:
             check(out[j], O.search(demands[j], 9, 60_000), f"{n_points} points, point {j}")
+
+
+def _star_with_factors(n_tasks, seed, variants=2, replicas=2, batches=(1, 4)):
+    rng = wl.SplitMix64(seed)
+    p = wl.make_pipeline([-1] + [0] * (n_tasks - 1), variants, replicas, batches, rng)
+    # factors that grow with accuracy (Section 4.2), 0.75 .. 2.25
+    p.variant_factor_q4 = [3 + (a - 600000) // 60000 for a in p.acc_ppm]
+    return p
+
+
+@pytest.mark.parametrize("n_tasks,seed", [(4, 5), (5, 9), (3, 2)])
+def test_per_variant_factors_on_stars_with_three_and_more_leaves(n_tasks, seed):
+    """A detector feeding 2, 3 and 4 classifiers: with classes the tiles hold task 1's choices and the
+    first task's choices of the class become part of the work item, with the tasks after task 1.  Odd path
+    counts divide the objective, 18 choices per task leave most lanes' slots empty.  Against the checker's
+    brute force and the kernel that scores whole plans per lane, at demands from idle to overload, with
+    worker budgets and latency limits that bind."""
+    p = _star_with_factors(n_tasks, seed)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n == 18 ** n_tasks
+    demands = [0, 20_000, 90_000, 250_000, 600_000, 2_000_000]
+    found = 0
+    for workers, slo in ((4 * n_tasks, 400_000), (n_tasks + 2, 400_000), (4 * n_tasks, 60_000)):
+        for flags in (0, TIE):
+            by_class = P.alloc_search(demands, workers, slo, flags=flags)
+            per_lane = P.alloc_search(demands, workers, slo, flags=flags | LANE)
+            for d, a, b in zip(demands, by_class, per_lane):
+                assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
+                    a.as_tuple()[2:] == b.as_tuple()[2:], (d, workers, slo, flags, a.as_tuple(), b.as_tuple())
+            if n <= 18 ** 4:
+                for d, a in zip(demands[:4], by_class[:4]):
+                    check(a, O.search(d, workers, slo, tie_index_only=bool(flags & TIE)), f"demand {d} workers {workers}")
+            found += sum(r.status == binding.LOKI_FOUND for r in by_class)
+    assert found >= 8
