@@ -279,6 +279,15 @@ int loki_plan_trace(loki_problem_t *problem, const int64_t *trace_mqps, int32_t 
  * LOKI_E_ARG if no blocking search has completed yet. */
 int loki_last_search_ms(const loki_problem_t *problem, float *ms);
 
+/* Number of plans whose score the kernels of the most recent search on this handle (blocking or
+ * enqueued) formed, for callers that relate kernel time to work done.  The index range times the
+ * number of demand points, except where per-variant factors are searched class by class (see
+ * variant_factor_q4): plans whose first-task choice cannot serve the demand are settled on the
+ * host per choice (they still count as infeasible in the results), and the figure is the sum over
+ * the (demand point, class) pairs of the plans of the class's first-task choices; for an index range
+ * shorter than the space it is then an upper estimate.  LOKI_E_ARG before the first search. */
+int loki_last_search_plans_scored(const loki_problem_t *problem, uint64_t *plans);
+
 /* Measurement aid for the roofline (for callers that report a fraction of peak, not for the
  * search itself): sustained issue rate, in wavefront instructions per second over the whole
  * GPU, of a dependency-free stream of one vector-ALU instruction class, 8 wavefronts per SIMD.

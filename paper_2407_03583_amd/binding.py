@@ -26,7 +26,7 @@ UINT64_MAX = (1 << 64) - 1
 
 EXPORTS = ["loki_problem_create", "loki_problem_destroy", "loki_num_candidates", "loki_workspace_bytes",
            "loki_decode", "loki_alloc_search", "loki_alloc_search_enqueue", "loki_alloc_eval",
-           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_measure_valu_rate", "loki_last_search_ms", "loki_strerror", "loki_last_hip_error"]
+           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_measure_valu_rate", "loki_last_search_ms", "loki_last_search_plans_scored", "loki_strerror", "loki_last_hip_error"]
 
 
 class LokiError(RuntimeError):
@@ -141,6 +141,8 @@ def lib():
         L.loki_measure_valu_rate.argtypes = [C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
         L.loki_last_search_ms.restype = C.c_int
         L.loki_last_search_ms.argtypes = [P, C.POINTER(C.c_float)]
+        L.loki_last_search_plans_scored.restype = C.c_int
+        L.loki_last_search_plans_scored.argtypes = [P, C.POINTER(C.c_uint64)]
         L.loki_strerror.restype = C.c_char_p
         L.loki_strerror.argtypes = [C.c_int]
         L.loki_last_hip_error.restype = C.c_int
@@ -291,6 +293,12 @@ class Problem:
         ms = (C.c_float * 3)()
         _check(lib().loki_last_search_ms(self._h, ms), "loki_last_search_ms")
         return [float(v) for v in ms]
+
+    def last_search_plans_scored(self) -> int:
+        """Plans whose score the kernels of the last search formed (see the header)."""
+        n = C.c_uint64()
+        _check(lib().loki_last_search_plans_scored(self._h, C.byref(n)), "loki_last_search_plans_scored")
+        return int(n.value)
 
 
 RATE_KINDS = {"v_mul_f64": 0, "v_add_f64": 1, "v_max_f64": 2, "search_mix": 3, "v_add_u32": 4, "v_fma_f64": 5,

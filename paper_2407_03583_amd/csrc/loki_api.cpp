@@ -129,6 +129,8 @@ struct loki_problem {
     bool staged_pending = false;
     float last_ms[3] = {0.f, 0.f, 0.f};  // per-task tables, main search kernel, final merge
     bool have_ms = false;
+    uint64_t last_scored = 0;  // plans the kernels of the last search scored
+    bool have_scored = false;
 };
 
 namespace {
@@ -438,6 +440,13 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     int rc = build_class_points(p, demand_mqps, n_demand, cp);
     if (rc) return rc;
     const int64_t V = int64_t(cp.amount.size());
+    {
+        const uint64_t span = index_end - index_begin, c0 = p->dev.C[0];
+        const uint64_t per_choice = (span + c0 - 1) / c0;  // exact for the whole space
+        p->last_scored = 0;
+        for (int64_t v = 0; v < V; v++) p->last_scored += uint64_t(cp.count[size_t(v)]) * per_choice;
+        p->have_scored = true;
+    }
     std::vector<int64_t> batch_first;
     {
         // work items per first-task choice when the tiles hold task 1's choices (else one batch size fits all)
@@ -559,6 +568,8 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     }
     // the objective couples the tasks
     if (p->dev.has_vf || p->dev.has_path) flags |= LOKI_SEARCH_PER_LANE;
+    p->last_scored = (index_end - index_begin) * uint64_t(n_demand);
+    p->have_scored = true;
     const size_t cb = const_block(p);
     const Layout lay = search_layout(cb, p->dev.table_total, p->dev.C[0], n_demand);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
@@ -1181,6 +1192,13 @@ int loki_measure_valu_rate(int kind, void *d_workspace, size_t workspace_bytes, 
     if (e1) (void)hipEventDestroy(e1);
     if (e != hipSuccess) return hip_fail(e);
     *wave_instructions_per_second = double(blocks) * 4.0 * double(iters) * 16.0 / (double(ms) * 1e-3);
+    return LOKI_OK;
+}
+
+int loki_last_search_plans_scored(const loki_problem_t *p, uint64_t *plans) {
+    if (!p || !plans) return LOKI_E_NULL;
+    if (!p->have_scored) return LOKI_E_ARG;
+    *plans = p->last_scored;
     return LOKI_OK;
 }
 

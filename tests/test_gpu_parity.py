@@ -468,6 +468,12 @@ def test_per_variant_factors_class_by_class_on_a_detector_with_two_classifiers()
     p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]   # 0.75 .. 1.5
     P, O = binding.Problem(p), oracle.Problem(p)
     n = P.num_candidates()
+    p_choices = 4 ** 4 * 4      # choices of the first task
+
+    def usable(O, c0, d):       # the first task's choice c0 hosts something and serves all of demand d
+        r = O.route_table(c0, d)
+        return r.unserved[0] == 0 and any(r.capacity[0][k] > 0 for k in range(4))
+
     demands = sorted(w.demand_mqps)[::40] + [0, 30_000]
     for flags in (0, TIE):
         by_class = P.alloc_search(demands, w.workers, w.slo_us, flags=flags)
@@ -476,6 +482,12 @@ def test_per_variant_factors_class_by_class_on_a_detector_with_two_classifiers()
             assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
                 a.as_tuple()[2:] == b.as_tuple()[2:], (d, flags, a.as_tuple(), b.as_tuple())
     assert sum(r.status == binding.LOKI_FOUND for r in by_class) >= 3
+    # the kernels of the last call (per lane) scored every plan; class by class, plans whose first-task
+    # choice cannot serve the demand never reach them
+    assert P.last_search_plans_scored() == n * len(demands)
+    P.alloc_search(demands, w.workers, w.slo_us)
+    served = sum(sum(1 for c0 in range(p_choices) if usable(O, c0, d)) for d in demands)
+    assert P.last_search_plans_scored() == served * (n // p_choices) < n * len(demands)
     for d in (demands[1], 30_000):
         check(P.alloc_search([d], w.workers, w.slo_us)[0], O.search(d, w.workers, w.slo_us), f"demand {d}")
     cut = n // 3 + 777
