@@ -564,3 +564,48 @@ def test_per_variant_factors_on_stars_with_three_and_more_leaves(n_tasks, seed):
                     check(a, O.search(d, workers, slo, tie_index_only=bool(flags & TIE)), f"demand {d} workers {workers}")
             found += sum(r.status == binding.LOKI_FOUND for r in by_class)
     assert found >= 8
+
+
+def test_per_variant_factors_on_a_star_with_a_batch_size_per_variant():
+    """The class-by-class search with the other index layout (a batch size per hosted variant)."""
+    p = _star_with_factors(3, 21, variants=2, replicas=2, batches=(1, 4))
+    p.per_variant_batch = True
+    P, O = binding.Problem(p), oracle.Problem(p)
+    assert P.num_candidates() == 25 ** 3
+    demands = [0, 40_000, 150_000, 500_000]
+    for workers, slo in ((12, 400_000), (5, 400_000), (12, 50_000)):
+        by_class = P.alloc_search(demands, workers, slo)
+        per_lane = P.alloc_search(demands, workers, slo, flags=LANE)
+        for d, a, b in zip(demands, by_class, per_lane):
+            assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
+                a.as_tuple()[2:] == b.as_tuple()[2:], (d, workers, slo, a.as_tuple(), b.as_tuple())
+            check(a, O.search(d, workers, slo), f"demand {d} workers {workers} slo {slo}")
+
+
+def test_per_variant_factors_on_a_star_whose_second_task_cannot_be_ordered_into_runs():
+    """Task 1 has 66 replica counts x 64 profiled latencies, more buckets than the ordering kernel sorts,
+    so its choices cannot fill the tiles: the class-by-class search keeps the first task's choices there."""
+    rng = random.Random(5)
+    k1, nb1 = 8, 8
+    p = SimpleNamespace(
+        n_tasks=3, parent=[-1, 0, 0], fanout_q4=[4, 6, 3], n_variants=[2, k1, 2], n_batches=[1, nb1, 1],
+        batch_size=[2] + [1 << b for b in range(nb1)] + [4],
+        max_replicas=[2, 2] + [63, 1, 1, 0, 0, 0, 0, 0] + [3, 3],
+        acc_ppm=[700000, 900000] + [600000 + 40000 * k for k in range(k1)] + [650000, 880000],
+        latency_us=[4000, 9000] + [1000 + 37 * (k * nb1 + b) for k in range(k1) for b in range(nb1)] + [5000, 8000],
+        thr_mqps=[300000, 200000] + [20000 + 5000 * b + 1000 * k for k in range(k1) for b in range(nb1)] + [400000, 250000],
+        variant_factor_q4=[3, 6] + [4] * k1 + [4, 4])
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n == 9 * (64 * 2 * 2 * nb1) * 16
+    demands = [0, 60_000, 200_000, 450_000]
+    hit = 0
+    for workers, slo in ((70, 200_000), (9, 200_000), (70, 24_000)):
+        by_class = P.alloc_search(demands, workers, slo)
+        per_lane = P.alloc_search(demands, workers, slo, flags=LANE)
+        for d, a, b in zip(demands, by_class, per_lane):
+            assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
+                a.as_tuple()[2:] == b.as_tuple()[2:], (d, workers, slo, a.as_tuple(), b.as_tuple())
+        check(by_class[1], O.search(demands[1], workers, slo), f"workers {workers} slo {slo}")
+        hit += sum(r.status == binding.LOKI_FOUND for r in by_class)
+    assert hit >= 4
