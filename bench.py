@@ -118,9 +118,10 @@ def main() -> int:
     if variant:
         w.name += "+" + "+".join(variant)
     # what the library does anyway: whole plans per lane with path tables, and with per-variant factors
-    # unless every other task is a child of the first one (then the tabulated kernels run class by class)
+    # on chains (a star or a tree with two or more leaves is searched class by class by the tabulated kernels)
     star = all(par == 0 for par in w.pipeline.parent[1:]) and w.pipeline.n_tasks >= 2
-    by_class = args.variant_factors and star and not args.per_lane and not args.path_tables
+    leaves = sum(1 for i in range(w.pipeline.n_tasks) if i not in w.pipeline.parent)
+    by_class = args.variant_factors and (star or leaves >= 2) and not args.per_lane and not args.path_tables
     args.per_lane = args.per_lane or args.path_tables or (args.variant_factors and not by_class)
     P = binding.Problem(w.pipeline)
     n = P.num_candidates()

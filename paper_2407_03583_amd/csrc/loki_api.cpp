@@ -5,7 +5,9 @@
 
 #include <algorithm>
 #include <cstring>
+#include <map>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "../../include/loki_alloc.h"
@@ -41,7 +43,8 @@ struct Layout {
 
 // `cb` is the size of the constant block: the problem constants followed by the profiled path
 // accuracies (if any), see const_block().
-// c1: choices of task 1 when its run order is needed too (class-by-class searches), else 0.
+// c1: choices of the tile task of a class-by-class search with swapped roles (then off_perm1 holds a list of
+// the choices of every task, table_total entries per point, and off_run1 the tile task's runs), else 0.
 Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, uint32_t c1 = 0) {
     Layout l;
     l.off_P = 0;
@@ -50,7 +53,7 @@ Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, ui
     l.off_perm = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
     l.off_run = align_up(l.off_perm + size_t(M) * c0 * sizeof(uint32_t));
     l.off_perm1 = align_up(l.off_run + size_t(M) * c0 * sizeof(uint32_t));
-    l.off_run1 = align_up(l.off_perm1 + size_t(M) * c1 * sizeof(uint32_t));
+    l.off_run1 = align_up(l.off_perm1 + size_t(M) * (c1 ? table_total : 0u) * sizeof(uint32_t));
     l.off_recs = align_up(l.off_run1 + size_t(M) * c1 * sizeof(uint32_t));
     l.off_results = align_up(l.off_recs + (size_t(kTargetBlocks) + size_t(M)) * sizeof(BestRec));
     l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
@@ -83,8 +86,8 @@ ClassLayout class_layout(size_t cb, uint32_t table_total, uint32_t c0, uint32_t 
     l.off_P = 0;
     l.off_vDn = cb;
     l.off_vOut = align_up(l.off_vDn + size_t(kMaxClassPoints) * kMaxTasks * sizeof(int64_t));
-    l.off_vCount = align_up(l.off_vOut + size_t(kMaxClassPoints) * sizeof(int64_t));
-    l.off_vPoint = align_up(l.off_vCount + size_t(kMaxClassPoints) * sizeof(uint32_t));
+    l.off_vCount = align_up(l.off_vOut + size_t(kMaxClassPoints) * kMaxTasks * sizeof(int64_t));
+    l.off_vPoint = align_up(l.off_vCount + size_t(kMaxClassPoints) * kMaxTasks * sizeof(uint32_t));
     l.off_batch = align_up(l.off_vPoint + size_t(kMaxClassPoints) * sizeof(int32_t));
     l.batch = search_layout(0, table_total, c0, class_batch(table_total), c1);
     l.off_class_results = l.off_batch + l.batch.off_results;
@@ -229,16 +232,16 @@ int check_scalars(int32_t workers, int64_t slo_us, int64_t comm_us) {
     return LOKI_OK;
 }
 
-// What choice c of the first task does with demand D (eq. (2), Algorithm 1's fill rule; the first task's
-// units are milli-QPS): whether it serves all of it, and the requests it creates per unit of a child's
-// fan-out, sum_k routed(k) * r(0,k) (eq. (1) with per-variant factors).  Mirrors the kernels' eval_task.
-bool first_task_outflow(const loki_problem *p, uint64_t c, int64_t D, int64_t *outflow) {
+// What choice c of task i does with demand D in the task's own units (eq. (2), Algorithm 1's fill rule):
+// whether it serves all of it, and the requests it creates per unit of a child's fan-out,
+// sum_k routed(k) * r(i,k) (eq. (1) with per-variant factors).  Mirrors the kernels' eval_task.
+bool task_outflow(const loki_problem *p, int i, uint64_t c, int64_t D, int64_t *outflow) {
     const DevProblem &d = p->dev;
-    const int K = d.K[0], nb = d.nb[0];
+    const int K = d.K[i], nb = d.nb[i];
     int32_t x[kMaxVariants], beta[kMaxVariants];
     for (int k = 0; k < K; k++) {
-        const uint64_t g = c % d.radix[0][k];
-        c /= d.radix[0][k];
+        const uint64_t g = c % d.radix[i][k];
+        c /= d.radix[i][k];
         if (d.pv_batch) {
             x[k] = g == 0 ? 0 : int32_t((g - 1) / nb) + 1;
             beta[k] = g == 0 ? 0 : int32_t((g - 1) % nb);
@@ -251,11 +254,11 @@ bool first_task_outflow(const loki_problem *p, uint64_t c, int64_t D, int64_t *o
     int64_t rem = D, out = 0;
     bool any = false;
     for (int o = 0; o < K; o++) {
-        const int k = d.order[0][o];
+        const int k = d.order[i][o];
         if (x[k] == 0) continue;
-        const int64_t cap = int64_t(x[k]) * d.thr_s[0][k][beta[k]];
+        const int64_t cap = int64_t(x[k]) * d.thr_s[i][k][beta[k]];
         const int64_t routed = std::min(rem, cap);
-        out += routed * int64_t(d.vf[0][k]);
+        out += routed * int64_t(d.vf[i][k]);
         rem -= routed;
         any = true;
     }
@@ -263,38 +266,87 @@ bool first_task_outflow(const loki_problem *p, uint64_t c, int64_t D, int64_t *o
     return any && rem == 0;
 }
 
-// The (demand point, class) pairs of a call: per demand point the distinct amounts of requests the
-// first task's usable choices create, ascending, with the number of choices per amount.
+// The points of a class-by-class search: per demand point every combination of one class per task that
+// has children, a class being one amount of requests the task's usable choices create under the demand
+// the classes of its ancestors give it.  That fixes every task's demand.  Per point: the demands, the
+// amounts (-1 for a leaf), and per task the number of its choices that belong (all of a leaf's).
 struct ClassPoints {
     std::vector<int64_t> Dn;        // [n][kMaxTasks]
-    std::vector<int64_t> amount;    // [n]
-    std::vector<uint32_t> count;    // [n]
+    std::vector<int64_t> amount;    // [n][kMaxTasks]
+    std::vector<uint32_t> count;    // [n][kMaxTasks]
     std::vector<int32_t> point;     // [n]
+    size_t size() const { return point.size(); }
 };
 
-int build_class_points(const loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, ClassPoints &cp) {
-    std::vector<int64_t> amounts;
-    for (int32_t m = 0; m < n_demand; m++) {
-        int64_t Dn[kMaxTasks];
-        const int rc = task_demand(p, demand_mqps[m], Dn);  // range proof with the largest factors
-        if (rc) return rc;
-        amounts.clear();
-        for (uint64_t c = 0; c < p->dev.C[0]; c++) {
+struct ClassWalk {
+    const loki_problem *p;
+    ClassPoints *cp;
+    int32_t point;
+    int64_t Dn[kMaxTasks], amount[kMaxTasks];
+    uint32_t count[kMaxTasks];
+    // classes of (task, demand), kept while one demand point is walked
+    std::map<std::pair<int, int64_t>, std::vector<std::pair<int64_t, uint32_t>>> memo;
+};
+
+// Tasks in index order (parents first).  Returns LOKI_E_ARG when the call has too many points.
+int walk_classes(ClassWalk &w, int i) {
+    const loki_problem *p = w.p;
+    if (i == p->n) {
+        if (int64_t(w.cp->size()) >= kMaxClassPoints) return LOKI_E_ARG;  // caller falls back
+        w.cp->point.push_back(w.point);
+        for (int j = 0; j < kMaxTasks; j++) {
+            w.cp->Dn.push_back(j < p->n ? w.Dn[j] : 0);
+            w.cp->amount.push_back(j < p->n ? w.amount[j] : -1);
+            w.cp->count.push_back(j < p->n ? w.count[j] : 1u);
+        }
+        return LOKI_OK;
+    }
+    if (i > 0) w.Dn[i] = w.amount[p->dev.parent[i]] * int64_t(p->fanout_q4[i]);
+    if (p->dev.is_leaf[i]) {
+        w.amount[i] = -1;
+        w.count[i] = p->dev.C[i];
+        return walk_classes(w, i + 1);
+    }
+    auto key = std::make_pair(i, w.Dn[i]);
+    auto it = w.memo.find(key);
+    if (it == w.memo.end()) {
+        std::vector<int64_t> amounts;
+        for (uint64_t c = 0; c < p->dev.C[i]; c++) {
             int64_t out;
-            if (first_task_outflow(p, c, demand_mqps[m], &out)) amounts.push_back(out);
+            if (task_outflow(p, i, c, w.Dn[i], &out)) amounts.push_back(out);
         }
         std::sort(amounts.begin(), amounts.end());
+        std::vector<std::pair<int64_t, uint32_t>> classes;
         for (size_t a = 0; a < amounts.size();) {
             size_t b = a;
             while (b < amounts.size() && amounts[b] == amounts[a]) b++;
-            if (int64_t(cp.amount.size()) >= kMaxClassPoints) return LOKI_E_ARG;  // caller falls back
-            cp.amount.push_back(amounts[a]);
-            cp.count.push_back(uint32_t(b - a));
-            cp.point.push_back(m);
-            for (int i = 0; i < kMaxTasks; i++)
-                cp.Dn.push_back(i == 0 ? demand_mqps[m] : (i < p->n ? amounts[a] * int64_t(p->fanout_q4[i]) : 0));
+            classes.emplace_back(amounts[a], uint32_t(b - a));
             a = b;
         }
+        it = w.memo.emplace(key, std::move(classes)).first;
+    }
+    for (const auto &cls : it->second) {
+        w.amount[i] = cls.first;
+        w.count[i] = cls.second;
+        const int rc = walk_classes(w, i + 1);
+        if (rc) return rc;
+    }
+    return LOKI_OK;
+}
+
+int build_class_points(const loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, ClassPoints &cp) {
+    ClassWalk w;
+    w.p = p;
+    w.cp = &cp;
+    for (int32_t m = 0; m < n_demand; m++) {
+        int64_t bound[kMaxTasks];
+        const int rc = task_demand(p, demand_mqps[m], bound);  // range proof with the largest factors
+        if (rc) return rc;
+        w.memo.clear();
+        w.point = m;
+        w.Dn[0] = demand_mqps[m];
+        const int rc2 = walk_classes(w, 0);
+        if (rc2) return rc2;
     }
     return LOKI_OK;
 }
@@ -302,19 +354,21 @@ int build_class_points(const loki_problem *p, const int64_t *demand_mqps, int32_
 // Order of the (demand point, class) pairs and their split into batches.  The blocks of a launch are
 // shared out evenly among its pairs, so a batch should hold pairs of similar size: pairs go by
 // descending number of first-task choices, a batch takes as many as leave each of its pairs about one
-// block per kClassItemsPerBlock work items, and inside a batch the pairs of a demand point are kept
-// together (the merge folds stretches of equal points).
+// block per kClassItemsPerBlock work items (items: work items per pair, 1 each where that does not
+// apply), and inside a batch the pairs of a demand point are kept together (the merge folds stretches
+// of equal points).
 constexpr uint64_t kClassItemsPerBlock = 8;
 
-void plan_class_batches(ClassPoints &cp, uint64_t items_per_choice, int32_t batch_limit, std::vector<int64_t> &batch_first) {
-    const size_t V = cp.amount.size();
+void plan_class_batches(ClassPoints &cp, const std::vector<uint64_t> &items, int32_t batch_limit,
+                        std::vector<int64_t> &batch_first) {
+    const size_t V = cp.size();
     std::vector<uint32_t> order(V);
     for (size_t v = 0; v < V; v++) order[v] = uint32_t(v);
-    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return cp.count[a] > cp.count[b]; });
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return items[a] > items[b]; });
     batch_first.clear();
     for (size_t at = 0; at < V;) {
-        const uint64_t items = std::max<uint64_t>(1, uint64_t(cp.count[order[at]]) * items_per_choice);
-        const uint64_t blocks = std::max<uint64_t>(1, (items + kClassItemsPerBlock - 1) / kClassItemsPerBlock);
+        const uint64_t most = std::max<uint64_t>(1, items[order[at]]);
+        const uint64_t blocks = std::max<uint64_t>(1, (most + kClassItemsPerBlock - 1) / kClassItemsPerBlock);
         const size_t take = size_t(std::min<uint64_t>(uint64_t(batch_limit), std::max<uint64_t>(1, kTargetBlocks / blocks)));
         const size_t end = std::min(V, at + take);
         std::stable_sort(order.begin() + at, order.begin() + end,
@@ -325,25 +379,27 @@ void plan_class_batches(ClassPoints &cp, uint64_t items_per_choice, int32_t batc
     batch_first.push_back(int64_t(V));
     ClassPoints out;
     out.Dn.resize(cp.Dn.size());
-    out.amount.resize(V);
-    out.count.resize(V);
+    out.amount.resize(cp.amount.size());
+    out.count.resize(cp.count.size());
     out.point.resize(V);
     for (size_t v = 0; v < V; v++) {
-        const uint32_t src = order[v];
-        std::copy(cp.Dn.begin() + size_t(src) * kMaxTasks, cp.Dn.begin() + size_t(src + 1) * kMaxTasks,
-                  out.Dn.begin() + v * kMaxTasks);
-        out.amount[v] = cp.amount[src];
-        out.count[v] = cp.count[src];
+        const size_t src = order[v];
+        for (int j = 0; j < kMaxTasks; j++) {
+            out.Dn[v * kMaxTasks + j] = cp.Dn[src * kMaxTasks + j];
+            out.amount[v * kMaxTasks + j] = cp.amount[src * kMaxTasks + j];
+            out.count[v * kMaxTasks + j] = cp.count[src * kMaxTasks + j];
+        }
         out.point[v] = cp.point[src];
     }
     cp = std::move(out);
 }
 
 // Launch configuration and launches of the tabulated kernels (per-task tables, run order, the kernel
-// that visits every plan) for the A.M points A describes.  root_choices: the most first-task choices any
-// point visits (all of them, or the largest class).  before_search / after_search: events recorded around
-// the kernel that visits every plan, or null.
-int launch_tabulated(loki_problem *p, SearchArgs A, uint32_t root_choices, uint64_t index_begin, uint64_t index_end,
+// that visits every plan) for the A.M points A describes.  most: the most first-task choices any point
+// visits (all of them, or the largest class); with swapped roles (A.swap, set by the caller: classes, two
+// or more leaves, whole space) the most combinations of the work item's tasks any point has.
+// before_search / after_search: events recorded around the kernel that visits every plan, or null.
+int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t index_begin, uint64_t index_end,
                      hipStream_t stream, hipEvent_t before_search, hipEvent_t after_search) {
     const int n = p->n, L = n - 1;
     const uint64_t span = index_end - index_begin;
@@ -356,17 +412,13 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint32_t root_choices, uint6
     uint64_t F = 1;
     for (int j = 1; j < L; j++) F *= p->dev.C[j];
     const uint32_t C0 = n >= 2 ? p->dev.C[0] : 1u;
-    uint32_t mid_count = std::max<uint32_t>(1u, std::min(root_choices, C0));
-    // Classes on a tree of three or more tasks, whole space: a point's first-task choices are few, so
-    // task 1's choices fill the tiles and the first task's join the work item (see combine_kernel).
-    A.swap = 0;
-    A.far2_count = 1;
-    if (A.class_out && n >= 3 && span > 0 && index_begin == 0 && index_end == p->n_candidates &&
-        uint64_t(p->dev.sum_r1 + 1) * uint64_t(p->dev.n_lat1) + 1 <= 4096) {
-        A.swap = 1;
-        for (int j = 2; j < L; j++) A.far2_count *= p->dev.C[j];
-        F = uint64_t(mid_count) * A.far2_count;  // the most any point has; a point's own count is taken in the kernel
-        mid_count = p->dev.C[1];
+    uint32_t mid_count = static_cast<uint32_t>(std::max<uint64_t>(1u, std::min<uint64_t>(most, C0)));
+    if (A.swap) {
+        // a point's choices of the tasks with children are few, so the first leaf's choices fill the tiles
+        // and all the other tasks but the last make up the work item (see combine_kernel)
+        A.swap_tasks = uint32_t(L);
+        F = std::max<uint64_t>(1, most);  // the most any point has; a point's own count is taken in the kernel
+        mid_count = p->dev.C[p->dev.tile_task];
     }
     A.far_count = F;
     A.tile_len = kMidTile;
@@ -422,9 +474,23 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint32_t root_choices, uint6
     return LOKI_OK;
 }
 
+// How a class-by-class search of [index_begin, index_end) would run: 2 with swapped roles (two or more
+// leaves, the first leaf's choices orderable into runs and its index part within 32 bits, whole space),
+// 1 with the first task's choices in the tiles (every other task a child of the first one, its choices
+// orderable into runs), 0 not at all.
+int class_search_mode(const loki_problem *p, uint64_t index_begin, uint64_t index_end) {
+    if (!p->dev.has_vf || p->dev.has_path || p->n < 2 || p->dev.table_total > (1u << 16)) return 0;
+    const int t = p->dev.tile_task;
+    if (p->dev.n_paths >= 2 && index_begin == 0 && index_end == p->n_candidates && index_end > 0 &&
+        uint64_t(p->dev.sum_r_t + 1) * uint64_t(p->dev.n_lat_t) + 1 <= 4096 &&
+        p->dev.stride[t] <= (uint64_t(1) << 32) / p->dev.C[t])
+        return 2;
+    if (p->star && uint64_t(p->dev.sum_r0 + 1) * uint64_t(p->dev.n_lat0) + 1 <= 4096) return 1;
+    return 0;
+}
+
 bool class_search_applies(const loki_problem *p) {
-    return p->dev.has_vf && !p->dev.has_path && p->star && p->dev.table_total <= (1u << 16) &&
-           uint64_t(p->dev.sum_r0 + 1) * uint64_t(p->dev.n_lat0) + 1 <= 4096;
+    return class_search_mode(p, 0, p->n_candidates) != 0 || class_search_mode(p, 0, 0) != 0;
 }
 
 int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers,
@@ -432,31 +498,49 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
                          void *d_workspace, size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed,
                          void **results_at) {
     const size_t cb = const_block(p);
-    const ClassLayout lay = class_layout(cb, p->dev.table_total, p->dev.C[0], p->n >= 2 ? p->dev.C[1] : 0u, n_demand);
+    const int mode = class_search_mode(p, index_begin, index_end);
+    if (mode == 0) return LOKI_E_ARG;  // caller takes the general path
+    const bool swap = mode == 2;
+    const int L = p->n - 1, T = p->dev.tile_task;
+    const ClassLayout lay = class_layout(cb, p->dev.table_total, p->dev.C[0], p->dev.C[T], n_demand);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
         return LOKI_E_WORKSPACE;
     if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
     ClassPoints cp;
     int rc = build_class_points(p, demand_mqps, n_demand, cp);
     if (rc) return rc;
-    const int64_t V = int64_t(cp.amount.size());
+    const int64_t V = int64_t(cp.size());
+    // per point: the combinations of the work item's tasks (swapped roles) or the first task's choices
+    auto far_of = [&](int64_t v) {
+        const uint32_t *cnt = cp.count.data() + size_t(v) * kMaxTasks;
+        if (!swap) return uint64_t(cnt[0]);
+        uint64_t far = 1;
+        for (int j = 0; j < L; j++)
+            if (j != T) far *= cnt[j];
+        return far;
+    };
     {
         const uint64_t span = index_end - index_begin, c0 = p->dev.C[0];
-        const uint64_t per_choice = (span + c0 - 1) / c0;  // exact for the whole space
         p->last_scored = 0;
-        for (int64_t v = 0; v < V; v++) p->last_scored += uint64_t(cp.count[size_t(v)]) * per_choice;
+        for (int64_t v = 0; v < V; v++) {
+            const uint32_t *cnt = cp.count.data() + size_t(v) * kMaxTasks;
+            uint64_t plans = uint64_t(cnt[0]) * ((span + c0 - 1) / c0);  // exact for the whole space
+            if (swap) {
+                plans = 1;
+                for (int j = 0; j < p->n; j++) plans *= cnt[j];
+            }
+            p->last_scored += plans;
+        }
         p->have_scored = true;
     }
     std::vector<int64_t> batch_first;
     {
-        // work items per first-task choice when the tiles hold task 1's choices (else one batch size fits all)
-        const int L = p->n - 1;
-        uint64_t per_choice = 0;
-        if (p->n >= 3 && index_begin == 0 && index_end == p->n_candidates) {
-            per_choice = (p->dev.C[1] + kMidTile - 1) / kMidTile;
-            for (int j = 2; j < L; j++) per_choice *= p->dev.C[j];
-        }
-        plan_class_batches(cp, per_choice, class_batch(p->dev.table_total), batch_first);
+        // work items per point with swapped roles (else one batch size fits all)
+        const uint64_t mid_tiles = (p->dev.C[T] + kMidTile - 1) / kMidTile;
+        std::vector<uint64_t> items(size_t(V), 1);
+        if (swap)
+            for (int64_t v = 0; v < V; v++) items[size_t(v)] = far_of(v) * mid_tiles;
+        plan_class_batches(cp, items, class_batch(p->dev.table_total), batch_first);
     }
 
     rc = ensure_staging(p, n_demand);
@@ -465,7 +549,7 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
         LOKI_HIP(hipEventSynchronize(p->staged));
         p->staged_pending = false;
     }
-    const size_t per_point = kMaxTasks * sizeof(int64_t) + sizeof(int64_t) + sizeof(uint32_t) + sizeof(int32_t);
+    const size_t per_point = kMaxTasks * (2 * sizeof(int64_t) + sizeof(uint32_t)) + sizeof(int32_t);
     if (!p->class_staging) {
         void *ptr = nullptr;
         LOKI_HIP(hipHostMalloc(&ptr, size_t(kMaxClassPoints) * per_point, hipHostMallocDefault));
@@ -476,8 +560,8 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, cb, hipMemcpyHostToDevice, stream));
     if (V > 0) {
         unsigned char *h = p->class_staging;
-        const size_t nDn = size_t(V) * kMaxTasks * sizeof(int64_t), nOut = size_t(V) * sizeof(int64_t),
-                     nCount = size_t(V) * sizeof(uint32_t), nPoint = size_t(V) * sizeof(int32_t);
+        const size_t nDn = size_t(V) * kMaxTasks * sizeof(int64_t), nOut = size_t(V) * kMaxTasks * sizeof(int64_t),
+                     nCount = size_t(V) * kMaxTasks * sizeof(uint32_t), nPoint = size_t(V) * sizeof(int32_t);
         std::memcpy(h, cp.Dn.data(), nDn);
         std::memcpy(h + nDn, cp.amount.data(), nOut);
         std::memcpy(h + nDn + nOut, cp.count.data(), nCount);
@@ -511,8 +595,9 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     A.recs = reinterpret_cast<BestRec *>(bw + lay.batch.off_recs);
     A.perm = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm);
     A.run_end = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run);
-    A.perm1 = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm1);
-    A.run_end1 = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run1);
+    A.perm_all = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm1);
+    A.run_end_t = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run1);
+    A.swap = swap ? 1u : 0u;
     A.results = ws + lay.off_class_results;
     path_budgets(p, slo_us, comm_us, A.budget);
     A.begin = index_begin;
@@ -522,8 +607,8 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
         int64_t others = 0;
         for (int i = 1; i < p->n; i++) others += p->sum_r[i];
         A.w_free = static_cast<int32_t>(std::max<int64_t>(int64_t(workers) - others, -1));
-        const int64_t others1 = p->n >= 2 ? others + p->sum_r[0] - p->sum_r[1] : 0;  // all tasks but task 1
-        A.w_free1 = static_cast<int32_t>(std::max<int64_t>(int64_t(workers) - others1, -1));
+        const int64_t others_t = others + p->sum_r[0] - p->sum_r[T];  // all tasks but the tile task
+        A.w_free_t = static_cast<int32_t>(std::max<int64_t>(int64_t(workers) - others_t, -1));
     }
     A.tie_index_only = G.tie_index_only;
     for (size_t b = 0; b + 1 < batch_first.size(); b++) {
@@ -531,10 +616,10 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
         const int32_t nb = int32_t(batch_first[b + 1] - v0);
         A.M = nb;
         A.Dn = reinterpret_cast<const int64_t *>(ws + lay.off_vDn) + size_t(v0) * kMaxTasks;
-        A.class_out = reinterpret_cast<const int64_t *>(ws + lay.off_vOut) + v0;
-        A.root_count = reinterpret_cast<const uint32_t *>(ws + lay.off_vCount) + v0;
-        uint32_t most = 1;
-        for (int32_t j = 0; j < nb; j++) most = std::max(most, cp.count[size_t(v0 + j)]);
+        A.class_amount = reinterpret_cast<const int64_t *>(ws + lay.off_vOut) + size_t(v0) * kMaxTasks;
+        A.class_count = reinterpret_cast<const uint32_t *>(ws + lay.off_vCount) + size_t(v0) * kMaxTasks;
+        uint64_t most = 1;
+        for (int32_t j = 0; j < nb; j++) most = std::max(most, far_of(v0 + j));
         const bool first = v0 == 0, last = v0 + nb >= V;
         rc = launch_tabulated(p, A, most, index_begin, index_end, stream, timed && first ? p->ev[1] : nullptr,
                               timed && last ? p->ev[2] : nullptr);
@@ -561,7 +646,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     // Per-variant factors: a task's demand depends on its parent's part of the plan.  Where every other
     // task is a child of the first one, that dependence is one number per first-task choice (the requests
     // it creates), and the tabulated kernels run once per distinct value; otherwise whole plans per lane.
-    if (class_search_applies(p) && !(flags & LOKI_SEARCH_PER_LANE)) {
+    if (class_search_mode(p, index_begin, index_end) != 0 && !(flags & LOKI_SEARCH_PER_LANE)) {
         rc = enqueue_class_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
                                   d_workspace, workspace_bytes, stream, d_results, timed, results_at);
         if (rc != LOKI_E_ARG) return rc;  // LOKI_E_ARG: too many classes, take the general path
@@ -792,16 +877,18 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         d.sum_r0 = 0;
         for (int k = 0; k < d.K[0]; k++) d.sum_r0 += in->max_replicas[k];  // task 0's variants come first
     }
-    d.n_lat1 = 1;
-    if (n >= 2) {  // the same for task 1
+    {  // the same for the first leaf (the task whose choices fill the tiles when the roles are swapped)
+        int t = 0;
+        while (t < n - 1 && !d.is_leaf[t]) t++;
+        d.tile_task = t;
         std::vector<int32_t> lats;
-        for (int k = 0; k < d.K[1]; k++)
-            for (int bi = 0; bi < d.nb[1]; bi++) lats.push_back(int32_t(d.lat[1][k][bi]));
+        for (int k = 0; k < d.K[t]; k++)
+            for (int bi = 0; bi < d.nb[t]; bi++) lats.push_back(int32_t(d.lat[t][k][bi]));
         std::sort(lats.begin(), lats.end());
         lats.erase(std::unique(lats.begin(), lats.end()), lats.end());
-        d.n_lat1 = int32_t(lats.size());
-        for (size_t q = 0; q < lats.size(); q++) d.lat1_sorted[q] = lats[q];
-        d.sum_r1 = p->sum_r[1];
+        d.n_lat_t = int32_t(lats.size());
+        for (size_t q = 0; q < lats.size(); q++) d.lat_t_sorted[q] = lats[q];
+        d.sum_r_t = p->sum_r[t];
     }
     d.n_paths = 0;
     for (int i = 0; i < n; i++) d.n_paths += d.is_leaf[i];
@@ -885,7 +972,7 @@ int loki_workspace_bytes(const loki_problem_t *p, int64_t n_demand, size_t *byte
     *bytes = std::max(search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total,
                       eval_layout(const_block(p), n_demand).total);
     if (class_search_applies(p))
-        *bytes = std::max(*bytes, class_layout(const_block(p), p->dev.table_total, p->dev.C[0], p->n >= 2 ? p->dev.C[1] : 0u, n_demand).total);
+        *bytes = std::max(*bytes, class_layout(const_block(p), p->dev.table_total, p->dev.C[0], p->dev.C[p->dev.tile_task], n_demand).total);
     return LOKI_OK;
 }
 

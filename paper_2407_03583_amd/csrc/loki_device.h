@@ -36,7 +36,7 @@ struct DevProblem {
     int32_t sum_r0;                         // sum of the replica limits of task 0
     int32_t has_vf;                         // per-variant multiplicative factors are present
     int32_t pv_batch;                       // a batch size per hosted variant instead of one per task
-    int32_t pad1;
+    int32_t tile_task;                      // class-by-class searches with swapped roles: the leaf whose choices fill the tiles
     int32_t lat0_sorted[kMaxVariants * kMaxBatches];  // those latencies, ascending
     // How the path values that do not involve the last task are formed from the first task's accuracy:
     // a list of steps, each "multiply by the accuracy of task prog_task[q]" (kStepMul), "the value is a
@@ -61,10 +61,10 @@ struct DevProblem {
     uint32_t path_total;                    // entries over all leaves
     uint32_t path_off[kMaxTasks];           // first entry of leaf i's table
     int32_t leaf_path[kMaxTasks][kMaxTasks];  // tasks on the chain root..i, root first (path_len[i] of them)
-    // the same ordering data as n_lat0 / sum_r0 / lat0_sorted for task 1 (used when its records fill the tiles)
-    int32_t n_lat1;
-    int32_t sum_r1;
-    int32_t lat1_sorted[kMaxVariants * kMaxBatches];
+    // the same ordering data as n_lat0 / sum_r0 / lat0_sorted for the task tile_task
+    int32_t n_lat_t;
+    int32_t sum_r_t;
+    int32_t lat_t_sorted[kMaxVariants * kMaxBatches];
 };
 
 // What a task contributes to any plan that uses one of its choices
@@ -110,20 +110,21 @@ struct SearchArgs {
     uint32_t *run_end;      // [M][C_0] end (exclusive) of the run each position belongs to
     void *results;          // [M] loki_result_t
     const double *path_acc; // [path_total] profiled path accuracies as fractions, or null
-    // Per-variant factors on a tree whose other tasks all hang off the first task: a "point" of the launch
-    // is then a (demand point, class) pair, the class being one value of the requests the first task
-    // creates per unit of fan-out.  class_out[point] is that value (first-task choices that create another
-    // amount do not belong to the point), root_count[point] the number of first-task choices that do.
-    const int64_t *class_out;   // null: points are plain demand points
-    const uint32_t *root_count;
-    // With classes on a tree of three or more tasks the roles of the first two tasks are swapped: a
-    // point's few first-task choices become part of the work item (with the tasks after task 1), and
-    // the tiles hold task 1's choices in the run order perm1 / run_end1 ([M][C_1]).
-    uint32_t *perm1;
-    uint32_t *run_end1;
-    uint64_t far2_count;    // prod of C_j over the tasks strictly between task 1 and the last
+    // Per-variant factors searched class by class: a "point" of the launch is a demand point together
+    // with one value, per task that has children, of the requests the task creates per unit of fan-out
+    // (that fixes every task's demand).  class_amount[point][i] is that value for task i (-1: any choice of
+    // task i belongs to the point), class_count[point][i] the number of task i's choices that belong.
+    const int64_t *class_amount;   // [M][kMaxTasks]; null: points are plain demand points
+    const uint32_t *class_count;   // [M][kMaxTasks]
+    // With swapped roles (swap != 0; two or more leaves, whole space) the tiles hold the choices of the
+    // first leaf (DevProblem::tile_task) in the run order perm_all / run_end_t, and every other task but the
+    // last is part of the work item: a task with children through the list of its choices that belong to
+    // the point (perm_all lists them first), a leaf through all of its choices.
+    uint32_t *perm_all;     // [M][table_total]: per task (at table_off) its choices, usable ones first
+    uint32_t *run_end_t;    // [M][C_tile_task]
     uint32_t swap;
-    int32_t w_free1;        // like w_free, for task 1
+    uint32_t swap_tasks;    // number of tasks (the ordering kernel runs for every task but the last)
+    int32_t w_free_t;       // like w_free, for the tile task
     int64_t budget[kMaxTasks];  // per task i: floor((slo - comm*path_len[i]) / 2), -1 if negative
     uint64_t begin, end;    // index range
     uint64_t far_count;     // F = prod of C_j over the tasks strictly between the first and the last

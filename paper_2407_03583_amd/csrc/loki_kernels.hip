@@ -480,8 +480,11 @@ __global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A)
     rec.a = task_accuracy(o, Dn);
     rec.w = o.w;
     bool usable = o.any && o.rem == 0;
-    // (demand point, class) pairs: only the first-task choices that create the class's amount of requests
-    if (A.class_out && i == 0) usable = usable && o.outflow == A.class_out[m];
+    // class by class: only the choices that create the class's amount of requests belong to the point
+    if (A.class_amount) {
+        const int64_t amount = A.class_amount[static_cast<size_t>(m) * kMaxTasks + i];
+        if (amount >= 0) usable = usable && o.outflow == amount;
+    }
     rec.lat = usable ? static_cast<int32_t>(o.maxlat) : kNever;
     A.table[static_cast<size_t>(m) * sP.table_total + t] = rec;
 }
@@ -510,34 +513,42 @@ __device__ __forceinline__ uint32_t root_bucket(const int32_t *lat_sorted, uint3
     return static_cast<uint32_t>(wk) * n_lat + rank;
 }
 
-// blockIdx.y = 0: the first task's choices; 1 (launched only when the roles of the first two tasks are
-// swapped): task 1's.
+// Without swapped roles one launch row: the first task's choices into A.perm / A.run_end.  With swapped
+// roles blockIdx.y is the task: the tile task's choices go into runs (A.perm_all at the task's offset,
+// A.run_end_t), every other task's choices are only split into usable ones first and the rest.
 __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) {
     __shared__ uint32_t sHist[kMaxBuckets];   // counts, then next free position per bucket
     __shared__ uint32_t sEnd[kMaxBuckets];    // end position per bucket
     __shared__ uint32_t sWaveTot[kSortThreads / 64];
     const int m = blockIdx.x;
     const DevProblem *P = A.P;
-    const bool second = blockIdx.y != 0;
-    const uint32_t C0 = second ? P->C[1] : P->C[0];
-    const TaskRec *tab = A.table + static_cast<size_t>(m) * P->table_total + (second ? P->table_off[1] : 0u);
-    uint32_t *perm = (second ? A.perm1 : A.perm) + static_cast<size_t>(m) * C0;
-    uint32_t *run_end = (second ? A.run_end1 : A.run_end) + static_cast<size_t>(m) * C0;
-    const uint32_t n_lat = static_cast<uint32_t>(second ? P->n_lat1 : P->n_lat0);
-    const int32_t *lat_sorted = second ? P->lat1_sorted : P->lat0_sorted;
-    const int32_t w_free = second ? A.w_free1 : A.w_free;
-    const uint32_t n_buckets = static_cast<uint32_t>((second ? P->sum_r1 : P->sum_r0) + 1) * n_lat + 1;
-    if (n_buckets > kMaxBuckets) {
+    const int task = A.swap ? static_cast<int>(blockIdx.y) : 0;
+    const bool tile = A.swap && task == P->tile_task;
+    const bool runs = !A.swap || tile;
+    const uint32_t C0 = P->C[task];
+    const TaskRec *tab = A.table + static_cast<size_t>(m) * P->table_total + P->table_off[task];
+    uint32_t *perm = A.swap ? A.perm_all + static_cast<size_t>(m) * P->table_total + P->table_off[task]
+                            : A.perm + static_cast<size_t>(m) * C0;
+    uint32_t *run_end = A.swap ? (tile ? A.run_end_t + static_cast<size_t>(m) * C0 : nullptr)
+                               : A.run_end + static_cast<size_t>(m) * C0;
+    const uint32_t n_lat = static_cast<uint32_t>(tile ? P->n_lat_t : P->n_lat0);
+    const int32_t *lat_sorted = tile ? P->lat_t_sorted : P->lat0_sorted;
+    const int32_t w_free = tile ? A.w_free_t : A.w_free;
+    const uint32_t n_buckets = runs ? static_cast<uint32_t>((tile ? P->sum_r_t : P->sum_r0) + 1) * n_lat + 1 : 2u;
+    auto bucket_of = [&](const TaskRec &rec) -> uint32_t {
+        if (!runs) return rec.lat == kNever ? 1u : 0u;
+        return root_bucket(lat_sorted, n_lat, rec, n_buckets, w_free);
+    };
+    if (n_buckets > kMaxBuckets) {  // (never with swapped roles: the host checks the tile task's buckets)
         for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) {
             perm[r] = r;
-            run_end[r] = r + 1;
+            if (run_end) run_end[r] = r + 1;
         }
         return;
     }
     for (uint32_t b = threadIdx.x; b < kMaxBuckets; b += kSortThreads) sHist[b] = 0;
     __syncthreads();
-    for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads)
-        atomicAdd(&sHist[root_bucket(lat_sorted, n_lat, tab[r], n_buckets, w_free)], 1u);
+    for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) atomicAdd(&sHist[bucket_of(tab[r])], 1u);
     __syncthreads();
     // exclusive prefix sum over the buckets: each thread owns kMaxBuckets / kSortThreads consecutive ones
     constexpr uint32_t kPer = kMaxBuckets / kSortThreads;
@@ -564,10 +575,10 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
     }
     __syncthreads();
     for (uint32_t r = threadIdx.x; r < C0; r += kSortThreads) {
-        const uint32_t b = root_bucket(lat_sorted, n_lat, tab[r], n_buckets, w_free);
+        const uint32_t b = bucket_of(tab[r]);
         const uint32_t at = atomicAdd(&sHist[b], 1u);  // order inside a bucket is immaterial
         perm[at] = r;
-        run_end[at] = sEnd[b];
+        if (run_end) run_end[at] = sEnd[b];
     }
 }
 
@@ -582,11 +593,13 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // then only forms the S*64 objectives (one fp64 multiply, one add each), keeps
 // their running maximum, and compares that with the lanes' best.
 //
-// SWAP (per-variant factors class by class, three or more tasks, whole space): a point owns only the few
-// first-task choices of its class, too few to fill a tile.  The tile then holds task 1's choices (in
-// their own run order), and the point's first-task choices join the tasks after task 1 in the work
-// item.  Every task but the first is a leaf below it here, so what an entry needs is the first task's
-// record (the same for the whole tile) and its own.
+// SWAP (per-variant factors class by class, two or more leaves, whole space): a point owns only a few
+// choices of every task that has children, too few to fill a tile.  The tile then holds the choices of
+// the first leaf (in their own run order), and every other task but the last is part of the work item:
+// a task with children through the list of its choices that belong to the point, a leaf through all of
+// its choices.  What an entry needs besides its own record is the same for the whole tile: the
+// products and latency sums along the chains of the tile's and the last task's ancestors, and the path
+// values of the other leaves.
 template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE, bool SWAP>
 __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(5))) combine_kernel(SearchArgs A) {
     constexpr uint32_t kHeadBytes = offsetof(DevProblem, lat);
@@ -610,17 +623,29 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     const uint32_t C0 = n >= 2 ? uni(sP->C[0]) : 1u;
     // first-task choices to visit, in run order: all of them, or with classes those of this point's class
     // (the ordering kernel puts them first; the rest belong to other points)
-    const uint32_t roots = A.root_count ? uni(A.root_count[m]) : C0;
-    // the task whose choices fill the tiles: the first one, or task 1
-    const uint32_t Cmid = SWAP ? uni(sP->C[1]) : C0;
+    const uint32_t roots = A.class_count ? uni(A.class_count[static_cast<size_t>(m) * kMaxTasks]) : C0;
+    // the task whose choices fill the tiles: the first one, or the first leaf
+    const int T = SWAP ? uni(sP->tile_task) : 0;
+    const uint32_t Cmid = SWAP ? uni(sP->C[T]) : C0;
     const uint32_t mid_count = SWAP ? Cmid : roots;
     const uint64_t strideL = uni64(sP->stride[L]);
     const TaskRec *tab = A.table + static_cast<size_t>(m) * uni(sP->table_total);
     const TaskRec *tabL = tab + uni(sP->table_off[L]);
-    const TaskRec *tabM = SWAP ? tab + uni(sP->table_off[1]) : tab;
-    const uint32_t *perm0 = A.perm + static_cast<size_t>(m) * C0;
-    const uint32_t *perm = SWAP ? A.perm1 + static_cast<size_t>(m) * Cmid : perm0;
-    const uint32_t *run_end = SWAP ? A.run_end1 + static_cast<size_t>(m) * Cmid : A.run_end + static_cast<size_t>(m) * C0;
+    const TaskRec *tabM = SWAP ? tab + uni(sP->table_off[T]) : tab;
+    const uint32_t *perm_m = SWAP ? A.perm_all + static_cast<size_t>(m) * uni(sP->table_total) : nullptr;
+    const uint32_t *perm = SWAP ? perm_m + uni(sP->table_off[T]) : A.perm + static_cast<size_t>(m) * C0;
+    const uint32_t *run_end = SWAP ? A.run_end_t + static_cast<size_t>(m) * Cmid : A.run_end + static_cast<size_t>(m) * C0;
+    // SWAP: how many choices each task of the work item ranges over for this point
+    uint32_t cntj[kMaxTasks];
+    uint64_t far_swap = 1;
+#pragma unroll
+    for (int j = 0; j < kMaxTasks; j++) {
+        cntj[j] = 1;
+        if (SWAP && j < L && j != T) {
+            cntj[j] = uni(A.class_count[static_cast<size_t>(m) * kMaxTasks + j]);
+            far_swap *= cntj[j];
+        }
+    }
     const bool tie_index_only = A.tie_index_only != 0;
     const double npd = static_cast<double>(uni(sP->n_paths));
     const int32_t W = A.W;
@@ -629,7 +654,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     const uint32_t chunk_in_group = wave % cpb, midpart = wave / cpb, mid_split = kWavesPerBlock / cpb;
 
     // SWAP: the number of work items depends on the point (its first-task choices times the rest)
-    const uint64_t far_m = SWAP ? static_cast<uint64_t>(roots) * A.far2_count : A.far_span;
+    const uint64_t far_m = SWAP ? far_swap : A.far_span;
     const uint64_t items_m = SWAP ? static_cast<uint64_t>(A.chunk_groups) * far_m * A.mid_tiles : A.items;
     const uint64_t item_lo = items_m * blockIdx.x / A.blocks_per_m;
     const uint64_t item_hi = items_m * (blockIdx.x + 1) / A.blocks_per_m;
@@ -662,20 +687,17 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         r = uni(static_cast<uint32_t>(item % A.mid_tiles));
         const uint64_t t = item / A.mid_tiles;
         if (SWAP) {
-            // digits: position among the point's first-task choices, then the tasks after task 1;
-            // f keeps the latter as one number, cj[0] the first task's choice itself
-            const uint64_t ff = t % far_m;
+            // one digit per task of the work item: its position in the task's list for this point
+            uint64_t rest = t % far_m;
             g = uni(static_cast<uint32_t>(t / far_m));
-            cj[0] = uni(perm0[static_cast<uint32_t>(ff % roots)]);
-            uint64_t rest = ff / roots;
-            f = uni64(rest);
-            cj[1] = 0;
+            f = 0;
 #pragma unroll
-            for (int j = 2; j < kMaxTasks; j++) {
+            for (int j = 0; j < kMaxTasks; j++) {
                 cj[j] = 0;
-                if (j < L) {
-                    cj[j] = uni(static_cast<uint32_t>(rest % sP->C[j]));
-                    rest /= sP->C[j];
+                if (j < L && j != T) {
+                    const uint32_t d = static_cast<uint32_t>(rest % cntj[j]);
+                    rest /= cntj[j];
+                    cj[j] = uni(perm_m[uni(sP->table_off[j]) + d]);
                 }
             }
             return;
@@ -736,28 +758,37 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
 #pragma unroll
         for (int j = 0; j < kMaxTasks; j++) flp[j] = 0;
         int64_t tl_base = A.budget[L];  // latency left for the tile's task and the last task together
-        double a_first = 1.0;           // SWAP: the first task's accuracy in this work item
+        double a_first = 1.0, a_last = 1.0;  // SWAP: products over the ancestors of the tile task and of the last task
         if (SWAP) {
-            // the first task's record and those of the tasks after task 1 (all leaves below the first
-            // task) are the same for the whole tile; lat0_cap bounds the latency of the entry's own task
-            const TaskRec rec0 = tab[cj[0]];
-            const int32_t w0 = uni(rec0.w), l0 = uni(rec0.lat);
-            a_first = __longlong_as_double(static_cast<long long>(uni64(static_cast<uint64_t>(__double_as_longlong(rec0.a)))));
-            w_far = w0;
-            ok_far = l0 != kNever;
+            // every task of the work item, in topological order: replicas, products and latency sums along
+            // the chains from the first task (eq. (12) root first, eq. (7)); a leaf closes its path
+            double pp[kMaxTasks];
 #pragma unroll
-            for (int j = 2; j < kMaxTasks; j++) {
-                if (j < L) {
+            for (int j = 0; j < kMaxTasks; j++) pp[j] = 0.0;
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++) {
+                if (j < L && j != T) {
                     const TaskRec rec = tab[sP->table_off[j] + cj[j]];
                     const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
+                    const double ra = __longlong_as_double(
+                        static_cast<long long>(uni64(static_cast<uint64_t>(__double_as_longlong(rec.a)))));
                     w_far += rw;
-                    ok_far = ok_far && rlat != kNever && A.budget[j] >= 0 &&
-                             static_cast<int64_t>(l0) + rlat <= A.budget[j];
+                    ok_far = ok_far && rlat != kNever;
+                    const int par = j > 0 ? uni(sP->parent[j]) : 0;
+                    pp[j] = j == 0 ? ra : pick_below(pp, par, j) * ra;
+                    flp[j] = (j == 0 ? 0 : pick_below(flp, par, j)) + rlat;   // here with the first task included
+                    if (uni(sP->is_leaf[j])) {
+                        ok_far = ok_far && A.budget[j] >= 0 && flp[j] <= A.budget[j];
+                        if (threadIdx.x == 0) sFac[j] = pp[j];   // the leaf's path value (published below)
+                    }
                 }
             }
-            lat0_cap = A.budget[1] < 0 ? -1 : A.budget[1] - l0;
+            const int parT = uni(sP->parent[T]), parL = uni(sP->parent[L]);
+            a_first = pick_below(pp, parT, kMaxTasks);    // product over the tile task's ancestors
+            a_last = pick_below(pp, parL, kMaxTasks);     // product over the last task's ancestors
+            lat0_cap = A.budget[T] < 0 ? -1 : A.budget[T] - pick_below(flp, parT, kMaxTasks);
             if (lat0_cap < 0) ok_far = false;
-            tl_base = tl_base < 0 ? -1 : tl_base - l0;
+            tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parL, kMaxTasks);
         } else {
 #pragma unroll
             for (int j = 1; j < kMaxTasks; j++) {
@@ -791,13 +822,18 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
         const uint32_t left = tile_base < mid_count ? mid_count - tile_base : 0u;
         const uint32_t cnt = left < A.tile_len ? left : A.tile_len;
         // index contribution of everything but the tile's task and the last one
-        const uint64_t base_f = SWAP ? cj[0] + static_cast<uint64_t>(C0) * Cmid * f : static_cast<uint64_t>(C0) * f;
+        uint64_t base_f = static_cast<uint64_t>(C0) * f;
+        if (SWAP) {
+            base_f = 0;
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++)
+                if (j < L && j != T) base_f += cj[j] * uni64(sP->stride[j]);
+        }
 
         // The accuracies the steps multiply by, one per step, for this combination of the tasks in
         // between.  (The factors of the previous item were last read before its tile was published.)
-        if (SWAP) {  // the accuracies of the tasks after task 1, by task
-            if (threadIdx.x >= 2 && threadIdx.x < static_cast<uint32_t>(L))
-                sFac[threadIdx.x] = tab[sP->table_off[threadIdx.x] + pick32(cj, threadIdx.x)].a;
+        if (SWAP) {
+            // (the other leaves' path values were written to sFac above)
         } else if (threadIdx.x < static_cast<uint32_t>(sP->n_prog)) {
             const int t = sP->prog_task[threadIdx.x];
             if (t >= 0) sFac[threadIdx.x] = tab[sP->table_off[t] + pick32(cj, t)].a;
@@ -833,15 +869,16 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             }
             // path values root first (eq. (12) objective, product stand-in): value = a_0 * a_j1 * a_j2 ...
             if (SWAP) {
-                // leaves in ascending order: task 1 (the entry's), then the tasks after it; the last
-                // task's own path value is added per plan
+                // leaves in ascending order: the tile task (the first leaf, the entry's own), then the
+                // other leaves of the work item; the last task's path value is added per plan
 #pragma unroll
                 for (int k = 0; k < kSide; k++) {
                     presum[k] = a_first * a0s[k];
-                    pre[k] = a_first;
+                    pre[k] = a_last;
                 }
-                for (int j = 2; j < L; j++) {
-                    const double v = a_first * sFac[j];
+                for (int j = 0; j < L; j++) {
+                    if (j == T || !uni(sP->is_leaf[j])) continue;
+                    const double v = sFac[j];
 #pragma unroll
                     for (int k = 0; k < kSide; k++) presum[k] = presum[k] + v;
                 }
@@ -898,7 +935,8 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     }
                     sVal[e] = uv;
                     sLim[e] = ul;
-                    sChoice[e] = SWAP ? C0 * cMs[k] : cMs[k];  // the entry's part of the plan's index
+                    // the entry's part of the plan's index (SWAP: below 2^32, checked on the host)
+                    sChoice[e] = SWAP ? static_cast<uint32_t>(uni64(sP->stride[T])) * cMs[k] : cMs[k];
                 }
             }
         }
@@ -1475,7 +1513,7 @@ hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStrea
 }
 
 hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream) {
-    hipLaunchKernelGGL(root_order_kernel, dim3(A.M, A.swap ? 2 : 1), dim3(kSortThreads), 0, stream, A);
+    hipLaunchKernelGGL(root_order_kernel, dim3(A.M, A.swap ? A.swap_tasks : 1), dim3(kSortThreads), 0, stream, A);
     return hipGetLastError();
 }
 

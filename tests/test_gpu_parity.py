@@ -609,3 +609,64 @@ def test_per_variant_factors_on_a_star_whose_second_task_cannot_be_ordered_into_
         check(by_class[1], O.search(demands[1], workers, slo), f"workers {workers} slo {slo}")
         hit += sum(r.status == binding.LOKI_FOUND for r in by_class)
     assert hit >= 4
+
+
+@pytest.mark.parametrize("parent,seed", [([-1, 0, 1, 0], 3), ([-1, 0, 0, 1], 4), ([-1, 0, 1, 1], 6),
+                                         ([-1, 0, 1, 0, 3], 8), ([-1, 0, 1, 0, 0], 11)])
+def test_per_variant_factors_on_deeper_trees_class_by_class(parent, seed):
+    """Trees with several tasks that have children (config 5's shape among them): a point of the launch
+    fixes one amount of created requests per such task, the first leaf's choices fill the tiles, the
+    lists of the other tasks' choices make up the work items.  Against the kernel that scores whole
+    plans per lane and, on the four-task trees, the checker's brute force."""
+    rng = wl.SplitMix64(seed)
+    p = wl.make_pipeline(parent, 2, 2, (1, 4), rng)
+    p.variant_factor_q4 = [3 + (a - 600000) // 60000 for a in p.acc_ppm]
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n_tasks = len(parent)
+    n = P.num_candidates()
+    assert n == 18 ** n_tasks
+    demands = [0, 20_000, 90_000, 250_000, 600_000]
+    found = 0
+    for workers, slo in ((4 * n_tasks, 600_000), (n_tasks + 2, 600_000), (4 * n_tasks, 90_000)):
+        for flags in (0, TIE):
+            by_class = P.alloc_search(demands, workers, slo, flags=flags)
+            scored = P.last_search_plans_scored()
+            per_lane = P.alloc_search(demands, workers, slo, flags=flags | LANE)
+            assert scored < n * len(demands) == P.last_search_plans_scored()
+            for d, a, b in zip(demands, by_class, per_lane):
+                assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
+                    a.as_tuple()[2:] == b.as_tuple()[2:], (d, workers, slo, flags, a.as_tuple(), b.as_tuple())
+            if n_tasks == 4:
+                for d, a in zip(demands[:4], by_class[:4]):
+                    check(a, O.search(d, workers, slo, tie_index_only=bool(flags & TIE)), f"demand {d} workers {workers}")
+            found += sum(r.status == binding.LOKI_FOUND for r in by_class)
+    assert found >= 6
+
+
+@pytest.mark.parametrize("full_task", [2, 3])
+def test_per_variant_factors_on_config_5s_tree_with_full_size_tiles(full_task):
+    """Config 5's profiles and tree (0 -> 1 -> 2, 0 -> 3) with factors, one variant masked out in three of
+    the four tasks (256 choices each) and all 1,024 choices in the first leaf (two tiles of 512 entries) or
+    in the last task (8 register slots per lane): 2^34 plans per demand point, class by class against the
+    kernel that scores whole plans per lane, the winners also through the checker."""
+    import copy
+    w = wl.config(5)
+    p = copy.deepcopy(w.pipeline)
+    p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]
+    for i in range(4):
+        if i != full_task:
+            p.max_replicas[4 * i + 1] = 0
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n == 1 << 34
+    demands = [100_000, 300_000, 700_000]
+    by_class = P.alloc_search(demands, w.workers, w.slo_us)
+    assert P.last_search_plans_scored() < n * len(demands)
+    per_lane = P.alloc_search(demands, w.workers, w.slo_us, flags=LANE)
+    for d, a, b in zip(demands, by_class, per_lane):
+        assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
+            a.as_tuple()[2:] == b.as_tuple()[2:], (d, a.as_tuple(), b.as_tuple())
+        if a.status == binding.LOKI_FOUND:
+            e = O.eval(a.index, d, w.workers, w.slo_us)
+            assert e.infeasible == 0 and bits(e.accuracy) == bits(a.accuracy) and e.workers == a.workers_used
+    assert sum(r.status == binding.LOKI_FOUND and r.n_feasible > 1000 for r in by_class) >= 2
