@@ -87,6 +87,8 @@ def main() -> int:
     ap.add_argument("--per-variant-batch", action="store_true", help="a batch size per hosted variant")
     ap.add_argument("--path-tables", action="store_true",
                     help="objective from seeded profiled path accuracies (whole plans per lane)")
+    ap.add_argument("--demand-qps", type=float, default=None,
+                    help="replace the configuration's demand points by this one demand (queries/s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the other configurations and the instruction-rate probes (profiling runs: "
@@ -115,6 +117,9 @@ def main() -> int:
     if args.path_tables:
         w.pipeline.path_acc_ppm = wl.draw_path_tables(w.pipeline, wl.SplitMix64(w.seed + 1))
         variant.append("path_tables")
+    if args.demand_qps is not None:
+        w.demand_mqps = [int(round(args.demand_qps * 1000))]
+        variant.append(f"demand{args.demand_qps:g}qps")
     if variant:
         w.name += "+" + "+".join(variant)
     # what the library does anyway: whole plans per lane with path tables, and with per-variant factors

@@ -119,10 +119,15 @@ typedef struct {
                                     for a child j are sum_k routed(i,k) * r(i,k) * fanout_q4[j] (Section 5.1:
                                     outgoing = incoming * multFactor * branchRatio), a child's demand depends
                                     on its parent's part of the plan and tasks work in units of milli-QPS /
-                                    16^depth.  Searches score whole plans per lane (LOKI_SEARCH_PER_LANE),
-                                    except where every other task is a child of task 0: a child's demand then
-                                    depends on task 0's choice only through the requests it creates, and the
-                                    tabulated kernels run once per distinct amount (same results). */
+                                    16^depth.  A task's demand then depends on its ancestors' choices only
+                                    through the amounts of requests they create, which take few distinct
+                                    values: a whole-space search of a tree with two or more leaves (and any
+                                    search of a pipeline whose other tasks are all children of task 0) runs
+                                    the tabulated kernels once per combination of such amounts, the host
+                                    settling the choices that cannot serve their demand (same results).
+                                    Chains of three or more tasks, index ranges of other trees and calls with
+                                    more than 65,535 such combinations score whole plans per lane
+                                    (LOKI_SEARCH_PER_LANE). */
     int32_t per_variant_batch;   /* 0: one batch size per task.  1: a batch size per hosted variant, the y(i,k)
                                     of Section 4.1 "Output" and eq. (4); see the index layout above */
     const int32_t *path_acc_ppm; /* NULL, or the profiled end-to-end accuracy A-hat(p) of every variant path
@@ -281,10 +286,10 @@ int loki_last_search_ms(const loki_problem_t *problem, float *ms);
 
 /* Number of plans whose score the kernels of the most recent search on this handle (blocking or
  * enqueued) formed, for callers that relate kernel time to work done.  The index range times the
- * number of demand points, except where per-variant factors are searched class by class (see
- * variant_factor_q4): plans whose first-task choice cannot serve the demand are settled on the
- * host per choice (they still count as infeasible in the results), and the figure is the sum over
- * the (demand point, class) pairs of the plans of the class's first-task choices; for an index range
+ * number of demand points, except where per-variant factors are searched once per combination of
+ * created amounts (see variant_factor_q4): plans with a choice that cannot serve its demand at a
+ * task that has children are settled on the host per choice (they still count as infeasible in the
+ * results), and the figure is the number of plans of the remaining choices; for an index range
  * shorter than the space it is then an upper estimate.  LOKI_E_ARG before the first search. */
 int loki_last_search_plans_scored(const loki_problem_t *problem, uint64_t *plans);
 

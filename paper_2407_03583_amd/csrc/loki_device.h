@@ -169,7 +169,7 @@ struct RouteArgs {
 
 // Merge of the per-class results into the results of the demand points they belong to.
 struct MergeArgs {
-    const void *class_results;  // [n] loki_result_t, one per (demand point, class)
+    void *class_results;        // [n] loki_result_t, one per (demand point, class); folded in place
     const int32_t *point;       // [n] demand point of each
     void *results;              // [M] loki_result_t, updated in place
     int32_t n;

@@ -1455,30 +1455,46 @@ __global__ void results_init_kernel(MergeArgs A) {
     static_cast<ResultOut *>(A.results)[m] = o;
 }
 
-// The classes of a demand point follow one another; the thread of the first class of each such stretch
-// folds the whole stretch into the point's result (a point's classes may continue in the next batch,
-// hence the read of what is there).
+// The classes of a demand point follow one another.  Two launches: first every stretch is cut into pieces
+// of at most kMergePiece classes (a piece starts at a multiple of kMergePiece or where the point changes)
+// and the thread of a piece's first class folds the piece into that class's slot; then the thread of a
+// stretch's first class folds the piece heads into the point's result (a point's classes may continue in
+// the next batch, hence the read of what is there).
+constexpr int kMergePiece = 32;
+
+__device__ __forceinline__ void merge_result(ResultOut &o, const ResultOut &c, bool tie_index_only) {
+    o.n_feasible += c.n_feasible;
+    if (c.status == 0 && (o.status != 0 || better(c.accuracy, c.workers_used, c.index, o.accuracy, o.workers_used,
+                                                  o.index, tie_index_only))) {
+        o.index = c.index;
+        o.accuracy = c.accuracy;
+        o.workers_used = c.workers_used;
+        o.status = 0;
+    }
+}
+
+template <bool PIECES>
 __global__ void __launch_bounds__(kBlockThreads) class_merge_kernel(MergeArgs A) {
     const int v0 = blockIdx.x * kBlockThreads + threadIdx.x;
     if (v0 >= A.n) return;
     const int point = A.point[v0];
-    if (v0 > 0 && A.point[v0 - 1] == point) return;
-    const ResultOut *in = static_cast<const ResultOut *>(A.class_results);
-    ResultOut *out = static_cast<ResultOut *>(A.results);
+    const bool stretch_start = v0 == 0 || A.point[v0 - 1] != point;
+    ResultOut *in = static_cast<ResultOut *>(A.class_results);
     const bool tie_index_only = A.tie_index_only != 0;
-    ResultOut o = out[point];
-    for (int v = v0; v < A.n && A.point[v] == point; v++) {
-        const ResultOut c = in[v];
-        o.n_feasible += c.n_feasible;
-        if (c.status == 0 && (o.status != 0 || better(c.accuracy, c.workers_used, c.index, o.accuracy, o.workers_used,
-                                                      o.index, tie_index_only))) {
-            o.index = c.index;
-            o.accuracy = c.accuracy;
-            o.workers_used = c.workers_used;
-            o.status = 0;
-        }
+    if (PIECES) {
+        if (!stretch_start && v0 % kMergePiece != 0) return;
+        const int end = (v0 / kMergePiece + 1) * kMergePiece;
+        ResultOut o = in[v0];
+        for (int v = v0 + 1; v < A.n && v < end && A.point[v] == point; v++) merge_result(o, in[v], tie_index_only);
+        in[v0] = o;
+    } else {
+        if (!stretch_start) return;
+        ResultOut *out = static_cast<ResultOut *>(A.results);
+        ResultOut o = out[point];
+        for (int v = v0; v < A.n && A.point[v] == point; v = (v / kMergePiece + 1) * kMergePiece)
+            merge_result(o, in[v], tie_index_only);
+        out[point] = o;
     }
-    out[point] = o;
 }
 
 template <int S>
@@ -1554,7 +1570,9 @@ hipError_t launch_results_init(const MergeArgs &A, hipStream_t stream) {
 }
 
 hipError_t launch_class_merge(const MergeArgs &A, hipStream_t stream) {
-    hipLaunchKernelGGL(class_merge_kernel, dim3((A.n + kBlockThreads - 1) / kBlockThreads), dim3(kBlockThreads), 0, stream, A);
+    const dim3 grid((A.n + kBlockThreads - 1) / kBlockThreads), block(kBlockThreads);
+    hipLaunchKernelGGL(class_merge_kernel<true>, grid, block, 0, stream, A);
+    hipLaunchKernelGGL(class_merge_kernel<false>, grid, block, 0, stream, A);
     return hipGetLastError();
 }
 

@@ -670,3 +670,22 @@ def test_per_variant_factors_on_config_5s_tree_with_full_size_tiles(full_task):
             e = O.eval(a.index, d, w.workers, w.slo_us)
             assert e.infeasible == 0 and bits(e.accuracy) == bits(a.accuracy) and e.workers == a.workers_used
     assert sum(r.status == binding.LOKI_FOUND and r.n_feasible > 1000 for r in by_class) >= 2
+
+
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_unit_factors_class_by_class_reproduce_the_stored_full_size_results(cfg):
+    """r(i,k) = 1.00 for every variant is the model with one factor per edge (eq. (1)), but the library
+    cannot know that and searches class by class: every task with children then has one class (all of its
+    usable choices), and the search with swapped roles must return, on the benchmark's full sizes, the
+    stored results of the checker for the plain model bit for bit (2^40 plans on config 5)."""
+    import copy
+    doc, w = golden(cfg)
+    p = copy.deepcopy(w.pipeline)
+    p.variant_factor_q4 = [4] * len(p.acc_ppm)
+    P = binding.Problem(p)
+    points = list(range(0, len(w.demand_mqps), 37))
+    demands = [w.demand_mqps[m] for m in points]
+    out = P.alloc_search(demands, w.workers, w.slo_us, w.comm_us)
+    assert P.last_search_plans_scored() <= doc["n_candidates"] * len(points)
+    for m, res in zip(points, out):
+        check(res, doc["results"][m], f"cfg{cfg} point {m} with unit factors")
