@@ -122,11 +122,9 @@ def main() -> int:
         variant.append(f"demand{args.demand_qps:g}qps")
     if variant:
         w.name += "+" + "+".join(variant)
-    # what the library does anyway: whole plans per lane with path tables, and with per-variant factors
-    # on chains (a star or a tree with two or more leaves is searched class by class by the tabulated kernels)
-    star = all(par == 0 for par in w.pipeline.parent[1:]) and w.pipeline.n_tasks >= 2
-    leaves = sum(1 for i in range(w.pipeline.n_tasks) if i not in w.pipeline.parent)
-    by_class = args.variant_factors and (star or leaves >= 2) and not args.per_lane and not args.path_tables
+    # what the library does anyway: whole plans per lane with path tables; per-variant factors are searched
+    # class by class by the tabulated kernels (whole space, two or more tasks)
+    by_class = args.variant_factors and w.pipeline.n_tasks >= 2 and not args.per_lane and not args.path_tables
     args.per_lane = args.per_lane or args.path_tables or (args.variant_factors and not by_class)
     P = binding.Problem(w.pipeline)
     n = P.num_candidates()

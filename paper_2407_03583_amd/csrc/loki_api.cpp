@@ -474,14 +474,14 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     return LOKI_OK;
 }
 
-// How a class-by-class search of [index_begin, index_end) would run: 2 with swapped roles (two or more
-// leaves, the first leaf's choices orderable into runs and its index part within 32 bits, whole space),
+// How a class-by-class search of [index_begin, index_end) would run: 2 with swapped roles (three or more
+// tasks, the tile task's choices orderable into runs and its index part within 32 bits, whole space),
 // 1 with the first task's choices in the tiles (every other task a child of the first one, its choices
 // orderable into runs), 0 not at all.
 int class_search_mode(const loki_problem *p, uint64_t index_begin, uint64_t index_end) {
     if (!p->dev.has_vf || p->dev.has_path || p->n < 2 || p->dev.table_total > (1u << 16)) return 0;
     const int t = p->dev.tile_task;
-    if (p->dev.n_paths >= 2 && index_begin == 0 && index_end == p->n_candidates && index_end > 0 &&
+    if (p->n >= 3 && index_begin == 0 && index_end == p->n_candidates && index_end > 0 &&
         uint64_t(p->dev.sum_r_t + 1) * uint64_t(p->dev.n_lat_t) + 1 <= 4096 &&
         p->dev.stride[t] <= (uint64_t(1) << 32) / p->dev.C[t])
         return 2;
@@ -880,6 +880,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
     {  // the same for the first leaf (the task whose choices fill the tiles when the roles are swapped)
         int t = 0;
         while (t < n - 1 && !d.is_leaf[t]) t++;
+        if (t == n - 1 && n >= 2) t = n - 2;  // a chain: the last task's parent
         d.tile_task = t;
         std::vector<int32_t> lats;
         for (int k = 0; k < d.K[t]; k++)

@@ -627,7 +627,11 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     // the task whose choices fill the tiles: the first one, or the first leaf
     const int T = SWAP ? uni(sP->tile_task) : 0;
     const uint32_t Cmid = SWAP ? uni(sP->C[T]) : C0;
-    const uint32_t mid_count = SWAP ? Cmid : roots;
+    // SWAP: the tile task is the first leaf (all of its choices), or on a chain, which has no leaf to
+    // spare, the last task's parent (its choices that belong to the point; perm_all lists them first)
+    const bool tile_leaf = !SWAP || uni(sP->is_leaf[T]) != 0;
+    const uint32_t mid_count =
+        SWAP ? (tile_leaf ? Cmid : uni(A.class_count[static_cast<size_t>(m) * kMaxTasks + T])) : roots;
     const uint64_t strideL = uni64(sP->stride[L]);
     const TaskRec *tab = A.table + static_cast<size_t>(m) * uni(sP->table_total);
     const TaskRec *tabL = tab + uni(sP->table_off[L]);
@@ -785,10 +789,16 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             }
             const int parT = uni(sP->parent[T]), parL = uni(sP->parent[L]);
             a_first = pick_below(pp, parT, kMaxTasks);    // product over the tile task's ancestors
-            a_last = pick_below(pp, parL, kMaxTasks);     // product over the last task's ancestors
-            lat0_cap = A.budget[T] < 0 ? -1 : A.budget[T] - pick_below(flp, parT, kMaxTasks);
-            if (lat0_cap < 0) ok_far = false;
-            tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parL, kMaxTasks);
+            if (tile_leaf) {
+                a_last = pick_below(pp, parL, kMaxTasks);     // product over the last task's ancestors
+                lat0_cap = A.budget[T] < 0 ? -1 : A.budget[T] - pick_below(flp, parT, kMaxTasks);
+                if (lat0_cap < 0) ok_far = false;
+                tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parL, kMaxTasks);
+            } else {
+                // the tile task is the last task's parent: its accuracy and latency enter the last task's
+                // path per entry, and it closes no path of its own
+                tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parT, kMaxTasks);
+            }
         } else {
 #pragma unroll
             for (int j = 1; j < kMaxTasks; j++) {
@@ -871,16 +881,18 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             if (SWAP) {
                 // leaves in ascending order: the tile task (the first leaf, the entry's own), then the
                 // other leaves of the work item; the last task's path value is added per plan
+                bool none = !tile_leaf;   // no path value in the sum yet
 #pragma unroll
                 for (int k = 0; k < kSide; k++) {
-                    presum[k] = a_first * a0s[k];
-                    pre[k] = a_last;
+                    presum[k] = tile_leaf ? a_first * a0s[k] : 0.0;
+                    pre[k] = tile_leaf ? a_last : a_first * a0s[k];
                 }
                 for (int j = 0; j < L; j++) {
                     if (j == T || !uni(sP->is_leaf[j])) continue;
                     const double v = sFac[j];
 #pragma unroll
-                    for (int k = 0; k < kSide; k++) presum[k] = presum[k] + v;
+                    for (int k = 0; k < kSide; k++) presum[k] = none ? v : presum[k] + v;
+                    none = false;
                 }
             }
             bool first = true;
@@ -914,8 +926,8 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     MidLim ul;
                     uv.pre = pre[k];
                     uv.presum = presum[k];
-                    // (SWAP: the entry's task is not on the last task's path)
-                    int64_t tl = tl_base < 0 ? -1 : tl_base - (SWAP ? 0 : static_cast<int64_t>(lat0s[k]));
+                    // (SWAP with a leaf in the tiles: the entry's task is not on the last task's path)
+                    int64_t tl = tl_base < 0 ? -1 : tl_base - ((SWAP && tile_leaf) ? 0 : static_cast<int64_t>(lat0s[k]));
                     if (tl < 0) tl = -1;
                     if (tl > kNever - 1) tl = kNever - 1;
                     ul.tl = static_cast<int32_t>(tl);
@@ -1500,8 +1512,9 @@ __global__ void __launch_bounds__(kBlockThreads) class_merge_kernel(MergeArgs A)
 template <int S>
 hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
-    if (A.swap) {  // several leaves, whole space (the host sets swap only then)
-        if (divide) hipLaunchKernelGGL((combine_kernel<S, true, true, false, true>), grid, block, 0, stream, A);
+    if (A.swap) {  // whole space (the host sets swap only then)
+        if (!has_presum) hipLaunchKernelGGL((combine_kernel<S, false, false, false, true>), grid, block, 0, stream, A);
+        else if (divide) hipLaunchKernelGGL((combine_kernel<S, true, true, false, true>), grid, block, 0, stream, A);
         else hipLaunchKernelGGL((combine_kernel<S, true, false, false, true>), grid, block, 0, stream, A);
         return hipGetLastError();
     }

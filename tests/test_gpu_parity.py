@@ -689,3 +689,52 @@ def test_unit_factors_class_by_class_reproduce_the_stored_full_size_results(cfg)
     assert P.last_search_plans_scored() <= doc["n_candidates"] * len(points)
     for m, res in zip(points, out):
         check(res, doc["results"][m], f"cfg{cfg} point {m} with unit factors")
+
+
+@pytest.mark.parametrize("n_tasks,seed", [(3, 31), (4, 32), (3, 34)])
+def test_per_variant_factors_on_chains_class_by_class(n_tasks, seed):
+    """A chain has one leaf, the last task, so nothing spare to fill the tiles with: the choices of the
+    last task's parent that belong to the point do, and its accuracy and latency enter the last task's
+    path per entry.  Against the kernel that scores whole plans per lane and the checker's brute force."""
+    rng = wl.SplitMix64(seed)
+    p = wl.make_pipeline([-1] + list(range(n_tasks - 1)), 2, 2, (1, 4), rng)
+    p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    # (four tasks deep the fixed-point range leaves room for some tens of queries per second only)
+    demands = [0, 10_000, 40_000, 120_000, 400_000] if n_tasks == 3 else [0, 2_000, 8_000, 20_000, 30_000]
+    found = 0
+    for workers, slo in ((4 * n_tasks, 900_000), (n_tasks + 2, 900_000), (4 * n_tasks, 120_000)):
+        for flags in (0, TIE):
+            by_class = P.alloc_search(demands, workers, slo, flags=flags)
+            assert P.last_search_plans_scored() < n * len(demands)
+            per_lane = P.alloc_search(demands, workers, slo, flags=flags | LANE)
+            for d, a, b in zip(demands, by_class, per_lane):
+                assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
+                    a.as_tuple()[2:] == b.as_tuple()[2:], (d, workers, slo, flags, a.as_tuple(), b.as_tuple())
+            if n_tasks <= 4:
+                for d, a in zip(demands[:4], by_class[:4]):
+                    check(a, O.search(d, workers, slo, tie_index_only=bool(flags & TIE)), f"demand {d} workers {workers}")
+            found += sum(r.status == binding.LOKI_FOUND for r in by_class)
+    assert found >= 6
+
+
+def test_per_variant_factors_on_config_2s_chain_at_full_size():
+    """Config 2 (a chain of three tasks, 2^30 plans) with factors: class by class against per lane, and
+    with unit factors against the stored results of the checker for the plain model."""
+    import copy
+    doc, w = golden(2)
+    p = copy.deepcopy(w.pipeline)
+    p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]
+    P = binding.Problem(p)
+    demands = [50_000, 150_000, 400_000]
+    by_class = P.alloc_search(demands, w.workers, w.slo_us)
+    assert P.last_search_plans_scored() < P.num_candidates() * len(demands)
+    per_lane = P.alloc_search(demands, w.workers, w.slo_us, flags=LANE)
+    for d, a, b in zip(demands, by_class, per_lane):
+        assert a.as_tuple()[0] == b.as_tuple()[0] and bits(a.accuracy) == bits(b.accuracy) and \
+            a.as_tuple()[2:] == b.as_tuple()[2:], (d, a.as_tuple(), b.as_tuple())
+    assert sum(r.status == binding.LOKI_FOUND for r in by_class) >= 2
+    p.variant_factor_q4 = [4] * len(p.acc_ppm)
+    out = binding.Problem(p).alloc_search(w.demand_mqps, w.workers, w.slo_us, w.comm_us)
+    check(out[0], doc["results"][0], "cfg2 with unit factors")
