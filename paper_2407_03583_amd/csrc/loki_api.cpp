@@ -122,6 +122,9 @@ struct loki_problem {
     int32_t sum_r[kMaxTasks];   // sum of the replica limits of the task
     uint64_t n_candidates;
     std::vector<double> path_acc;  // profiled path accuracies as fractions (ppm / 10^6), all leaves
+    // class-by-class searches: every choice of every task decoded once (replicas and batch position per
+    // variant, at (table_off[i] + c) * kMaxVariants), filled on first use
+    std::vector<uint8_t> choice_x, choice_beta;
     // pinned staging of the (demand point, class) descriptors: [Dn 8 int64 | amount int64 | count u32 | point i32] arrays
     unsigned char *class_staging = nullptr;
     bool star = false;  // every other task is a child of the first task
@@ -235,22 +238,37 @@ int check_scalars(int32_t workers, int64_t slo_us, int64_t comm_us) {
 // What choice c of task i does with demand D in the task's own units (eq. (2), Algorithm 1's fill rule):
 // whether it serves all of it, and the requests it creates per unit of a child's fan-out,
 // sum_k routed(k) * r(i,k) (eq. (1) with per-variant factors).  Mirrors the kernels' eval_task.
-bool task_outflow(const loki_problem *p, int i, uint64_t c, int64_t D, int64_t *outflow) {
+void decode_choices(loki_problem *p) {
     const DevProblem &d = p->dev;
-    const int K = d.K[i], nb = d.nb[i];
-    int32_t x[kMaxVariants], beta[kMaxVariants];
-    for (int k = 0; k < K; k++) {
-        const uint64_t g = c % d.radix[i][k];
-        c /= d.radix[i][k];
-        if (d.pv_batch) {
-            x[k] = g == 0 ? 0 : int32_t((g - 1) / nb) + 1;
-            beta[k] = g == 0 ? 0 : int32_t((g - 1) % nb);
-        } else {
-            x[k] = int32_t(g);
+    p->choice_x.assign(size_t(d.table_total) * kMaxVariants, 0);
+    p->choice_beta.assign(size_t(d.table_total) * kMaxVariants, 0);
+    for (int i = 0; i < p->n; i++) {
+        const int K = d.K[i], nb = d.nb[i];
+        for (uint32_t c0 = 0; c0 < d.C[i]; c0++) {
+            uint8_t *x = p->choice_x.data() + (size_t(d.table_off[i]) + c0) * kMaxVariants;
+            uint8_t *beta = p->choice_beta.data() + (size_t(d.table_off[i]) + c0) * kMaxVariants;
+            uint64_t c = c0;
+            for (int k = 0; k < K; k++) {
+                const uint64_t g = c % d.radix[i][k];
+                c /= d.radix[i][k];
+                if (d.pv_batch) {
+                    x[k] = uint8_t(g == 0 ? 0 : (g - 1) / nb + 1);
+                    beta[k] = uint8_t(g == 0 ? 0 : (g - 1) % nb);
+                } else {
+                    x[k] = uint8_t(g);
+                }
+            }
+            if (!d.pv_batch)
+                for (int k = 0; k < K; k++) beta[k] = uint8_t(c);
         }
     }
-    if (!d.pv_batch)
-        for (int k = 0; k < K; k++) beta[k] = int32_t(c);
+}
+
+bool task_outflow(const loki_problem *p, int i, uint32_t c, int64_t D, int64_t *outflow) {
+    const DevProblem &d = p->dev;
+    const int K = d.K[i];
+    const uint8_t *x = p->choice_x.data() + (size_t(d.table_off[i]) + c) * kMaxVariants;
+    const uint8_t *beta = p->choice_beta.data() + (size_t(d.table_off[i]) + c) * kMaxVariants;
     int64_t rem = D, out = 0;
     bool any = false;
     for (int o = 0; o < K; o++) {
@@ -310,18 +328,15 @@ int walk_classes(ClassWalk &w, int i) {
     auto key = std::make_pair(i, w.Dn[i]);
     auto it = w.memo.find(key);
     if (it == w.memo.end()) {
-        std::vector<int64_t> amounts;
-        for (uint64_t c = 0; c < p->dev.C[i]; c++) {
-            int64_t out;
-            if (task_outflow(p, i, c, w.Dn[i], &out)) amounts.push_back(out);
-        }
-        std::sort(amounts.begin(), amounts.end());
+        // few distinct amounts among many choices: a sorted list with binary search
         std::vector<std::pair<int64_t, uint32_t>> classes;
-        for (size_t a = 0; a < amounts.size();) {
-            size_t b = a;
-            while (b < amounts.size() && amounts[b] == amounts[a]) b++;
-            classes.emplace_back(amounts[a], uint32_t(b - a));
-            a = b;
+        for (uint32_t c = 0; c < p->dev.C[i]; c++) {
+            int64_t out;
+            if (!task_outflow(p, i, c, w.Dn[i], &out)) continue;
+            auto at = std::lower_bound(classes.begin(), classes.end(), out,
+                                       [](const std::pair<int64_t, uint32_t> &cls, int64_t v) { return cls.first < v; });
+            if (at != classes.end() && at->first == out) at->second++;
+            else classes.insert(at, std::make_pair(out, 1u));
         }
         it = w.memo.emplace(key, std::move(classes)).first;
     }
@@ -334,7 +349,8 @@ int walk_classes(ClassWalk &w, int i) {
     return LOKI_OK;
 }
 
-int build_class_points(const loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, ClassPoints &cp) {
+int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, ClassPoints &cp) {
+    if (p->choice_x.empty()) decode_choices(p);
     ClassWalk w;
     w.p = p;
     w.cp = &cp;
