@@ -122,10 +122,11 @@ def main() -> int:
         variant.append(f"demand{args.demand_qps:g}qps")
     if variant:
         w.name += "+" + "+".join(variant)
-    # what the library does anyway: whole plans per lane with path tables; per-variant factors are searched
-    # class by class by the tabulated kernels (whole space, two or more tasks)
+    # what the library does anyway: per-variant factors are searched class by class by the tabulated kernels
+    # (whole space, two or more tasks); profiled path accuracies with the feasibility part tabulated, unless
+    # per-variant factors come with them (then whole plans per lane)
     by_class = args.variant_factors and w.pipeline.n_tasks >= 2 and not args.per_lane and not args.path_tables
-    args.per_lane = args.per_lane or args.path_tables or (args.variant_factors and not by_class)
+    args.per_lane = args.per_lane or (args.variant_factors and not by_class)
     P = binding.Problem(w.pipeline)
     n = P.num_candidates()
     m = len(w.demand_mqps)
@@ -162,10 +163,11 @@ def main() -> int:
     main_ms = sum(k[1] for k in kernel_ms) / len(kernel_ms)
     n_paths = sum(1 for i in range(w.pipeline.n_tasks) if i not in w.pipeline.parent)
     ops = algorithmic_lane_ops(w.pipeline.n_tasks, n_paths, args.per_lane, w.pipeline)
+    no_count = args.path_tables and not args.per_lane   # see the note in the roofline object
     # work the kernels did: every plan of the range, except class by class, where plans whose first-task
     # choice cannot serve the demand are settled per choice on the host and never reach the kernels
     scored = P.last_search_plans_scored()
-    achieved = ops * scored / (main_ms * 1e-3) / 1e12
+    achieved = None if no_count else ops * scored / (main_ms * 1e-3) / 1e12
 
     out = {
         "metric": "allocation candidates evaluated/sec (1 GPU)",
@@ -182,16 +184,20 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "seed": w.seed, "candidates": n, "demand_points": m,
                    "index_end": end, "evaluations_per_step": evaluations, "plans_scored_by_kernels": scored,
-                   "kernel": ("path" if args.path_tables else "per_lane") if args.per_lane
-                   else ("tabulated_by_class" if by_class else "tabulated"),
+                   "kernel": ("per_lane_paths" if args.path_tables else "per_lane") if args.per_lane
+                   else ("tabulated_by_class" if by_class else ("tabulated_paths" if args.path_tables else "tabulated")),
                    "feasible_fraction_point0": first[0].n_feasible / end},
         "kernel_ms": {"task_tables": sum(k[0] for k in kernel_ms) / len(kernel_ms), "search": main_ms,
                       "final_merge": sum(k[2] for k in kernel_ms) / len(kernel_ms)},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
-                     "frac": achieved / VALU_PEAK_TLANEOPS,
+                     "frac": None if no_count else achieved / VALU_PEAK_TLANEOPS,
                      "traffic": measured_traffic(w.name, "per_lane" if args.per_lane else "tabulated"),
-                     "lane_ops_per_candidate": ops},
+                     "lane_ops_per_candidate": None if no_count else ops},
     }
+    if no_count:
+        out["roofline"]["note"] = ("profiled path accuracies: feasibility is taken per run of first-task choices "
+                                   "and the walk over the variant paths runs for feasible plans only, so no "
+                                   "per-plan operation count applies")
     # the other benchmark configurations, one timed blocking call each (context for `value`)
     if not args.per_lane and not variant and not args.no_context:
         others = {}
@@ -214,7 +220,7 @@ def main() -> int:
     if not args.no_context:
         mix = binding.measure_valu_rate("search_mix")
         out["roofline"]["sustained_mix_Tlane_op_s"] = mix * 64 / 1e12
-        out["roofline"]["frac_of_sustained_mix"] = achieved / (mix * 64 / 1e12)
+        out["roofline"]["frac_of_sustained_mix"] = None if no_count else achieved / (mix * 64 / 1e12)
         out["roofline"]["sustained_u32_Tlane_op_s"] = binding.measure_valu_rate("v_add_u32") * 64 / 1e12
     if not args.no_cpu_baseline:
         import oracle

@@ -143,7 +143,10 @@ typedef struct {
                                     order.  fp64 order: c(p) multiplied up root first, times A-hat(p)/10^6,
                                     terms added with the root's variants outermost and every level in route
                                     order, task paths added in leaf order, one division by their number.
-                                    Tasks are coupled through c(p): every search scores whole plans per lane. */
+                                    The objective couples the tasks through c(p), feasibility does not: a
+                                    search takes feasibility from the per-task tables and walks the variant
+                                    paths for feasible plans only (whole plans per lane together with
+                                    variant_factor_q4 and with LOKI_SEARCH_PER_LANE; same results). */
 } loki_pipeline_t;
 
 typedef struct loki_problem loki_problem_t; /* opaque handle */

@@ -420,7 +420,10 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     const int n = p->n, L = n - 1;
     const uint64_t span = index_end - index_begin;
     const uint32_t n_points = static_cast<uint32_t>(A.M);
-    const uint32_t max_bpm = std::max<uint32_t>(1u, (kTargetBlocks + n_points - 1) / n_points);
+    // (with profiled path accuracies a quarter of the blocks: every block ends with one walk over the
+    // variant paths for the few plans left in its queues, which longer blocks spread over more work)
+    const uint32_t target_blocks = p->dev.has_path ? kTargetBlocks / 4 : kTargetBlocks;
+    const uint32_t max_bpm = std::max<uint32_t>(1u, (target_blocks + n_points - 1) / n_points);
     const uint32_t CL = p->dev.C[L];
     const int slots = CL >= 512 ? 8 : 4;
     const uint32_t chunk = 64u * slots;
@@ -484,7 +487,15 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     LOKI_HIP(launch_task_table(A, p->dev.table_total, stream));
     if (n >= 2) LOKI_HIP(launch_root_order(A, stream));
     if (before_search) LOKI_HIP(hipEventRecord(before_search, stream));
-    LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, stream));
+    if (p->dev.has_path) {
+        // profiled path accuracies (one factor per edge): the same walk over the plan space for feasibility,
+        // the objective from the walk over the variant paths for feasible plans only
+        int path_levels = 0;
+        for (int i = 0; i < n; i++) path_levels = std::max(path_levels, p->dev.path_len[i]);
+        LOKI_HIP(launch_path_combine(A, slots, range, path_levels, stream));
+    } else {
+        LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, stream));
+    }
     if (after_search) LOKI_HIP(hipEventRecord(after_search, stream));
     LOKI_HIP(launch_final_reduce(A, stream));
     return LOKI_OK;
@@ -667,8 +678,8 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
                                   d_workspace, workspace_bytes, stream, d_results, timed, results_at);
         if (rc != LOKI_E_ARG) return rc;  // LOKI_E_ARG: too many classes, take the general path
     }
-    // the objective couples the tasks
-    if (p->dev.has_vf || p->dev.has_path) flags |= LOKI_SEARCH_PER_LANE;
+    // per-variant factors that cannot be searched class by class couple the tasks' feasibility
+    if (p->dev.has_vf) flags |= LOKI_SEARCH_PER_LANE;
     p->last_scored = (index_end - index_begin) * uint64_t(n_demand);
     p->have_scored = true;
     const size_t cb = const_block(p);

@@ -1106,6 +1106,275 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                      A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
 }
 
+// plans waiting for the walk over the variant paths, per wavefront: below 64 waiting + at most 64 new per push
+constexpr uint32_t kWalkQueue = 128;
+
+// ---- kernel: profiled path accuracies on top of the per-task tables -----------------------------------------
+// Feasibility is separable even where the objective is not (one factor per edge: a task's demand, and so
+// its record, does not depend on the other tasks).  This kernel walks the plan space like combine_kernel
+// (same work items, tiles of first-task choices in run order, the last task's records in registers) but
+// only takes the feasibility masks, once per run; the plans of a run that are feasible go, by index, into
+// a queue of the wavefront, and whenever 64 are waiting every lane walks the variant paths of one
+// (path_objective).  The cost is a few instructions per 512 plans plus the walk for feasible plans only.
+template <int S, bool RANGE, int MAXD>
+__global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) path_combine_kernel(SearchArgs A) {
+    __shared__ DevProblem sPfull;
+    __shared__ MidLim sLim[kMidTile];
+    __shared__ uint32_t sChoice[kMidTile];
+    __shared__ uint64_t sWalkIdx[kWavesPerBlock][kWalkQueue];
+    __shared__ int32_t sWalkW[kWavesPerBlock][kWalkQueue];
+    __shared__ BestRec sBest[kWavesPerBlock];
+    stage_problem(&sPfull, A.P, sizeof(DevProblem));
+    __syncthreads();
+    const DevProblem *sP = &sPfull;
+
+    const uint32_t lane = threadIdx.x & 63;
+    const int wave = uni(static_cast<int>(threadIdx.x >> 6));
+    const int m = blockIdx.y;
+    const int n = uni(sP->n_tasks), L = n - 1;
+    const uint32_t CL = uni(sP->C[L]);
+    const uint32_t C0 = n >= 2 ? uni(sP->C[0]) : 1u;
+    const uint64_t strideL = uni64(sP->stride[L]);
+    const TaskRec *tab = A.table + static_cast<size_t>(m) * uni(sP->table_total);
+    const TaskRec *tabL = tab + uni(sP->table_off[L]);
+    const uint32_t *perm = A.perm + static_cast<size_t>(m) * C0;
+    const uint32_t *run_end = A.run_end + static_cast<size_t>(m) * C0;
+    const bool tie_index_only = A.tie_index_only != 0;
+    const int32_t W = A.W;
+    const int64_t *Dn = A.Dn + static_cast<size_t>(m) * kMaxTasks;
+
+    const uint32_t cpb = A.cpb;
+    const uint32_t chunk_in_group = wave % cpb, midpart = wave / cpb, mid_split = kWavesPerBlock / cpb;
+
+    int32_t w[S], lat[S];
+    double bacc = -1.0;
+    int32_t bw = kNever;
+    uint64_t bidx = ~0ull;
+    uint64_t nfeas = 0;      // wavefront total
+    uint32_t waiting = 0;    // plans in this wavefront's queue (the same in every lane)
+    uint32_t cur_group = ~0u;
+    uint32_t cl0 = 0;        // this lane's choice of the last task in slot 0
+
+    // the first `count` lanes take the queue entries [from, from + count) and walk them
+    auto walk_queued = [&](uint32_t from, uint32_t count) {
+        if (lane < count) {
+            const uint64_t idx = sWalkIdx[wave][from + lane];
+            const int32_t workers = sWalkW[wave][from + lane];
+            uint32_t c[kMaxTasks];
+            uint64_t rest = idx;
+#pragma unroll
+            for (int i = 0; i < kMaxTasks; i++) {
+                c[i] = 0;
+                if (i < n) {
+                    c[i] = static_cast<uint32_t>(rest % sP->C[i]);
+                    rest /= sP->C[i];
+                }
+            }
+            const double acc = path_objective<MAXD>(sP, A.path_acc, c, Dn);
+            if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                bacc = acc;
+                bw = workers;
+                bidx = idx;
+            }
+        }
+    };
+
+    const uint64_t item_lo = A.items * blockIdx.x / A.blocks_per_m;
+    const uint64_t item_hi = A.items * (blockIdx.x + 1) / A.blocks_per_m;
+    for (uint64_t item = item_lo; item < item_hi; ++item) {
+        // position of the item: tile r, combination f of the tasks in between, chunk group g
+        const uint32_t r = uni(static_cast<uint32_t>(item % A.mid_tiles));
+        const uint64_t t = item / A.mid_tiles;
+        const uint64_t f = uni64((A.far_first + t % A.far_span) % A.far_count);
+        const uint32_t g = uni(static_cast<uint32_t>(t / A.far_span));
+        uint32_t cj[kMaxTasks];
+        {
+            uint64_t rest = f;
+#pragma unroll
+            for (int j = 1; j < kMaxTasks; j++) {
+                cj[j] = 0;
+                if (j < L) {
+                    cj[j] = uni(static_cast<uint32_t>(rest % sP->C[j]));
+                    rest /= sP->C[j];
+                }
+            }
+            cj[0] = 0;
+        }
+        if (g != cur_group) {
+            cur_group = g;
+            cl0 = A.cl_first + (g * cpb + chunk_in_group) * (64u * S) + lane;
+#pragma unroll
+            for (int s = 0; s < S; s++) {
+                const uint32_t cL = cl0 + s * 64;
+                if (cL < CL) {
+                    const TaskRec rec = tabL[cL];
+                    w[s] = rec.w;
+                    lat[s] = rec.lat;
+                } else {
+                    w[s] = 0;
+                    lat[s] = kNever;
+                }
+            }
+        }
+        // what the tasks strictly between the first and the last contribute (eq. (3), eq. (7))
+        int64_t flp[kMaxTasks];
+        int64_t w_far = 0;
+        bool ok_far = true;
+        int64_t lat0_cap = kNever - 1;
+#pragma unroll
+        for (int j = 0; j < kMaxTasks; j++) flp[j] = 0;
+#pragma unroll
+        for (int j = 1; j < kMaxTasks; j++) {
+            if (j < L) {
+                const TaskRec rec = tab[sP->table_off[j] + cj[j]];
+                const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
+                w_far += rw;
+                ok_far = ok_far && rlat != kNever;
+                flp[j] = pick_below(flp, uni(sP->parent[j]), j) + rlat;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kMaxTasks; j++) {
+            if (j < L && uni(sP->is_leaf[j])) {
+                const int64_t room = A.budget[j] < 0 ? -1 : A.budget[j] - flp[j];
+                if (room < lat0_cap) lat0_cap = room;
+            }
+        }
+        if (lat0_cap < 0) ok_far = false;
+        int64_t tl_base = A.budget[L];
+        if (n >= 2) tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, uni(sP->parent[L]), kMaxTasks);
+        const int64_t w_room = static_cast<int64_t>(W) - w_far;
+
+        const uint32_t tile_base = r * A.tile_len;
+        const uint32_t left = tile_base < C0 ? C0 - tile_base : 0u;
+        const uint32_t cnt = left < A.tile_len ? left : A.tile_len;
+        const uint64_t base_f = static_cast<uint64_t>(C0) * f;
+
+        __syncthreads();  // the previous item's tile is no longer being read
+        for (uint32_t e = threadIdx.x; e < cnt; e += kBlockThreads) {
+            uint32_t cM = 0;
+            int32_t w0 = 0, lat0 = 0;
+            bool ok = ok_far;
+            if (n >= 2) {
+                cM = perm[tile_base + e];
+                const TaskRec rec = tab[cM];
+                w0 = rec.w;
+                lat0 = rec.lat;
+                ok = ok_far && rec.lat != kNever && static_cast<int64_t>(rec.lat) <= lat0_cap;
+            }
+            MidLim ul;
+            int64_t tl = tl_base < 0 ? -1 : tl_base - static_cast<int64_t>(lat0);
+            if (tl < 0) tl = -1;
+            if (tl > kNever - 1) tl = kNever - 1;
+            ul.tl = static_cast<int32_t>(tl);
+            const int64_t wr = w_room - static_cast<int64_t>(w0);
+            ul.w_rem = (ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
+            ul.cl_lo = n >= 2 ? run_end[tile_base + e] - tile_base : e + 1;
+            ul.cl_cnt = CL;
+            if (RANGE) {
+                const uint64_t base = base_f + cM;
+                const uint64_t lo = A.begin > base ? (A.begin - base + strideL - 1) / strideL : 0;
+                uint64_t hi = A.end > base ? (A.end - base + strideL - 1) / strideL : 0;
+                if (hi > CL) hi = CL;
+                ul.cl_lo = static_cast<uint32_t>(lo < hi ? lo : hi);
+                ul.cl_cnt = static_cast<uint32_t>(hi > lo ? hi - lo : 0);
+            }
+            sLim[e] = ul;
+            sChoice[e] = cM;
+        }
+        __syncthreads();
+
+        const uint32_t e_lo = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * midpart / mid_split);
+        const uint32_t e_hi = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * (midpart + 1) / mid_split);
+        uint32_t e = e_lo;
+        while (e < e_hi) {
+            // ---- start of a run: which of the S*64 plans are feasible, valid for every record of the run
+            const MidLim ul = sLim[e];
+            uint32_t run_hi = e + 1;
+            if (!RANGE) {
+                run_hi = uni(ul.cl_lo);
+                if (run_hi > e_hi) run_hi = e_hi;
+            }
+            const int32_t w_rem = uni(ul.w_rem), tl = uni(ul.tl);
+            uint64_t fm[S];
+            uint32_t run_feas = 0;
+#pragma unroll
+            for (int s = 0; s < S; s++) {
+                bool ok = (w[s] <= w_rem) & (lat[s] <= tl);
+                if (RANGE) ok = ok & ((cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt);
+                fm[s] = __builtin_amdgcn_ballot_w64(ok);
+                run_feas += static_cast<uint32_t>(__builtin_popcountll(fm[s]));
+            }
+            if (run_feas != 0) {
+                for (uint32_t ee = e; ee < run_hi; ee++) {
+                    const uint64_t low = base_f + sChoice[ee];
+                    const int32_t w_out = W - sLim[ee].w_rem;  // replicas of all tasks but the last
+#pragma unroll
+                    for (int s = 0; s < S; s++) {
+                        if (fm[s] == 0) continue;
+                        if ((fm[s] >> lane) & 1) {
+                            const uint32_t at = waiting + static_cast<uint32_t>(__builtin_popcountll(fm[s] & ((1ull << lane) - 1)));
+                            sWalkIdx[wave][at] = low + strideL * (cl0 + s * 64);
+                            sWalkW[wave][at] = w_out + w[s];
+                        }
+                        waiting += static_cast<uint32_t>(__builtin_popcountll(fm[s]));
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                        if (waiting >= 64) {
+                            waiting -= 64;
+                            walk_queued(waiting, 64);
+                            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                        }
+                    }
+                    nfeas += run_feas;
+                }
+            }
+            e = run_hi;
+        }
+    }
+    // What is left in the four queues (fewer than 64 plans each) is walked by the block as a whole: the
+    // wavefronts' leftovers are put one after the other, and every thread below their total takes one.
+    __shared__ uint32_t sLeft[kWavesPerBlock];
+    if (lane == 0) sLeft[wave] = waiting;
+    __syncthreads();
+    {
+        uint32_t total = 0, mine = threadIdx.x, src_wave = 0;
+        bool have = false;
+#pragma unroll
+        for (int v = 0; v < kWavesPerBlock; v++) {
+            const uint32_t c = sLeft[v];
+            if (!have && mine < total + c && mine >= total) {
+                have = true;
+                src_wave = v;
+                mine -= total;
+            }
+            total += c;
+        }
+        if (have) {
+            const uint64_t idx = sWalkIdx[src_wave][mine];
+            const int32_t workers = sWalkW[src_wave][mine];
+            uint32_t c[kMaxTasks];
+            uint64_t rest = idx;
+#pragma unroll
+            for (int i = 0; i < kMaxTasks; i++) {
+                c[i] = 0;
+                if (i < n) {
+                    c[i] = static_cast<uint32_t>(rest % sP->C[i]);
+                    rest /= sP->C[i];
+                }
+            }
+            const double acc = path_objective<MAXD>(sP, A.path_acc, c, Dn);
+            if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                bacc = acc;
+                bw = workers;
+                bidx = idx;
+            }
+        }
+    }
+    __syncthreads();
+    block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
+                     A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
+}
+
 // ---- kernel: every lane scores whole plans (no tables) ---------------------------------------------------
 // A work item is one choice of every task but the last plus a strip of kStrip choices of the
 // last task.  The lane scores the shared part once (each task in topological order, so that
@@ -1121,7 +1390,6 @@ constexpr uint32_t kStrip = 64;
 // total order).  The loops below therefore have the same trip count in every lane of a wavefront.
 // The four-level walk is held to the registers of 3 wavefronts per SIMD: its spills cost less than the
 // scoring loop gains from the third wavefront.
-constexpr uint32_t kWalkQueue = 128;  // per wavefront: below 64 waiting + at most 64 new per step
 
 template <bool PV, bool VF, int MAXD>
 __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_search_kernel(SearchArgs A) {
@@ -1569,6 +1837,21 @@ hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_v
     else if (path_levels <= 4) launch_per_lane_depth<4>(A, pv_batch, has_vf, stream);
     else launch_per_lane_depth<kMaxTasks>(A, pv_batch, has_vf, stream);
     return hipGetLastError();
+}
+
+template <int S, int MAXD>
+hipError_t launch_path_combine_s(const SearchArgs &A, bool range, hipStream_t stream) {
+    const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
+    if (range) hipLaunchKernelGGL((path_combine_kernel<S, true, MAXD>), grid, block, 0, stream, A);
+    else hipLaunchKernelGGL((path_combine_kernel<S, false, MAXD>), grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_path_combine(const SearchArgs &A, int slots, bool range, int path_levels, hipStream_t stream) {
+    if (path_levels <= 4)
+        return slots == 8 ? launch_path_combine_s<8, 4>(A, range, stream) : launch_path_combine_s<4, 4>(A, range, stream);
+    return slots == 8 ? launch_path_combine_s<8, kMaxTasks>(A, range, stream)
+                      : launch_path_combine_s<4, kMaxTasks>(A, range, stream);
 }
 
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream) {

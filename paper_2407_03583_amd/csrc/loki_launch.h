@@ -14,6 +14,7 @@ hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool 
                           hipStream_t stream);
 // path_levels: 0, or with profiled path accuracies the number of tasks on the longest root-to-leaf chain
 // (selects how many levels of the walk over the variant paths are compiled in)
+hipError_t launch_path_combine(const SearchArgs &A, int slots, bool range, int path_levels, hipStream_t stream);
 hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels,
                                   hipStream_t stream);
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);

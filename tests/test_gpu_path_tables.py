@@ -17,6 +17,8 @@ pytestmark = pytest.mark.gpu
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 TIE = binding.LOKI_TIE_INDEX_ONLY
+LANE = binding.LOKI_SEARCH_PER_LANE   # the kernel that scores whole plans per lane (else: the tabulated walk
+                                      # over the plan space with the variant paths walked for feasible plans)
 
 
 def bits(x):
@@ -64,16 +66,17 @@ def test_small_random_problems(variant_factors, per_variant_batch):
         P, O = binding.Problem(w.pipeline), oracle.Problem(w.pipeline)
         n = P.num_candidates()
         d = w.demand_mqps[0]
-        for flags in (0, TIE):
+        for flags in (0, TIE, LANE, LANE | TIE):
             res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, flags=flags)[0]
-            ref = O.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags))
+            ref = O.search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=bool(flags & TIE))
             assert agree(res, ref), (seed, flags, res.as_tuple(), ref.as_tuple())
         found += res.status == 0
         check_plans(P, O, list(range(0, n, max(1, n // 300))), d, w.workers, w.slo_us, w.comm_us)
         # a split range merges to the same answer as the checker on the same range
         a, b = n // 3, n - n // 5
-        res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, begin=a, end=b)[0]
-        assert agree(res, O.search(d, w.workers, w.slo_us, w.comm_us, begin=a, end=b)), seed
+        for flags in (0, LANE):
+            res = P.alloc_search([d], w.workers, w.slo_us, w.comm_us, begin=a, end=b, flags=flags)[0]
+            assert agree(res, O.search(d, w.workers, w.slo_us, w.comm_us, begin=a, end=b)), (seed, flags)
     assert found >= 8
 
 
@@ -88,10 +91,10 @@ def test_plans_that_split_traffic_at_every_task(variant_factors, per_variant_bat
         n = P.num_candidates()
         feasible += check_plans(P, O, rng.sample(range(n), min(n, 3000)), demand, 99, 1_000_000)
         if n <= 300_000:
-            for flags in (0, TIE):
+            for flags in (0, TIE, LANE):
                 res = P.alloc_search([demand, demand // 2, 2 * demand], 99, 1_000_000, flags=flags)
                 for d, r in zip([demand, demand // 2, 2 * demand], res):
-                    assert agree(r, O.search(d, 99, 1_000_000, tie_index_only=bool(flags))), (d, flags)
+                    assert agree(r, O.search(d, 99, 1_000_000, tie_index_only=bool(flags & TIE))), (d, flags)
     assert feasible > 300
 
 
@@ -107,10 +110,12 @@ def test_four_task_tree_with_three_variants():
     assert n == (27 * 2) ** 4
     demands = [20_000, 60_000, 150_000, 300_000]
     out = P.alloc_search(demands, 20, 600_000)
+    per_lane = P.alloc_search(demands, 20, 600_000, flags=LANE)
     found = 0
-    for d, res in zip(demands, out):
+    for d, res, res_lane in zip(demands, out, per_lane):
         ref = O.search(d, 20, 600_000)
         assert agree(res, ref), (d, res.as_tuple(), ref.as_tuple())
+        assert agree(res_lane, ref), (d, res_lane.as_tuple(), ref.as_tuple())
         found += ref.found
     assert found == 3
     half = n // 2 + 12345
@@ -139,9 +144,10 @@ def test_deep_chain_reaches_the_last_level():
     P, O = binding.Problem(p), oracle.Problem(p)
     assert P.num_candidates() == 6 ** 8
     for demand, W in ((150_000, 24), (0, 8), (100_000, 12)):
-        res = P.alloc_search([demand], W, 100_000)[0]
         ref = O.search(demand, W, 100_000)
-        assert agree(res, ref), (demand, res.as_tuple(), ref.as_tuple())
+        for flags in (0, LANE):
+            res = P.alloc_search([demand], W, 100_000, flags=flags)[0]
+            assert agree(res, ref), (demand, flags, res.as_tuple(), ref.as_tuple())
 
 
 def test_plan_trace_with_path_tables():
@@ -164,3 +170,31 @@ def test_plan_trace_with_path_tables():
         assert s.phase == want, t
         phases.add(s.phase)
     assert phases == {0, 1, 2}
+
+
+def test_config_sizes_with_path_tables_tabulated_against_per_lane():
+    """Config 2 (2^30 plans) with profiled path accuracies: the tabulated walk over the plan space against the
+    kernel that scores whole plans per lane, full space and a ragged index range; config 5 (2^40 plans,
+    out of the per-lane kernel's reach): the winner through the checker, the feasible count against the
+    stored result of the plain model (feasibility does not depend on the objective)."""
+    w = wl.config(2)
+    p = w.pipeline
+    p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(w.seed + 1))
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    for begin, end in ((0, n), (n // 7 + 3, n - n // 11)):
+        a = P.alloc_search(w.demand_mqps, w.workers, w.slo_us, begin=begin, end=end)[0]
+        b = P.alloc_search(w.demand_mqps, w.workers, w.slo_us, begin=begin, end=end, flags=LANE)[0]
+        assert agree(a, b), (begin, end, a.as_tuple(), b.as_tuple())
+        assert a.status == 0 and a.n_feasible > 100_000
+        e = O.eval(a.index, w.demand_mqps[0], w.workers, w.slo_us)
+        assert e.infeasible == 0 and bits(e.accuracy) == bits(a.accuracy) and e.workers == a.workers_used
+    w5 = wl.config(5)
+    p5 = w5.pipeline
+    p5.path_acc_ppm = wl.draw_path_tables(p5, wl.SplitMix64(w5.seed + 1))
+    P5, O5 = binding.Problem(p5), oracle.Problem(p5)
+    r = P5.alloc_search(w5.demand_mqps, w5.workers, w5.slo_us)[0]
+    doc = json.load(open(os.path.join(GOLDEN, "cfg5.json")))
+    assert r.status == 0 and r.n_feasible == doc["results"][0]["n_feasible"] == 108
+    e = O5.eval(r.index, w5.demand_mqps[0], w5.workers, w5.slo_us)
+    assert e.infeasible == 0 and bits(e.accuracy) == bits(r.accuracy) and e.workers == r.workers_used
