@@ -1117,7 +1117,7 @@ constexpr uint32_t kWalkQueue = 128;
 // a queue of the wavefront, and whenever 64 are waiting every lane walks the variant paths of one
 // (path_objective).  The cost is a few instructions per 512 plans plus the walk for feasible plans only.
 template <int S, bool RANGE, int MAXD>
-__global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) path_combine_kernel(SearchArgs A) {
+__global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine_kernel(SearchArgs A) {
     __shared__ DevProblem sPfull;
     __shared__ MidLim sLim[kMidTile];
     __shared__ uint32_t sChoice[kMidTile];
