@@ -738,3 +738,20 @@ def test_per_variant_factors_on_config_2s_chain_at_full_size():
     p.variant_factor_q4 = [4] * len(p.acc_ppm)
     out = binding.Problem(p).alloc_search(w.demand_mqps, w.workers, w.slo_us, w.comm_us)
     check(out[0], doc["results"][0], "cfg2 with unit factors")
+
+
+def test_plan_trace_with_per_variant_factors():
+    """The demand-trace planner with per-variant factors: its batched search runs class by class; every
+    step against the checker, on a two-task pipeline and on a detector with two classifiers."""
+    for parent, seed in (([-1, 0], 41), ([-1, 0, 0], 42)):
+        rng = wl.SplitMix64(seed)
+        p = wl.make_pipeline(parent, 2, 2, (1, 4), rng)
+        p.variant_factor_q4 = [3 + (a - 600000) // 60000 for a in p.acc_ppm]
+        P, O = binding.Problem(p), oracle.Problem(p)
+        ramp = [9_000 * t for t in range(40)]
+        steps = P.plan_trace(ramp, 400_000, 3 * len(parent), 500_000)
+        found = 0
+        for t, s in enumerate(steps):
+            check(s.plan, O.search(s.estimate_mqps, 3 * len(parent), 500_000), f"{parent} step {t}")
+            found += s.plan.status == binding.LOKI_FOUND
+        assert 5 <= found < len(steps)
