@@ -44,10 +44,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (429 + 1024) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (262 + 1024) * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (425 + 1024) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (276 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "ac23b0f98d8f7766e548bd6db738f1e026dfe2467c3938c5604f82f803f3636a"
+TRAFFIC_SOURCES_SHA256 = "d4812a5adf7e92f8cfa50be44c621329cb4e76b3310f871fa67c8f2829d8a4d5"
 
 
 def measured_traffic(workload: str, kernel: str):
