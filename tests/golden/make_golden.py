@@ -5,6 +5,11 @@ which tests/test_oracle_pins.py checks against the plain per-index search).
 Usage: python tests/golden/make_golden.py [--threads T] cfg [cfg ...]
 Runtime on 8 cores: cfg 1-2 seconds, cfg 3 about 3 minutes, cfg 4 about
 25 minutes, cfg 5 about 1.6 hours (5,829 s measured).
+
+       python tests/golden/make_golden.py --variants
+writes tests/golden/variants.json: the optional parts of the model on the 2^30-plan
+configurations (per-variant factors on config 2's chain and config 4's tree, profiled
+path accuracies on config 2), each by the plain per-index search; about 3 minutes.
 """
 from __future__ import annotations
 
@@ -30,11 +35,49 @@ def record(b, demand):
                 workers=int(b.workers), n_feasible=int(b.n_feasible))
 
 
+def factors_rising_with_accuracy(p):
+    """Per-variant multiplicative factors 0.75 .. 1.5, larger for more accurate variants (Section 4.2)."""
+    return [3 + (a - 600000) // 90000 for a in p.acc_ppm]
+
+
+VARIANT_CASES = [  # name, config, what to add, demand points (milli-QPS; None: the configuration's first)
+    ("cfg2_variant_factors", 2, "variant_factors", [50_000, 150_000, 400_000]),
+    ("cfg4_variant_factors", 4, "variant_factors", [150_000, 600_000]),
+    ("cfg2_path_tables", 2, "path_tables", None),
+]
+
+
+def variants(threads):
+    doc = dict(written_by="tests/golden/make_golden.py --variants (oracle.Problem.search, every index)", cases={})
+    for name, cfg, what, demands in VARIANT_CASES:
+        w = wl.config(cfg)
+        p = w.pipeline
+        if what == "variant_factors":
+            p.variant_factor_q4 = factors_rising_with_accuracy(p)
+        else:
+            p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(w.seed + 1))
+        prob = oracle.Problem(p)
+        t0 = time.time()
+        results = []
+        for d in demands or w.demand_mqps[:1]:
+            results.append(record(prob.search(d, w.workers, w.slo_us, w.comm_us, threads=threads), d))
+            print(f"{name} demand {d} {time.time() - t0:.0f}s", flush=True)
+        doc["cases"][name] = dict(config=cfg, what=what, workload_digest=w.digest(), n_candidates=prob.num_candidates(),
+                                  workers=w.workers, slo_us=w.slo_us, comm_us=w.comm_us, results=results,
+                                  seconds=round(time.time() - t0, 1))
+    with open(os.path.join(HERE, "variants.json"), "w") as f:
+        json.dump(doc, f, indent=1)
+        f.write("\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--threads", type=int, default=None)
-    ap.add_argument("cfgs", type=int, nargs="+")
+    ap.add_argument("--variants", action="store_true")
+    ap.add_argument("cfgs", type=int, nargs="*")
     args = ap.parse_args()
+    if args.variants:
+        variants(args.threads)
     for cfg in args.cfgs:
         w = wl.config(cfg)
         prob = oracle.Problem(w.pipeline)
