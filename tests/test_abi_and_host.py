@@ -164,3 +164,22 @@ def test_bench_refuses_more_than_one_gpu_and_counts_operations():
     t = bench.measured_traffic("cfg5_tree4_k4", "tabulated")
     assert t is None or t == (425 + 1024) * 1024
     assert bench.measured_traffic("cfg1_chain2_k3", "tabulated") is None
+
+
+def test_workspace_covers_the_searches_a_handle_may_run():
+    """The size a caller must provide grows with what the handle's searches keep on the device: with
+    per-variant factors the descriptors of up to 65,535 (demand point, classes) points and a batch of per-point
+    task tables; with profiled path accuracies the table itself.  Chains, stars and deeper trees alike."""
+    import copy
+    for cfg in (2, 4, 5):
+        w = wl.config(cfg)
+        plain = binding.Problem(w.pipeline).workspace_bytes(4)
+        p = copy.deepcopy(w.pipeline)
+        p.variant_factor_q4 = [4] * len(p.acc_ppm)
+        with_factors = binding.Problem(p).workspace_bytes(4)
+        assert with_factors > plain + 65_535 * 8 * (8 + 8 + 4), (cfg, plain, with_factors)
+        assert with_factors < (1 << 30)
+        q = copy.deepcopy(w.pipeline)
+        q.path_acc_ppm = wl.draw_path_tables(q, wl.SplitMix64(1))
+        with_tables = binding.Problem(q).workspace_bytes(4)
+        assert plain < with_tables <= plain + 8 * len(q.path_acc_ppm) + 256
