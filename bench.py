@@ -47,7 +47,7 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (425 + 1024) * 1024,
                           ("cfg5_tree4_k4", "per_lane"): (276 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "d4812a5adf7e92f8cfa50be44c621329cb4e76b3310f871fa67c8f2829d8a4d5"
+TRAFFIC_SOURCES_SHA256 = "171400fde19afff7c37e33814c08a84d805c36431322904c95a9ac1b853d33f5"
 
 
 def measured_traffic(workload: str, kernel: str):

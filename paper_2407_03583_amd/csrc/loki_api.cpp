@@ -38,13 +38,13 @@ thread_local int g_last_hip = 0;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t off_P, off_Dn, off_table, off_perm, off_run, off_perm1, off_run1, off_recs, off_results, total;
+    size_t off_P, off_Dn, off_table, off_perm, off_run, off_perm_all, off_run_t, off_recs, off_results, total;
 };
 
 // `cb` is the size of the constant block: the problem constants followed by the profiled path
 // accuracies (if any), see const_block().
-// c1: choices of the tile task of a class-by-class search with swapped roles (then off_perm1 holds a list of
-// the choices of every task, table_total entries per point, and off_run1 the tile task's runs), else 0.
+// c1: choices of the tile task of a class-by-class search with swapped roles (then off_perm_all holds a list of
+// the choices of every task, table_total entries per point, and off_run_t the tile task's runs), else 0.
 Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, uint32_t c1 = 0) {
     Layout l;
     l.off_P = 0;
@@ -52,18 +52,17 @@ Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, ui
     l.off_table = align_up(l.off_Dn + size_t(M) * kMaxTasks * sizeof(int64_t));
     l.off_perm = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
     l.off_run = align_up(l.off_perm + size_t(M) * c0 * sizeof(uint32_t));
-    l.off_perm1 = align_up(l.off_run + size_t(M) * c0 * sizeof(uint32_t));
-    l.off_run1 = align_up(l.off_perm1 + size_t(M) * (c1 ? table_total : 0u) * sizeof(uint32_t));
-    l.off_recs = align_up(l.off_run1 + size_t(M) * c1 * sizeof(uint32_t));
+    l.off_perm_all = align_up(l.off_run + size_t(M) * c0 * sizeof(uint32_t));
+    l.off_run_t = align_up(l.off_perm_all + size_t(M) * (c1 ? table_total : 0u) * sizeof(uint32_t));
+    l.off_recs = align_up(l.off_run_t + size_t(M) * c1 * sizeof(uint32_t));
     l.off_results = align_up(l.off_recs + (size_t(kTargetBlocks) + size_t(M)) * sizeof(BestRec));
     l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
     return l;
 }
 
-// Per-variant factors on a tree whose other tasks all hang off the first task: the search runs over
-// (demand point, class) pairs, a batch of them per set of launches: as many as keep the per-pair task
-// tables within kClassTableBytes, between 256 and 4096 (more pairs per launch give every block several
-// work items, which spreads its start-up cost).
+// Per-variant factors searched class by class: a point of a launch is a demand point with one class (one
+// amount of created requests) per task that has children.  A batch of points per set of launches: as many
+// as keep the per-point task tables within kClassTableBytes, between 256 and 4096.
 constexpr int64_t kMaxClassPoints = 65535;
 constexpr size_t kClassTableBytes = size_t(256) << 20;
 int32_t class_batch(uint32_t table_total) {
@@ -71,9 +70,8 @@ int32_t class_batch(uint32_t table_total) {
     return int32_t(std::min<size_t>(4096, std::max<size_t>(256, fit)));
 }
 
-// Whether a handle's searches can run class by class: per-variant factors, product objective, every
-// other task a child of the first one, the first task's choices orderable into runs, and tables small
-// enough to keep a batch of copies of them in the workspace.
+// Whether some search of the handle can run class by class (see class_search_mode): the workspace is then
+// sized for it.
 bool class_search_applies(const loki_problem *p);
 
 struct ClassLayout {
@@ -367,12 +365,11 @@ int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t n_de
     return LOKI_OK;
 }
 
-// Order of the (demand point, class) pairs and their split into batches.  The blocks of a launch are
-// shared out evenly among its pairs, so a batch should hold pairs of similar size: pairs go by
-// descending number of first-task choices, a batch takes as many as leave each of its pairs about one
-// block per kClassItemsPerBlock work items (items: work items per pair, 1 each where that does not
-// apply), and inside a batch the pairs of a demand point are kept together (the merge folds stretches
-// of equal points).
+// Order of the points of a class-by-class search and their split into batches.  The blocks of a launch
+// are shared out evenly among its points, so a batch should hold points of similar size: they go by
+// descending number of work items (items[]; 1 each where the roles are not swapped), a batch takes as
+// many as leave each of its points about one block per kClassItemsPerBlock work items, and inside a batch
+// the points of a demand point are kept together (the merge folds stretches of equal demand points).
 constexpr uint64_t kClassItemsPerBlock = 8;
 
 void plan_class_batches(ClassPoints &cp, const std::vector<uint64_t> &items, int32_t batch_limit,
@@ -622,8 +619,8 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     A.recs = reinterpret_cast<BestRec *>(bw + lay.batch.off_recs);
     A.perm = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm);
     A.run_end = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run);
-    A.perm_all = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm1);
-    A.run_end_t = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run1);
+    A.perm_all = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm_all);
+    A.run_end_t = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run_t);
     A.swap = swap ? 1u : 0u;
     A.results = ws + lay.off_class_results;
     path_budgets(p, slo_us, comm_us, A.budget);
