@@ -347,21 +347,34 @@ int walk_classes(ClassWalk &w, int i) {
     return LOKI_OK;
 }
 
-int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, ClassPoints &cp) {
+// The points of the demand points [first, n_demand), as many whole demand points as stay within
+// kMaxClassPoints; *next is the first demand point left out.  LOKI_E_ARG when a single demand point has more.
+int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t first, int32_t n_demand, ClassPoints &cp,
+                       int32_t *next) {
     if (p->choice_x.empty()) decode_choices(p);
     ClassWalk w;
     w.p = p;
     w.cp = &cp;
-    for (int32_t m = 0; m < n_demand; m++) {
+    int32_t m = first;
+    for (; m < n_demand; m++) {
         int64_t bound[kMaxTasks];
         const int rc = task_demand(p, demand_mqps[m], bound);  // range proof with the largest factors
         if (rc) return rc;
+        const size_t before = cp.size();
         w.memo.clear();
         w.point = m;
         w.Dn[0] = demand_mqps[m];
         const int rc2 = walk_classes(w, 0);
+        if (rc2 == LOKI_E_ARG && m > first) {  // this demand point starts the next group
+            cp.point.resize(before);
+            cp.Dn.resize(before * kMaxTasks);
+            cp.amount.resize(before * kMaxTasks);
+            cp.count.resize(before * kMaxTasks);
+            break;
+        }
         if (rc2) return rc2;
     }
+    *next = m;
     return LOKI_OK;
 }
 
@@ -530,49 +543,8 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
         return LOKI_E_WORKSPACE;
     if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
-    ClassPoints cp;
-    int rc = build_class_points(p, demand_mqps, n_demand, cp);
+    int rc = ensure_staging(p, n_demand);
     if (rc) return rc;
-    const int64_t V = int64_t(cp.size());
-    // per point: the combinations of the work item's tasks (swapped roles) or the first task's choices
-    auto far_of = [&](int64_t v) {
-        const uint32_t *cnt = cp.count.data() + size_t(v) * kMaxTasks;
-        if (!swap) return uint64_t(cnt[0]);
-        uint64_t far = 1;
-        for (int j = 0; j < L; j++)
-            if (j != T) far *= cnt[j];
-        return far;
-    };
-    {
-        const uint64_t span = index_end - index_begin, c0 = p->dev.C[0];
-        p->last_scored = 0;
-        for (int64_t v = 0; v < V; v++) {
-            const uint32_t *cnt = cp.count.data() + size_t(v) * kMaxTasks;
-            uint64_t plans = uint64_t(cnt[0]) * ((span + c0 - 1) / c0);  // exact for the whole space
-            if (swap) {
-                plans = 1;
-                for (int j = 0; j < p->n; j++) plans *= cnt[j];
-            }
-            p->last_scored += plans;
-        }
-        p->have_scored = true;
-    }
-    std::vector<int64_t> batch_first;
-    {
-        // work items per point with swapped roles (else one batch size fits all)
-        const uint64_t mid_tiles = (p->dev.C[T] + kMidTile - 1) / kMidTile;
-        std::vector<uint64_t> items(size_t(V), 1);
-        if (swap)
-            for (int64_t v = 0; v < V; v++) items[size_t(v)] = far_of(v) * mid_tiles;
-        plan_class_batches(cp, items, class_batch(p->dev.table_total), batch_first);
-    }
-
-    rc = ensure_staging(p, n_demand);
-    if (rc) return rc;
-    if (p->staged_pending) {  // an earlier call's copies may still be reading the staging buffers
-        LOKI_HIP(hipEventSynchronize(p->staged));
-        p->staged_pending = false;
-    }
     const size_t per_point = kMaxTasks * (2 * sizeof(int64_t) + sizeof(uint32_t)) + sizeof(int32_t);
     if (!p->class_staging) {
         void *ptr = nullptr;
@@ -580,23 +552,6 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
         p->class_staging = static_cast<unsigned char *>(ptr);
     }
     unsigned char *ws = static_cast<unsigned char *>(d_workspace);
-    fill_const_block(p);
-    LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, cb, hipMemcpyHostToDevice, stream));
-    if (V > 0) {
-        unsigned char *h = p->class_staging;
-        const size_t nDn = size_t(V) * kMaxTasks * sizeof(int64_t), nOut = size_t(V) * kMaxTasks * sizeof(int64_t),
-                     nCount = size_t(V) * kMaxTasks * sizeof(uint32_t), nPoint = size_t(V) * sizeof(int32_t);
-        std::memcpy(h, cp.Dn.data(), nDn);
-        std::memcpy(h + nDn, cp.amount.data(), nOut);
-        std::memcpy(h + nDn + nOut, cp.count.data(), nCount);
-        std::memcpy(h + nDn + nOut + nCount, cp.point.data(), nPoint);
-        LOKI_HIP(hipMemcpyAsync(ws + lay.off_vDn, h, nDn, hipMemcpyHostToDevice, stream));
-        LOKI_HIP(hipMemcpyAsync(ws + lay.off_vOut, h + nDn, nOut, hipMemcpyHostToDevice, stream));
-        LOKI_HIP(hipMemcpyAsync(ws + lay.off_vCount, h + nDn + nOut, nCount, hipMemcpyHostToDevice, stream));
-        LOKI_HIP(hipMemcpyAsync(ws + lay.off_vPoint, h + nDn + nOut + nCount, nPoint, hipMemcpyHostToDevice, stream));
-    }
-    LOKI_HIP(hipEventRecord(p->staged, stream));
-    p->staged_pending = true;
 
     MergeArgs G;
     std::memset(&G, 0, sizeof(G));
@@ -604,12 +559,6 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     if (results_at) *results_at = G.results;
     G.M = n_demand;
     G.tie_index_only = (flags & LOKI_TIE_INDEX_ONLY) ? 1u : 0u;
-    if (timed) LOKI_HIP(hipEventRecord(p->ev[0], stream));
-    LOKI_HIP(launch_results_init(G, stream));
-    if (timed && V == 0) {
-        LOKI_HIP(hipEventRecord(p->ev[1], stream));
-        LOKI_HIP(hipEventRecord(p->ev[2], stream));
-    }
 
     SearchArgs A;
     std::memset(&A, 0, sizeof(A));
@@ -635,23 +584,101 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
         A.w_free_t = static_cast<int32_t>(std::max<int64_t>(int64_t(workers) - others_t, -1));
     }
     A.tie_index_only = G.tie_index_only;
-    for (size_t b = 0; b + 1 < batch_first.size(); b++) {
-        const int64_t v0 = batch_first[b];
-        const int32_t nb = int32_t(batch_first[b + 1] - v0);
-        A.M = nb;
-        A.Dn = reinterpret_cast<const int64_t *>(ws + lay.off_vDn) + size_t(v0) * kMaxTasks;
-        A.class_amount = reinterpret_cast<const int64_t *>(ws + lay.off_vOut) + size_t(v0) * kMaxTasks;
-        A.class_count = reinterpret_cast<const uint32_t *>(ws + lay.off_vCount) + size_t(v0) * kMaxTasks;
-        uint64_t most = 1;
-        for (int32_t j = 0; j < nb; j++) most = std::max(most, far_of(v0 + j));
-        const bool first = v0 == 0, last = v0 + nb >= V;
-        rc = launch_tabulated(p, A, most, index_begin, index_end, stream, timed && first ? p->ev[1] : nullptr,
-                              timed && last ? p->ev[2] : nullptr);
-        if (rc) return rc;
-        G.class_results = A.results;
-        G.point = reinterpret_cast<const int32_t *>(ws + lay.off_vPoint) + v0;
-        G.n = nb;
-        LOKI_HIP(launch_class_merge(G, stream));
+
+    // The demand points are taken in groups whose points fit the descriptor arrays (one group unless the call
+    // has many demand points or tasks with children); the first group is built before anything is enqueued,
+    // so that a call that cannot run class by class at all leaves no work behind.
+    p->last_scored = 0;
+    p->have_scored = true;
+    bool enqueued = false, first_search = true;
+    for (int32_t m0 = 0; m0 < n_demand;) {
+        ClassPoints cp;
+        int32_t m1 = m0;
+        rc = build_class_points(p, demand_mqps, m0, n_demand, cp, &m1);
+        if (rc) return rc;  // (LOKI_E_ARG: one demand point alone has too many points; the caller falls back)
+        const int64_t V = int64_t(cp.size());
+        // per point: the combinations of the work item's tasks (swapped roles) or the first task's choices
+        auto far_of = [&](int64_t v) {
+            const uint32_t *cnt = cp.count.data() + size_t(v) * kMaxTasks;
+            if (!swap) return uint64_t(cnt[0]);
+            uint64_t far = 1;
+            for (int j = 0; j < L; j++)
+                if (j != T) far *= cnt[j];
+            return far;
+        };
+        {
+            const uint64_t span = index_end - index_begin, c0 = p->dev.C[0];
+            for (int64_t v = 0; v < V; v++) {
+                const uint32_t *cnt = cp.count.data() + size_t(v) * kMaxTasks;
+                uint64_t plans = uint64_t(cnt[0]) * ((span + c0 - 1) / c0);  // exact for the whole space
+                if (swap) {
+                    plans = 1;
+                    for (int j = 0; j < p->n; j++) plans *= cnt[j];
+                }
+                p->last_scored += plans;
+            }
+        }
+        std::vector<int64_t> batch_first;
+        {
+            // work items per point with swapped roles (else one batch size fits all)
+            const uint64_t mid_tiles = (p->dev.C[T] + kMidTile - 1) / kMidTile;
+            std::vector<uint64_t> items(size_t(V), 1);
+            if (swap)
+                for (int64_t v = 0; v < V; v++) items[size_t(v)] = far_of(v) * mid_tiles;
+            plan_class_batches(cp, items, class_batch(p->dev.table_total), batch_first);
+        }
+
+        if (p->staged_pending) {  // earlier copies (a previous call, the previous group) may still read the staging buffers
+            LOKI_HIP(hipEventSynchronize(p->staged));
+            p->staged_pending = false;
+        }
+        if (!enqueued) {
+            fill_const_block(p);
+            LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, cb, hipMemcpyHostToDevice, stream));
+            if (timed) LOKI_HIP(hipEventRecord(p->ev[0], stream));
+            LOKI_HIP(launch_results_init(G, stream));
+            enqueued = true;
+        }
+        if (V > 0) {
+            unsigned char *h = p->class_staging;
+            const size_t nDn = size_t(V) * kMaxTasks * sizeof(int64_t), nOut = size_t(V) * kMaxTasks * sizeof(int64_t),
+                         nCount = size_t(V) * kMaxTasks * sizeof(uint32_t), nPoint = size_t(V) * sizeof(int32_t);
+            std::memcpy(h, cp.Dn.data(), nDn);
+            std::memcpy(h + nDn, cp.amount.data(), nOut);
+            std::memcpy(h + nDn + nOut, cp.count.data(), nCount);
+            std::memcpy(h + nDn + nOut + nCount, cp.point.data(), nPoint);
+            LOKI_HIP(hipMemcpyAsync(ws + lay.off_vDn, h, nDn, hipMemcpyHostToDevice, stream));
+            LOKI_HIP(hipMemcpyAsync(ws + lay.off_vOut, h + nDn, nOut, hipMemcpyHostToDevice, stream));
+            LOKI_HIP(hipMemcpyAsync(ws + lay.off_vCount, h + nDn + nOut, nCount, hipMemcpyHostToDevice, stream));
+            LOKI_HIP(hipMemcpyAsync(ws + lay.off_vPoint, h + nDn + nOut + nCount, nPoint, hipMemcpyHostToDevice, stream));
+        }
+        LOKI_HIP(hipEventRecord(p->staged, stream));
+        p->staged_pending = true;
+
+        for (size_t b = 0; b + 1 < batch_first.size(); b++) {
+            const int64_t v0 = batch_first[b];
+            const int32_t nb = int32_t(batch_first[b + 1] - v0);
+            A.M = nb;
+            A.Dn = reinterpret_cast<const int64_t *>(ws + lay.off_vDn) + size_t(v0) * kMaxTasks;
+            A.class_amount = reinterpret_cast<const int64_t *>(ws + lay.off_vOut) + size_t(v0) * kMaxTasks;
+            A.class_count = reinterpret_cast<const uint32_t *>(ws + lay.off_vCount) + size_t(v0) * kMaxTasks;
+            uint64_t most = 1;
+            for (int32_t j = 0; j < nb; j++) most = std::max(most, far_of(v0 + j));
+            // (the event after the search kernel is recorded again by every batch: the last one counts)
+            rc = launch_tabulated(p, A, most, index_begin, index_end, stream, timed && first_search ? p->ev[1] : nullptr,
+                                  timed ? p->ev[2] : nullptr);
+            if (rc) return rc;
+            first_search = false;
+            G.class_results = A.results;
+            G.point = reinterpret_cast<const int32_t *>(ws + lay.off_vPoint) + v0;
+            G.n = nb;
+            LOKI_HIP(launch_class_merge(G, stream));
+        }
+        m0 = m1;
+    }
+    if (timed && first_search) {  // nothing to search at all
+        LOKI_HIP(hipEventRecord(p->ev[1], stream));
+        LOKI_HIP(hipEventRecord(p->ev[2], stream));
     }
     if (timed) LOKI_HIP(hipEventRecord(p->ev[3], stream));
     return LOKI_OK;

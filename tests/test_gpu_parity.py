@@ -503,8 +503,8 @@ def test_per_variant_factors_class_by_class_on_a_detector_with_two_classifiers()
 
 def test_per_variant_factors_with_more_classes_than_one_call_takes():
     """65,535 demand points on a small detector-and-classifier pipeline with factors: the (demand point,
-    class) pairs exceed what one call handles class by class, so the library scores whole plans per lane;
-    12,000 points stay below the limit.  Both against the checker on samples."""
+    class) pairs exceed what the descriptor arrays hold, so the library takes the demand points in groups;
+    12,000 points fit one group.  Both against the checker on samples."""
     p = SimpleNamespace(n_tasks=2, parent=[-1, 0], fanout_q4=[4, 6], n_variants=[2, 2], n_batches=[2, 1],
                         batch_size=[1, 4, 2], max_replicas=[2, 2, 3, 3], acc_ppm=[700000, 900000, 650000, 880000],
                         latency_us=[3000, 9000, 5000, 14000, 4000, 7000],
@@ -527,6 +527,7 @@ def test_per_variant_factors_with_more_classes_than_one_call_takes():
     for n_points in (65_535, 12_000):
         demands = [rng.randint(0, 1_500_000) for _ in range(n_points)]
         out = P.alloc_search(demands, 9, 60_000)
+        assert P.last_search_plans_scored() < P.num_candidates() * n_points     # class by class, not per lane
         for j in list(range(0, n_points, 997)) + [n_points - 1]:
             check(out[j], O.search(demands[j], 9, 60_000), f"{n_points} points, point {j}")
 
@@ -780,3 +781,25 @@ def test_model_variants_at_full_size_against_stored_checker_results():
         for res, ref in zip(out, case["results"]):
             check(res, ref, f"{name} demand {ref['demand_mqps']}")
         assert any(r["found"] and r["n_feasible"] > 1000 for r in case["results"]), name
+
+
+def test_per_variant_factors_sweep_on_a_deeper_tree_in_groups():
+    """Config 5's shape (0 -> 1 -> 2, 0 -> 3) with 3 variants per task and 4,000 demand points: two tasks have
+    children, so a demand point has hundreds of (class, class) points and the call is taken in several
+    groups of demand points.  Sampled demand points against the checker's brute force (65,536 plans each)."""
+    rng = wl.SplitMix64(77)
+    p = wl.make_pipeline([-1, 0, 1, 0], 3, 1, (1, 4), rng)
+    p.variant_factor_q4 = [3 + (a - 600000) // 60000 for a in p.acc_ppm]
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n == 16 ** 4
+    r = random.Random(5)
+    demands = [r.randint(0, 400_000) for _ in range(4000)]
+    out = P.alloc_search(demands, 10, 700_000)
+    scored = P.last_search_plans_scored()
+    assert scored < n * len(demands)
+    found = 0
+    for j in list(range(0, len(demands), 131)) + [len(demands) - 1]:
+        check(out[j], O.search(demands[j], 10, 700_000), f"point {j} demand {demands[j]}")
+        found += out[j].status == binding.LOKI_FOUND
+    assert found >= 5
