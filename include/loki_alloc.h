@@ -121,12 +121,10 @@ typedef struct {
                                     on its parent's part of the plan and tasks work in units of milli-QPS /
                                     16^depth.  A task's demand then depends on its ancestors' choices only
                                     through the amounts of requests they create, which take few distinct
-                                    values: a whole-space search (and any search of a pipeline whose other
-                                    tasks are all children of task 0) runs the tabulated kernels once per
-                                    combination of such amounts, the host settling the choices that cannot
-                                    serve their demand (same results).  Index ranges of other pipelines and
-                                    demand points with more than 65,535 such combinations score whole plans
-                                    per lane (LOKI_SEARCH_PER_LANE). */
+                                    values: a search runs the tabulated kernels once per combination of such
+                                    amounts, the host settling the choices that cannot serve their demand
+                                    (same results).  Demand points with more than 65,535 such combinations
+                                    score whole plans per lane (LOKI_SEARCH_PER_LANE). */
     int32_t per_variant_batch;   /* 0: one batch size per task.  1: a batch size per hosted variant, the y(i,k)
                                     of Section 4.1 "Output" and eq. (4); see the index layout above */
     const int32_t *path_acc_ppm; /* NULL, or the profiled end-to-end accuracy A-hat(p) of every variant path

@@ -512,13 +512,15 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
 }
 
 // How a class-by-class search of [index_begin, index_end) would run: 2 with swapped roles (three or more
-// tasks, the tile task's choices orderable into runs and its index part within 32 bits, whole space),
+// tasks, the tile task's choices orderable into runs and its index part within 32 bits),
 // 1 with the first task's choices in the tiles (every other task a child of the first one, its choices
 // orderable into runs), 0 not at all.
 int class_search_mode(const loki_problem *p, uint64_t index_begin, uint64_t index_end) {
     if (!p->dev.has_vf || p->dev.has_path || p->n < 2 || p->dev.table_total > (1u << 16)) return 0;
     const int t = p->dev.tile_task;
-    if (p->n >= 3 && index_begin == 0 && index_end == p->n_candidates && index_end > 0 &&
+    (void)index_begin;
+    (void)index_end;
+    if (p->n >= 3 &&
         uint64_t(p->dev.sum_r_t + 1) * uint64_t(p->dev.n_lat_t) + 1 <= 4096 &&
         p->dev.stride[t] <= (uint64_t(1) << 32) / p->dev.C[t])
         return 2;

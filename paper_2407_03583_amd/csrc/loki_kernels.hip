@@ -593,7 +593,7 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // then only forms the S*64 objectives (one fp64 multiply, one add each), keeps
 // their running maximum, and compares that with the lanes' best.
 //
-// SWAP (per-variant factors class by class, two or more leaves, whole space): a point owns only a few
+// SWAP (per-variant factors class by class, three or more tasks): a point owns only a few
 // choices of every task that has children, too few to fill a tile.  The tile then holds the choices of
 // the first leaf (in their own run order), and every other task but the last is part of the work item:
 // a task with children through the list of its choices that belong to the point, a leaf through all of
@@ -938,7 +938,8 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     ul.cl_lo = n >= 2 ? run_end[tile_base + e] - tile_base : e + 1;
                     ul.cl_cnt = CL;
                     if (RANGE) {
-                        const uint64_t base = base_f + cMs[k];  // index of the plan with the last task's choice 0
+                        // index of the plan with the last task's choice 0
+                        const uint64_t base = base_f + (SWAP ? uni64(sP->stride[T]) * cMs[k] : static_cast<uint64_t>(cMs[k]));
                         const uint64_t lo = A.begin > base ? (A.begin - base + strideL - 1) / strideL : 0;
                         uint64_t hi = A.end > base ? (A.end - base + strideL - 1) / strideL : 0;
                         if (hi > CL) hi = CL;
@@ -1780,10 +1781,14 @@ __global__ void __launch_bounds__(kBlockThreads) class_merge_kernel(MergeArgs A)
 template <int S>
 hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
-    if (A.swap) {  // whole space (the host sets swap only then)
-        if (!has_presum) hipLaunchKernelGGL((combine_kernel<S, false, false, false, true>), grid, block, 0, stream, A);
-        else if (divide) hipLaunchKernelGGL((combine_kernel<S, true, true, false, true>), grid, block, 0, stream, A);
-        else hipLaunchKernelGGL((combine_kernel<S, true, false, false, true>), grid, block, 0, stream, A);
+    if (A.swap) {
+#define LOKI_LAUNCH_SWAP(P, D)                                                                                   \
+    if (range) hipLaunchKernelGGL((combine_kernel<S, P, D, true, true>), grid, block, 0, stream, A);             \
+    else hipLaunchKernelGGL((combine_kernel<S, P, D, false, true>), grid, block, 0, stream, A);
+        if (!has_presum) { LOKI_LAUNCH_SWAP(false, false) }
+        else if (divide) { LOKI_LAUNCH_SWAP(true, true) }
+        else { LOKI_LAUNCH_SWAP(true, false) }
+#undef LOKI_LAUNCH_SWAP
         return hipGetLastError();
     }
 #define LOKI_LAUNCH(P, D, R)                                                            \

@@ -642,6 +642,24 @@ def test_per_variant_factors_on_deeper_trees_class_by_class(parent, seed):
                     check(a, O.search(d, workers, slo, tie_index_only=bool(flags & TIE)), f"demand {d} workers {workers}")
             found += sum(r.status == binding.LOKI_FOUND for r in by_class)
     assert found >= 6
+    # ragged index ranges run class by class as well (every tile entry then carries its own interval of the
+    # last task's choices): against the checker on the same ranges
+    cuts = [0, n // 5 + 3, n // 2 + 77, n - n // 7, n]
+    for d in demands[1:4]:
+        parts = []
+        for a, b in zip(cuts, cuts[1:]):
+            res = P.alloc_search([d], 4 * n_tasks, 600_000, begin=a, end=b)[0]
+            assert P.last_search_plans_scored() < n       # (an upper estimate of what the kernels scored)
+            if n_tasks == 4:
+                check(res, O.search(d, 4 * n_tasks, 600_000, begin=a, end=b), f"demand {d} range {a}..{b}")
+            parts.append(res)
+        whole = P.alloc_search([d], 4 * n_tasks, 600_000)[0]
+        assert sum(r.n_feasible for r in parts) == whole.n_feasible
+        hits = [r for r in parts if r.status == binding.LOKI_FOUND]
+        if hits:
+            best = min(hits, key=lambda r: (-r.accuracy, r.workers_used, r.index))
+            assert (best.index, bits(best.accuracy), best.workers_used) == \
+                (whole.index, bits(whole.accuracy), whole.workers_used)
 
 
 @pytest.mark.parametrize("full_task", [2, 3])
