@@ -44,10 +44,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (425 + 1024) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (276 + 1024) * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (430 + 1024) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (264 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "171400fde19afff7c37e33814c08a84d805c36431322904c95a9ac1b853d33f5"
+TRAFFIC_SOURCES_SHA256 = "68e138eb44beb4d39ef6d6d7365fd8d5384e61a987d395de561a37a7adcfa859"
 
 
 def measured_traffic(workload: str, kernel: str):
