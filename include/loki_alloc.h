@@ -225,7 +225,9 @@ int loki_alloc_search(loki_problem_t *problem, const int64_t *demand_mqps, int32
 /* Same, but only enqueues: results are left in device memory at d_results
  * ([n_demand] loki_result_t, device, 8-byte aligned) when the stream reaches
  * that point; nothing is copied back and the call does not wait for the GPU
- * (it may wait for the staging copy of the previous call on this handle). */
+ * (it may wait for the staging copy of the previous call on this handle, and a
+ * search with per-variant factors whose demand points are taken in groups waits
+ * for every group's descriptors but the last to be copied). */
 int loki_alloc_search_enqueue(loki_problem_t *problem, const int64_t *demand_mqps, int32_t n_demand,
                               int32_t workers, int64_t slo_us, int64_t comm_us, uint32_t flags,
                               uint64_t index_begin, uint64_t index_end,
