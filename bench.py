@@ -123,9 +123,9 @@ def main() -> int:
     if variant:
         w.name += "+" + "+".join(variant)
     # what the library does anyway: per-variant factors are searched class by class by the tabulated kernels
-    # (whole space, two or more tasks); profiled path accuracies with the feasibility part tabulated, unless
-    # per-variant factors come with them (then whole plans per lane)
-    by_class = args.variant_factors and w.pipeline.n_tasks >= 2 and not args.per_lane and not args.path_tables
+    # (two or more tasks); profiled path accuracies with the feasibility part tabulated and the variant paths
+    # walked for feasible plans only
+    by_class = args.variant_factors and w.pipeline.n_tasks >= 2 and not args.per_lane
     args.per_lane = args.per_lane or (args.variant_factors and not by_class)
     P = binding.Problem(w.pipeline)
     n = P.num_candidates()
@@ -185,7 +185,8 @@ def main() -> int:
         "config": {"workload": w.name, "seed": w.seed, "candidates": n, "demand_points": m,
                    "index_end": end, "evaluations_per_step": evaluations, "plans_scored_by_kernels": scored,
                    "kernel": ("per_lane_paths" if args.path_tables else "per_lane") if args.per_lane
-                   else ("tabulated_by_class" if by_class else ("tabulated_paths" if args.path_tables else "tabulated")),
+                   else (("tabulated_by_class_paths" if args.path_tables else "tabulated_by_class") if by_class
+                         else ("tabulated_paths" if args.path_tables else "tabulated")),
                    "feasible_fraction_point0": first[0].n_feasible / end},
         "kernel_ms": {"task_tables": sum(k[0] for k in kernel_ms) / len(kernel_ms), "search": main_ms,
                       "final_merge": sum(k[2] for k in kernel_ms) / len(kernel_ms)},

@@ -143,8 +143,8 @@ typedef struct {
                                     order, task paths added in leaf order, one division by their number.
                                     The objective couples the tasks through c(p), feasibility does not: a
                                     search takes feasibility from the per-task tables and walks the variant
-                                    paths for feasible plans only (whole plans per lane together with
-                                    variant_factor_q4 and with LOKI_SEARCH_PER_LANE; same results). */
+                                    paths for feasible plans only (whole plans per lane with
+                                    LOKI_SEARCH_PER_LANE; same results). */
 } loki_pipeline_t;
 
 typedef struct loki_problem loki_problem_t; /* opaque handle */

@@ -516,7 +516,7 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
 // 1 with the first task's choices in the tiles (every other task a child of the first one, its choices
 // orderable into runs), 0 not at all.
 int class_search_mode(const loki_problem *p, uint64_t index_begin, uint64_t index_end) {
-    if (!p->dev.has_vf || p->dev.has_path || p->n < 2 || p->dev.table_total > (1u << 16)) return 0;
+    if (!p->dev.has_vf || p->n < 2 || p->dev.table_total > (1u << 16)) return 0;
     const int t = p->dev.tile_task;
     (void)index_begin;
     (void)index_end;
@@ -573,6 +573,7 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     A.perm_all = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm_all);
     A.run_end_t = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run_t);
     A.swap = swap ? 1u : 0u;
+    A.path_acc = device_path_acc(p, ws);
     A.results = ws + lay.off_class_results;
     path_budgets(p, slo_us, comm_us, A.budget);
     A.begin = index_begin;

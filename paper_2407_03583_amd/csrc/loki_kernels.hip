@@ -1117,7 +1117,7 @@ constexpr uint32_t kWalkQueue = 128;
 // only takes the feasibility masks, once per run; the plans of a run that are feasible go, by index, into
 // a queue of the wavefront, and whenever 64 are waiting every lane walks the variant paths of one
 // (path_objective).  The cost is a few instructions per 512 plans plus the walk for feasible plans only.
-template <int S, bool RANGE, int MAXD>
+template <int S, bool RANGE, int MAXD, bool SWAP>
 __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine_kernel(SearchArgs A) {
     __shared__ DevProblem sPfull;
     __shared__ MidLim sLim[kMidTile];
@@ -1138,8 +1138,27 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
     const uint64_t strideL = uni64(sP->stride[L]);
     const TaskRec *tab = A.table + static_cast<size_t>(m) * uni(sP->table_total);
     const TaskRec *tabL = tab + uni(sP->table_off[L]);
-    const uint32_t *perm = A.perm + static_cast<size_t>(m) * C0;
-    const uint32_t *run_end = A.run_end + static_cast<size_t>(m) * C0;
+    // SWAP (with per-variant factors, class by class): the tile task and the work item's digits as in
+    // combine_kernel; only replicas and latencies matter here, the objective comes from the walk
+    const int T = SWAP ? uni(sP->tile_task) : 0;
+    const bool tile_leaf = !SWAP || uni(sP->is_leaf[T]) != 0;
+    const uint32_t Cmid = SWAP ? uni(sP->C[T]) : C0;
+    const uint32_t mid_count =
+        SWAP ? (tile_leaf ? Cmid : uni(A.class_count[static_cast<size_t>(m) * kMaxTasks + T])) : C0;
+    const TaskRec *tabM = SWAP ? tab + uni(sP->table_off[T]) : tab;
+    const uint32_t *perm_m = SWAP ? A.perm_all + static_cast<size_t>(m) * uni(sP->table_total) : nullptr;
+    const uint32_t *perm = SWAP ? perm_m + uni(sP->table_off[T]) : A.perm + static_cast<size_t>(m) * C0;
+    const uint32_t *run_end = SWAP ? A.run_end_t + static_cast<size_t>(m) * Cmid : A.run_end + static_cast<size_t>(m) * C0;
+    uint32_t cntj[kMaxTasks];
+    uint64_t far_swap = 1;
+#pragma unroll
+    for (int j = 0; j < kMaxTasks; j++) {
+        cntj[j] = 1;
+        if (SWAP && j < L && j != T) {
+            cntj[j] = uni(A.class_count[static_cast<size_t>(m) * kMaxTasks + j]);
+            far_swap *= cntj[j];
+        }
+    }
     const bool tie_index_only = A.tie_index_only != 0;
     const int32_t W = A.W;
     const int64_t *Dn = A.Dn + static_cast<size_t>(m) * kMaxTasks;
@@ -1180,16 +1199,29 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
         }
     };
 
-    const uint64_t item_lo = A.items * blockIdx.x / A.blocks_per_m;
-    const uint64_t item_hi = A.items * (blockIdx.x + 1) / A.blocks_per_m;
+    const uint64_t far_m = SWAP ? far_swap : A.far_span;
+    const uint64_t items_m = SWAP ? static_cast<uint64_t>(A.chunk_groups) * far_m * A.mid_tiles : A.items;
+    const uint64_t item_lo = items_m * blockIdx.x / A.blocks_per_m;
+    const uint64_t item_hi = items_m * (blockIdx.x + 1) / A.blocks_per_m;
     for (uint64_t item = item_lo; item < item_hi; ++item) {
         // position of the item: tile r, combination f of the tasks in between, chunk group g
         const uint32_t r = uni(static_cast<uint32_t>(item % A.mid_tiles));
         const uint64_t t = item / A.mid_tiles;
-        const uint64_t f = uni64((A.far_first + t % A.far_span) % A.far_count);
-        const uint32_t g = uni(static_cast<uint32_t>(t / A.far_span));
+        const uint64_t f = SWAP ? 0 : uni64((A.far_first + t % A.far_span) % A.far_count);
+        const uint32_t g = uni(static_cast<uint32_t>(t / far_m));
         uint32_t cj[kMaxTasks];
-        {
+        if (SWAP) {
+            uint64_t rest = t % far_m;
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++) {
+                cj[j] = 0;
+                if (j < L && j != T) {
+                    const uint32_t d = static_cast<uint32_t>(rest % cntj[j]);
+                    rest /= cntj[j];
+                    cj[j] = uni(perm_m[uni(sP->table_off[j]) + d]);
+                }
+            }
+        } else {
             uint64_t rest = f;
 #pragma unroll
             for (int j = 1; j < kMaxTasks; j++) {
@@ -1224,32 +1256,62 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
         int64_t lat0_cap = kNever - 1;
 #pragma unroll
         for (int j = 0; j < kMaxTasks; j++) flp[j] = 0;
-#pragma unroll
-        for (int j = 1; j < kMaxTasks; j++) {
-            if (j < L) {
-                const TaskRec rec = tab[sP->table_off[j] + cj[j]];
-                const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
-                w_far += rw;
-                ok_far = ok_far && rlat != kNever;
-                flp[j] = pick_below(flp, uni(sP->parent[j]), j) + rlat;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < kMaxTasks; j++) {
-            if (j < L && uni(sP->is_leaf[j])) {
-                const int64_t room = A.budget[j] < 0 ? -1 : A.budget[j] - flp[j];
-                if (room < lat0_cap) lat0_cap = room;
-            }
-        }
-        if (lat0_cap < 0) ok_far = false;
         int64_t tl_base = A.budget[L];
-        if (n >= 2) tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, uni(sP->parent[L]), kMaxTasks);
+        if (SWAP) {
+            // the work item's tasks in topological order: replicas, latency sums along the chains from the
+            // first task (here with the first task included); a leaf closes its path (eq. (7))
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++) {
+                if (j < L && j != T) {
+                    const TaskRec rec = tab[sP->table_off[j] + cj[j]];
+                    const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
+                    w_far += rw;
+                    ok_far = ok_far && rlat != kNever;
+                    flp[j] = (j == 0 ? 0 : pick_below(flp, uni(sP->parent[j]), j)) + rlat;
+                    if (uni(sP->is_leaf[j])) ok_far = ok_far && A.budget[j] >= 0 && flp[j] <= A.budget[j];
+                }
+            }
+            const int parT = uni(sP->parent[T]);
+            if (tile_leaf) {
+                lat0_cap = A.budget[T] < 0 ? -1 : A.budget[T] - pick_below(flp, parT, kMaxTasks);
+                if (lat0_cap < 0) ok_far = false;
+                tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, uni(sP->parent[L]), kMaxTasks);
+            } else {
+                tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parT, kMaxTasks);
+            }
+        } else {
+#pragma unroll
+            for (int j = 1; j < kMaxTasks; j++) {
+                if (j < L) {
+                    const TaskRec rec = tab[sP->table_off[j] + cj[j]];
+                    const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
+                    w_far += rw;
+                    ok_far = ok_far && rlat != kNever;
+                    flp[j] = pick_below(flp, uni(sP->parent[j]), j) + rlat;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++) {
+                if (j < L && uni(sP->is_leaf[j])) {
+                    const int64_t room = A.budget[j] < 0 ? -1 : A.budget[j] - flp[j];
+                    if (room < lat0_cap) lat0_cap = room;
+                }
+            }
+            if (lat0_cap < 0) ok_far = false;
+            if (n >= 2) tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, uni(sP->parent[L]), kMaxTasks);
+        }
         const int64_t w_room = static_cast<int64_t>(W) - w_far;
 
         const uint32_t tile_base = r * A.tile_len;
-        const uint32_t left = tile_base < C0 ? C0 - tile_base : 0u;
+        const uint32_t left = tile_base < mid_count ? mid_count - tile_base : 0u;
         const uint32_t cnt = left < A.tile_len ? left : A.tile_len;
-        const uint64_t base_f = static_cast<uint64_t>(C0) * f;
+        uint64_t base_f = static_cast<uint64_t>(C0) * f;
+        if (SWAP) {
+            base_f = 0;
+#pragma unroll
+            for (int j = 0; j < kMaxTasks; j++)
+                if (j < L && j != T) base_f += cj[j] * uni64(sP->stride[j]);
+        }
 
         __syncthreads();  // the previous item's tile is no longer being read
         for (uint32_t e = threadIdx.x; e < cnt; e += kBlockThreads) {
@@ -1258,13 +1320,13 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
             bool ok = ok_far;
             if (n >= 2) {
                 cM = perm[tile_base + e];
-                const TaskRec rec = tab[cM];
+                const TaskRec rec = tabM[cM];
                 w0 = rec.w;
                 lat0 = rec.lat;
                 ok = ok_far && rec.lat != kNever && static_cast<int64_t>(rec.lat) <= lat0_cap;
             }
             MidLim ul;
-            int64_t tl = tl_base < 0 ? -1 : tl_base - static_cast<int64_t>(lat0);
+            int64_t tl = tl_base < 0 ? -1 : tl_base - ((SWAP && tile_leaf) ? 0 : static_cast<int64_t>(lat0));
             if (tl < 0) tl = -1;
             if (tl > kNever - 1) tl = kNever - 1;
             ul.tl = static_cast<int32_t>(tl);
@@ -1273,7 +1335,7 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
             ul.cl_lo = n >= 2 ? run_end[tile_base + e] - tile_base : e + 1;
             ul.cl_cnt = CL;
             if (RANGE) {
-                const uint64_t base = base_f + cM;
+                const uint64_t base = base_f + (SWAP ? uni64(sP->stride[T]) * cM : static_cast<uint64_t>(cM));
                 const uint64_t lo = A.begin > base ? (A.begin - base + strideL - 1) / strideL : 0;
                 uint64_t hi = A.end > base ? (A.end - base + strideL - 1) / strideL : 0;
                 if (hi > CL) hi = CL;
@@ -1281,7 +1343,7 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
                 ul.cl_cnt = static_cast<uint32_t>(hi > lo ? hi - lo : 0);
             }
             sLim[e] = ul;
-            sChoice[e] = cM;
+            sChoice[e] = SWAP ? static_cast<uint32_t>(uni64(sP->stride[T])) * cM : cM;
         }
         __syncthreads();
 
@@ -1847,8 +1909,13 @@ hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_v
 template <int S, int MAXD>
 hipError_t launch_path_combine_s(const SearchArgs &A, bool range, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
-    if (range) hipLaunchKernelGGL((path_combine_kernel<S, true, MAXD>), grid, block, 0, stream, A);
-    else hipLaunchKernelGGL((path_combine_kernel<S, false, MAXD>), grid, block, 0, stream, A);
+    if (A.swap) {
+        if (range) hipLaunchKernelGGL((path_combine_kernel<S, true, MAXD, true>), grid, block, 0, stream, A);
+        else hipLaunchKernelGGL((path_combine_kernel<S, false, MAXD, true>), grid, block, 0, stream, A);
+    } else {
+        if (range) hipLaunchKernelGGL((path_combine_kernel<S, true, MAXD, false>), grid, block, 0, stream, A);
+        else hipLaunchKernelGGL((path_combine_kernel<S, false, MAXD, false>), grid, block, 0, stream, A);
+    }
     return hipGetLastError();
 }
 

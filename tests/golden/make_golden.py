@@ -9,7 +9,8 @@ Runtime on 8 cores: cfg 1-2 seconds, cfg 3 about 3 minutes, cfg 4 about
        python tests/golden/make_golden.py --variants
 writes tests/golden/variants.json: the optional parts of the model on the 2^30-plan
 configurations (per-variant factors on config 2's chain and config 4's tree, profiled
-path accuracies on config 2), each by the plain per-index search; about 3 minutes.
+path accuracies on config 2, both together on config 2), each by the plain per-index
+search; about 4 minutes.
 """
 from __future__ import annotations
 
@@ -44,6 +45,7 @@ VARIANT_CASES = [  # name, config, what to add, demand points (milli-QPS; None: 
     ("cfg2_variant_factors", 2, "variant_factors", [50_000, 150_000, 400_000]),
     ("cfg4_variant_factors", 4, "variant_factors", [150_000, 600_000]),
     ("cfg2_path_tables", 2, "path_tables", None),
+    ("cfg2_factors_and_path_tables", 2, "both", [150_000, 400_000]),
 ]
 
 
@@ -52,9 +54,9 @@ def variants(threads):
     for name, cfg, what, demands in VARIANT_CASES:
         w = wl.config(cfg)
         p = w.pipeline
-        if what == "variant_factors":
+        if what in ("variant_factors", "both"):
             p.variant_factor_q4 = factors_rising_with_accuracy(p)
-        else:
+        if what in ("path_tables", "both"):
             p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(w.seed + 1))
         prob = oracle.Problem(p)
         t0 = time.time()

@@ -777,19 +777,19 @@ def test_plan_trace_with_per_variant_factors():
 
 
 def test_model_variants_at_full_size_against_stored_checker_results():
-    """Per-variant factors on config 2's chain and config 4's tree, profiled path accuracies on config 2:
-    2^30 plans per demand point, the library's default search (class by class; tabulated feasibility with
-    the walk for feasible plans) against results of the checker's plain per-index search stored by
-    tests/golden/make_golden.py --variants."""
+    """Per-variant factors on config 2's chain and config 4's tree, profiled path accuracies on config 2,
+    both together on config 2: 2^30 plans per demand point, the library's default search (class by class;
+    tabulated feasibility with the walk for feasible plans) against results of the checker's plain
+    per-index search stored by tests/golden/make_golden.py --variants."""
     path = os.path.join(HERE, "golden", "variants.json")
     with open(path) as f:
         doc = json.load(f)
     for name, case in doc["cases"].items():
         w = wl.config(case["config"])
         p = w.pipeline
-        if case["what"] == "variant_factors":
+        if case["what"] in ("variant_factors", "both"):
             p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]
-        else:
+        if case["what"] in ("path_tables", "both"):
             p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(w.seed + 1))
         assert case["workload_digest"] == w.digest(), "stored results are for different inputs"
         P = binding.Problem(p)
