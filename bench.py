@@ -47,7 +47,7 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (430 + 1024) * 1024,
                           ("cfg5_tree4_k4", "per_lane"): (264 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "68e138eb44beb4d39ef6d6d7365fd8d5384e61a987d395de561a37a7adcfa859"
+TRAFFIC_SOURCES_SHA256 = "73378c9838c42e4b89af7e99eb5371836c35b73b780da0af823381ba0df2b8af"
 
 
 def measured_traffic(workload: str, kernel: str):
