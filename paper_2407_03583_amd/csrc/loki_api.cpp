@@ -126,6 +126,7 @@ struct loki_problem {
     // pinned staging of the (demand point, class) descriptors: [Dn 8 int64 | amount int64 | count u32 | point i32] arrays
     unsigned char *class_staging = nullptr;
     bool star = false;  // every other task is a child of the first task
+    bool class_small_space = false;  // the class-by-class search under way reaches fewer than 2^33 plans
     // pinned staging: [DevProblem, path accuracies | Dn (cap_points * 8 int64) | results (cap_points)]
     unsigned char *staging = nullptr;
     int64_t cap_points = 0;
@@ -383,10 +384,13 @@ int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t firs
 // descending number of work items (items[]; 1 each where the roles are not swapped), a batch takes as
 // many as leave each of its points about one block per kClassItemsPerBlock work items, and inside a batch
 // the points of a demand point are kept together (the merge folds stretches of equal demand points).
+// With profiled path accuracies a work item's cost is the walks of its feasible plans, which sit in a few
+// items: one block per work item then, so that as many blocks as possible share them.
 constexpr uint64_t kClassItemsPerBlock = 8;
+uint64_t class_items_per_block(const loki_problem *p) { return p->dev.has_path ? 1 : kClassItemsPerBlock; }
 
 void plan_class_batches(ClassPoints &cp, const std::vector<uint64_t> &items, int32_t batch_limit,
-                        std::vector<int64_t> &batch_first) {
+                        uint64_t items_per_block, std::vector<int64_t> &batch_first) {
     const size_t V = cp.size();
     std::vector<uint32_t> order(V);
     for (size_t v = 0; v < V; v++) order[v] = uint32_t(v);
@@ -394,7 +398,7 @@ void plan_class_batches(ClassPoints &cp, const std::vector<uint64_t> &items, int
     batch_first.clear();
     for (size_t at = 0; at < V;) {
         const uint64_t most = std::max<uint64_t>(1, items[order[at]]);
-        const uint64_t blocks = std::max<uint64_t>(1, (most + kClassItemsPerBlock - 1) / kClassItemsPerBlock);
+        const uint64_t blocks = std::max<uint64_t>(1, (most + items_per_block - 1) / items_per_block);
         const size_t take = size_t(std::min<uint64_t>(uint64_t(batch_limit), std::max<uint64_t>(1, kTargetBlocks / blocks)));
         const size_t end = std::min(V, at + take);
         std::stable_sort(order.begin() + at, order.begin() + end,
@@ -435,7 +439,12 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     const uint32_t target_blocks = p->dev.has_path ? kTargetBlocks / 4 : kTargetBlocks;
     const uint32_t max_bpm = std::max<uint32_t>(1u, (target_blocks + n_points - 1) / n_points);
     const uint32_t CL = p->dev.C[L];
-    const int slots = CL >= 512 ? 8 : 4;
+    // (class by class with profiled path accuracies on a small plan space: the cost is the walks of the
+    // feasible plans, which sit in few of the work items, and the overhead of smaller items is small in
+    // absolute terms; 4 slots per lane and one chunk of the last task per block then, so that more blocks
+    // share the walks)
+    const bool fine_items = p->dev.has_path && A.class_amount != nullptr && A.swap && p->class_small_space;
+    const int slots = (CL >= 512 && !fine_items) ? 8 : 4;
     const uint32_t chunk = 64u * slots;
     const uint64_t strideL = p->dev.stride[L];
     uint64_t F = 1;
@@ -465,7 +474,7 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
         const uint32_t n_chunks = (cl_last - cl_first + 1 + chunk - 1) / chunk;
         A.cl_first = cl_first;
         A.cpb = 1;
-        while (A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
+        while (!fine_items && A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
         A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
         // a range shorter than one step of the last task's choice touches only some of the
         // combinations of the tasks in between, in cyclic order from that of its first index
@@ -489,7 +498,7 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(std::max<uint64_t>(A.items, 1), max_bpm));
     if (A.swap)  // the pairs of a batch are of similar size (plan_class_batches): several work items per block
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(
-            A.blocks_per_m, std::max<uint64_t>(1, (A.items + kClassItemsPerBlock - 1) / kClassItemsPerBlock)));
+            A.blocks_per_m, std::max<uint64_t>(1, (A.items + class_items_per_block(p) - 1) / class_items_per_block(p))));
     if (A.items > (uint64_t(1) << 62) / A.blocks_per_m) A.blocks_per_m = 1;  // keep items*block in 64 bits
     const bool range = !(index_begin == 0 && index_end == p->n_candidates);
     const int np = p->dev.n_paths;
@@ -621,6 +630,16 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
                 p->last_scored += plans;
             }
         }
+        {
+            uint64_t group_plans = 0;
+            for (int64_t v = 0; v < V; v++) {
+                const uint32_t *cnt = cp.count.data() + size_t(v) * kMaxTasks;
+                uint64_t plans = 1;
+                for (int j = 0; j < p->n; j++) plans = std::min<uint64_t>(plans * cnt[j], uint64_t(1) << 40);
+                group_plans += plans;
+            }
+            p->class_small_space = group_plans < (uint64_t(1) << 33);
+        }
         std::vector<int64_t> batch_first;
         {
             // work items per point with swapped roles (else one batch size fits all)
@@ -628,7 +647,7 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
             std::vector<uint64_t> items(size_t(V), 1);
             if (swap)
                 for (int64_t v = 0; v < V; v++) items[size_t(v)] = far_of(v) * mid_tiles;
-            plan_class_batches(cp, items, class_batch(p->dev.table_total), batch_first);
+            plan_class_batches(cp, items, class_batch(p->dev.table_total), class_items_per_block(p), batch_first);
         }
 
         if (p->staged_pending) {  // earlier copies (a previous call, the previous group) may still read the staging buffers
