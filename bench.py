@@ -47,7 +47,7 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (430 + 1024) * 1024,
                           ("cfg5_tree4_k4", "per_lane"): (264 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "73378c9838c42e4b89af7e99eb5371836c35b73b780da0af823381ba0df2b8af"
+TRAFFIC_SOURCES_SHA256 = "a5a3c1efab88cd75112a391f43c1f6e22363aaa7b0ae4698d8942da97418b2ce"
 
 
 def measured_traffic(workload: str, kernel: str):
