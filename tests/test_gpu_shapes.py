@@ -1,4 +1,5 @@
 """GPU parity on shapes that take the less travelled paths of the tabulated kernel."""
+import os
 import random
 import struct
 from types import SimpleNamespace
@@ -300,3 +301,27 @@ def test_handles_can_be_created_used_and_destroyed_many_times():
     for h in (a, b, c):
         h.close()
         h.close()   # closing twice is harmless
+
+
+def test_bench_prints_one_json_line_with_the_agreed_fields():
+    """bench.py end to end on the smallest configuration, plain and with the optional parts of the model."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for extra, kernel in (([], "tabulated"), (["--variant-factors"], "tabulated_by_class"),
+                          (["--path-tables"], "tabulated_paths"), (["--per-lane"], "per_lane"),
+                          (["--variant-factors", "--path-tables"], "tabulated_by_class_paths")):
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--config", "1", "--steps", "2", "--warmup", "1",
+                            "--no-cpu-baseline", "--no-context"] + extra, capture_output=True, text=True, timeout=300)
+        assert r.returncode == 0, r.stderr[-2000:]
+        lines = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
+        assert len(lines) == 1
+        d = json.loads(lines[0])
+        for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                    "vs_baseline", "dtype", "data", "config", "roofline"):
+            assert key in d, key
+        assert d["n_gpus"] == 1 and d["steps"] == 2 and d["vs_baseline"] is None and d["data"] == "synthetic"
+        assert d["config"]["kernel"] == kernel and d["config"]["workload"].startswith("cfg1_")
+        assert d["value"] > 0 and d["ms_per_step"] > 0
+        assert d["roofline"]["bound"] == "alu" and set(("achieved", "peak", "unit", "frac", "traffic")) <= set(d["roofline"])
