@@ -44,10 +44,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (430 + 1024) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (264 + 1024) * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (426 + 1024) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (270 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "a5a3c1efab88cd75112a391f43c1f6e22363aaa7b0ae4698d8942da97418b2ce"
+TRAFFIC_SOURCES_SHA256 = "7021c383be65e4d8708bf8e0c29263d9116674a73c8937ce7dea5fc0c06bc779"
 
 
 def measured_traffic(workload: str, kernel: str):
@@ -163,7 +163,18 @@ def main() -> int:
     main_ms = sum(k[1] for k in kernel_ms) / len(kernel_ms)
     n_paths = sum(1 for i in range(w.pipeline.n_tasks) if i not in w.pipeline.parent)
     ops = algorithmic_lane_ops(w.pipeline.n_tasks, n_paths, args.per_lane, w.pipeline)
-    no_count = args.path_tables and not args.per_lane   # see the note in the roofline object
+    # profiled path accuracies on a tree with several leaves (task paths of at most 4 tasks): the library forms
+    # one value per leaf and the plans are combined as in the product form, with one add and one max/compare
+    # per plan (the walks, one per tile entry and per lane slot, are not counted)
+    par = w.pipeline.parent
+    depth = [0] * w.pipeline.n_tasks
+    for i in range(1, w.pipeline.n_tasks):
+        depth[i] = depth[par[i]] + 1
+    by_leaf = (args.path_tables and not args.per_lane and w.pipeline.n_tasks >= 3 and n_paths >= 2
+               and max(depth) + 1 <= 4)
+    if by_leaf:
+        ops = 2
+    no_count = args.path_tables and not args.per_lane and not by_leaf   # see the note in the roofline object
     # work the kernels did: every plan of the range, except class by class, where plans whose first-task
     # choice cannot serve the demand are settled per choice on the host and never reach the kernels
     scored = P.last_search_plans_scored()
@@ -186,7 +197,7 @@ def main() -> int:
                    "index_end": end, "evaluations_per_step": evaluations, "plans_scored_by_kernels": scored,
                    "kernel": ("per_lane_paths" if args.path_tables else "per_lane") if args.per_lane
                    else (("tabulated_by_class_paths" if args.path_tables else "tabulated_by_class") if by_class
-                         else ("tabulated_paths" if args.path_tables else "tabulated")),
+                         else ("tabulated_paths" if args.path_tables else "tabulated")) + ("_by_leaf" if by_leaf else ""),
                    "feasible_fraction_point0": first[0].n_feasible / end},
         "kernel_ms": {"task_tables": sum(k[0] for k in kernel_ms) / len(kernel_ms), "search": main_ms,
                       "final_merge": sum(k[2] for k in kernel_ms) / len(kernel_ms)},
@@ -195,6 +206,10 @@ def main() -> int:
                      "traffic": measured_traffic(w.name, "per_lane" if args.per_lane else "tabulated"),
                      "lane_ops_per_candidate": None if no_count else ops},
     }
+    if by_leaf:
+        out["roofline"]["note"] = ("profiled path accuracies leaf by leaf: 2 operations per visited plan (add, "
+                                   "max/compare); the walks over the variant paths, one per tile entry and per "
+                                   "lane slot, are not counted")
     if no_count:
         out["roofline"]["note"] = ("profiled path accuracies: feasibility is taken per run of first-task choices "
                                    "and the walk over the variant paths runs for feasible plans only, so no "

@@ -143,7 +143,9 @@ typedef struct {
                                     order, task paths added in leaf order, one division by their number.
                                     The objective couples the tasks through c(p), feasibility does not: a
                                     search takes feasibility from the per-task tables and walks the variant
-                                    paths for feasible plans only (whole plans per lane with
+                                    paths for feasible plans only; on a tree with two or more leaves (task
+                                    paths of at most 4 tasks) it forms each leaf's sum once for all the plans
+                                    that share the choices along that leaf's path (whole plans per lane with
                                     LOKI_SEARCH_PER_LANE; same results). */
 } loki_pipeline_t;
 

@@ -318,7 +318,10 @@ int walk_classes(ClassWalk &w, int i) {
         }
         return LOKI_OK;
     }
-    if (i > 0) w.Dn[i] = w.amount[p->dev.parent[i]] * int64_t(p->fanout_q4[i]);
+    // (one factor per edge: the demand is the parent's times the edge's factor, and every usable choice of a
+    // task is in its one class, written as amount -1 = "any")
+    const bool per_variant = p->dev.has_vf != 0;
+    if (i > 0) w.Dn[i] = (per_variant ? w.amount[p->dev.parent[i]] : w.Dn[p->dev.parent[i]]) * int64_t(p->fanout_q4[i]);
     if (p->dev.is_leaf[i]) {
         w.amount[i] = -1;
         w.count[i] = p->dev.C[i];
@@ -332,6 +335,7 @@ int walk_classes(ClassWalk &w, int i) {
         for (uint32_t c = 0; c < p->dev.C[i]; c++) {
             int64_t out;
             if (!task_outflow(p, i, c, w.Dn[i], &out)) continue;
+            if (!per_variant) out = -1;
             auto at = std::lower_bound(classes.begin(), classes.end(), out,
                                        [](const std::pair<int64_t, uint32_t> &cls, int64_t v) { return cls.first < v; });
             if (at != classes.end() && at->first == out) at->second++;
@@ -387,7 +391,19 @@ int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t firs
 // With profiled path accuracies a work item's cost is the walks of its feasible plans, which sit in a few
 // items: one block per work item then, so that as many blocks as possible share them.
 constexpr uint64_t kClassItemsPerBlock = 8;
-uint64_t class_items_per_block(const loki_problem *p) { return p->dev.has_path ? 1 : kClassItemsPerBlock; }
+// With profiled path accuracies and swapped roles: whether the objective is taken leaf by leaf (the tile task
+// is a leaf, so every leaf's value depends on the entry, on the lane or on the work item alone; the kernel
+// compiles 4 levels of the walk over the variant paths).
+bool leaf_values_apply(const loki_problem *p) {
+    if (!p->dev.has_path || p->n < 3 || !p->dev.is_leaf[p->dev.tile_task] || p->dev.n_paths < 2) return false;
+    for (int i = 0; i < p->n; i++)
+        if (p->dev.path_len[i] > 4) return false;
+    return true;
+}
+
+uint64_t class_items_per_block(const loki_problem *p) {
+    return (p->dev.has_path && !leaf_values_apply(p)) ? 1 : kClassItemsPerBlock;
+}
 
 void plan_class_batches(ClassPoints &cp, const std::vector<uint64_t> &items, int32_t batch_limit,
                         uint64_t items_per_block, std::vector<int64_t> &batch_first) {
@@ -436,14 +452,16 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     const uint32_t n_points = static_cast<uint32_t>(A.M);
     // (with profiled path accuracies a quarter of the blocks: every block ends with one walk over the
     // variant paths for the few plans left in its queues, which longer blocks spread over more work)
-    const uint32_t target_blocks = p->dev.has_path ? kTargetBlocks / 4 : kTargetBlocks;
+    const bool leaf_values = A.swap && leaf_values_apply(p);
+    const uint32_t target_blocks = (p->dev.has_path && !leaf_values) ? kTargetBlocks / 4 : kTargetBlocks;
     const uint32_t max_bpm = std::max<uint32_t>(1u, (target_blocks + n_points - 1) / n_points);
     const uint32_t CL = p->dev.C[L];
     // (class by class with profiled path accuracies on a small plan space: the cost is the walks of the
     // feasible plans, which sit in few of the work items, and the overhead of smaller items is small in
     // absolute terms; 4 slots per lane and one chunk of the last task per block then, so that more blocks
     // share the walks)
-    const bool fine_items = p->dev.has_path && A.class_amount != nullptr && A.swap && p->class_small_space;
+    const bool fine_items =
+        p->dev.has_path && !leaf_values && A.class_amount != nullptr && A.swap && p->class_small_space;
     const int slots = (CL >= 512 && !fine_items) ? 8 : 4;
     const uint32_t chunk = 64u * slots;
     const uint64_t strideL = p->dev.stride[L];
@@ -506,14 +524,17 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     LOKI_HIP(launch_task_table(A, p->dev.table_total, stream));
     if (n >= 2) LOKI_HIP(launch_root_order(A, stream));
     if (before_search) LOKI_HIP(hipEventRecord(before_search, stream));
-    if (p->dev.has_path) {
+    if (leaf_values) {
+        // profiled path accuracies, the objective leaf by leaf: the plans cost what they cost in the product form
+        LOKI_HIP(launch_combine(A, slots, true, divide, range, true, stream));
+    } else if (p->dev.has_path) {
         // profiled path accuracies (one factor per edge): the same walk over the plan space for feasibility,
         // the objective from the walk over the variant paths for feasible plans only
         int path_levels = 0;
         for (int i = 0; i < n; i++) path_levels = std::max(path_levels, p->dev.path_len[i]);
         LOKI_HIP(launch_path_combine(A, slots, range, path_levels, stream));
     } else {
-        LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, stream));
+        LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, false, stream));
     }
     if (after_search) LOKI_HIP(hipEventRecord(after_search, stream));
     LOKI_HIP(launch_final_reduce(A, stream));
@@ -525,7 +546,10 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
 // 1 with the first task's choices in the tiles (every other task a child of the first one, its choices
 // orderable into runs), 0 not at all.
 int class_search_mode(const loki_problem *p, uint64_t index_begin, uint64_t index_end) {
-    if (!p->dev.has_vf || p->n < 2 || p->dev.table_total > (1u << 16)) return 0;
+    // (without per-variant factors only for the sake of profiled path accuracies taken leaf by leaf: every
+    // demand point is then a single point, the roles swapped)
+    const bool per_variant = p->dev.has_vf != 0;
+    if (!(per_variant || leaf_values_apply(p)) || p->n < 2 || p->dev.table_total > (1u << 16)) return 0;
     const int t = p->dev.tile_task;
     (void)index_begin;
     (void)index_end;
@@ -533,7 +557,7 @@ int class_search_mode(const loki_problem *p, uint64_t index_begin, uint64_t inde
         uint64_t(p->dev.sum_r_t + 1) * uint64_t(p->dev.n_lat_t) + 1 <= 4096 &&
         p->dev.stride[t] <= (uint64_t(1) << 32) / p->dev.C[t])
         return 2;
-    if (p->star && uint64_t(p->dev.sum_r0 + 1) * uint64_t(p->dev.n_lat0) + 1 <= 4096) return 1;
+    if (per_variant && p->star && uint64_t(p->dev.sum_r0 + 1) * uint64_t(p->dev.n_lat0) + 1 <= 4096) return 1;
     return 0;
 }
 

@@ -365,6 +365,42 @@ __device__ __noinline__ double path_objective(const DevProblem *P, const double 
     return total / static_cast<double>(P->n_paths);
 }
 
+// The part of that objective that belongs to one leaf: the sum over the variant paths of the task path
+// root..leaf, in the order of path_objective.  Only the choices of the tasks on that path are read (and, of
+// Dn, the path's tasks, or only Dn[0] with per-variant factors), so a search may form the value once for all
+// the plans that share those choices.
+template <int MAXD>
+__device__ __noinline__ double leaf_paths_sum(const DevProblem *P, const double *path_acc, int leaf,
+                                              const uint32_t (&c)[kMaxTasks], const int64_t *Dn) {
+    PathWalk X;
+    X.P = P;
+    const int n = P->n_tasks;
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        X.c[i] = c[i];
+        X.dn[i] = i < n ? Dn[i] : 0;
+    }
+    if (P->has_vf) {
+        // every task's demand follows from what its parent's part of the plan creates (eq. (1))
+        int64_t created = 0;
+        const int len = P->path_len[leaf];
+        for (int s = 0; s < len; s++) {
+            const int i = P->leaf_path[leaf][s];
+            const int64_t dn = s == 0 ? Dn[0] : created * static_cast<int64_t>(P->fanout[i]);
+            TaskOut o;
+            eval_task_any(P, i, pick32(c, i), dn, o);
+            created = o.outflow;
+#pragma unroll
+            for (int q = 0; q < kMaxTasks; q++) X.dn[q] = q == i ? dn : X.dn[q];
+        }
+    }
+    X.leaf = leaf;
+    X.tab = path_acc + P->path_off[leaf];
+    X.sum = 0.0;
+    path_level<0, MAXD>(X, 0, X.dn[0], 0.0, 0u, 1u);
+    return X.sum;
+}
+
 // ---- ordering and reductions -----------------------------------------------------------------------
 // Strict total order on found plans: accuracy desc, workers asc (unless tie_index_only), index asc.
 // A record with acc < 0 means "nothing found" and loses to everything.
@@ -600,9 +636,20 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // its choices.  What an entry needs besides its own record is the same for the whole tile: the
 // products and latency sums along the chains of the tile's and the last task's ancestors, and the path
 // values of the other leaves.
-template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE, bool SWAP>
-__global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(5))) combine_kernel(SearchArgs A) {
-    constexpr uint32_t kHeadBytes = offsetof(DevProblem, lat);
+//
+// PATHD > 0 (with SWAP, a leaf in the tiles, profiled path accuracies): the objective is the sum, in leaf
+// order, of one value per leaf, and a leaf's value (leaf_paths_sum, PATHD levels compiled) depends on the
+// choices along its own task path only.  The tile task's value is formed per entry when the tile is built,
+// the other leaves' values of the work item once per item, and the last task's value per lane and slot
+// whenever the choices of its ancestors change (they are the slowest digits of the work item); `a` holds
+// that value, the entries carry `pre` = 1, and the loop over the plans is the one of the product form.
+template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE, bool SWAP, int PATHD = 0>
+// (4 wavefronts per SIMD then: the walk's registers spill, the loop over the plans does not; measured against
+// 2, 3 and 5)
+__global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(PATHD > 0 ? 4 : 5)))
+combine_kernel(SearchArgs A) {
+    static_assert(PATHD == 0 || (SWAP && HAS_PRESUM), "path values per leaf need swapped roles and two leaves");
+    constexpr uint32_t kHeadBytes = PATHD > 0 ? sizeof(DevProblem) : offsetof(DevProblem, lat);
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
     __shared__ MidVal sVal[kMidTile + 2];  // two spare entries: the record fetch runs ahead of the run's end
     __shared__ MidLim sLim[kMidTile];
@@ -650,6 +697,10 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             far_swap *= cntj[j];
         }
     }
+    // SWAP: the last task's ancestors are the slowest digits of the work item
+    uint32_t anc_last = 0;
+    if (SWAP)
+        for (int i = uni(sP->parent[L]); i >= 0; i = uni(sP->parent[i])) anc_last |= 1u << i;
     const bool tie_index_only = A.tie_index_only != 0;
     const double npd = static_cast<double>(uni(sP->n_paths));
     const int32_t W = A.W;
@@ -679,6 +730,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
     uint32_t cur_group = ~0u;
     uint32_t cbase = 0;  // first choice of the last task in this wavefront's chunk
     uint32_t cl0 = 0;    // this lane's choice in slot 0
+    uint64_t last_for = ~0ull;  // PATHD: the choices of the last task's ancestors that `a` was formed for
 
     // Position of the first item in (tile r, digits of the tasks in between, chunk group g);
     // later items advance it like an odometer, so no division sits in the item loop.
@@ -696,12 +748,16 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
             g = uni(static_cast<uint32_t>(t / far_m));
             f = 0;
 #pragma unroll
-            for (int j = 0; j < kMaxTasks; j++) {
-                cj[j] = 0;
-                if (j < L && j != T) {
-                    const uint32_t d = static_cast<uint32_t>(rest % cntj[j]);
-                    rest /= cntj[j];
-                    cj[j] = uni(perm_m[uni(sP->table_off[j]) + d]);
+            for (int j = 0; j < kMaxTasks; j++) cj[j] = 0;
+#pragma unroll
+            for (int pass = 0; pass < 2; pass++) {
+#pragma unroll
+                for (int j = 0; j < kMaxTasks; j++) {
+                    if (j < L && j != T && ((anc_last >> j) & 1u) == static_cast<uint32_t>(pass)) {
+                        const uint32_t d = static_cast<uint32_t>(rest % cntj[j]);
+                        rest /= cntj[j];
+                        cj[j] = uni(perm_m[uni(sP->table_off[j]) + d]);
+                    }
                 }
             }
             return;
@@ -739,6 +795,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     lat[s] = kNever;
                 }
             }
+            last_for = ~0ull;
             minw = kNever;
             cmin = ~0u;
             cfirst = ~0u;
@@ -783,7 +840,7 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                     flp[j] = (j == 0 ? 0 : pick_below(flp, par, j)) + rlat;   // here with the first task included
                     if (uni(sP->is_leaf[j])) {
                         ok_far = ok_far && A.budget[j] >= 0 && flp[j] <= A.budget[j];
-                        if (threadIdx.x == 0) sFac[j] = pp[j];   // the leaf's path value (published below)
+                        if (PATHD == 0 && threadIdx.x == 0) sFac[j] = pp[j];   // the leaf's path value (published below)
                     }
                 }
             }
@@ -798,6 +855,35 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                 // the tile task is the last task's parent: its accuracy and latency enter the last task's
                 // path per entry, and it closes no path of its own
                 tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parT, kMaxTasks);
+            }
+            if constexpr (PATHD > 0) {
+                if (ok_far) {
+                    const int64_t *Dn = A.Dn + static_cast<size_t>(m) * kMaxTasks;
+                    // the other leaves of the work item, one thread each (published with the factors below)
+                    for (int j = 0; j < L; j++)
+                        if (j != T && uni(sP->is_leaf[j]) && threadIdx.x == static_cast<uint32_t>(j))
+                            sFac[j] = leaf_paths_sum<PATHD>(sP, A.path_acc, j, cj, Dn);
+                    // the last task's value of every lane and slot, when its ancestors' choices have changed
+                    uint64_t now_for = 0;
+#pragma unroll
+                    for (int j = 0; j < kMaxTasks; j++)
+                        if ((anc_last >> j) & 1u) now_for += cj[j] * uni64(sP->stride[j]);
+                    if (now_for != last_for) {
+                        last_for = now_for;
+                        uint32_t cw[kMaxTasks];
+#pragma unroll
+                        for (int j = 0; j < kMaxTasks; j++) cw[j] = cj[j];
+#pragma unroll
+                        for (int s = 0; s < S; s++) {
+                            a[s] = 0.0;
+                            if (lat[s] != kNever) {
+#pragma unroll
+                                for (int j = 0; j < kMaxTasks; j++) cw[j] = j == L ? cl0 + s * 64 : cw[j];
+                                a[s] = leaf_paths_sum<PATHD>(sP, A.path_acc, L, cw, Dn);
+                            }
+                        }
+                    }
+                }
             }
         } else {
 #pragma unroll
@@ -886,6 +972,18 @@ __global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per
                 for (int k = 0; k < kSide; k++) {
                     presum[k] = tile_leaf ? a_first * a0s[k] : 0.0;
                     pre[k] = tile_leaf ? a_last : a_first * a0s[k];
+                    if constexpr (PATHD > 0) {
+                        // the entry's own value, for entries some plan can use
+                        presum[k] = 0.0;
+                        pre[k] = 1.0;
+                        if (oks[k] && w_room >= static_cast<int64_t>(w0s[k]) && e_first + k * kBlockThreads < cnt) {
+                            uint32_t cw[kMaxTasks];
+#pragma unroll
+                            for (int j = 0; j < kMaxTasks; j++) cw[j] = j == T ? cMs[k] : cj[j];
+                            presum[k] = leaf_paths_sum<PATHD>(sP, A.path_acc, T, cw,
+                                                              A.Dn + static_cast<size_t>(m) * kMaxTasks);
+                        }
+                    }
                 }
                 for (int j = 0; j < L; j++) {
                     if (j == T || !uni(sP->is_leaf[j])) continue;
@@ -1841,8 +1939,22 @@ __global__ void __launch_bounds__(kBlockThreads) class_merge_kernel(MergeArgs A)
 }
 
 template <int S>
-hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, hipStream_t stream) {
+hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, bool leaf_values,
+                            hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
+    if (leaf_values) {
+        // profiled path accuracies, one value per leaf (the caller has checked: swapped roles, a leaf in the
+        // tiles, task paths of at most 4 tasks)
+        if (!A.swap || !has_presum) return hipErrorInvalidValue;
+#define LOKI_LAUNCH_PATHS(D, R) hipLaunchKernelGGL((combine_kernel<S, true, D, R, true, 4>), grid, block, 0, stream, A);
+        if (divide) {
+            if (range) { LOKI_LAUNCH_PATHS(true, true) } else { LOKI_LAUNCH_PATHS(true, false) }
+        } else {
+            if (range) { LOKI_LAUNCH_PATHS(false, true) } else { LOKI_LAUNCH_PATHS(false, false) }
+        }
+#undef LOKI_LAUNCH_PATHS
+        return hipGetLastError();
+    }
     if (A.swap) {
 #define LOKI_LAUNCH_SWAP(P, D)                                                                                   \
     if (range) hipLaunchKernelGGL((combine_kernel<S, P, D, true, true>), grid, block, 0, stream, A);             \
@@ -1882,9 +1994,9 @@ hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream) {
 }
 
 hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool divide, bool range,
-                          hipStream_t stream) {
-    if (slots == 8) return launch_combine_s<8>(A, has_presum, divide, range, stream);
-    return launch_combine_s<4>(A, has_presum, divide, range, stream);
+                          bool leaf_values, hipStream_t stream) {
+    if (slots == 8) return launch_combine_s<8>(A, has_presum, divide, range, leaf_values, stream);
+    return launch_combine_s<4>(A, has_presum, divide, range, leaf_values, stream);
 }
 
 template <int MAXD>

@@ -10,8 +10,10 @@ namespace loki {
 
 hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStream_t stream);
 hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream);
+// leaf_values: profiled path accuracies with one value per leaf (needs A.swap, a leaf in the tiles, two or
+// more leaves and task paths of at most 4 tasks; see leaf_values_apply in loki_api.cpp)
 hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool divide, bool range,
-                          hipStream_t stream);
+                          bool leaf_values, hipStream_t stream);
 // path_levels: 0, or with profiled path accuracies the number of tasks on the longest root-to-leaf chain
 // (selects how many levels of the walk over the variant paths are compiled in)
 hipError_t launch_path_combine(const SearchArgs &A, int slots, bool range, int path_levels, hipStream_t stream);

@@ -46,6 +46,8 @@ VARIANT_CASES = [  # name, config, what to add, demand points (milli-QPS; None: 
     ("cfg4_variant_factors", 4, "variant_factors", [150_000, 600_000]),
     ("cfg2_path_tables", 2, "path_tables", None),
     ("cfg2_factors_and_path_tables", 2, "both", [150_000, 400_000]),
+    ("cfg4_path_tables", 4, "path_tables", [150_000, 600_000]),
+    ("cfg4_factors_and_path_tables", 4, "both", [600_000]),
 ]
 
 

@@ -162,14 +162,15 @@ def test_bench_refuses_more_than_one_gpu_and_counts_operations():
     assert abs(bench.VALU_PEAK_TLANEOPS - 39.3216) < 1e-9
     # the HBM traffic figure is reported only for the sources it was measured with
     t = bench.measured_traffic("cfg5_tree4_k4", "tabulated")
-    assert t is None or t == (430 + 1024) * 1024
+    assert t is None or t == (426 + 1024) * 1024
     assert bench.measured_traffic("cfg1_chain2_k3", "tabulated") is None
 
 
 def test_workspace_covers_the_searches_a_handle_may_run():
     """The size a caller must provide grows with what the handle's searches keep on the device: with
     per-variant factors the descriptors of up to 65,535 (demand point, classes) points and a batch of per-point
-    task tables; with profiled path accuracies the table itself.  Chains, stars and deeper trees alike."""
+    task tables; with profiled path accuracies the table itself, and on trees with two or more leaves the same
+    descriptors and batch.  Chains, stars and deeper trees alike."""
     import copy
     for cfg in (2, 4, 5):
         w = wl.config(cfg)
@@ -182,4 +183,7 @@ def test_workspace_covers_the_searches_a_handle_may_run():
         q = copy.deepcopy(w.pipeline)
         q.path_acc_ppm = wl.draw_path_tables(q, wl.SplitMix64(1))
         with_tables = binding.Problem(q).workspace_bytes(4)
-        assert plain < with_tables <= plain + 8 * len(q.path_acc_ppm) + 256
+        if cfg == 2:   # a chain: the plan space is walked as without tables
+            assert plain < with_tables <= plain + 8 * len(q.path_acc_ppm) + 256
+        else:          # two leaves: searched point by point like per-variant factors (one point per demand point)
+            assert with_factors <= with_tables <= with_factors + 8 * len(q.path_acc_ppm) + 256

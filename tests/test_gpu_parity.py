@@ -777,10 +777,11 @@ def test_plan_trace_with_per_variant_factors():
 
 
 def test_model_variants_at_full_size_against_stored_checker_results():
-    """Per-variant factors on config 2's chain and config 4's tree, profiled path accuracies on config 2,
-    both together on config 2: 2^30 plans per demand point, the library's default search (class by class;
-    tabulated feasibility with the walk for feasible plans) against results of the checker's plain
-    per-index search stored by tests/golden/make_golden.py --variants."""
+    """Per-variant factors on config 2's chain and config 4's tree, profiled path accuracies on both,
+    both together on both: 2^30 plans per demand point, the library's default search (class by class;
+    on the chain tabulated feasibility with the walk for feasible plans, on the tree the objective leaf
+    by leaf) against results of the checker's plain per-index search stored by
+    tests/golden/make_golden.py --variants."""
     path = os.path.join(HERE, "golden", "variants.json")
     with open(path) as f:
         doc = json.load(f)

@@ -198,3 +198,63 @@ def test_config_sizes_with_path_tables_tabulated_against_per_lane():
     assert r.status == 0 and r.n_feasible == doc["results"][0]["n_feasible"] == 108
     e = O5.eval(r.index, w5.demand_mqps[0], w5.workers, w5.slo_us)
     assert e.infeasible == 0 and bits(e.accuracy) == bits(r.accuracy) and e.workers == r.workers_used
+
+
+TREES_WITH_SEVERAL_LEAVES = [
+    ([-1, 0, 0], "star, two leaves"),
+    ([-1, 0, 0, 0], "star, three leaves: the path count is no power of two, one leaf belongs to the work item"),
+    ([-1, 0, 1, 0], "paths of three and two tasks"),
+    ([-1, 0, 1, 1], "both leaves under task 1: the last task has two ancestors"),
+    ([-1, 0, 0, 1, 2], "two chains of three tasks"),
+    ([-1, 0, 1, 2, 3, 0], "a path of five tasks, longer than the leaf-by-leaf kernel walks"),
+]
+
+
+# (with per-variant factors the fixed-point range check leaves no demand worth testing at five levels)
+@pytest.mark.parametrize("parent,what,variant_factors",
+                         [(t, w, vf) for t, w in TREES_WITH_SEVERAL_LEAVES for vf in (False, True)
+                          if not (vf and len(t) == 6)])
+def test_trees_with_several_leaves_leaf_by_leaf(parent, what, variant_factors):
+    """With two or more leaves the objective is a sum of one value per leaf, each a function of the choices
+    along that leaf's task path (Section 4.1 "Accuracy": the system accuracy averages over the task paths);
+    the search forms each value once for all the plans that share those choices.  Whole space, both tie
+    rules, several demand points, and index ranges, against the checker's plan-by-plan search."""
+    n = len(parent)
+    rng = wl.SplitMix64(900 + 7 * n + sum(parent))
+    p = wl.make_pipeline(parent, 2, 2 if n <= 5 else 1, (1, 4), rng)
+    p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(901 + n))
+    if variant_factors:
+        p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]
+    P, O = binding.Problem(p), oracle.Problem(p)
+    N = P.num_candidates()
+    assert N <= 2_000_000
+    workers, slo = 3 * n, 500_000
+    demands = {3: [15_000, 40_000, 90_000, 200_000], 4: [15_000, 40_000, 90_000, 200_000],
+               5: [1_000, 4_000, 10_000, 25_000], 6: [500, 1_000, 2_000, 4_000]}[n]
+    found = 0
+    for flags in (0, TIE):
+        out = P.alloc_search(demands, workers, slo, flags=flags)
+        for d, res in zip(demands, out):
+            ref = O.search(d, workers, slo, tie_index_only=bool(flags))
+            assert agree(res, ref), (what, d, flags, res.as_tuple(), ref.as_tuple())
+            found += ref.found
+    assert found >= 4, what
+    # which way the search went shows in the number of plans its kernels visited: leaf by leaf the work
+    # items hold only usable choices of the tasks with children; the walk over the whole space visits all
+    if not variant_factors:
+        if n <= 5:
+            assert 0 < P.last_search_plans_scored() < N * len(demands), what
+        else:
+            assert P.last_search_plans_scored() == N * len(demands), what
+    d = demands[1]
+    cuts = [0, N // 7, N // 2 + 3, N - N // 5, N]
+    total = 0
+    for a, b in zip(cuts, cuts[1:]):
+        res = P.alloc_search([d], workers, slo, begin=a, end=b)[0]
+        assert agree(res, O.search(d, workers, slo, begin=a, end=b)), (what, a, b)
+        total += res.n_feasible
+    assert total == P.alloc_search([d], workers, slo)[0].n_feasible > 0
+    # a tight worker budget and a tight latency limit
+    for w_, s_ in ((n + 2, slo), (workers, 160_000 if n <= 5 else 260_000)):
+        res = P.alloc_search([d], w_, s_)[0]
+        assert agree(res, O.search(d, w_, s_)), (what, w_, s_)
