@@ -258,3 +258,7 @@ def test_trees_with_several_leaves_leaf_by_leaf(parent, what, variant_factors):
     for w_, s_ in ((n + 2, slo), (workers, 160_000 if n <= 5 else 260_000)):
         res = P.alloc_search([d], w_, s_)[0]
         assert agree(res, O.search(d, w_, s_)), (what, w_, s_)
+    # no demand at all: no variant has traffic, every hop hands on to the first hosted variant
+    res = P.alloc_search([0, 1], workers, slo)
+    for d0, r in zip([0, 1], res):
+        assert agree(r, O.search(d0, workers, slo)), (what, "demand", d0)
