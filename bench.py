@@ -44,10 +44,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (426 + 1024) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (270 + 1024) * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (430 + 1024) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (266 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "7021c383be65e4d8708bf8e0c29263d9116674a73c8937ce7dea5fc0c06bc779"
+TRAFFIC_SOURCES_SHA256 = "4a9a4ec9623a7e5e105fbea5915e848a6a645efe8455e996480b88fc287f53cf"
 
 
 def measured_traffic(workload: str, kernel: str):
@@ -163,15 +163,16 @@ def main() -> int:
     main_ms = sum(k[1] for k in kernel_ms) / len(kernel_ms)
     n_paths = sum(1 for i in range(w.pipeline.n_tasks) if i not in w.pipeline.parent)
     ops = algorithmic_lane_ops(w.pipeline.n_tasks, n_paths, args.per_lane, w.pipeline)
-    # profiled path accuracies on a tree with several leaves (task paths of at most 4 tasks): the library forms
-    # one value per leaf and the plans are combined as in the product form, with one add and one max/compare
-    # per plan (the walks, one per tile entry and per lane slot, are not counted)
+    # profiled path accuracies on a tree with several leaves (at most 64 variant combinations above every
+    # leaf): the library forms one value per leaf and the plans are combined as in the product form, with one
+    # add and one max/compare per plan (the sums over the variant paths, one per tile entry and per lane slot,
+    # are not counted)
     par = w.pipeline.parent
-    depth = [0] * w.pipeline.n_tasks
+    above = [1] * w.pipeline.n_tasks   # variant combinations of the tasks above task i
     for i in range(1, w.pipeline.n_tasks):
-        depth[i] = depth[par[i]] + 1
+        above[i] = above[par[i]] * w.pipeline.n_variants[par[i]]
     by_leaf = (args.path_tables and not args.per_lane and w.pipeline.n_tasks >= 3 and n_paths >= 2
-               and max(depth) + 1 <= 4)
+               and max(above[i] for i in range(w.pipeline.n_tasks) if i not in par) <= 64)
     if by_leaf:
         ops = 2
     no_count = args.path_tables and not args.per_lane and not by_leaf   # see the note in the roofline object
@@ -208,7 +209,7 @@ def main() -> int:
     }
     if by_leaf:
         out["roofline"]["note"] = ("profiled path accuracies leaf by leaf: 2 operations per visited plan (add, "
-                                   "max/compare); the walks over the variant paths, one per tile entry and per "
+                                   "max/compare); the sums over the variant paths, one per tile entry and per "
                                    "lane slot, are not counted")
     if no_count:
         out["roofline"]["note"] = ("profiled path accuracies: feasibility is taken per run of first-task choices "

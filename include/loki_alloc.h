@@ -143,10 +143,10 @@ typedef struct {
                                     order, task paths added in leaf order, one division by their number.
                                     The objective couples the tasks through c(p), feasibility does not: a
                                     search takes feasibility from the per-task tables and walks the variant
-                                    paths for feasible plans only; on a tree with two or more leaves (task
-                                    paths of at most 4 tasks) it forms each leaf's sum once for all the plans
-                                    that share the choices along that leaf's path (whole plans per lane with
-                                    LOKI_SEARCH_PER_LANE; same results). */
+                                    paths for feasible plans only; on a tree with two or more leaves (at most
+                                    64 variant combinations above every leaf) it forms each leaf's sum once
+                                    for all the plans that share the choices along that leaf's path (whole
+                                    plans per lane with LOKI_SEARCH_PER_LANE; same results). */
 } loki_pipeline_t;
 
 typedef struct loki_problem loki_problem_t; /* opaque handle */

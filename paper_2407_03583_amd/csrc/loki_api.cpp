@@ -393,11 +393,15 @@ int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t firs
 constexpr uint64_t kClassItemsPerBlock = 8;
 // With profiled path accuracies and swapped roles: whether the objective is taken leaf by leaf (the tile task
 // is a leaf, so every leaf's value depends on the entry, on the lane or on the work item alone; the kernel
-// compiles 4 levels of the walk over the variant paths).
+// keeps at most kMaxPrefix branches of the walk over the variant paths above a leaf).
 bool leaf_values_apply(const loki_problem *p) {
     if (!p->dev.has_path || p->n < 3 || !p->dev.is_leaf[p->dev.tile_task] || p->dev.n_paths < 2) return false;
-    for (int i = 0; i < p->n; i++)
-        if (p->dev.path_len[i] > 4) return false;
+    for (int i = 0; i < p->n; i++) {
+        if (!p->dev.is_leaf[i]) continue;
+        uint64_t branches = 1;
+        for (int j = p->dev.parent[i]; j >= 0; j = p->dev.parent[j]) branches *= uint64_t(p->dev.K[j]);
+        if (branches > uint64_t(kMaxPrefix)) return false;
+    }
     return true;
 }
 

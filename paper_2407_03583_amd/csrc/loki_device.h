@@ -15,6 +15,9 @@ constexpr int kWavesPerBlock = kBlockThreads / 64;
 constexpr int kMidTile = 512;               // most root-task choices staged in LDS per work item
 constexpr int kStepMul = 0, kStepLeaf = 1, kStepPre = 2;
 constexpr int32_t kNever = 0x7fffffff;      // latency marker: this choice can never be part of a feasible plan
+constexpr int kMaxPrefix = 64;              // profiled path accuracies leaf by leaf: most branches of the walk over the
+                                            // variant paths above a leaf (product of the variant counts of the tasks
+                                            // root..leaf's parent)
 
 // Per-handle constants (Table 1 inputs after validation, plus derived radices).
 struct DevProblem {

@@ -365,40 +365,155 @@ __device__ __noinline__ double path_objective(const DevProblem *P, const double 
     return total / static_cast<double>(P->n_paths);
 }
 
-// The part of that objective that belongs to one leaf: the sum over the variant paths of the task path
-// root..leaf, in the order of path_objective.  Only the choices of the tasks on that path are read (and, of
-// Dn, the path's tasks, or only Dn[0] with per-variant factors), so a search may form the value once for all
-// the plans that share those choices.
-template <int MAXD>
-__device__ __noinline__ double leaf_paths_sum(const DevProblem *P, const double *path_acc, int leaf,
-                                              const uint32_t (&c)[kMaxTasks], const int64_t *Dn) {
-    PathWalk X;
-    X.P = P;
-    const int n = P->n_tasks;
-#pragma unroll
-    for (int i = 0; i < kMaxTasks; i++) {
-        X.c[i] = c[i];
-        X.dn[i] = i < n ? Dn[i] : 0;
+// The part of that objective that belongs to one leaf, the sum over the variant paths of the task path
+// root..leaf, depends on the choices of the tasks on that path only, so a search may form it once for all the
+// plans that share them.  It is taken in two steps.  path_prefixes expands the walk level by level for every
+// task of the path but the leaf: the branches with a nonzero share, in the nested order of path_level (an
+// order-preserving expansion of a list keeps that order), each with what the leaf's level needs of it.
+// leaf_level_sum then adds up the leaf's own level over those branches, for one choice of the leaf.
+struct PathPrefix {
+    int64_t lo, len;   // the interval of the leaf's request stream that holds this branch's requests
+    double mass;       // c(p) up to here
+    uint32_t entry;    // position in the leaf's table so far
+    uint32_t pad;
+};
+
+struct ChoiceDigits {
+    uint64_t digits;     // replicas, 8 bits per variant
+    uint32_t betas;      // batch position, 4 bits per variant (per-variant batch sizes only)
+    uint32_t beta_task;  // the task's batch position otherwise
+};
+
+__device__ __forceinline__ ChoiceDigits choice_digits(const DevProblem *P, int i, uint32_t c) {
+    const int K = P->K[i];
+    const bool pv = P->pv_batch != 0;
+    const uint32_t nb = static_cast<uint32_t>(P->nb[i]);
+    ChoiceDigits d;
+    d.digits = 0;
+    d.betas = 0;
+    for (int k = 0; k < K; k++) {
+        const uint32_t radix = P->radix[i][k];
+        const uint32_t q = c / radix;
+        const uint32_t g = c - q * radix;
+        c = q;
+        uint32_t x = g;
+        if (pv) {
+            x = g == 0 ? 0u : (g - 1) / nb + 1;
+            d.betas |= (g == 0 ? 0u : (g - 1) % nb) << (4 * k);
+        }
+        d.digits |= static_cast<uint64_t>(x) << (8 * k);
     }
-    if (P->has_vf) {
-        // every task's demand follows from what its parent's part of the plan creates (eq. (1))
+    d.beta_task = c;
+    return d;
+}
+
+// One thread.  c: the plan's choices (only those of the path's tasks above the leaf are read); Dn: the
+// demands of the point (only Dn[0] with per-variant factors, where a task's demand is what its parent's part
+// of the plan creates, eq. (1)).  tmp, out: kMaxPrefix entries each; the branches end up in out.  Returns their
+// number; dn_leaf: the leaf's demand, stride_leaf: the table stride of the leaf's variant.
+__device__ __noinline__ int path_prefixes(const DevProblem *P, int leaf, const uint32_t (&c)[kMaxTasks], const int64_t *Dn,
+                                          PathPrefix *tmp, PathPrefix *out, int64_t &dn_leaf, uint32_t &stride_leaf) {
+    const bool pv = P->pv_batch != 0, has_vf = P->has_vf != 0;
+    const int levels = P->path_len[leaf] - 1;   // at least one: the leaf is not the root
+    int n = 1;
+    int64_t dn = Dn[0];
+    uint32_t stride = 1;
+    PathPrefix *from = nullptr;
+    for (int J = 0; J < levels; J++) {
+        const int i = P->leaf_path[leaf][J], next = P->leaf_path[leaf][J + 1];
+        const int K = P->K[i];
+        const int64_t fan = static_cast<int64_t>(P->fanout[next]);
+        const ChoiceDigits d = choice_digits(P, i, pick32(c, i));
+        PathPrefix *to = ((levels - 1 - J) & 1) ? tmp : out;
+        int m = 0;
         int64_t created = 0;
-        const int len = P->path_len[leaf];
-        for (int s = 0; s < len; s++) {
-            const int i = P->leaf_path[leaf][s];
-            const int64_t dn = s == 0 ? Dn[0] : created * static_cast<int64_t>(P->fanout[i]);
-            TaskOut o;
-            eval_task_any(P, i, pick32(c, i), dn, o);
-            created = o.outflow;
-#pragma unroll
-            for (int q = 0; q < kMaxTasks; q++) X.dn[q] = q == i ? dn : X.dn[q];
+        for (int q = 0; q < n; q++) {
+            PathPrefix up;   // the whole stream at the root
+            up.lo = 0;
+            up.len = dn;
+            up.mass = 0.0;
+            up.entry = 0;
+            if (J > 0) up = from[q];
+            int64_t at = 0, made = 0;
+            bool any = false;
+            for (int r = 0; r < K; r++) {
+                const int k = P->order[i][r];
+                const int64_t x = static_cast<int64_t>((d.digits >> (8 * k)) & 0xff);
+                if (x == 0) continue;
+                const uint32_t beta = pv ? (d.betas >> (4 * k)) & 0xf : d.beta_task;
+                const int64_t cap = x * P->thr_s[i][k][beta];
+                const int64_t room = dn - at;
+                const int64_t routed = room < cap ? room : cap;
+                double share;
+                if (up.len > 0) {
+                    const int64_t hi_a = at + routed, hi_b = up.lo + up.len;
+                    const int64_t ov = (hi_a < hi_b ? hi_a : hi_b) - (at > up.lo ? at : up.lo);
+                    share = ov > 0 ? static_cast<double>(ov) / static_cast<double>(up.len) : 0.0;
+                } else {
+                    share = any ? 0.0 : 1.0;
+                }
+                any = true;
+                const int64_t sent = has_vf ? routed * static_cast<int64_t>(P->vf[i][k]) : routed;
+                if (share != 0.0 && m < kMaxPrefix) {
+                    PathPrefix b;
+                    b.lo = made * fan;
+                    b.len = sent * fan;
+                    b.mass = J == 0 ? share : up.mass * share;
+                    b.entry = up.entry + static_cast<uint32_t>(k) * stride;
+                    b.pad = 0;
+                    to[m++] = b;
+                }
+                at += routed;
+                made += sent;
+            }
+            created = made;
+        }
+        dn = has_vf ? created * fan : Dn[next];
+        stride *= static_cast<uint32_t>(K);
+        from = to;
+        n = m;
+    }
+    dn_leaf = dn;
+    stride_leaf = stride;
+    return n;
+}
+
+// tab: the leaf's table; i, c: the leaf and its choice; dn: its demand; recs[0..n): the branches above it.
+__device__ __noinline__ double leaf_level_sum(const DevProblem *P, const double *tab, int i, uint32_t c, int64_t dn,
+                                              const PathPrefix *recs, int n, uint32_t stride) {
+    const bool pv = P->pv_batch != 0;
+    const int K = P->K[i];
+    const ChoiceDigits d = choice_digits(P, i, c);
+    double sum = 0.0;
+    for (int q = 0; q < n; q++) {
+        const PathPrefix up = recs[q];
+        int64_t at = 0;
+        bool any = false;
+        for (int r = 0; r < K; r++) {
+            const int k = P->order[i][r];
+            const int64_t x = static_cast<int64_t>((d.digits >> (8 * k)) & 0xff);
+            if (x == 0) continue;
+            const uint32_t beta = pv ? (d.betas >> (4 * k)) & 0xf : d.beta_task;
+            const int64_t cap = x * P->thr_s[i][k][beta];
+            const int64_t room = dn - at;
+            const int64_t routed = room < cap ? room : cap;
+            double share;
+            if (up.len > 0) {
+                const int64_t hi_a = at + routed, hi_b = up.lo + up.len;
+                const int64_t ov = (hi_a < hi_b ? hi_a : hi_b) - (at > up.lo ? at : up.lo);
+                share = ov > 0 ? static_cast<double>(ov) / static_cast<double>(up.len) : 0.0;
+            } else {
+                share = any ? 0.0 : 1.0;
+            }
+            any = true;
+            if (share != 0.0) {
+                const double m = up.mass * share;
+                sum = sum + m * tab[up.entry + static_cast<uint32_t>(k) * stride];
+            }
+            at += routed;
         }
     }
-    X.leaf = leaf;
-    X.tab = path_acc + P->path_off[leaf];
-    X.sum = 0.0;
-    path_level<0, MAXD>(X, 0, X.dn[0], 0.0, 0u, 1u);
-    return X.sum;
+    return sum;
 }
 
 // ---- ordering and reductions -----------------------------------------------------------------------
@@ -637,19 +752,24 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // products and latency sums along the chains of the tile's and the last task's ancestors, and the path
 // values of the other leaves.
 //
-// PATHD > 0 (with SWAP, a leaf in the tiles, profiled path accuracies): the objective is the sum, in leaf
-// order, of one value per leaf, and a leaf's value (leaf_paths_sum, PATHD levels compiled) depends on the
-// choices along its own task path only.  The tile task's value is formed per entry when the tile is built,
-// the other leaves' values of the work item once per item, and the last task's value per lane and slot
-// whenever the choices of its ancestors change (they are the slowest digits of the work item); `a` holds
-// that value, the entries carry `pre` = 1, and the loop over the plans is the one of the product form.
-template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE, bool SWAP, int PATHD = 0>
-// (4 wavefronts per SIMD then: the walk's registers spill, the loop over the plans does not; measured against
-// 2, 3 and 5)
-__global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(PATHD > 0 ? 4 : 5)))
+// BY_LEAF (with SWAP, a leaf in the tiles, profiled path accuracies): the objective is the sum, in leaf
+// order, of one value per leaf, and a leaf's value depends on the choices along its own task path only.
+// Per work item one thread expands the branches above the tile leaf (path_prefixes; also above the last
+// task when the choices of its ancestors have changed: they are the slowest digits of the work item) and
+// forms the values of the item's other leaves; the tile leaf's value is then formed per entry when the tile
+// is built and the last task's per lane and slot (leaf_level_sum).  `a` holds that value, the entries carry
+// `pre` = 1, and the loop over the plans is the one of the product form.
+template <int S, bool HAS_PRESUM, bool DIVIDE, bool RANGE, bool SWAP, bool BY_LEAF = false>
+__global__ void __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(BY_LEAF ? 4 : 5)))
 combine_kernel(SearchArgs A) {
-    static_assert(PATHD == 0 || (SWAP && HAS_PRESUM), "path values per leaf need swapped roles and two leaves");
-    constexpr uint32_t kHeadBytes = PATHD > 0 ? sizeof(DevProblem) : offsetof(DevProblem, lat);
+    static_assert(!BY_LEAF || (SWAP && HAS_PRESUM), "path values per leaf need swapped roles and two leaves");
+    constexpr uint32_t kHeadBytes = BY_LEAF ? sizeof(DevProblem) : offsetof(DevProblem, lat);
+    // BY_LEAF: the branches above the tile leaf and above the last task, their number, the leaf's demand and
+    // table stride ([0] tile leaf, [1] last task)
+    __shared__ PathPrefix sTmp[BY_LEAF ? kMaxPrefix : 1], sAbove[2][BY_LEAF ? kMaxPrefix : 1];
+    __shared__ int sAboveN[2];
+    __shared__ int64_t sLeafDn[2];
+    __shared__ uint32_t sLeafStride[2];
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
     __shared__ MidVal sVal[kMidTile + 2];  // two spare entries: the record fetch runs ahead of the run's end
     __shared__ MidLim sLim[kMidTile];
@@ -730,7 +850,12 @@ combine_kernel(SearchArgs A) {
     uint32_t cur_group = ~0u;
     uint32_t cbase = 0;  // first choice of the last task in this wavefront's chunk
     uint32_t cl0 = 0;    // this lane's choice in slot 0
-    uint64_t last_for = ~0ull;  // PATHD: the choices of the last task's ancestors that `a` was formed for
+    // BY_LEAF: the choices of the last task's ancestors that `a` was formed for, and of the tile leaf's
+    // ancestors that its branches were expanded for
+    uint64_t last_for = ~0ull, tile_for = ~0ull;
+    uint32_t anc_tile = 0;
+    if (BY_LEAF)
+        for (int i = uni(sP->parent[T]); i >= 0; i = uni(sP->parent[i])) anc_tile |= 1u << i;
 
     // Position of the first item in (tile r, digits of the tasks in between, chunk group g);
     // later items advance it like an odometer, so no division sits in the item loop.
@@ -820,6 +945,7 @@ combine_kernel(SearchArgs A) {
         for (int j = 0; j < kMaxTasks; j++) flp[j] = 0;
         int64_t tl_base = A.budget[L];  // latency left for the tile's task and the last task together
         double a_first = 1.0, a_last = 1.0;  // SWAP: products over the ancestors of the tile task and of the last task
+        bool new_last = false;               // BY_LEAF: the last task's ancestors have changed, `a` is to be formed anew
         if (SWAP) {
             // every task of the work item, in topological order: replicas, products and latency sums along
             // the chains from the first task (eq. (12) root first, eq. (7)); a leaf closes its path
@@ -840,7 +966,7 @@ combine_kernel(SearchArgs A) {
                     flp[j] = (j == 0 ? 0 : pick_below(flp, par, j)) + rlat;   // here with the first task included
                     if (uni(sP->is_leaf[j])) {
                         ok_far = ok_far && A.budget[j] >= 0 && flp[j] <= A.budget[j];
-                        if (PATHD == 0 && threadIdx.x == 0) sFac[j] = pp[j];   // the leaf's path value (published below)
+                        if (!BY_LEAF && threadIdx.x == 0) sFac[j] = pp[j];   // the leaf's path value (published below)
                     }
                 }
             }
@@ -856,32 +982,35 @@ combine_kernel(SearchArgs A) {
                 // path per entry, and it closes no path of its own
                 tl_base = tl_base < 0 ? -1 : tl_base - pick_below(flp, parT, kMaxTasks);
             }
-            if constexpr (PATHD > 0) {
+            if constexpr (BY_LEAF) {
+                new_last = false;
                 if (ok_far) {
-                    const int64_t *Dn = A.Dn + static_cast<size_t>(m) * kMaxTasks;
-                    // the other leaves of the work item, one thread each (published with the factors below)
-                    for (int j = 0; j < L; j++)
-                        if (j != T && uni(sP->is_leaf[j]) && threadIdx.x == static_cast<uint32_t>(j))
-                            sFac[j] = leaf_paths_sum<PATHD>(sP, A.path_acc, j, cj, Dn);
-                    // the last task's value of every lane and slot, when its ancestors' choices have changed
-                    uint64_t now_for = 0;
+                    uint64_t now_for = 0, now_tile = 0;
 #pragma unroll
-                    for (int j = 0; j < kMaxTasks; j++)
+                    for (int j = 0; j < kMaxTasks; j++) {
                         if ((anc_last >> j) & 1u) now_for += cj[j] * uni64(sP->stride[j]);
-                    if (now_for != last_for) {
-                        last_for = now_for;
-                        uint32_t cw[kMaxTasks];
-#pragma unroll
-                        for (int j = 0; j < kMaxTasks; j++) cw[j] = cj[j];
-#pragma unroll
-                        for (int s = 0; s < S; s++) {
-                            a[s] = 0.0;
-                            if (lat[s] != kNever) {
-#pragma unroll
-                                for (int j = 0; j < kMaxTasks; j++) cw[j] = j == L ? cl0 + s * 64 : cw[j];
-                                a[s] = leaf_paths_sum<PATHD>(sP, A.path_acc, L, cw, Dn);
-                            }
+                        if ((anc_tile >> j) & 1u) now_tile += cj[j] * uni64(sP->stride[j]);
+                    }
+                    new_last = now_for != last_for;
+                    const bool new_tile = now_tile != tile_for;
+                    last_for = now_for;
+                    tile_for = now_tile;
+                    if (threadIdx.x == 0) {
+                        const int64_t *Dn = A.Dn + static_cast<size_t>(m) * kMaxTasks;
+                        // the other leaves of the work item (their branches pass through the tile leaf's arrays)
+                        bool others = false;
+                        for (int j = 0; j < L; j++) {
+                            if (j == T || !sP->is_leaf[j]) continue;
+                            int64_t dn;
+                            uint32_t st;
+                            const int nb = path_prefixes(sP, j, cj, Dn, sTmp, sAbove[0], dn, st);
+                            sFac[j] = leaf_level_sum(sP, A.path_acc + sP->path_off[j], j, pick32(cj, j), dn, sAbove[0], nb, st);
+                            others = true;
                         }
+                        if (new_tile || others)
+                            sAboveN[0] = path_prefixes(sP, T, cj, Dn, sTmp, sAbove[0], sLeafDn[0], sLeafStride[0]);
+                        if (new_last)
+                            sAboveN[1] = path_prefixes(sP, L, cj, Dn, sTmp, sAbove[1], sLeafDn[1], sLeafStride[1]);
                     }
                 }
             }
@@ -935,6 +1064,19 @@ combine_kernel(SearchArgs A) {
             if (t >= 0) sFac[threadIdx.x] = tab[sP->table_off[t] + pick32(cj, t)].a;
         }
         __syncthreads();  // the previous item's tile is no longer being read; the factors are visible
+        if constexpr (BY_LEAF) {
+            if (new_last) {
+                // the last task's value of every lane and slot
+                const double *tabL_acc = A.path_acc + uni(sP->path_off[L]);
+#pragma unroll
+                for (int s = 0; s < S; s++) {
+                    a[s] = 0.0;
+                    if (lat[s] != kNever)
+                        a[s] = leaf_level_sum(sP, tabL_acc, L, cl0 + s * 64, sLeafDn[1], sAbove[1], sAboveN[1],
+                                              sLeafStride[1]);
+                }
+            }
+        }
         // Every thread builds its entries of the tile two at a time, side by side: the steps are read once
         // per pair and applied to both.
         constexpr int kSide = 2;
@@ -972,17 +1114,13 @@ combine_kernel(SearchArgs A) {
                 for (int k = 0; k < kSide; k++) {
                     presum[k] = tile_leaf ? a_first * a0s[k] : 0.0;
                     pre[k] = tile_leaf ? a_last : a_first * a0s[k];
-                    if constexpr (PATHD > 0) {
+                    if constexpr (BY_LEAF) {
                         // the entry's own value, for entries some plan can use
                         presum[k] = 0.0;
                         pre[k] = 1.0;
-                        if (oks[k] && w_room >= static_cast<int64_t>(w0s[k]) && e_first + k * kBlockThreads < cnt) {
-                            uint32_t cw[kMaxTasks];
-#pragma unroll
-                            for (int j = 0; j < kMaxTasks; j++) cw[j] = j == T ? cMs[k] : cj[j];
-                            presum[k] = leaf_paths_sum<PATHD>(sP, A.path_acc, T, cw,
-                                                              A.Dn + static_cast<size_t>(m) * kMaxTasks);
-                        }
+                        if (oks[k] && w_room >= static_cast<int64_t>(w0s[k]) && e_first + k * kBlockThreads < cnt)
+                            presum[k] = leaf_level_sum(sP, A.path_acc + uni(sP->path_off[T]), T, cMs[k], sLeafDn[0],
+                                                       sAbove[0], sAboveN[0], sLeafStride[0]);
                     }
                 }
                 for (int j = 0; j < L; j++) {
@@ -1944,9 +2082,9 @@ hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, b
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
     if (leaf_values) {
         // profiled path accuracies, one value per leaf (the caller has checked: swapped roles, a leaf in the
-        // tiles, task paths of at most 4 tasks)
+        // tiles, at most kMaxPrefix branches above every leaf)
         if (!A.swap || !has_presum) return hipErrorInvalidValue;
-#define LOKI_LAUNCH_PATHS(D, R) hipLaunchKernelGGL((combine_kernel<S, true, D, R, true, 4>), grid, block, 0, stream, A);
+#define LOKI_LAUNCH_PATHS(D, R) hipLaunchKernelGGL((combine_kernel<S, true, D, R, true, true>), grid, block, 0, stream, A);
         if (divide) {
             if (range) { LOKI_LAUNCH_PATHS(true, true) } else { LOKI_LAUNCH_PATHS(true, false) }
         } else {

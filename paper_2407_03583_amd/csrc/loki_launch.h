@@ -11,7 +11,7 @@ namespace loki {
 hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStream_t stream);
 hipError_t launch_root_order(const SearchArgs &A, hipStream_t stream);
 // leaf_values: profiled path accuracies with one value per leaf (needs A.swap, a leaf in the tiles, two or
-// more leaves and task paths of at most 4 tasks; see leaf_values_apply in loki_api.cpp)
+// more leaves and at most kMaxPrefix branches above every leaf; see leaf_values_apply in loki_api.cpp)
 hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool divide, bool range,
                           bool leaf_values, hipStream_t stream);
 // path_levels: 0, or with profiled path accuracies the number of tasks on the longest root-to-leaf chain

@@ -200,37 +200,41 @@ def test_config_sizes_with_path_tables_tabulated_against_per_lane():
     assert e.infeasible == 0 and bits(e.accuracy) == bits(r.accuracy) and e.workers == r.workers_used
 
 
-TREES_WITH_SEVERAL_LEAVES = [
-    ([-1, 0, 0], "star, two leaves"),
-    ([-1, 0, 0, 0], "star, three leaves: the path count is no power of two, one leaf belongs to the work item"),
-    ([-1, 0, 1, 0], "paths of three and two tasks"),
-    ([-1, 0, 1, 1], "both leaves under task 1: the last task has two ancestors"),
-    ([-1, 0, 0, 1, 2], "two chains of three tasks"),
-    ([-1, 0, 1, 2, 3, 0], "a path of five tasks, longer than the leaf-by-leaf kernel walks"),
+TREES_WITH_SEVERAL_LEAVES = [   # parents, what the case is for, variants per task
+    ([-1, 0, 0], "star, two leaves", 2),
+    ([-1, 0, 0, 0], "star, three leaves: the path count is no power of two, one leaf belongs to the work item", 2),
+    ([-1, 0, 1, 0], "paths of three and two tasks", 2),
+    ([-1, 0, 1, 1], "both leaves under task 1: the last task has two ancestors", 2),
+    ([-1, 0, 0, 1, 2], "two chains of three tasks", 2),
+    ([-1, 0, 1, 2, 3, 0], "a path of five tasks", 2),
+    ([-1, 0, 1, 2, 3, 0], "a path of five tasks with 81 branches above its leaf: more than are taken leaf by leaf", 3),
 ]
 
 
 # (with per-variant factors the fixed-point range check leaves no demand worth testing at five levels)
-@pytest.mark.parametrize("parent,what,variant_factors",
-                         [(t, w, vf) for t, w in TREES_WITH_SEVERAL_LEAVES for vf in (False, True)
+@pytest.mark.parametrize("parent,what,n_variants,variant_factors",
+                         [(t, w, k, vf) for t, w, k in TREES_WITH_SEVERAL_LEAVES for vf in (False, True)
                           if not (vf and len(t) == 6)])
-def test_trees_with_several_leaves_leaf_by_leaf(parent, what, variant_factors):
+def test_trees_with_several_leaves_leaf_by_leaf(parent, what, n_variants, variant_factors):
     """With two or more leaves the objective is a sum of one value per leaf, each a function of the choices
     along that leaf's task path (Section 4.1 "Accuracy": the system accuracy averages over the task paths);
     the search forms each value once for all the plans that share those choices.  Whole space, both tie
     rules, several demand points, and index ranges, against the checker's plan-by-plan search."""
     n = len(parent)
     rng = wl.SplitMix64(900 + 7 * n + sum(parent))
-    p = wl.make_pipeline(parent, 2, 2 if n <= 5 else 1, (1, 4), rng)
+    p = wl.make_pipeline(parent, n_variants, 2 if n <= 5 else 1, (1, 4) if n_variants == 2 else (2,), rng)
     p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(901 + n))
     if variant_factors:
         p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]
+    by_leaf = n_variants ** (n - 2) <= 64   # (holds for these trees: the deepest leaf has n - 2 ancestors)
     P, O = binding.Problem(p), oracle.Problem(p)
     N = P.num_candidates()
     assert N <= 2_000_000
     workers, slo = 3 * n, 500_000
     demands = {3: [15_000, 40_000, 90_000, 200_000], 4: [15_000, 40_000, 90_000, 200_000],
                5: [1_000, 4_000, 10_000, 25_000], 6: [500, 1_000, 2_000, 4_000]}[n]
+    if n_variants == 3:
+        demands = [2_000, 8_000, 20_000, 50_000]
     found = 0
     for flags in (0, TIE):
         out = P.alloc_search(demands, workers, slo, flags=flags)
@@ -242,7 +246,7 @@ def test_trees_with_several_leaves_leaf_by_leaf(parent, what, variant_factors):
     # which way the search went shows in the number of plans its kernels visited: leaf by leaf the work
     # items hold only usable choices of the tasks with children; the walk over the whole space visits all
     if not variant_factors:
-        if n <= 5:
+        if by_leaf:
             assert 0 < P.last_search_plans_scored() < N * len(demands), what
         else:
             assert P.last_search_plans_scored() == N * len(demands), what
