@@ -187,3 +187,11 @@ def test_workspace_covers_the_searches_a_handle_may_run():
             assert plain < with_tables <= plain + 8 * len(q.path_acc_ppm) + 256
         else:          # two leaves: searched point by point like per-variant factors (one point per demand point)
             assert with_factors <= with_tables <= with_factors + 8 * len(q.path_acc_ppm) + 256
+    # that route is taken with at most 64 variant combinations above every leaf: a path of five tasks with two
+    # variants each has 16 above its leaf, with three variants 81
+    for k, by_leaf in ((2, True), (3, False)):
+        t = wl.make_pipeline([-1, 0, 1, 2, 3, 0], k, 1, (2,), wl.SplitMix64(3))
+        plain = binding.Problem(t).workspace_bytes(4)
+        t.path_acc_ppm = wl.draw_path_tables(t, wl.SplitMix64(4))
+        with_tables = binding.Problem(t).workspace_bytes(4)
+        assert (with_tables > plain + 65_535 * 8 * (8 + 8 + 4)) == by_leaf, (k, plain, with_tables)
