@@ -80,7 +80,9 @@ enum {
     LOKI_E_RANGE = -3,         /* a value outside the documented range, or fixed-point overflow risk */
     LOKI_E_WORKSPACE = -4,     /* workspace too small or misaligned (needs 256-byte alignment) */
     LOKI_E_HIP = -5,           /* a HIP runtime call failed; loki_last_hip_error() has the code */
-    LOKI_E_ARG = -6            /* inconsistent scalar arguments (empty range reversed, bad flags, ...) */
+    LOKI_E_ARG = -6,           /* inconsistent scalar arguments (empty range reversed, bad flags, ...) */
+    LOKI_E_STATIC_LIMIT = -7   /* loki_alloc_search_static: the search needs more than LOKI_STATIC_SCRATCH_BYTES
+                                  of device scratch, or has more than LOKI_STATIC_MAX_DEMAND_POINTS demand points */
 };
 
 /* flags of loki_alloc_search */
@@ -235,6 +237,31 @@ int loki_alloc_search_enqueue(loki_problem_t *problem, const int64_t *demand_mqp
                               uint64_t index_begin, uint64_t index_end,
                               void *d_workspace, size_t workspace_bytes, void *hip_stream,
                               void *d_results);
+
+/* loki_alloc_search for callers that cannot allocate device memory or must not cause an allocation: code
+ * running around a HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  There is no
+ * workspace argument: the device scratch of the search is a file-scope device array of
+ * LOKI_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends), and the
+ * call itself allocates nothing -- no device or pinned memory, no events; the handle's host staging is
+ * ordinary memory owned since loki_problem_create.  The caller still passes the inputs and the output
+ * array.  Results are those of loki_alloc_search bit for bit.
+ *   demand_mqps  host, [n_demand], n_demand <= LOKI_STATIC_MAX_DEMAND_POINTS
+ *   out          host, [n_demand]; valid on return (the call waits for the stream)
+ * All searches of all handles on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (other threads, other streams) race and must be serialised by the caller.  The array keeps the previous
+ * call's contents; a search overwrites every part it reads, nothing has to be cleared.
+ * A search never runs class by class here (that needs a large workspace and pinned descriptors):
+ * per-variant factors score whole plans per lane and profiled path accuracies walk the variant paths of
+ * feasible plans, as with LOKI_SEARCH_PER_LANE or on chains.
+ * Errors: as loki_alloc_search, and LOKI_E_STATIC_LIMIT when the search of this problem with n_demand
+ * demand points needs more scratch than the array holds (4 MiB cover one demand point of about 180,000
+ * choices summed over the tasks) or n_demand exceeds LOKI_STATIC_MAX_DEMAND_POINTS; nothing is launched then. */
+#define LOKI_STATIC_SCRATCH_BYTES (4u << 20)
+#define LOKI_STATIC_MAX_DEMAND_POINTS 64
+int loki_alloc_search_static(loki_problem_t *problem, const int64_t *demand_mqps, int32_t n_demand,
+                             int32_t workers, int64_t slo_us, int64_t comm_us, uint32_t flags,
+                             uint64_t index_begin, uint64_t index_end, void *hip_stream,
+                             loki_result_t *out);
 
 /* Evaluate listed plans one by one (each lane scores one plan from scratch).
  *   indices  host, [n_indices], each < N;  out host, [n_indices]. */

@@ -18,6 +18,8 @@ MAX_VARIANTS = 8
 
 LOKI_OK = 0
 LOKI_E_NULL, LOKI_E_INVALID_GRAPH, LOKI_E_RANGE, LOKI_E_WORKSPACE, LOKI_E_HIP, LOKI_E_ARG = -1, -2, -3, -4, -5, -6
+LOKI_E_STATIC_LIMIT = -7
+LOKI_STATIC_SCRATCH_BYTES, LOKI_STATIC_MAX_DEMAND_POINTS = 4 << 20, 64
 LOKI_TIE_WORKERS_THEN_INDEX, LOKI_TIE_INDEX_ONLY, LOKI_SEARCH_PER_LANE = 0, 1, 2
 LOKI_FOUND, LOKI_NO_FEASIBLE = 0, 1
 LOKI_BAD_WORKERS, LOKI_BAD_DEMAND, LOKI_BAD_EMPTY, LOKI_BAD_LATENCY = 1, 2, 4, 8
@@ -25,7 +27,7 @@ LOKI_PHASE_HARDWARE, LOKI_PHASE_ACCURACY, LOKI_PHASE_OVERLOAD = 0, 1, 2
 UINT64_MAX = (1 << 64) - 1
 
 EXPORTS = ["loki_problem_create", "loki_problem_destroy", "loki_num_candidates", "loki_workspace_bytes",
-           "loki_decode", "loki_alloc_search", "loki_alloc_search_enqueue", "loki_alloc_eval",
+           "loki_decode", "loki_alloc_search", "loki_alloc_search_enqueue", "loki_alloc_search_static", "loki_alloc_eval",
            "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_measure_valu_rate", "loki_last_search_ms", "loki_last_search_plans_scored", "loki_strerror", "loki_last_hip_error"]
 
 
@@ -124,6 +126,8 @@ def lib():
         L.loki_alloc_search.argtypes = search_args + [C.POINTER(Result)]
         L.loki_alloc_search_enqueue.restype = C.c_int
         L.loki_alloc_search_enqueue.argtypes = search_args + [C.c_void_p]
+        L.loki_alloc_search_static.restype = C.c_int
+        L.loki_alloc_search_static.argtypes = search_args[:9] + [C.c_void_p, C.POINTER(Result)]
         L.loki_alloc_eval.restype = C.c_int
         L.loki_alloc_eval.argtypes = [P, C.POINTER(C.c_uint64), C.c_int64, C.c_int64, C.c_int32, C.c_int64,
                                       C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(Eval)]
@@ -237,6 +241,17 @@ class Problem:
         _check(lib().loki_alloc_search(self._h, _arr(C.c_int64, demand_mqps), m, workers, slo_us, comm_us, flags,
                                        begin, end, ws.data_ptr(), ws.numel(), self._stream(), out),
                "loki_alloc_search")
+        return list(out)
+
+    def alloc_search_static(self, demand_mqps: Sequence[int], workers: int, slo_us: int, comm_us: int = 0, *,
+                            flags: int = 0, begin: int = 0, end: Optional[int] = None) -> List[Result]:
+        """The search in the library's own static device scratch: no workspace, nothing allocated."""
+        if end is None:
+            end = self.num_candidates()
+        m = len(demand_mqps)
+        out = (Result * m)()
+        _check(lib().loki_alloc_search_static(self._h, _arr(C.c_int64, demand_mqps), m, workers, slo_us, comm_us,
+                                              flags, begin, end, self._stream(), out), "loki_alloc_search_static")
         return list(out)
 
     def alloc_search_enqueue(self, demand_mqps: Sequence[int], workers: int, slo_us: int, comm_us: int = 0, *,

@@ -7,8 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libloki_alloc.so")
-SOURCES = ["loki_kernels.hip", "loki_valu_rate.hip", "loki_api.cpp"]
-HEADERS = ["loki_device.h", "loki_launch.h"]
+SOURCES = ["loki_kernels.hip", "loki_valu_rate.hip", "loki_static.hip", "loki_api.cpp"]
+HEADERS = ["loki_device.h", "loki_launch.h", "loki_host.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

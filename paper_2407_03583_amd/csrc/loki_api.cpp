@@ -12,6 +12,7 @@
 
 #include "../../include/loki_alloc.h"
 #include "loki_device.h"
+#include "loki_host.h"
 #include "loki_launch.h"
 
 using namespace loki;
@@ -130,6 +131,9 @@ struct loki_problem {
     // pinned staging: [DevProblem, path accuracies | Dn (cap_points * 8 int64) | results (cap_points)]
     unsigned char *staging = nullptr;
     int64_t cap_points = 0;
+    // ordinary host memory with the same head ([DevProblem, path accuracies | Dn of kNoAllocPoints points]) for
+    // searches that must not allocate: sized when the handle is created, copied from as it is
+    std::vector<unsigned char> plain_block;
     hipEvent_t staged = nullptr, ev[4] = {nullptr, nullptr, nullptr, nullptr};
     bool staged_pending = false;
     float last_ms[3] = {0.f, 0.f, 0.f};  // per-task tables, main search kernel, final merge
@@ -156,10 +160,11 @@ size_t const_block(const loki_problem *p) {
     return align_up(sizeof(DevProblem) + p->path_acc.size() * sizeof(double));
 }
 
-void fill_const_block(loki_problem *p) {
-    std::memcpy(p->staging, &p->dev, sizeof(DevProblem));
+void fill_const_block(loki_problem *p, unsigned char *dst = nullptr) {
+    if (!dst) dst = p->staging;
+    std::memcpy(dst, &p->dev, sizeof(DevProblem));
     if (!p->path_acc.empty())
-        std::memcpy(p->staging + sizeof(DevProblem), p->path_acc.data(), p->path_acc.size() * sizeof(double));
+        std::memcpy(dst + sizeof(DevProblem), p->path_acc.data(), p->path_acc.size() * sizeof(double));
 }
 
 const double *device_path_acc(const loki_problem *p, const unsigned char *ws) {
@@ -735,11 +740,16 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
 }
 
 // results_at (optional): where on the device the results of the demand points are written.
+// no_alloc: nothing is allocated on the way (no pinned staging, no events, no class-by-class search, which
+// needs both): the head of the workspace is copied from the handle's ordinary host block, so the copy
+// is done when hipMemcpyAsync returns; timed must be false and n_demand at most kNoAllocPoints.
 int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers, int64_t slo_us,
                    int64_t comm_us, uint32_t flags, uint64_t index_begin, uint64_t index_end, void *d_workspace,
-                   size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed, void **results_at) {
+                   size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed, void **results_at,
+                   bool no_alloc = false) {
     if (!p || !demand_mqps || !d_workspace) return LOKI_E_NULL;
     if (n_demand < 1 || n_demand > LOKI_MAX_DEMAND_POINTS) return LOKI_E_ARG;
+    if (no_alloc && (timed || n_demand > kNoAllocPoints)) return LOKI_E_ARG;
     if (flags & ~(LOKI_TIE_INDEX_ONLY | LOKI_SEARCH_PER_LANE)) return LOKI_E_ARG;
     if (index_begin > index_end || index_end > p->n_candidates) return LOKI_E_ARG;
     int rc = check_scalars(workers, slo_us, comm_us);
@@ -747,7 +757,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     // Per-variant factors: a task's demand depends on its parent's part of the plan.  Where every other
     // task is a child of the first one, that dependence is one number per first-task choice (the requests
     // it creates), and the tabulated kernels run once per distinct value; otherwise whole plans per lane.
-    if (class_search_mode(p, index_begin, index_end) != 0 && !(flags & LOKI_SEARCH_PER_LANE)) {
+    if (!no_alloc && class_search_mode(p, index_begin, index_end) != 0 && !(flags & LOKI_SEARCH_PER_LANE)) {
         rc = enqueue_class_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
                                   d_workspace, workspace_bytes, stream, d_results, timed, results_at);
         if (rc != LOKI_E_ARG) return rc;  // LOKI_E_ARG: too many classes, take the general path
@@ -762,25 +772,31 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         return LOKI_E_WORKSPACE;
     if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
 
-    rc = ensure_staging(p, n_demand);
-    if (rc) return rc;
-    if (p->staged_pending) {  // the previous call's copy may still be reading the staging buffer
-        LOKI_HIP(hipEventSynchronize(p->staged));
-        p->staged_pending = false;
+    unsigned char *host_head = p->plain_block.data();
+    if (!no_alloc) {
+        rc = ensure_staging(p, n_demand);
+        if (rc) return rc;
+        if (p->staged_pending) {  // the previous call's copy may still be reading the staging buffer
+            LOKI_HIP(hipEventSynchronize(p->staged));
+            p->staged_pending = false;
+        }
+        host_head = p->staging;
     }
-    int64_t *hDn = reinterpret_cast<int64_t *>(p->staging + cb);
+    int64_t *hDn = reinterpret_cast<int64_t *>(host_head + cb);
     for (int32_t m = 0; m < n_demand; m++) {
         rc = task_demand(p, demand_mqps[m], hDn + size_t(m) * kMaxTasks);
         if (rc) return rc;
     }
-    fill_const_block(p);
+    fill_const_block(p, host_head);
 
     unsigned char *ws = static_cast<unsigned char *>(d_workspace);
     const size_t head = cb + size_t(n_demand) * kMaxTasks * sizeof(int64_t);
     static_assert(sizeof(DevProblem) % 8 == 0, "alignment of the demand block");
-    LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, p->staging, head, hipMemcpyHostToDevice, stream));
-    LOKI_HIP(hipEventRecord(p->staged, stream));
-    p->staged_pending = true;
+    LOKI_HIP(hipMemcpyAsync(ws + lay.off_P, host_head, head, hipMemcpyHostToDevice, stream));
+    if (!no_alloc) {
+        LOKI_HIP(hipEventRecord(p->staged, stream));
+        p->staged_pending = true;
+    }
 
     SearchArgs A;
     std::memset(&A, 0, sizeof(A));
@@ -1047,6 +1063,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         }
     }
 
+    p->plain_block.assign(const_block(p) + size_t(kNoAllocPoints) * kMaxTasks * sizeof(int64_t), 0);
     *out = p;
     return LOKI_OK;
 }
@@ -1400,6 +1417,7 @@ const char *loki_strerror(int code) {
         case LOKI_E_WORKSPACE: return "workspace too small or misaligned";
         case LOKI_E_HIP: return "HIP runtime error";
         case LOKI_E_ARG: return "inconsistent arguments";
+        case LOKI_E_STATIC_LIMIT: return "search needs more scratch memory or demand points than the library's static buffer holds";
         default: return "unknown error";
     }
 }
@@ -1407,3 +1425,30 @@ const char *loki_strerror(int code) {
 int loki_last_hip_error(void) { return g_last_hip; }
 
 }  // extern "C"
+
+namespace loki {
+
+int plain_search_bytes(const loki_problem_t *p, int32_t n_demand, size_t *bytes) {
+    if (!p || !bytes) return LOKI_E_NULL;
+    if (n_demand < 1) return LOKI_E_ARG;
+    *bytes = search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total;
+    return LOKI_OK;
+}
+
+int search_without_allocation(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers,
+                              int64_t slo_us, int64_t comm_us, uint32_t flags, uint64_t index_begin,
+                              uint64_t index_end, void *d_workspace, size_t workspace_bytes, hipStream_t stream,
+                              loki_result_t *out) {
+    void *d_res = nullptr;
+    const int rc = enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
+                                  d_workspace, workspace_bytes, stream, nullptr, false, &d_res, true);
+    if (rc) return rc;
+    // straight into the caller's array (ordinary host memory: the copy is staged by the runtime)
+    LOKI_HIP(hipMemcpyAsync(out, d_res, size_t(n_demand) * sizeof(loki_result_t), hipMemcpyDeviceToHost, stream));
+    LOKI_HIP(hipStreamSynchronize(stream));
+    return LOKI_OK;
+}
+
+int note_hip_error(int hip_error) { return hip_fail(static_cast<hipError_t>(hip_error)); }
+
+}  // namespace loki

@@ -195,3 +195,20 @@ def test_workspace_covers_the_searches_a_handle_may_run():
         t.path_acc_ppm = wl.draw_path_tables(t, wl.SplitMix64(4))
         with_tables = binding.Problem(t).workspace_bytes(4)
         assert (with_tables > plain + 65_535 * 8 * (8 + 8 + 4)) == by_leaf, (k, plain, with_tables)
+
+
+def test_static_scratch_search_refuses_oversize_before_touching_the_gpu():
+    """The limits of the entry point that allocates nothing are checked on the host, ahead of any HIP call."""
+    import ctypes as C
+    w = wl.config(3)
+    P = binding.Problem(w.pipeline)
+    n = P.num_candidates()
+    for m in (64, 65):
+        out = (binding.Result * m)()
+        rc = binding.lib().loki_alloc_search_static(P._h, (C.c_int64 * m)(*([w.demand_mqps[0]] * m)), m, w.workers,
+                                                    w.slo_us, 0, 0, 0, n, None, out)
+        assert rc == binding.LOKI_E_STATIC_LIMIT
+    assert b"static" in binding.lib().loki_strerror(binding.LOKI_E_STATIC_LIMIT)
+    header = open(os.path.join(ROOT, "include", "loki_alloc.h")).read()
+    assert f"#define LOKI_STATIC_SCRATCH_BYTES ({binding.LOKI_STATIC_SCRATCH_BYTES >> 20}u << 20)" in header
+    assert f"#define LOKI_STATIC_MAX_DEMAND_POINTS {binding.LOKI_STATIC_MAX_DEMAND_POINTS}" in header
