@@ -39,7 +39,7 @@ thread_local int g_last_hip = 0;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t off_P, off_Dn, off_table, off_perm, off_run, off_perm_all, off_run_t, off_recs, off_results, total;
+    size_t off_P, off_Dn, off_table, off_perm, off_run, off_perm_all, off_run_t, off_recs, off_floor, off_results, total;
 };
 
 // `cb` is the size of the constant block: the problem constants followed by the profiled path
@@ -56,7 +56,8 @@ Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, ui
     l.off_perm_all = align_up(l.off_run + size_t(M) * c0 * sizeof(uint32_t));
     l.off_run_t = align_up(l.off_perm_all + size_t(M) * (c1 ? table_total : 0u) * sizeof(uint32_t));
     l.off_recs = align_up(l.off_run_t + size_t(M) * c1 * sizeof(uint32_t));
-    l.off_results = align_up(l.off_recs + (size_t(kTargetBlocks) + size_t(M)) * sizeof(BestRec));
+    l.off_floor = align_up(l.off_recs + (size_t(kTargetBlocks) + size_t(M)) * sizeof(BestRec));
+    l.off_results = align_up(l.off_floor + size_t(M) * sizeof(unsigned long long));
     l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
     return l;
 }
@@ -610,6 +611,7 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     A.P = reinterpret_cast<const DevProblem *>(ws + lay.off_P);
     A.table = reinterpret_cast<TaskRec *>(bw + lay.batch.off_table);
     A.recs = reinterpret_cast<BestRec *>(bw + lay.batch.off_recs);
+    A.floor = reinterpret_cast<unsigned long long *>(bw + lay.batch.off_floor);
     A.perm = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm);
     A.run_end = reinterpret_cast<uint32_t *>(bw + lay.batch.off_run);
     A.perm_all = reinterpret_cast<uint32_t *>(bw + lay.batch.off_perm_all);
@@ -804,6 +806,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     A.Dn = reinterpret_cast<const int64_t *>(ws + lay.off_Dn);
     A.table = reinterpret_cast<TaskRec *>(ws + lay.off_table);
     A.recs = reinterpret_cast<BestRec *>(ws + lay.off_recs);
+    A.floor = reinterpret_cast<unsigned long long *>(ws + lay.off_floor);
     A.perm = reinterpret_cast<uint32_t *>(ws + lay.off_perm);
     A.run_end = reinterpret_cast<uint32_t *>(ws + lay.off_run);
     A.results = d_results ? d_results : static_cast<void *>(ws + lay.off_results);

@@ -112,6 +112,7 @@ struct SearchArgs {
     uint32_t *perm;         // [M][C_0] first-task choices in run order
     uint32_t *run_end;      // [M][C_0] end (exclusive) of the run each position belongs to
     void *results;          // [M] loki_result_t
+    unsigned long long *floor;  // [M] bit pattern of the largest key a block of the point has reported so far
     const double *path_acc; // [path_total] profiled path accuracies as fractions, or null
     // Per-variant factors searched class by class: a "point" of the launch is a demand point together
     // with one value, per task that has children, of the requests the task creates per unit of fan-out

@@ -23,6 +23,8 @@
 
 #include <stddef.h>
 
+#include <type_traits>
+
 #include "loki_device.h"
 #include "loki_launch.h"
 
@@ -585,6 +587,62 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
     return v;
 }
 
+// Largest value of a wavefront, in every lane.  Must be called by all 64 lanes.
+template <int STEP>
+__device__ __forceinline__ double wave_max_f64_step(double v) {
+    const uint64_t b = static_cast<uint64_t>(__double_as_longlong(v));
+    const uint64_t o = (static_cast<uint64_t>(wave_xchg<STEP>(static_cast<uint32_t>(b >> 32))) << 32) |
+                       wave_xchg<STEP>(static_cast<uint32_t>(b));
+    return __builtin_fmax(v, __longlong_as_double(static_cast<long long>(o)));
+}
+__device__ __forceinline__ double wave_max_f64(double v) {
+    v = wave_max_f64_step<0>(v);
+    v = wave_max_f64_step<1>(v);
+    v = wave_max_f64_step<2>(v);
+    v = wave_max_f64_step<3>(v);
+    v = wave_max_f64_step<4>(v);
+    return wave_max_f64_step<5>(v);
+}
+
+template <int STEP>
+__device__ __forceinline__ uint32_t wave_min_u32_step(uint32_t v) {
+    const uint32_t o = wave_xchg<STEP>(v);
+    return o < v ? o : v;
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    v = wave_min_u32_step<0>(v);
+    v = wave_min_u32_step<1>(v);
+    v = wave_min_u32_step<2>(v);
+    v = wave_min_u32_step<3>(v);
+    v = wave_min_u32_step<4>(v);
+    return wave_min_u32_step<5>(v);
+}
+
+// Among plans of equal objective: the first in the order (workers unless tie_index_only, then the last
+// task's choice, then the rest of the index), in every lane.  "Nothing yet" is (kNever, ~0, ~0) and loses.
+template <int STEP>
+__device__ __forceinline__ void wave_first_step(int32_t &w, uint32_t &cl, uint64_t &low, bool tie_index_only) {
+    const int32_t ow = static_cast<int32_t>(wave_xchg<STEP>(static_cast<uint32_t>(w)));
+    const uint32_t ocl = wave_xchg<STEP>(cl);
+    const uint64_t olow = (static_cast<uint64_t>(wave_xchg<STEP>(static_cast<uint32_t>(low >> 32))) << 32) |
+                          wave_xchg<STEP>(static_cast<uint32_t>(low));
+    bool take = (ocl < cl) | ((ocl == cl) & (olow < low));
+    if (!tie_index_only) take = (ow < w) | ((ow == w) & take);
+    if (take) {
+        w = ow;
+        cl = ocl;
+        low = olow;
+    }
+}
+__device__ __forceinline__ void wave_first(int32_t &w, uint32_t &cl, uint64_t &low, bool tie_index_only) {
+    wave_first_step<0>(w, cl, low, tie_index_only);
+    wave_first_step<1>(w, cl, low, tie_index_only);
+    wave_first_step<2>(w, cl, low, tie_index_only);
+    wave_first_step<3>(w, cl, low, tie_index_only);
+    wave_first_step<4>(w, cl, low, tie_index_only);
+    wave_first_step<5>(w, cl, low, tie_index_only);
+}
+
 // Block-level merge of per-wavefront records and store of one BestRec.
 // nfeas is the wavefront's total (uniform across its lanes).
 __device__ __forceinline__ void block_store_best(double acc, int32_t w, uint64_t idx, uint64_t nfeas, bool tie_index_only,
@@ -620,6 +678,7 @@ __global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A)
     __syncthreads();
     const uint32_t t = blockIdx.x * kBlockThreads + threadIdx.x;
     const int m = blockIdx.y;
+    if (t == 0) A.floor[m] = 0;  // largest key reported by a block of this point so far: none yet
     if (t >= sP.table_total) return;
     int i = sP.n_tasks - 1;
     while (i > 0 && t < sP.table_off[i]) i--;
@@ -776,6 +835,10 @@ combine_kernel(SearchArgs A) {
     __shared__ uint32_t sChoice[kMidTile];  // first-task choice of each tile entry (cold path only)
     __shared__ double sFac[64];             // the accuracies the path-value steps multiply by (per work item)
     __shared__ BestRec sBest[kWavesPerBlock];
+    __shared__ double sTop[kWavesPerBlock][2];  // per wavefront: largest pre / presum of a tile; the largest key
+    __shared__ uint32_t sGo;                    // the block takes the second pass
+    __shared__ uint32_t sBlk;                   // second pass: fewest workers (order by index: lowest choice of the last
+                                                // task) of the best plans the block's wavefronts have found so far
     DevProblem *sP = reinterpret_cast<DevProblem *>(sPraw);  // only the head is valid
     stage_problem(sP, A.P, kHeadBytes);
     __syncthreads();
@@ -836,16 +899,20 @@ combine_kernel(SearchArgs A) {
 
     double a[S];
     int32_t w[S], lat[S];
-    // best plan so far in this lane: key (path sum, or accuracy when DIVIDE), workers, and the index
-    // split into the last task's choice and the rest (index = rest + strideL * choice, rest < strideL)
+    // The block walks its work items twice.  The first pass keeps, per lane, nothing but the largest key
+    // (path sum, or accuracy when DIVIDE) among its feasible plans -- no compare-and-branch in the loop
+    // over the plans, so its cost does not depend on how many plans are feasible or tie -- and counts the
+    // feasible plans.  The second pass, taken only by blocks whose largest key can still be the demand
+    // point's, settles which of the plans that reach the block's largest key comes first in the order
+    // (fewest workers, then lowest index); it skips whatever cannot hold such a plan.
     double bsum = -1.0;
+    double gb = -1.0;       // second pass: the block's largest key
+    bool lane_in = false;   // second pass: this lane reached it in the first pass
+    // second pass: the best plan with that key this wavefront has seen (the same in every lane): workers, and
+    // the index split into the last task's choice and the rest (index = rest + strideL * choice, rest < strideL)
     int32_t bw = kNever;
     uint32_t bcl = ~0u;
     uint64_t blow = ~0ull;
-    // of this lane's slots that can ever be feasible: fewest replicas and the lowest choice having them,
-    // and the lowest choice at all (what a tie needs to beat the lane's best is bounded by these)
-    int32_t minw = kNever;
-    uint32_t cmin = ~0u, cfirst = ~0u;
     uint64_t nfeas = 0;  // wavefront total
     uint32_t cur_group = ~0u;
     uint32_t cbase = 0;  // first choice of the last task in this wavefront's chunk
@@ -900,6 +967,34 @@ combine_kernel(SearchArgs A) {
         }
         cj[0] = 0;
     };
+    // the next item of the whole space (the tile, then the digits of the tasks in between, then the chunk group)
+    auto advance = [&]() {
+        if (++r == A.mid_tiles) {
+            r = 0;
+            ++f;
+            bool carry = true;
+#pragma unroll
+            for (int j = 1; j < kMaxTasks; j++) {
+                if (j < L && carry) {
+                    if (++cj[j] == uni(sP->C[j])) {
+                        cj[j] = 0;
+                    } else {
+                        carry = false;
+                    }
+                }
+            }
+            if (carry) {  // every digit wrapped (or there is none): next chunk group
+                f = 0;
+                ++g;
+            }
+        }
+    };
+    // settle_tag: std::false_type for the first pass, std::true_type for the second
+    auto walk = [&](auto settle_tag) {
+    constexpr bool SETTLE = decltype(settle_tag)::value;
+    cur_group = ~0u;
+    last_for = ~0ull;
+    tile_for = ~0ull;
     if (item_lo < item_hi) locate(item_lo);
     for (uint64_t item = item_lo; item < item_hi; ++item) {
         if (g != cur_group) {
@@ -921,19 +1016,6 @@ combine_kernel(SearchArgs A) {
                 }
             }
             last_for = ~0ull;
-            minw = kNever;
-            cmin = ~0u;
-            cfirst = ~0u;
-#pragma unroll
-            for (int s = S - 1; s >= 0; s--) {
-                if (lat[s] != kNever) {
-                    cfirst = cl0 + s * 64;
-                    if (w[s] <= minw) {
-                        minw = w[s];
-                        cmin = cl0 + s * 64;
-                    }
-                }
-            }
         }
         // What the tasks strictly between the first and the last contribute (the same for the
         // whole tile): replicas, feasibility, latency along each chain without the first task.
@@ -1064,6 +1146,30 @@ combine_kernel(SearchArgs A) {
             if (t >= 0) sFac[threadIdx.x] = tab[sP->table_off[t] + pick32(cj, t)].a;
         }
         __syncthreads();  // the previous item's tile is no longer being read; the factors are visible
+        if constexpr (SETTLE) {
+            // Second pass: a work item none of whose plans can come before the best plan some wavefront of the
+            // block has found is skipped as a whole.  sBlk changes only while tiles are walked, never between
+            // this barrier and the next one, so every thread of the block decides alike.
+            const uint32_t seen = sBlk;
+            bool skip = !ok_far;
+            if (tie_index_only) {
+                // the lowest choice of the last task any wavefront of the block holds in this chunk group
+                skip = skip || A.cl_first + g * cpb * (64u * S) > seen;
+            } else {
+                // every task hosts at least one replica in a feasible plan
+                const int64_t least = w_far + (n >= 2 ? 2 : 1);
+                skip = skip || least > static_cast<int64_t>(seen);
+            }
+            if (skip) {
+                if (BY_LEAF && new_last) last_for = ~0ull;  // the lane values were not formed for these ancestors
+                if (RANGE || SWAP) {
+                    if (item + 1 < item_hi) locate(item + 1);
+                } else {
+                    advance();
+                }
+                continue;
+            }
+        }
         if constexpr (BY_LEAF) {
             if (new_last) {
                 // the last task's value of every lane and slot
@@ -1080,6 +1186,7 @@ combine_kernel(SearchArgs A) {
         // Every thread builds its entries of the tile two at a time, side by side: the steps are read once
         // per pair and applied to both.
         constexpr int kSide = 2;
+        double top_pre = 0.0, top_presum = 0.0;  // second pass: largest values among this thread's usable entries
         for (uint32_t e_first = threadIdx.x; e_first < cnt; e_first += kSide * kBlockThreads) {
             uint32_t cMs[kSide];
             double a0s[kSide], val[kSide], presum[kSide], pre[kSide];
@@ -1134,25 +1241,20 @@ combine_kernel(SearchArgs A) {
             bool first = true;
             const int n_prog = SWAP ? 0 : uni(sP->n_prog);
             for (int q = 0; q < n_prog; q++) {
+                // one step, written without branches: what a step of another kind would have computed is
+                // formed too and dropped (only a multiply step's slot of sFac holds a value)
                 const int op = uni(static_cast<int>(sP->prog_op[q]));
-                if (op == kStepMul) {
-                    const double fac = sFac[q];
+                const bool is_mul = op == kStepMul, is_leaf = op == kStepLeaf, is_pre = op == kStepPre;
+                const double fac = sFac[q];
 #pragma unroll
-                    for (int k = 0; k < kSide; k++) val[k] = val[k] * fac;
-                } else if (op == kStepLeaf) {
-#pragma unroll
-                    for (int k = 0; k < kSide; k++) {
-                        presum[k] = first ? val[k] : presum[k] + val[k];
-                        val[k] = a0s[k];
-                    }
-                    first = false;
-                } else {
-#pragma unroll
-                    for (int k = 0; k < kSide; k++) {
-                        pre[k] = val[k];
-                        val[k] = a0s[k];
-                    }
+                for (int k = 0; k < kSide; k++) {
+                    const double prod = val[k] * fac;
+                    const double sum = first ? val[k] : presum[k] + val[k];
+                    presum[k] = is_leaf ? sum : presum[k];
+                    pre[k] = is_pre ? val[k] : pre[k];
+                    val[k] = is_mul ? prod : a0s[k];
                 }
+                first = first && !is_leaf;
             }
 #pragma unroll
             for (int k = 0; k < kSide; k++) {
@@ -1184,9 +1286,23 @@ combine_kernel(SearchArgs A) {
                     }
                     sVal[e] = uv;
                     sLim[e] = ul;
+                    if (SETTLE && ul.w_rem >= 0) {
+                        top_pre = __builtin_fmax(top_pre, uv.pre);
+                        top_presum = __builtin_fmax(top_presum, uv.presum);
+                    }
                     // the entry's part of the plan's index (SWAP: below 2^32, checked on the host)
                     sChoice[e] = SWAP ? static_cast<uint32_t>(uni64(sP->stride[T])) * cMs[k] : cMs[k];
                 }
+            }
+        }
+        if constexpr (SETTLE) {
+            // the largest pre / presum of the tile, for the bound below: one slot per wavefront, written by
+            // every wavefront for every item (read after the barrier, rewritten after the next item's first one)
+            top_pre = wave_max_f64(top_pre);
+            top_presum = wave_max_f64(top_presum);
+            if (lane == 0) {
+                sTop[wave][0] = top_pre;
+                sTop[wave][1] = top_presum;
             }
         }
         __syncthreads();
@@ -1194,6 +1310,7 @@ combine_kernel(SearchArgs A) {
         // this wavefront's contiguous part of the tile
         const uint32_t e_lo = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * midpart / mid_split);
         const uint32_t e_hi = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * (midpart + 1) / mid_split);
+        if constexpr (!SETTLE) {
         uint32_t fcount = 0;  // feasible plans of this item seen by this wavefront (< 2^20)
         uint32_t e = e_lo;
         // the limits and the first record of a run are fetched during the run before it
@@ -1213,7 +1330,6 @@ combine_kernel(SearchArgs A) {
                 ul_ahead = sLim[e_next];
                 u_ahead = sVal[e_next];
             }
-            uint64_t fm[S];
             int32_t amh[S];  // high word of the accuracy, or of a huge negative number where the plan is infeasible
             uint32_t run_feas = 0;
             const int32_t w_rem = uni(ul.w_rem), tl = uni(ul.tl);  // the same in every lane: scalar operands
@@ -1221,19 +1337,20 @@ combine_kernel(SearchArgs A) {
             for (int s = 0; s < S; s++) {
                 // one ballot per compare: the masks then come straight from the compare results
                 const bool ok_w = w[s] <= w_rem, ok_l = lat[s] <= tl;
-                fm[s] = __builtin_amdgcn_ballot_w64(ok_w) & __builtin_amdgcn_ballot_w64(ok_l);
+                uint64_t fm = __builtin_amdgcn_ballot_w64(ok_w) & __builtin_amdgcn_ballot_w64(ok_l);
                 bool ok = ok_w & ok_l;
                 if (RANGE) {
                     const bool ok_r = (cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt;
-                    fm[s] &= __builtin_amdgcn_ballot_w64(ok_r);
+                    fm &= __builtin_amdgcn_ballot_w64(ok_r);
                     ok = ok & ok_r;
                 }
-                run_feas += static_cast<uint32_t>(__builtin_popcountll(fm[s]));
+                run_feas += static_cast<uint32_t>(__builtin_popcountll(fm));
                 amh[s] = ok ? __double2hiint(a[s]) : static_cast<int32_t>(0xFFE00000u);
             }
-            // ---- every record of the run: S*64 objectives; an infeasible plan's stand-in is far below
-            // any best, so one running maximum and one compare per record tell whether any lane improved
-            auto score = [&](const MidVal &u, uint32_t ee) {
+            fcount += run_feas * (run_hi - e);
+            // ---- every record of the run: S*64 objectives into the lane's running maximum; an infeasible
+            // plan's stand-in is far below any key
+            auto score = [&](const MidVal &u) {
                 double kmax = 0.0;
 #pragma unroll
                 for (int s = 0; s < S; s++) {
@@ -1243,53 +1360,7 @@ combine_kernel(SearchArgs A) {
                     if (DIVIDE) key = key / npd;
                     kmax = s == 0 ? key : __builtin_fmax(kmax, key);
                 }
-                fcount += run_feas;
-                if (__builtin_expect(__builtin_amdgcn_ballot_w64(kmax >= bsum) != 0, 0)) {
-                    // Some lane's maximum reached its best.  Usually that is a tie that cannot win:
-                    // first bound what a tie of this lane could achieve, and only if some lane can
-                    // really improve redo the slots with the real masks and the full order.
-                    asm volatile("" : "+s"(ee));
-                    uint32_t cl = cl0;
-                    asm volatile("" : "+v"(cl));
-                    const uint64_t low = base_f + sChoice[ee];  // index of the plan without the last task's part
-                    // replicas of all tasks but the last, from the entry itself: the entries of a run
-                    // share their masks, not necessarily their replica counts
-                    const int32_t w_out = W - sLim[ee].w_rem;
-                    bool maybe = kmax > bsum;
-                    const bool low_wins = low < blow;
-                    if (tie_index_only) {
-                        maybe = maybe | (cfirst < bcl) | ((cfirst == bcl) & low_wins);
-                    } else {
-                        const int32_t t = w_out + minw;
-                        maybe = maybe | (t < bw) | ((t == bw) & ((cmin < bcl) | ((cmin == bcl) & low_wins)));
-                    }
-                    if (__builtin_amdgcn_ballot_w64(maybe & (kmax >= bsum)) != 0) {
-#pragma unroll
-                        for (int s = 0; s < S; s++) {
-                            const double tprod = u.pre * a[s];
-                            double key = HAS_PRESUM ? u.presum + tprod : tprod;
-                            if (DIVIDE) key = key / npd;
-                            // which lanes have a feasible plan here that reaches their best; usually none
-                            const uint64_t hit = fm[s] & __builtin_amdgcn_ballot_w64(key >= bsum);
-                            if (hit == 0) continue;
-                            if ((hit >> lane) & 1) {
-                                const uint32_t cL = cl + s * 64;
-                                const int32_t wt = w_out + w[s];
-                                bool win = key > bsum;
-                                if (key == bsum) {
-                                    const bool idx_wins = (cL < bcl) | ((cL == bcl) & low_wins);
-                                    win = tie_index_only ? idx_wins : ((wt < bw) | ((wt == bw) & idx_wins));
-                                }
-                                if (win) {
-                                    bsum = key;
-                                    bw = wt;
-                                    bcl = cL;
-                                    blow = low;
-                                }
-                            }
-                        }
-                    }
-                }
+                bsum = __builtin_fmax(bsum, kmax);
             };
             // two records in flight: the next one is fetched while the current one is used.  The fetch
             // may reach up to two entries past the run (the tile arrays are padded for that); what it
@@ -1300,10 +1371,10 @@ combine_kernel(SearchArgs A) {
             const char *val_bytes = reinterpret_cast<const char *>(sVal);
             while (true) {
                 const MidVal uB = *reinterpret_cast<const MidVal *>(val_bytes + eb + sizeof(MidVal));
-                score(uA, e);
+                score(uA);
                 if (e + 1 >= run_hi) break;
                 uA = *reinterpret_cast<const MidVal *>(val_bytes + eb + 2 * sizeof(MidVal));
-                score(uB, e + 1);
+                score(uB);
                 if (e + 2 >= run_hi) break;
                 e += 2;
                 eb += 2 * static_cast<uint32_t>(sizeof(MidVal));
@@ -1311,33 +1382,173 @@ combine_kernel(SearchArgs A) {
             e = run_hi;
         }
         nfeas += fcount;
-        // next item
-        if (RANGE || SWAP) {
-            if (item + 1 < item_hi) locate(item + 1);
-        } else if (++r == A.mid_tiles) {
-            r = 0;
-            ++f;
-            bool carry = true;
+        } else {
+        // ---- second pass.  A slot can reach the block's key in this tile only if it does so with the
+        // tile's largest pre and presum: every operation of the key is monotone in each operand (all
+        // values are non-negative), so that is an upper bound on the slot's key with any entry.
+        double tile_pre = sTop[0][0], tile_presum = sTop[0][1];
 #pragma unroll
-            for (int j = 1; j < kMaxTasks; j++) {
-                if (j < L && carry) {
-                    if (++cj[j] == uni(sP->C[j])) {
-                        cj[j] = 0;
-                    } else {
-                        carry = false;
+        for (int v = 1; v < kWavesPerBlock; v++) {
+            tile_pre = __builtin_fmax(tile_pre, sTop[v][0]);
+            tile_presum = __builtin_fmax(tile_presum, sTop[v][1]);
+        }
+        uint32_t can = 0;  // bit s: slot s of this lane may reach the key
+#pragma unroll
+        for (int s = 0; s < S; s++) {
+            const double tprod = tile_pre * a[s];
+            double key = HAS_PRESUM ? tile_presum + tprod : tprod;
+            if (DIVIDE) key = key / npd;
+            if (lane_in && lat[s] != kNever && key >= gb) can |= 1u << s;
+        }
+        uint32_t e = __builtin_amdgcn_ballot_w64(can != 0) != 0 ? e_lo : e_hi;
+        while (e < e_hi) {
+            // ---- start of a run: the slots that are feasible with the run's limits and may reach the key
+            const MidLim ul = sLim[e];
+            uint32_t run_hi = e + 1;
+            if (!RANGE) {
+                run_hi = uni(ul.cl_lo);
+                if (run_hi > e_hi) run_hi = e_hi;
+            }
+            const int32_t w_rem = uni(ul.w_rem), tl = uni(ul.tl);
+            uint64_t fm[S];
+            int32_t amh[S];
+            // of this lane's eligible slots: fewest replicas and the lowest choice having them, and the
+            // lowest choice at all
+            int32_t minw = kNever;
+            uint32_t cmin = ~0u, cfirst = ~0u;
+            uint64_t any = 0;
+#pragma unroll
+            for (int s = S - 1; s >= 0; s--) {
+                bool ok = (w[s] <= w_rem) & (lat[s] <= tl) & (((can >> s) & 1u) != 0);
+                if (RANGE) ok = ok & ((cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt);
+                fm[s] = __builtin_amdgcn_ballot_w64(ok);
+                any |= fm[s];
+                amh[s] = ok ? __double2hiint(a[s]) : static_cast<int32_t>(0xFFE00000u);
+                if (ok) {
+                    cfirst = cl0 + s * 64;
+                    if (w[s] <= minw) {
+                        minw = w[s];
+                        cmin = cl0 + s * 64;
                     }
                 }
             }
-            if (carry) {  // every digit wrapped (or there is none): next chunk group
-                f = 0;
-                ++g;
+            if (any == 0) {
+                e = run_hi;
+                continue;
             }
+            // what any plan of this wavefront in this run has at least: the fewest replicas of the last task
+            // and the lowest choice having them (order by workers), or the lowest choice (order by index)
+            const uint32_t mw = wave_min_u32(static_cast<uint32_t>(minw));
+            const uint32_t cf = wave_min_u32(tie_index_only ? cfirst : (static_cast<uint32_t>(minw) == mw ? cmin : ~0u));
+            // The records of the run, 64 at a time: every lane looks at one entry and tells from the entry's
+            // replicas and index part alone whether a plan of this wavefront there could come before the best
+            // one found so far; only those records are scored.  (A bound taken with an older best holds for
+            // a newer one.)
+            for (uint32_t base = e; base < run_hi; base += 64) {
+            bool may = false;
+            if (base + lane < run_hi) {
+                // replicas of all tasks but the last, from the entry itself (the entries of a run share
+                // their masks, not necessarily their replica counts), and the entry's part of the index
+                const int32_t w_out_l = W - sLim[base + lane].w_rem;
+                const uint64_t low_l = base_f + sChoice[base + lane];
+                const bool idx_may = (cf < bcl) | ((cf == bcl) & (low_l < blow));
+                const int32_t t = w_out_l + static_cast<int32_t>(mw);
+                may = tie_index_only ? idx_may : ((t < bw) | ((t == bw) & idx_may));
+            }
+            uint64_t todo = __builtin_amdgcn_ballot_w64(may);
+            while (todo != 0) {
+                const uint32_t ee = base + static_cast<uint32_t>(__builtin_ctzll(todo));
+                todo &= todo - 1;
+                const int32_t w_out = W - uni(sLim[ee].w_rem);
+                const uint64_t low = base_f + uni(sChoice[ee]);
+                const MidVal u = sVal[ee];
+                double kmax = 0.0;
+#pragma unroll
+                for (int s = 0; s < S; s++) {
+                    const double am = __hiloint2double(amh[s], __double2loint(a[s]));
+                    const double tprod = u.pre * am;
+                    double key = HAS_PRESUM ? u.presum + tprod : tprod;
+                    if (DIVIDE) key = key / npd;
+                    kmax = s == 0 ? key : __builtin_fmax(kmax, key);
+                }
+                if (__builtin_amdgcn_ballot_w64(kmax >= gb) == 0) continue;
+                // some plan of this record has the block's key: the full order among them
+                bool won = false;
+#pragma unroll
+                for (int s = 0; s < S; s++) {
+                    const double tprod = u.pre * a[s];
+                    double key = HAS_PRESUM ? u.presum + tprod : tprod;
+                    if (DIVIDE) key = key / npd;
+                    const uint64_t hit = fm[s] & __builtin_amdgcn_ballot_w64(key >= gb);
+                    if (hit == 0) continue;
+                    if ((hit >> lane) & 1) {
+                        const uint32_t cL = cl0 + s * 64;
+                        const int32_t wt = w_out + w[s];
+                        const bool idx_wins = (cL < bcl) | ((cL == bcl) & (low < blow));
+                        const bool win = tie_index_only ? idx_wins : ((wt < bw) | ((wt == bw) & idx_wins));
+                        if (win) {
+                            bw = wt;
+                            bcl = cL;
+                            blow = low;
+                            won = true;
+                        }
+                    }
+                }
+                // every lane takes over the wavefront's best, which the bounds above are compared with; the
+                // block's other wavefronts learn of it through sBlk (work items that cannot do better are skipped)
+                if (__builtin_amdgcn_ballot_w64(won) != 0) {
+                    wave_first(bw, bcl, blow, tie_index_only);
+                    if (lane == 0) atomicMin(&sBlk, tie_index_only ? bcl : static_cast<uint32_t>(bw));
+                }
+            }
+            }
+            e = run_hi;
+        }
+        }
+        // next item
+        if (RANGE || SWAP) {
+            if (item + 1 < item_hi) locate(item + 1);
+        } else {
+            advance();
         }
     }
+    };
+    walk(std::false_type{});
+
+    // The block's largest key, and whether it can still be the demand point's: the largest key any block of
+    // the demand point has reported so far is kept in A.floor[m] (bit patterns of non-negative doubles order
+    // like the doubles).  A block below it cannot hold the best plan and skips the second pass; blocks that
+    // tie with it take the pass, the order among their plans is settled by the final merge.
+    {
+        const double wmax = wave_max_f64(bsum);
+        if (lane == 0) sTop[wave][0] = wmax;
+        __syncthreads();
+        double m4 = sTop[0][0];
+#pragma unroll
+        for (int v = 1; v < kWavesPerBlock; v++) m4 = __builtin_fmax(m4, sTop[v][0]);
+        // (a stand-in times a zero product is -0.0: as a key that is the key 0.0)
+        m4 = m4 > -0.5 ? m4 + 0.0 : -1.0;
+        if (threadIdx.x == 0) {
+            uint32_t go = 0;
+            if (m4 >= 0.0) {
+                const unsigned long long mine = static_cast<unsigned long long>(__double_as_longlong(m4));
+                const unsigned long long seen = atomicMax(A.floor + m, mine);
+                go = seen <= mine ? 1u : 0u;
+            }
+            sGo = go;
+            sBlk = ~0u;
+        }
+        __syncthreads();
+        gb = m4;
+    }
+    if (sGo != 0) {
+        lane_in = bsum == gb;
+        walk(std::true_type{});
+    }
     // the key is the path sum unless DIVIDE; dividing by the (power-of-two) path count is exact and monotone
-    double bacc = bsum;
-    if (!DIVIDE && bsum >= 0.0) bacc = bsum / npd;
-    const uint64_t bidx = bsum >= 0.0 ? blow + strideL * bcl : ~0ull;
+    double bacc = bw != kNever ? gb : -1.0;
+    if (!DIVIDE && bacc >= 0.0) bacc = bacc / npd;
+    const uint64_t bidx = bw != kNever ? blow + strideL * bcl : ~0ull;
     __syncthreads();
     block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
                      A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
