@@ -29,8 +29,11 @@ namespace {
 // Blocks per launch: far more than the 1024 that are resident at once, so that the hardware's own
 // block dispatch evens out compute units and demand points that finish at different times.
 constexpr uint32_t kTargetBlocks = 32768;
-constexpr uint32_t kMinTile = 256;     // shortest tile of root-task choices per work item
-constexpr uint64_t kFewItems = 8192;   // below this many work items per launch the tile is shortened
+constexpr uint32_t kMinTile = 128;     // shortest tile of root-task choices per work item
+// Below this many work items per launch the tile is shortened: a launch should have more blocks than the
+// 1280 that are resident at once.  Not sooner: the entries of a tile are walked in runs of equal limits,
+// and a longer tile has longer runs.
+constexpr uint64_t kFewItems = 2048;
 constexpr int64_t kTwo53 = int64_t(1) << 53;
 constexpr size_t kAlign = 256;
 
@@ -528,6 +531,8 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
         A.blocks_per_m = static_cast<uint32_t>(std::min<uint64_t>(
             A.blocks_per_m, std::max<uint64_t>(1, (A.items + class_items_per_block(p) - 1) / class_items_per_block(p))));
     if (A.items > (uint64_t(1) << 62) / A.blocks_per_m) A.blocks_per_m = 1;  // keep items*block in 64 bits
+    A.items_per_block = A.items / A.blocks_per_m;
+    A.items_extra = A.items % A.blocks_per_m;
     const bool range = !(index_begin == 0 && index_end == p->n_candidates);
     const int np = p->dev.n_paths;
     const bool divide = (np & (np - 1)) != 0;
@@ -623,6 +628,7 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     A.begin = index_begin;
     A.end = index_end;
     A.W = workers;
+    A.w_most_last = p->sum_r[p->n - 1];
     {
         int64_t others = 0;
         for (int i = 1; i < p->n; i++) others += p->sum_r[i];
@@ -816,6 +822,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     A.begin = index_begin;
     A.end = index_end;
     A.W = workers;
+    A.w_most_last = p->sum_r[p->n - 1];
     {
         int64_t others = 0;
         for (int i = 1; i < p->n; i++) others += p->sum_r[i];

@@ -137,12 +137,15 @@ struct SearchArgs {
     // combinations of all tasks but the last, cyclically from far_first.
     uint64_t far_first, far_span;
     uint64_t items;         // work items per demand point
+    uint64_t items_per_block, items_extra;  // items / blocks_per_m and items % blocks_per_m (tabulated kernels, whole
+                                            // launch; with swapped roles a point's own count is divided in the kernel)
     uint32_t cl_first;      // first choice of the last task touched by the range
     uint32_t chunk_groups;  // groups of chunks of the last task
     uint32_t tile_len;      // root-task choices per work item, at most kMidTile
     uint32_t mid_tiles;     // ceil(C_0 / tile_len)
     uint32_t cpb;           // chunks handled side by side in a block (1, 2 or 4)
     int32_t W;
+    int32_t w_most_last;    // sum of the replica limits of the last task: no choice of it hosts more
     int32_t w_free;         // first-task replica counts up to this never make the worker budget bind (may be < 0)
     int32_t M;
     uint32_t blocks_per_m;

@@ -587,6 +587,13 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
     return v;
 }
 
+// v_max_f64 as it stands, for operands known to be numbers.
+__device__ __forceinline__ double max_f64_instruction(double x, double y) {
+    double r;
+    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+
 // Largest value of a wavefront, in every lane.  Must be called by all 64 lanes.
 template <int STEP>
 __device__ __forceinline__ double wave_max_f64_step(double v) {
@@ -714,11 +721,13 @@ constexpr int kSortThreads = 1024;
 // never bind, whatever the other tasks choose (negative: none).  Choices at or below it leave the
 // last task the same feasibility masks, so they share a bucket per latency; the workers of a
 // winning plan are taken from its own entry, not from the run.
+// lat_sorted: the task's distinct latencies, ascending (in LDS: every choice looks all of them up, and the
+// count below has no dependent reads).
 __device__ __forceinline__ uint32_t root_bucket(const int32_t *lat_sorted, uint32_t n_lat, const TaskRec &rec,
                                                 uint32_t n_buckets, int32_t w_free) {
     if (rec.lat == kNever) return n_buckets - 1;
-    uint32_t rank = 0;
-    while (rank + 1 < n_lat && lat_sorted[rank] < rec.lat) rank++;
+    uint32_t rank = 0;  // number of latencies below this one, the last one left out
+    for (uint32_t q = 0; q + 1 < n_lat; q++) rank += lat_sorted[q] < rec.lat ? 1u : 0u;
     const int32_t wk = w_free < 0 ? rec.w : (rec.w > w_free ? rec.w - w_free : 0);
     return static_cast<uint32_t>(wk) * n_lat + rank;
 }
@@ -742,7 +751,9 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
     uint32_t *run_end = A.swap ? (tile ? A.run_end_t + static_cast<size_t>(m) * C0 : nullptr)
                                : A.run_end + static_cast<size_t>(m) * C0;
     const uint32_t n_lat = static_cast<uint32_t>(tile ? P->n_lat_t : P->n_lat0);
-    const int32_t *lat_sorted = tile ? P->lat_t_sorted : P->lat0_sorted;
+    __shared__ int32_t sLat[kMaxVariants * kMaxBatches];
+    if (threadIdx.x < n_lat) sLat[threadIdx.x] = tile ? P->lat_t_sorted[threadIdx.x] : P->lat0_sorted[threadIdx.x];
+    const int32_t *lat_sorted = sLat;  // (visible after the barrier that follows the histogram's reset)
     const int32_t w_free = tile ? A.w_free_t : A.w_free;
     const uint32_t n_buckets = runs ? static_cast<uint32_t>((tile ? P->sum_r_t : P->sum_r0) + 1) * n_lat + 1 : 2u;
     auto bucket_of = [&](const TaskRec &rec) -> uint32_t {
@@ -894,8 +905,25 @@ combine_kernel(SearchArgs A) {
     // SWAP: the number of work items depends on the point (its first-task choices times the rest)
     const uint64_t far_m = SWAP ? far_swap : A.far_span;
     const uint64_t items_m = SWAP ? static_cast<uint64_t>(A.chunk_groups) * far_m * A.mid_tiles : A.items;
-    const uint64_t item_lo = items_m * blockIdx.x / A.blocks_per_m;
-    const uint64_t item_hi = items_m * (blockIdx.x + 1) / A.blocks_per_m;
+    // Quotients of numbers that fit 32 bits are taken in 32 bits (a 64-bit division costs as much as
+    // several tile records, and a block with few work items takes a dozen of them to find its place).
+    const bool narrow = items_m <= 0xffffffffull && (SWAP || A.far_count <= 0xffffffffull);
+    auto divmod = [&](uint64_t x, uint64_t y, uint64_t &quot, uint64_t &rem) {
+        if (narrow) {
+            const uint32_t x32 = static_cast<uint32_t>(x), y32 = static_cast<uint32_t>(y);
+            const uint32_t q32 = x32 / y32;
+            quot = q32;
+            rem = x32 - q32 * y32;
+        } else {
+            quot = x / y;
+            rem = x - quot * y;
+        }
+    };
+    // the block's share of the work items: items_m / blocks each, the first items_m % blocks blocks one more
+    uint64_t per_block = A.items_per_block, extra = A.items_extra;
+    if (SWAP) divmod(items_m, A.blocks_per_m, per_block, extra);
+    const uint64_t item_lo = per_block * blockIdx.x + (blockIdx.x < extra ? blockIdx.x : extra);
+    const uint64_t item_hi = item_lo + per_block + (blockIdx.x < extra ? 1 : 0);
 
     double a[S];
     int32_t w[S], lat[S];
@@ -932,12 +960,14 @@ combine_kernel(SearchArgs A) {
     // With an index range only the combinations the range touches are visited: far_span of them,
     // cyclically from far_first (the whole space: all far_count from 0).
     auto locate = [&](uint64_t item) {
-        r = uni(static_cast<uint32_t>(item % A.mid_tiles));
-        const uint64_t t = item / A.mid_tiles;
+        uint64_t t, rr;
+        divmod(item, A.mid_tiles, t, rr);
+        r = uni(static_cast<uint32_t>(rr));
         if (SWAP) {
             // one digit per task of the work item: its position in the task's list for this point
-            uint64_t rest = t % far_m;
-            g = uni(static_cast<uint32_t>(t / far_m));
+            uint64_t rest, gg;
+            divmod(t, far_m, gg, rest);
+            g = uni(static_cast<uint32_t>(gg));
             f = 0;
 #pragma unroll
             for (int j = 0; j < kMaxTasks; j++) cj[j] = 0;
@@ -946,23 +976,27 @@ combine_kernel(SearchArgs A) {
 #pragma unroll
                 for (int j = 0; j < kMaxTasks; j++) {
                     if (j < L && j != T && ((anc_last >> j) & 1u) == static_cast<uint32_t>(pass)) {
-                        const uint32_t d = static_cast<uint32_t>(rest % cntj[j]);
-                        rest /= cntj[j];
-                        cj[j] = uni(perm_m[uni(sP->table_off[j]) + d]);
+                        uint64_t d;
+                        divmod(rest, cntj[j], rest, d);
+                        cj[j] = uni(perm_m[uni(sP->table_off[j]) + static_cast<uint32_t>(d)]);
                     }
                 }
             }
             return;
         }
-        f = uni64((A.far_first + t % A.far_span) % A.far_count);
-        g = uni(static_cast<uint32_t>(t / A.far_span));
+        uint64_t gg, ff;
+        divmod(t, A.far_span, gg, ff);
+        if (RANGE) ff = (A.far_first + ff) % A.far_count;  // (the whole space: far_first = 0, far_span = far_count)
+        f = uni64(ff);
+        g = uni(static_cast<uint32_t>(gg));
         uint64_t rest = f;
 #pragma unroll
         for (int j = 1; j < kMaxTasks; j++) {
             cj[j] = 0;
             if (j < L) {
-                cj[j] = uni(static_cast<uint32_t>(rest % sP->C[j]));
-                rest /= sP->C[j];
+                uint64_t d;
+                divmod(rest, uni(sP->C[j]), rest, d);
+                cj[j] = uni(static_cast<uint32_t>(d));
             }
         }
         cj[0] = 0;
@@ -1333,19 +1367,30 @@ combine_kernel(SearchArgs A) {
             int32_t amh[S];  // high word of the accuracy, or of a huge negative number where the plan is infeasible
             uint32_t run_feas = 0;
             const int32_t w_rem = uni(ul.w_rem), tl = uni(ul.tl);  // the same in every lane: scalar operands
+            if (!RANGE && w_rem >= A.w_most_last) {
+                // the workers left cover whatever the last task may host (eq. (3) cannot bind in this run):
+                // the latency alone decides (a choice that can never be used carries the latency kNever)
 #pragma unroll
-            for (int s = 0; s < S; s++) {
-                // one ballot per compare: the masks then come straight from the compare results
-                const bool ok_w = w[s] <= w_rem, ok_l = lat[s] <= tl;
-                uint64_t fm = __builtin_amdgcn_ballot_w64(ok_w) & __builtin_amdgcn_ballot_w64(ok_l);
-                bool ok = ok_w & ok_l;
-                if (RANGE) {
-                    const bool ok_r = (cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt;
-                    fm &= __builtin_amdgcn_ballot_w64(ok_r);
-                    ok = ok & ok_r;
+                for (int s = 0; s < S; s++) {
+                    const bool ok = lat[s] <= tl;
+                    run_feas += static_cast<uint32_t>(__builtin_popcountll(__builtin_amdgcn_ballot_w64(ok)));
+                    amh[s] = ok ? __double2hiint(a[s]) : static_cast<int32_t>(0xFFE00000u);
                 }
-                run_feas += static_cast<uint32_t>(__builtin_popcountll(fm));
-                amh[s] = ok ? __double2hiint(a[s]) : static_cast<int32_t>(0xFFE00000u);
+            } else {
+#pragma unroll
+                for (int s = 0; s < S; s++) {
+                    // one ballot per compare: the masks then come straight from the compare results
+                    const bool ok_w = w[s] <= w_rem, ok_l = lat[s] <= tl;
+                    uint64_t fm = __builtin_amdgcn_ballot_w64(ok_w) & __builtin_amdgcn_ballot_w64(ok_l);
+                    bool ok = ok_w & ok_l;
+                    if (RANGE) {
+                        const bool ok_r = (cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt;
+                        fm &= __builtin_amdgcn_ballot_w64(ok_r);
+                        ok = ok & ok_r;
+                    }
+                    run_feas += static_cast<uint32_t>(__builtin_popcountll(fm));
+                    amh[s] = ok ? __double2hiint(a[s]) : static_cast<int32_t>(0xFFE00000u);
+                }
             }
             fcount += run_feas * (run_hi - e);
             // ---- every record of the run: S*64 objectives into the lane's running maximum; an infeasible
@@ -1360,7 +1405,9 @@ combine_kernel(SearchArgs A) {
                     if (DIVIDE) key = key / npd;
                     kmax = s == 0 ? key : __builtin_fmax(kmax, key);
                 }
-                bsum = __builtin_fmax(bsum, kmax);
+                // (the instruction itself: through the builtin the compiler first re-canonicalises the
+                // loop-carried operand, one more instruction per record)
+                bsum = max_f64_instruction(bsum, kmax);
             };
             // two records in flight: the next one is fetched while the current one is used.  The fetch
             // may reach up to two entries past the run (the tile arrays are padded for that); what it
