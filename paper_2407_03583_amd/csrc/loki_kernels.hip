@@ -729,7 +729,9 @@ __device__ __forceinline__ uint32_t root_bucket(const int32_t *lat_sorted, uint3
     uint32_t rank = 0;  // number of latencies below this one, the last one left out
     for (uint32_t q = 0; q + 1 < n_lat; q++) rank += lat_sorted[q] < rec.lat ? 1u : 0u;
     const int32_t wk = w_free < 0 ? rec.w : (rec.w > w_free ? rec.w - w_free : 0);
-    return static_cast<uint32_t>(wk) * n_lat + rank;
+    // latency first, replicas ascending within a latency: consecutive runs of one latency differ only in
+    // the workers they leave, and those that leave more than the last task can ever host look alike to it
+    return rank * ((n_buckets - 1) / n_lat) + static_cast<uint32_t>(wk);
 }
 
 // Without swapped roles one launch row: the first task's choices into A.perm / A.run_end.  With swapped
@@ -841,7 +843,7 @@ combine_kernel(SearchArgs A) {
     __shared__ int64_t sLeafDn[2];
     __shared__ uint32_t sLeafStride[2];
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
-    __shared__ MidVal sVal[kMidTile + 2];  // two spare entries: the record fetch runs ahead of the run's end
+    __shared__ MidVal sVal[kMidTile + 4];  // four spare entries: the record fetch runs ahead of the run's end
     __shared__ MidLim sLim[kMidTile];
     __shared__ uint32_t sChoice[kMidTile];  // first-task choice of each tile entry (cold path only)
     __shared__ double sFac[64];             // the accuracies the path-value steps multiply by (per work item)
@@ -1346,6 +1348,9 @@ combine_kernel(SearchArgs A) {
         const uint32_t e_hi = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * (midpart + 1) / mid_split);
         if constexpr (!SETTLE) {
         uint32_t fcount = 0;  // feasible plans of this item seen by this wavefront (< 2^20)
+        int32_t amh[S];       // high word of the accuracy, or of a huge negative number where the plan is infeasible
+        uint32_t run_feas = 0;
+        int32_t prev_w = -2, prev_tl = -2;  // limits the masks were last taken for (none yet in this item)
         uint32_t e = e_lo;
         // the limits and the first record of a run are fetched during the run before it
         MidLim ul_ahead = sLim[e_lo < e_hi ? e_lo : 0];
@@ -1364,10 +1369,17 @@ combine_kernel(SearchArgs A) {
                 ul_ahead = sLim[e_next];
                 u_ahead = sVal[e_next];
             }
-            int32_t amh[S];  // high word of the accuracy, or of a huge negative number where the plan is infeasible
-            uint32_t run_feas = 0;
             const int32_t w_rem = uni(ul.w_rem), tl = uni(ul.tl);  // the same in every lane: scalar operands
-            if (!RANGE && w_rem >= A.w_most_last) {
+            // a run whose limits bind the last task like those of the run before it keeps that run's masks
+            // (the ordering kernel lines up the runs of one latency by the workers they leave)
+            const int32_t w_eff = w_rem < A.w_most_last ? w_rem : A.w_most_last;
+            const bool same_masks = !RANGE && w_eff == prev_w && tl == prev_tl;
+            prev_w = w_eff;
+            prev_tl = tl;
+            if (same_masks) {
+                // nothing to do
+            } else if (!RANGE && w_rem >= A.w_most_last) {
+                run_feas = 0;
                 // the workers left cover whatever the last task may host (eq. (3) cannot bind in this run):
                 // the latency alone decides (a choice that can never be used carries the latency kNever)
 #pragma unroll
@@ -1377,6 +1389,7 @@ combine_kernel(SearchArgs A) {
                     amh[s] = ok ? __double2hiint(a[s]) : static_cast<int32_t>(0xFFE00000u);
                 }
             } else {
+                run_feas = 0;
 #pragma unroll
                 for (int s = 0; s < S; s++) {
                     // one ballot per compare: the masks then come straight from the compare results
@@ -1409,23 +1422,34 @@ combine_kernel(SearchArgs A) {
                 // loop-carried operand, one more instruction per record)
                 bsum = max_f64_instruction(bsum, kmax);
             };
-            // two records in flight: the next one is fetched while the current one is used.  The fetch
-            // may reach up to two entries past the run (the tile arrays are padded for that); what it
-            // brings is then not used.  The entry's byte offset lives in a vector register, so that the
-            // reads take their distance as an immediate and one add per pair moves them on.
+            // Three records in flight: a record is fetched two steps before it is used, so that the read's
+            // latency is covered by the scoring of the two records before it.  The fetch may reach up to four
+            // entries past the run (the tile array is padded for that); what it brings is then not used.  The
+            // entry's byte offset lives in a vector register, so that the reads take their distance as an
+            // immediate and one add per round moves them on.
             uint32_t eb = e * static_cast<uint32_t>(sizeof(MidVal));
             asm volatile("" : "+v"(eb));
             const char *val_bytes = reinterpret_cast<const char *>(sVal);
+            auto fetch = [&](uint32_t ahead) {
+                return *reinterpret_cast<const MidVal *>(val_bytes + eb + ahead * sizeof(MidVal));
+            };
+            MidVal uB = fetch(1), uC = uA;
             while (true) {
-                const MidVal uB = *reinterpret_cast<const MidVal *>(val_bytes + eb + sizeof(MidVal));
+                uC = fetch(2);
                 score(uA);
                 if (e + 1 >= run_hi) break;
-                uA = *reinterpret_cast<const MidVal *>(val_bytes + eb + 2 * sizeof(MidVal));
+                uA = fetch(3);
                 score(uB);
                 if (e + 2 >= run_hi) break;
-                e += 2;
-                eb += 2 * static_cast<uint32_t>(sizeof(MidVal));
+                uB = fetch(4);
+                score(uC);
+                if (e + 3 >= run_hi) break;
+                e += 3;
+                eb += 3 * static_cast<uint32_t>(sizeof(MidVal));
             }
+            // (the records in flight count as used on every way out: their reads stay where they stand
+            // instead of sinking to just before their use)
+            asm volatile("" : : "v"(uA.pre), "v"(uB.pre), "v"(uC.pre));
             e = run_hi;
         }
         nfeas += fcount;
