@@ -813,8 +813,10 @@ __global__ void __launch_bounds__(kSortThreads) root_order_kernel(SearchArgs A) 
 // each wavefront walks its part of the tile.  Per run (same latency left, and the same workers
 // left or more than the last task can ever use) it takes the feasibility of its S*64 plans
 // once (eq. (3), eq. (7)); per record it
-// then only forms the S*64 objectives (one fp64 multiply, one add each), keeps
-// their running maximum, and compares that with the lanes' best.
+// then only forms the S*64 objectives (one fp64 multiply, one add each) and keeps
+// their running maximum.  That first pass leaves every lane with the largest key of its feasible
+// plans; a second pass over the same work items, taken only by blocks whose largest key can still
+// be the demand point's, settles which plan with that key comes first in the order (see the kernel).
 //
 // SWAP (per-variant factors class by class, three or more tasks): a point owns only a few
 // choices of every task that has children, too few to fill a tile.  The tile then holds the choices of
@@ -845,7 +847,7 @@ combine_kernel(SearchArgs A) {
     __shared__ __attribute__((aligned(16))) unsigned char sPraw[kHeadBytes];
     __shared__ MidVal sVal[kMidTile + 4];  // four spare entries: the record fetch runs ahead of the run's end
     __shared__ MidLim sLim[kMidTile];
-    __shared__ uint32_t sChoice[kMidTile];  // first-task choice of each tile entry (cold path only)
+    __shared__ uint32_t sChoice[kMidTile];  // first-task choice of each tile entry (second pass only)
     __shared__ double sFac[64];             // the accuracies the path-value steps multiply by (per work item)
     __shared__ BestRec sBest[kWavesPerBlock];
     __shared__ double sTop[kWavesPerBlock][2];  // per wavefront: largest pre / presum of a tile; the largest key
