@@ -88,9 +88,10 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        # LOKI_ORACLE_LIB: a test may point at a deliberately broken build of the checker to show
-        # that the pins notice (tests/test_oracle_mutants.py); otherwise the in-tree build is used
-        override = os.environ.get("LOKI_ORACLE_LIB")
+        # A test may point at a deliberately broken build of the checker to show that the pins notice
+        # (tests/test_oracle_mutants.py sets both variables for its subprocesses); LOKI_ORACLE_LIB alone
+        # is ignored, so that no other process can end up with a checker that is not the in-tree one
+        override = os.environ.get("LOKI_ORACLE_LIB") if os.environ.get("LOKI_ORACLE_MUTANT_TEST") == "1" else None
         if not override:
             build()
         L = C.CDLL(override or _LIB)

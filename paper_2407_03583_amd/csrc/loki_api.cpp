@@ -68,7 +68,10 @@ Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, ui
 // Per-variant factors searched class by class: a point of a launch is a demand point with one class (one
 // amount of created requests) per task that has children.  A batch of points per set of launches: as many
 // as keep the per-point task tables within kClassTableBytes, between 256 and 4096.
-constexpr int64_t kMaxClassPoints = 65535;
+#ifndef LOKI_CLASS_POINTS_LIMIT
+#define LOKI_CLASS_POINTS_LIMIT 65535  // (a CPU test build of the host side lowers it to reach the paths beyond it)
+#endif
+constexpr int64_t kMaxClassPoints = LOKI_CLASS_POINTS_LIMIT;
 constexpr size_t kClassTableBytes = size_t(256) << 20;
 int32_t class_batch(uint32_t table_total) {
     const size_t fit = kClassTableBytes / (size_t(std::max<uint32_t>(table_total, 1u)) * sizeof(TaskRec));
@@ -580,6 +583,11 @@ bool class_search_applies(const loki_problem *p) {
     return class_search_mode(p, 0, p->n_candidates) != 0 || class_search_mode(p, 0, 0) != 0;
 }
 
+int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers, int64_t slo_us,
+                   int64_t comm_us, uint32_t flags, uint64_t index_begin, uint64_t index_end, void *d_workspace,
+                   size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed, void **results_at,
+                   bool no_alloc);
+
 int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers,
                          int64_t slo_us, int64_t comm_us, uint32_t flags, uint64_t index_begin, uint64_t index_end,
                          void *d_workspace, size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed,
@@ -593,6 +601,13 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
         return LOKI_E_WORKSPACE;
     if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
+    // every demand point is range-checked before anything is enqueued: the points are taken in groups below,
+    // and an error in a later group must not leave the work of the earlier ones behind
+    for (int32_t m = 0; m < n_demand; m++) {
+        int64_t bound[kMaxTasks];
+        const int rc_m = task_demand(p, demand_mqps[m], bound);
+        if (rc_m) return rc_m;
+    }
     int rc = ensure_staging(p, n_demand);
     if (rc) return rc;
     const size_t per_point = kMaxTasks * (2 * sizeof(int64_t) + sizeof(uint32_t)) + sizeof(int32_t);
@@ -648,7 +663,23 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
         ClassPoints cp;
         int32_t m1 = m0;
         rc = build_class_points(p, demand_mqps, m0, n_demand, cp, &m1);
-        if (rc) return rc;  // (LOKI_E_ARG: one demand point alone has too many points; the caller falls back)
+        if (rc == LOKI_E_ARG && enqueued) {
+            // This demand point alone has more points than the descriptor arrays hold, and earlier groups are
+            // already on the stream: it is searched per lane, here, into its own result slot.  (The per-lane
+            // search lays its few buffers over the front of the workspace, which the groups before it no
+            // longer need when the stream gets there and the groups after it fill again.)
+            const uint64_t scored = p->last_scored;
+            rc = enqueue_search(p, demand_mqps + m0, 1, workers, slo_us, comm_us, flags | LOKI_SEARCH_PER_LANE,
+                                index_begin, index_end, d_workspace, workspace_bytes, stream,
+                                static_cast<unsigned char *>(G.results) + size_t(m0) * sizeof(loki_result_t), false,
+                                nullptr, false);
+            if (rc) return rc;
+            p->last_scored += scored;
+            // the constant block of the class-by-class layout is the same block; the descriptors are rewritten per group
+            m0 += 1;
+            continue;
+        }
+        if (rc) return rc;  // (LOKI_E_ARG: the first demand point alone has too many points; the caller falls back)
         const int64_t V = int64_t(cp.size());
         // per point: the combinations of the work item's tasks (swapped roles) or the first task's choices
         auto far_of = [&](int64_t v) {
@@ -754,7 +785,7 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
 int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers, int64_t slo_us,
                    int64_t comm_us, uint32_t flags, uint64_t index_begin, uint64_t index_end, void *d_workspace,
                    size_t workspace_bytes, hipStream_t stream, void *d_results, bool timed, void **results_at,
-                   bool no_alloc = false) {
+                   bool no_alloc) {
     if (!p || !demand_mqps || !d_workspace) return LOKI_E_NULL;
     if (n_demand < 1 || n_demand > LOKI_MAX_DEMAND_POINTS) return LOKI_E_ARG;
     if (no_alloc && (timed || n_demand > kNoAllocPoints)) return LOKI_E_ARG;
@@ -965,7 +996,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
                 if (lat < 1 || lat > (int64_t(1) << 30) || thr < 0 || thr > (int64_t(1) << 40)) rc = LOKI_E_RANGE;
                 d.lat[i][k][bi] = int32_t(lat);  // range-checked above
                 if (thr > (int64_t(1) << 54) / scale) rc = LOKI_E_RANGE;  // keeps 255 replicas * thr * scale below 2^63
-                d.thr_s[i][k][bi] = thr * scale;
+                if (rc == LOKI_OK) d.thr_s[i][k][bi] = thr * scale;
             }
         }
         if (rc) break;
@@ -1149,7 +1180,8 @@ int loki_alloc_search_enqueue(loki_problem_t *p, const int64_t *demand_mqps, int
                               void *d_results) {
     if (!d_results) return LOKI_E_NULL;
     return enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
-                          d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream), d_results, false, nullptr);
+                          d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream), d_results, false, nullptr,
+                          false);
 }
 
 int loki_alloc_search(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_demand, int32_t workers,
@@ -1159,7 +1191,7 @@ int loki_alloc_search(loki_problem_t *p, const int64_t *demand_mqps, int32_t n_d
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     void *d_res = nullptr;
     int rc = enqueue_search(p, demand_mqps, n_demand, workers, slo_us, comm_us, flags, index_begin, index_end,
-                            d_workspace, workspace_bytes, stream, nullptr, true, &d_res);
+                            d_workspace, workspace_bytes, stream, nullptr, true, &d_res, false);
     if (rc) return rc;
     unsigned char *hres = p->staging + const_block(p) +
                           align_up(size_t(p->cap_points) * kMaxTasks * sizeof(int64_t));

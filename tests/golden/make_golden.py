@@ -1,10 +1,18 @@
 """Write tests/golden/cfg<N>.json: full-space search results of the benchmark
-configurations, computed by the CPU checker only (oracle/'s tabulated walk,
-which tests/test_oracle_pins.py checks against the plain per-index search).
+configurations, computed by the CPU checker only.  Every file says in `written_by`
+which of the checker's two searches produced it:
+  --plain   oracle.Problem.search: lo_eval on every index, the definition itself
+            (configs 1 and 2: seconds to a minute on 8 cores);
+  default   oracle.Problem.search_tabulated: the same two functions composed through a
+            per-task table while an odometer walks the indices -- what makes 2^38 .. 2^40
+            evaluations affordable (configs 3 - 5).  tests/test_oracle_pins.py checks it
+            against the plain search in full on small problems and on slices of every
+            config, and tests/test_oracle_pins.py::test_config5_golden_from_single_plan_
+            evaluations re-derives config 5's stored result from lo_eval alone.
 
-Usage: python tests/golden/make_golden.py [--threads T] cfg [cfg ...]
-Runtime on 8 cores: cfg 1-2 seconds, cfg 3 about 3 minutes, cfg 4 about
-25 minutes, cfg 5 about 1.6 hours (5,829 s measured).
+Usage: python tests/golden/make_golden.py [--threads T] [--plain] cfg [cfg ...]
+Runtime on 8 cores: cfg 1-2 seconds (--plain: cfg 2 about half a minute), cfg 3 about
+3 minutes, cfg 4 about 25 minutes, cfg 5 about 1.6 hours (5,829 s measured).
 
        python tests/golden/make_golden.py --variants
 writes tests/golden/variants.json: the optional parts of the model on the 2^30-plan
@@ -78,6 +86,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--variants", action="store_true")
+    ap.add_argument("--plain", action="store_true", help="lo_eval on every index instead of the tabulated walk")
     ap.add_argument("cfgs", type=int, nargs="*")
     args = ap.parse_args()
     if args.variants:
@@ -85,17 +94,19 @@ def main():
     for cfg in args.cfgs:
         w = wl.config(cfg)
         prob = oracle.Problem(w.pipeline)
+        search = prob.search if args.plain else prob.search_tabulated
         doc = dict(config=cfg, name=w.name, seed=w.seed, workload_digest=w.digest(),
                    n_candidates=prob.num_candidates(), workers=w.workers, slo_us=w.slo_us, comm_us=w.comm_us,
-                   written_by="tests/golden/make_golden.py (oracle.Problem.search_tabulated)",
+                   written_by="tests/golden/make_golden.py --plain (oracle.Problem.search: lo_eval on every index)"
+                   if args.plain else "tests/golden/make_golden.py (oracle.Problem.search_tabulated)",
                    results=[], results_index_only=[])
         t0 = time.time()
         for m, d in enumerate(w.demand_mqps):
-            b = prob.search_tabulated(d, w.workers, w.slo_us, w.comm_us, threads=args.threads)
+            b = search(d, w.workers, w.slo_us, w.comm_us, threads=args.threads)
             doc["results"].append(record(b, d))
             if m < INDEX_ONLY_POINTS[cfg]:
-                b = prob.search_tabulated(d, w.workers, w.slo_us, w.comm_us, tie_index_only=True,
-                                          threads=args.threads)
+                b = search(d, w.workers, w.slo_us, w.comm_us, tie_index_only=True,
+                           threads=args.threads)
                 doc["results_index_only"].append(record(b, d))
             print(f"cfg {cfg} point {m + 1}/{len(w.demand_mqps)} {time.time() - t0:.0f}s", flush=True)
         doc["seconds"] = round(time.time() - t0, 1)

@@ -632,3 +632,75 @@ def test_hardware_scaling_step_is_the_search_over_the_most_accurate_variants():
             best_possible = sum((math.prod(top[i] for i in path) for path in paths), Fraction(0)) / len(paths)
             assert Fraction(full.accuracy) < best_possible
     assert step1_feasible >= 15 and step2_only >= 3
+
+
+# ---- the stored full-size results against single-plan evaluations ---------------------------------
+
+def test_stored_results_say_which_search_wrote_them():
+    """Configs 1 and 2 are stored from the plain per-index search; 3 - 5 from the tabulated walk."""
+    for cfg in (1, 2, 3, 4, 5):
+        with open(os.path.join(HERE, "golden", f"cfg{cfg}.json")) as f:
+            doc = json.load(f)
+        plain = "oracle.Problem.search:" in doc["written_by"]
+        assert plain == (cfg <= 2), (cfg, doc["written_by"])
+        assert plain or "search_tabulated" in doc["written_by"]
+
+
+def test_config5_golden_from_single_plan_evaluations():
+    """Config 5's stored result (2^40 plans, written by the tabulated walk) re-derived from lo_eval alone.
+
+    With one factor per edge a task's demand does not depend on the other tasks, so whether a task's part
+    of a plan serves its demand and hosts something is a property of that task's choice; a plan with one
+    unusable choice is infeasible whatever the rest (eq. (2)).  So: find each task's usable choices by
+    evaluating plans that differ from a usable base plan in that task only, evaluate every combination of
+    usable choices with lo_eval, count the feasible ones and keep the best under the order."""
+    with open(os.path.join(HERE, "golden", "cfg5.json")) as f:
+        doc = json.load(f)
+    w = wl.config(5)
+    assert w.digest() == doc["workload_digest"]
+    p = w.pipeline
+    prob = oracle.Problem(p)
+    D, W, slo = w.demand_mqps[0], w.workers, w.slo_us
+    want = doc["results"][0]
+    C = [1024] * 4
+    stride = [1, 1024, 1024 ** 2, 1024 ** 3]
+    usable = []
+    for i in range(4):
+        mine = []
+        for c in range(C[i]):
+            e = prob.eval(c * stride[i], D, 10 ** 6, 10 ** 12)   # every other task at choice 0
+            hosted = e.task_maxlat[i] > 0                         # some variant of the task is in use
+            if hosted and e.task_unserved[i] == 0:
+                mine.append(c)
+        usable.append(mine)
+    combos = 1
+    for u in usable:
+        combos *= len(u)
+    assert 108 <= combos < 20_000_000, [len(u) for u in usable]   # 8.9 million: about 15 s of lo_eval calls
+    import ctypes
+    lo_eval, pipe, e = oracle.lib().lo_eval, ctypes.byref(prob.c), oracle.EvalOut()
+    out = ctypes.byref(e)
+    n_feasible, best = 0, None
+    for c3 in usable[3]:
+        for c2 in usable[2]:
+            for c1 in usable[1]:
+                base = 1024 * c1 + 1024 ** 2 * c2 + 1024 ** 3 * c3
+                for c0 in usable[0]:
+                    lo_eval(pipe, base + c0, D, W, slo, w.comm_us, out)
+                    if e.infeasible:
+                        continue
+                    n_feasible += 1
+                    key = (-e.accuracy, e.workers, base + c0)
+                    if best is None or key < best:
+                        best = key
+    assert n_feasible == want["n_feasible"] == 108
+    assert (best[2], best[1], float(-best[0]).hex()) == (want["index"], want["workers"], want["accuracy_hex"])
+    # and a plan with an unusable choice is indeed infeasible whatever the rest: spot checks
+    rng = random.Random(5)
+    for _ in range(2000):
+        i = rng.randrange(4)
+        bad = rng.choice([c for c in range(1024) if c not in set(usable[i])])
+        c = [rng.choice(usable[j]) for j in range(4)]
+        c[i] = bad
+        e = prob.eval(sum(c[j] * stride[j] for j in range(4)), D, W, slo, w.comm_us)
+        assert e.infeasible & (oracle.BAD_DEMAND | oracle.BAD_EMPTY)
