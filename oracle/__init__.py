@@ -47,7 +47,8 @@ class _Pipeline(C.Structure):
                 ("thr_mqps", C.POINTER(C.c_int64)),
                 ("variant_factor_q4", C.POINTER(C.c_int32)),
                 ("per_variant_batch", C.c_int32),
-                ("path_acc_ppm", C.POINTER(C.c_int32))]
+                ("path_acc_ppm", C.POINTER(C.c_int32)),
+                ("latency_per_path", C.c_int32)]
 
 
 class EvalOut(C.Structure):
@@ -162,7 +163,8 @@ class Problem:
                            else C.POINTER(C.c_int32)(),
                            1 if getattr(pipeline, "per_variant_batch", False) else 0,
                            C.cast(k["path_acc_ppm"], C.POINTER(C.c_int32)) if pt is not None
-                           else C.POINTER(C.c_int32)())
+                           else C.POINTER(C.c_int32)(),
+                           1 if getattr(pipeline, "latency_per_path", False) else 0)
         self.per_variant_batch = bool(getattr(pipeline, "per_variant_batch", False))
 
     def num_candidates(self) -> int:

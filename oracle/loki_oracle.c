@@ -214,8 +214,10 @@ static void task_eval(const lo_pipeline *p, const lo_layout *L, int i, const int
 }
 
 /* ---- the pipeline part: budget, latency, objective -------------------------- */
+/* task_latency_bound: take the latency verdict from the per-task bound (sum over a task path of the
+ * largest latency in use); 0 leaves the latency out, for the caller that applies eq. (7) path by path. */
 static void pipeline_eval(const lo_pipeline *p, const lo_task_t *t, const int64_t *Dn, int32_t workers_cap,
-                          int64_t slo_us, int64_t comm_us, lo_eval_t *out)
+                          int64_t slo_us, int64_t comm_us, int task_latency_bound, lo_eval_t *out)
 {
     int n = p->n_tasks;
     int mask = 0;
@@ -248,7 +250,7 @@ static void pipeline_eval(const lo_pipeline *p, const lo_task_t *t, const int64_
             len++;
         }
         int64_t room = slo_us - comm_us * (int64_t)len; /* communication latency per server on the path */
-        if (room < 0 || lat > room / 2)                /* SLO halved for queueing; eq. (7) */
+        if (task_latency_bound && (room < 0 || lat > room / 2)) /* SLO halved for queueing; eq. (7) */
             mask |= LO_BAD_LATENCY;
     }
     out->infeasible = mask;
@@ -378,6 +380,86 @@ static double path_objective(const lo_pipeline *p, const lo_layout *L, uint64_t 
     return total / (double)n_paths;
 }
 
+/* ---- eq. (7) as printed: the latency of every variant path with traffic ------------------------
+ * A variant path p (one variant per task of a root-to-leaf task path) has traffic, I(p) = 1 in
+ * Table 1, when every hop of it carries requests under the routing Algorithm 1 produces for the plan:
+ * the frontend sends requests to the root's variant, and the routing table of every variant on the
+ * path sends some of its requests to the next one.  At zero demand nothing is routed; the path of the
+ * first hosted variants then stands for the plan, as for the accuracy. */
+typedef struct {
+    const lo_pipeline *p;
+    const lo_layout *L;
+    const lo_route_t *r;
+    const int32_t *x;
+    const int *path;
+    int len;
+    int64_t limit;
+    int violated;
+} lo_latency_walk;
+
+static void latency_walk(lo_latency_walk *c, int depth, int prev_variant, int64_t so_far)
+{
+    const lo_pipeline *p = c->p;
+    int i = c->path[depth], K = p->n_variants[i];
+    int order[LO_MAX_VARIANTS];
+    route_order(p, c->L, i, order);
+    int first_hosted = -1;
+    for (int o = 0; o < K && first_hosted < 0; o++)
+        if (c->x[c->L->voff[i] + order[o]] > 0)
+            first_hosted = order[o];
+    int has_traffic = depth == 0 ? c->r->demand[0] > 0 : c->r->routed[c->path[depth - 1]][prev_variant] > 0;
+    for (int k = 0; k < K; k++) {
+        int taken;
+        if (has_traffic)
+            taken = (depth == 0 ? c->r->prob[0][0][k] : c->r->prob[i][prev_variant][k]) > 0.0;
+        else
+            taken = k == first_hosted;
+        if (!taken)
+            continue;
+        int64_t lat = so_far + c->r->budget_us[i][k]; /* l(i,k) at the variant's configured batch size */
+        if (depth == c->len - 1) {
+            if (lat > c->limit)
+                c->violated = 1;
+        } else {
+            latency_walk(c, depth + 1, k, lat);
+        }
+    }
+}
+
+static int latency_violated_on_some_path(const lo_pipeline *p, const lo_layout *L, uint64_t index,
+                                         int64_t demand_mqps, int64_t slo_us, int64_t comm_us)
+{
+    lo_route_t r;
+    int32_t x[LO_MAX_TASKS * LO_MAX_VARIANTS], beta[LO_MAX_TASKS * LO_MAX_VARIANTS];
+    int n = p->n_tasks;
+    lo_route_table(p, index, demand_mqps, &r);
+    lo_decode(p, index, x, beta);
+    int is_leaf[LO_MAX_TASKS];
+    for (int i = 0; i < n; i++)
+        is_leaf[i] = 1;
+    for (int i = 1; i < n; i++)
+        is_leaf[p->parent[i]] = 0;
+    int violated = 0;
+    for (int leaf = 0; leaf < n; leaf++) {
+        if (!is_leaf[leaf])
+            continue;
+        int rev[LO_MAX_TASKS], path[LO_MAX_TASKS], len = 0;
+        for (int i = leaf; i >= 0; i = p->parent[i])
+            rev[len++] = i;
+        for (int s = 0; s < len; s++)
+            path[s] = rev[len - 1 - s];
+        int64_t room = slo_us - comm_us * (int64_t)len; /* communication latency per server on the path */
+        if (room < 0) {
+            violated = 1;
+            continue;
+        }
+        lo_latency_walk c = {p, L, &r, x, path, len, room / 2 /* SLO halved for queueing */, 0};
+        latency_walk(&c, 0, 0, 0);
+        violated |= c.violated;
+    }
+    return violated;
+}
+
 void lo_eval(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, int32_t workers, int64_t slo_us,
              int64_t comm_us, lo_eval_t *out)
 {
@@ -396,7 +478,14 @@ void lo_eval(const lo_pipeline *p, uint64_t index, int64_t demand_mqps, int32_t 
             Dn[i] = t[p->parent[i]].outflow * (int64_t)p->fanout_q4[i];
         task_eval(p, &L, i, x, beta, Dn[i], scale[i], &t[i], NULL);
     }
-    pipeline_eval(p, t, Dn, workers, slo_us, comm_us, out);
+    pipeline_eval(p, t, Dn, workers, slo_us, comm_us, !p->latency_per_path, out);
+    if (p->latency_per_path && !(out->infeasible & (LO_BAD_DEMAND | LO_BAD_EMPTY)) &&
+        latency_violated_on_some_path(p, &L, index, demand_mqps, slo_us, comm_us)) {
+        out->infeasible |= LO_BAD_LATENCY; /* eq. (7) on a variant path with traffic */
+        out->accuracy = 0.0;
+        for (int i = 0; i < L.n; i++)
+            out->task_acc[i] = 0.0;
+    }
     if (p->path_acc_ppm && !out->infeasible)
         out->accuracy = path_objective(p, &L, index, demand_mqps);
 }
@@ -493,7 +582,7 @@ void lo_search_tabulated(const lo_pipeline *p, int64_t demand_mqps, int32_t work
     lo_layout L;
     int64_t Dn[LO_MAX_TASKS], scale[LO_MAX_TASKS];
     lo_task_t *table[LO_MAX_TASKS];
-    if (p->variant_factor_q4 || p->path_acc_ppm) { /* a task's demand is not fixed / the objective couples tasks: no table */
+    if (p->variant_factor_q4 || p->path_acc_ppm || p->latency_per_path) { /* a task's demand is not fixed / the objective or the latency limit couples tasks: no table */
         lo_search(p, demand_mqps, workers, slo_us, comm_us, tie_index_only, index_begin, index_end, 1, n_threads, out);
         return;
     }
@@ -528,7 +617,7 @@ void lo_search_tabulated(const lo_pipeline *p, int64_t demand_mqps, int32_t work
             lo_eval_t e;
             for (int i = 0; i < L.n; i++)
                 t[i] = table[i][choice[i]];
-            pipeline_eval(p, t, Dn, workers, slo_us, comm_us, &e);
+            pipeline_eval(p, t, Dn, workers, slo_us, comm_us, 1, &e);
             if (!e.infeasible) {
                 b.n_feasible++;
                 if (better(e.accuracy, e.workers, index, &b, tie_index_only)) {

@@ -20,7 +20,10 @@
  *     (Algorithm 1's fill rule),
  *   - every root-to-leaf path's processing latency within half of the SLO
  *     after the per-hop communication latency is deducted (eq. (6), (7),
- *     the SLO halving and the communication-latency paragraph of Section 4.2),
+ *     the SLO halving and the communication-latency paragraph of Section 4.2);
+ *     per task path the sum of the largest in-use latency of every task, or
+ *     with latency_per_path eq. (7) itself: the latency of every variant path
+ *     that carries traffic under Algorithm 1's routing,
  *   - pipeline accuracy = mean over root-to-leaf paths of the product of the
  *     tasks' traffic-weighted accuracies (Section 2.1's pipeline accuracy,
  *     eq. (12) objective); or, when profiled end-to-end accuracies of the
@@ -42,10 +45,11 @@
  * Pins: tests/test_oracle_*.py (hand-derived worked example, closed forms,
  * exact-rational brute force, invariants, and an LP / MILP solver on the
  * paper's own formulation where the two must agree: product tables, task paths
- * of two tasks, latency not binding).  Unpinned: the paper's MILP optimum with
- * unbounded replica counts, with a binding latency limit (its limit is per
- * variant path, the search's per task) or on longer paths (solver-chosen path
- * ratios can beat hop-by-hop routing there).
+ * of two tasks, latency not binding; with latency_per_path the feasible set
+ * against the formulation's own eq. (7) for the routing Algorithm 1 produces).
+ * Unpinned: the paper's MILP optimum with unbounded replica counts, and on
+ * longer paths or with a binding latency limit where solver-chosen path
+ * ratios can beat hop-by-hop routing.
  */
 #ifndef LOKI_ORACLE_H
 #define LOKI_ORACLE_H
@@ -85,6 +89,13 @@ typedef struct {
     const int32_t *path_acc_ppm; /* NULL, or A-hat(p) in ppm: concat over the leaves in ascending task index;
                                     a leaf's table has one entry per combination of variants of the tasks
                                     root..leaf, entry = sum_j k_j * prod_{j'<j} K_j' (root least significant) */
+    int32_t latency_per_path;    /* 0: a task path's latency is the sum over its tasks of the largest latency
+                                    among the variants in use (an upper bound on what eq. (7) limits).
+                                    1: eq. (7) as printed: every variant path p with traffic (I(p) = 1 in
+                                    Table 1, i.e. every hop of p carries requests under Algorithm 1's routing)
+                                    has sum_{(i,k) in p} l(i,k) within the budget.  The latency bit is then
+                                    taken only for plans that serve all demand at every task (the routing of
+                                    a plan that does not is not the one the plan would run with). */
 } lo_pipeline;
 
 typedef struct {

@@ -134,10 +134,15 @@ def evaluate(p, index: int, demand_mqps: int, workers: int, slo_us: int, comm_us
             path.append(i)
             i = tasks[i]["parent"]
         paths.append(path[::-1])
-    for path in paths:
-        room = slo_us - comm_us * len(path)
-        if room < 0 or sum(lat_task[i] for i in path) > room // 2:
+    if getattr(p, "latency_per_path", False):
+        # eq. (7) itself: every variant path that carries traffic, for plans that serve all demand
+        if not mask & (BAD_DEMAND | BAD_EMPTY) and slow_path_with_traffic(p, index, demand_mqps, slo_us, comm_us):
             mask |= BAD_LATENCY
+    else:
+        for path in paths:
+            room = slo_us - comm_us * len(path)
+            if room < 0 or sum(lat_task[i] for i in path) > room // 2:
+                mask |= BAD_LATENCY
     out = dict(infeasible=mask, workers=used_workers, accuracy=0.0, task_lat=lat_task)
     if mask == 0 and getattr(p, "path_acc_ppm", None) is not None:
         out["exact"] = path_objective_exact(p, index, demand_mqps)
@@ -270,3 +275,63 @@ def path_objective_exact(p, index: int, demand_mqps: int) -> Fraction:
             n *= s_
         offset += n
     return total / len(leaves)
+
+
+def variant_paths_with_traffic(p, index: int, demand_mqps: int):
+    """Per root-to-leaf task path: the variant paths (one variant per task) every hop of which carries
+    requests -- I(p) = 1 in the paper's Table 1.  Taken from the intervals of placement(): a downstream
+    variant gets requests from an upstream one exactly when their intervals of the downstream task's request
+    stream overlap in more than a point.  At zero demand the path of the first hosted variants."""
+    tasks, plan, demand, spans, created = placement(p, index, demand_mqps)
+    leaves = [i for i in range(len(tasks)) if all(t["parent"] != i for t in tasks)]
+
+    def by_accuracy(i, ks):
+        return sorted(ks, key=lambda k: (-tasks[i]["variants"][k]["acc"], k))
+
+    def upstream_span(i, par, kp):
+        order = by_accuracy(par, created[par])
+        lo = sum((created[par][k] for k in order[:order.index(kp)]), Fraction(0)) * tasks[i]["fan"]
+        return lo, lo + created[par][kp] * tasks[i]["fan"]
+
+    out = []
+    for leaf in leaves:
+        path, i = [], leaf
+        while i >= 0:
+            path.append(i)
+            i = tasks[i]["parent"]
+        path = path[::-1]
+        found = []
+
+        def walk(depth, chosen):
+            i = path[depth]
+            if depth == 0:
+                lo, hi = Fraction(0), demand[0]
+            else:
+                lo, hi = upstream_span(i, path[depth - 1], chosen[-1])
+            if hi == lo:
+                hosted = by_accuracy(i, [k for k in range(len(plan[i][0])) if plan[i][0][k] > 0])
+                nxt = hosted[:1]
+            else:
+                nxt = [k for k, (a, b) in spans[i].items() if min(b, hi) - max(a, lo) > 0]
+            for k in nxt:
+                if depth == len(path) - 1:
+                    found.append(tuple(chosen + [k]))
+                else:
+                    walk(depth + 1, chosen + [k])
+
+        walk(0, [])
+        out.append((path, found))
+    return out
+
+
+def slow_path_with_traffic(p, index: int, demand_mqps: int, slo_us: int, comm_us: int) -> bool:
+    tasks = _tables(p)
+    plan = decode(p, index)
+    for path, found in variant_paths_with_traffic(p, index, demand_mqps):
+        room = slo_us - comm_us * len(path)
+        if room < 0:
+            return True
+        for ks in found:
+            if sum(tasks[i]["variants"][k]["lat"][plan[i][1][k]] for i, k in zip(path, ks)) > room // 2:
+                return True
+    return False

@@ -55,6 +55,20 @@ MUTANTS = [
      "path_walk(c, depth + 1, k, m, e, stride);"),
     ("frontend split ignored at the root", "share = depth == 0 ? c->r->prob[0][0][k] : c->r->prob[i][prev_variant][k];",
      "share = depth == 0 ? (k == first_hosted ? 1.0 : 0.0) : c->r->prob[i][prev_variant][k];"),
+    # eq. (7) on the variant paths with traffic
+    ("every pairing of in-use variants counts as a path with traffic",
+     "taken = (depth == 0 ? c->r->prob[0][0][k] : c->r->prob[i][prev_variant][k]) > 0.0;",
+     "taken = c->r->routed[i][k] > 0;"),
+    ("routing table of the path's latency read transposed",
+     "taken = (depth == 0 ? c->r->prob[0][0][k] : c->r->prob[i][prev_variant][k]) > 0.0;",
+     "taken = (depth == 0 ? c->r->prob[0][0][k] : c->r->prob[i][k][prev_variant]) > 0.0;"),
+    ("latency so far not carried down the path", "latency_walk(c, depth + 1, k, lat);", "latency_walk(c, depth + 1, k, 0);"),
+    ("path latency at the budget counted as a violation", "if (lat > c->limit)", "if (lat >= c->limit)"),
+    ("SLO of the per-path rule not halved", "room / 2 /* SLO halved for queueing */", "room /* SLO halved for queueing */"),
+    ("per-path rule on, per-task bound still applied",
+     "pipeline_eval(p, t, Dn, workers, slo_us, comm_us, !p->latency_per_path, out);",
+     "pipeline_eval(p, t, Dn, workers, slo_us, comm_us, 1, out);"),
+    ("only the first leaf's paths checked", "violated |= c.violated;", "violated |= c.violated; break;"),
 ]
 
 
@@ -70,7 +84,8 @@ def test_pins_catch_a_planted_mistake(what, old, new):
                         "-I", os.path.join(ROOT, "oracle"), "-o", lib, src], check=True)
         env = dict(os.environ, LOKI_ORACLE_LIB=lib, LOKI_ORACLE_MUTANT_TEST="1")
         r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
-                            os.path.join(ROOT, "tests", "test_oracle_path_tables.py"), "-x", "-q", "-p", "no:cacheprovider",
+                            os.path.join(ROOT, "tests", "test_oracle_path_tables.py"),
+                            os.path.join(ROOT, "tests", "test_oracle_latency_per_path.py"), "-x", "-q", "-p", "no:cacheprovider",
                             "-k", "not slices and not zero_demand and not symmetry and not config5_golden"],
                            env=env, cwd=ROOT, capture_output=True, text=True, timeout=600)
         assert r.returncode != 0, f"no pin noticed: {what}\n{r.stdout[-800:]}"
