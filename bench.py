@@ -88,6 +88,9 @@ def main() -> int:
     ap.add_argument("--path-tables", action="store_true",
                     help="objective from seeded profiled path accuracies (feasibility from the per-task tables; "
                          "one value per leaf on trees, a walk over the variant paths of feasible plans on chains)")
+    ap.add_argument("--latency-per-path", action="store_true",
+                    help="eq. (7) on every variant path with traffic instead of the per-task bound "
+                         "(whole plans per lane: the library takes that kernel under this rule)")
     ap.add_argument("--demand-qps", type=float, default=None,
                     help="replace the configuration's demand points by this one demand (queries/s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -118,6 +121,9 @@ def main() -> int:
     if args.path_tables:
         w.pipeline.path_acc_ppm = wl.draw_path_tables(w.pipeline, wl.SplitMix64(w.seed + 1))
         variant.append("path_tables")
+    if args.latency_per_path:
+        w.pipeline.latency_per_path = True
+        variant.append("latency_per_path")
     if args.demand_qps is not None:
         w.demand_mqps = [int(round(args.demand_qps * 1000))]
         variant.append(f"demand{args.demand_qps:g}qps")
@@ -126,6 +132,7 @@ def main() -> int:
     # what the library does anyway: per-variant factors are searched class by class by the tabulated kernels
     # (two or more tasks); profiled path accuracies with the feasibility part tabulated and the variant paths
     # walked for feasible plans only
+    args.per_lane = args.per_lane or args.latency_per_path
     by_class = args.variant_factors and w.pipeline.n_tasks >= 2 and not args.per_lane
     args.per_lane = args.per_lane or (args.variant_factors and not by_class)
     P = binding.Problem(w.pipeline)

@@ -149,6 +149,23 @@ typedef struct {
                                     64 variant combinations above every leaf) it forms each leaf's sum once
                                     for all the plans that share the choices along that leaf's path (whole
                                     plans per lane with LOKI_SEARCH_PER_LANE; same results). */
+    int32_t latency_per_path;    /* How eq. (7) is applied (Section 4.1 "Latency", eq. (6), (7), Table 1's I(p)).
+                                    0: per root-to-leaf task path, the sum over its tasks of the largest latency
+                                    among the task's variants in use must meet the halved SLO.  That sum bounds
+                                    the latency of every variant path from above, and is attained by a path
+                                    with traffic wherever a task's latency grows with its accuracy (Algorithm 1
+                                    pairs the most accurate variants in use of consecutive tasks); it lets
+                                    feasibility be tabulated per task.
+                                    1: eq. (7) as stated: every variant path that carries requests under
+                                    Algorithm 1's routing (the frontend reaches the root's variant, and each
+                                    variant's routing table gives the next one a nonzero probability) must meet
+                                    it, at each variant's configured batch size; variant paths without traffic
+                                    limit nothing.  At zero demand the first hosted variants stand for the plan.
+                                    LOKI_BAD_LATENCY is then reported only for plans that host every task and
+                                    serve all demand (the routing of the others is not defined).  A plan that
+                                    is feasible under 0 is feasible under 1.  Searches score whole plans per
+                                    lane under this rule (LOKI_SEARCH_PER_LANE is implied): the per-task bound
+                                    decides most plans, the others walk their variant paths. */
 } loki_pipeline_t;
 
 typedef struct loki_problem loki_problem_t; /* opaque handle */

@@ -47,9 +47,9 @@
  * paper's own formulation where the two must agree: product tables, task paths
  * of two tasks, latency not binding; with latency_per_path the feasible set
  * against the formulation's own eq. (7) for the routing Algorithm 1 produces).
- * Unpinned: the paper's MILP optimum with unbounded replica counts, and on
- * longer paths or with a binding latency limit where solver-chosen path
- * ratios can beat hop-by-hop routing.
+ * Unpinned: the paper's MILP optimum with unbounded replica counts, and the
+ * optimum over solver-chosen path ratios on longer paths or with a binding
+ * latency limit, which can beat hop-by-hop routing.
  */
 #ifndef LOKI_ORACLE_H
 #define LOKI_ORACLE_H

@@ -53,7 +53,8 @@ class PipelineC(C.Structure):
                 ("thr_mqps", C.POINTER(C.c_int64)),
                 ("variant_factor_q4", C.POINTER(C.c_int32)),
                 ("per_variant_batch", C.c_int32),
-                ("path_acc_ppm", C.POINTER(C.c_int32))]
+                ("path_acc_ppm", C.POINTER(C.c_int32)),
+                ("latency_per_path", C.c_int32)]
 
 
 class Result(C.Structure):
@@ -175,7 +176,8 @@ def _pipeline_struct(p):
     s = PipelineC(int(p.n_tasks), *[C.cast(a, C.POINTER(a._type_)) for a in keep],
                   C.cast(vf_arr, C.POINTER(C.c_int32)) if vf_arr is not None else C.POINTER(C.c_int32)(),
                   1 if getattr(p, "per_variant_batch", False) else 0,
-                  C.cast(pt_arr, C.POINTER(C.c_int32)) if pt_arr is not None else C.POINTER(C.c_int32)())
+                  C.cast(pt_arr, C.POINTER(C.c_int32)) if pt_arr is not None else C.POINTER(C.c_int32)(),
+                  1 if getattr(p, "latency_per_path", False) else 0)
     keep.extend([vf_arr, pt_arr])
     return s, keep
 

@@ -793,6 +793,8 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     if (index_begin > index_end || index_end > p->n_candidates) return LOKI_E_ARG;
     int rc = check_scalars(workers, slo_us, comm_us);
     if (rc) return rc;
+    // eq. (7) on the variant paths with traffic couples the tasks of a path: whole plans per lane
+    if (p->dev.lat_per_path) flags |= LOKI_SEARCH_PER_LANE;
     // Per-variant factors: a task's demand depends on its parent's part of the plan.  Where every other
     // task is a child of the first one, that dependence is one number per first-task choice (the requests
     // it creates), and the tabulated kernels run once per distinct value; otherwise whole plans per lane.
@@ -890,7 +892,8 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         int path_levels = 0;
         if (p->dev.has_path)
             for (int i = 0; i < n; i++) path_levels = std::max(path_levels, p->dev.path_len[i]);
-        LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, path_levels, stream));
+        LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, path_levels,
+                                        p->dev.lat_per_path != 0, stream));
         if (timed) LOKI_HIP(hipEventRecord(p->ev[2], stream));
         LOKI_HIP(launch_final_reduce(A, stream));
     } else {
@@ -925,7 +928,9 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
     d.n_tasks = n;
     d.has_vf = in->variant_factor_q4 ? 1 : 0;
     d.pv_batch = in->per_variant_batch ? 1 : 0;
-    if (in->per_variant_batch != 0 && in->per_variant_batch != 1) {
+    d.lat_per_path = in->latency_per_path ? 1 : 0;
+    if ((in->per_variant_batch != 0 && in->per_variant_batch != 1) ||
+        (in->latency_per_path != 0 && in->latency_per_path != 1)) {
         delete p;
         return LOKI_E_RANGE;
     }

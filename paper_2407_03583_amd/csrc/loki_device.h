@@ -68,6 +68,8 @@ struct DevProblem {
     int32_t n_lat_t;
     int32_t sum_r_t;
     int32_t lat_t_sorted[kMaxVariants * kMaxBatches];
+    int32_t lat_per_path;                   // eq. (7) on every variant path with traffic instead of the per-task bound
+    int32_t pad3;
 };
 
 // What a task contributes to any plan that uses one of its choices

@@ -98,6 +98,8 @@ struct TaskOut {
     int64_t weighted;   // sum routed * acc_ppm
     int32_t first_acc;  // accuracy of the first hosted variant in route order
     int64_t outflow;    // sum routed * variant factor: what the task creates per unit of child fan-out
+    int32_t lat_top;    // latency of the first variant in use in route order (the most accurate one)
+    int32_t lat_bot;    // latency of the last variant in use in route order
 };
 
 // Decode choice c of task i (variant 0 least significant; the batch digit on top, or a batch
@@ -132,7 +134,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     }
     const uint32_t beta_task = c;
     int64_t rem = Dn, weighted = 0, outflow = 0;
-    int32_t any = 0, first_acc = 0, maxlat = 0;
+    int32_t any = 0, first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
     constexpr bool has_vf = VF;
     for (int r = 0; r < K; r++) {
         const int k = P->order[i][r];
@@ -145,7 +147,11 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         const bool hosted = x > 0;
         const bool used = hosted && (routed > 0 || !any);
         if (used && lat > maxlat) maxlat = lat;
-        if (hosted && !any) first_acc = acc;
+        if (used) lat_bot = lat;
+        if (hosted && !any) {
+            first_acc = acc;
+            lat_top = lat;
+        }
         weighted += routed * static_cast<int64_t>(acc);
         if (has_vf) outflow += routed * static_cast<int64_t>(P->vf[i][k]);
         rem -= routed;
@@ -158,6 +164,8 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     o.weighted = weighted;
     o.first_acc = first_acc;
     o.outflow = outflow;
+    o.lat_top = lat_top;
+    o.lat_bot = lat_bot;
 }
 
 // The same with the two switches read from the problem (kernels that are not time critical).
@@ -178,6 +186,9 @@ __device__ __forceinline__ double task_accuracy(const TaskOut &o, int64_t Dn) {
 }
 
 // ---- a whole plan in one lane ---------------------------------------------------------------------
+// Under the per-path latency rule the per-task bound is not applied here: the caller settles
+// kBadLatency (and clears the accuracy) with some_path_too_slow for plans that have none of the demand and
+// empty bits.
 __device__ __forceinline__ void eval_plan(const DevProblem *P, const uint32_t (&c)[kMaxTasks], const int64_t *Dn,
                                           const int64_t *budget, int32_t W, uint32_t &mask, int32_t &workers,
                                           double &accuracy) {
@@ -223,7 +234,7 @@ __device__ __forceinline__ void eval_plan(const DevProblem *P, const uint32_t (&
 #pragma unroll
     for (int i = 0; i < kMaxTasks; i++) {
         if (i < n && P->is_leaf[i]) {
-            if (budget[i] < 0 || pl[i] > budget[i]) mask |= kBadLatency;  // eq. (7) with the halved SLO
+            if (!P->lat_per_path && (budget[i] < 0 || pl[i] > budget[i])) mask |= kBadLatency;  // eq. (7), halved SLO
             sum = first ? pp[i] : sum + pp[i];
             first = false;
         }
@@ -367,19 +378,6 @@ __device__ __noinline__ double path_objective(const DevProblem *P, const double 
     return total / static_cast<double>(P->n_paths);
 }
 
-// The part of that objective that belongs to one leaf, the sum over the variant paths of the task path
-// root..leaf, depends on the choices of the tasks on that path only, so a search may form it once for all the
-// plans that share them.  It is taken in two steps.  path_prefixes expands the walk level by level for every
-// task of the path but the leaf: the branches with a nonzero share, in the nested order of path_level (an
-// order-preserving expansion of a list keeps that order), each with what the leaf's level needs of it.
-// leaf_level_sum then adds up the leaf's own level over those branches, for one choice of the leaf.
-struct PathPrefix {
-    int64_t lo, len;   // the interval of the leaf's request stream that holds this branch's requests
-    double mass;       // c(p) up to here
-    uint32_t entry;    // position in the leaf's table so far
-    uint32_t pad;
-};
-
 struct ChoiceDigits {
     uint64_t digits;     // replicas, 8 bits per variant
     uint32_t betas;      // batch position, 4 bits per variant (per-variant batch sizes only)
@@ -408,6 +406,122 @@ __device__ __forceinline__ ChoiceDigits choice_digits(const DevProblem *P, int i
     d.beta_task = c;
     return d;
 }
+
+// ---- eq. (7) on the variant paths with traffic ---------------------------------------------------------------
+// The latency of a variant path (eq. (6)) counts when the path carries requests (Table 1's I(p)): the
+// frontend reaches the root's variant and every variant on the path sends some of its requests to the
+// next one under Algorithm 1.  The walk is path_level's, with the latency so far in place of c(p): a
+// downstream variant is reached when its interval of the request stream overlaps the interval that holds
+// the upstream variant's requests; a variant that sends nothing (only at zero demand) hands on to the
+// first hosted variant.  worst: the largest latency met at the leaf.
+struct LatencyWalk {
+    const DevProblem *P;
+    int leaf;
+    uint32_t c[kMaxTasks];
+    int64_t dn[kMaxTasks];
+    int64_t worst;
+};
+
+template <int J, int MAXD>
+__device__ void latency_level(LatencyWalk &X, int64_t lo, int64_t len, int64_t lat) {
+    const DevProblem *P = X.P;
+    const int i = P->leaf_path[X.leaf][J];
+    const int K = P->K[i];
+    const bool pv = P->pv_batch != 0, has_vf = P->has_vf != 0;
+    const ChoiceDigits d = choice_digits(P, i, pick32(X.c, i));
+    const int64_t dn = pick_below(X.dn, i, kMaxTasks);
+    const bool last = J == P->path_len[X.leaf] - 1;
+    const int next = last ? 0 : P->leaf_path[X.leaf][J + 1 < MAXD ? J + 1 : J];
+    const int64_t fan = last ? 0 : static_cast<int64_t>(P->fanout[next]);
+    int64_t at = 0, made = 0;
+    bool any = false;
+    for (int r = 0; r < K; r++) {
+        const int k = P->order[i][r];
+        const int64_t x = static_cast<int64_t>((d.digits >> (8 * k)) & 0xff);
+        if (x == 0) continue;
+        const uint32_t beta = pv ? (d.betas >> (4 * k)) & 0xf : d.beta_task;
+        const int64_t cap = x * P->thr_s[i][k][beta];
+        const int64_t room = dn - at;
+        const int64_t routed = room < cap ? room : cap;
+        bool reached;
+        if (len > 0) {
+            const int64_t hi_a = at + routed, hi_b = lo + len;
+            reached = (hi_a < hi_b ? hi_a : hi_b) > (at > lo ? at : lo);
+        } else {
+            reached = !any;
+        }
+        any = true;
+        const int64_t out = has_vf ? routed * static_cast<int64_t>(P->vf[i][k]) : routed;
+        if (reached) {
+            const int64_t l = lat + static_cast<int64_t>(P->lat[i][k][beta]);  // l(i,k) at the configured batch size
+            if (last) {
+                X.worst = l > X.worst ? l : X.worst;
+            } else {
+                if constexpr (J + 1 < MAXD) latency_level<J + 1, MAXD>(X, made * fan, out * fan, l);
+            }
+        }
+        at += routed;
+        made += out;
+    }
+}
+
+// True when some variant path with traffic of a plan that hosts every task and serves all demand exceeds
+// its budget (budget[leaf]: the halved SLO less the communication latency of the leaf's chain, negative when
+// nothing is left).  Dn as for path_objective.
+template <int MAXD>
+__device__ __noinline__ bool some_path_too_slow(const DevProblem *P, const uint32_t (&c)[kMaxTasks], const int64_t *Dn,
+                                                const int64_t *budget) {
+    LatencyWalk X;
+    X.P = P;
+    const int n = P->n_tasks;
+    const bool has_vf = P->has_vf != 0;
+    int64_t out[kMaxTasks];
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        X.c[i] = c[i];
+        X.dn[i] = 0;
+        out[i] = 0;
+    }
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        if (i < n) {
+            int64_t dn = Dn[i];
+            if (has_vf) {
+                if (i > 0) dn = pick_below(out, P->parent[i], i) * static_cast<int64_t>(P->fanout[i]);
+                TaskOut o;
+                eval_task_any(P, i, c[i], dn, o);
+                out[i] = o.outflow;
+            }
+            X.dn[i] = dn;
+        }
+    }
+    bool slow = false;
+    for (int leaf = 0; leaf < n; leaf++) {
+        if (!P->is_leaf[leaf]) continue;
+        if (budget[leaf] < 0) {
+            slow = true;
+            continue;
+        }
+        X.leaf = leaf;
+        X.worst = 0;
+        latency_level<0, MAXD>(X, 0, X.dn[0], 0);
+        if (X.worst > budget[leaf]) slow = true;
+    }
+    return slow;
+}
+
+// The part of that objective that belongs to one leaf, the sum over the variant paths of the task path
+// root..leaf, depends on the choices of the tasks on that path only, so a search may form it once for all the
+// plans that share them.  It is taken in two steps.  path_prefixes expands the walk level by level for every
+// task of the path but the leaf: the branches with a nonzero share, in the nested order of path_level (an
+// order-preserving expansion of a list keeps that order), each with what the leaf's level needs of it.
+// leaf_level_sum then adds up the leaf's own level over those branches, for one choice of the leaf.
+struct PathPrefix {
+    int64_t lo, len;   // the interval of the leaf's request stream that holds this branch's requests
+    double mass;       // c(p) up to here
+    uint32_t entry;    // position in the leaf's table so far
+    uint32_t pad;
+};
 
 // One thread.  c: the plan's choices (only those of the path's tasks above the leaf are read); Dn: the
 // demands of the point (only Dn[0] with per-variant factors, where a task's demand is what its parent's part
@@ -1973,19 +2087,32 @@ constexpr uint32_t kStrip = 64;
 // total order).  The loops below therefore have the same trip count in every lane of a wavefront.
 // The four-level walk is held to the registers of 3 wavefronts per SIMD: its spills cost less than the
 // scoring loop gains from the third wavefront.
+//
+// LAT: eq. (7) on every variant path with traffic (the template switches PV and VF are not used then: the
+// problem's own are read).  Two bounds settle most plans in the scoring loop.  From above, the per-task bound
+// (every task's slowest variant in use).  From below, two variant paths that always carry requests when all
+// demand is served: the first variants in use of every task (the head of every task's request stream goes
+// from one to the next) and the last ones (so does the tail).  A plan between the bounds that is feasible
+// otherwise goes through the same queue, marked, and the lane that takes it walks its variant paths
+// (some_path_too_slow) before anything else.  Without profiled path accuracies the queue also carries the
+// accuracy found in the scoring loop.
+constexpr int32_t kWalkCheckLatency = 1 << 30;  // queue entry: latency not settled yet (or'ed into the workers)
 
-template <bool PV, bool VF, int MAXD>
+template <bool PV, bool VF, int MAXD, bool LAT = false>
 __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_search_kernel(SearchArgs A) {
+    constexpr bool kQueue = MAXD > 0 || LAT;
+    constexpr int kLatLevels = MAXD > 0 ? MAXD : kMaxTasks;
     __shared__ DevProblem sP;
     __shared__ BestRec sBest[kWavesPerBlock];
-    __shared__ uint64_t sWalkIdx[MAXD > 0 ? kWavesPerBlock : 1][MAXD > 0 ? kWalkQueue : 1];
-    __shared__ int32_t sWalkW[MAXD > 0 ? kWavesPerBlock : 1][MAXD > 0 ? kWalkQueue : 1];
+    __shared__ uint64_t sWalkIdx[kQueue ? kWavesPerBlock : 1][kQueue ? kWalkQueue : 1];
+    __shared__ int32_t sWalkW[kQueue ? kWavesPerBlock : 1][kQueue ? kWalkQueue : 1];
+    __shared__ double sWalkAcc[LAT && MAXD == 0 ? kWavesPerBlock : 1][LAT && MAXD == 0 ? kWalkQueue : 1];
     stage_problem(&sP, A.P, sizeof(DevProblem));
     __syncthreads();
     const DevProblem *P = &sP;
     const int m = blockIdx.y;
     const int n = P->n_tasks, L = n - 1;
-    constexpr bool has_vf = VF;
+    const bool has_vf = LAT ? P->has_vf != 0 : VF;
     const bool tie_index_only = A.tie_index_only != 0;
     const uint64_t lanes = static_cast<uint64_t>(gridDim.x) * kBlockThreads;
     const uint64_t strideL = P->stride[L];  // number of choice combinations of all other tasks
@@ -2009,10 +2136,11 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
 
     // the first `count` lanes take the queue entries [from, from + count) and walk them
     auto walk_queued = [&](uint32_t from, uint32_t count) {
-        if constexpr (MAXD > 0) {
+        if constexpr (kQueue) {
             if (lane < count) {
                 const uint64_t idx = sWalkIdx[wave][from + lane];
-                const int32_t workers = sWalkW[wave][from + lane];
+                const int32_t entry = sWalkW[wave][from + lane];
+                const int32_t workers = entry & ~kWalkCheckLatency;
                 uint32_t c[kMaxTasks];
                 uint64_t rest = idx;
 #pragma unroll
@@ -2023,15 +2151,36 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
                         rest /= P->C[i];
                     }
                 }
-                const double acc = path_objective<MAXD>(P, A.path_acc, c, Dn);
-                if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
-                    bacc = acc;
-                    bw = workers;
-                    bidx = idx;
+                bool feasible = true;
+                if constexpr (LAT) {
+                    if (entry & kWalkCheckLatency) {
+                        feasible = !some_path_too_slow<kLatLevels>(P, c, Dn, A.budget);
+                        if (feasible) nfeas++;
+                    }
+                }
+                if (feasible) {
+                    double acc;
+                    if constexpr (MAXD > 0) acc = path_objective<MAXD>(P, A.path_acc, c, Dn);
+                    else acc = sWalkAcc[wave][from + lane];
+                    if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                        bacc = acc;
+                        bw = workers;
+                        bidx = idx;
+                    }
                 }
             }
         }
     };
+    auto task_of = [&](int i, uint32_t ci, int64_t dn, TaskOut &t) {
+        if constexpr (LAT) eval_task_any(P, i, ci, dn, t);
+        else eval_task<PV, VF>(P, i, ci, dn, t);
+    };
+    bool no_room = false;   // some chain's communication latency alone exceeds the SLO: nothing is feasible
+    if constexpr (LAT) {
+#pragma unroll
+        for (int i = 0; i < kMaxTasks; i++)
+            if (i < n && P->is_leaf[i] && A.budget[i] < 0) no_room = true;
+    }
 
     const uint64_t first_item = static_cast<uint64_t>(blockIdx.x) * kBlockThreads + threadIdx.x;
     const uint64_t rounds = (items + lanes - 1) / lanes;
@@ -2046,20 +2195,24 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
         const uint32_t c_hi = c_lo + kStrip < CL ? c_lo + kStrip : CL;
         // strips wholly outside [begin, end) are not scored
         if (live && (o + strideL * c_lo >= A.end || o + strideL * (c_hi - 1) < A.begin)) live = false;
-        if constexpr (MAXD == 0) {
+        if constexpr (!kQueue) {
             if (!live) continue;
         }
 
         // ---- the shared part: tasks 0 .. L-1
         double pp[kMaxTasks];    // product of accuracies root..i, root first
         int64_t pl[kMaxTasks];   // latency sum root..i
+        int64_t plt[kMaxTasks], plb[kMaxTasks];  // the same over the first / the last variants in use (LAT)
         int64_t out[kMaxTasks];  // requests task i creates per unit of child fan-out
         uint32_t mask0 = 0;
         int32_t workers0 = 0;
+        bool below0 = false;     // LAT: a variant path that surely carries requests is too slow already
 #pragma unroll
         for (int i = 0; i < kMaxTasks; i++) {
             pp[i] = 0.0;
             pl[i] = 0;
+            plt[i] = 0;
+            plb[i] = 0;
             out[i] = 0;
         }
         double presum = 0.0;
@@ -2075,7 +2228,7 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
                     int64_t dn = Dn[i];
                     if (has_vf && i > 0) dn = pick_below(out, par, i) * static_cast<int64_t>(P->fanout[i]);
                     TaskOut t;
-                    eval_task<PV, VF>(P, i, ci, dn, t);
+                    task_of(i, ci, dn, t);
                     out[i] = t.outflow;
                     workers0 += t.w;
                     if (!t.any) mask0 |= kBadEmpty;
@@ -2088,12 +2241,17 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
                         pp[i] = pick_below(pp, par, i) * a;
                         pl[i] = pick_below(pl, par, i) + t.maxlat;
                     }
+                    if constexpr (LAT) {
+                        plt[i] = (i == 0 ? 0 : pick_below(plt, par, i)) + t.lat_top;
+                        plb[i] = (i == 0 ? 0 : pick_below(plb, par, i)) + t.lat_bot;
+                    }
                 }
             }
 #pragma unroll
             for (int i = 0; i < kMaxTasks; i++) {
                 if (i < L && P->is_leaf[i]) {
                     if (A.budget[i] < 0 || pl[i] > A.budget[i]) mask0 |= kBadLatency;
+                    if (LAT && (plt[i] > A.budget[i] || plb[i] > A.budget[i])) below0 = true;
                     presum = first ? pp[i] : presum + pp[i];
                     first = false;
                 }
@@ -2101,19 +2259,23 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
         }
         const double pre = pick_below(pp, parL, kMaxTasks);
         const int64_t lat_pre = n >= 2 ? pick_below(pl, parL, kMaxTasks) : 0;
+        const int64_t top_pre = LAT && n >= 2 ? pick_below(plt, parL, kMaxTasks) : 0;
+        const int64_t bot_pre = LAT && n >= 2 ? pick_below(plb, parL, kMaxTasks) : 0;
         int64_t dnL = Dn[L];
         if (has_vf && n >= 2) dnL = pick_below(out, parL, kMaxTasks) * static_cast<int64_t>(P->fanout[L]);
 
         // ---- the strip: the last task's choices
-        const uint32_t steps = MAXD > 0 ? kStrip : c_hi - c_lo;
+        const uint32_t steps = kQueue ? kStrip : c_hi - c_lo;
         for (uint32_t step = 0; step < steps; step++) {
             const uint32_t cL = c_lo + step;
             const uint64_t idx = o + strideL * cL;
-            bool feasible = false;
-            int32_t workers = 0;
+            bool feasible = false;  // by the per-task latency bound and everything else
+            bool to_queue = false;
+            int32_t workers = 0, entry = 0;
+            double acc = 0.0;
             if (live && cL < c_hi && idx >= A.begin && idx < A.end) {
                 TaskOut t;
-                eval_task<PV, VF>(P, L, cL, dnL, t);
+                task_of(L, cL, dnL, t);
                 uint32_t mask = mask0;
                 workers = workers0 + t.w;
                 if (!t.any) mask |= kBadEmpty;
@@ -2121,13 +2283,16 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
                 if (workers > A.W) mask |= kBadWorkers;                                            // eq. (3)
                 if (A.budget[L] < 0 || lat_pre + t.maxlat > A.budget[L]) mask |= kBadLatency;  // eq. (7)
                 feasible = mask == 0;
+                // feasible but for the per-task bound: the variant paths with traffic decide
+                const bool open = LAT && mask == kBadLatency && !no_room && !below0 &&
+                                  top_pre + t.lat_top <= A.budget[L] && bot_pre + t.lat_bot <= A.budget[L];
                 if constexpr (MAXD == 0) {
-                    if (feasible) {
+                    if (feasible || open) {
                         const double a = task_accuracy(t, dnL);
                         const double path = n >= 2 ? pre * a : a;
                         const double sum = first ? path : presum + path;
-                        const double acc = sum / npd;
-                        if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                        acc = sum / npd;
+                        if (feasible && better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
                             bacc = acc;
                             bw = workers;
                             bidx = idx;
@@ -2135,16 +2300,19 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
                     }
                 }
                 if (feasible) nfeas++;
+                to_queue = (MAXD > 0 && feasible) || open;
+                entry = open ? workers | kWalkCheckLatency : workers;
             }
-            if constexpr (MAXD > 0) {
-                // every lane of the wavefront is here: queue the feasible plans, walk 64 when there are that many
-                const uint64_t vote = __ballot(feasible);
+            if constexpr (kQueue) {
+                // every lane of the wavefront is here: queue the plans to walk, walk 64 when there are that many
+                const uint64_t vote = __ballot(to_queue);
                 if (vote) {
-                    if (feasible) {
+                    if (to_queue) {
                         const uint32_t at = waiting + __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(vote >> 32),
                                                           __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(vote), 0u));
                         sWalkIdx[wave][at] = idx;
-                        sWalkW[wave][at] = workers;
+                        sWalkW[wave][at] = entry;
+                        if constexpr (LAT && MAXD == 0) sWalkAcc[wave][at] = acc;
                     }
                     waiting += static_cast<uint32_t>(__popcll(vote));
                     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -2157,7 +2325,7 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
             }
         }
     }
-    if constexpr (MAXD > 0) walk_queued(0, waiting);
+    if constexpr (kQueue) walk_queued(0, waiting);
     nfeas = wave_sum(nfeas);
     block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
                      A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
@@ -2225,6 +2393,10 @@ __global__ void __launch_bounds__(kBlockThreads) eval_kernel(EvalArgs A) {
     int32_t workers;
     double acc;
     eval_plan(&sP, c, A.Dn, A.budget, A.W, mask, workers, acc);
+    if (sP.lat_per_path && !(mask & (kBadDemand | kBadEmpty)) && some_path_too_slow<kMaxTasks>(&sP, c, A.Dn, A.budget)) {
+        mask |= kBadLatency;
+        acc = 0.0;
+    }
     if (A.path_acc && mask == 0) acc = path_objective<kMaxTasks>(&sP, A.path_acc, c, A.Dn);
     EvalOut o;
     o.accuracy = acc;
@@ -2433,7 +2605,15 @@ void launch_per_lane_depth(const SearchArgs &A, bool pv_batch, bool has_vf, hipS
     }
 }
 
-hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels, hipStream_t stream) {
+hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels, bool latency_per_path,
+                                  hipStream_t stream) {
+    if (latency_per_path) {
+        const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
+        if (path_levels <= 0) hipLaunchKernelGGL((per_lane_search_kernel<false, false, 0, true>), grid, block, 0, stream, A);
+        else if (path_levels <= 4) hipLaunchKernelGGL((per_lane_search_kernel<false, false, 4, true>), grid, block, 0, stream, A);
+        else hipLaunchKernelGGL((per_lane_search_kernel<false, false, kMaxTasks, true>), grid, block, 0, stream, A);
+        return hipGetLastError();
+    }
     if (path_levels <= 0) launch_per_lane_depth<0>(A, pv_batch, has_vf, stream);
     else if (path_levels <= 4) launch_per_lane_depth<4>(A, pv_batch, has_vf, stream);
     else launch_per_lane_depth<kMaxTasks>(A, pv_batch, has_vf, stream);

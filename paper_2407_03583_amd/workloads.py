@@ -88,6 +88,9 @@ class Pipeline:
     # one entry per combination of variants of the tasks root..leaf, the root's variant least significant.
     # None = the product of the single-model accuracies stands in for it.
     path_acc_ppm: Optional[List[int]] = None
+    # False: eq. (7) through the per-task bound (the slowest variant in use of every task of a path).
+    # True: eq. (7) on every variant path that carries requests under Algorithm 1's routing.
+    latency_per_path: bool = False
 
     def leaf_paths(self) -> List[List[int]]:
         """Task indices root..leaf for every leaf, leaves in ascending index."""
@@ -142,6 +145,8 @@ class Pipeline:
         if self.path_acc_ppm is not None:
             h.update(b"path_acc_ppm")
             h.update(",".join(str(int(v)) for v in self.path_acc_ppm).encode())
+        if self.latency_per_path:
+            h.update(b"latency_per_path")
         return h.hexdigest()
 
 

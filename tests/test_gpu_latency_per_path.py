@@ -1,0 +1,221 @@
+"""GPU parity for eq. (7) on the variant paths with traffic (Section 4.1 eq. (6), (7), Table 1's I(p);
+traffic from Algorithm 1's routing, Section 5.1): per-plan masks and objectives and search results against
+the CPU checker under the same rule, bit for bit."""
+import json
+import os
+import random
+import struct
+from types import SimpleNamespace
+
+import pytest
+
+import oracle
+from paper_2407_03583_amd import binding, workloads as wl
+from test_oracle_latency_per_path import split_traffic_problem, with_rule
+from test_oracle_path_tables import tight_problem
+
+pytestmark = pytest.mark.gpu
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+TIE = binding.LOKI_TIE_INDEX_ONLY
+LANE = binding.LOKI_SEARCH_PER_LANE
+LAT = binding.LOKI_BAD_LATENCY
+
+
+def bits(x):
+    return struct.unpack("<Q", struct.pack("<d", x))[0]
+
+
+def agree(res, ref):
+    got, want = res.as_tuple(), ref.as_tuple()
+    return got[0] == want[0] and bits(got[1]) == bits(want[1]) and got[2:] == want[2:]
+
+
+def check_plans(P, O, indices, demand, workers, slo, comm=0):
+    out = P.alloc_eval(indices, demand, workers, slo, comm)
+    feasible = 0
+    for idx, got in zip(indices, out):
+        e = O.eval(idx, demand, workers, slo, comm)
+        assert got.infeasible == e.infeasible and got.workers == e.workers, (idx, got.infeasible, e.infeasible)
+        assert bits(got.accuracy) == bits(e.accuracy), (idx, got.accuracy, e.accuracy)
+        feasible += e.infeasible == 0
+    return feasible
+
+
+def binding_slos(p):
+    """SLOs at 60, 75 and 90 % of what the slowest variant of every task of the slowest chain would need."""
+    slowest = 0
+    off = [sum(p.n_variants[:i]) for i in range(p.n_tasks + 1)]
+    nb = p.n_batches
+    boff = [0]
+    for i in range(p.n_tasks):
+        boff.append(boff[-1] + p.n_variants[i] * nb[i])
+    for path in p.leaf_paths():
+        slowest = max(slowest, sum(max(p.latency_us[boff[i]:boff[i + 1]]) for i in path))
+    return [slowest * 2 * f // 100 for f in (60, 75, 90)]
+
+
+def test_hand_derived_example():
+    doc = json.load(open(os.path.join(GOLDEN, "latency_per_path_example.json")))
+    for case in doc["cases"]:
+        for per_path, key in ((False, "per_task_infeasible"), (True, "per_path_infeasible")):
+            p = with_rule(SimpleNamespace(**dict(doc["pipeline"], thr_mqps=case["thr_mqps"])), per_path)
+            P, O = binding.Problem(p), oracle.Problem(p)
+            got = P.alloc_eval([doc["plan_index"]], case["demand_mqps"], doc["workers"], case["slo_us"])[0]
+            assert got.infeasible == case[key], (case["what"], per_path)
+            check_plans(P, O, list(range(P.num_candidates())), case["demand_mqps"], doc["workers"], case["slo_us"])
+            for flags in (0, TIE, LANE):
+                res = P.alloc_search([case["demand_mqps"]], doc["workers"], case["slo_us"], flags=flags)[0]
+                ref = O.search(case["demand_mqps"], doc["workers"], case["slo_us"], tie_index_only=bool(flags & TIE))
+                assert agree(res, ref), (case["what"], per_path, flags)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_every_plan_and_the_search_on_split_traffic(seed):
+    """Problems whose latencies do not follow the accuracies, so the two rules part on many plans: every plan's
+    mask and accuracy, and the search at both SLOs, several demand points in one call, with a split range."""
+    rng = random.Random(1000 + seed)
+    parent = [[-1, 0], [-1, 0, 1], [-1, 0, 0], [-1, 0, 1, 1]][seed % 4]
+    p, demand, slos = split_traffic_problem(rng, parent)
+    p = with_rule(p, True)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    for slo in slos:
+        check_plans(P, O, list(range(n)), demand, 99, slo)
+        demands = [demand, 0, demand // 2, demand * 3 // 4]
+        for flags in (0, TIE):
+            res = P.alloc_search(demands, 99, slo, flags=flags)
+            for d, r in zip(demands, res):
+                ref = O.search(d, 99, slo, tie_index_only=bool(flags & TIE))
+                assert agree(r, ref), (seed, slo, d, flags, r.as_tuple(), ref.as_tuple())
+        a, b = n // 3 + 1, n - n // 4
+        parts = [P.alloc_search([demand], 99, slo, begin=lo, end=hi)[0] for lo, hi in ((0, a), (a, b), (b, n))]
+        for (lo, hi), r in zip(((0, a), (a, b), (b, n)), parts):
+            assert agree(r, O.search(demand, 99, slo, begin=lo, end=hi)), (seed, slo, lo, hi)
+
+
+def test_the_rules_part_on_these_problems():
+    """The library's own two rules give different numbers of feasible plans on a good share of the problems
+    above (the comparison there is not between two copies of the per-task bound)."""
+    differ = 0
+    for seed in range(12):
+        rng = random.Random(1000 + seed)
+        p, demand, slos = split_traffic_problem(rng, [[-1, 0], [-1, 0, 1], [-1, 0, 0], [-1, 0, 1, 1]][seed % 4])
+        a = binding.Problem(with_rule(p, False)).alloc_search([demand], 99, slos[0])[0]
+        b = binding.Problem(with_rule(p, True)).alloc_search([demand], 99, slos[0])[0]
+        assert b.n_feasible >= a.n_feasible
+        differ += b.n_feasible > a.n_feasible
+    assert differ >= 3, differ
+
+
+@pytest.mark.parametrize("variant_factors", [False, True])
+@pytest.mark.parametrize("per_variant_batch", [False, True])
+@pytest.mark.parametrize("path_tables", [False, True])
+def test_with_the_optional_parts_of_the_model(variant_factors, per_variant_batch, path_tables):
+    """Per-variant factors (a child's demand follows from its parent's routing), a batch size per hosted
+    variant (l(i,k) at the variant's own batch size) and profiled path accuracies, in every combination."""
+    rng = random.Random(700 + 4 * variant_factors + 2 * per_variant_batch + path_tables)
+    feasible = searched = 0
+    for _ in range(8):
+        p, demand = tight_problem(rng, variant_factors, per_variant_batch)
+        if not path_tables:
+            p.path_acc_ppm = None
+        p = with_rule(p, True)
+        P, O = binding.Problem(p), oracle.Problem(p)
+        n = P.num_candidates()
+        for slo in binding_slos(p)[1:]:
+            feasible += check_plans(P, O, rng.sample(range(n), min(n, 1500)), demand, 99, slo)
+            if n <= 60_000:
+                searched += 1
+                for flags in (0, TIE):
+                    res = P.alloc_search([demand, demand // 2], 99, slo, flags=flags)
+                    for d, r in zip([demand, demand // 2], res):
+                        ref = O.search(d, 99, slo, tie_index_only=bool(flags & TIE))
+                        assert agree(r, ref), (d, slo, flags, r.as_tuple(), ref.as_tuple())
+    assert feasible > 150 and searched >= 4, (feasible, searched)
+
+
+def test_random_small_problems_with_communication_latency():
+    """The library's small random problems (worker budgets that bind, communication latency per server,
+    replica limits of zero) under the per-path rule."""
+    found = 0
+    for seed in range(40):
+        w = wl.random_small(seed, max_candidates=6000, variant_factors=seed % 5 == 4, path_tables=seed % 4 == 3)
+        p = with_rule(w.pipeline, True)
+        P, O = binding.Problem(p), oracle.Problem(p)
+        n = P.num_candidates()
+        for slo in (w.slo_us, w.slo_us * 2 // 3):
+            for d in w.demand_mqps[:2]:
+                res = P.alloc_search([d], w.workers, slo, w.comm_us)[0]
+                ref = O.search(d, w.workers, slo, w.comm_us)
+                assert agree(res, ref), (seed, slo, d, res.as_tuple(), ref.as_tuple())
+                found += ref.found
+        check_plans(P, O, list(range(0, n, max(1, n // 300))), w.demand_mqps[0], w.workers, w.slo_us * 2 // 3, w.comm_us)
+    assert found >= 10, found
+
+
+def test_no_room_left_by_the_communication_latency():
+    rng = random.Random(5)
+    p, demand, slos = split_traffic_problem(rng, [-1, 0, 1])
+    p = with_rule(p, True)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    # three servers at 10 ms each leave nothing of a 25 ms SLO
+    check_plans(P, O, list(range(n)), demand, 99, 25_000, 10_000)
+    res = P.alloc_search([demand], 99, 25_000, 10_000)[0]
+    assert agree(res, O.search(demand, 99, 25_000, 10_000)) and res.n_feasible == 0
+
+
+def test_three_task_chain_with_two_million_plans():
+    """Chain of three tasks, three variants with up to three replicas and two batch sizes each: 2,097,152
+    plans; throughputs such that a task's demand needs two or three replicas, so traffic is split."""
+    rng = wl.SplitMix64(91)
+    p = wl.make_pipeline([-1, 0, 1], 3, 3, (1, 4), rng)
+    r2 = random.Random(17)
+    v = 0
+    for i in range(3):   # latencies that do not follow the accuracies
+        for k in range(3):
+            for b in range(2):
+                p.latency_us[(v + k) * 2 + b] = r2.randint(3000, 30000)
+        v += 3
+    p = with_rule(p, True)
+    P, O, O_bound = binding.Problem(p), oracle.Problem(p), oracle.Problem(with_rule(p, False))
+    assert P.num_candidates() == (4 ** 3 * 2) ** 3
+    slo = binding_slos(p)[0]
+    demands = [150_000, 400_000]
+    out = P.alloc_search(demands, 24, slo)
+    more = 0
+    for d, res in zip(demands, out):
+        ref = O.search(d, 24, slo)
+        assert agree(res, ref), (d, res.as_tuple(), ref.as_tuple())
+        more += ref.n_feasible > O_bound.search(d, 24, slo).n_feasible
+    assert more >= 1
+
+
+def test_four_task_tree_with_268_million_plans():
+    """Tree 0 -> 1 -> {2, 3} with 128 choices per task, latencies drawn independently of everything else: the
+    launch configuration of a large search (every block busy for many rounds, the queues of plans whose
+    variant paths must be walked filling and draining many times)."""
+    p = wl.make_pipeline([-1, 0, 1, 1], 3, 3, (1, 4), wl.SplitMix64(92))
+    r2 = random.Random(18)
+    for j in range(len(p.latency_us)):
+        p.latency_us[j] = r2.randint(3000, 30000)
+    p = with_rule(p, True)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    assert P.num_candidates() == 128 ** 4
+    slo = binding_slos(p)[0]
+    demands = [180_000, 150_000]
+    for d, res in zip(demands, P.alloc_search(demands, 32, slo)):
+        ref = O.search(d, 32, slo)
+        assert agree(res, ref), (d, res.as_tuple(), ref.as_tuple())
+    assert ref.n_feasible > 0
+
+
+def test_entry_point_without_allocation_follows_the_rule():
+    rng = random.Random(1003)
+    p, demand, slos = split_traffic_problem(rng, [-1, 0, 1, 1])
+    p = with_rule(p, True)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    res = P.alloc_search_static([demand, demand // 2], 99, slos[0])
+    for d, r in zip([demand, demand // 2], res):
+        assert agree(r, O.search(d, 99, slos[0]))

@@ -126,6 +126,44 @@ def test_rules_agree_where_latency_grows_with_accuracy():
             assert a.as_tuple() == b.as_tuple(), (seed, slo)
 
 
+def test_first_and_last_variants_in_use_always_share_a_path():
+    """When all demand is served, the head of every task's request stream goes from the first variant in use
+    of a task (route order) to the first one of its child, and the tail from the last to the last: both
+    variant paths carry requests whatever the capacities, so their latency bounds the per-path rule from
+    below, as the per-task sum bounds it from above.  Checked on the checker's routing tables."""
+    seen = gap = 0
+    for seed in range(12):
+        rng = random.Random(1000 + seed)
+        parent = [[-1, 0], [-1, 0, 1], [-1, 0, 0], [-1, 0, 1, 1]][seed % 4]
+        p, demand, slos = split_traffic_problem(rng, parent)
+        O = oracle.Problem(with_rule(p, True))
+        voff = [sum(p.n_variants[:i]) for i in range(p.n_tasks)]
+        for idx in range(O.num_candidates()):
+            r = O.route_table(idx, demand)
+            x, _ = O.decode(idx)
+            if any(r.unserved[i] > 0 or not any(x[voff[i]:voff[i] + p.n_variants[i]]) for i in range(p.n_tasks)):
+                continue
+            order = [sorted(range(p.n_variants[i]), key=lambda k: (-p.acc_ppm[voff[i] + k], k)) for i in range(p.n_tasks)]
+            used = [[k for k in order[i] if r.routed[i][k] > 0] for i in range(p.n_tasks)]
+            for pick in (0, -1):
+                for i in range(1, p.n_tasks):
+                    up, down = used[parent[i]][pick], used[i][pick]
+                    assert r.prob[i][up][down] > 0.0, (seed, idx, i, pick)
+                assert r.prob[0][0][used[0][pick]] > 0.0
+            # and the bounds: lower <= worst path with traffic <= upper, the budget placed on each in turn
+            lat = [[p.latency_us[voff[i] + k] for k in range(p.n_variants[i])] for i in range(p.n_tasks)]
+            for path in p.leaf_paths():
+                low = max(sum(lat[i][used[i][pick]] for i in path) for pick in (0, -1))
+                high = sum(max(lat[i][k] for k in used[i]) for i in path)
+                assert low <= high
+                gap += low < high
+            seen += 1
+            e_low = O.eval(idx, demand, 99, 2 * max(max(sum(lat[i][used[i][pick]] for i in path) for pick in (0, -1))
+                                                    for path in p.leaf_paths()) - 1)
+            assert e_low.infeasible & LAT, (seed, idx)
+    assert seen > 500 and gap > 100, (seen, gap)
+
+
 def test_one_variant_in_use_per_task_makes_the_rules_agree():
     """With a single variant per task there is one variant path, and both rules are its latency."""
     for seed in range(10):
