@@ -183,7 +183,13 @@ def main() -> int:
                and max(above[i] for i in range(w.pipeline.n_tasks) if i not in par) <= 64)
     if by_leaf:
         ops = 2
-    no_count = args.path_tables and not args.per_lane and not by_leaf   # see the note in the roofline object
+    # profiled path accuracies on a single task path (at most 64 variant combinations above the last task): the
+    # library bounds the objective of every feasible plan from above and walks the variant paths only of
+    # those that can still reach the best seen; priced like the product form (what a search over these plans
+    # costs at the least), the bound and the walks are overhead
+    pruned = (args.path_tables and not args.per_lane and not args.variant_factors and n_paths == 1
+              and above[w.pipeline.n_tasks - 1] <= 64)
+    no_count = args.path_tables and not args.per_lane and not by_leaf and not pruned   # see the roofline note
     # work the kernels did: every plan of the range, except class by class, where plans whose first-task
     # choice cannot serve the demand are settled per choice on the host and never reach the kernels
     scored = P.last_search_plans_scored()
@@ -221,6 +227,11 @@ def main() -> int:
         out["roofline"]["note"] = ("profiled path accuracies leaf by leaf: 2 operations per visited plan (add, "
                                    "max/compare); the sums over the variant paths, one per tile entry and per "
                                    "lane slot, are not counted")
+    if pruned:
+        out["roofline"]["note"] = ("profiled path accuracies on one task path: priced like the product form "
+                                   f"({ops} operations per visited plan); the upper bound taken for every feasible "
+                                   "plan and the walks over the variant paths of the plans it does not rule out "
+                                   "are not counted")
     if no_count:
         out["roofline"]["note"] = ("profiled path accuracies: feasibility is taken per run of first-task choices "
                                    "and the walk over the variant paths runs for feasible plans only, so no "

@@ -30,6 +30,8 @@ namespace {
 // block dispatch evens out compute units and demand points that finish at different times.
 constexpr uint32_t kTargetBlocks = 32768;
 constexpr uint32_t kMinTile = 128;     // shortest tile of root-task choices per work item
+constexpr uint32_t kPruneTile = 256;   // longest tile where most feasible plans are spared the walk (profiled path
+                                       // accuracies on one task path): the walks left sit in few work items
 // Below this many work items per launch the tile is shortened: a launch should have more blocks than the
 // 1280 that are resident at once.  Not sooner: the entries of a tile are walked in runs of equal limits,
 // and a longer tile has longer runs.
@@ -469,6 +471,14 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     // (with profiled path accuracies a quarter of the blocks: every block ends with one walk over the
     // variant paths for the few plans left in its queues, which longer blocks spread over more work)
     const bool leaf_values = A.swap && leaf_values_apply(p);
+    // (a single task path with one factor per edge: an upper bound on the objective spares most feasible plans
+    // the walk, see path_combine_kernel; the plans that are walked sit in few places of the plan space, so the
+    // work items are made small, and the bound keeps 8 more registers per slot)
+    uint64_t above = 1;
+    for (int j = 0; j < L; j++) above *= uint64_t(p->dev.K[j]);
+    const bool prune = p->dev.has_path && !leaf_values && !A.swap && !p->dev.has_vf && p->dev.n_paths == 1 &&
+                       above <= uint64_t(kMaxPrefix);
+    A.prune = prune ? 1u : 0u;   // (the table kernel needs it too: it leaves the variants in use in the records)
     const uint32_t target_blocks = (p->dev.has_path && !leaf_values) ? kTargetBlocks / 4 : kTargetBlocks;
     const uint32_t max_bpm = std::max<uint32_t>(1u, (target_blocks + n_points - 1) / n_points);
     const uint32_t CL = p->dev.C[L];
@@ -478,7 +488,7 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
     // share the walks)
     const bool fine_items =
         p->dev.has_path && !leaf_values && A.class_amount != nullptr && A.swap && p->class_small_space;
-    const int slots = (CL >= 512 && !fine_items) ? 8 : 4;
+    const int slots = (CL >= 512 && !fine_items && !prune) ? 8 : 4;
     const uint32_t chunk = 64u * slots;
     const uint64_t strideL = p->dev.stride[L];
     uint64_t F = 1;
@@ -508,7 +518,7 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
         const uint32_t n_chunks = (cl_last - cl_first + 1 + chunk - 1) / chunk;
         A.cl_first = cl_first;
         A.cpb = 1;
-        while (!fine_items && A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
+        while (!fine_items && !prune && A.cpb * 2 <= n_chunks && A.cpb * 2 <= uint32_t(kWavesPerBlock)) A.cpb *= 2;
         A.chunk_groups = (n_chunks + A.cpb - 1) / A.cpb;
         // a range shorter than one step of the last task's choice touches only some of the
         // combinations of the tasks in between, in cyclic order from that of its first index
@@ -523,7 +533,7 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
         A.items = uint64_t(A.chunk_groups) * A.far_span * A.mid_tiles;
         // a search with few work items gets shorter ones: blocks that meet many feasible plans
         // run long, and only spare items let the others take over the rest
-        while (A.tile_len > kMinTile && A.items * n_points < kFewItems) {
+        while (A.tile_len > kMinTile && ((prune && A.tile_len > kPruneTile) || A.items * n_points < kFewItems)) {
             A.tile_len /= 2;
             A.mid_tiles = (mid_count + A.tile_len - 1) / A.tile_len;
             A.items = uint64_t(A.chunk_groups) * A.far_span * A.mid_tiles;

@@ -152,6 +152,9 @@ struct SearchArgs {
     int32_t M;
     uint32_t blocks_per_m;
     uint32_t tie_index_only;
+    uint32_t prune;         // profiled path accuracies, tabulated: feasible plans whose upper bound is below the
+                            // best objective seen are not walked (one task path, one factor per edge, at most
+                            // kMaxPrefix variant combinations above the last task)
 };
 
 // Mirrors loki_route_t (include/loki_alloc.h).

@@ -98,6 +98,7 @@ struct TaskOut {
     int64_t weighted;   // sum routed * acc_ppm
     int32_t first_acc;  // accuracy of the first hosted variant in route order
     int64_t outflow;    // sum routed * variant factor: what the task creates per unit of child fan-out
+    uint32_t used;      // bit k: variant k is in use
     int32_t lat_top;    // latency of the first variant in use in route order (the most accurate one)
     int32_t lat_bot;    // latency of the last variant in use in route order
 };
@@ -135,6 +136,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     const uint32_t beta_task = c;
     int64_t rem = Dn, weighted = 0, outflow = 0;
     int32_t any = 0, first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
+    uint32_t in_use = 0;
     constexpr bool has_vf = VF;
     for (int r = 0; r < K; r++) {
         const int k = P->order[i][r];
@@ -148,6 +150,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         const bool used = hosted && (routed > 0 || !any);
         if (used && lat > maxlat) maxlat = lat;
         if (used) lat_bot = lat;
+        in_use |= used ? 1u << k : 0u;
         if (hosted && !any) {
             first_acc = acc;
             lat_top = lat;
@@ -164,6 +167,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     o.weighted = weighted;
     o.first_acc = first_acc;
     o.outflow = outflow;
+    o.used = in_use;
     o.lat_top = lat_top;
     o.lat_bot = lat_bot;
 }
@@ -405,6 +409,32 @@ __device__ __forceinline__ ChoiceDigits choice_digits(const DevProblem *P, int i
     }
     d.beta_task = c;
     return d;
+}
+
+// The part of task i's requests that each variant serves under choice c at demand dn (the first hosted one
+// serves "all" of no demand).  share is written with constant subscripts only, so that it stays in registers.
+__device__ __forceinline__ void choice_shares(const DevProblem *P, int i, uint32_t c, int64_t dn,
+                                              float (&share)[kMaxVariants]) {
+    const int K = P->K[i];
+    const bool pv = P->pv_batch != 0;
+    const ChoiceDigits d = choice_digits(P, i, c);
+    int64_t rem = dn;
+    bool any = false;
+#pragma unroll
+    for (int k = 0; k < kMaxVariants; k++) share[k] = 0.0f;
+    for (int r = 0; r < K; r++) {
+        const int k = P->order[i][r];
+        const int64_t x = static_cast<int64_t>((d.digits >> (8 * k)) & 0xff);
+        const uint32_t beta = pv ? (d.betas >> (4 * k)) & 0xf : d.beta_task;
+        const int64_t cap = x * P->thr_s[i][k][beta];
+        const int64_t routed = rem < cap ? rem : cap;
+        const bool in_use = x > 0 && (routed > 0 || !any);
+        const float part = dn > 0 ? static_cast<float>(static_cast<double>(routed) / static_cast<double>(dn)) : 1.0f;
+#pragma unroll
+        for (int kk = 0; kk < kMaxVariants; kk++) share[kk] = (in_use && kk == k) ? part : share[kk];
+        rem -= routed;
+        any = any || x > 0;
+    }
 }
 
 // ---- eq. (7) on the variant paths with traffic ---------------------------------------------------------------
@@ -808,7 +838,9 @@ __global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A)
     TaskOut o;
     eval_task_any(&sP, i, c, Dn, o);
     TaskRec rec;
-    rec.a = task_accuracy(o, Dn);
+    // (A.prune: the objective comes from profiled path accuracies and an upper bound on it wants the variants in
+    // use of every choice; the accuracy is not read then and its field carries the bit mask as a number)
+    rec.a = A.prune ? static_cast<double>(o.used) : task_accuracy(o, Dn);
     rec.w = o.w;
     bool usable = o.any && o.rem == 0;
     // class by class: only the choices that create the class's amount of requests belong to the point
@@ -1744,6 +1776,23 @@ combine_kernel(SearchArgs A) {
 // plans waiting for the walk over the variant paths, per wavefront: below 64 waiting + at most 64 new per push
 constexpr uint32_t kWalkQueue = 128;
 
+// The objective of plan idx from its profiled path accuracies (a call, so that the loops that queue plans
+// keep their registers).
+template <int MAXD>
+__device__ __noinline__ double walk_plan(const DevProblem *P, const double *path_acc, const int64_t *Dn, uint64_t idx) {
+    uint32_t c[kMaxTasks];
+    uint64_t rest = idx;
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        c[i] = 0;
+        if (i < P->n_tasks) {
+            c[i] = static_cast<uint32_t>(rest % P->C[i]);
+            rest /= P->C[i];
+        }
+    }
+    return path_objective<MAXD>(P, path_acc, c, Dn);
+}
+
 // ---- kernel: profiled path accuracies on top of the per-task tables -----------------------------------------
 // Feasibility is separable even where the objective is not (one factor per edge: a task's demand, and so
 // its record, does not depend on the other tasks).  This kernel walks the plan space like combine_kernel
@@ -1751,11 +1800,31 @@ constexpr uint32_t kWalkQueue = 128;
 // only takes the feasibility masks, once per run; the plans of a run that are feasible go, by index, into
 // a queue of the wavefront, and whenever 64 are waiting every lane walks the variant paths of one
 // (path_objective).  The cost is a few instructions per 512 plans plus the walk for feasible plans only.
+//
+// A.prune (one task path, one factor per edge, at most kMaxPrefix variant combinations above the last task):
+// most feasible plans are not walked at all.  The shares c(p) of a plan's variant paths add up, over the
+// variants of the tasks above, to the part s(k) of the last task's requests that its variant k serves (every
+// hop hands on the whole stream), so   sum_p c(p) A-hat(p)  <=  sum_k s(k) * max A-hat(p', k)   with the
+// maximum over the combinations p' of variants in use of the tasks above.  s comes with the lane's choice of the
+// last task (registers, formed when a chunk group first meets a feasible run); the variants in use of the other
+// tasks' choices come with their table records (task_table_kernel leaves the bit mask where the accuracy would
+// be); the maxima are formed per work item (over the tasks in between) and per tile entry (LDS).  A feasible
+// plan whose bound (taken in fp32 and widened by 1e-5 for the rounding on both sides) is below the best
+// objective seen so far for the demand point (the wavefront's own, and A.floor[m] shared through memory, read
+// again after every 64 walks) can neither win nor tie: it is counted and dropped.  Every item is gone through
+// twice, the first time only to find, per lane, the feasible plan with the largest bound: walking those first
+// gives the threshold a good plan of the same item.  The plans that are walked sit in few places of the plan
+// space, so the items are short, and a block's items lie blocks_per_m apart.
 template <int S, bool RANGE, int MAXD, bool SWAP>
 __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine_kernel(SearchArgs A) {
     __shared__ DevProblem sPfull;
     __shared__ MidLim sLim[kMidTile];
     __shared__ uint32_t sChoice[kMidTile];
+    __shared__ float sCol[SWAP ? 1 : kMidTile][kMaxVariants];
+    __shared__ float sTab[SWAP ? 1 : kMaxPrefix * kMaxVariants];   // prune: the last task's table of path accuracies
+    // prune: per variant of the first and of the last task, the largest table entry over the combinations of
+    // variants in use of the tasks in between (those of the work item)
+    __shared__ float sFar[SWAP ? 1 : kMaxVariants][kMaxVariants];
     __shared__ uint64_t sWalkIdx[kWavesPerBlock][kWalkQueue];
     __shared__ int32_t sWalkW[kWavesPerBlock][kWalkQueue];
     __shared__ BestRec sBest[kWavesPerBlock];
@@ -1808,23 +1877,23 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
     uint32_t waiting = 0;    // plans in this wavefront's queue (the same in every lane)
     uint32_t cur_group = ~0u;
     uint32_t cl0 = 0;        // this lane's choice of the last task in slot 0
+    const bool prune = !SWAP && A.prune != 0;
+    const int KL = uni(sP->K[L]);
+    const double *tabPath = A.path_acc + uni(sP->path_off[L]);
+    float sh[S][kMaxVariants];    // prune: the part of the last task's requests each of its variants serves
+    uint32_t sh_group = ~0u;      // the chunk group sh belongs to
+    double thr = 0.0;             // prune: best objective known for the demand point (the same in every lane)
+#pragma unroll
+    for (int s = 0; s < S; s++)
+#pragma unroll
+        for (int k = 0; k < kMaxVariants; k++) sh[s][k] = 0.0f;
 
     // the first `count` lanes take the queue entries [from, from + count) and walk them
     auto walk_queued = [&](uint32_t from, uint32_t count) {
         if (lane < count) {
             const uint64_t idx = sWalkIdx[wave][from + lane];
             const int32_t workers = sWalkW[wave][from + lane];
-            uint32_t c[kMaxTasks];
-            uint64_t rest = idx;
-#pragma unroll
-            for (int i = 0; i < kMaxTasks; i++) {
-                c[i] = 0;
-                if (i < n) {
-                    c[i] = static_cast<uint32_t>(rest % sP->C[i]);
-                    rest /= sP->C[i];
-                }
-            }
-            const double acc = path_objective<MAXD>(sP, A.path_acc, c, Dn);
+            const double acc = walk_plan<MAXD>(sP, A.path_acc, Dn, idx);
             if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
                 bacc = acc;
                 bw = workers;
@@ -1833,11 +1902,28 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
         }
     };
 
+    // prune: combinations of variants of the tasks above the last one, and the table in LDS
+    uint32_t Qabove = 1;
+#pragma unroll
+    for (int j = 0; j < kMaxTasks; j++)
+        if (j < L) Qabove *= static_cast<uint32_t>(uni(sP->K[j]));
+    if constexpr (!SWAP) {
+        if (prune) {
+            for (uint32_t t = threadIdx.x; t < Qabove * static_cast<uint32_t>(KL); t += kBlockThreads)
+                sTab[t] = static_cast<float>(tabPath[t]);
+            __syncthreads();
+        }
+    }
+
     const uint64_t far_m = SWAP ? far_swap : A.far_span;
     const uint64_t items_m = SWAP ? static_cast<uint64_t>(A.chunk_groups) * far_m * A.mid_tiles : A.items;
     const uint64_t item_lo = items_m * blockIdx.x / A.blocks_per_m;
     const uint64_t item_hi = items_m * (blockIdx.x + 1) / A.blocks_per_m;
-    for (uint64_t item = item_lo; item < item_hi; ++item) {
+    // (prune: the block's items lie blocks_per_m apart, so that the few places of the plan space where plans are
+    // walked are shared out among the blocks)
+    const bool apart = prune;
+    const uint64_t item_step = apart ? A.blocks_per_m : 1;
+    for (uint64_t item = apart ? blockIdx.x : item_lo; item < (apart ? items_m : item_hi); item += item_step) {
         // position of the item: tile r, combination f of the tasks in between, chunk group g
         const uint32_t r = uni(static_cast<uint32_t>(item % A.mid_tiles));
         const uint64_t t = item / A.mid_tiles;
@@ -1880,6 +1966,44 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
                 } else {
                     w[s] = 0;
                     lat[s] = kNever;
+                }
+            }
+        }
+        // prune: the variants in use of the tasks strictly between the first and the last, and what the
+        // other blocks of the demand point have found so far
+        uint32_t used_far[kMaxTasks];
+#pragma unroll
+        for (int j = 0; j < kMaxTasks; j++) used_far[j] = 0;
+        if (prune) {
+#pragma unroll
+            for (int j = 1; j < kMaxTasks; j++)
+                if (j < L) used_far[j] = uni(static_cast<uint32_t>(tab[sP->table_off[j] + cj[j]].a));
+            const double shared = __longlong_as_double(static_cast<long long>(
+                __hip_atomic_load(A.floor + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+            if (shared > thr) thr = shared;
+            if constexpr (!SWAP) {
+                // (read while the tile is staged, between this item's two barriers; every thread is past the
+                // previous item's staging here)
+                const uint32_t K0v = n >= 2 ? static_cast<uint32_t>(uni(sP->K[0])) : 1u;
+                if (threadIdx.x < K0v * static_cast<uint32_t>(KL)) {
+                    const uint32_t k_first = threadIdx.x % K0v, k_last = threadIdx.x / K0v;
+                    float v = 0.0f;
+                    for (uint32_t q = k_first; q < Qabove; q += K0v) {
+                        uint32_t rest = q / K0v;
+                        bool in_use = true;
+#pragma unroll
+                        for (int j = 1; j < kMaxTasks; j++) {
+                            if (j < L) {
+                                const uint32_t Kj = static_cast<uint32_t>(sP->K[j]);
+                                const uint32_t k = rest % Kj;
+                                rest /= Kj;
+                                in_use = in_use && ((used_far[j] >> k) & 1u) != 0;
+                            }
+                        }
+                        const float t = sTab[q + Qabove * k_last];
+                        v = (in_use && t > v) ? t : v;
+                    }
+                    sFar[k_first][k_last] = v;
                 }
             }
         }
@@ -1978,11 +2102,43 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
             }
             sLim[e] = ul;
             sChoice[e] = SWAP ? static_cast<uint32_t>(uni64(sP->stride[T])) * cM : cM;
+            if constexpr (!SWAP) {
+                if (prune) {
+                    // per variant of the last task: the largest table entry over the combinations of variants in
+                    // use of the tasks above (the first task's from this entry's record)
+                    float col[kMaxVariants];
+#pragma unroll
+                    for (int k = 0; k < kMaxVariants; k++) col[k] = 0.0f;
+                    if (ul.w_rem >= 0) {
+                        const uint32_t used0 = n >= 2 ? static_cast<uint32_t>(tabM[cM].a) : 1u;
+                        for (int k_first = 0; k_first < kMaxVariants; k_first++) {
+                            if (((used0 >> k_first) & 1u) == 0) continue;
+#pragma unroll
+                            for (int k = 0; k < kMaxVariants; k++) {
+                                const float v = k < KL ? sFar[k_first][k] : 0.0f;
+                                col[k] = v > col[k] ? v : col[k];
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int k = 0; k < kMaxVariants; k++) sCol[e][k] = col[k];
+                }
+            }
         }
         __syncthreads();
 
         const uint32_t e_lo = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * midpart / mid_split);
         const uint32_t e_hi = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * (midpart + 1) / mid_split);
+        // prune: the item is gone through twice.  The first time nothing is walked: every lane keeps the feasible
+        // plan with the largest bound it meets, these (at most 64) plans are walked, and the best of them, a
+        // good plan of this very item, is the threshold the second time round (plans come in an order in which
+        // the objective tends to rise, so a threshold learnt on the way would lag behind).  An item without
+        // feasible plans ends after the first time.
+        float cand_ub = -1.0f;
+        uint32_t cand_at = 0;    // entry * 8 + slot
+        bool item_any = true;
+        for (int pass = prune ? 0 : 1; pass < 2 && item_any; pass++) {
+        if (pass == 0) item_any = false;
         uint32_t e = e_lo;
         while (e < e_hi) {
             // ---- start of a run: which of the S*64 plans are feasible, valid for every record of the run
@@ -2003,29 +2159,103 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
                 run_feas += static_cast<uint32_t>(__builtin_popcountll(fm[s]));
             }
             if (run_feas != 0) {
+                if constexpr (!SWAP) {
+                    if (pass == 0) {  // (prune)
+                        item_any = true;
+                        if (sh_group != cur_group) {
+                            sh_group = cur_group;
+#pragma unroll
+                            for (int s = 0; s < S; s++) {
+                                const uint32_t cL = cl0 + s * 64;
+                                choice_shares(sP, L, cL < CL ? cL : 0u, Dn[L], sh[s]);
+                            }
+                        }
+                    }
+                }
                 for (uint32_t ee = e; ee < run_hi; ee++) {
                     const uint64_t low = base_f + sChoice[ee];
                     const int32_t w_out = W - sLim[ee].w_rem;  // replicas of all tasks but the last
+                    float thr_f = static_cast<float>(thr) * 0.99999f;
 #pragma unroll
                     for (int s = 0; s < S; s++) {
                         if (fm[s] == 0) continue;
-                        if ((fm[s] >> lane) & 1) {
-                            const uint32_t at = waiting + static_cast<uint32_t>(__builtin_popcountll(fm[s] & ((1ull << lane) - 1)));
+                        uint64_t km = fm[s];   // the plans of this slot that go on to the walk
+                        if (prune) {
+                            float ub = 0.0f;
+#pragma unroll
+                            for (int k = 0; k < kMaxVariants; k++) ub = __builtin_fmaf(sh[s][k], sCol[ee][k], ub);
+                            if (pass == 0) {
+                                if (((fm[s] >> lane) & 1) != 0 && ub > cand_ub) {
+                                    cand_ub = ub;
+                                    cand_at = ee * 8 + s;
+                                }
+                                continue;
+                            }
+                            km = __builtin_amdgcn_ballot_w64(((fm[s] >> lane) & 1) != 0 && ub * 1.00001f >= thr_f);
+                            if (km == 0) continue;
+                        }
+                        if ((km >> lane) & 1) {
+                            const uint32_t at = waiting + static_cast<uint32_t>(__builtin_popcountll(km & ((1ull << lane) - 1)));
                             sWalkIdx[wave][at] = low + strideL * (cl0 + s * 64);
                             sWalkW[wave][at] = w_out + w[s];
                         }
-                        waiting += static_cast<uint32_t>(__builtin_popcountll(fm[s]));
+                        waiting += static_cast<uint32_t>(__builtin_popcountll(km));
                         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                         if (waiting >= 64) {
                             waiting -= 64;
                             walk_queued(waiting, 64);
                             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                            if (prune) {
+                                const double seen = wave_max_f64(bacc);
+                                if (seen > thr) {
+                                    thr = seen;
+                                    if (lane == 0) atomicMax(A.floor + m, static_cast<unsigned long long>(__double_as_longlong(seen)));
+                                }
+                                const double shared = __longlong_as_double(static_cast<long long>(
+                                    __hip_atomic_load(A.floor + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+                                if (shared > thr) thr = shared;
+                                thr_f = static_cast<float>(thr) * 0.99999f;
+                            }
                         }
                     }
-                    nfeas += run_feas;
+                    if (pass == 1) nfeas += run_feas;
                 }
             }
             e = run_hi;
+        }
+        if (pass == 0 && item_any) {
+            // walk every lane's candidate, unless what the demand point has reached elsewhere rules it out (and what
+            // was waiting), and take the threshold from the result
+            {
+                const double shared = __longlong_as_double(static_cast<long long>(
+                    __hip_atomic_load(A.floor + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+                if (shared > thr) thr = shared;
+            }
+            const bool have = cand_ub >= 0.0f && cand_ub * 1.00001f >= static_cast<float>(thr) * 0.99999f;
+            const uint64_t vote = __builtin_amdgcn_ballot_w64(have);
+            if (have) {
+                const uint32_t ee = cand_at >> 3, s_at = cand_at & 7u;
+                const uint32_t at = waiting + static_cast<uint32_t>(__builtin_popcountll(vote & ((1ull << lane) - 1)));
+                int32_t w_s = 0;
+#pragma unroll
+                for (int s = 0; s < S; s++) w_s = static_cast<uint32_t>(s) == s_at ? w[s] : w_s;
+                sWalkIdx[wave][at] = base_f + sChoice[ee] + strideL * (cl0 + s_at * 64);
+                sWalkW[wave][at] = W - sLim[ee].w_rem + w_s;
+            }
+            waiting += static_cast<uint32_t>(__builtin_popcountll(vote));
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            while (waiting > 0) {
+                const uint32_t take = waiting < 64 ? waiting : 64;
+                waiting -= take;
+                walk_queued(waiting, take);
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            }
+            const double seen = wave_max_f64(bacc);
+            if (seen > thr) {
+                thr = seen;
+                if (lane == 0) atomicMax(A.floor + m, static_cast<unsigned long long>(__double_as_longlong(seen)));
+            }
+        }
         }
     }
     // What is left in the four queues (fewer than 64 plans each) is walked by the block as a whole: the
@@ -2049,17 +2279,7 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
         if (have) {
             const uint64_t idx = sWalkIdx[src_wave][mine];
             const int32_t workers = sWalkW[src_wave][mine];
-            uint32_t c[kMaxTasks];
-            uint64_t rest = idx;
-#pragma unroll
-            for (int i = 0; i < kMaxTasks; i++) {
-                c[i] = 0;
-                if (i < n) {
-                    c[i] = static_cast<uint32_t>(rest % sP->C[i]);
-                    rest /= sP->C[i];
-                }
-            }
-            const double acc = path_objective<MAXD>(sP, A.path_acc, c, Dn);
+            const double acc = walk_plan<MAXD>(sP, A.path_acc, Dn, idx);
             if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
                 bacc = acc;
                 bw = workers;

@@ -98,6 +98,39 @@ def test_plans_that_split_traffic_at_every_task(variant_factors, per_variant_bat
     assert feasible > 300
 
 
+@pytest.mark.parametrize("n_tasks,k,replicas", [(2, 5, 2), (2, 5, 3), (3, 4, 1), (3, 3, 2), (1, 6, 2)])
+def test_chains_with_many_feasible_plans(n_tasks, k, replicas):
+    """Single task paths, where the tabulated search skips the walk for plans whose upper bound on the objective
+    cannot reach the best one seen: dense demand points (many feasible plans, many of them near the top),
+    several points per call, ties on and off, split ranges, against the checker's plain search."""
+    rng = wl.SplitMix64(300 + 10 * n_tasks + k)
+    p = wl.make_pipeline([-1] + list(range(n_tasks - 1)), k, replicas, (1, 4), rng)
+    p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(301 + k))
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    demands = [0, 20_000, 60_000, 120_000, 200_000, 350_000]
+    dense = 0
+    for flags in (0, TIE):
+        out = P.alloc_search(demands, 24, 400_000, flags=flags)
+        for d, res in zip(demands, out):
+            ref = O.search(d, 24, 400_000, tie_index_only=bool(flags & TIE))
+            assert agree(res, ref), (d, flags, res.as_tuple(), ref.as_tuple())
+            dense += ref.n_feasible * 20 > n
+    assert dense >= 2
+    a, b = n // 3 + 7, n - n // 4
+    for lo, hi in ((0, a), (a, b), (b, n)):
+        res = P.alloc_search([60_000], 24, 400_000, begin=lo, end=hi)[0]
+        assert agree(res, O.search(60_000, 24, 400_000, begin=lo, end=hi)), (lo, hi)
+    # a table that rises with the first task's variant only, and one that is constant: bounds that are tight
+    # for every plan (nothing can be skipped on the strength of the bound alone)
+    for table in ([600_000 + 40_000 * (e % k) for e in range(k ** n_tasks)], [777_000] * (k ** n_tasks)):
+        p.path_acc_ppm = table
+        P, O = binding.Problem(p), oracle.Problem(p)
+        for d in (60_000, 200_000):
+            res, ref = P.alloc_search([d], 24, 400_000)[0], O.search(d, 24, 400_000)
+            assert agree(res, ref), (d, res.as_tuple(), ref.as_tuple())
+
+
 def test_four_task_tree_with_three_variants():
     """Tree 0 -> 1 -> 2, 0 -> 3: two task paths of different length, tables of 27 and 9 entries, 8.5
     million plans, searched in one call for several demand points and in two halves."""
