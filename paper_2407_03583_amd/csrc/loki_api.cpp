@@ -132,7 +132,6 @@ struct loki_problem {
     std::vector<double> path_acc;  // profiled path accuracies as fractions (ppm / 10^6), all leaves
     // class-by-class searches: every choice of every task decoded once (replicas and batch position per
     // variant, at (table_off[i] + c) * kMaxVariants), filled on first use
-    std::vector<uint8_t> choice_x, choice_beta;
     // pinned staging of the (demand point, class) descriptors: [Dn 8 int64 | amount int64 | count u32 | point i32] arrays
     unsigned char *class_staging = nullptr;
     bool star = false;  // every other task is a child of the first task
@@ -145,6 +144,15 @@ struct loki_problem {
     std::vector<unsigned char> plain_block;
     hipEvent_t staged = nullptr, ev[4] = {nullptr, nullptr, nullptr, nullptr};
     bool staged_pending = false;
+    // A second set of the pinned buffers and their event: every search call takes the set the call before it
+    // did not use (rotate_staging), so that the host never waits for the copies of the call just enqueued, which
+    // sit behind that call's predecessors' kernels on the stream, but for those of the call before.
+    struct StagingSet {
+        unsigned char *class_staging = nullptr, *staging = nullptr;
+        int64_t cap_points = 0;
+        hipEvent_t staged = nullptr;
+        bool staged_pending = false;
+    } spare;
     float last_ms[3] = {0.f, 0.f, 0.f};  // per-task tables, main search kernel, final merge
     bool have_ms = false;
     uint64_t last_scored = 0;  // plans the kernels of the last search scored
@@ -185,11 +193,19 @@ size_t staging_bytes(const loki_problem *p, int64_t points) {
            align_up(size_t(points) * sizeof(loki_result_t));
 }
 
+void rotate_staging(loki_problem *p) {
+    std::swap(p->class_staging, p->spare.class_staging);
+    std::swap(p->staging, p->spare.staging);
+    std::swap(p->cap_points, p->spare.cap_points);
+    std::swap(p->staged, p->spare.staged);
+    std::swap(p->staged_pending, p->spare.staged_pending);
+}
+
 int ensure_staging(loki_problem *p, int64_t points) {
-    if (!p->staged) {  // first GPU use of this handle: events for staging reuse and timing
+    if (!p->staged)  // first GPU use of this set of buffers: the event for their reuse
         LOKI_HIP(hipEventCreateWithFlags(&p->staged, hipEventDisableTiming));
+    if (!p->ev[0])  // first GPU use of this handle: events for timing
         for (auto &e : p->ev) LOKI_HIP(hipEventCreate(&e));
-    }
     if (points <= p->cap_points) return LOKI_OK;
     if (p->staged_pending) {
         LOKI_HIP(hipEventSynchronize(p->staged));
@@ -248,53 +264,83 @@ int check_scalars(int32_t workers, int64_t slo_us, int64_t comm_us) {
     return LOKI_OK;
 }
 
-// What choice c of task i does with demand D in the task's own units (eq. (2), Algorithm 1's fill rule):
-// whether it serves all of it, and the requests it creates per unit of a child's fan-out,
-// sum_k routed(k) * r(i,k) (eq. (1) with per-variant factors).  Mirrors the kernels' eval_task.
-void decode_choices(loki_problem *p) {
-    const DevProblem &d = p->dev;
-    p->choice_x.assign(size_t(d.table_total) * kMaxVariants, 0);
-    p->choice_beta.assign(size_t(d.table_total) * kMaxVariants, 0);
-    for (int i = 0; i < p->n; i++) {
-        const int K = d.K[i], nb = d.nb[i];
-        for (uint32_t c0 = 0; c0 < d.C[i]; c0++) {
-            uint8_t *x = p->choice_x.data() + (size_t(d.table_off[i]) + c0) * kMaxVariants;
-            uint8_t *beta = p->choice_beta.data() + (size_t(d.table_off[i]) + c0) * kMaxVariants;
-            uint64_t c = c0;
-            for (int k = 0; k < K; k++) {
-                const uint64_t g = c % d.radix[i][k];
-                c /= d.radix[i][k];
-                if (d.pv_batch) {
-                    x[k] = uint8_t(g == 0 ? 0 : (g - 1) / nb + 1);
-                    beta[k] = uint8_t(g == 0 ? 0 : (g - 1) % nb);
-                } else {
-                    x[k] = uint8_t(g);
-                }
-            }
-            if (!d.pv_batch)
-                for (int k = 0; k < K; k++) beta[k] = uint8_t(c);
+// The classes of task i at demand D in the task's own units: the amounts of requests its usable choices create
+// per unit of a child's fan-out, sum_k routed(k) * r(i,k) (eq. (1) with per-variant factors; eq. (2) and
+// Algorithm 1's fill rule, as the kernels' eval_task has them), each with the number of choices that create it,
+// in ascending order of the amount.  The choices are not gone through one by one: with the variants taken most
+// accurate first, everything is settled once the variants so far reach D (they are full but the last, which
+// takes the rest), whatever the replicas of the variants after them, so the digits form a tree that is only
+// entered where the capacity so far is below D.
+typedef std::vector<std::pair<int64_t, uint32_t>> ClassList;
+
+struct ClassTree {
+    const DevProblem *d;
+    int i;
+    int64_t D;
+    bool per_variant;
+    uint32_t below[kMaxVariants + 1];  // choices of the variants from route position r on (one batch size per task:
+                                       // for one value of it)
+    ClassList *classes;
+    size_t last;  // the class hit last
+};
+
+void class_hit(ClassTree &t, int64_t amount, uint32_t count) {
+    ClassList &cl = *t.classes;
+    if (!t.per_variant) amount = -1;
+    if (t.last < cl.size() && cl[t.last].first == amount) {
+        cl[t.last].second += count;
+        return;
+    }
+    auto at = std::lower_bound(cl.begin(), cl.end(), amount,
+                               [](const std::pair<int64_t, uint32_t> &c, int64_t v) { return c.first < v; });
+    if (at != cl.end() && at->first == amount) at->second += count;
+    else at = cl.insert(at, std::make_pair(amount, count));
+    t.last = size_t(at - cl.begin());
+}
+
+// r: route position; upto < D: capacity of the variants before it; created: what they create when full;
+// batch: the task's batch position (one batch size per task).
+void class_tree(ClassTree &t, int r, int64_t upto, int64_t created, int batch) {
+    const DevProblem &d = *t.d;
+    const int i = t.i, k = d.order[i][r], nb = d.nb[i];
+    const int64_t factor = d.vf[i][k];
+    for (uint32_t g = 0; g < d.radix[i][k]; g++) {
+        int64_t x = g;
+        int beta = batch;
+        if (d.pv_batch) {  // g = 0: not hosted; else 1 + (replicas - 1) * |B_i| + batch position
+            x = g == 0 ? 0 : int64_t((g - 1) / uint32_t(nb)) + 1;
+            beta = g == 0 ? 0 : int((g - 1) % uint32_t(nb));
+        }
+        const int64_t mine = x * d.thr_s[i][k][beta];  // below 2^62 by the range proof of the throughputs
+        if (mine >= t.D - upto) {
+            class_hit(t, created + (t.D - upto) * factor, t.below[r + 1]);
+        } else if (r + 1 < d.K[i]) {
+            class_tree(t, r + 1, upto + mine, created + mine * factor, batch);
         }
     }
 }
 
-bool task_outflow(const loki_problem *p, int i, uint32_t c, int64_t D, int64_t *outflow) {
+void task_classes(const loki_problem *p, int i, int64_t D, bool per_variant, ClassList &classes) {
     const DevProblem &d = p->dev;
-    const int K = d.K[i];
-    const uint8_t *x = p->choice_x.data() + (size_t(d.table_off[i]) + c) * kMaxVariants;
-    const uint8_t *beta = p->choice_beta.data() + (size_t(d.table_off[i]) + c) * kMaxVariants;
-    int64_t rem = D, out = 0;
-    bool any = false;
-    for (int o = 0; o < K; o++) {
-        const int k = d.order[i][o];
-        if (x[k] == 0) continue;
-        const int64_t cap = int64_t(x[k]) * d.thr_s[i][k][beta[k]];
-        const int64_t routed = std::min(rem, cap);
-        out += routed * int64_t(d.vf[i][k]);
-        rem -= routed;
-        any = true;
+    classes.clear();
+    classes.reserve(64);
+    ClassTree t;
+    t.d = &d;
+    t.i = i;
+    t.D = D;
+    t.per_variant = per_variant;
+    t.classes = &classes;
+    t.last = ~size_t(0);
+    t.below[d.K[i]] = 1;
+    for (int r = d.K[i] - 1; r >= 0; r--) t.below[r] = t.below[r + 1] * d.radix[i][d.order[i][r]];
+    const int batches = d.pv_batch ? 1 : d.nb[i];
+    if (D == 0) {
+        // nothing to serve: every choice that hosts something is usable and creates nothing
+        const uint32_t hosting = (t.below[0] - 1) * uint32_t(batches);
+        if (hosting) class_hit(t, 0, hosting);
+        return;
     }
-    *outflow = out;
-    return any && rem == 0;
+    for (int b = 0; b < batches; b++) class_tree(t, 0, 0, 0, b);
 }
 
 // The points of a class-by-class search: per demand point every combination of one class per task that
@@ -324,12 +370,11 @@ int walk_classes(ClassWalk &w, int i) {
     const loki_problem *p = w.p;
     if (i == p->n) {
         if (int64_t(w.cp->size()) >= kMaxClassPoints) return LOKI_E_ARG;  // caller falls back
+        // (the slots past the last task hold 0 / -1 / 1 from the start of the demand point's walk)
         w.cp->point.push_back(w.point);
-        for (int j = 0; j < kMaxTasks; j++) {
-            w.cp->Dn.push_back(j < p->n ? w.Dn[j] : 0);
-            w.cp->amount.push_back(j < p->n ? w.amount[j] : -1);
-            w.cp->count.push_back(j < p->n ? w.count[j] : 1u);
-        }
+        w.cp->Dn.insert(w.cp->Dn.end(), w.Dn, w.Dn + kMaxTasks);
+        w.cp->amount.insert(w.cp->amount.end(), w.amount, w.amount + kMaxTasks);
+        w.cp->count.insert(w.cp->count.end(), w.count, w.count + kMaxTasks);
         return LOKI_OK;
     }
     // (one factor per edge: the demand is the parent's times the edge's factor, and every usable choice of a
@@ -344,17 +389,8 @@ int walk_classes(ClassWalk &w, int i) {
     auto key = std::make_pair(i, w.Dn[i]);
     auto it = w.memo.find(key);
     if (it == w.memo.end()) {
-        // few distinct amounts among many choices: a sorted list with binary search
-        std::vector<std::pair<int64_t, uint32_t>> classes;
-        for (uint32_t c = 0; c < p->dev.C[i]; c++) {
-            int64_t out;
-            if (!task_outflow(p, i, c, w.Dn[i], &out)) continue;
-            if (!per_variant) out = -1;
-            auto at = std::lower_bound(classes.begin(), classes.end(), out,
-                                       [](const std::pair<int64_t, uint32_t> &cls, int64_t v) { return cls.first < v; });
-            if (at != classes.end() && at->first == out) at->second++;
-            else classes.insert(at, std::make_pair(out, 1u));
-        }
+        ClassList classes;
+        task_classes(p, i, w.Dn[i], per_variant, classes);
         it = w.memo.emplace(key, std::move(classes)).first;
     }
     for (const auto &cls : it->second) {
@@ -370,7 +406,6 @@ int walk_classes(ClassWalk &w, int i) {
 // kMaxClassPoints; *next is the first demand point left out.  LOKI_E_ARG when a single demand point has more.
 int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t first, int32_t n_demand, ClassPoints &cp,
                        int32_t *next) {
-    if (p->choice_x.empty()) decode_choices(p);
     ClassWalk w;
     w.p = p;
     w.cp = &cp;
@@ -382,6 +417,11 @@ int build_class_points(loki_problem *p, const int64_t *demand_mqps, int32_t firs
         const size_t before = cp.size();
         w.memo.clear();
         w.point = m;
+        for (int j = 0; j < kMaxTasks; j++) {
+            w.Dn[j] = 0;
+            w.amount[j] = -1;
+            w.count[j] = 1u;
+        }
         w.Dn[0] = demand_mqps[m];
         const int rc2 = walk_classes(w, 0);
         if (rc2 == LOKI_E_ARG && m > first) {  // this demand point starts the next group
@@ -618,14 +658,8 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
         const int rc_m = task_demand(p, demand_mqps[m], bound);
         if (rc_m) return rc_m;
     }
-    int rc = ensure_staging(p, n_demand);
-    if (rc) return rc;
+    int rc = LOKI_OK;
     const size_t per_point = kMaxTasks * (2 * sizeof(int64_t) + sizeof(uint32_t)) + sizeof(int32_t);
-    if (!p->class_staging) {
-        void *ptr = nullptr;
-        LOKI_HIP(hipHostMalloc(&ptr, size_t(kMaxClassPoints) * per_point, hipHostMallocDefault));
-        p->class_staging = static_cast<unsigned char *>(ptr);
-    }
     unsigned char *ws = static_cast<unsigned char *>(d_workspace);
 
     MergeArgs G;
@@ -732,7 +766,15 @@ int enqueue_class_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_
             plan_class_batches(cp, items, class_batch(p->dev.table_total), class_items_per_block(p), batch_first);
         }
 
-        if (p->staged_pending) {  // earlier copies (a previous call, the previous group) may still read the staging buffers
+        // (the pinned buffers of this call's set; a demand point searched per lane in between has moved on to the other)
+        rc = ensure_staging(p, n_demand);
+        if (rc) return rc;
+        if (!p->class_staging) {
+            void *ptr = nullptr;
+            LOKI_HIP(hipHostMalloc(&ptr, size_t(kMaxClassPoints) * per_point, hipHostMallocDefault));
+            p->class_staging = static_cast<unsigned char *>(ptr);
+        }
+        if (p->staged_pending) {  // earlier copies (the call before the last, the previous group) may still read them
             LOKI_HIP(hipEventSynchronize(p->staged));
             p->staged_pending = false;
         }
@@ -803,6 +845,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     if (index_begin > index_end || index_end > p->n_candidates) return LOKI_E_ARG;
     int rc = check_scalars(workers, slo_us, comm_us);
     if (rc) return rc;
+    if (!no_alloc) rotate_staging(p);
     // eq. (7) on the variant paths with traffic couples the tasks of a path: whole plans per lane
     if (p->dev.lat_per_path) flags |= LOKI_SEARCH_PER_LANE;
     // Per-variant factors: a task's demand depends on its parent's part of the plan.  Where every other
@@ -1126,10 +1169,16 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
 
 void loki_problem_destroy(loki_problem_t *p) {
     if (!p) return;
-    if (p->staged_pending && p->staged) (void)hipEventSynchronize(p->staged);
-    if (p->staging) (void)hipHostFree(p->staging);
-    if (p->class_staging) (void)hipHostFree(p->class_staging);
-    if (p->staged) (void)hipEventDestroy(p->staged);
+    for (int set = 0; set < 2; set++) {
+        if (p->staged_pending && p->staged) (void)hipEventSynchronize(p->staged);
+        if (p->staging) (void)hipHostFree(p->staging);
+        if (p->class_staging) (void)hipHostFree(p->class_staging);
+        if (p->staged) (void)hipEventDestroy(p->staged);
+        p->staging = p->class_staging = nullptr;
+        p->staged = nullptr;
+        p->staged_pending = false;
+        rotate_staging(p);
+    }
     for (auto e : p->ev)
         if (e) (void)hipEventDestroy(e);
     delete p;
