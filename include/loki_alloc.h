@@ -341,6 +341,14 @@ int loki_last_search_ms(const loki_problem_t *problem, float *ms);
  * shorter than the space it is then an upper estimate.  LOKI_E_ARG before the first search. */
 int loki_last_search_plans_scored(const loki_problem_t *problem, uint64_t *plans);
 
+/* Width, in bits, of the integer arithmetic with which the most recent search of this handle that scored
+ * whole plans per lane (LOKI_SEARCH_PER_LANE, or a search the library took that way) filled the variants
+ * (eq. (2), Algorithm 1's fill rule): 32 when every R(i,k) * q * scale of the problem and every task's demand
+ * at every demand point of the call are below 2^32 (and the objective is the product form under the default
+ * latency rule), else 64.  The results are the same either way; the figure is for tests and measurements.
+ * LOKI_E_ARG before the first such search. */
+int loki_last_search_fill_bits(const loki_problem_t *problem, int32_t *bits);
+
 /* Measurement aid for the roofline (for callers that report a fraction of peak, not for the
  * search itself): sustained issue rate, in wavefront instructions per second over the whole
  * GPU, of a dependency-free stream of one vector-ALU instruction class, 8 wavefronts per SIMD.

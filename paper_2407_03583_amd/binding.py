@@ -28,7 +28,7 @@ UINT64_MAX = (1 << 64) - 1
 
 EXPORTS = ["loki_problem_create", "loki_problem_destroy", "loki_num_candidates", "loki_workspace_bytes",
            "loki_decode", "loki_alloc_search", "loki_alloc_search_enqueue", "loki_alloc_search_static", "loki_alloc_eval",
-           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_measure_valu_rate", "loki_last_search_ms", "loki_last_search_plans_scored", "loki_strerror", "loki_last_hip_error"]
+           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_measure_valu_rate", "loki_last_search_ms", "loki_last_search_plans_scored", "loki_last_search_fill_bits", "loki_strerror", "loki_last_hip_error"]
 
 
 class LokiError(RuntimeError):
@@ -148,6 +148,8 @@ def lib():
         L.loki_last_search_ms.argtypes = [P, C.POINTER(C.c_float)]
         L.loki_last_search_plans_scored.restype = C.c_int
         L.loki_last_search_plans_scored.argtypes = [P, C.POINTER(C.c_uint64)]
+        L.loki_last_search_fill_bits.restype = C.c_int
+        L.loki_last_search_fill_bits.argtypes = [P, C.POINTER(C.c_int32)]
         L.loki_strerror.restype = C.c_char_p
         L.loki_strerror.argtypes = [C.c_int]
         L.loki_last_hip_error.restype = C.c_int
@@ -310,6 +312,12 @@ class Problem:
         ms = (C.c_float * 3)()
         _check(lib().loki_last_search_ms(self._h, ms), "loki_last_search_ms")
         return [float(v) for v in ms]
+
+    def last_search_fill_bits(self) -> int:
+        """32 or 64: the integer width of the last per-lane search's fill."""
+        b = C.c_int32()
+        _check(lib().loki_last_search_fill_bits(self._h, C.byref(b)), "loki_last_search_fill_bits")
+        return int(b.value)
 
     def last_search_plans_scored(self) -> int:
         """Plans whose score the kernels of the last search formed (see the header)."""

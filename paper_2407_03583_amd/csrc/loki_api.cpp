@@ -128,6 +128,8 @@ struct loki_problem {
     int32_t voff[kMaxTasks];
     int32_t max_vf[kMaxTasks];  // largest variant factor of the task (4 without per-variant factors)
     int32_t sum_r[kMaxTasks];   // sum of the replica limits of the task
+    bool caps_fit32 = true;     // every R(i,k) * q * scale is below 2^32 (a per-lane search may fill in 32 bits)
+    int32_t last_fill_bits = 0; // width of the fill arithmetic of the last search that scored whole plans per lane
     uint64_t n_candidates;
     std::vector<double> path_acc;  // profiled path accuracies as fractions (ppm / 10^6), all leaves
     // class-by-class searches: every choice of every task decoded once (replicas and batch position per
@@ -945,6 +947,13 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         int path_levels = 0;
         if (p->dev.has_path)
             for (int i = 0; i < n; i++) path_levels = std::max(path_levels, p->dev.path_len[i]);
+        // the 32-bit fill: every capacity below 2^32 (shown when the handle was made) and so every task's demand
+        // at every point (with per-variant factors hDn holds what the task's demand cannot exceed)
+        bool narrow = p->caps_fit32 && path_levels == 0 && !p->dev.lat_per_path;
+        for (int32_t m = 0; narrow && m < n_demand; m++)
+            for (int i = 0; i < n; i++) narrow = narrow && hDn[size_t(m) * kMaxTasks + i] < (int64_t(1) << 32);
+        A.narrow = narrow ? 1u : 0u;
+        p->last_fill_bits = narrow ? 32 : 64;
         LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, path_levels,
                                         p->dev.lat_per_path != 0, stream));
         if (timed) LOKI_HIP(hipEventRecord(p->ev[2], stream));
@@ -1055,6 +1064,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
                 d.lat[i][k][bi] = int32_t(lat);  // range-checked above
                 if (thr > (int64_t(1) << 54) / scale) rc = LOKI_E_RANGE;  // keeps 255 replicas * thr * scale below 2^63
                 if (rc == LOKI_OK) d.thr_s[i][k][bi] = thr * scale;
+                if (rc == LOKI_OK && R > 0 && d.thr_s[i][k][bi] > ((int64_t(1) << 32) - 1) / R) p->caps_fit32 = false;
             }
         }
         if (rc) break;
@@ -1504,6 +1514,13 @@ int loki_measure_valu_rate(int kind, void *d_workspace, size_t workspace_bytes, 
     if (e1) (void)hipEventDestroy(e1);
     if (e != hipSuccess) return hip_fail(e);
     *wave_instructions_per_second = double(blocks) * 4.0 * double(iters) * 16.0 / (double(ms) * 1e-3);
+    return LOKI_OK;
+}
+
+int loki_last_search_fill_bits(const loki_problem_t *p, int32_t *bits) {
+    if (!p || !bits) return LOKI_E_NULL;
+    if (p->last_fill_bits == 0) return LOKI_E_ARG;
+    *bits = p->last_fill_bits;
     return LOKI_OK;
 }
 

@@ -152,6 +152,7 @@ struct SearchArgs {
     int32_t M;
     uint32_t blocks_per_m;
     uint32_t tie_index_only;
+    uint32_t narrow;        // per-lane search: every demand and every x * q * scale of the call is below 2^32
     uint32_t prune;         // profiled path accuracies, tabulated: feasible plans whose upper bound is below the
                             // best objective seen are not walked (one task path, one factor per edge, at most
                             // kMaxPrefix variant combinations above the last task)

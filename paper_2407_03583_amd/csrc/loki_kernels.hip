@@ -107,7 +107,9 @@ struct TaskOut {
 // position inside every variant's digit) and fill the hosted variants most accurate first
 // (eq. (2), Algorithm 1's fill rule).
 // PV: a batch size per hosted variant; VF: per-variant multiplicative factors.
-template <bool PV, bool VF>
+// NARROW: the caller has shown that the demand and every x * q * scale the task can meet are below 2^32: the
+// fill runs on 32-bit values (the sums of routed * accuracy and routed * factor stay 64-bit).  Same results.
+template <bool PV, bool VF, bool NARROW = false>
 __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o) {
     const int K = P->K[i];
     constexpr bool pv = PV;
@@ -134,10 +136,49 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         w += static_cast<int32_t>(x);
     }
     const uint32_t beta_task = c;
+    constexpr bool has_vf = VF;
+    if constexpr (NARROW) {
+        uint32_t rem = static_cast<uint32_t>(Dn);
+        uint64_t weighted = 0, outflow = 0;
+        int32_t any = 0, first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
+        uint32_t in_use = 0;
+        for (int r = 0; r < K; r++) {
+            const int k = P->order[i][r];
+            const uint32_t x = static_cast<uint32_t>(digits >> (8 * k)) & 0xffu;
+            const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
+            const uint32_t cap = x * static_cast<uint32_t>(P->thr_s[i][k][beta]);
+            const int32_t lat = P->lat[i][k][beta];
+            const uint32_t acc = static_cast<uint32_t>(P->acc[i][k]);
+            const uint32_t routed = rem < cap ? rem : cap;
+            const bool hosted = x > 0;
+            const bool used = hosted && (routed > 0 || !any);
+            if (used && lat > maxlat) maxlat = lat;
+            if (used) lat_bot = lat;
+            in_use |= used ? 1u << k : 0u;
+            if (hosted && !any) {
+                first_acc = static_cast<int32_t>(acc);
+                lat_top = lat;
+            }
+            weighted += static_cast<uint64_t>(routed) * acc;
+            if (has_vf) outflow += static_cast<uint64_t>(routed) * static_cast<uint32_t>(P->vf[i][k]);
+            rem -= routed;
+            any |= hosted ? 1 : 0;
+        }
+        o.w = w;
+        o.any = any;
+        o.rem = static_cast<int64_t>(rem);
+        o.maxlat = maxlat;
+        o.weighted = static_cast<int64_t>(weighted);
+        o.first_acc = first_acc;
+        o.outflow = static_cast<int64_t>(outflow);
+        o.used = in_use;
+        o.lat_top = lat_top;
+        o.lat_bot = lat_bot;
+        return;
+    }
     int64_t rem = Dn, weighted = 0, outflow = 0;
     int32_t any = 0, first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
     uint32_t in_use = 0;
-    constexpr bool has_vf = VF;
     for (int r = 0; r < K; r++) {
         const int k = P->order[i][r];
         const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
@@ -2318,7 +2359,8 @@ constexpr uint32_t kStrip = 64;
 // accuracy found in the scoring loop.
 constexpr int32_t kWalkCheckLatency = 1 << 30;  // queue entry: latency not settled yet (or'ed into the workers)
 
-template <bool PV, bool VF, int MAXD, bool LAT = false>
+// NARROW: the host has shown that every capacity and demand of the call is below 2^32 (eval_task's 32-bit fill).
+template <bool PV, bool VF, int MAXD, bool LAT = false, bool NARROW = false>
 __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_search_kernel(SearchArgs A) {
     constexpr bool kQueue = MAXD > 0 || LAT;
     constexpr int kLatLevels = MAXD > 0 ? MAXD : kMaxTasks;
@@ -2342,6 +2384,9 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
     // choice combinations of the other tasks touched by the range: far_span of them, cyclically from far_first
     const uint64_t items = A.far_span * n_strips;
     const double npd = static_cast<double>(P->n_paths);
+    // a power of two of task paths: dividing by it is multiplying by its inverse, exactly
+    const bool np_pow2 = (P->n_paths & (P->n_paths - 1)) == 0;
+    const double np_inv = 1.0 / npd;
     const int parL = n >= 2 ? P->parent[L] : 0;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int64_t Dn[kMaxTasks];
@@ -2393,7 +2438,7 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
     };
     auto task_of = [&](int i, uint32_t ci, int64_t dn, TaskOut &t) {
         if constexpr (LAT) eval_task_any(P, i, ci, dn, t);
-        else eval_task<PV, VF>(P, i, ci, dn, t);
+        else eval_task<PV, VF, NARROW>(P, i, ci, dn, t);
     };
     bool no_room = false;   // some chain's communication latency alone exceeds the SLO: nothing is feasible
     if constexpr (LAT) {
@@ -2511,7 +2556,7 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_sea
                         const double a = task_accuracy(t, dnL);
                         const double path = n >= 2 ? pre * a : a;
                         const double sum = first ? path : presum + path;
-                        acc = sum / npd;
+                        acc = np_pow2 ? sum * np_inv : sum / npd;
                         if (feasible && better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
                             bacc = acc;
                             bw = workers;
@@ -2816,6 +2861,18 @@ hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool 
 template <int MAXD>
 void launch_per_lane_depth(const SearchArgs &A, bool pv_batch, bool has_vf, hipStream_t stream) {
     const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
+    if constexpr (MAXD == 0) {
+        if (A.narrow) {
+            if (pv_batch) {
+                if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<true, true, 0, false, true>), grid, block, 0, stream, A);
+                else hipLaunchKernelGGL((per_lane_search_kernel<true, false, 0, false, true>), grid, block, 0, stream, A);
+            } else {
+                if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<false, true, 0, false, true>), grid, block, 0, stream, A);
+                else hipLaunchKernelGGL((per_lane_search_kernel<false, false, 0, false, true>), grid, block, 0, stream, A);
+            }
+            return;
+        }
+    }
     if (pv_batch) {
         if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<true, true, MAXD>), grid, block, 0, stream, A);
         else hipLaunchKernelGGL((per_lane_search_kernel<true, false, MAXD>), grid, block, 0, stream, A);
