@@ -349,17 +349,6 @@ int loki_last_search_plans_scored(const loki_problem_t *problem, uint64_t *plans
  * LOKI_E_ARG before the first such search. */
 int loki_last_search_fill_bits(const loki_problem_t *problem, int32_t *bits);
 
-/* Measurement aid for the roofline (for callers that report a fraction of peak, not for the
- * search itself): sustained issue rate, in wavefront instructions per second over the whole
- * GPU, of a dependency-free stream of one vector-ALU instruction class, 8 wavefronts per SIMD.
- *   kind  0 v_mul_f64, 1 v_add_f64, 2 v_max_f64, 3 the search's multiply/add/max mix, 4 v_add_u32,
- *         5 v_fma_f64, 6 v_rcp_f64, 7 v_mul_lo_u32, 8 v_mul_hi_u32, 9 v_min_u32,
- *         10 ds_read_b64 (LDS reads of 8 bytes per lane, 16 in flight per wavefront)
- *   d_workspace  device, >= 4 MiB.  Blocks until the measurement (tens of ms) is done.
- * The nominal figure is compute_units * 4 SIMDs * clock / 4 cycles. */
-int loki_measure_valu_rate(int kind, void *d_workspace, size_t workspace_bytes, void *hip_stream,
-                           double *wave_instructions_per_second);
-
 const char *loki_strerror(int code);
 int loki_last_hip_error(void);
 

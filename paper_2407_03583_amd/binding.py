@@ -28,7 +28,7 @@ UINT64_MAX = (1 << 64) - 1
 
 EXPORTS = ["loki_problem_create", "loki_problem_destroy", "loki_num_candidates", "loki_workspace_bytes",
            "loki_decode", "loki_alloc_search", "loki_alloc_search_enqueue", "loki_alloc_search_static", "loki_alloc_eval",
-           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_measure_valu_rate", "loki_last_search_ms", "loki_last_search_plans_scored", "loki_last_search_fill_bits", "loki_strerror", "loki_last_hip_error"]
+           "loki_route_table", "loki_route_workspace_bytes", "loki_route_table_batch", "loki_plan_trace", "loki_last_search_ms", "loki_last_search_plans_scored", "loki_last_search_fill_bits", "loki_strerror", "loki_last_hip_error"]
 
 
 class LokiError(RuntimeError):
@@ -142,8 +142,6 @@ def lib():
         L.loki_plan_trace.restype = C.c_int
         L.loki_plan_trace.argtypes = [P, C.POINTER(C.c_int64), C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                       C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(PlanStep)]
-        L.loki_measure_valu_rate.restype = C.c_int
-        L.loki_measure_valu_rate.argtypes = [C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
         L.loki_last_search_ms.restype = C.c_int
         L.loki_last_search_ms.argtypes = [P, C.POINTER(C.c_float)]
         L.loki_last_search_plans_scored.restype = C.c_int
@@ -330,14 +328,35 @@ RATE_KINDS = {"v_mul_f64": 0, "v_add_f64": 1, "v_max_f64": 2, "search_mix": 3, "
               "v_rcp_f64": 6, "v_mul_lo_u32": 7, "v_mul_hi_u32": 8, "v_min_u32": 9, "ds_read_b64": 10}
 
 
+PROBE_EXPORTS = ["loki_measure_valu_rate"]   # include/loki_probe.h, libloki_probe.so
+_probe = None
+
+
+def probe_lib():
+    """The instruction-rate probe, a library of its own beside the search library."""
+    global _probe
+    if _probe is None:
+        from . import build
+        if not os.path.exists(build.PROBE_LIB):
+            raise RuntimeError(f"{build.PROBE_LIB} is missing: run `python -m paper_2407_03583_amd.build` first")
+        import torch  # noqa: F401  (its HIP runtime first, as for the search library)
+        L = C.CDLL(build.PROBE_LIB)
+        L.loki_measure_valu_rate.restype = C.c_int
+        L.loki_measure_valu_rate.argtypes = [C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double),
+                                             C.POINTER(C.c_int)]
+        _probe = L
+    return _probe
+
+
 def measure_valu_rate(kind: str) -> float:
     """Sustained wavefront instructions per second of one vector-ALU instruction class."""
     import torch
     ws = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")
-    rate = C.c_double()
-    _check(lib().loki_measure_valu_rate(RATE_KINDS[kind], ws.data_ptr(), ws.numel(),
-                                        int(torch.cuda.current_stream().cuda_stream), C.byref(rate)),
-           "loki_measure_valu_rate")
+    rate, hip_error = C.c_double(), C.c_int(0)
+    rc = probe_lib().loki_measure_valu_rate(RATE_KINDS[kind], ws.data_ptr(), ws.numel(),
+                                            int(torch.cuda.current_stream().cuda_stream), C.byref(rate), C.byref(hip_error))
+    if rc != 0:
+        raise RuntimeError(f"loki_measure_valu_rate: error {rc} (HIP code {hip_error.value})")
     return float(rate.value)
 
 

@@ -1487,36 +1487,6 @@ int loki_last_search_ms(const loki_problem_t *p, float *ms) {
     return LOKI_OK;
 }
 
-int loki_measure_valu_rate(int kind, void *d_workspace, size_t workspace_bytes, void *hip_stream,
-                           double *wave_instructions_per_second) {
-    if (!d_workspace || !wave_instructions_per_second) return LOKI_E_NULL;
-    if (kind < 0 || kind > LOKI_RATE_LAST) return LOKI_E_ARG;
-    // many short blocks: the block dispatcher then keeps every SIMD full to the end, as in the search
-    // (fewer trips for the classes that issue at a quarter of the rate or less)
-    const bool slow = kind == LOKI_RATE_RCP_F64 || kind == LOKI_RATE_MUL_LO_U32 || kind == LOKI_RATE_MUL_HI_U32 ||
-                      kind == LOKI_RATE_LDS_READ_B64;
-    const int blocks = 32768, iters = slow ? 1000 : 6250, sink_blocks = 2048;
-    if (workspace_bytes < size_t(sink_blocks) * 256 * sizeof(double) || (reinterpret_cast<uintptr_t>(d_workspace) % 8) != 0)
-        return LOKI_E_WORKSPACE;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    LOKI_HIP(hipEventCreate(&e0));
-    hipError_t e = hipEventCreate(&e1);
-    double *out = static_cast<double *>(d_workspace);
-    if (e == hipSuccess) e = launch_valu_rate(kind, out, blocks, 100, stream);  // warm-up
-    if (e == hipSuccess) e = hipEventRecord(e0, stream);
-    if (e == hipSuccess) e = launch_valu_rate(kind, out, blocks, iters, stream);
-    if (e == hipSuccess) e = hipEventRecord(e1, stream);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    (void)hipEventDestroy(e0);
-    if (e1) (void)hipEventDestroy(e1);
-    if (e != hipSuccess) return hip_fail(e);
-    *wave_instructions_per_second = double(blocks) * 4.0 * double(iters) * 16.0 / (double(ms) * 1e-3);
-    return LOKI_OK;
-}
-
 int loki_last_search_fill_bits(const loki_problem_t *p, int32_t *bits) {
     if (!p || !bits) return LOKI_E_NULL;
     if (p->last_fill_bits == 0) return LOKI_E_ARG;

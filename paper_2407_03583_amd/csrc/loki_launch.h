@@ -26,21 +26,4 @@ hipError_t launch_class_merge(const MergeArgs &A, hipStream_t stream);
 hipError_t launch_eval(const EvalArgs &A, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &A, hipStream_t stream);
 
-// instruction classes of launch_valu_rate (mirrors LOKI_RATE_* of the public header)
-#define LOKI_RATE_MUL_F64 0
-#define LOKI_RATE_ADD_F64 1
-#define LOKI_RATE_MAX_F64 2
-#define LOKI_RATE_SEARCH_MIX 3
-#define LOKI_RATE_ADD_U32 4
-#define LOKI_RATE_FMA_F64 5
-#define LOKI_RATE_RCP_F64 6
-#define LOKI_RATE_MUL_LO_U32 7
-#define LOKI_RATE_MUL_HI_U32 8
-#define LOKI_RATE_MIN_U32 9
-#define LOKI_RATE_LDS_READ_B64 10
-#define LOKI_RATE_LAST LOKI_RATE_LDS_READ_B64
-// `out` needs 2048 * 256 doubles (a sink shared by blocks 2048 apart); every thread runs iters trips
-// of 16 instructions
-hipError_t launch_valu_rate(int kind, double *out, int blocks, int iters, hipStream_t stream);
-
 }  // namespace loki

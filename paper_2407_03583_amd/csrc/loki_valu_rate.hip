@@ -2,9 +2,26 @@
 // with dependency-free streams (16 independent instructions per loop trip, up to 8 wavefronts
 // per SIMD, many more blocks than fit at once).  A measurement aid for the roofline: the nominal peak assumes one vector instruction
 // per SIMD every 4 cycles at 2.4 GHz; this tells what the GPU at hand actually sustains.
+// Built into a library of its own (libloki_probe.so, include/loki_probe.h): the search library does not carry it.
 #include <hip/hip_runtime.h>
 
-#include "loki_launch.h"
+#include <stdint.h>
+
+#include "../../include/loki_probe.h"
+
+// instruction classes (the `kind` of loki_measure_valu_rate)
+#define LOKI_RATE_MUL_F64 0
+#define LOKI_RATE_ADD_F64 1
+#define LOKI_RATE_MAX_F64 2
+#define LOKI_RATE_SEARCH_MIX 3
+#define LOKI_RATE_ADD_U32 4
+#define LOKI_RATE_FMA_F64 5
+#define LOKI_RATE_RCP_F64 6
+#define LOKI_RATE_MUL_LO_U32 7
+#define LOKI_RATE_MUL_HI_U32 8
+#define LOKI_RATE_MIN_U32 9
+#define LOKI_RATE_LDS_READ_B64 10
+#define LOKI_RATE_LAST LOKI_RATE_LDS_READ_B64
 
 #pragma clang fp contract(off)
 
@@ -119,7 +136,9 @@ __global__ void __launch_bounds__(256) valu_rate_kernel(double *out, int iters, 
 
 }  // namespace
 
-hipError_t launch_valu_rate(int kind, double *out, int blocks, int iters, hipStream_t stream) {
+// `out` needs 2048 * 256 doubles (a sink shared by blocks 2048 apart); every thread runs iters trips
+// of 16 instructions
+static hipError_t launch_valu_rate(int kind, double *out, int blocks, int iters, hipStream_t stream) {
     const dim3 grid(blocks), block(256);
     switch (kind) {
         case LOKI_RATE_MUL_F64: hipLaunchKernelGGL(valu_rate_kernel<LOKI_RATE_MUL_F64>, grid, block, 0, stream, out, iters, 0.5); break;
@@ -139,3 +158,36 @@ hipError_t launch_valu_rate(int kind, double *out, int blocks, int iters, hipStr
 }
 
 }  // namespace loki
+
+extern "C" int loki_measure_valu_rate(int kind, void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                                      double *wave_instructions_per_second, int *hip_error) {
+    if (!d_workspace || !wave_instructions_per_second) return -1;
+    if (kind < 0 || kind > LOKI_RATE_LAST) return -6;
+    // many short blocks: the block dispatcher then keeps every SIMD full to the end, as in the search
+    // (fewer trips for the classes that issue at a quarter of the rate or less)
+    const bool slow = kind == LOKI_RATE_RCP_F64 || kind == LOKI_RATE_MUL_LO_U32 || kind == LOKI_RATE_MUL_HI_U32 ||
+                      kind == LOKI_RATE_LDS_READ_B64;
+    const int blocks = 32768, iters = slow ? 1000 : 6250, sink_blocks = 2048;
+    if (workspace_bytes < size_t(sink_blocks) * 256 * sizeof(double) || (reinterpret_cast<uintptr_t>(d_workspace) % 8) != 0)
+        return -4;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    double *out = static_cast<double *>(d_workspace);
+    if (e == hipSuccess) e = loki::launch_valu_rate(kind, out, blocks, 100, stream);  // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, stream);
+    if (e == hipSuccess) e = loki::launch_valu_rate(kind, out, blocks, iters, stream);
+    if (e == hipSuccess) e = hipEventRecord(e1, stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e != hipSuccess) {
+        if (hip_error) *hip_error = static_cast<int>(e);
+        return -5;
+    }
+    *wave_instructions_per_second = double(blocks) * 4.0 * double(iters) * 16.0 / (double(ms) * 1e-3);
+    return 0;
+}

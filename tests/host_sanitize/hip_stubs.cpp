@@ -136,9 +136,5 @@ hipError_t launch_route(const RouteArgs &A, hipStream_t) {
     touch(A.out, size_t(A.n));
     return hipSuccess;
 }
-hipError_t launch_valu_rate(int, double *out, int, int, hipStream_t) {
-    touch(out, size_t(2048) * 256);
-    return hipSuccess;
-}
 
 }  // namespace loki

@@ -21,6 +21,11 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert hasattr(L, name), name
     assert declared == set(binding.EXPORTS)
+    # the instruction-rate probe is a library of its own with a header of its own
+    probe = set(re.findall(r"\b(loki_[a-z_]+)\s*\(", open(os.path.join(ROOT, "include", "loki_probe.h")).read()))
+    assert probe == set(binding.PROBE_EXPORTS) and not probe & declared
+    for name in probe:
+        assert hasattr(binding.probe_lib(), name) and not hasattr(L, name), name
 
 
 def test_num_candidates_and_decode_match_the_checker():
