@@ -44,10 +44,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (2155 + 7215) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (253.5 + 1024) * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (2155 + 7201) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (246.5 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "1b40a72382a35e72c10d2e99ad74c2434ff566a589884b99aa78b583d32bc3a6"
+TRAFFIC_SOURCES_SHA256 = "17af321c7a4346efdcb6cce89dd314a26f1ac84e7cbbc71181749bc9afc1ea60"
 
 
 def measured_traffic(workload: str, kernel: str):

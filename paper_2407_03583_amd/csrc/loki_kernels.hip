@@ -143,7 +143,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         int32_t any = 0, first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
         uint32_t in_use = 0;
         for (int r = 0; r < K; r++) {
-            const int k = P->order[i][r];
+            const int k = uni(P->order[i][r]);  // the same in every lane: the table addresses below stay scalar
             const uint32_t x = static_cast<uint32_t>(digits >> (8 * k)) & 0xffu;
             const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
             const uint32_t cap = x * static_cast<uint32_t>(P->thr_s[i][k][beta]);
