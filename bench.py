@@ -47,7 +47,7 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (2155 + 7201) * 1024,
                           ("cfg5_tree4_k4", "per_lane"): (246.5 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "17af321c7a4346efdcb6cce89dd314a26f1ac84e7cbbc71181749bc9afc1ea60"
+TRAFFIC_SOURCES_SHA256 = "7b2f78abee6cf6ba90536c57b5a4680cf2c07fd5d66f18feb855ed2ab4ba8bc7"
 
 
 def measured_traffic(workload: str, kernel: str):

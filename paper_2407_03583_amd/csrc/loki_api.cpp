@@ -954,8 +954,11 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
             for (int i = 0; i < n; i++) narrow = narrow && hDn[size_t(m) * kMaxTasks + i] < (int64_t(1) << 32);
         A.narrow = narrow ? 1u : 0u;
         p->last_fill_bits = narrow ? 32 : 64;
-        LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, path_levels,
-                                        p->dev.lat_per_path != 0, stream));
+        int latency_levels = 0;
+        if (p->dev.lat_per_path)
+            for (int i = 0; i < n; i++) latency_levels = std::max(latency_levels, p->dev.path_len[i]);
+        LOKI_HIP(launch_per_lane_search(A, p->dev.pv_batch != 0, p->dev.has_vf != 0, path_levels, latency_levels,
+                                        stream));
         if (timed) LOKI_HIP(hipEventRecord(p->ev[2], stream));
         LOKI_HIP(launch_final_reduce(A, stream));
     } else {

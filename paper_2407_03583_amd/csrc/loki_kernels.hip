@@ -2360,10 +2360,19 @@ constexpr uint32_t kStrip = 64;
 constexpr int32_t kWalkCheckLatency = 1 << 30;  // queue entry: latency not settled yet (or'ed into the workers)
 
 // NARROW: the host has shown that every capacity and demand of the call is below 2^32 (eval_task's 32-bit fill).
-template <bool PV, bool VF, int MAXD, bool LAT = false, bool NARROW = false>
-__global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 3 : 1) per_lane_search_kernel(SearchArgs A) {
+// LATD: 0, or with LAT the number of levels of the walk over the variant paths compiled in (the longest task
+// path of the problem, 4 or 8; MAXD when that is not 0).  The kernels with a latency walk are held to the
+// registers of 2 wavefronts per SIMD: 3 spill into the scoring loop, and 1 (twice the registers, the upper half
+// of them reachable only through copies) leaves the loop's waits uncovered; built that way the eight-level
+// kernel with both walks also returned a plan below the best one, which tests/test_gpu_latency_per_path.py
+// now checks for on a six-task chain.
+template <bool PV, bool VF, int MAXD, int LATD = 0, bool NARROW = false>
+__global__ void __launch_bounds__(kBlockThreads, LATD > 0 ? 2 : (MAXD == 4 ? 3 : 1))
+    per_lane_search_kernel(SearchArgs A) {
+    constexpr bool LAT = LATD > 0;
     constexpr bool kQueue = MAXD > 0 || LAT;
-    constexpr int kLatLevels = MAXD > 0 ? MAXD : kMaxTasks;
+    constexpr int kLatLevels = LATD > 0 ? LATD : 1;
+    static_assert(MAXD == 0 || LATD == 0 || LATD == MAXD, "one depth for both walks");
     __shared__ DevProblem sP;
     __shared__ BestRec sBest[kWavesPerBlock];
     __shared__ uint64_t sWalkIdx[kQueue ? kWavesPerBlock : 1][kQueue ? kWalkQueue : 1];
@@ -2864,11 +2873,11 @@ void launch_per_lane_depth(const SearchArgs &A, bool pv_batch, bool has_vf, hipS
     if constexpr (MAXD == 0) {
         if (A.narrow) {
             if (pv_batch) {
-                if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<true, true, 0, false, true>), grid, block, 0, stream, A);
-                else hipLaunchKernelGGL((per_lane_search_kernel<true, false, 0, false, true>), grid, block, 0, stream, A);
+                if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<true, true, 0, 0, true>), grid, block, 0, stream, A);
+                else hipLaunchKernelGGL((per_lane_search_kernel<true, false, 0, 0, true>), grid, block, 0, stream, A);
             } else {
-                if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<false, true, 0, false, true>), grid, block, 0, stream, A);
-                else hipLaunchKernelGGL((per_lane_search_kernel<false, false, 0, false, true>), grid, block, 0, stream, A);
+                if (has_vf) hipLaunchKernelGGL((per_lane_search_kernel<false, true, 0, 0, true>), grid, block, 0, stream, A);
+                else hipLaunchKernelGGL((per_lane_search_kernel<false, false, 0, 0, true>), grid, block, 0, stream, A);
             }
             return;
         }
@@ -2882,13 +2891,19 @@ void launch_per_lane_depth(const SearchArgs &A, bool pv_batch, bool has_vf, hipS
     }
 }
 
-hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels, bool latency_per_path,
+hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels, int latency_levels,
                                   hipStream_t stream) {
-    if (latency_per_path) {
+    if (latency_levels > 0) {
         const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
-        if (path_levels <= 0) hipLaunchKernelGGL((per_lane_search_kernel<false, false, 0, true>), grid, block, 0, stream, A);
-        else if (path_levels <= 4) hipLaunchKernelGGL((per_lane_search_kernel<false, false, 4, true>), grid, block, 0, stream, A);
-        else hipLaunchKernelGGL((per_lane_search_kernel<false, false, kMaxTasks, true>), grid, block, 0, stream, A);
+        const bool deep = latency_levels > 4;
+        if (path_levels <= 0) {
+            if (deep) hipLaunchKernelGGL((per_lane_search_kernel<false, false, 0, kMaxTasks>), grid, block, 0, stream, A);
+            else hipLaunchKernelGGL((per_lane_search_kernel<false, false, 0, 4>), grid, block, 0, stream, A);
+        } else if (deep) {
+            hipLaunchKernelGGL((per_lane_search_kernel<false, false, kMaxTasks, kMaxTasks>), grid, block, 0, stream, A);
+        } else {
+            hipLaunchKernelGGL((per_lane_search_kernel<false, false, 4, 4>), grid, block, 0, stream, A);
+        }
         return hipGetLastError();
     }
     if (path_levels <= 0) launch_per_lane_depth<0>(A, pv_batch, has_vf, stream);

@@ -17,9 +17,10 @@ hipError_t launch_combine(const SearchArgs &A, int slots, bool has_presum, bool 
 // path_levels: 0, or with profiled path accuracies the number of tasks on the longest root-to-leaf chain
 // (selects how many levels of the walk over the variant paths are compiled in)
 hipError_t launch_path_combine(const SearchArgs &A, int slots, bool range, int path_levels, hipStream_t stream);
-// latency_per_path: eq. (7) on the variant paths with traffic (DevProblem::lat_per_path must be set)
+// latency_levels: 0, or for eq. (7) on the variant paths with traffic (DevProblem::lat_per_path must be set) the
+// number of tasks on the longest root-to-leaf chain
 hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels,
-                                  bool latency_per_path, hipStream_t stream);
+                                  int latency_levels, hipStream_t stream);
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_results_init(const MergeArgs &A, hipStream_t stream);
 hipError_t launch_class_merge(const MergeArgs &A, hipStream_t stream);

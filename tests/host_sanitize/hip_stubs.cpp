@@ -102,7 +102,7 @@ hipError_t launch_path_combine(const SearchArgs &A, int slots, bool, int, hipStr
     if (slots != 4 && slots != 8) return hipErrorInvalidValue;
     return visit(A);
 }
-hipError_t launch_per_lane_search(const SearchArgs &A, bool, bool, int, bool, hipStream_t) { return visit(A); }
+hipError_t launch_per_lane_search(const SearchArgs &A, bool, bool, int, int, hipStream_t) { return visit(A); }
 
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t) {
     // "nothing found" for every point

@@ -211,6 +211,28 @@ def test_four_task_tree_with_268_million_plans():
     assert ref.n_feasible > 0
 
 
+@pytest.mark.parametrize("path_tables", [False, True])
+def test_six_task_chain_takes_the_eight_level_walk(path_tables):
+    """Task paths of more than four tasks use the kernel with eight levels of the walk compiled in (with and
+    without profiled path accuracies, whose own walk then has eight levels too)."""
+    rng = random.Random(77)
+    p, demand, slos = split_traffic_problem(rng, [-1, 0, 1, 2, 3, 4])
+    if path_tables:
+        p.path_acc_ppm = wl.draw_path_tables(p, wl.SplitMix64(5))
+    p = with_rule(p, True)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n >= 4096
+    found = 0
+    for slo in slos:
+        check_plans(P, O, rng.sample(range(n), min(n, 4000)), demand, 99, slo)
+        for d, res in zip([demand, demand // 2], P.alloc_search([demand, demand // 2], 99, slo)):
+            ref = O.search(d, 99, slo)
+            assert agree(res, ref), (slo, d, res.as_tuple(), ref.as_tuple())
+            found += ref.found
+    assert found >= 1
+
+
 def test_entry_point_without_allocation_follows_the_rule():
     rng = random.Random(1003)
     p, demand, slos = split_traffic_problem(rng, [-1, 0, 1, 1])
