@@ -5,6 +5,7 @@ tests/host_sanitize/hip_stubs.cpp stands in for the HIP runtime and for the kern
 every array its kernel would write, so a layout that is too small is an ASan report); tests/host_sanitize/
 driver.cpp reads one problem from a text file, runs every entry point over it and prints what the host
 computes itself, which is compared with the CPU checker here.  No GPU."""
+import itertools
 import os
 import random
 import subprocess
@@ -123,6 +124,92 @@ def test_model_variants_run_clean(driver, tmp_path, cfg, what):
     lines = run(driver, tmp_path, p, demands, w.workers, w.slo_us, w.comm_us, indices, [0, n // 2, n // 5, n // 5 + 99999])
     assert all("rc 0" in ln for ln in lines if ln.startswith(("search", "range")))
     check_host_outputs(lines, p, demands[0], indices)
+
+
+def plans_with_usable_inner_choices(p, demand):
+    """Plans in which every task that has children serves all the demand its ancestors' choices create for it
+    (eq. (1) with per-variant factors, eq. (2) with most-accurate-first filling): what a class-by-class search
+    hands to the kernels.  Plain enumeration over the choices, task by task, in exact integers."""
+    n = p.n_tasks
+    voff = [sum(p.n_variants[:i]) for i in range(n + 1)]
+    boff = [0]
+    for i in range(n):
+        boff.append(boff[-1] + p.n_variants[i] * p.n_batches[i])
+    depth = [0] * n
+    for i in range(1, n):
+        depth[i] = depth[p.parent[i]] + 1
+    has_children = [i in p.parent for i in range(n)]
+    pv = getattr(p, "per_variant_batch", False)
+
+    def choices(i):
+        """(replicas, batch position) per variant for every choice of task i."""
+        K, nb = p.n_variants[i], p.n_batches[i]
+        R = p.max_replicas[voff[i]:voff[i + 1]]
+        per_variant = [[(0, 0)] + [(x, b) for x in range(1, R[k] + 1) for b in range(nb)] for k in range(K)] if pv else None
+        if pv:
+            return [list(c) for c in itertools.product(*per_variant)]
+        return [[(x, b) for x in xs] for b in range(nb) for xs in itertools.product(*[range(R[k] + 1) for k in range(K)])]
+
+    def created(i, choice, D):
+        """None if the choice cannot serve D; else what it creates per unit of a child's fan-out."""
+        K, nb = p.n_variants[i], p.n_batches[i]
+        order = sorted(range(K), key=lambda k: (-p.acc_ppm[voff[i] + k], k))
+        rem, out, any_hosted = D, 0, False
+        for k in order:
+            x, b = choice[k]
+            if x == 0:
+                continue
+            any_hosted = True
+            cap = x * p.thr_mqps[boff[i] + k * nb + b] * 16 ** depth[i]
+            routed = min(rem, cap)
+            out += routed * p.variant_factor_q4[voff[i] + k]
+            rem -= routed
+        return out if any_hosted and rem == 0 else None
+
+    all_choices = [choices(i) for i in range(n)]
+
+    def count(i, demand_of):
+        if i == n:
+            return 1
+        D = demand_of[i]
+        if not has_children[i]:
+            return len(all_choices[i]) * count(i + 1, demand_of)
+        by_amount = {}
+        for c in all_choices[i]:
+            out = created(i, c, D)
+            if out is not None:
+                by_amount[out] = by_amount.get(out, 0) + 1
+        total = 0
+        for out, members in by_amount.items():
+            nxt = dict(demand_of)
+            for j in range(i + 1, n):
+                if p.parent[j] == i:
+                    nxt[j] = out * p.fanout_q4[j]
+            total += members * count(i + 1, nxt)
+        return total
+
+    return count(0, {0: demand})
+
+
+def test_class_counts_against_plain_enumeration(driver, tmp_path):
+    """The host finds the classes of a task from a walk over the tree of its variants' digits; the number of
+    plans it hands to the kernels (loki_last_search_plans_scored) must be the number of plans whose tasks with
+    children can all serve their demand, counted here choice by choice."""
+    by_class = 0
+    for seed in range(40):
+        w = wl.random_small(seed, max_candidates=6000, variant_factors=True, per_variant_batch=seed % 3 == 2)
+        p = w.pipeline
+        n = p.num_candidates()
+        demands = [w.demand_mqps[0], w.demand_mqps[0] // 2, 0]
+        lines = run(driver, tmp_path, p, demands, w.workers, w.slo_us, w.comm_us)
+        scored = [int(ln.split()[2]) for ln in lines if ln.startswith("scored 0 ")]
+        assert len(scored) == 4
+        want = sum(plans_with_usable_inner_choices(p, d) for d in demands)
+        # flags 0 and 1: class by class where the problem allows it; 2 and 3: whole plans per lane
+        assert scored[2] == scored[3] == n * len(demands)
+        assert scored[0] == scored[1] and scored[0] in (want, n * len(demands)), (seed, scored, want, n)
+        by_class += scored[0] == want and want != n * len(demands)
+    assert by_class >= 10, by_class
 
 
 def test_limit_cases_run_clean(driver, tmp_path):
