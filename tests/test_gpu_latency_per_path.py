@@ -231,6 +231,12 @@ def test_six_task_chain_takes_the_eight_level_walk(path_tables):
             assert agree(res, ref), (slo, d, res.as_tuple(), ref.as_tuple())
             found += ref.found
     assert found >= 1
+    # the same chain under the default rule, tabulated and per lane (the eight-level kernels without the latency walk)
+    q = with_rule(p, False)
+    P0, O0 = binding.Problem(q), oracle.Problem(q)
+    for flags in (0, LANE):
+        for d, res in zip([demand, demand // 2], P0.alloc_search([demand, demand // 2], 99, slos[1], flags=flags)):
+            assert agree(res, O0.search(d, 99, slos[1])), (flags, d)
 
 
 def test_entry_point_without_allocation_follows_the_rule():
