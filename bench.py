@@ -47,7 +47,7 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (2155 + 7201) * 1024,
                           ("cfg5_tree4_k4", "per_lane"): (246.5 + 1024) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "7b2f78abee6cf6ba90536c57b5a4680cf2c07fd5d66f18feb855ed2ab4ba8bc7"
+TRAFFIC_SOURCES_SHA256 = "e43c369b8aa842153dbf0abc6169cb61124cddc91a7c979ced847c774306d927"
 
 
 def measured_traffic(workload: str, kernel: str):
@@ -89,8 +89,9 @@ def main() -> int:
                     help="objective from seeded profiled path accuracies (feasibility from the per-task tables; "
                          "one value per leaf on trees, a walk over the variant paths of feasible plans on chains)")
     ap.add_argument("--latency-per-path", action="store_true",
-                    help="eq. (7) on every variant path with traffic instead of the per-task bound "
-                         "(whole plans per lane: the library takes that kernel under this rule)")
+                    help="eq. (7) on every variant path with traffic instead of the per-task bound (tabulated, "
+                         "with a second kernel for the plans only this rule admits; with --variant-factors or "
+                         "--path-tables whole plans per lane)")
     ap.add_argument("--demand-qps", type=float, default=None,
                     help="replace the configuration's demand points by this one demand (queries/s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -132,7 +133,9 @@ def main() -> int:
     # what the library does anyway: per-variant factors are searched class by class by the tabulated kernels
     # (two or more tasks); profiled path accuracies with the feasibility part tabulated and the variant paths
     # walked for feasible plans only
-    args.per_lane = args.per_lane or args.latency_per_path
+    # (the per-path latency rule: on the tables with a second kernel for the plans only that rule admits, unless
+    # per-variant factors or path tables are present as well, where the library scores whole plans per lane)
+    args.per_lane = args.per_lane or (args.latency_per_path and (args.variant_factors or args.path_tables))
     by_class = args.variant_factors and w.pipeline.n_tasks >= 2 and not args.per_lane
     args.per_lane = args.per_lane or (args.variant_factors and not by_class)
     P = binding.Problem(w.pipeline)

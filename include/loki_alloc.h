@@ -163,9 +163,14 @@ typedef struct {
                                     limit nothing.  At zero demand the first hosted variants stand for the plan.
                                     LOKI_BAD_LATENCY is then reported only for plans that host every task and
                                     serve all demand (the routing of the others is not defined).  A plan that
-                                    is feasible under 0 is feasible under 1.  Searches score whole plans per
-                                    lane under this rule (LOKI_SEARCH_PER_LANE is implied): the per-task bound
-                                    decides most plans, the others walk their variant paths. */
+                                    is feasible under 0 is feasible under 1.  A search under this rule takes
+                                    the plans that 0 admits from the per-task tables as ever, and picks out, in
+                                    a second pass over the plan space, the plans 0 rejects whose two variant
+                                    paths that always carry requests (the first and the last variants in use of
+                                    every task) meet the budget: only those walk their variant paths.  With
+                                    per-variant factors or profiled path accuracies as well, whole plans are
+                                    scored per lane (LOKI_SEARCH_PER_LANE is implied), with the same two bounds
+                                    deciding most plans. */
 } loki_pipeline_t;
 
 typedef struct loki_problem loki_problem_t; /* opaque handle */

@@ -44,26 +44,31 @@ thread_local int g_last_hip = 0;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t off_P, off_Dn, off_table, off_perm, off_run, off_perm_all, off_run_t, off_recs, off_floor, off_results, total;
+    size_t off_P, off_Dn, off_table, off_lat2, off_perm, off_run, off_perm_all, off_run_t, off_recs, off_floor, off_results,
+        off_results_open, total;
 };
 
 // `cb` is the size of the constant block: the problem constants followed by the profiled path
 // accuracies (if any), see const_block().
 // c1: choices of the tile task of a class-by-class search with swapped roles (then off_perm_all holds a list of
 // the choices of every task, table_total entries per point, and off_run_t the tile task's runs), else 0.
-Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, uint32_t c1 = 0) {
+// per_path: eq. (7) on the variant paths with traffic (a second table of two latencies per choice, and a second
+// set of results for the plans only that rule admits).
+Layout search_layout(size_t cb, uint32_t table_total, uint32_t c0, int64_t M, uint32_t c1 = 0, bool per_path = false) {
     Layout l;
     l.off_P = 0;
     l.off_Dn = cb;
     l.off_table = align_up(l.off_Dn + size_t(M) * kMaxTasks * sizeof(int64_t));
-    l.off_perm = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
+    l.off_lat2 = align_up(l.off_table + size_t(M) * table_total * sizeof(TaskRec));
+    l.off_perm = align_up(l.off_lat2 + (per_path ? size_t(M) * table_total * sizeof(TaskLat2) : 0));
     l.off_run = align_up(l.off_perm + size_t(M) * c0 * sizeof(uint32_t));
     l.off_perm_all = align_up(l.off_run + size_t(M) * c0 * sizeof(uint32_t));
     l.off_run_t = align_up(l.off_perm_all + size_t(M) * (c1 ? table_total : 0u) * sizeof(uint32_t));
     l.off_recs = align_up(l.off_run_t + size_t(M) * c1 * sizeof(uint32_t));
     l.off_floor = align_up(l.off_recs + (size_t(kTargetBlocks) + size_t(M)) * sizeof(BestRec));
     l.off_results = align_up(l.off_floor + size_t(M) * sizeof(unsigned long long));
-    l.total = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
+    l.off_results_open = align_up(l.off_results + size_t(M) * sizeof(loki_result_t));
+    l.total = align_up(l.off_results_open + (per_path ? size_t(M) * sizeof(loki_result_t) : 0));
     return l;
 }
 
@@ -505,8 +510,9 @@ void plan_class_batches(ClassPoints &cp, const std::vector<uint64_t> &items, int
 // visits (all of them, or the largest class); with swapped roles (A.swap, set by the caller: classes, two
 // or more leaves, whole space) the most combinations of the work item's tasks any point has.
 // before_search / after_search: events recorded around the kernel that visits every plan, or null.
+// open_results: with A.lat2 set (per-path latency rule on the tables), where the results of the second kernel go.
 int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t index_begin, uint64_t index_end,
-                     hipStream_t stream, hipEvent_t before_search, hipEvent_t after_search) {
+                     hipStream_t stream, hipEvent_t before_search, hipEvent_t after_search, void *open_results = nullptr) {
     const int n = p->n, L = n - 1;
     const uint64_t span = index_end - index_begin;
     const uint32_t n_points = static_cast<uint32_t>(A.M);
@@ -605,6 +611,20 @@ int launch_tabulated(loki_problem *p, SearchArgs A, uint64_t most, uint64_t inde
         LOKI_HIP(launch_path_combine(A, slots, range, path_levels, stream));
     } else {
         LOKI_HIP(launch_combine(A, slots, np > 1, divide, range, false, stream));
+    }
+    if (A.lat2) {
+        // the per-path latency rule: the plans only that rule admits, into results of their own, folded in below
+        // (the block records are free again once the first merge has read them; the stream keeps the order)
+        LOKI_HIP(launch_final_reduce(A, stream));
+        SearchArgs B = A;
+        B.results = open_results;
+        int latency_levels = 0;
+        for (int i = 0; i < n; i++) latency_levels = std::max(latency_levels, p->dev.path_len[i]);
+        LOKI_HIP(launch_open_plans(B, slots, range, latency_levels, stream));
+        if (after_search) LOKI_HIP(hipEventRecord(after_search, stream));
+        LOKI_HIP(launch_final_reduce(B, stream));
+        LOKI_HIP(launch_fold_results(A.results, B.results, A.M, A.tie_index_only != 0, stream));
+        return LOKI_OK;
     }
     if (after_search) LOKI_HIP(hipEventRecord(after_search, stream));
     LOKI_HIP(launch_final_reduce(A, stream));
@@ -848,8 +868,12 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     int rc = check_scalars(workers, slo_us, comm_us);
     if (rc) return rc;
     if (!no_alloc) rotate_staging(p);
-    // eq. (7) on the variant paths with traffic couples the tasks of a path: whole plans per lane
-    if (p->dev.lat_per_path) flags |= LOKI_SEARCH_PER_LANE;
+    // eq. (7) on the variant paths with traffic couples the tasks of a path.  With one factor per edge and the
+    // product-form objective the tables still do most of the work: the plans the per-task bound admits as ever,
+    // then the few it rejects whose sure paths are fast enough, one by one (open_plans_kernel); a single task
+    // has one variant per path and the two rules are the same.  Otherwise whole plans per lane.
+    const bool per_path_on_tables = p->dev.lat_per_path && !p->dev.has_vf && !p->dev.has_path && !(flags & LOKI_SEARCH_PER_LANE);
+    if (p->dev.lat_per_path && !per_path_on_tables) flags |= LOKI_SEARCH_PER_LANE;
     // Per-variant factors: a task's demand depends on its parent's part of the plan.  Where every other
     // task is a child of the first one, that dependence is one number per first-task choice (the requests
     // it creates), and the tabulated kernels run once per distinct value; otherwise whole plans per lane.
@@ -863,7 +887,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     p->last_scored = (index_end - index_begin) * uint64_t(n_demand);
     p->have_scored = true;
     const size_t cb = const_block(p);
-    const Layout lay = search_layout(cb, p->dev.table_total, p->dev.C[0], n_demand);
+    const Layout lay = search_layout(cb, p->dev.table_total, p->dev.C[0], n_demand, 0, p->dev.lat_per_path != 0);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
         return LOKI_E_WORKSPACE;
     if (d_results && (reinterpret_cast<uintptr_t>(d_results) % 8) != 0) return LOKI_E_WORKSPACE;
@@ -907,6 +931,12 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
     if (results_at) *results_at = A.results;
     A.path_acc = device_path_acc(p, ws);
     path_budgets(p, slo_us, comm_us, A.budget);
+    if (per_path_on_tables && p->n >= 2) {
+        // (a task path whose communication latency alone exceeds the SLO leaves nothing feasible under either rule)
+        bool room = true;
+        for (int i = 0; i < p->n; i++) room = room && (!p->dev.is_leaf[i] || A.budget[i] >= 0);
+        if (room) A.lat2 = reinterpret_cast<TaskLat2 *>(ws + lay.off_lat2);
+    }
     A.begin = index_begin;
     A.end = index_end;
     A.W = workers;
@@ -963,7 +993,7 @@ int enqueue_search(loki_problem *p, const int64_t *demand_mqps, int32_t n_demand
         LOKI_HIP(launch_final_reduce(A, stream));
     } else {
         rc = launch_tabulated(p, A, n >= 2 ? p->dev.C[0] : 1u, index_begin, index_end, stream,
-                              timed ? p->ev[1] : nullptr, timed ? p->ev[2] : nullptr);
+                              timed ? p->ev[1] : nullptr, timed ? p->ev[2] : nullptr, ws + lay.off_results_open);
         if (rc) return rc;
     }
     if (timed) LOKI_HIP(hipEventRecord(p->ev[3], stream));
@@ -1206,7 +1236,7 @@ int loki_num_candidates(const loki_problem_t *p, uint64_t *n) {
 int loki_workspace_bytes(const loki_problem_t *p, int64_t n_demand, size_t *bytes) {
     if (!p || !bytes) return LOKI_E_NULL;
     if (n_demand < 1) return LOKI_E_ARG;
-    *bytes = std::max(search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total,
+    *bytes = std::max(search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand, 0, p->dev.lat_per_path != 0).total,
                       eval_layout(const_block(p), n_demand).total);
     if (class_search_applies(p))
         *bytes = std::max(*bytes, class_layout(const_block(p), p->dev.table_total, p->dev.C[0], p->dev.C[p->dev.tile_task], n_demand).total);
@@ -1527,7 +1557,7 @@ namespace loki {
 int plain_search_bytes(const loki_problem_t *p, int32_t n_demand, size_t *bytes) {
     if (!p || !bytes) return LOKI_E_NULL;
     if (n_demand < 1) return LOKI_E_ARG;
-    *bytes = search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand).total;
+    *bytes = search_layout(const_block(p), p->dev.table_total, p->dev.C[0], n_demand, 0, p->dev.lat_per_path != 0).total;
     return LOKI_OK;
 }
 

@@ -81,6 +81,14 @@ struct TaskRec {
                    // choice leaves demand unserved or hosts nothing
 };
 
+// With eq. (7) taken on the variant paths with traffic: the latencies of the first and of the last variant in
+// use of a choice (route order); kNever like TaskRec::lat.  Two variant paths always carry requests when all
+// demand is served (the first variants in use of every task, and the last ones), so their sums bound the
+// slowest path with traffic from below as TaskRec::lat's sums bound it from above.
+struct TaskLat2 {
+    int32_t top, bot;
+};
+
 // What the plans sharing one choice of every task but the last have in common,
 // staged in LDS per work item and read as a broadcast.  MidVal feeds the
 // objective; MidLim holds the limits left for the last task and is the same
@@ -115,6 +123,7 @@ struct SearchArgs {
     uint32_t *run_end;      // [M][C_0] end (exclusive) of the run each position belongs to
     void *results;          // [M] loki_result_t
     unsigned long long *floor;  // [M] bit pattern of the largest key a block of the point has reported so far
+    TaskLat2 *lat2;         // [M][table_total], or null: only written and read under the per-path latency rule
     const double *path_acc; // [path_total] profiled path accuracies as fractions, or null
     // Per-variant factors searched class by class: a "point" of the launch is a demand point together
     // with one value, per task that has children, of the requests the task creates per unit of fan-out

@@ -891,6 +891,12 @@ __global__ void __launch_bounds__(kBlockThreads) task_table_kernel(SearchArgs A)
     }
     rec.lat = usable ? static_cast<int32_t>(o.maxlat) : kNever;
     A.table[static_cast<size_t>(m) * sP.table_total + t] = rec;
+    if (A.lat2) {
+        TaskLat2 l2;
+        l2.top = usable ? o.lat_top : kNever;
+        l2.bot = usable ? o.lat_bot : kNever;
+        A.lat2[static_cast<size_t>(m) * sP.table_total + t] = l2;
+    }
 }
 
 // ---- kernel: order the first task's choices into runs of equal (feasible, replicas, latency) ------------
@@ -2333,6 +2339,231 @@ __global__ void __launch_bounds__(kBlockThreads, MAXD == 4 ? 2 : 1) path_combine
                      A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
 }
 
+
+// ---- kernel: eq. (7) on the variant paths with traffic, on top of the per-task tables ---------------------
+// Under that rule a plan is feasible if the per-task sum of the slowest variants in use meets the budget (those
+// plans are found by combine_kernel as ever: the sum bounds every variant path from above), or if it does not
+// but every variant path that carries requests does.  This kernel visits the plan space like
+// path_combine_kernel (same work items, tiles of first-task choices, the last task's records in registers) and
+// picks out the plans of the second kind that are still open: usable choices everywhere, worker budget met, the
+// per-task sum too slow on some task path, and the two variant paths that always carry requests (first and
+// last variants in use, TaskLat2) within the budget on every task path.  Those few go, by index, into a queue
+// of the wavefront, and whenever 64 are waiting every lane walks the variant paths of one
+// (some_path_too_slow) and scores it if it passes.  One factor per edge, product-form objective, two tasks or
+// more, every budget non-negative (the host sees to all four).
+template <int LATD>
+__device__ __noinline__ bool score_open_plan(const DevProblem *P, const int64_t *Dn, const int64_t *budget, int32_t W,
+                                             uint64_t idx, double *accuracy, int32_t *workers) {
+    uint32_t c[kMaxTasks];
+    uint64_t rest = idx;
+#pragma unroll
+    for (int i = 0; i < kMaxTasks; i++) {
+        c[i] = 0;
+        if (i < P->n_tasks) {
+            c[i] = static_cast<uint32_t>(rest % P->C[i]);
+            rest /= P->C[i];
+        }
+    }
+    if (some_path_too_slow<LATD>(P, c, Dn, budget)) return false;
+    uint32_t mask;
+    eval_plan(P, c, Dn, budget, W, mask, *workers, *accuracy);  // (the per-task latency bound is off in P)
+    return mask == 0;
+}
+
+template <int S, bool RANGE, int LATD>
+__global__ void __launch_bounds__(kBlockThreads, 2) open_plans_kernel(SearchArgs A) {
+    __shared__ DevProblem sPfull;
+    __shared__ MidLim sLim[kMidTile];       // w_rem: -1 unless the entry can be part of an open plan
+    __shared__ int32_t sTopRoom[kMidTile], sBotRoom[kMidTile];  // what the two sure paths leave the last task
+    __shared__ uint32_t sChoice[kMidTile];
+    __shared__ uint32_t sBoundMet[kMidTile];  // the per-task sums of the entry's part meet every budget they close
+    __shared__ uint64_t sWalkIdx[kWavesPerBlock][kWalkQueue];
+    __shared__ BestRec sBest[kWavesPerBlock];
+    stage_problem(&sPfull, A.P, sizeof(DevProblem));
+    __syncthreads();
+    const DevProblem *sP = &sPfull;
+
+    const uint32_t lane = threadIdx.x & 63;
+    const int wave = uni(static_cast<int>(threadIdx.x >> 6));
+    const int m = blockIdx.y;
+    const int n = uni(sP->n_tasks), L = n - 1;
+    const uint32_t CL = uni(sP->C[L]);
+    const uint32_t C0 = uni(sP->C[0]);
+    const uint64_t strideL = uni64(sP->stride[L]);
+    const uint32_t table_total = uni(sP->table_total);
+    const TaskRec *tab = A.table + static_cast<size_t>(m) * table_total;
+    const TaskLat2 *tab2 = A.lat2 + static_cast<size_t>(m) * table_total;
+    const uint32_t offL = uni(sP->table_off[L]);
+    const uint32_t *perm = A.perm + static_cast<size_t>(m) * C0;
+    const bool tie_index_only = A.tie_index_only != 0;
+    const int32_t W = A.W;
+    const int64_t *Dn = A.Dn + static_cast<size_t>(m) * kMaxTasks;
+    const int parL = uni(sP->parent[L]);
+
+    const uint32_t cpb = A.cpb;
+    const uint32_t chunk_in_group = wave % cpb, midpart = wave / cpb, mid_split = kWavesPerBlock / cpb;
+
+    int32_t w[S], lat[S], top[S], bot[S];
+    double bacc = -1.0;
+    int32_t bw = kNever;
+    uint64_t bidx = ~0ull;
+    uint64_t nfeas = 0;      // this lane's
+    uint32_t waiting = 0;    // plans in this wavefront's queue (the same in every lane)
+    uint32_t cur_group = ~0u;
+    uint32_t cl0 = 0;
+
+    auto walk_queued = [&](uint32_t from, uint32_t count) {
+        if (lane < count) {
+            const uint64_t idx = sWalkIdx[wave][from + lane];
+            double acc;
+            int32_t workers;
+            if (score_open_plan<LATD>(sP, Dn, A.budget, W, idx, &acc, &workers)) {
+                nfeas++;
+                if (better(acc, workers, idx, bacc, bw, bidx, tie_index_only)) {
+                    bacc = acc;
+                    bw = workers;
+                    bidx = idx;
+                }
+            }
+        }
+    };
+
+    const uint64_t items_m = A.items;
+    const uint64_t item_lo = items_m * blockIdx.x / A.blocks_per_m;
+    const uint64_t item_hi = items_m * (blockIdx.x + 1) / A.blocks_per_m;
+    for (uint64_t item = item_lo; item < item_hi; ++item) {
+        const uint32_t r = uni(static_cast<uint32_t>(item % A.mid_tiles));
+        const uint64_t t = item / A.mid_tiles;
+        const uint64_t f = uni64((A.far_first + t % A.far_span) % A.far_count);
+        const uint32_t g = uni(static_cast<uint32_t>(t / A.far_span));
+        if (g != cur_group) {
+            cur_group = g;
+            cl0 = A.cl_first + (g * cpb + chunk_in_group) * (64u * S) + lane;
+#pragma unroll
+            for (int s = 0; s < S; s++) {
+                const uint32_t cL = cl0 + s * 64;
+                if (cL < CL) {
+                    const TaskRec rec = tab[offL + cL];
+                    const TaskLat2 l2 = tab2[offL + cL];
+                    w[s] = rec.w;
+                    lat[s] = rec.lat;
+                    top[s] = l2.top;
+                    bot[s] = l2.bot;
+                } else {
+                    w[s] = 0;
+                    lat[s] = top[s] = bot[s] = kNever;
+                }
+            }
+        }
+        // the tasks strictly between the first and the last: replicas, and along the chains from the first
+        // task (left out here, added per entry) the three latency sums; a leaf among them closes its path
+        int64_t fl[kMaxTasks], ft[kMaxTasks], fb[kMaxTasks];
+        int64_t w_far = 0;
+        bool ok_far = true;
+        int64_t lat0_cap = kNever - 1, top0_cap = kNever - 1, bot0_cap = kNever - 1;
+#pragma unroll
+        for (int j = 0; j < kMaxTasks; j++) fl[j] = ft[j] = fb[j] = 0;
+        {
+            uint64_t rest = f;
+#pragma unroll
+            for (int j = 1; j < kMaxTasks; j++) {
+                if (j < L) {
+                    const uint32_t cj = uni(static_cast<uint32_t>(rest % sP->C[j]));
+                    rest /= sP->C[j];
+                    const TaskRec rec = tab[sP->table_off[j] + cj];
+                    const TaskLat2 l2 = tab2[sP->table_off[j] + cj];
+                    const int32_t rw = uni(rec.w), rlat = uni(rec.lat);
+                    const int par = uni(sP->parent[j]);
+                    w_far += rw;
+                    ok_far = ok_far && rlat != kNever;
+                    fl[j] = pick_below(fl, par, j) + rlat;
+                    ft[j] = pick_below(ft, par, j) + uni(l2.top);
+                    fb[j] = pick_below(fb, par, j) + uni(l2.bot);
+                    if (uni(sP->is_leaf[j])) {
+                        lat0_cap = lat0_cap < A.budget[j] - fl[j] ? lat0_cap : A.budget[j] - fl[j];
+                        top0_cap = top0_cap < A.budget[j] - ft[j] ? top0_cap : A.budget[j] - ft[j];
+                        bot0_cap = bot0_cap < A.budget[j] - fb[j] ? bot0_cap : A.budget[j] - fb[j];
+                    }
+                }
+            }
+        }
+        if (top0_cap < 0 || bot0_cap < 0) ok_far = false;  // a sure path is too slow whatever the first task does
+        const int64_t w_room = static_cast<int64_t>(W) - w_far;
+        const int64_t tl_base = A.budget[L] - pick_below(fl, parL, kMaxTasks);
+        const int64_t tt_base = A.budget[L] - pick_below(ft, parL, kMaxTasks);
+        const int64_t tb_base = A.budget[L] - pick_below(fb, parL, kMaxTasks);
+
+        const uint32_t tile_base = r * A.tile_len;
+        const uint32_t left = tile_base < C0 ? C0 - tile_base : 0u;
+        const uint32_t cnt = left < A.tile_len ? left : A.tile_len;
+        const uint64_t base_f = static_cast<uint64_t>(C0) * f;
+
+        __syncthreads();  // the previous item's tile is no longer being read
+        for (uint32_t e = threadIdx.x; e < cnt; e += kBlockThreads) {
+            const uint32_t c0 = perm[tile_base + e];
+            const TaskRec rec = tab[c0];
+            const TaskLat2 l2 = tab2[c0];
+            const bool usable = ok_far && rec.lat != kNever;
+            const bool sure_ok = usable && static_cast<int64_t>(l2.top) <= top0_cap && static_cast<int64_t>(l2.bot) <= bot0_cap;
+            auto room = [](int64_t v) { return static_cast<int32_t>(v < -1 ? -1 : (v > kNever - 1 ? kNever - 1 : v)); };
+            MidLim ul;
+            ul.tl = room(tl_base - rec.lat);
+            const int64_t wr = w_room - static_cast<int64_t>(rec.w);
+            ul.w_rem = (sure_ok && wr >= 0) ? static_cast<int32_t>(wr) : -1;
+            ul.cl_lo = 0;
+            ul.cl_cnt = CL;
+            if (RANGE) {
+                const uint64_t base = base_f + static_cast<uint64_t>(c0);
+                const uint64_t lo = A.begin > base ? (A.begin - base + strideL - 1) / strideL : 0;
+                uint64_t hi = A.end > base ? (A.end - base + strideL - 1) / strideL : 0;
+                if (hi > CL) hi = CL;
+                ul.cl_lo = static_cast<uint32_t>(lo < hi ? lo : hi);
+                ul.cl_cnt = static_cast<uint32_t>(hi > lo ? hi - lo : 0);
+            }
+            sLim[e] = ul;
+            sTopRoom[e] = usable ? room(tt_base - l2.top) : -1;
+            sBotRoom[e] = usable ? room(tb_base - l2.bot) : -1;
+            sBoundMet[e] = (usable && static_cast<int64_t>(rec.lat) <= lat0_cap) ? 1u : 0u;
+            sChoice[e] = c0;
+        }
+        __syncthreads();
+
+        const uint32_t e_lo = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * midpart / mid_split);
+        const uint32_t e_hi = static_cast<uint32_t>(static_cast<uint64_t>(cnt) * (midpart + 1) / mid_split);
+        for (uint32_t e = e_lo; e < e_hi; e++) {
+            const MidLim ul = sLim[e];
+            const int32_t w_rem = uni(ul.w_rem);
+            if (w_rem < 0) continue;
+            const int32_t tl = uni(ul.tl), tt = uni(sTopRoom[e]), tb = uni(sBotRoom[e]);
+            const bool bound_met = uni(sBoundMet[e]) != 0;
+            const uint64_t low = base_f + sChoice[e];
+#pragma unroll
+            for (int s = 0; s < S; s++) {
+                // usable, within the worker budget, both sure paths fast enough, the per-task sum not
+                bool open = (w[s] <= w_rem) & (top[s] <= tt) & (bot[s] <= tb) & !(bound_met & (lat[s] <= tl));
+                if (RANGE) open = open & ((cl0 + s * 64 - ul.cl_lo) < ul.cl_cnt);
+                const uint64_t vote = __builtin_amdgcn_ballot_w64(open);
+                if (vote == 0) continue;
+                if (open) {
+                    const uint32_t at = waiting + static_cast<uint32_t>(__builtin_popcountll(vote & ((1ull << lane) - 1)));
+                    sWalkIdx[wave][at] = low + strideL * (cl0 + s * 64);
+                }
+                waiting += static_cast<uint32_t>(__builtin_popcountll(vote));
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                if (waiting >= 64) {
+                    waiting -= 64;
+                    walk_queued(waiting, 64);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                }
+            }
+        }
+    }
+    walk_queued(0, waiting);
+    nfeas = wave_sum(nfeas);
+    block_store_best(bacc, bw, bidx, nfeas, tie_index_only, sBest,
+                     A.recs + static_cast<size_t>(m) * A.blocks_per_m + blockIdx.x);
+}
+
 // ---- kernel: every lane scores whole plans (no tables) ---------------------------------------------------
 // A work item is one choice of every task but the last plus a strip of kStrip choices of the
 // last task.  The lane scores the shared part once (each task in topological order, so that
@@ -2806,6 +3037,15 @@ __global__ void __launch_bounds__(kBlockThreads) class_merge_kernel(MergeArgs A)
     }
 }
 
+// results[m] takes in other[m]: feasible counts added, the better plan kept.
+__global__ void fold_results_kernel(void *results, const void *other, int M, uint32_t tie_index_only) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= M) return;
+    ResultOut o = static_cast<ResultOut *>(results)[m];
+    merge_result(o, static_cast<const ResultOut *>(other)[m], tie_index_only != 0);
+    static_cast<ResultOut *>(results)[m] = o;
+}
+
 template <int S>
 hipError_t launch_combine_s(const SearchArgs &A, bool has_presum, bool divide, bool range, bool leaf_values,
                             hipStream_t stream) {
@@ -2930,6 +3170,27 @@ hipError_t launch_path_combine(const SearchArgs &A, int slots, bool range, int p
         return slots == 8 ? launch_path_combine_s<8, 4>(A, range, stream) : launch_path_combine_s<4, 4>(A, range, stream);
     return slots == 8 ? launch_path_combine_s<8, kMaxTasks>(A, range, stream)
                       : launch_path_combine_s<4, kMaxTasks>(A, range, stream);
+}
+
+template <int S, int LATD>
+hipError_t launch_open_plans_s(const SearchArgs &A, bool range, hipStream_t stream) {
+    const dim3 grid(A.blocks_per_m, A.M), block(kBlockThreads);
+    if (range) hipLaunchKernelGGL((open_plans_kernel<S, true, LATD>), grid, block, 0, stream, A);
+    else hipLaunchKernelGGL((open_plans_kernel<S, false, LATD>), grid, block, 0, stream, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_open_plans(const SearchArgs &A, int slots, bool range, int latency_levels, hipStream_t stream) {
+    if (latency_levels <= 4)
+        return slots == 8 ? launch_open_plans_s<8, 4>(A, range, stream) : launch_open_plans_s<4, 4>(A, range, stream);
+    return slots == 8 ? launch_open_plans_s<8, kMaxTasks>(A, range, stream)
+                      : launch_open_plans_s<4, kMaxTasks>(A, range, stream);
+}
+
+hipError_t launch_fold_results(void *results, const void *other, int M, bool tie_index_only, hipStream_t stream) {
+    hipLaunchKernelGGL(fold_results_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, results, other, M,
+                       tie_index_only ? 1u : 0u);
+    return hipGetLastError();
 }
 
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream) {

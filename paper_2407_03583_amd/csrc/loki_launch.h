@@ -21,6 +21,11 @@ hipError_t launch_path_combine(const SearchArgs &A, int slots, bool range, int p
 // number of tasks on the longest root-to-leaf chain
 hipError_t launch_per_lane_search(const SearchArgs &A, bool pv_batch, bool has_vf, int path_levels,
                                   int latency_levels, hipStream_t stream);
+// Per-path latency rule on top of the tables (A.lat2 set): the plans the per-task bound rejects but whose variant
+// paths with traffic all meet the budget; block records like the other search kernels.
+hipError_t launch_open_plans(const SearchArgs &A, int slots, bool range, int latency_levels, hipStream_t stream);
+// results[m] takes in other[m] (both loki_result_t arrays on the device)
+hipError_t launch_fold_results(void *results, const void *other, int M, bool tie_index_only, hipStream_t stream);
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t stream);
 hipError_t launch_results_init(const MergeArgs &A, hipStream_t stream);
 hipError_t launch_class_merge(const MergeArgs &A, hipStream_t stream);

@@ -26,7 +26,7 @@ int main(int argc, char **argv) {
     if (argc < 2) return 2;
     FILE *f = std::fopen(argv[1], "r");
     if (!f) return 2;
-    const auto head = read_list(f);  // n_tasks, per_variant_batch, has_vf, has_path, workers, slo, comm
+    const auto head = read_list(f);  // n_tasks, per_variant_batch, has_vf, has_path, workers, slo, comm, latency_per_path
     const auto parent = narrow(read_list(f)), fanout = narrow(read_list(f)), nv = narrow(read_list(f)),
                nb = narrow(read_list(f)), bs = narrow(read_list(f)), rep = narrow(read_list(f)),
                acc = narrow(read_list(f));
@@ -50,6 +50,7 @@ int main(int argc, char **argv) {
     P.per_variant_batch = int32_t(head[1]);
     P.variant_factor_q4 = head[2] ? vf.data() : nullptr;
     P.path_acc_ppm = head[3] ? path.data() : nullptr;
+    P.latency_per_path = head.size() > 7 ? int32_t(head[7]) : 0;
     const int32_t workers = int32_t(head[4]);
     const int64_t slo = head[5], comm = head[6];
     loki_problem_t *h = nullptr;

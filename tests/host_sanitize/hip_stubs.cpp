@@ -56,6 +56,7 @@ const DevProblem &problem_of(const SearchArgs &A) { return *A.P; }
 hipError_t launch_task_table(const SearchArgs &A, uint32_t table_total, hipStream_t) {
     if (table_total != problem_of(A).table_total) return hipErrorInvalidValue;
     touch(A.table, size_t(A.M) * table_total);
+    if (A.lat2) touch(A.lat2, size_t(A.M) * table_total);
     touch(A.floor, size_t(A.M));
     volatile int64_t sink = 0;
     for (size_t q = 0; q < size_t(A.M) * kMaxTasks; q++) sink = sink + A.Dn[q];
@@ -103,6 +104,19 @@ hipError_t launch_path_combine(const SearchArgs &A, int slots, bool, int, hipStr
     return visit(A);
 }
 hipError_t launch_per_lane_search(const SearchArgs &A, bool, bool, int, int, hipStream_t) { return visit(A); }
+hipError_t launch_open_plans(const SearchArgs &A, int slots, bool, int levels, hipStream_t) {
+    if ((slots != 4 && slots != 8) || levels < 2 || !A.lat2) return hipErrorInvalidValue;
+    volatile uint32_t sink = 0;   // the second table, as the task table kernel leaves it
+    for (size_t q = 0; q < size_t(A.M) * problem_of(A).table_total; q++)
+        sink = sink + uint32_t(A.lat2[q].top) + uint32_t(A.lat2[q].bot);
+    return visit(A);
+}
+hipError_t launch_fold_results(void *results, const void *other, int M, bool, hipStream_t) {
+    touch(static_cast<unsigned char *>(results), size_t(M) * 32);
+    volatile unsigned char sink = 0;
+    for (size_t q = 0; q < size_t(M) * 32; q++) sink = sink + static_cast<const unsigned char *>(other)[q];
+    return hipSuccess;
+}
 
 hipError_t launch_final_reduce(const SearchArgs &A, hipStream_t) {
     // "nothing found" for every point

@@ -239,6 +239,29 @@ def test_six_task_chain_takes_the_eight_level_walk(path_tables):
             assert agree(res, O0.search(d, 99, slos[1])), (flags, d)
 
 
+@pytest.mark.parametrize("cfg,points", [(2, 1), (3, 6), (4, 5)])
+def test_benchmark_configurations_on_the_tables_against_per_lane(cfg, points):
+    """The search under the rule on the per-task tables (the plans the per-task bound admits, then the open ones
+    in a second pass) against whole plans per lane, at the configurations' full sizes (2^28 - 2^30 plans per
+    demand point); the rule must admit more plans than the default one somewhere."""
+    w = wl.config(cfg)
+    step = max(1, len(w.demand_mqps) // points)
+    demands = w.demand_mqps[::step][:points]
+    P = binding.Problem(with_rule(w.pipeline, True))
+    on_tables = P.alloc_search(demands, w.workers, w.slo_us, w.comm_us)
+    per_lane = P.alloc_search(demands, w.workers, w.slo_us, w.comm_us, flags=LANE)
+    assert [r.as_tuple() for r in on_tables] == [r.as_tuple() for r in per_lane]
+    by_bound = binding.Problem(with_rule(w.pipeline, False)).alloc_search(demands, w.workers, w.slo_us, w.comm_us)
+    assert all(a.n_feasible >= b.n_feasible for a, b in zip(on_tables, by_bound))
+    if cfg != 4:
+        assert any(a.n_feasible > b.n_feasible for a, b in zip(on_tables, by_bound))
+    n = P.num_candidates()
+    lo, hi = n // 3 + 11, n - n // 7
+    a = P.alloc_search(demands[:1], w.workers, w.slo_us, w.comm_us, begin=lo, end=hi)[0]
+    b = P.alloc_search(demands[:1], w.workers, w.slo_us, w.comm_us, begin=lo, end=hi, flags=LANE)[0]
+    assert a.as_tuple() == b.as_tuple()
+
+
 def test_entry_point_without_allocation_follows_the_rule():
     rng = random.Random(1003)
     p, demand, slos = split_traffic_problem(rng, [-1, 0, 1, 1])

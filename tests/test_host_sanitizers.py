@@ -41,7 +41,7 @@ def write_problem(path, p, demands, workers, slo, comm, indices, ranges):
     vf = getattr(p, "variant_factor_q4", None)
     pt = getattr(p, "path_acc_ppm", None)
     lists = [[p.n_tasks, 1 if getattr(p, "per_variant_batch", False) else 0, 1 if vf is not None else 0,
-              1 if pt is not None else 0, workers, slo, comm],
+              1 if pt is not None else 0, workers, slo, comm, 1 if getattr(p, "latency_per_path", False) else 0],
              p.parent, p.fanout_q4, p.n_variants, p.n_batches, p.batch_size, p.max_replicas, p.acc_ppm,
              p.latency_us, p.thr_mqps, vf or [], pt or [], demands, indices, ranges]
     with open(path, "w") as f:
@@ -103,13 +103,17 @@ def test_benchmark_configurations_run_clean(driver, tmp_path, cfg):
     check_host_outputs(lines, w.pipeline, demands[0], indices)
 
 
-@pytest.mark.parametrize("what", ["variant_factors", "per_variant_batch", "path_tables", "complete_model"])
+@pytest.mark.parametrize("what", ["variant_factors", "per_variant_batch", "path_tables", "complete_model",
+                                  "latency_per_path", "latency_per_path_complete_model"])
 @pytest.mark.parametrize("cfg", [2, 4, 5])
 def test_model_variants_run_clean(driver, tmp_path, cfg, what):
     """Per-variant factors run class by class on the host: the walk over the classes, the batches of points,
     their descriptors and the merge arguments all go through the sanitizers."""
     w = wl.config(cfg)
     p = w.pipeline
+    if what.startswith("latency_per_path"):   # on the tables with the second kernel, or whole plans per lane
+        p.latency_per_path = True
+        what = what[len("latency_per_path_"):]
     if what in ("variant_factors", "complete_model"):
         p.variant_factor_q4 = [3 + (a - 600000) // 90000 for a in p.acc_ppm]
     if what == "per_variant_batch":
