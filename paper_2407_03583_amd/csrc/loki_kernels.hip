@@ -74,6 +74,13 @@ __device__ __forceinline__ int64_t pick_below(const int64_t (&v)[kMaxTasks], int
     return static_cast<int64_t>(pick_bits(b, idx, bound));
 }
 
+// The problem constants in device memory, not written while a kernel runs, seen through the constant address
+// space: a read whose address is the same in every lane becomes a scalar load.
+using ScalarProblem = const __attribute__((address_space(4))) DevProblem *;
+__device__ __forceinline__ ScalarProblem scalar_view(const DevProblem *p) {
+    return (ScalarProblem)p;  // NOLINT: an address space cast has no named form
+}
+
 __device__ __forceinline__ uint32_t uni(uint32_t v) {
     return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
 }
@@ -109,63 +116,84 @@ struct TaskOut {
 // PV: a batch size per hosted variant; VF: per-variant multiplicative factors.
 // NARROW: the caller has shown that the demand and every x * q * scale the task can meet are below 2^32: the
 // fill runs on 32-bit values (the sums of routed * accuracy and routed * factor stay 64-bit).  Same results.
-template <bool PV, bool VF, bool NARROW = false>
-__device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o) {
-    const int K = P->K[i];
+// U: where the fields that are the same in every lane (counts, radices, reciprocals, route order, accuracies,
+// factors) are read from: P itself, or the constants in device memory seen through the constant address space,
+// which turns those reads into scalar loads (the per-lane search; the block's copy in LDS then only serves the
+// reads whose address depends on the lane: throughput and latency at the lane's batch size).
+template <bool PV, bool VF, bool NARROW = false, typename UniformView = const DevProblem *>
+__device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o,
+                                          UniformView U) {
+    const int K = U->K[i];
     constexpr bool pv = PV;
-    const uint32_t nb = static_cast<uint32_t>(P->nb[i]);
-    uint64_t digits = 0;  // replicas, 8 bits per variant
-    uint32_t betas = 0;   // batch position, 4 bits per variant (per-variant batch sizes only)
+    const uint32_t nb = static_cast<uint32_t>(U->nb[i]);
+    uint32_t dlo = 0, dhi = 0;  // replicas, 8 bits per variant: variants 0..3 and 4..7
+    uint32_t betas = 0;         // batch position, 4 bits per variant (per-variant batch sizes only)
     int32_t w = 0;
-    for (int k = 0; k < K; k++) {
-        const uint32_t radix = P->radix[i][k];
+    auto digit = [&](int k) -> uint32_t {
+        const uint32_t radix = U->radix[i][k];
         // exact quotients by multiply-shift: c * radix < 2^32 with one batch size per task (radix <= 256),
         // c * radix <= 2^36 otherwise (both checked at problem creation)
-        const uint32_t q = pv ? static_cast<uint32_t>((static_cast<uint64_t>(c) * P->magic[i][k]) >> 36)
-                              : (radix == 1 ? c : __umulhi(c, P->magic32[i][k]));
+        const uint32_t q = pv ? static_cast<uint32_t>((static_cast<uint64_t>(c) * U->magic[i][k]) >> 36)
+                              : (radix == 1 ? c : __umulhi(c, U->magic32[i][k]));
         const uint32_t g = c - q * radix;
         c = q;
         uint32_t x = g;
         if (pv) {  // g = 0: not hosted; else 1 + (x-1)*nb + batch position
             const uint32_t t = g - 1;
-            const uint32_t xq = static_cast<uint32_t>((static_cast<uint64_t>(t) * P->magic_nb[i]) >> 36);
+            const uint32_t xq = static_cast<uint32_t>((static_cast<uint64_t>(t) * U->magic_nb[i]) >> 36);
             x = g == 0 ? 0u : xq + 1;
             betas |= (g == 0 ? 0u : t - xq * nb) << (4 * k);
         }
-        digits |= static_cast<uint64_t>(x) << (8 * k);
         w += static_cast<int32_t>(x);
-    }
+        return x;
+    };
+    const int K_lo = K < 4 ? K : 4;
+    for (int k = 0; k < K_lo; k++) dlo |= digit(k) << (8 * k);
+    for (int k = 4; k < K; k++) dhi |= digit(k) << (8 * (k - 4));
+    const uint64_t digits = (static_cast<uint64_t>(dhi) << 32) | dlo;
+    // byte k of the pair: one byte permute (selector bytes 0..3 pick from the second operand, 4..7 from the
+    // first, 0x0c yields zero)
+    [[maybe_unused]] auto replicas_of = [&](int k) -> uint32_t {
+        return __builtin_amdgcn_perm(dhi, dlo, 0x0c0c0c00u | static_cast<uint32_t>(k));
+    };
     const uint32_t beta_task = c;
     constexpr bool has_vf = VF;
     if constexpr (NARROW) {
         uint32_t rem = static_cast<uint32_t>(Dn);
         uint64_t weighted = 0, outflow = 0;
-        int32_t any = 0, first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
+        int32_t first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
+        bool any = false;
         uint32_t in_use = 0;
         for (int r = 0; r < K; r++) {
-            const int k = uni(P->order[i][r]);  // the same in every lane: the table addresses below stay scalar
-            const uint32_t x = static_cast<uint32_t>(digits >> (8 * k)) & 0xffu;
+            const int k = uni(U->order[i][r]);  // the same in every lane: the table addresses below stay scalar
+            const uint32_t x = replicas_of(k);
             const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
             const uint32_t cap = x * static_cast<uint32_t>(P->thr_s[i][k][beta]);
             const int32_t lat = P->lat[i][k][beta];
-            const uint32_t acc = static_cast<uint32_t>(P->acc[i][k]);
             const uint32_t routed = rem < cap ? rem : cap;
             const bool hosted = x > 0;
-            const bool used = hosted && (routed > 0 || !any);
+            const bool used = routed > 0 || (hosted && !any);
             if (used && lat > maxlat) maxlat = lat;
             if (used) lat_bot = lat;
             in_use |= used ? 1u << k : 0u;
-            if (hosted && !any) {
-                first_acc = static_cast<int32_t>(acc);
-                lat_top = lat;
-            }
-            weighted += static_cast<uint64_t>(routed) * acc;
-            if (has_vf) outflow += static_cast<uint64_t>(routed) * static_cast<uint32_t>(P->vf[i][k]);
+            if (hosted && !any) lat_top = lat;
+            weighted += static_cast<uint64_t>(routed) * static_cast<uint32_t>(U->acc[i][k]);
+            if (has_vf) outflow += static_cast<uint64_t>(routed) * static_cast<uint32_t>(U->vf[i][k]);
             rem -= routed;
-            any |= hosted ? 1 : 0;
+            any = any || hosted;
+        }
+        // the accuracy of the first hosted variant only counts for a task without demand
+        if (Dn == 0) {
+            bool found = false;
+            for (int r = 0; r < K; r++) {
+                const int k = uni(U->order[i][r]);
+                const bool hosted = replicas_of(k) > 0;
+                if (hosted && !found) first_acc = U->acc[i][k];
+                found = found || hosted;
+            }
         }
         o.w = w;
-        o.any = any;
+        o.any = any ? 1 : 0;
         o.rem = static_cast<int64_t>(rem);
         o.maxlat = maxlat;
         o.weighted = static_cast<int64_t>(weighted);
@@ -180,12 +208,12 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     int32_t any = 0, first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
     uint32_t in_use = 0;
     for (int r = 0; r < K; r++) {
-        const int k = P->order[i][r];
+        const int k = U->order[i][r];
         const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
         const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
         const int64_t cap = x * P->thr_s[i][k][beta];
         const int32_t lat = P->lat[i][k][beta];
-        const int32_t acc = P->acc[i][k];
+        const int32_t acc = U->acc[i][k];
         const int64_t routed = rem < cap ? rem : cap;
         const bool hosted = x > 0;
         const bool used = hosted && (routed > 0 || !any);
@@ -197,7 +225,7 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
             lat_top = lat;
         }
         weighted += routed * static_cast<int64_t>(acc);
-        if (has_vf) outflow += routed * static_cast<int64_t>(P->vf[i][k]);
+        if (has_vf) outflow += routed * static_cast<int64_t>(U->vf[i][k]);
         rem -= routed;
         any |= hosted ? 1 : 0;
     }
@@ -211,6 +239,11 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     o.used = in_use;
     o.lat_top = lat_top;
     o.lat_bot = lat_bot;
+}
+
+template <bool PV, bool VF, bool NARROW = false>
+__device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o) {
+    eval_task<PV, VF, NARROW, const DevProblem *>(P, i, c, Dn, o, P);
 }
 
 // The same with the two switches read from the problem (kernels that are not time critical).
@@ -2612,6 +2645,7 @@ __global__ void __launch_bounds__(kBlockThreads, LATD > 0 ? 2 : (MAXD == 4 ? 3 :
     stage_problem(&sP, A.P, sizeof(DevProblem));
     __syncthreads();
     const DevProblem *P = &sP;
+    const ScalarProblem PS = scalar_view(A.P);
     const int m = blockIdx.y;
     const int n = P->n_tasks, L = n - 1;
     const bool has_vf = LAT ? P->has_vf != 0 : VF;
@@ -2678,7 +2712,7 @@ __global__ void __launch_bounds__(kBlockThreads, LATD > 0 ? 2 : (MAXD == 4 ? 3 :
     };
     auto task_of = [&](int i, uint32_t ci, int64_t dn, TaskOut &t) {
         if constexpr (LAT) eval_task_any(P, i, ci, dn, t);
-        else eval_task<PV, VF, NARROW>(P, i, ci, dn, t);
+        else eval_task<PV, VF, NARROW, ScalarProblem>(P, i, ci, dn, t, PS);
     };
     bool no_room = false;   // some chain's communication latency alone exceeds the SLO: nothing is feasible
     if constexpr (LAT) {
