@@ -30,24 +30,29 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
     fp64 add (the other paths' sum) when the tree has several leaves, and one fp64 max/compare
     against the lane's best.  The two feasibility compares of eq. (3) and eq. (7) are taken
     once per run of first-task choices with equal replicas and latency and are not counted.
-    Per-lane kernel (estimate): the last task is scored per plan -- 20 per variant (digit, capacity,
-    fill, weighted sum) + 30 (one fp64 division, conversions) -- plus 50 to finish the plan (masks,
-    path value, sum, division, key); the other tasks are scored once per strip of 64 plans."""
+    Per-lane kernel: the last task is scored per plan, and what that needs is counted, not what the kernel
+    executes (about twice as much: table addresses, the step to the next choice level by level, mask
+    bookkeeping) -- per variant 8: the replicas' byte, capacity `x * q`, `min` with the demand left, the
+    subtraction, the multiply-add into the accuracy sum, the in-use test, max and select of the latency;
+    per plan 12: next choice (2), sum of replicas, workers add and compare, latency add and compare, the
+    unserved and empty tests, index and range test (3).  The fp64 division and the comparison with the
+    best plan run for feasible plans only and are not counted.  The other tasks are scored once per strip
+    of 64 plans (8 per variant + 32 with their division)."""
     if not per_lane:
         return (1 if n_tasks >= 2 else 0) + (1 if n_paths > 1 else 0) + 1
-    per_task = [20 * k + 30 for k in pipeline.n_variants]
+    ks = list(pipeline.n_variants)
     # (with profiled path accuracies the walk over the variant paths runs for feasible plans only and is
     # not counted)
-    return per_task[-1] + 50 + sum(per_task[:-1]) / 64.0
+    return 8 * ks[-1] + 12 + sum(8 * k + 32 for k in ks[:-1]) / 64.0
 
 
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (2155 + 7201) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (246.5 + 1024) * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (2167 + 7192) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (4857 + 449330) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "e43c369b8aa842153dbf0abc6169cb61124cddc91a7c979ced847c774306d927"
+TRAFFIC_SOURCES_SHA256 = "b2a5439f6ae9ed9dfe7052d98f815853669b2ba3cc0df0d5a47f32aa50c007b4"
 
 
 def measured_traffic(workload: str, kernel: str):

@@ -1106,6 +1106,7 @@ int loki_problem_create(const loki_pipeline_t *in, loki_problem_t **out) {
         for (int k = 0; k < K; k++) ord[k] = k;
         std::stable_sort(ord, ord + K, [&](int x, int y) { return d.acc[i][x] > d.acc[i][y]; });
         for (int k = 0; k < K; k++) d.order[i][k] = ord[k];
+        for (int r = 0; r < K; r++) d.route[i][r] = RouteStep{ord[r], d.acc[i][ord[r]], d.vf[i][ord[r]], 0};
         d.C[i] = uint32_t(choices);
         d.stride[i] = N;
         d.table_off[i] = table_total;

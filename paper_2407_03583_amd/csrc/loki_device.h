@@ -19,6 +19,14 @@ constexpr int kMaxPrefix = 64;              // profiled path accuracies leaf by 
                                             // variant paths above a leaf (product of the variant counts of the tasks
                                             // root..leaf's parent)
 
+// What the fill needs of the variant at one position of a task's route order, side by side (one 16-byte read).
+struct RouteStep {
+    int32_t k;      // the variant
+    int32_t acc;    // its accuracy, ppm
+    int32_t vf;     // its multiplicative factor, quarters (4 when absent)
+    int32_t pad;
+};
+
 // Per-handle constants (Table 1 inputs after validation, plus derived radices).
 struct DevProblem {
     int32_t n_tasks;
@@ -70,6 +78,7 @@ struct DevProblem {
     int32_t lat_t_sorted[kMaxVariants * kMaxBatches];
     int32_t lat_per_path;                   // eq. (7) on every variant path with traffic instead of the per-task bound
     int32_t pad3;
+    RouteStep route[kMaxTasks][kMaxVariants];  // order / acc / vf again, by route position
 };
 
 // What a task contributes to any plan that uses one of its choices

@@ -110,24 +110,27 @@ struct TaskOut {
     int32_t lat_bot;    // latency of the last variant in use in route order
 };
 
+// A choice of a task taken apart: the replicas of every variant and the batch position(s).
+struct ChoiceParts {
+    uint32_t lo, hi;      // replicas, 8 bits per variant: variants 0..3 and 4..7
+    uint32_t betas;       // batch position, 4 bits per variant (per-variant batch sizes only)
+    uint32_t beta_task;   // the task's batch position (one batch size per task)
+    int32_t w;            // sum of replicas
+};
+
 // Decode choice c of task i (variant 0 least significant; the batch digit on top, or a batch
-// position inside every variant's digit) and fill the hosted variants most accurate first
-// (eq. (2), Algorithm 1's fill rule).
-// PV: a batch size per hosted variant; VF: per-variant multiplicative factors.
-// NARROW: the caller has shown that the demand and every x * q * scale the task can meet are below 2^32: the
-// fill runs on 32-bit values (the sums of routed * accuracy and routed * factor stay 64-bit).  Same results.
+// position inside every variant's digit).
+// PV: a batch size per hosted variant.
 // U: where the fields that are the same in every lane (counts, radices, reciprocals, route order, accuracies,
 // factors) are read from: P itself, or the constants in device memory seen through the constant address space,
 // which turns those reads into scalar loads (the per-lane search; the block's copy in LDS then only serves the
 // reads whose address depends on the lane: throughput and latency at the lane's batch size).
-template <bool PV, bool VF, bool NARROW = false, typename UniformView = const DevProblem *>
-__device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o,
-                                          UniformView U) {
+template <bool PV, typename UniformView>
+__device__ __forceinline__ void decode_choice(UniformView U, int i, uint32_t c, ChoiceParts &g) {
     const int K = U->K[i];
     constexpr bool pv = PV;
     const uint32_t nb = static_cast<uint32_t>(U->nb[i]);
-    uint32_t dlo = 0, dhi = 0;  // replicas, 8 bits per variant: variants 0..3 and 4..7
-    uint32_t betas = 0;         // batch position, 4 bits per variant (per-variant batch sizes only)
+    uint32_t dlo = 0, dhi = 0, betas = 0;
     int32_t w = 0;
     auto digit = [&](int k) -> uint32_t {
         const uint32_t radix = U->radix[i][k];
@@ -135,14 +138,14 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         // c * radix <= 2^36 otherwise (both checked at problem creation)
         const uint32_t q = pv ? static_cast<uint32_t>((static_cast<uint64_t>(c) * U->magic[i][k]) >> 36)
                               : (radix == 1 ? c : __umulhi(c, U->magic32[i][k]));
-        const uint32_t g = c - q * radix;
+        const uint32_t d = c - q * radix;
         c = q;
-        uint32_t x = g;
-        if (pv) {  // g = 0: not hosted; else 1 + (x-1)*nb + batch position
-            const uint32_t t = g - 1;
+        uint32_t x = d;
+        if (pv) {  // d = 0: not hosted; else 1 + (x-1)*nb + batch position
+            const uint32_t t = d - 1;
             const uint32_t xq = static_cast<uint32_t>((static_cast<uint64_t>(t) * U->magic_nb[i]) >> 36);
-            x = g == 0 ? 0u : xq + 1;
-            betas |= (g == 0 ? 0u : t - xq * nb) << (4 * k);
+            x = d == 0 ? 0u : xq + 1;
+            betas |= (d == 0 ? 0u : t - xq * nb) << (4 * k);
         }
         w += static_cast<int32_t>(x);
         return x;
@@ -150,22 +153,66 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     const int K_lo = K < 4 ? K : 4;
     for (int k = 0; k < K_lo; k++) dlo |= digit(k) << (8 * k);
     for (int k = 4; k < K; k++) dhi |= digit(k) << (8 * (k - 4));
-    const uint64_t digits = (static_cast<uint64_t>(dhi) << 32) | dlo;
-    // byte k of the pair: one byte permute (selector bytes 0..3 pick from the second operand, 4..7 from the
-    // first, 0x0c yields zero)
-    [[maybe_unused]] auto replicas_of = [&](int k) -> uint32_t {
-        return __builtin_amdgcn_perm(dhi, dlo, 0x0c0c0c00u | static_cast<uint32_t>(k));
+    g.lo = dlo;
+    g.hi = dhi;
+    g.betas = betas;
+    g.beta_task = c;
+    g.w = w;
+}
+
+// One batch size per task: the parts of choice c + 1 from those of choice c (add one to the mixed-radix number,
+// variant 0 least significant, the batch position on top).  A level is only visited while some lane of the
+// wavefront still carries.  The sum of replicas is taken anew from the bytes.
+template <typename UniformView>
+__device__ __forceinline__ void next_choice(UniformView U, int i, ChoiceParts &g) {
+    const int K = U->K[i];
+    bool carry = true;
+    auto level = [&](uint32_t &word, int k, int pos) {
+        const uint32_t top = U->radix[i][k] - 1;  // the largest digit
+        const uint32_t d = (word >> (8 * pos)) & 0xffu;
+        const bool at_top = d == top;
+        const uint32_t next = at_top ? word & ~(0xffu << (8 * pos)) : word + (1u << (8 * pos));
+        word = carry ? next : word;
+        carry = carry && at_top;
     };
-    const uint32_t beta_task = c;
+    bool done = false;
+    const int K_lo = K < 4 ? K : 4;
+    for (int k = 0; k < K_lo && !done; k++) {
+        level(g.lo, k, k);
+        done = __ballot(carry) == 0;
+    }
+    for (int k = 4; k < K && !done; k++) {
+        level(g.hi, k, k - 4);
+        done = __ballot(carry) == 0;
+    }
+    g.beta_task += carry ? 1u : 0u;
+    g.w = static_cast<int32_t>(__builtin_amdgcn_sad_u8(g.lo, 0u, __builtin_amdgcn_sad_u8(g.hi, 0u, 0u)));
+}
+
+// Fill the hosted variants of a decoded choice most accurate first (eq. (2), Algorithm 1's fill rule).
+// PV: a batch size per hosted variant; VF: per-variant multiplicative factors.
+// NARROW: the caller has shown that the demand and every x * q * scale the task can meet are below 2^32: the
+// fill runs on 32-bit values (the sums of routed * accuracy and routed * factor stay 64-bit).  Same results.
+template <bool PV, bool VF, bool NARROW, typename UniformView>
+__device__ __forceinline__ void fill_task(const DevProblem *P, UniformView U, int i, const ChoiceParts &g, int64_t Dn,
+                                          TaskOut &o) {
+    const int K = U->K[i];
+    constexpr bool pv = PV;
+    const uint32_t dlo = g.lo, dhi = g.hi, betas = g.betas, beta_task = g.beta_task;
     constexpr bool has_vf = VF;
     if constexpr (NARROW) {
+        // byte k of the pair: one byte permute (selector bytes 0..3 pick from the second operand, 4..7 from
+        // the first, 0x0c yields zero)
+        auto replicas_of = [&](int k) -> uint32_t {
+            return __builtin_amdgcn_perm(dhi, dlo, 0x0c0c0c00u | static_cast<uint32_t>(k));
+        };
         uint32_t rem = static_cast<uint32_t>(Dn);
         uint64_t weighted = 0, outflow = 0;
         int32_t first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
         bool any = false;
         uint32_t in_use = 0;
         for (int r = 0; r < K; r++) {
-            const int k = uni(U->order[i][r]);  // the same in every lane: the table addresses below stay scalar
+            const int k = uni(U->route[i][r].k);  // the same in every lane: the table addresses below stay scalar
             const uint32_t x = replicas_of(k);
             const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
             const uint32_t cap = x * static_cast<uint32_t>(P->thr_s[i][k][beta]);
@@ -177,8 +224,8 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
             if (used) lat_bot = lat;
             in_use |= used ? 1u << k : 0u;
             if (hosted && !any) lat_top = lat;
-            weighted += static_cast<uint64_t>(routed) * static_cast<uint32_t>(U->acc[i][k]);
-            if (has_vf) outflow += static_cast<uint64_t>(routed) * static_cast<uint32_t>(U->vf[i][k]);
+            weighted += static_cast<uint64_t>(routed) * static_cast<uint32_t>(U->route[i][r].acc);
+            if (has_vf) outflow += static_cast<uint64_t>(routed) * static_cast<uint32_t>(U->route[i][r].vf);
             rem -= routed;
             any = any || hosted;
         }
@@ -186,13 +233,12 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         if (Dn == 0) {
             bool found = false;
             for (int r = 0; r < K; r++) {
-                const int k = uni(U->order[i][r]);
-                const bool hosted = replicas_of(k) > 0;
-                if (hosted && !found) first_acc = U->acc[i][k];
+                const bool hosted = replicas_of(uni(U->route[i][r].k)) > 0;
+                if (hosted && !found) first_acc = U->route[i][r].acc;
                 found = found || hosted;
             }
         }
-        o.w = w;
+        o.w = g.w;
         o.any = any ? 1 : 0;
         o.rem = static_cast<int64_t>(rem);
         o.maxlat = maxlat;
@@ -204,16 +250,17 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
         o.lat_bot = lat_bot;
         return;
     }
+    const uint64_t digits = (static_cast<uint64_t>(dhi) << 32) | dlo;
     int64_t rem = Dn, weighted = 0, outflow = 0;
     int32_t any = 0, first_acc = 0, maxlat = 0, lat_top = 0, lat_bot = 0;
     uint32_t in_use = 0;
     for (int r = 0; r < K; r++) {
-        const int k = U->order[i][r];
+        const int k = U->route[i][r].k;
         const int64_t x = static_cast<int64_t>((digits >> (8 * k)) & 0xff);
         const uint32_t beta = pv ? (betas >> (4 * k)) & 0xf : beta_task;
         const int64_t cap = x * P->thr_s[i][k][beta];
         const int32_t lat = P->lat[i][k][beta];
-        const int32_t acc = U->acc[i][k];
+        const int32_t acc = U->route[i][r].acc;
         const int64_t routed = rem < cap ? rem : cap;
         const bool hosted = x > 0;
         const bool used = hosted && (routed > 0 || !any);
@@ -225,11 +272,11 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
             lat_top = lat;
         }
         weighted += routed * static_cast<int64_t>(acc);
-        if (has_vf) outflow += routed * static_cast<int64_t>(U->vf[i][k]);
+        if (has_vf) outflow += routed * static_cast<int64_t>(U->route[i][r].vf);
         rem -= routed;
         any |= hosted ? 1 : 0;
     }
-    o.w = w;
+    o.w = g.w;
     o.any = any;
     o.rem = rem;
     o.maxlat = maxlat;
@@ -239,6 +286,15 @@ __device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c
     o.used = in_use;
     o.lat_top = lat_top;
     o.lat_bot = lat_bot;
+}
+
+// Decode and fill.
+template <bool PV, bool VF, bool NARROW = false, typename UniformView = const DevProblem *>
+__device__ __forceinline__ void eval_task(const DevProblem *P, int i, uint32_t c, int64_t Dn, TaskOut &o,
+                                          UniformView U) {
+    ChoiceParts g;
+    decode_choice<PV>(U, i, c, g);
+    fill_task<PV, VF, NARROW>(P, U, i, g, Dn, o);
 }
 
 template <bool PV, bool VF, bool NARROW = false>
@@ -2631,11 +2687,12 @@ constexpr int32_t kWalkCheckLatency = 1 << 30;  // queue entry: latency not sett
 // kernel with both walks also returned a plan below the best one, which tests/test_gpu_latency_per_path.py
 // now checks for on a six-task chain.
 template <bool PV, bool VF, int MAXD, int LATD = 0, bool NARROW = false>
-__global__ void __launch_bounds__(kBlockThreads, LATD > 0 ? 2 : (MAXD == 4 ? 3 : 1))
+__global__ void __launch_bounds__(kBlockThreads, LATD > 0 ? 2 : (MAXD == 4 ? 3 : (MAXD == 0 && NARROW && !PV ? 6 : 1)))
     per_lane_search_kernel(SearchArgs A) {
     constexpr bool LAT = LATD > 0;
     constexpr bool kQueue = MAXD > 0 || LAT;
     constexpr int kLatLevels = LATD > 0 ? LATD : 1;
+    constexpr bool kStepChoice = !LAT && !PV;
     static_assert(MAXD == 0 || LATD == 0 || LATD == MAXD, "one depth for both walks");
     __shared__ DevProblem sP;
     __shared__ BestRec sBest[kWavesPerBlock];
@@ -2805,16 +2862,23 @@ __global__ void __launch_bounds__(kBlockThreads, LATD > 0 ? 2 : (MAXD == 4 ? 3 :
 
         // ---- the strip: the last task's choices
         const uint32_t steps = kQueue ? kStrip : c_hi - c_lo;
+        // one batch size per task: the last task's choice is decoded at the head of the strip and stepped from
+        // there; the plan's index likewise
+        [[maybe_unused]] ChoiceParts partsL;
+        if constexpr (kStepChoice) decode_choice<false>(PS, L, c_lo, partsL);
+        uint64_t idx_next = o + strideL * c_lo;
         for (uint32_t step = 0; step < steps; step++) {
             const uint32_t cL = c_lo + step;
-            const uint64_t idx = o + strideL * cL;
+            const uint64_t idx = idx_next;
+            idx_next += strideL;
             bool feasible = false;  // by the per-task latency bound and everything else
             bool to_queue = false;
             int32_t workers = 0, entry = 0;
             double acc = 0.0;
             if (live && cL < c_hi && idx >= A.begin && idx < A.end) {
                 TaskOut t;
-                task_of(L, cL, dnL, t);
+                if constexpr (kStepChoice) fill_task<PV, VF, NARROW>(P, PS, L, partsL, dnL, t);
+                else task_of(L, cL, dnL, t);
                 uint32_t mask = mask0;
                 workers = workers0 + t.w;
                 if (!t.any) mask |= kBadEmpty;
@@ -2862,6 +2926,7 @@ __global__ void __launch_bounds__(kBlockThreads, LATD > 0 ? 2 : (MAXD == 4 ? 3 :
                     }
                 }
             }
+            if constexpr (kStepChoice) next_choice(PS, L, partsL);
         }
     }
     if constexpr (kQueue) walk_queued(0, waiting);

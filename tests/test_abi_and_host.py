@@ -163,11 +163,11 @@ def test_bench_refuses_more_than_one_gpu_and_counts_operations():
     assert bench.algorithmic_lane_ops(4, 2, False, p5) == 3          # multiply, add, max/compare
     assert bench.algorithmic_lane_ops(3, 1, False, wl.config(2).pipeline) == 2
     assert bench.algorithmic_lane_ops(1, 1, False, p5) == 1
-    assert bench.algorithmic_lane_ops(4, 2, True, p5) == (20 * 4 + 30) + 50 + 3 * (20 * 4 + 30) / 64.0
+    assert bench.algorithmic_lane_ops(4, 2, True, p5) == (8 * 4 + 12) + 3 * (8 * 4 + 32) / 64.0
     assert abs(bench.VALU_PEAK_TLANEOPS - 39.3216) < 1e-9
     # the HBM traffic figure is reported only for the sources it was measured with
     t = bench.measured_traffic("cfg5_tree4_k4", "tabulated")
-    assert t is None or t == (2155 + 7201) * 1024
+    assert t is None or t == (2167 + 7192) * 1024
     assert bench.measured_traffic("cfg1_chain2_k3", "tabulated") is None
 
 
