@@ -81,3 +81,40 @@ def test_config_2_takes_the_32_bit_fill():
     assert P.last_search_fill_bits() == 32
     ref = P.alloc_search(w.demand_mqps, w.workers, w.slo_us, w.comm_us)
     assert [r.as_tuple() for r in res] == [r.as_tuple() for r in ref] and n == 1 << 30
+
+
+@pytest.mark.parametrize("wide", [False, True])
+def test_stepping_through_the_choices_of_a_last_task_with_eight_variants(wide):
+    """The per-lane search decodes the last task's choice once per strip of 64 and steps from there.  Here the
+    last task has eight variants with replica limits 255, 0, 1, 0, 2, 1, 0, 1 (radices 256 and 1 among them, a
+    carry out of the low four variants into the high four every 512 choices) and two batch sizes on top:
+    12,288 choices, 147,456 plans with the first task's 12; whole space and ranges that start and end inside
+    strips, both fill widths, against the CPU checker."""
+    limits = [255, 0, 1, 0, 2, 1, 0, 1]
+    acc = [600_000, 990_000, 950_000, 640_000, 900_000, 700_000, 980_000, 850_000]
+    lat, thr = [], []
+    for k in range(8):
+        lat += [3000 + 900 * k, 5000 + 1100 * k]
+        thr += [(40 + 7 * k) * 1000, (70 + 9 * k) * 1000]
+    if wide:
+        thr[8] = thr[9] = 1 << 33   # variant 4: one replica serves anything, and its capacity is beyond 32 bits
+    p = wl.Pipeline(n_tasks=2, parent=[-1, 0], fanout_q4=[4, 6], n_variants=[2, 8], n_batches=[2, 2],
+                    batch_size=[1, 4, 1, 8], max_replicas=[2, 1] + limits, acc_ppm=[900_000, 800_000] + acc,
+                    latency_us=[4000, 7000, 3000, 5000] + lat, thr_mqps=[2_000_000, 3_500_000, 2_500_000, 4_000_000] + thr)
+    P, O = binding.Problem(p), oracle.Problem(p)
+    n = P.num_candidates()
+    assert n == 12 * 12288
+    found = 0
+    for demand, W, slo in ((900_000, 40, 60_000), (2_400_000, 90, 45_000), (5_000_000, 200, 80_000), (0, 5, 30_000),
+                           (12_000_000, 262, 100_000)):
+        for flags in (LANE, LANE | TIE):
+            res = P.alloc_search([demand], W, slo, 500, flags=flags)[0]
+            assert P.last_search_fill_bits() == (64 if wide else 32)
+            ref = O.search(demand, W, slo, 500, tie_index_only=bool(flags & TIE))
+            assert agree(res, ref), (demand, W, flags, res.as_tuple(), ref.as_tuple())
+            found += ref.found
+        for a, b in ((12 * 500 + 7, 12 * 1100 + 3), (12 * 4090, 12 * 4103 + 5), (n - 12 * 70, n), (12 * 6143 + 11, 12 * 6145)):
+            res = P.alloc_search([demand], W, slo, 500, flags=LANE, begin=a, end=b)[0]
+            ref = O.search(demand, W, slo, 500, begin=a, end=b)
+            assert agree(res, ref), (demand, W, a, b, res.as_tuple(), ref.as_tuple())
+    assert found >= 6, found
