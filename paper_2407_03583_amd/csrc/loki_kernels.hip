@@ -2500,6 +2500,7 @@ __global__ void __launch_bounds__(kBlockThreads, 2) open_plans_kernel(SearchArgs
     uint32_t waiting = 0;    // plans in this wavefront's queue (the same in every lane)
     uint32_t cur_group = ~0u;
     uint32_t cl0 = 0;
+    uint32_t least_w = 0, least_top = 0, least_bot = 0, most_lat = 0;   // over the wavefront's usable choices
 
     auto walk_queued = [&](uint32_t from, uint32_t count) {
         if (lane < count) {
@@ -2543,6 +2544,22 @@ __global__ void __launch_bounds__(kBlockThreads, 2) open_plans_kernel(SearchArgs
                     lat[s] = top[s] = bot[s] = kNever;
                 }
             }
+            // what the wavefront's choices of the last task ask for at the least (and, for the per-task sum, at
+            // the most): an entry that cannot meet that has no open plan here
+            uint32_t lw = ~0u, lt = ~0u, lb = ~0u, hl = ~0u;
+#pragma unroll
+            for (int s = 0; s < S; s++) {
+                if (lat[s] != kNever) {
+                    lw = lw < static_cast<uint32_t>(w[s]) ? lw : static_cast<uint32_t>(w[s]);
+                    lt = lt < static_cast<uint32_t>(top[s]) ? lt : static_cast<uint32_t>(top[s]);
+                    lb = lb < static_cast<uint32_t>(bot[s]) ? lb : static_cast<uint32_t>(bot[s]);
+                    hl = hl < ~static_cast<uint32_t>(lat[s]) ? hl : ~static_cast<uint32_t>(lat[s]);
+                }
+            }
+            least_w = uni(wave_min_u32(lw));
+            least_top = uni(wave_min_u32(lt));
+            least_bot = uni(wave_min_u32(lb));
+            most_lat = ~uni(wave_min_u32(hl));   // 0 when no choice is usable (least_* then rule every entry out)
         }
         // the tasks strictly between the first and the last: replicas, and along the chains from the first
         // task (left out here, added per entry) the three latency sums; a leaf among them closes its path
@@ -2625,6 +2642,10 @@ __global__ void __launch_bounds__(kBlockThreads, 2) open_plans_kernel(SearchArgs
             if (w_rem < 0) continue;
             const int32_t tl = uni(ul.tl), tt = uni(sTopRoom[e]), tb = uni(sBotRoom[e]);
             const bool bound_met = uni(sBoundMet[e]) != 0;
+            if (tt < 0 || tb < 0 || static_cast<uint32_t>(w_rem) < least_w || static_cast<uint32_t>(tt) < least_top ||
+                static_cast<uint32_t>(tb) < least_bot)
+                continue;   // no choice of the wavefront fits
+            if (bound_met && tl >= 0 && static_cast<uint32_t>(tl) >= most_lat) continue;   // the per-task sum admits all
             const uint64_t low = base_f + sChoice[e];
 #pragma unroll
             for (int s = 0; s < S; s++) {
