@@ -49,10 +49,10 @@ def algorithmic_lane_ops(n_tasks: int, n_paths: int, per_lane: bool, pipeline) -
 # HBM bytes per launch of the dominant kernel: rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch (KiB, scale
 # factor 1.0 against a plain copy; profiles/combine_kernel_cfg5.md, profiles/per_lane_search_kernel_cfg5.md).
 # They hold for the kernel sources they were taken with; with other sources `traffic` is null.
-MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (2167 + 7192) * 1024,
-                          ("cfg5_tree4_k4", "per_lane"): (4857 + 449330) * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg5_tree4_k4", "tabulated"): (2175 + 7216) * 1024,
+                          ("cfg5_tree4_k4", "per_lane"): (4853 + 449660) * 1024}
 TRAFFIC_SOURCES = ("loki_device.h", "loki_launch.h", "loki_kernels.hip", "loki_api.cpp")
-TRAFFIC_SOURCES_SHA256 = "b2a5439f6ae9ed9dfe7052d98f815853669b2ba3cc0df0d5a47f32aa50c007b4"
+TRAFFIC_SOURCES_SHA256 = "6bda9c9677b168721864393e01c5c06e6794650b56d34edc804f754cca2b17f7"
 
 
 def measured_traffic(workload: str, kernel: str):
