@@ -2706,7 +2706,10 @@ constexpr int32_t kWalkCheckLatency = 1 << 30;  // queue entry: latency not sett
 // registers of 2 wavefronts per SIMD: 3 spill into the scoring loop, and 1 (twice the registers, the upper half
 // of them reachable only through copies) leaves the loop's waits uncovered; built that way the eight-level
 // kernel with both walks also returned a plan below the best one, which tests/test_gpu_latency_per_path.py
-// now checks for on a six-task chain.
+// now checks for on a six-task chain.  The plain kernel with the 32-bit fill and one batch size per task is held
+// to the registers of 6 wavefronts per SIMD (80; its scalar loads and LDS reads want the cover): what spills is
+// the part that scores the other tasks once per strip, plus one reload per feasible plan; at 8 the feasible-plan
+// path of the strip loop reloads more.
 template <bool PV, bool VF, int MAXD, int LATD = 0, bool NARROW = false>
 __global__ void __launch_bounds__(kBlockThreads, LATD > 0 ? 2 : (MAXD == 4 ? 3 : (MAXD == 0 && NARROW && !PV ? 6 : 1)))
     per_lane_search_kernel(SearchArgs A) {
